@@ -1,0 +1,296 @@
+"""CPU oracle for the Accordion gradient-compression hot path (arxiv 2010.16248).
+
+TEST INFRASTRUCTURE ONLY.  This file is a plain, slow, obviously-correct numpy
+statement of what the path computes.  It is imported by the tests, by the smoke
+check and by the benchmark's cpu_baseline leg, and by nothing else; the product
+(the HIP library and its binding) shares no code with it and never calls it.
+
+What is computed, and where the paper defines it
+------------------------------------------------
+* Distributed SGD with a compressor C(., l) and the mean over workers:
+  Section 3, "Distributed SGD with adaptive gradient compression".
+* Error feedback ("memory term"): Section 5.3 and Appendix A, "Hyperparameters":
+  the part of (gradient + memory) that the compressor dropped is the next memory.
+* PowerSGD: Section 5 names it (low-rank factorisation per layer); the steps are
+  the ones the benchmark spec fixes: P = M Q, orthogonalise P, Q = M^T P,
+  decompress P Q^T, with M = gradient + memory.  1-D tensors are not compressed
+  (appendix "Compression Ratio Selection").
+* TopK: Section 5, "choosing the K entries with largest absolute values"; per
+  gradient tensor (Section 1).  Ties go to the lower flat index.
+* Accumulated per-layer gradient, its norm, the critical-regime test and the two
+  levels: Section 4.2 (equation and Algorithm 1), "Computational and memory
+  overhead".
+
+Precision: operands and stored state are fp32 (the paper's implementation is
+fp32 PyTorch); every contraction, norm and orthogonalisation is evaluated in fp64
+on those fp32 operands and rounded to fp32 where it is stored.  The error-feedback
+add, the TopK comparison and the regime decision are taken in fp32, because they
+decide integers (which entries are kept, which level is used) and both sides must
+decide in the same precision.
+
+Pins: tests/test_oracle_*.py check every function below against brute force on
+tiny inputs, library QR/SVD, closed forms, the paper's printed "Data Sent"
+columns and hand-written decision sequences.  The choice of k from a percentage
+(ceil) and the start-critical convention have no printed value to pin against:
+"parity unpinned" for those two conventions (they are documented readings).
+"""
+from __future__ import annotations
+
+import math
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+F32 = np.float32
+F64 = np.float64
+
+POWERSGD = 0
+TOPK = 1
+
+
+# ---------------------------------------------------------------------------
+# elementary pieces
+# ---------------------------------------------------------------------------
+
+def ef_add(g: np.ndarray, e: np.ndarray) -> np.ndarray:
+    """Delta = gradient + error memory, one fp32 add per element
+    (Section 5.3 "with error-feedback"; Appendix A "with memory term")."""
+    return (g.astype(F32) + e.astype(F32)).astype(F32)
+
+
+def k_from_fraction(n: int, num: int, den: int) -> int:
+    """Kept count for "K = num/den of the entries" (Section 5): the paper does not
+    say how a fractional count is rounded; reading: ceil, at least 1."""
+    return max(1, -((-int(n) * int(num)) // int(den)))
+
+
+def effective_rank(rank: int, rows: int, cols: int) -> int:
+    """A rank above min(rows, cols) cannot be used; it is capped."""
+    return max(1, min(int(rank), int(rows), int(cols)))
+
+
+def gram_schmidt(p: np.ndarray) -> np.ndarray:
+    """Orthonormalise the columns of P in order (modified Gram-Schmidt):
+    column i has its components along the finished columns j < i removed one after
+    the other, then is scaled to unit length; a column of zero length stays zero."""
+    a = p.astype(F64).copy()
+    r = a.shape[1]
+    for i in range(r):
+        for j in range(i):
+            a[:, i] -= np.dot(a[:, j], a[:, i]) * a[:, j]
+        nrm = math.sqrt(float(np.dot(a[:, i], a[:, i])))
+        if nrm > 0.0:
+            a[:, i] /= nrm
+        else:
+            a[:, i] = 0.0
+    return a.astype(F32)
+
+
+def powersgd_layer(deltas: Sequence[np.ndarray], q: np.ndarray):
+    """One PowerSGD round for one layer over W workers.
+
+    deltas: W matrices (n x m, fp32) = gradient + memory of each worker.
+    q:      m x r right factor from the previous step (fp32).
+    Returns (P_hat n x r, Q_bar m x r, D n x m), all fp32:
+      P_w = Delta_w Q;  P_bar = mean_w P_w;  P_hat = orthonormalised P_bar;
+      Q_w = Delta_w^T P_hat;  Q_bar = mean_w Q_w;  D = P_hat Q_bar^T.
+    The two means are what the all-reduce produces (Section 5.1 "Implementation")
+    together with the 1/N of the update rule (Section 3)."""
+    w = len(deltas)
+    q64 = q.astype(F64)
+    p_w = [(d.astype(F64) @ q64).astype(F32) for d in deltas]
+    p_bar = (sum(p.astype(F64) for p in p_w) / w).astype(F32)
+    p_hat = gram_schmidt(p_bar)
+    ph64 = p_hat.astype(F64)
+    q_w = [(d.astype(F64).T @ ph64).astype(F32) for d in deltas]
+    q_bar = (sum(x.astype(F64) for x in q_w) / w).astype(F32)
+    d_out = (ph64 @ q_bar.astype(F64).T).astype(F32)
+    return p_hat, q_bar, d_out
+
+
+def topk_select(delta: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """The k entries of a flat fp32 tensor with the largest absolute value
+    (Section 5).  Order: |value| descending, compared on the fp32 bit pattern with
+    the sign cleared (so +0 and -0 tie); equal magnitudes: lower flat index first.
+    Returns (indices ascending, int32; values = the untouched entries, fp32)."""
+    flat = np.ascontiguousarray(delta, dtype=F32).reshape(-1)
+    key = (flat.view(np.uint32) & np.uint32(0x7FFFFFFF)).astype(np.int64)
+    order = np.argsort(-key, kind="stable")      # stable: ties keep index order
+    kept = np.sort(order[:k]).astype(np.int32)
+    return kept, flat[kept].copy()
+
+
+def topk_residual(delta: np.ndarray, kept: np.ndarray) -> np.ndarray:
+    """Error memory after TopK: zero where an entry was sent, Delta elsewhere."""
+    e = np.array(delta, dtype=F32).reshape(-1).copy()
+    e[kept] = F32(0.0)
+    return e
+
+
+def sparse_mean(n: int, payloads: Sequence[Tuple[np.ndarray, np.ndarray]], n_workers: int) -> np.ndarray:
+    """Dense mean of W sparse payloads (the all-gather of Section 5.1 followed by
+    the 1/N sum of Section 3).  Taken in fp32, workers in order 0..W-1 starting
+    from +0, then one division by W, so that the result has one definite value."""
+    acc = np.zeros(n, dtype=F32)
+    for idx, val in payloads:
+        acc[idx] = (acc[idx] + val.astype(F32)).astype(F32)
+    return (acc / F32(n_workers)).astype(F32)
+
+
+def layer_norm(a: np.ndarray) -> np.float32:
+    """l2 norm of one layer's accumulated gradient (Section 4.2, "Computational and
+    memory overhead"), summed in fp64 and stored as fp32."""
+    x = a.astype(F64).reshape(-1)
+    return F32(math.sqrt(float(np.dot(x, x))))
+
+
+def regime_is_critical(old, curr, has_old: bool, eta, lr_curr, lr_next) -> bool:
+    """Algorithm 1 / the Section 4.2 criterion, in fp32:
+    critical  <=>  | ||D_old|| - ||D_curr|| | / ||D_old|| >= eta   or   lr_next < lr_curr.
+    Readings where the paper is silent: no previous norm yet, or a previous norm of
+    zero (the ratio is undefined) => critical, as early training is."""
+    if F32(lr_next) < F32(lr_curr):
+        return True
+    if not has_old:
+        return True
+    old = F32(old)
+    curr = F32(curr)
+    if old == F32(0.0):
+        return True
+    ratio = F32(np.abs(F32(old - curr))) / old
+    return bool(F32(ratio) >= F32(eta))
+
+
+# ---------------------------------------------------------------------------
+# the whole path as a state machine
+# ---------------------------------------------------------------------------
+
+class AccordionOracle:
+    """State: error memory e[w] (W x N), accumulated gradient A (N), right factors Q
+    (one m x r_max block per matrix layer), previous norms, level per layer.
+
+    layers: sequence of (offset, rows, cols, is_matrix).
+    level_crit / level_noncrit: rank (PowerSGD) or numerator of K over k_den (TopK)
+    used inside / outside critical regimes.  In the paper's words the level used in
+    critical regimes is l_low (low compression: higher rank, larger K)."""
+
+    def __init__(self, method: int, layers, n_workers: int, level_crit: int,
+                 level_noncrit: int, k_den: int = 100, eta: float = 0.5,
+                 initial_level: int = 1, q_init: np.ndarray | None = None):
+        self.method = int(method)
+        self.layers = [tuple(int(v) for v in l) for l in layers]
+        self.W = int(n_workers)
+        self.level_crit, self.level_noncrit = int(level_crit), int(level_noncrit)
+        self.k_den = int(k_den)
+        self.eta = F32(eta)
+        self.N = sum(r * c for (_, r, c, _) in self.layers)
+        nl = len(self.layers)
+        self.e = np.zeros((self.W, self.N), dtype=F32)
+        self.A = np.zeros(self.N, dtype=F32)
+        self.level = np.full(nl, int(initial_level), dtype=np.int32)
+        self.norm_old = np.zeros(nl, dtype=F32)
+        self.norm_curr = np.zeros(nl, dtype=F32)
+        self.norm_prev = np.zeros(nl, dtype=F32)   # the old norm the last decision used
+        self.has_old = np.zeros(nl, dtype=np.int32)
+        self.r_max = max(self.level_crit, self.level_noncrit) if method == POWERSGD else 0
+        self.Q = {}
+        if method == POWERSGD:
+            pos = 0
+            for li, (_, r, c, is_m) in enumerate(self.layers):
+                if is_m:
+                    blk = c * self.r_max
+                    self.Q[li] = np.array(q_init[pos:pos + blk], dtype=F32).reshape(c, self.r_max).copy()
+                    pos += blk
+        self.words_last = 0
+        self.words_cum = 0
+        # intermediates of the last step, kept for comparison
+        self.P_hat = {}
+        self.Q_bar = {}
+        self.payload = {}       # (worker, layer) -> (idx, val)
+
+    # -- level lookup ------------------------------------------------------
+    def level_value(self, li: int) -> int:
+        return self.level_crit if self.level[li] == 1 else self.level_noncrit
+
+    def layer_rank(self, li: int) -> int:
+        _, r, c, _ = self.layers[li]
+        return effective_rank(self.level_value(li), r, c)
+
+    def layer_k(self, li: int) -> int:
+        _, r, c, _ = self.layers[li]
+        return k_from_fraction(r * c, self.level_value(li), self.k_den)
+
+    # -- one training step ---------------------------------------------------
+    def step(self, grads: Sequence[np.ndarray]) -> np.ndarray:
+        """Consume one gradient per worker, return the averaged decompressed
+        gradient (N, fp32); updates e, A, Q and the payload counters."""
+        assert len(grads) == self.W
+        out = np.zeros(self.N, dtype=F32)
+        # accumulate the raw gradient of worker 0 (the deciding node, Section 3 "Goals")
+        self.A = (self.A + grads[0].astype(F32)).astype(F32)
+        delta = [ef_add(grads[w], self.e[w]) for w in range(self.W)]
+        words = 0
+        self.P_hat, self.Q_bar, self.payload = {}, {}, {}
+        for li, (off, rows, cols, is_m) in enumerate(self.layers):
+            n = rows * cols
+            sl = slice(off, off + n)
+            if self.method == POWERSGD:
+                if is_m:
+                    r = self.layer_rank(li)
+                    mats = [delta[w][sl].reshape(rows, cols) for w in range(self.W)]
+                    p_hat, q_bar, d = powersgd_layer(mats, self.Q[li][:, :r])
+                    self.Q[li][:, :r] = q_bar          # warm start of the next step
+                    self.P_hat[li], self.Q_bar[li] = p_hat, q_bar
+                    out[sl] = d.reshape(-1)
+                    for w in range(self.W):
+                        self.e[w, sl] = (mats[w] - d).astype(F32).reshape(-1)
+                    words += r * (rows + cols)
+                else:
+                    # 1-D tensors are sent as they are: plain mean, no memory
+                    acc = sum(grads[w][sl].astype(F64) for w in range(self.W)) / self.W
+                    out[sl] = acc.astype(F32)
+                    self.e[:, sl] = F32(0.0)
+                    words += n
+            else:
+                k = self.layer_k(li)
+                pays = []
+                for w in range(self.W):
+                    idx, val = topk_select(delta[w][sl], k)
+                    self.e[w, sl] = topk_residual(delta[w][sl], idx)
+                    self.payload[(w, li)] = (idx, val)
+                    pays.append((idx, val))
+                out[sl] = sparse_mean(n, pays, self.W)
+                words += 2 * k
+        self.words_last = words
+        self.words_cum += words
+        return out
+
+    # -- end of a window -----------------------------------------------------
+    def detect_regime(self, lr_curr: float, lr_next: float) -> np.ndarray:
+        """Norm of each layer's accumulated gradient, Algorithm 1 per layer, then
+        curr -> old and the accumulator restarts.  Returns the new level vector
+        (1 = critical)."""
+        for li, (off, rows, cols, _) in enumerate(self.layers):
+            c = layer_norm(self.A[off:off + rows * cols])
+            crit = regime_is_critical(self.norm_old[li], c, bool(self.has_old[li]),
+                                      self.eta, lr_curr, lr_next)
+            self.level[li] = 1 if crit else 0
+            self.norm_prev[li] = self.norm_old[li]
+            self.norm_curr[li] = c
+            self.norm_old[li] = c
+            self.has_old[li] = 1
+        self.A[:] = F32(0.0)
+        return self.level.copy()
+
+    def reset_accumulator(self) -> None:
+        self.A[:] = F32(0.0)
+
+    def words_per_step(self) -> int:
+        """Floats one worker sends per step at the current levels."""
+        total = 0
+        for li, (_, rows, cols, is_m) in enumerate(self.layers):
+            if self.method == POWERSGD:
+                total += self.layer_rank(li) * (rows + cols) if is_m else rows * cols
+            else:
+                total += 2 * self.layer_k(li)
+        return total

@@ -1,0 +1,135 @@
+"""Pins for the oracle's TopK, residual and sparse mean (CPU only).
+
+Each check is independent of the oracle's own formula: a hand-worked example,
+a brute-force selection written with Python's sorted() on tuples, and the
+defining properties of a top-k set with the lower-index tie rule."""
+import struct
+
+import numpy as np
+import pytest
+
+from oracle import accordion_oracle as orc
+
+
+def brute_force_topk(values, k):
+    """Selection by explicit (magnitude-bits, index) tuples in pure Python."""
+    def mag(v):
+        return struct.unpack("<I", struct.pack("<f", float(v)))[0] & 0x7FFFFFFF
+    ranked = sorted(range(len(values)), key=lambda i: (-mag(values[i]), i))
+    return sorted(ranked[:k])
+
+
+def test_hand_worked_example():
+    # Section 5: keep the K entries with the largest absolute value.
+    d = np.array([0.5, -2.0, 2.0, 0.0, -0.0, 1.0, -3.0], dtype=np.float32)
+    idx, val = orc.topk_select(d, 3)
+    assert idx.tolist() == [1, 2, 6]
+    assert val.tolist() == [-2.0, 2.0, -3.0]
+    idx, val = orc.topk_select(d, 2)          # |-2| ties with |2|: index 1 wins
+    assert idx.tolist() == [1, 6]
+    idx, _ = orc.topk_select(d, 6)            # +0 and -0 tie: index 3 wins over 4
+    assert idx.tolist() == [0, 1, 2, 3, 5, 6]
+    e = orc.topk_residual(d, np.array([1, 6]))
+    assert e.tolist() == [0.5, 0.0, 2.0, 0.0, -0.0, 1.0, 0.0]
+
+
+@pytest.mark.parametrize("case", ["normal", "quantised", "all_equal", "all_zero", "sparse_rows", "signed_zero"])
+@pytest.mark.parametrize("n", [1, 7, 64, 1000])
+def test_against_brute_force(case, n):
+    rng = np.random.default_rng([len(case), ord(case[0]), ord(case[-1]), n])
+    if case == "normal":
+        d = rng.standard_normal(n)
+    elif case == "quantised":
+        d = rng.integers(-3, 4, n) * 0.25
+    elif case == "all_equal":
+        d = np.full(n, -1.5)
+    elif case == "all_zero":
+        d = np.zeros(n)
+    elif case == "sparse_rows":
+        d = rng.standard_normal(n) * (rng.random(n) < 0.05)
+    else:
+        d = np.where(rng.random(n) < 0.5, 0.0, -0.0)
+    d = d.astype(np.float32)
+    for k in sorted({1, max(1, n // 10), max(1, n // 2), n}):
+        idx, val = orc.topk_select(d, k)
+        assert idx.dtype == np.int32
+        assert idx.tolist() == brute_force_topk(d.tolist(), k)
+        assert val.view(np.uint32).tolist() == d[idx].view(np.uint32).tolist()
+
+
+def test_defining_properties_and_residual_invariant():
+    rng = np.random.default_rng(5)
+    d = (rng.integers(-50, 51, 5000) * 0.125).astype(np.float32)   # heavy ties
+    for k in (1, 13, 500, 2500, 5000):
+        idx, val = orc.topk_select(d, k)
+        assert len(idx) == k and np.all(np.diff(idx) > 0)
+        kept = np.zeros(d.size, bool)
+        kept[idx] = True
+        a = np.abs(d)
+        if k < d.size:
+            thr = a[kept].min()
+            assert a[~kept].max() <= thr
+            # among entries equal to the threshold, every kept index precedes every dropped one
+            tk = np.flatnonzero(kept & (a == thr))
+            td = np.flatnonzero(~kept & (a == thr))
+            if len(td):
+                assert tk.max() < td.min()
+        # compressed + residual == gradient + old residual, bit for bit
+        e = orc.topk_residual(d, idx)
+        scat = np.zeros_like(d)
+        scat[idx] = val
+        assert np.array_equal((scat + e).view(np.uint32) & 0x7FFFFFFF, d.view(np.uint32) & 0x7FFFFFFF)
+        assert np.array_equal(scat + e, d)
+        assert not np.any(e[idx] != 0)
+
+
+def test_k_from_fraction():
+    assert orc.k_from_fraction(64, 1, 100) == 1        # 0.64 -> 1
+    assert orc.k_from_fraction(1000, 10, 100) == 100
+    assert orc.k_from_fraction(1001, 10, 100) == 101   # ceil
+    assert orc.k_from_fraction(10, 1, 100) == 1
+    assert orc.k_from_fraction(7, 100, 100) == 7
+
+
+def test_sparse_mean_hand_and_fp64():
+    # two workers, n = 5: worker 0 keeps {1: 2.0, 3: -1.0}; worker 1 keeps {3: 0.5, 4: 4.0}
+    p0 = (np.array([1, 3], np.int32), np.array([2.0, -1.0], np.float32))
+    p1 = (np.array([3, 4], np.int32), np.array([0.5, 4.0], np.float32))
+    out = orc.sparse_mean(5, [p0, p1], 2)
+    assert out.tolist() == [0.0, 1.0, 0.0, -0.25, 2.0]
+    rng = np.random.default_rng(3)
+    n, W = 400, 5
+    pays, dense = [], np.zeros((W, n))
+    for w in range(W):
+        idx = np.sort(rng.choice(n, 60, replace=False)).astype(np.int32)
+        val = rng.standard_normal(60).astype(np.float32)
+        dense[w, idx] = val
+        pays.append((idx, val))
+    ref = dense.sum(0) / W
+    got = orc.sparse_mean(n, pays, W)
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-7)
+    assert np.all(got[dense.any(0) == 0] == 0)
+
+
+def test_topk_step_state_machine():
+    # W = 2, two "layers" (a 2x3 matrix and a 4-vector), K = 50 %
+    layers = [(0, 2, 3, 1), (6, 1, 4, 0)]
+    o = orc.AccordionOracle(orc.TOPK, layers, 2, 50, 25, 100, 0.5, 1)
+    g0 = np.array([1, -5, 2, 0, 3, -1, 7, 1, -1, 0], np.float32)
+    g1 = np.array([0, 1, 2, -3, 0, 0, 1, 1, 1, 1], np.float32)
+    out = o.step([g0, g1])
+    # layer 0 (n=6, k=3): w0 keeps idx 1,2,4 (|-5|,|2|,|3|); w1 keeps 1,2,3
+    assert o.payload[(0, 0)][0].tolist() == [1, 2, 4]
+    assert o.payload[(1, 0)][0].tolist() == [1, 2, 3]
+    # layer 1 (n=4, k=2): w0 keeps idx 0 (7) and 1 (|1| ties |-1|: lower index); w1 keeps 0,1 (all ties)
+    assert o.payload[(0, 1)][0].tolist() == [0, 1]
+    assert o.payload[(1, 1)][0].tolist() == [0, 1]
+    assert out.tolist() == [0, -2.0, 2.0, -1.5, 1.5, 0, 4.0, 1.0, 0, 0]
+    assert o.e[0].tolist() == [1, 0, 0, 0, 0, -1, 0, 0, -1, 0]
+    assert o.e[1].tolist() == [0, 0, 0, 0, 0, 0, 0, 0, 1, 1]
+    assert o.A.tolist() == g0.tolist()                 # raw gradient of worker 0 only
+    assert o.words_last == 2 * (3 + 2)
+    # second step: memory is added before selection
+    out2 = o.step([np.zeros(10, np.float32), np.zeros(10, np.float32)])
+    assert o.payload[(0, 0)][0].tolist() == [0, 1, 5]    # delta = [1,0,0,0,0,-1]: 1, then tie 0s: idx1; -1
+    assert o.payload[(0, 0)][1].tolist() == [1.0, 0.0, -1.0]
