@@ -1,0 +1,180 @@
+/*
+ * accordion.h -- C ABI of the Accordion gradient-compression hot path for one
+ * AMD MI355X (gfx950).  arxiv 2010.16248.
+ *
+ * What the library computes, per training step, for W simulated data-parallel
+ * workers on one GPU (the paper's setting: Section 3; compressors: Section 5):
+ *
+ *   Delta_w = g_w + e_w                       error feedback ("memory term", Sec. 5.3, App. A)
+ *   A      += g_0                             per-layer accumulated gradient (Sec. 4.2)
+ *   PowerSGD, matrix layers:  P_w = Delta_w Q,  P^ = orthonormalise(mean_w P_w),
+ *                             Q_w = Delta_w^T P^,  Q~ = mean_w Q_w (next step's Q),
+ *                             D = P^ Q~^T,  e_w = Delta_w - D
+ *             1-D layers:     D = mean_w g_w,  e_w = 0      (App. "Compression Ratio Selection")
+ *   TopK, every layer:        keep the k entries of Delta_w with the largest |.|
+ *                             (ties: lower flat index), payload (index, value),
+ *                             e_w = Delta_w with the kept entries zeroed,
+ *                             D = (sum over workers of their kept values) / W
+ *   end of a window:          c_l = ||A_l||_2,  Algorithm 1 per layer
+ *                             (| old - c | / old >= eta  or  lr_next < lr_curr  => critical),
+ *                             old <- c,  A <- 0; the level picks rank / k of the next window.
+ *
+ * Levels.  The paper's l_low is LOW COMPRESSION (higher rank, larger K) and is the
+ * level used inside critical regimes; l_high is used outside.  To avoid the word
+ * "low" the configuration names them *_crit and *_noncrit.
+ *
+ * Conventions.
+ *  - Every function returns an int32 status (ACC_OK = 0).  Nothing throws, aborts or logs;
+ *    accordion_last_error() gives a static, human-readable string for the last failure.
+ *  - All tensors are fp32.  "flat" buffers hold all layers concatenated at acc_layer.offset
+ *    (in elements); a matrix layer is rows x cols row-major (conv weight out x in x kh x kw
+ *    = out x (in*kh*kw)); a 1-D layer has rows = 1.
+ *  - Pointers named *_dev are DEVICE pointers and must be 16-byte aligned; pointers named
+ *    *_host are HOST pointers.  The library never allocates or frees device memory: the
+ *    caller provides one workspace of accordion_workspace_bytes() bytes (256-byte aligned)
+ *    that must outlive the context, plus every gradient / output buffer.
+ *  - Every call that does device work enqueues it on the HIP stream given at init and returns
+ *    without waiting.  The accordion_get_* / accordion_set_state / payload_words calls
+ *    synchronise that stream.
+ *  - Levels, ranks and kept counts live in device memory and are read by the kernels, so a
+ *    level switch costs no host round trip.
+ *  - Inputs must be finite; NaN/Inf give unspecified (but memory-safe) results.
+ *  - A context is not thread-safe; calls that overlap on one context race.
+ */
+#ifndef ACCORDION_H
+#define ACCORDION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  ACC_OK = 0,
+  ACC_EINVAL = 1,    /* bad argument (null, out of range, misaligned) */
+  ACC_ESTATE = 2,    /* call out of order for the step state machine */
+  ACC_ENOSPACE = 3,  /* workspace or host buffer too small */
+  ACC_EHIP = 4       /* a HIP runtime call failed */
+};
+
+enum { ACC_POWERSGD = 0, ACC_TOPK = 1 };
+
+#define ACC_MAX_WORKERS 32
+#define ACC_MAX_RANK 4
+
+typedef struct acc_layer {
+  int64_t offset;     /* first element of the layer in the flat buffers */
+  int32_t rows, cols; /* matrix: n x m; 1-D tensor: rows = 1 */
+  int32_t is_matrix;  /* 1: compressed by PowerSGD; 0: 1-D tensor (sent raw by PowerSGD) */
+} acc_layer;
+
+typedef struct acc_config {
+  int32_t method;              /* ACC_POWERSGD or ACC_TOPK */
+  int32_t n_layers;
+  const acc_layer* layers;     /* host array, copied at init; layers must not overlap */
+  int64_t n_params;            /* length of the flat buffers; >= max(offset + rows*cols) */
+  int32_t n_workers;           /* W in [1, ACC_MAX_WORKERS] */
+  int32_t rank_crit;           /* PowerSGD rank inside critical regimes, in [1, ACC_MAX_RANK] */
+  int32_t rank_noncrit;        /* PowerSGD rank outside */
+  int32_t k_num_crit;          /* TopK: k = max(1, ceil(n * num / den)) per layer */
+  int32_t k_num_noncrit;
+  int32_t k_den;
+  float   eta;                 /* detection threshold of Sec. 4.2; the paper uses 0.5 */
+  int32_t initial_level;       /* level before the first decision: 1 = critical, 0 = not */
+} acc_config;
+
+typedef struct acc_ctx acc_ctx;
+
+/* Size of the device workspace for this configuration (host-only arithmetic, no GPU needed).
+ * Errors: ACC_EINVAL for null pointers or an invalid configuration. */
+int32_t accordion_workspace_bytes(const acc_config* cfg, size_t* out_bytes);
+
+/* Create a context (Algorithm 1's hyper-parameters l_low/l_high/eta and the layer table).
+ * workspace_dev: device memory, >= accordion_workspace_bytes(), 256-byte aligned, owned by the
+ *   caller; it is cleared here (e = 0, A = 0, no previous norms, level = initial_level).
+ * q_init_host: PowerSGD only -- for every matrix layer, in layer order, cols x r_max floats
+ *   (row-major, r_max = max(rank_crit, rank_noncrit)), the caller's N(0,1) start for Q.
+ *   Ignored (may be NULL) for TopK.
+ * hip_stream: a hipStream_t (NULL = the default stream).
+ * Errors: ACC_EINVAL, ACC_ENOSPACE (workspace too small), ACC_EHIP.  On error *out is NULL. */
+int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t workspace_bytes,
+                       const float* q_init_host, void* hip_stream, acc_ctx** out);
+
+/* Free the host-side context (the workspace stays the caller's). */
+int32_t accordion_destroy(acc_ctx* ctx);
+
+/* Static description of the last error of this context (or of the last failed init when
+ * ctx is NULL). */
+const char* accordion_last_error(const acc_ctx* ctx);
+
+/* C(g_w, l): one worker's compression (Sec. 3 update rule; Sec. 5 compressors).
+ * phase 0: Delta_w = grad + e_w (kept in place of e_w); worker 0 also does A += grad.
+ *          PowerSGD: P_w = Delta_w Q.  TopK: select, write the payload, zero the kept
+ *          entries of e_w.   grad_dev: N floats; for PowerSGD it must stay unmodified until
+ *          accordion_aggregate(ctx, 0) has run (the raw 1-D tensors are averaged there).
+ * phase 1: PowerSGD only: Q_w = Delta_w^T P^ (grad_dev is ignored and may be NULL).
+ * Order per step: phase 0 for each worker once (any order), aggregate(0), [phase 1 for each
+ * worker, aggregate(1)], decompress.  Anything else returns ACC_ESTATE and touches nothing. */
+int32_t accordion_compress_step(acc_ctx* ctx, int32_t worker, const float* grad_dev, int32_t phase);
+
+/* The mean over workers that the all-reduce / all-gather provides (Sec. 5.1 "Implementation",
+ * Sec. 3).  phase 0, PowerSGD: P^ = orthonormalise(mean_w P_w) by modified Gram-Schmidt in
+ * column order (a zero column stays zero), and the mean of the raw 1-D tensors.
+ * phase 0, TopK: the W payloads count as gathered (no arithmetic; the sum is in decompress).
+ * phase 1, PowerSGD only: Q~ = mean_w Q_w, stored as the next step's Q. */
+int32_t accordion_aggregate(acc_ctx* ctx, int32_t phase);
+
+/* Averaged, decompressed gradient of this step into out_dev (N floats, fully overwritten).
+ * PowerSGD: D = P^ Q~^T on matrix layers and e_w = Delta_w - D for every worker; 1-D layers get
+ * the plain mean.  TopK: D[i] = (sum over workers, in worker order from +0, of the values kept
+ * at i) / W.  Ends the step. */
+int32_t accordion_decompress(acc_ctx* ctx, float* out_dev);
+
+/* The whole step for all workers with batched launches: phase 0 for every worker,
+ * aggregate, [phase 1, aggregate], decompress.  grads_host_array: HOST array of W DEVICE
+ * pointers (N floats each).  Same results as the call-by-call sequence. */
+int32_t accordion_step_all(acc_ctx* ctx, const float* const* grads_host_array, float* out_dev);
+
+/* End of a window (Sec. 4.2; Algorithm 1): c_l = ||A_l||_2 (fp64 sum, fp32 result), per layer
+ * critical <=> no previous norm, previous norm 0, |old - c| / old >= eta, or lr_next < lr_curr;
+ * level <- critical; old <- c; A <- 0.  Only between steps (else ACC_ESTATE). */
+int32_t accordion_detect_regime(acc_ctx* ctx, float lr_curr, float lr_next);
+
+/* A <- 0 without a decision (to measure one epoch out of several, Sec. 5.1 "Hyperparameters"). */
+int32_t accordion_reset_accumulator(acc_ctx* ctx);
+
+/* --- read-backs (synchronise the stream) ------------------------------------------------ */
+
+/* levels_host: n_layers int32, 1 = critical. */
+int32_t accordion_get_levels(acc_ctx* ctx, int32_t* levels_host);
+/* old_host: the previous norm the last decision compared against (0 if none);
+ * curr_host: the norm it computed.  n_layers floats each. */
+int32_t accordion_get_norms(acc_ctx* ctx, float* old_host, float* curr_host);
+/* TopK payload of (worker, layer) from the last step: idx_host (int32, ascending, layer-local
+ * flat index) and val_host (fp32), each with room for capacity entries; *count_out = k.
+ * Errors: ACC_ENOSPACE if capacity < k (count_out is still set). */
+int32_t accordion_get_payload(acc_ctx* ctx, int32_t worker, int32_t layer, int32_t* idx_host,
+                              float* val_host, int64_t capacity, int64_t* count_out);
+/* PowerSGD factors of a matrix layer from the last step: p_hat_host rows x r and q_host
+ * cols x r (row-major, r = *rank_out, the rank that step used); room for ACC_MAX_RANK
+ * columns each is required. */
+int32_t accordion_get_factors(acc_ctx* ctx, int32_t layer, float* p_hat_host, float* q_host,
+                              int32_t* rank_out);
+/* Floats one worker sent in the last step / since init (PowerSGD: r(n+m) per matrix layer
+ * + n per 1-D layer; TopK: 2k per layer -- the accounting of the paper's "Data Sent"). */
+int32_t accordion_payload_words(acc_ctx* ctx, int64_t* last_step, int64_t* cumulative);
+
+/* State export / import for checkpointing and step-by-step comparison.  Layout (bytes, all
+ * little-endian fp32/int32, no padding):  e_0 .. e_{W-1} (N each) | A (N) | Q (sum over
+ * matrix layers of cols*r_max; absent for TopK) | norm_old (L) | has_old (L, int32) |
+ * level (L, int32).  accordion_state_bytes gives the size.  Only between steps. */
+int32_t accordion_state_bytes(const acc_ctx* ctx, size_t* out_bytes);
+int32_t accordion_get_state(acc_ctx* ctx, void* state_host, size_t bytes);
+int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACCORDION_H */

@@ -1,0 +1,290 @@
+"""ctypes binding of libaccordion.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+include/accordion.h; this module converts Python arguments to C ones and checks
+status codes.  PyTorch is used for device memory and the stream handle, nothing
+else.  There is no CPU fallback: if the shared library is missing or fails to
+load, every call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+ACC_OK, ACC_EINVAL, ACC_ESTATE, ACC_ENOSPACE, ACC_EHIP = 0, 1, 2, 3, 4
+ACC_POWERSGD, ACC_TOPK = 0, 1
+ACC_MAX_WORKERS = 32
+ACC_MAX_RANK = 4
+
+_STATUS = {0: "ACC_OK", 1: "ACC_EINVAL", 2: "ACC_ESTATE", 3: "ACC_ENOSPACE", 4: "ACC_EHIP"}
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaccordion.so")
+
+
+class acc_layer(C.Structure):
+    _fields_ = [("offset", C.c_int64), ("rows", C.c_int32), ("cols", C.c_int32),
+                ("is_matrix", C.c_int32)]
+
+
+class acc_config(C.Structure):
+    _fields_ = [("method", C.c_int32), ("n_layers", C.c_int32),
+                ("layers", C.POINTER(acc_layer)), ("n_params", C.c_int64),
+                ("n_workers", C.c_int32), ("rank_crit", C.c_int32), ("rank_noncrit", C.c_int32),
+                ("k_num_crit", C.c_int32), ("k_num_noncrit", C.c_int32), ("k_den", C.c_int32),
+                ("eta", C.c_float), ("initial_level", C.c_int32)]
+
+
+class AccordionError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+EXPORTS = [
+    "accordion_workspace_bytes", "accordion_init", "accordion_destroy", "accordion_last_error",
+    "accordion_compress_step", "accordion_aggregate", "accordion_decompress", "accordion_step_all",
+    "accordion_detect_regime", "accordion_reset_accumulator", "accordion_get_levels",
+    "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
+    "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
+]
+
+
+def load_library() -> C.CDLL:
+    """Load libaccordion.so (built in-tree by paper_2010_16248_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                           "`python -m paper_2010_16248_amd.build` (there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    sig = {
+        "accordion_workspace_bytes": [C.POINTER(acc_config), C.POINTER(C.c_size_t)],
+        "accordion_init": [C.POINTER(acc_config), vp, C.c_size_t, vp, vp, C.POINTER(vp)],
+        "accordion_destroy": [vp],
+        "accordion_compress_step": [vp, i32, vp, i32],
+        "accordion_aggregate": [vp, i32],
+        "accordion_decompress": [vp, vp],
+        "accordion_step_all": [vp, C.POINTER(vp), vp],
+        "accordion_detect_regime": [vp, f32, f32],
+        "accordion_reset_accumulator": [vp],
+        "accordion_get_levels": [vp, vp],
+        "accordion_get_norms": [vp, vp, vp],
+        "accordion_get_payload": [vp, i32, i32, vp, vp, i64, C.POINTER(i64)],
+        "accordion_get_factors": [vp, i32, vp, vp, C.POINTER(i32)],
+        "accordion_payload_words": [vp, C.POINTER(i64), C.POINTER(i64)],
+        "accordion_state_bytes": [vp, C.POINTER(C.c_size_t)],
+        "accordion_get_state": [vp, vp, C.c_size_t],
+        "accordion_set_state": [vp, vp, C.c_size_t],
+    }
+    for name, args in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = i32
+    lib.accordion_last_error.argtypes = [vp]
+    lib.accordion_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def make_config(method: int, layers: Sequence, n_workers: int, level_crit: int, level_noncrit: int,
+                k_den: int = 100, eta: float = 0.5, initial_level: int = 1,
+                n_params: Optional[int] = None) -> Tuple[acc_config, object]:
+    """Build an acc_config; returns (config, keep_alive) -- the layer array must outlive the
+    calls that read it.  layers: objects with offset/rows/cols/is_matrix or 4-tuples."""
+    arr = (acc_layer * max(1, len(layers)))()
+    end = 0
+    for i, l in enumerate(layers):
+        off, r, c, m = (l.offset, l.rows, l.cols, l.is_matrix) if hasattr(l, "offset") else l
+        arr[i] = acc_layer(int(off), int(r), int(c), int(m))
+        end = max(end, int(off) + int(r) * int(c))
+    cfg = acc_config()
+    cfg.method = method
+    cfg.n_layers = len(layers)
+    cfg.layers = C.cast(arr, C.POINTER(acc_layer))
+    cfg.n_params = end if n_params is None else n_params
+    cfg.n_workers = n_workers
+    if method == ACC_POWERSGD:
+        cfg.rank_crit, cfg.rank_noncrit = level_crit, level_noncrit
+        cfg.k_num_crit = cfg.k_num_noncrit = cfg.k_den = 1
+    else:
+        cfg.rank_crit = cfg.rank_noncrit = 1
+        cfg.k_num_crit, cfg.k_num_noncrit, cfg.k_den = level_crit, level_noncrit, k_den
+    cfg.eta = eta
+    cfg.initial_level = initial_level
+    return cfg, arr
+
+
+def _check(lib, ctx, rc: int) -> None:
+    if rc != ACC_OK:
+        msg = lib.accordion_last_error(ctx)
+        raise AccordionError(rc, msg.decode() if msg else "")
+
+
+def accordion_workspace_bytes(cfg: acc_config) -> int:
+    lib = load_library()
+    out = C.c_size_t(0)
+    _check(lib, None, lib.accordion_workspace_bytes(C.byref(cfg), C.byref(out)))
+    return int(out.value)
+
+
+class Accordion:
+    """One context.  Methods carry the names of the C entry points they call."""
+
+    def __init__(self, method: int, layers: Sequence, n_workers: int, level_crit: int,
+                 level_noncrit: int, k_den: int = 100, eta: float = 0.5, initial_level: int = 1,
+                 q_init: Optional[np.ndarray] = None, device: str = "cuda:0"):
+        import torch  # device memory and the stream handle only
+
+        self._lib = load_library()
+        self._torch = torch
+        self.cfg, self._keep = make_config(method, layers, n_workers, level_crit, level_noncrit,
+                                           k_den, eta, initial_level)
+        self.method, self.n_workers, self.n_layers = method, n_workers, len(layers)
+        self.n_params = int(self.cfg.n_params)
+        self.layers = [(l.offset, l.rows, l.cols, l.is_matrix) if hasattr(l, "offset") else tuple(l)
+                       for l in layers]
+        self.device = torch.device(device)
+        nbytes = accordion_workspace_bytes(self.cfg)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        self.workspace_bytes = nbytes
+        with torch.cuda.device(self.device):
+            self.stream = torch.cuda.current_stream().cuda_stream
+        qptr = None
+        if method == ACC_POWERSGD:
+            q = np.ascontiguousarray(q_init, dtype=np.float32)
+            self._q_keep = q
+            qptr = q.ctypes.data_as(C.c_void_p)
+        ctx = C.c_void_p(None)
+        rc = self._lib.accordion_init(C.byref(self.cfg), C.c_void_p(self._ws_ptr), nbytes, qptr,
+                                      C.c_void_p(self.stream), C.byref(ctx))
+        _check(self._lib, None, rc)
+        self.ctx = ctx
+
+    # -- the hot path ---------------------------------------------------------------------
+    def compress_step(self, worker: int, grad, phase: int) -> None:
+        ptr = C.c_void_p(grad.data_ptr()) if grad is not None else None
+        _check(self._lib, self.ctx, self._lib.accordion_compress_step(self.ctx, worker, ptr, phase))
+
+    def aggregate(self, phase: int) -> None:
+        _check(self._lib, self.ctx, self._lib.accordion_aggregate(self.ctx, phase))
+
+    def decompress(self, out) -> None:
+        _check(self._lib, self.ctx, self._lib.accordion_decompress(self.ctx, C.c_void_p(out.data_ptr())))
+
+    def step_all(self, grads: Sequence, out) -> None:
+        arr = (C.c_void_p * len(grads))(*[g.data_ptr() for g in grads])
+        _check(self._lib, self.ctx,
+               self._lib.accordion_step_all(self.ctx, arr, C.c_void_p(out.data_ptr())))
+
+    def detect_regime(self, lr_curr: float, lr_next: float) -> None:
+        _check(self._lib, self.ctx, self._lib.accordion_detect_regime(self.ctx, lr_curr, lr_next))
+
+    def reset_accumulator(self) -> None:
+        _check(self._lib, self.ctx, self._lib.accordion_reset_accumulator(self.ctx))
+
+    # -- read-backs -----------------------------------------------------------------------
+    def get_levels(self) -> np.ndarray:
+        out = np.zeros(self.n_layers, dtype=np.int32)
+        _check(self._lib, self.ctx, self._lib.accordion_get_levels(self.ctx, out.ctypes.data_as(C.c_void_p)))
+        return out
+
+    def get_norms(self) -> Tuple[np.ndarray, np.ndarray]:
+        old = np.zeros(self.n_layers, dtype=np.float32)
+        cur = np.zeros(self.n_layers, dtype=np.float32)
+        _check(self._lib, self.ctx, self._lib.accordion_get_norms(
+            self.ctx, old.ctypes.data_as(C.c_void_p), cur.ctypes.data_as(C.c_void_p)))
+        return old, cur
+
+    def get_payload(self, worker: int, layer: int) -> Tuple[np.ndarray, np.ndarray]:
+        _, r, c, _ = self.layers[layer]
+        cap = r * c
+        idx = np.zeros(cap, dtype=np.int32)
+        val = np.zeros(cap, dtype=np.float32)
+        cnt = C.c_int64(0)
+        _check(self._lib, self.ctx, self._lib.accordion_get_payload(
+            self.ctx, worker, layer, idx.ctypes.data_as(C.c_void_p), val.ctypes.data_as(C.c_void_p),
+            cap, C.byref(cnt)))
+        k = int(cnt.value)
+        return idx[:k].copy(), val[:k].copy()
+
+    def get_factors(self, layer: int) -> Tuple[np.ndarray, np.ndarray]:
+        _, r, c, _ = self.layers[layer]
+        p = np.zeros(r * ACC_MAX_RANK, dtype=np.float32)
+        q = np.zeros(c * ACC_MAX_RANK, dtype=np.float32)
+        rank = C.c_int32(0)
+        _check(self._lib, self.ctx, self._lib.accordion_get_factors(
+            self.ctx, layer, p.ctypes.data_as(C.c_void_p), q.ctypes.data_as(C.c_void_p), C.byref(rank)))
+        k = int(rank.value)
+        return p[:r * k].reshape(r, k).copy(), q[:c * k].reshape(c, k).copy()
+
+    def payload_words(self) -> Tuple[int, int]:
+        a, b = C.c_int64(0), C.c_int64(0)
+        _check(self._lib, self.ctx, self._lib.accordion_payload_words(self.ctx, C.byref(a), C.byref(b)))
+        return int(a.value), int(b.value)
+
+    def state_bytes(self) -> int:
+        out = C.c_size_t(0)
+        _check(self._lib, self.ctx, self._lib.accordion_state_bytes(self.ctx, C.byref(out)))
+        return int(out.value)
+
+    def get_state(self) -> np.ndarray:
+        buf = np.zeros(self.state_bytes(), dtype=np.uint8)
+        _check(self._lib, self.ctx, self._lib.accordion_get_state(
+            self.ctx, buf.ctypes.data_as(C.c_void_p), buf.nbytes))
+        return buf
+
+    def set_state(self, buf: np.ndarray) -> None:
+        buf = np.ascontiguousarray(buf, dtype=np.uint8)
+        _check(self._lib, self.ctx, self._lib.accordion_set_state(
+            self.ctx, buf.ctypes.data_as(C.c_void_p), buf.nbytes))
+
+    # -- state blob helpers (layout documented in include/accordion.h) ---------------------
+    def q_total(self) -> int:
+        if self.method != ACC_POWERSGD:
+            return 0
+        rmax = max(self.cfg.rank_crit, self.cfg.rank_noncrit)
+        return sum(c * rmax for (_, r, c, m) in self.layers if m)
+
+    def unpack_state(self, buf: np.ndarray) -> dict:
+        N, W, L = self.n_params, self.n_workers, self.n_layers
+        f = buf.view(np.float32)
+        pos = 0
+        e = f[pos:pos + W * N].reshape(W, N); pos += W * N
+        A = f[pos:pos + N]; pos += N
+        qt = self.q_total()
+        Q = f[pos:pos + qt]; pos += qt
+        norm_old = f[pos:pos + L]; pos += L
+        has_old = buf.view(np.int32)[pos:pos + L]; pos += L
+        level = buf.view(np.int32)[pos:pos + L]; pos += L
+        return dict(e=e, A=A, Q=Q, norm_old=norm_old, has_old=has_old, level=level)
+
+    def pack_state(self, e, A, Q, norm_old, has_old, level) -> np.ndarray:
+        parts = [np.ascontiguousarray(e, np.float32).reshape(-1).view(np.uint8),
+                 np.ascontiguousarray(A, np.float32).view(np.uint8)]
+        if self.method == ACC_POWERSGD:
+            parts.append(np.ascontiguousarray(Q, np.float32).reshape(-1).view(np.uint8))
+        parts += [np.ascontiguousarray(norm_old, np.float32).view(np.uint8),
+                  np.ascontiguousarray(has_old, np.int32).view(np.uint8),
+                  np.ascontiguousarray(level, np.int32).view(np.uint8)]
+        return np.concatenate(parts)
+
+    def destroy(self) -> None:
+        if getattr(self, "ctx", None) is not None and self.ctx.value:
+            self._torch.cuda.synchronize(self.device)
+            self._lib.accordion_destroy(self.ctx)
+            self.ctx = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

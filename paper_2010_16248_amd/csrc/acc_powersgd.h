@@ -1,0 +1,495 @@
+// PowerSGD kernels: error-feedback add fused with P = Delta Q, mean + Gram-Schmidt,
+// Q = Delta^T P^, mean of Q, decompress + residual.  All products are HBM-bound at rank <= 4
+// (2r flop per 4-byte element), so the kernels stream the matrix once per pass with 16-byte
+// accesses and keep the thin factor in registers; no MFMA.
+//
+// Matrix tile: 64 rows x 256 columns, one workgroup of 4 waves.  A lane owns 4 columns
+// (vec4 layers: 4 adjacent columns, one 16-byte access per row; other layers: columns
+// lane, lane+64, lane+128, lane+192, 4-byte accesses).  A wave owns rows wave, wave+4, ...
+#pragma once
+#include "acc_common.h"
+
+namespace acc {
+
+template <bool V4>
+__device__ __forceinline__ void lane_cols(int col0, int lane, int cols, int (&col)[4], bool (&cm)[4]) {
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    col[v] = V4 ? col0 + lane * 4 + v : col0 + lane + 64 * v;
+    cm[v] = col[v] < cols;
+  }
+}
+
+template <bool V4>
+__device__ __forceinline__ void load_row(const float* __restrict__ p, int64_t rowbase,
+                                         const int (&col)[4], const bool (&cm)[4], float (&d)[4]) {
+  if (V4) {
+    if (cm[0]) {
+      const float4 t = *reinterpret_cast<const float4*>(p + rowbase + col[0]);
+      d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w;
+    } else {
+      d[0] = d[1] = d[2] = d[3] = 0.f;
+    }
+  } else {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) d[v] = cm[v] ? p[rowbase + col[v]] : 0.f;
+  }
+}
+
+template <bool V4>
+__device__ __forceinline__ void store_row(float* __restrict__ p, int64_t rowbase,
+                                          const int (&col)[4], const bool (&cm)[4],
+                                          const float (&d)[4]) {
+  if (V4) {
+    if (cm[0]) *reinterpret_cast<float4*>(p + rowbase + col[0]) = make_float4(d[0], d[1], d[2], d[3]);
+  } else {
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+      if (cm[v]) p[rowbase + col[v]] = d[v];
+  }
+}
+
+// ---- phase 0: Delta = g + e (in place of e), A += g (worker 0), P partial = Delta Q ---------
+
+template <int R, bool V4>
+__device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const float* __restrict__ g,
+                          float* __restrict__ e, float* __restrict__ A, float* __restrict__ ppart) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int col[4]; bool cm[4];
+  lane_cols<V4>(t.col0, lane, L.cols, col, cm);
+  float q[4][R];
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int k = 0; k < R; ++k)
+      q[v][k] = cm[v] ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
+
+  const int row_end = min(t.row0 + kMatRows, L.rows);
+  const int chunk = t.col0 / kMatCols;
+  constexpr int B = 4;   // rows in flight per wave
+  for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
+    float gd[B][4], ed[B][4], ad[B][4];
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      const int i = i0 + 4 * b;
+      if (i < row_end) {
+        const int64_t rb = L.offset + (int64_t)i * L.cols;
+        load_row<V4>(g, rb, col, cm, gd[b]);
+        load_row<V4>(e, rb, col, cm, ed[b]);
+        if (A) load_row<V4>(A, rb, col, cm, ad[b]);
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      const int i = i0 + 4 * b;
+      if (i < row_end) {                       // wave-uniform
+        const int64_t rb = L.offset + (int64_t)i * L.cols;
+        float d[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) d[v] = gd[b][v] + ed[b][v];
+        store_row<V4>(e, rb, col, cm, d);
+        if (A) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) ad[b][v] += gd[b][v];
+          store_row<V4>(A, rb, col, cm, ad[b]);
+        }
+        float acc[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+          float s = d[0] * q[0][k];
+          s = fmaf(d[1], q[1][k], s);
+          s = fmaf(d[2], q[2][k], s);
+          s = fmaf(d[3], q[3][k], s);
+          acc[k] = wave_sum(s);
+        }
+        if (lane == 0) {
+          float* dst = ppart + L.ppart_off + ((int64_t)chunk * L.rows + i) * ws.rmax;
+#pragma unroll
+          for (int k = 0; k < R; ++k) dst[k] = acc[k];
+        }
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradPtrs gp, int w0) {
+  const int w = w0 + blockIdx.y;
+  const float* __restrict__ g = gp.p[w];
+  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  float* __restrict__ A = (w == 0) ? ws.A : nullptr;
+  if ((int)blockIdx.x >= ws.n_mtiles) {
+    // 1-D layers: only the accumulation A += g of worker 0 happens here
+    if (w != 0) return;
+    const FlatTile ft = ws.ftiles[ws.vectiles[blockIdx.x - ws.n_mtiles]];
+    const LayerDev& L = ws.layers[ft.layer];
+    const TileGeom tg = tile_geom(L, ft);
+    for (int q = threadIdx.x; q < tg.nquads; q += kFlatThreads) {
+      const int64_t base = tg.a0 + 4 * (int64_t)q;
+      float4 a = ld_quad(ws.A, base, tg.lo, tg.hi);
+      const float4 gv = ld_quad(g, base, tg.lo, tg.hi);
+      a.x += gv.x; a.y += gv.y; a.z += gv.z; a.w += gv.w;
+      st_quad(ws.A, base, tg.lo, tg.hi, a);
+    }
+    return;
+  }
+  const MatTile t = ws.mtiles[blockIdx.x];
+  const LayerDev& L = ws.layers[t.layer];
+  const int r = L.rank[ws.level[t.layer]];
+  float* ppart = ws.Ppart + (int64_t)w * ws.ppart_stride;
+  if (L.vec4) {
+    switch (r) {
+      case 1: ef_p_tile<1, true>(ws, L, t, g, e, A, ppart); break;
+      case 2: ef_p_tile<2, true>(ws, L, t, g, e, A, ppart); break;
+      case 3: ef_p_tile<3, true>(ws, L, t, g, e, A, ppart); break;
+      default: ef_p_tile<4, true>(ws, L, t, g, e, A, ppart); break;
+    }
+  } else {
+    switch (r) {
+      case 1: ef_p_tile<1, false>(ws, L, t, g, e, A, ppart); break;
+      case 2: ef_p_tile<2, false>(ws, L, t, g, e, A, ppart); break;
+      case 3: ef_p_tile<3, false>(ws, L, t, g, e, A, ppart); break;
+      default: ef_p_tile<4, false>(ws, L, t, g, e, A, ppart); break;
+    }
+  }
+}
+
+// ---- aggregate 0: P_bar = mean over workers (and column chunks), Gram-Schmidt -----------
+
+// Sum over the 256 threads of a workgroup, same value for every thread.  `slot` alternates
+// between calls so that one barrier per call is enough.
+__device__ __forceinline__ float block_sum_256(float v, float (*red)[4], int& slot) {
+  v = wave_sum(v);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[slot][wave] = v;
+  __syncthreads();
+  const float r = (red[slot][0] + red[slot][1]) + (red[slot][2] + red[slot][3]);
+  slot ^= 1;
+  return r;
+}
+
+// Row i of P_bar: per worker the sum of the column-chunk partials (= P_w), then the mean.
+template <int R>
+__device__ __forceinline__ void pbar_row(const Ws& ws, const LayerDev& L, int i, float (&pb)[R]) {
+#pragma unroll
+  for (int k = 0; k < R; ++k) pb[k] = 0.f;
+  for (int w = 0; w < ws.W; ++w) {
+    const float* pp = ws.Ppart + (int64_t)w * ws.ppart_stride + L.ppart_off;
+    float pw[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) pw[k] = 0.f;
+    for (int c = 0; c < L.n_colchunks; ++c) {
+      const float* src = pp + ((int64_t)c * L.rows + i) * ws.rmax;
+#pragma unroll
+      for (int k = 0; k < R; ++k) pw[k] += src[k];
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k) pb[k] += pw[k];
+  }
+#pragma unroll
+  for (int k = 0; k < R; ++k) pb[k] = pb[k] / (float)ws.W;
+}
+
+// Modified Gram-Schmidt over the r columns of P_bar, in column order; a column of zero
+// length stays zero.  Layers of up to 1024 rows live in registers (4 rows per thread),
+// taller ones in global memory (each thread only ever touches its own rows).
+template <int R>
+__device__ void orth_layer(const Ws& ws, const LayerDev& L, float (*red)[4]) {
+  const int n = L.rows;
+  const int tid = threadIdx.x;
+  float* ph = ws.Phat + L.p_off;
+  int slot = 0;
+  if (n <= 4 * kFlatThreads) {
+    float v[4][R];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int i = s * kFlatThreads + tid;
+      if (i < n) {
+        pbar_row<R>(ws, L, i, v[s]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < R; ++k) v[s][k] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+#pragma unroll
+      for (int j = 0; j < R; ++j) {
+        if (j < k) {
+          float d = 0.f;
+#pragma unroll
+          for (int s = 0; s < 4; ++s) d = fmaf(v[s][j], v[s][k], d);
+          d = block_sum_256(d, red, slot);
+#pragma unroll
+          for (int s = 0; s < 4; ++s) v[s][k] = fmaf(-d, v[s][j], v[s][k]);
+        }
+      }
+      float nn = 0.f;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) nn = fmaf(v[s][k], v[s][k], nn);
+      nn = block_sum_256(nn, red, slot);
+      const float nrm = sqrtf(nn);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) v[s][k] = (nrm > 0.f) ? v[s][k] / nrm : 0.f;
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int i = s * kFlatThreads + tid;
+      if (i < n) {
+#pragma unroll
+        for (int k = 0; k < R; ++k) ph[(int64_t)i * ws.rmax + k] = v[s][k];
+      }
+    }
+  } else {
+    for (int i = tid; i < n; i += kFlatThreads) {
+      float pb[R];
+      pbar_row<R>(ws, L, i, pb);
+#pragma unroll
+      for (int k = 0; k < R; ++k) ph[(int64_t)i * ws.rmax + k] = pb[k];
+    }
+    for (int k = 0; k < R; ++k) {
+      for (int j = 0; j < k; ++j) {
+        float d = 0.f;
+        for (int i = tid; i < n; i += kFlatThreads)
+          d = fmaf(ph[(int64_t)i * ws.rmax + j], ph[(int64_t)i * ws.rmax + k], d);
+        d = block_sum_256(d, red, slot);
+        for (int i = tid; i < n; i += kFlatThreads)
+          ph[(int64_t)i * ws.rmax + k] =
+              fmaf(-d, ph[(int64_t)i * ws.rmax + j], ph[(int64_t)i * ws.rmax + k]);
+      }
+      float nn = 0.f;
+      for (int i = tid; i < n; i += kFlatThreads) {
+        const float x = ph[(int64_t)i * ws.rmax + k];
+        nn = fmaf(x, x, nn);
+      }
+      nn = block_sum_256(nn, red, slot);
+      const float nrm = sqrtf(nn);
+      for (int i = tid; i < n; i += kFlatThreads) {
+        const float x = ph[(int64_t)i * ws.rmax + k];
+        ph[(int64_t)i * ws.rmax + k] = (nrm > 0.f) ? x / nrm : 0.f;
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void psgd_orth_kernel(const Ws ws, const GradPtrs gp) {
+  __shared__ float red[2][4];
+  if ((int)blockIdx.x >= ws.n_mat) {
+    // 1-D layers are sent raw: mean over workers in worker order
+    const FlatTile ft = ws.ftiles[ws.vectiles[blockIdx.x - ws.n_mat]];
+    const LayerDev& L = ws.layers[ft.layer];
+    for (int i = threadIdx.x; i < ft.count; i += kFlatThreads) {
+      const int64_t a = L.offset + ft.start + i;
+      float s = gp.p[0][a];
+      for (int w = 1; w < ws.W; ++w) s += gp.p[w][a];
+      ws.vecmean[L.vec_off + ft.start + i] = s / (float)ws.W;
+    }
+    return;
+  }
+  const int li = ws.matlayers[blockIdx.x];
+  const LayerDev& L = ws.layers[li];
+  const int r = L.rank[ws.level[li]];
+  if (threadIdx.x == 0) ws.rank_used[li] = r;
+  switch (r) {
+    case 1: orth_layer<1>(ws, L, red); break;
+    case 2: orth_layer<2>(ws, L, red); break;
+    case 3: orth_layer<3>(ws, L, red); break;
+    default: orth_layer<4>(ws, L, red); break;
+  }
+}
+
+// ---- phase 1: Q partial = Delta^T P^ over one 64-row block -----------------------------------
+
+template <int R, bool V4>
+__device__ void q_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const float* __restrict__ e,
+                       float* __restrict__ qpart, float (*red)[16][64]) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int col[4]; bool cm[4];
+  lane_cols<V4>(t.col0, lane, L.cols, col, cm);
+  float acc[4][R];
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int k = 0; k < R; ++k) acc[v][k] = 0.f;
+  const int row_end = min(t.row0 + kMatRows, L.rows);
+  const float* __restrict__ ph = ws.Phat + L.p_off;
+  constexpr int B = 4;
+  for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
+    float d[B][4];
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      const int i = i0 + 4 * b;
+      if (i < row_end) load_row<V4>(e, L.offset + (int64_t)i * L.cols, col, cm, d[b]);
+    }
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      const int i = i0 + 4 * b;
+      if (i < row_end) {
+        float p[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) p[k] = ph[(int64_t)i * ws.rmax + k];
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+          for (int k = 0; k < R; ++k) acc[v][k] = fmaf(d[b][v], p[k], acc[v][k]);
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int k = 0; k < R; ++k) red[wave][v * R + k][lane] = acc[v][k];
+  __syncthreads();
+  // thread (wave, lane) finishes column slot v = wave of that lane: waves summed in order
+  {
+    const int v = wave;
+    const int cv = V4 ? t.col0 + lane * 4 + v : t.col0 + lane + 64 * v;
+    if (cv < L.cols) {
+      const int rb = t.row0 / kMatRows;
+      float* dst = qpart + L.qpart_off + ((int64_t)rb * L.cols + cv) * ws.rmax;
+#pragma unroll
+      for (int k = 0; k < R; ++k) {
+        const int s = v * R + k;
+        dst[k] = ((red[0][s][lane] + red[1][s][lane]) + red[2][s][lane]) + red[3][s][lane];
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void psgd_q_kernel(const Ws ws, int w0) {
+  __shared__ float red[4][16][64];
+  const int w = w0 + blockIdx.y;
+  const MatTile t = ws.mtiles[blockIdx.x];
+  const LayerDev& L = ws.layers[t.layer];
+  const int r = L.rank[ws.level[t.layer]];
+  const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  float* qpart = ws.Qpart + (int64_t)w * ws.qpart_stride;
+  if (L.vec4) {
+    switch (r) {
+      case 1: q_tile<1, true>(ws, L, t, e, qpart, red); break;
+      case 2: q_tile<2, true>(ws, L, t, e, qpart, red); break;
+      case 3: q_tile<3, true>(ws, L, t, e, qpart, red); break;
+      default: q_tile<4, true>(ws, L, t, e, qpart, red); break;
+    }
+  } else {
+    switch (r) {
+      case 1: q_tile<1, false>(ws, L, t, e, qpart, red); break;
+      case 2: q_tile<2, false>(ws, L, t, e, qpart, red); break;
+      case 3: q_tile<3, false>(ws, L, t, e, qpart, red); break;
+      default: q_tile<4, false>(ws, L, t, e, qpart, red); break;
+    }
+  }
+}
+
+// ---- aggregate 1: Q_bar = mean over workers of (sum over row blocks) -------------------------
+
+__global__ __launch_bounds__(256) void psgd_qmean_kernel(const Ws ws) {
+  const QTile t = ws.qtiles[blockIdx.x];
+  const LayerDev& L = ws.layers[t.layer];
+  const int r = L.rank[ws.level[t.layer]];
+  const int c = t.col0 + threadIdx.x;
+  if (c >= L.cols) return;
+  float tot[kMaxRank] = {0.f, 0.f, 0.f, 0.f};
+  for (int w = 0; w < ws.W; ++w) {
+    const float* qp = ws.Qpart + (int64_t)w * ws.qpart_stride + L.qpart_off;
+    float qw[kMaxRank] = {0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < L.n_rowblocks; ++rb) {
+      const float* src = qp + ((int64_t)rb * L.cols + c) * ws.rmax;
+      for (int k = 0; k < r; ++k) qw[k] += src[k];
+    }
+    for (int k = 0; k < r; ++k) tot[k] += qw[k];
+  }
+  float* dst = ws.Q + L.q_off + (int64_t)c * ws.rmax;
+  for (int k = 0; k < r; ++k) dst[k] = tot[k] / (float)ws.W;
+}
+
+// ---- decompress: D = P^ Q_bar^T, e_w = Delta_w - D ------------------------------------------
+
+template <int R, bool V4>
+__device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, float* __restrict__ e,
+                            float* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int col[4]; bool cm[4];
+  lane_cols<V4>(t.col0, lane, L.cols, col, cm);
+  float q[4][R];
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int k = 0; k < R; ++k)
+      q[v][k] = cm[v] ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
+  const int row_end = min(t.row0 + kMatRows, L.rows);
+  const float* __restrict__ ph = ws.Phat + L.p_off;
+  constexpr int B = 4;
+  for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
+    float d[B][4];
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      const int i = i0 + 4 * b;
+      if (i < row_end) load_row<V4>(e, L.offset + (int64_t)i * L.cols, col, cm, d[b]);
+    }
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      const int i = i0 + 4 * b;
+      if (i < row_end) {
+        const int64_t rb = L.offset + (int64_t)i * L.cols;
+        float p[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) p[k] = ph[(int64_t)i * ws.rmax + k];
+        float D[4], res[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          float s = p[0] * q[v][0];
+#pragma unroll
+          for (int k = 1; k < R; ++k) s = fmaf(p[k], q[v][k], s);
+          D[v] = s;
+          res[v] = d[b][v] - s;
+        }
+        store_row<V4>(e, rb, col, cm, res);
+        if (out) store_row<V4>(out, rb, col, cm, D);
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void psgd_decomp_kernel(const Ws ws, float* __restrict__ out) {
+  const int w = blockIdx.y;
+  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  if (blockIdx.x == 0 && w == 0 && threadIdx.x == 0) {
+    ws.words[1] = ws.words[0];
+    ws.words[2] += ws.words[0];
+  }
+  if ((int)blockIdx.x >= ws.n_mtiles) {
+    // 1-D layers: the plain mean goes out, no memory is kept
+    const FlatTile ft = ws.ftiles[ws.vectiles[blockIdx.x - ws.n_mtiles]];
+    const LayerDev& L = ws.layers[ft.layer];
+    for (int i = threadIdx.x; i < ft.count; i += kFlatThreads) {
+      const int64_t a = L.offset + ft.start + i;
+      e[a] = 0.f;
+      if (w == 0) out[a] = ws.vecmean[L.vec_off + ft.start + i];
+    }
+    return;
+  }
+  const MatTile t = ws.mtiles[blockIdx.x];
+  const LayerDev& L = ws.layers[t.layer];
+  const int r = L.rank[ws.level[t.layer]];
+  float* o = (w == 0) ? out : nullptr;
+  if (L.vec4) {
+    switch (r) {
+      case 1: decomp_tile<1, true>(ws, L, t, e, o); break;
+      case 2: decomp_tile<2, true>(ws, L, t, e, o); break;
+      case 3: decomp_tile<3, true>(ws, L, t, e, o); break;
+      default: decomp_tile<4, true>(ws, L, t, e, o); break;
+    }
+  } else {
+    switch (r) {
+      case 1: decomp_tile<1, false>(ws, L, t, e, o); break;
+      case 2: decomp_tile<2, false>(ws, L, t, e, o); break;
+      case 3: decomp_tile<3, false>(ws, L, t, e, o); break;
+      default: decomp_tile<4, false>(ws, L, t, e, o); break;
+    }
+  }
+}
+
+}  // namespace acc

@@ -1,0 +1,91 @@
+// Accumulated-gradient norms and the per-layer critical-regime decision (Section 4.2,
+// Algorithm 1 of the paper), entirely on the device.
+#pragma once
+#include "acc_common.h"
+
+namespace acc {
+
+// Per flat tile: sum of squares of A in fp64 (each fp32 square is exact in fp64), then A <- 0.
+__global__ __launch_bounds__(256) void norm_partial_kernel(const Ws ws) {
+  __shared__ double red[4];
+  const int tid = threadIdx.x;
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  const TileGeom tg = tile_geom(L, ft);
+  double s = 0.0;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int q = tid; q < tg.nquads; q += kFlatThreads) {
+    const int64_t base = tg.a0 + 4 * (int64_t)q;
+    const float4 a = ld_quad(ws.A, base, tg.lo, tg.hi);   // outside the tile: 0
+    s += (double)a.x * (double)a.x;
+    s += (double)a.y * (double)a.y;
+    s += (double)a.z * (double)a.z;
+    s += (double)a.w * (double)a.w;
+    st_quad(ws.A, base, tg.lo, tg.hi, zero);
+  }
+  s = wave_sum_f64(s);
+  if ((tid & 63) == 0) red[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) ws.norm_part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(256) void zero_accum_kernel(const Ws ws) {
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  const TileGeom tg = tile_geom(L, ft);
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int q = threadIdx.x; q < tg.nquads; q += kFlatThreads)
+    st_quad(ws.A, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi, zero);
+}
+
+// One wave per layer: c = sqrt(sum of the layer's tile partials), then Algorithm 1 in fp32:
+// critical <=> lr_next < lr_curr, or no previous norm, or previous norm 0,
+//              or |old - c| / old >= eta.   level <- critical; old <- c.
+__global__ __launch_bounds__(64) void regime_decide_kernel(const Ws ws, float lr_curr, float lr_next) {
+  const int li = blockIdx.x;
+  const int lane = threadIdx.x;
+  const LayerDev& L = ws.layers[li];
+  double s = 0.0;
+  for (int t = lane; t < L.ntiles; t += kWave) s += ws.norm_part[L.tile0 + t];
+  s = wave_sum_f64(s);
+  if (lane == 0) {
+    const float c = (float)sqrt(s);
+    const float old = ws.norm_old[li];
+    const bool has_old = ws.has_old[li] != 0;
+    bool crit;
+    if (lr_next < lr_curr) crit = true;
+    else if (!has_old) crit = true;
+    else if (old == 0.0f) crit = true;
+    else crit = (fabsf(old - c) / old) >= ws.eta;
+    ws.level[li] = crit ? 1 : 0;
+    ws.norm_prev[li] = old;
+    ws.norm_curr[li] = c;
+    ws.norm_old[li] = c;
+    ws.has_old[li] = 1;
+  }
+}
+
+// Floats one worker sends per step at the current levels (the paper's "Data Sent" unit).
+__global__ __launch_bounds__(256) void recount_words_kernel(const Ws ws, int method) {
+  __shared__ unsigned long long red[256];
+  unsigned long long s = 0;
+  for (int li = threadIdx.x; li < ws.L; li += 256) {
+    const LayerDev& L = ws.layers[li];
+    const int lv = ws.level[li];
+    if (method == 0) {
+      if (L.is_matrix) s += (unsigned long long)L.rank[lv] * (unsigned long long)(L.rows + L.cols);
+      else s += (unsigned long long)L.rows * (unsigned long long)L.cols;
+    } else {
+      s += 2ull * (unsigned long long)L.k[lv];
+    }
+  }
+  red[threadIdx.x] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long t = 0;
+    for (int i = 0; i < 256; ++i) t += red[i];
+    ws.words[0] = t;
+  }
+}
+
+}  // namespace acc

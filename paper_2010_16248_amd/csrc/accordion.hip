@@ -1,0 +1,682 @@
+// Host side of the Accordion hot-path library: configuration checks, workspace layout,
+// tile tables, the step state machine and the kernel launches.  The C ABI is declared and
+// documented in include/accordion.h.
+#include "../../include/accordion.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "acc_common.h"
+#include "acc_powersgd.h"
+#include "acc_regime.h"
+#include "acc_topk.h"
+
+using namespace acc;
+
+namespace {
+
+thread_local char g_init_error[256] = "no error";
+
+inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+struct Region { int64_t off = 0, bytes = 0; };
+
+// Everything that follows from the configuration alone (no GPU needed).
+struct Plan {
+  std::vector<LayerDev> layers;
+  std::vector<FlatTile> ftiles;
+  std::vector<MatTile> mtiles;
+  std::vector<QTile> qtiles;
+  std::vector<int32_t> vectiles;
+  std::vector<int32_t> matlayers;
+  int32_t rmax = 0;
+  int64_t N = 0, e_stride = 0;
+  int64_t q_total = 0, p_total = 0, ppart_stride = 0, qpart_stride = 0, vec_total = 0;
+  int64_t pay_stride = 0, cand_stride = 0, tile_stride = 0;
+  // workspace regions
+  Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
+  Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
+  Region r_A, r_e, r_norm_part;
+  Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean;
+  Region r_hist1, r_sel, r_cand, r_gt, r_eq, r_seloff, r_eqoff, r_payidx, r_payval;
+  int64_t total_bytes = 0;
+};
+
+int fail(char* buf, int code, const char* msg) {
+  std::snprintf(buf, 256, "%s", msg);
+  return code;
+}
+
+int make_plan(const acc_config* c, Plan& p, char* err) {
+  if (!c) return fail(err, ACC_EINVAL, "config is NULL");
+  if (c->method != ACC_POWERSGD && c->method != ACC_TOPK) return fail(err, ACC_EINVAL, "unknown method");
+  if (c->n_layers <= 0 || c->n_layers > (1 << 20)) return fail(err, ACC_EINVAL, "n_layers out of range");
+  if (!c->layers) return fail(err, ACC_EINVAL, "layers is NULL");
+  if (c->n_workers < 1 || c->n_workers > ACC_MAX_WORKERS) return fail(err, ACC_EINVAL, "n_workers out of range");
+  if (c->n_params <= 0 || c->n_params > (int64_t(1) << 40)) return fail(err, ACC_EINVAL, "n_params out of range");
+  if (!(c->eta >= 0.0f) || !std::isfinite(c->eta)) return fail(err, ACC_EINVAL, "eta must be finite and >= 0");
+  if (c->initial_level != 0 && c->initial_level != 1) return fail(err, ACC_EINVAL, "initial_level must be 0 or 1");
+  if (c->method == ACC_POWERSGD) {
+    if (c->rank_crit < 1 || c->rank_crit > ACC_MAX_RANK || c->rank_noncrit < 1 || c->rank_noncrit > ACC_MAX_RANK)
+      return fail(err, ACC_EINVAL, "rank out of [1, ACC_MAX_RANK]");
+  } else {
+    if (c->k_den < 1 || c->k_num_crit < 1 || c->k_num_noncrit < 1 || c->k_num_crit > c->k_den ||
+        c->k_num_noncrit > c->k_den)
+      return fail(err, ACC_EINVAL, "k fraction out of (0, 1]");
+  }
+  const int nl = c->n_layers;
+  // layers: positive shapes, inside the flat buffer, pairwise disjoint
+  std::vector<std::pair<int64_t, int64_t>> spans;
+  spans.reserve(nl);
+  for (int i = 0; i < nl; ++i) {
+    const acc_layer& l = c->layers[i];
+    if (l.rows < 1 || l.cols < 1) return fail(err, ACC_EINVAL, "layer with rows < 1 or cols < 1");
+    if (l.is_matrix != 0 && l.is_matrix != 1) return fail(err, ACC_EINVAL, "is_matrix must be 0 or 1");
+    const int64_t n = (int64_t)l.rows * l.cols;
+    if (n >= (int64_t(1) << 31)) return fail(err, ACC_EINVAL, "layer has 2^31 or more elements");
+    if (l.offset < 0 || l.offset + n > c->n_params) return fail(err, ACC_EINVAL, "layer outside [0, n_params)");
+    spans.emplace_back(l.offset, l.offset + n);
+  }
+  std::sort(spans.begin(), spans.end());
+  for (size_t i = 1; i < spans.size(); ++i)
+    if (spans[i].first < spans[i - 1].second) return fail(err, ACC_EINVAL, "layers overlap");
+
+  p.N = c->n_params;
+  p.e_stride = align_up(p.N, 64);
+  p.rmax = (c->method == ACC_POWERSGD) ? std::max(c->rank_crit, c->rank_noncrit) : 0;
+  p.layers.resize(nl);
+  int64_t ntile = 0;
+  for (int i = 0; i < nl; ++i) {
+    const acc_layer& l = c->layers[i];
+    LayerDev& d = p.layers[i];
+    std::memset(&d, 0, sizeof(d));
+    const int64_t n = (int64_t)l.rows * l.cols;
+    d.offset = l.offset;
+    d.rows = l.rows;
+    d.cols = l.cols;
+    d.is_matrix = (c->method == ACC_POWERSGD && l.is_matrix) ? 1 : 0;
+    d.vec4 = (l.offset % 4 == 0 && l.cols % 4 == 0) ? 1 : 0;
+    d.tile0 = (int32_t)ntile;
+    d.ntiles = (int32_t)((n + kTile - 1) / kTile);
+    d.toff = d.tile0 + i;
+    for (int t = 0; t < d.ntiles; ++t) {
+      FlatTile ft;
+      ft.layer = i;
+      ft.start = t * kTile;
+      ft.count = (int32_t)std::min<int64_t>(kTile, n - (int64_t)t * kTile);
+      ft.pad = 0;
+      p.ftiles.push_back(ft);
+    }
+    ntile += d.ntiles;
+    if (ntile > (int64_t(1) << 30)) return fail(err, ACC_EINVAL, "too many tiles");
+    if (c->method == ACC_POWERSGD) {
+      if (d.is_matrix) {
+        const int cap = std::min(l.rows, l.cols);
+        d.rank[0] = std::max(1, std::min(c->rank_noncrit, cap));
+        d.rank[1] = std::max(1, std::min(c->rank_crit, cap));
+        d.n_colchunks = (l.cols + kMatCols - 1) / kMatCols;
+        d.n_rowblocks = (l.rows + kMatRows - 1) / kMatRows;
+        d.q_off = p.q_total;
+        p.q_total += (int64_t)l.cols * p.rmax;
+        d.p_off = p.p_total;
+        p.p_total += (int64_t)l.rows * p.rmax;
+        d.ppart_off = p.ppart_stride;
+        p.ppart_stride += (int64_t)d.n_colchunks * l.rows * p.rmax;
+        d.qpart_off = p.qpart_stride;
+        p.qpart_stride += (int64_t)d.n_rowblocks * l.cols * p.rmax;
+        p.matlayers.push_back(i);
+        for (int rb = 0; rb < d.n_rowblocks; ++rb)
+          for (int cc = 0; cc < d.n_colchunks; ++cc) {
+            MatTile mt;
+            mt.layer = i;
+            mt.row0 = rb * kMatRows;
+            mt.col0 = cc * kMatCols;
+            mt.pad = 0;
+            p.mtiles.push_back(mt);
+          }
+        for (int cc = 0; cc < d.n_colchunks; ++cc) {
+          QTile qt;
+          qt.layer = i;
+          qt.col0 = cc * kMatCols;
+          p.qtiles.push_back(qt);
+        }
+      } else {
+        d.vec_off = p.vec_total;
+        p.vec_total += n;
+        for (int t = 0; t < d.ntiles; ++t) p.vectiles.push_back(d.tile0 + t);
+      }
+    } else {
+      auto kof = [&](int num) {
+        const int64_t k = ((int64_t)n * num + c->k_den - 1) / c->k_den;
+        return (int32_t)std::max<int64_t>(1, std::min<int64_t>(n, k));
+      };
+      d.k[0] = kof(c->k_num_noncrit);
+      d.k[1] = kof(c->k_num_crit);
+      d.pay_off = p.pay_stride;
+      p.pay_stride += std::max(d.k[0], d.k[1]);
+      d.cand_off = p.cand_stride;
+      d.cand_cap = std::min<int64_t>(n, std::max<int64_t>(n / 8, 4096));
+      p.cand_stride += d.cand_cap;
+    }
+  }
+  p.tile_stride = ntile + nl;
+
+  // workspace layout, 256-byte aligned regions
+  int64_t off = 0;
+  auto reg = [&](Region& r, int64_t bytes) {
+    r.off = off;
+    r.bytes = bytes;
+    off = align_up(off + std::max<int64_t>(bytes, 0), 256);
+  };
+  const int64_t W = c->n_workers;
+  reg(p.r_layers, (int64_t)sizeof(LayerDev) * nl);
+  reg(p.r_ftiles, (int64_t)sizeof(FlatTile) * (int64_t)p.ftiles.size());
+  reg(p.r_mtiles, (int64_t)sizeof(MatTile) * (int64_t)p.mtiles.size());
+  reg(p.r_qtiles, (int64_t)sizeof(QTile) * (int64_t)p.qtiles.size());
+  reg(p.r_vectiles, 4 * (int64_t)p.vectiles.size());
+  reg(p.r_matlayers, 4 * (int64_t)p.matlayers.size());
+  reg(p.r_level, 4 * (int64_t)nl);
+  reg(p.r_norm_old, 4 * (int64_t)nl);
+  reg(p.r_norm_prev, 4 * (int64_t)nl);
+  reg(p.r_norm_curr, 4 * (int64_t)nl);
+  reg(p.r_has_old, 4 * (int64_t)nl);
+  reg(p.r_rank_used, 4 * (int64_t)nl);
+  reg(p.r_words, 8 * 4);
+  reg(p.r_A, 4 * p.e_stride);
+  reg(p.r_e, 4 * p.e_stride * W);
+  reg(p.r_norm_part, 8 * ntile);
+  if (c->method == ACC_POWERSGD) {
+    reg(p.r_Q, 4 * p.q_total);
+    reg(p.r_Phat, 4 * p.p_total);
+    reg(p.r_Ppart, 4 * p.ppart_stride * W);
+    reg(p.r_Qpart, 4 * p.qpart_stride * W);
+    reg(p.r_vecmean, 4 * p.vec_total);
+  } else {
+    reg(p.r_hist1, 4 * (int64_t)kHistBins * nl * W);
+    reg(p.r_sel, (int64_t)sizeof(SelState) * nl * W);
+    reg(p.r_cand, 8 * p.cand_stride * W);
+    reg(p.r_gt, 4 * p.tile_stride * W);
+    reg(p.r_eq, 4 * p.tile_stride * W);
+    reg(p.r_seloff, 4 * p.tile_stride * W);
+    reg(p.r_eqoff, 4 * p.tile_stride * W);
+    reg(p.r_payidx, 4 * p.pay_stride * W);
+    reg(p.r_payval, 4 * p.pay_stride * W);
+  }
+  p.total_bytes = off;
+  return ACC_OK;
+}
+
+}  // namespace
+
+struct acc_ctx {
+  acc_config cfg;
+  std::vector<acc_layer> layers;
+  Plan plan;
+  Ws ws;
+  char* base = nullptr;
+  hipStream_t stream = nullptr;
+  // step state machine
+  bool in_step = false;
+  uint32_t p0_mask = 0, p1_mask = 0;
+  bool agg0 = false, agg1 = false;
+  GradPtrs grads;
+  char err[256];
+};
+
+namespace {
+
+#define ACC_HIP(ctx, call)                                                              \
+  do {                                                                                  \
+    hipError_t e_ = (call);                                                             \
+    if (e_ != hipSuccess) {                                                             \
+      std::snprintf((ctx)->err, 256, "%s failed: %s", #call, hipGetErrorString(e_));    \
+      return ACC_EHIP;                                                                  \
+    }                                                                                   \
+  } while (0)
+
+template <class T>
+T* at(acc_ctx* c, const Region& r) { return reinterpret_cast<T*>(c->base + r.off); }
+
+uint32_t all_workers_mask(const acc_ctx* c) {
+  return c->cfg.n_workers == 32 ? 0xffffffffu : ((1u << c->cfg.n_workers) - 1u);
+}
+
+int check_launch(acc_ctx* c, const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    std::snprintf(c->err, 256, "launch of %s failed: %s", what, hipGetErrorString(e));
+    return ACC_EHIP;
+  }
+  return ACC_OK;
+}
+
+#define ACC_LAUNCH(ctx, name, grid, block, ...)                              \
+  do {                                                                       \
+    hipLaunchKernelGGL(name, grid, block, 0, (ctx)->stream, __VA_ARGS__);    \
+    int rc_ = check_launch(ctx, #name);                                      \
+    if (rc_ != ACC_OK) return rc_;                                           \
+  } while (0)
+
+// --- launches of each stage for workers [w0, w0 + nw) ------------------------------------
+
+int launch_phase0(acc_ctx* c, int w0, int nw) {
+  const Ws& ws = c->ws;
+  if (c->cfg.method == ACC_POWERSGD) {
+    const int gx = ws.n_mtiles + (w0 == 0 ? ws.n_vectiles : 0);
+    if (gx > 0) ACC_LAUNCH(c, psgd_ef_p_kernel, dim3(gx, nw), dim3(256), ws, c->grads, w0);
+  } else {
+    ACC_LAUNCH(c, topk_ef_hist_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, c->grads, w0);
+    ACC_LAUNCH(c, topk_pick1_kernel, dim3(ws.L, nw), dim3(256), ws, w0);
+    ACC_LAUNCH(c, topk_cand_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
+    ACC_LAUNCH(c, topk_resolve_kernel, dim3(ws.L, nw), dim3(kResolveThreads), ws, w0);
+    ACC_LAUNCH(c, topk_compact_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
+  }
+  return ACC_OK;
+}
+
+int launch_agg0(acc_ctx* c) {
+  const Ws& ws = c->ws;
+  if (c->cfg.method == ACC_POWERSGD) {
+    const int gx = ws.n_mat + ws.n_vectiles;
+    if (gx > 0) ACC_LAUNCH(c, psgd_orth_kernel, dim3(gx), dim3(256), ws, c->grads);
+  }
+  return ACC_OK;
+}
+
+int launch_phase1(acc_ctx* c, int w0, int nw) {
+  const Ws& ws = c->ws;
+  if (ws.n_mtiles > 0) ACC_LAUNCH(c, psgd_q_kernel, dim3(ws.n_mtiles, nw), dim3(256), ws, w0);
+  return ACC_OK;
+}
+
+int launch_agg1(acc_ctx* c) {
+  const Ws& ws = c->ws;
+  if (ws.n_qtiles > 0) ACC_LAUNCH(c, psgd_qmean_kernel, dim3(ws.n_qtiles), dim3(256), ws);
+  return ACC_OK;
+}
+
+int launch_decompress(acc_ctx* c, float* out) {
+  const Ws& ws = c->ws;
+  if (c->cfg.method == ACC_POWERSGD) {
+    ACC_LAUNCH(c, psgd_decomp_kernel, dim3(ws.n_mtiles + ws.n_vectiles, ws.W), dim3(256), ws, out);
+  } else {
+    ACC_LAUNCH(c, topk_sparse_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, out);
+  }
+  return ACC_OK;
+}
+
+void end_step(acc_ctx* c) {
+  c->in_step = false;
+  c->p0_mask = c->p1_mask = 0;
+  c->agg0 = c->agg1 = false;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+size_t state_bytes_of(const acc_ctx* c) {
+  const Plan& p = c->plan;
+  const size_t L = (size_t)c->cfg.n_layers;
+  return 4 * ((size_t)p.N * (size_t)(c->cfg.n_workers + 1) + (size_t)p.q_total + 3 * L);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t accordion_workspace_bytes(const acc_config* cfg, size_t* out_bytes) {
+  if (!out_bytes) return fail(g_init_error, ACC_EINVAL, "out_bytes is NULL");
+  Plan p;
+  const int rc = make_plan(cfg, p, g_init_error);
+  if (rc != ACC_OK) return rc;
+  *out_bytes = (size_t)p.total_bytes;
+  return ACC_OK;
+}
+
+int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t workspace_bytes,
+                       const float* q_init_host, void* hip_stream, acc_ctx** out) {
+  if (!out) return fail(g_init_error, ACC_EINVAL, "out is NULL");
+  *out = nullptr;
+  acc_ctx* c = new (std::nothrow) acc_ctx();
+  if (!c) return fail(g_init_error, ACC_ENOSPACE, "out of host memory");
+  auto bail = [&](int rc, const char* msg) {
+    if (msg) std::snprintf(g_init_error, 256, "%s", msg);
+    else std::snprintf(g_init_error, 256, "%s", c->err);
+    delete c;
+    return rc;
+  };
+  int rc = make_plan(cfg, c->plan, g_init_error);
+  if (rc != ACC_OK) { delete c; return rc; }
+  if (!workspace_dev) return bail(ACC_EINVAL, "workspace is NULL");
+  if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255u) != 0) return bail(ACC_EINVAL, "workspace is not 256-byte aligned");
+  if (workspace_bytes < (size_t)c->plan.total_bytes) return bail(ACC_ENOSPACE, "workspace too small");
+  if (cfg->method == ACC_POWERSGD && c->plan.q_total > 0 && !q_init_host)
+    return bail(ACC_EINVAL, "q_init_host is NULL");
+  c->cfg = *cfg;
+  c->layers.assign(cfg->layers, cfg->layers + cfg->n_layers);
+  c->cfg.layers = c->layers.data();
+  c->base = static_cast<char*>(workspace_dev);
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  std::snprintf(c->err, 256, "no error");
+  std::memset(&c->grads, 0, sizeof(c->grads));
+  Plan& p = c->plan;
+
+  Ws& ws = c->ws;
+  std::memset(&ws, 0, sizeof(ws));
+  ws.layers = at<LayerDev>(c, p.r_layers);
+  ws.ftiles = at<FlatTile>(c, p.r_ftiles);
+  ws.mtiles = at<MatTile>(c, p.r_mtiles);
+  ws.qtiles = at<QTile>(c, p.r_qtiles);
+  ws.vectiles = at<int32_t>(c, p.r_vectiles);
+  ws.matlayers = at<int32_t>(c, p.r_matlayers);
+  ws.level = at<int32_t>(c, p.r_level);
+  ws.norm_old = at<float>(c, p.r_norm_old);
+  ws.norm_prev = at<float>(c, p.r_norm_prev);
+  ws.norm_curr = at<float>(c, p.r_norm_curr);
+  ws.has_old = at<int32_t>(c, p.r_has_old);
+  ws.rank_used = at<int32_t>(c, p.r_rank_used);
+  ws.words = at<unsigned long long>(c, p.r_words);
+  ws.A = at<float>(c, p.r_A);
+  ws.e = at<float>(c, p.r_e);
+  ws.e_stride = p.e_stride;
+  ws.norm_part = at<double>(c, p.r_norm_part);
+  if (cfg->method == ACC_POWERSGD) {
+    ws.Q = at<float>(c, p.r_Q);
+    ws.Phat = at<float>(c, p.r_Phat);
+    ws.Ppart = at<float>(c, p.r_Ppart);
+    ws.ppart_stride = p.ppart_stride;
+    ws.Qpart = at<float>(c, p.r_Qpart);
+    ws.qpart_stride = p.qpart_stride;
+    ws.vecmean = at<float>(c, p.r_vecmean);
+  } else {
+    ws.hist1 = at<uint32_t>(c, p.r_hist1);
+    ws.sel = at<SelState>(c, p.r_sel);
+    ws.cand = at<uint2>(c, p.r_cand);
+    ws.cand_stride = p.cand_stride;
+    ws.gt_cnt = at<uint32_t>(c, p.r_gt);
+    ws.eq_cnt = at<uint32_t>(c, p.r_eq);
+    ws.sel_off = at<uint32_t>(c, p.r_seloff);
+    ws.eq_off = at<uint32_t>(c, p.r_eqoff);
+    ws.pay_idx = at<int32_t>(c, p.r_payidx);
+    ws.pay_val = at<float>(c, p.r_payval);
+    ws.pay_stride = p.pay_stride;
+  }
+  ws.tile_stride = p.tile_stride;
+  ws.N = p.N;
+  ws.W = cfg->n_workers;
+  ws.L = cfg->n_layers;
+  ws.rmax = p.rmax;
+  ws.n_ftiles = (int32_t)p.ftiles.size();
+  ws.n_mtiles = (int32_t)p.mtiles.size();
+  ws.n_qtiles = (int32_t)p.qtiles.size();
+  ws.n_vectiles = (int32_t)p.vectiles.size();
+  ws.n_mat = (int32_t)p.matlayers.size();
+  ws.eta = cfg->eta;
+
+  auto init_dev = [&]() -> int {
+    ACC_HIP(c, hipMemsetAsync(c->base, 0, (size_t)p.total_bytes, c->stream));
+    ACC_HIP(c, hipStreamSynchronize(c->stream));
+    auto up = [&](const Region& r, const void* src) -> hipError_t {
+      if (r.bytes == 0) return hipSuccess;
+      return hipMemcpy(c->base + r.off, src, (size_t)r.bytes, hipMemcpyHostToDevice);
+    };
+    ACC_HIP(c, up(p.r_layers, p.layers.data()));
+    ACC_HIP(c, up(p.r_ftiles, p.ftiles.data()));
+    ACC_HIP(c, up(p.r_mtiles, p.mtiles.data()));
+    ACC_HIP(c, up(p.r_qtiles, p.qtiles.data()));
+    ACC_HIP(c, up(p.r_vectiles, p.vectiles.data()));
+    ACC_HIP(c, up(p.r_matlayers, p.matlayers.data()));
+    std::vector<int32_t> lv((size_t)cfg->n_layers, cfg->initial_level);
+    ACC_HIP(c, up(p.r_level, lv.data()));
+    if (cfg->method == ACC_POWERSGD && p.q_total > 0) ACC_HIP(c, up(p.r_Q, q_init_host));
+    ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)cfg->method);
+    ACC_HIP(c, hipStreamSynchronize(c->stream));
+    return ACC_OK;
+  };
+  rc = init_dev();
+  if (rc != ACC_OK) return bail(rc, nullptr);
+  *out = c;
+  return ACC_OK;
+}
+
+int32_t accordion_destroy(acc_ctx* ctx) {
+  if (!ctx) return ACC_EINVAL;
+  delete ctx;
+  return ACC_OK;
+}
+
+const char* accordion_last_error(const acc_ctx* ctx) { return ctx ? ctx->err : g_init_error; }
+
+int32_t accordion_compress_step(acc_ctx* c, int32_t worker, const float* grad_dev, int32_t phase) {
+  if (!c) return ACC_EINVAL;
+  if (worker < 0 || worker >= c->cfg.n_workers) return fail(c->err, ACC_EINVAL, "worker out of range");
+  const uint32_t bit = 1u << worker;
+  if (phase == 0) {
+    if (!grad_dev) return fail(c->err, ACC_EINVAL, "grad_dev is NULL");
+    if (misaligned(grad_dev)) return fail(c->err, ACC_EINVAL, "grad_dev is not 16-byte aligned");
+    if (c->agg0) return fail(c->err, ACC_ESTATE, "phase 0 after aggregate(0); finish the step with decompress first");
+    if (c->p0_mask & bit) return fail(c->err, ACC_ESTATE, "worker already compressed in this step");
+    c->grads.p[worker] = grad_dev;
+    const int rc = launch_phase0(c, worker, 1);
+    if (rc != ACC_OK) return rc;
+    c->in_step = true;
+    c->p0_mask |= bit;
+    return ACC_OK;
+  }
+  if (phase == 1) {
+    if (c->cfg.method != ACC_POWERSGD) return fail(c->err, ACC_EINVAL, "phase 1 exists for PowerSGD only");
+    if (!c->agg0 || c->agg1) return fail(c->err, ACC_ESTATE, "phase 1 needs aggregate(0) first and comes before aggregate(1)");
+    if (c->p1_mask & bit) return fail(c->err, ACC_ESTATE, "worker already did phase 1 in this step");
+    const int rc = launch_phase1(c, worker, 1);
+    if (rc != ACC_OK) return rc;
+    c->p1_mask |= bit;
+    return ACC_OK;
+  }
+  return fail(c->err, ACC_EINVAL, "phase must be 0 or 1");
+}
+
+int32_t accordion_aggregate(acc_ctx* c, int32_t phase) {
+  if (!c) return ACC_EINVAL;
+  if (phase == 0) {
+    if (c->agg0) return fail(c->err, ACC_ESTATE, "aggregate(0) already done");
+    if (c->p0_mask != all_workers_mask(c)) return fail(c->err, ACC_ESTATE, "aggregate(0) needs phase 0 of every worker");
+    const int rc = launch_agg0(c);
+    if (rc != ACC_OK) return rc;
+    c->agg0 = true;
+    return ACC_OK;
+  }
+  if (phase == 1) {
+    if (c->cfg.method != ACC_POWERSGD) return fail(c->err, ACC_EINVAL, "phase 1 exists for PowerSGD only");
+    if (!c->agg0 || c->agg1) return fail(c->err, ACC_ESTATE, "aggregate(1) out of order");
+    if (c->p1_mask != all_workers_mask(c)) return fail(c->err, ACC_ESTATE, "aggregate(1) needs phase 1 of every worker");
+    const int rc = launch_agg1(c);
+    if (rc != ACC_OK) return rc;
+    c->agg1 = true;
+    return ACC_OK;
+  }
+  return fail(c->err, ACC_EINVAL, "phase must be 0 or 1");
+}
+
+int32_t accordion_decompress(acc_ctx* c, float* out_dev) {
+  if (!c) return ACC_EINVAL;
+  if (!out_dev) return fail(c->err, ACC_EINVAL, "out_dev is NULL");
+  if (misaligned(out_dev)) return fail(c->err, ACC_EINVAL, "out_dev is not 16-byte aligned");
+  if (c->cfg.method == ACC_POWERSGD ? !c->agg1 : !c->agg0)
+    return fail(c->err, ACC_ESTATE, "decompress before the aggregation of this step is complete");
+  const int rc = launch_decompress(c, out_dev);
+  if (rc != ACC_OK) return rc;
+  end_step(c);
+  return ACC_OK;
+}
+
+int32_t accordion_step_all(acc_ctx* c, const float* const* grads_host_array, float* out_dev) {
+  if (!c) return ACC_EINVAL;
+  if (!grads_host_array) return fail(c->err, ACC_EINVAL, "grads_host_array is NULL");
+  if (!out_dev) return fail(c->err, ACC_EINVAL, "out_dev is NULL");
+  if (misaligned(out_dev)) return fail(c->err, ACC_EINVAL, "out_dev is not 16-byte aligned");
+  if (c->in_step) return fail(c->err, ACC_ESTATE, "a call-by-call step is in flight");
+  const int W = c->cfg.n_workers;
+  for (int w = 0; w < W; ++w) {
+    if (!grads_host_array[w]) return fail(c->err, ACC_EINVAL, "a gradient pointer is NULL");
+    if (misaligned(grads_host_array[w])) return fail(c->err, ACC_EINVAL, "a gradient pointer is not 16-byte aligned");
+  }
+  for (int w = 0; w < W; ++w) c->grads.p[w] = grads_host_array[w];
+  int rc = launch_phase0(c, 0, W);
+  if (rc == ACC_OK) rc = launch_agg0(c);
+  if (rc == ACC_OK && c->cfg.method == ACC_POWERSGD) {
+    rc = launch_phase1(c, 0, W);
+    if (rc == ACC_OK) rc = launch_agg1(c);
+  }
+  if (rc == ACC_OK) rc = launch_decompress(c, out_dev);
+  end_step(c);
+  return rc;
+}
+
+int32_t accordion_detect_regime(acc_ctx* c, float lr_curr, float lr_next) {
+  if (!c) return ACC_EINVAL;
+  if (c->in_step) return fail(c->err, ACC_ESTATE, "detect_regime inside a step");
+  const Ws& ws = c->ws;
+  ACC_LAUNCH(c, norm_partial_kernel, dim3(ws.n_ftiles), dim3(256), ws);
+  ACC_LAUNCH(c, regime_decide_kernel, dim3(ws.L), dim3(64), ws, lr_curr, lr_next);
+  ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), ws, (int)c->cfg.method);
+  return ACC_OK;
+}
+
+int32_t accordion_reset_accumulator(acc_ctx* c) {
+  if (!c) return ACC_EINVAL;
+  if (c->in_step) return fail(c->err, ACC_ESTATE, "reset_accumulator inside a step");
+  ACC_LAUNCH(c, zero_accum_kernel, dim3(c->ws.n_ftiles), dim3(256), c->ws);
+  return ACC_OK;
+}
+
+int32_t accordion_get_levels(acc_ctx* c, int32_t* levels_host) {
+  if (!c) return ACC_EINVAL;
+  if (!levels_host) return fail(c->err, ACC_EINVAL, "levels_host is NULL");
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  ACC_HIP(c, hipMemcpy(levels_host, c->ws.level, 4 * (size_t)c->cfg.n_layers, hipMemcpyDeviceToHost));
+  return ACC_OK;
+}
+
+int32_t accordion_get_norms(acc_ctx* c, float* old_host, float* curr_host) {
+  if (!c) return ACC_EINVAL;
+  if (!old_host || !curr_host) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  ACC_HIP(c, hipMemcpy(old_host, c->ws.norm_prev, 4 * (size_t)c->cfg.n_layers, hipMemcpyDeviceToHost));
+  ACC_HIP(c, hipMemcpy(curr_host, c->ws.norm_curr, 4 * (size_t)c->cfg.n_layers, hipMemcpyDeviceToHost));
+  return ACC_OK;
+}
+
+int32_t accordion_get_payload(acc_ctx* c, int32_t worker, int32_t layer, int32_t* idx_host,
+                              float* val_host, int64_t capacity, int64_t* count_out) {
+  if (!c) return ACC_EINVAL;
+  if (c->cfg.method != ACC_TOPK) return fail(c->err, ACC_EINVAL, "payloads exist for TopK only");
+  if (worker < 0 || worker >= c->cfg.n_workers) return fail(c->err, ACC_EINVAL, "worker out of range");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(c->err, ACC_EINVAL, "layer out of range");
+  if (!count_out) return fail(c->err, ACC_EINVAL, "count_out is NULL");
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  SelState s;
+  ACC_HIP(c, hipMemcpy(&s, c->ws.sel + (size_t)worker * c->cfg.n_layers + layer, sizeof(s), hipMemcpyDeviceToHost));
+  const LayerDev& L = c->plan.layers[layer];
+  const int64_t k = std::min<int64_t>(s.k, std::max(L.k[0], L.k[1]));
+  *count_out = k;
+  if (capacity < k) return fail(c->err, ACC_ENOSPACE, "payload buffers too small");
+  if (k == 0) return ACC_OK;
+  if (!idx_host || !val_host) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
+  const size_t o = (size_t)worker * c->plan.pay_stride + L.pay_off;
+  ACC_HIP(c, hipMemcpy(idx_host, c->ws.pay_idx + o, 4 * (size_t)k, hipMemcpyDeviceToHost));
+  ACC_HIP(c, hipMemcpy(val_host, c->ws.pay_val + o, 4 * (size_t)k, hipMemcpyDeviceToHost));
+  return ACC_OK;
+}
+
+int32_t accordion_get_factors(acc_ctx* c, int32_t layer, float* p_hat_host, float* q_host, int32_t* rank_out) {
+  if (!c) return ACC_EINVAL;
+  if (c->cfg.method != ACC_POWERSGD) return fail(c->err, ACC_EINVAL, "factors exist for PowerSGD only");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(c->err, ACC_EINVAL, "layer out of range");
+  const LayerDev& L = c->plan.layers[layer];
+  if (!L.is_matrix) return fail(c->err, ACC_EINVAL, "layer is not a matrix");
+  if (!p_hat_host || !q_host || !rank_out) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  int32_t r = 0;
+  ACC_HIP(c, hipMemcpy(&r, c->ws.rank_used + layer, 4, hipMemcpyDeviceToHost));
+  r = std::max(0, std::min(r, c->plan.rmax));
+  *rank_out = r;
+  const int rmax = c->plan.rmax;
+  std::vector<float> tp((size_t)L.rows * rmax), tq((size_t)L.cols * rmax);
+  ACC_HIP(c, hipMemcpy(tp.data(), c->ws.Phat + L.p_off, 4 * tp.size(), hipMemcpyDeviceToHost));
+  ACC_HIP(c, hipMemcpy(tq.data(), c->ws.Q + L.q_off, 4 * tq.size(), hipMemcpyDeviceToHost));
+  for (int i = 0; i < L.rows; ++i)
+    for (int k = 0; k < r; ++k) p_hat_host[(size_t)i * r + k] = tp[(size_t)i * rmax + k];
+  for (int j = 0; j < L.cols; ++j)
+    for (int k = 0; k < r; ++k) q_host[(size_t)j * r + k] = tq[(size_t)j * rmax + k];
+  return ACC_OK;
+}
+
+int32_t accordion_payload_words(acc_ctx* c, int64_t* last_step, int64_t* cumulative) {
+  if (!c) return ACC_EINVAL;
+  if (!last_step || !cumulative) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  unsigned long long w[3] = {0, 0, 0};
+  ACC_HIP(c, hipMemcpy(w, c->ws.words, sizeof(w), hipMemcpyDeviceToHost));
+  *last_step = (int64_t)w[1];
+  *cumulative = (int64_t)w[2];
+  return ACC_OK;
+}
+
+int32_t accordion_state_bytes(const acc_ctx* c, size_t* out_bytes) {
+  if (!c || !out_bytes) return ACC_EINVAL;
+  *out_bytes = state_bytes_of(c);
+  return ACC_OK;
+}
+
+static int32_t state_copy(acc_ctx* c, char* host, bool to_host) {
+  const Plan& p = c->plan;
+  const size_t N4 = 4 * (size_t)p.N, L4 = 4 * (size_t)c->cfg.n_layers;
+  auto cp = [&](void* dev, size_t bytes) -> hipError_t {
+    if (bytes == 0) return hipSuccess;
+    hipError_t e = to_host ? hipMemcpy(host, dev, bytes, hipMemcpyDeviceToHost)
+                           : hipMemcpy(dev, host, bytes, hipMemcpyHostToDevice);
+    host += bytes;
+    return e;
+  };
+  for (int w = 0; w < c->cfg.n_workers; ++w) ACC_HIP(c, cp(c->ws.e + (size_t)w * p.e_stride, N4));
+  ACC_HIP(c, cp(c->ws.A, N4));
+  if (c->cfg.method == ACC_POWERSGD) ACC_HIP(c, cp(c->ws.Q, 4 * (size_t)p.q_total));
+  ACC_HIP(c, cp(c->ws.norm_old, L4));
+  ACC_HIP(c, cp(c->ws.has_old, L4));
+  ACC_HIP(c, cp(c->ws.level, L4));
+  return ACC_OK;
+}
+
+int32_t accordion_get_state(acc_ctx* c, void* state_host, size_t bytes) {
+  if (!c) return ACC_EINVAL;
+  if (!state_host) return fail(c->err, ACC_EINVAL, "state_host is NULL");
+  if (c->in_step) return fail(c->err, ACC_ESTATE, "get_state inside a step");
+  if (bytes < state_bytes_of(c)) return fail(c->err, ACC_ENOSPACE, "state buffer too small");
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  return state_copy(c, static_cast<char*>(state_host), true);
+}
+
+int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
+  if (!c) return ACC_EINVAL;
+  if (!state_host) return fail(c->err, ACC_EINVAL, "state_host is NULL");
+  if (c->in_step) return fail(c->err, ACC_ESTATE, "set_state inside a step");
+  if (bytes < state_bytes_of(c)) return fail(c->err, ACC_ENOSPACE, "state buffer too small");
+  // levels must be 0 or 1: they index the per-layer rank / k tables in the kernels
+  const size_t L = (size_t)c->cfg.n_layers;
+  const int32_t* lv = reinterpret_cast<const int32_t*>(static_cast<const char*>(state_host) + state_bytes_of(c) - 4 * L);
+  for (size_t i = 0; i < L; ++i)
+    if (lv[i] != 0 && lv[i] != 1) return fail(c->err, ACC_EINVAL, "state holds a level other than 0 or 1");
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  const int32_t rc = state_copy(c, const_cast<char*>(static_cast<const char*>(state_host)), false);
+  if (rc != ACC_OK) return rc;
+  ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)c->cfg.method);
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  return ACC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,168 @@
+"""GPU parity: PowerSGD with error feedback against the oracle through the C ABI.
+
+Tolerance: 1e-5 relative (Frobenius norm, per layer) for P^, Q~, D and every residual, as the
+task's target states for fp32.  The comparison is teacher-forced: before every step the
+library is set to the oracle's state, because one subspace-iteration step amplifies rounding
+differences of nearly-degenerate directions and free-running trajectories drift apart."""
+import numpy as np
+import pytest
+
+from oracle import accordion_oracle as orc
+from paper_2010_16248_amd import binding as B
+from paper_2010_16248_amd import workloads as wl
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+def _forced_step(gpu, ora, grads, tag, tol=TOL):
+    gpu.set_state(H.oracle_state_blob(gpu, ora))
+    ranks = {li: ora.layer_rank(li) for li, l in enumerate(ora.layers) if l[3]}
+    out_ref = ora.step(grads)
+    dg = [H.to_dev(g) for g in grads]
+    out = H.dev_out(gpu.n_params)
+    gpu.step_all(dg, out)
+    got = out.cpu().numpy()
+    st = gpu.unpack_state(gpu.get_state())
+    worst = 0.0
+    qpos = 0
+    rmax = ora.r_max
+    for li, (off, rows, cols, is_m) in enumerate(ora.layers):
+        sl = slice(off, off + rows * cols)
+        if is_m:
+            p_hat, q_bar = gpu.get_factors(li)
+            assert p_hat.shape == (rows, ranks[li]), tag
+            errs = dict(P=H.rel_fro(p_hat, ora.P_hat[li]), Q=H.rel_fro(q_bar, ora.Q_bar[li]),
+                        D=H.rel_fro(got[sl], out_ref[sl]))
+            for w in range(gpu.n_workers):
+                errs[f"e{w}"] = H.rel_fro(st["e"][w, sl], ora.e[w, sl])
+            # the whole Q block (unused columns included) is the next warm start
+            qblk = st["Q"][qpos:qpos + cols * rmax].reshape(cols, rmax)
+            errs["Qstate"] = H.rel_fro(qblk, ora.Q[li])
+            qpos += cols * rmax
+            for k, v in errs.items():
+                assert v <= tol, f"{tag}: layer {li} ({rows}x{cols}) {k} rel err {v:.3e}"
+            worst = max(worst, max(errs.values()))
+        else:
+            assert H.rel_fro(got[sl], out_ref[sl]) <= 1e-6, f"{tag}: 1-D layer {li}"
+            assert np.all(st["e"][:, sl] == 0)
+    H.assert_bits_equal(st["A"], ora.A, f"{tag}: accumulator")
+    assert gpu.payload_words() == (ora.words_last, ora.words_cum)
+    return worst
+
+
+def test_tiny_config_both_ranks_with_switch():
+    """The smallest configuration: four matrices, W = 2, rank 2 inside / rank 1 outside
+    critical regimes, 20 steps in 2 windows of 10 with the eta = 0.5 test between them, then
+    10 more steps at the switched rank on the carried Q."""
+    print("case tiny_powersgd", flush=True)
+    w = wl.workload("tiny_powersgd")
+    q0 = wl.q_init(w, 2, w.seed)
+    for initial in (1, 0):
+        gpu, ora = H.make_pair(B.ACC_POWERSGD, w.layers, w.n_workers, 2, 1, 100, 0.5, initial, q0)
+        worst = 0.0
+        step = 0
+        for window in range(3):
+            for _ in range(10):
+                grads = [wl.gradient(w, k, step) for k in range(w.n_workers)]
+                worst = max(worst, _forced_step(gpu, ora, grads, f"init {initial} step {step}"))
+                step += 1
+            ref_lv = ora.detect_regime(0.1, 0.1)
+            gpu.detect_regime(0.1, 0.1)
+            assert np.array_equal(gpu.get_levels(), ref_lv)
+            old, cur = gpu.get_norms()
+            assert np.allclose(cur, ora.norm_curr, rtol=1e-6, atol=0)
+            assert np.allclose(old, ora.norm_prev, rtol=1e-6, atol=0)
+        # start critical: [crit (no history), non-crit, non-crit]; start non-critical: same decisions
+        assert ref_lv.tolist() == [0, 0, 0, 0]
+        print(f"initial_level {initial}: worst rel err {worst:.2e}", flush=True)
+        gpu.destroy()
+
+
+@pytest.mark.parametrize("crit,noncrit", [(4, 1), (3, 2), (2, 4)])
+def test_ragged_misaligned_layers_and_vectors(crit, noncrit):
+    """Matrices with rows/cols not multiples of 4 at misaligned offsets (4-byte access
+    path), rows below the rank (rank is capped), 1-D tensors in between."""
+    print(f"case ragged powersgd {crit}/{noncrit}", flush=True)
+    shapes = [(7, 13, 1), (1, 5, 0), (70, 300, 1), (3, 20, 1), (1, 77, 0), (130, 515, 1),
+              (2, 2, 1), (1, 1, 0), (64, 256, 1), (1, 9001, 0), (65, 257, 1)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    rmax = max(crit, noncrit)
+    q0 = wl.q_init(layers, rmax, 5)
+    gpu, ora = H.make_pair(B.ACC_POWERSGD, layers, 3, crit, noncrit, 100, 0.5, 1, q0)
+    rng = np.random.default_rng(2)
+    for step in range(4):
+        if step == 2:
+            ora.level[::2] = 0                       # mixed levels across layers
+        grads = [(rng.standard_normal(N) * 0.01).astype(np.float32) for _ in range(3)]
+        _forced_step(gpu, ora, grads, f"step {step}")
+    gpu.destroy()
+
+
+def test_tall_layer_uses_the_memory_resident_orthogonalisation():
+    print("case tall layer", flush=True)
+    layers = wl.make_layers([(1500, 40, 1), (1025, 8, 1)])
+    N = wl.total_params(layers)
+    q0 = wl.q_init(layers, 4, 6)
+    gpu, ora = H.make_pair(B.ACC_POWERSGD, layers, 2, 4, 2, 100, 0.5, 1, q0)
+    rng = np.random.default_rng(4)
+    for step in range(2):
+        grads = [rng.standard_normal(N).astype(np.float32) for _ in range(2)]
+        _forced_step(gpu, ora, grads, f"step {step}")
+    gpu.destroy()
+
+
+def test_zero_gradient_gives_zero_columns_not_nan():
+    layers = wl.make_layers([(16, 32, 1)])
+    q0 = wl.q_init(layers, 2, 7)
+    gpu, ora = H.make_pair(B.ACC_POWERSGD, layers, 1, 2, 1, 100, 0.5, 1, q0)
+    g = np.zeros(512, np.float32)
+    out_ref = ora.step([g])
+    out = H.dev_out(512)
+    gpu.step_all([H.to_dev(g)], out)
+    got = out.cpu().numpy()
+    assert np.all(got == 0) and np.all(out_ref == 0)
+    p_hat, q_bar = gpu.get_factors(0)
+    assert np.all(p_hat == 0) and np.all(q_bar == 0)
+    gpu.destroy()
+
+
+def test_call_by_call_equals_step_all_and_is_deterministic():
+    shapes = [(70, 300, 1), (1, 77, 0), (33, 64, 1)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 3
+    q0 = wl.q_init(layers, 2, 8)
+    rng = np.random.default_rng(9)
+    grads = [[rng.standard_normal(N).astype(np.float32) for _ in range(W)] for _ in range(2)]
+    results = []
+    for mode in ("all", "calls", "all"):
+        gpu, _ = H.make_pair(B.ACC_POWERSGD, layers, W, 2, 1, 100, 0.5, 1, q0)
+        outs = []
+        for step in range(2):
+            dg = [H.to_dev(g) for g in grads[step]]
+            out = H.dev_out(N)
+            if mode == "all":
+                gpu.step_all(dg, out)
+            else:
+                for w in (1, 2, 0):
+                    gpu.compress_step(w, dg[w], 0)
+                with pytest.raises(B.AccordionError):
+                    gpu.compress_step(0, None, 1)        # before aggregate(0)
+                gpu.aggregate(0)
+                with pytest.raises(B.AccordionError):
+                    gpu.decompress(out)                  # before phase 1
+                for w in (0, 2, 1):
+                    gpu.compress_step(w, None, 1)
+                gpu.aggregate(1)
+                gpu.decompress(out)
+            outs.append(out.cpu().numpy())
+        results.append((outs, gpu.get_state().copy()))
+        gpu.destroy()
+    for outs, st in results[1:]:
+        for a, b in zip(outs, results[0][0]):
+            H.assert_bits_equal(a, b, "decompressed mean")
+        assert np.array_equal(st, results[0][1])

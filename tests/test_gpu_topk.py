@@ -1,0 +1,145 @@
+"""GPU parity: TopK with error feedback against the oracle, bit for bit, through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import accordion_oracle as orc
+from paper_2010_16248_amd import binding as B
+from paper_2010_16248_amd import workloads as wl
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_step(gpu, ora, grads, tag):
+    out_ref = ora.step(grads)
+    dg = [H.to_dev(g) for g in grads]
+    out = H.dev_out(gpu.n_params)
+    gpu.step_all(dg, out)
+    H.assert_bits_equal(out.cpu().numpy(), out_ref, f"{tag}: mean")
+    for w in range(gpu.n_workers):
+        for li in range(gpu.n_layers):
+            idx, val = gpu.get_payload(w, li)
+            ri, rv = ora.payload[(w, li)]
+            assert np.array_equal(idx, ri), f"{tag}: indices worker {w} layer {li}"
+            H.assert_bits_equal(val, rv, f"{tag}: values worker {w} layer {li}")
+    st = gpu.unpack_state(gpu.get_state())
+    H.assert_bits_equal(st["e"], ora.e, f"{tag}: residual")
+    H.assert_bits_equal(st["A"], ora.A, f"{tag}: accumulator")
+    assert gpu.payload_words() == (ora.words_last, ora.words_cum)
+
+
+def _case_values(rng, case, n):
+    if case == "normal":
+        return rng.standard_normal(n)
+    if case == "quantised":
+        return rng.integers(-3, 4, n) * 0.25
+    if case == "all_equal":
+        return np.full(n, -1.5)
+    if case == "all_zero":
+        return np.zeros(n)
+    if case == "sparse":
+        return rng.standard_normal(n) * (rng.random(n) < 0.05)
+    raise KeyError(case)
+
+
+@pytest.mark.parametrize("crit,noncrit,den", [(10, 1, 100), (1, 1, 1), (1, 3, 1000), (99, 25, 100)])
+def test_ragged_misaligned_layers(crit, noncrit, den):
+    """Many small layers at 16-byte-misaligned offsets, W = 3, several steps so that the
+    memory feeds back; K from 0.1 % to 100 %."""
+    print(f"case ragged crit={crit} noncrit={noncrit} den={den}", flush=True)
+    layers = wl.random_layers(seed=11, n_layers=23, max_rows=40, max_cols=300)
+    N = wl.total_params(layers)
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, 3, crit, noncrit, den)
+    rng = np.random.default_rng(1)
+    for step in range(3):
+        grads = [rng.standard_normal(N).astype(np.float32) for _ in range(3)]
+        _check_step(gpu, ora, grads, f"step {step}")
+    # switch every layer to the other level by hand and go on
+    blob = H.oracle_state_blob(gpu, ora)
+    ora.level[:] = 0
+    st = gpu.unpack_state(blob)
+    st["level"][:] = 0
+    gpu.set_state(blob)
+    for step in range(2):
+        grads = [rng.standard_normal(N).astype(np.float32) for _ in range(3)]
+        _check_step(gpu, ora, grads, f"noncrit step {step}")
+    gpu.destroy()
+
+
+@pytest.mark.parametrize("case", ["normal", "quantised", "all_equal", "all_zero", "sparse"])
+def test_multi_tile_layers_with_ties(case):
+    """Layers that span several 8192-element tiles with ragged tails; value sets with heavy
+    ties (the lower index must win) including a tie class far larger than the candidate
+    list, which takes the re-read path."""
+    print(f"case multi-tile {case}", flush=True)
+    shapes = [(1, 3 * 8192 + 77, 0), (37, 1001, 1), (1, 5, 0), (3, 8192, 1), (1, 70001, 0)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, 2, 10, 1)
+    rng = np.random.default_rng([7, len(case)])
+    for step in range(2):
+        grads = [_case_values(rng, case, N).astype(np.float32) for _ in range(2)]
+        _check_step(gpu, ora, grads, f"{case} step {step}")
+    gpu.destroy()
+
+
+def test_call_by_call_equals_step_all_and_is_deterministic():
+    layers = wl.make_layers([(20, 900, 1), (1, 64, 0), (9, 9, 1)])
+    N = wl.total_params(layers)
+    W = 3
+    rng = np.random.default_rng(3)
+    grads = [[rng.standard_normal(N).astype(np.float32) for _ in range(W)] for _ in range(2)]
+    results = []
+    for mode in ("all", "calls", "all"):
+        gpu, _ = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+        outs = []
+        for step in range(2):
+            dg = [H.to_dev(g) for g in grads[step]]
+            out = H.dev_out(N)
+            if mode == "all":
+                gpu.step_all(dg, out)
+            else:
+                for w in (2, 0, 1):                      # any worker order
+                    gpu.compress_step(w, dg[w], 0)
+                gpu.aggregate(0)
+                gpu.decompress(out)
+            outs.append(out.cpu().numpy())
+        results.append((outs, gpu.get_state().copy()))
+        gpu.destroy()
+    for outs, st in results[1:]:
+        for a, b in zip(outs, results[0][0]):
+            H.assert_bits_equal(a, b, "mean")
+        assert np.array_equal(st, results[0][1])
+
+
+def test_state_machine_errors_come_from_the_host():
+    layers = wl.make_layers([(4, 10, 1)])
+    gpu, _ = H.make_pair(B.ACC_TOPK, layers, 2, 50, 10)
+    g = H.to_dev(np.ones(40, np.float32))
+    out = H.dev_out(40)
+    with pytest.raises(B.AccordionError) as ei:
+        gpu.aggregate(0)
+    assert ei.value.status == B.ACC_ESTATE
+    with pytest.raises(B.AccordionError):
+        gpu.decompress(out)
+    gpu.compress_step(0, g, 0)
+    with pytest.raises(B.AccordionError) as ei:
+        gpu.compress_step(0, g, 0)                       # same worker twice
+    assert ei.value.status == B.ACC_ESTATE
+    with pytest.raises(B.AccordionError) as ei:
+        gpu.compress_step(2, g, 0)                       # worker out of range
+    assert ei.value.status == B.ACC_EINVAL
+    with pytest.raises(B.AccordionError) as ei:
+        gpu.compress_step(1, g, 1)                       # TopK has no phase 1
+    assert ei.value.status == B.ACC_EINVAL
+    with pytest.raises(B.AccordionError) as ei:
+        gpu.detect_regime(0.1, 0.1)                      # inside a step
+    assert ei.value.status == B.ACC_ESTATE
+    with pytest.raises(B.AccordionError):
+        gpu.aggregate(0)                                 # worker 1 missing
+    gpu.compress_step(1, g, 0)
+    gpu.aggregate(0)
+    gpu.decompress(out)
+    assert np.all(out.cpu().numpy()[:20] == 1.0)         # k = 20 of 40 equal entries: first 20
+    assert np.all(out.cpu().numpy()[20:] == 0.0)
+    gpu.destroy()
