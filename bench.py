@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the Accordion gradient-compression hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic gradients for all W
+simulated workers: error-feedback add, gradient accumulation, compression at the layer's current
+level (TopK select + payload + residual, or the PowerSGD products, orthogonalisation and
+residual), the mean over workers, and -- every `window` steps -- the per-layer norms and the
+critical-regime decision that picks the next window's levels.  Gradients are resident in HBM
+before the timed region starts (a pool of distinct seeded batches, rotated).
+
+Prints ONE JSON line: gradient GB/s = 4 * N * W / t_step, plus the roofline of the dominant
+kernel (algorithmic bytes / its HIP-event duration against 8 TB/s) and the CPU oracle's rate on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this file (summaries under profiles/); None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+# scale of the gradients per window, cycled: makes the norm ratio cross eta = 0.5 so that both
+# levels are used while timing (decisions: critical, not, critical, not, ...)
+WINDOW_SCALES = [1.0, 0.3, 0.3, 1.0]
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet18_topk",
+                    choices=["tiny_powersgd", "resnet18_topk", "resnet18_powersgd", "vgg19_powersgd", "lstm_topk"])
+    ap.add_argument("--workers", type=int, default=0, help="override W of the workload")
+    ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept in HBM")
+    ap.add_argument("--window", type=int, default=20, help="steps per detection window")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket kernels with HIP events in the timed region")
+    ap.add_argument("--fixed-level", type=int, default=-1, help="0/1: never switch, use this level")
+    return ap.parse_args()
+
+
+def dominant_kernel(method):
+    from paper_2010_16248_amd import binding as B
+    return "topk_ef_hist_kernel" if method == B.ACC_TOPK else "psgd_ef_p_kernel"
+
+
+def algorithmic_bytes_dominant(n_params, W):
+    """Fused error-feedback pass: per worker read g and e, write Delta (12 B / element); worker 0
+    also reads and writes the accumulator (8 B / element)."""
+    return n_params * (12 * W + 8)
+
+
+def algorithmic_bytes_step(w, layers, W, levels_k_or_r):
+    """Bytes the method itself must move per step (one read/write of each operand per pass)."""
+    from paper_2010_16248_amd import binding as B
+    N = sum(l.numel for l in layers)
+    if w.method == B.ACC_TOPK:
+        kept = sum(levels_k_or_r)
+        return 12 * N * W + 8 * N + 2 * 8 * kept * W + 4 * N
+    mat = sum(l.numel for l in layers if l.is_matrix)
+    vec = N - mat
+    return 24 * mat * W + 8 * N + 4 * N + 4 * vec * W
+
+
+def cpu_baseline(w, W, n_steps, window):
+    """The oracle as it stands, single BLAS thread, on the same seeded inputs."""
+    from oracle import accordion_oracle as orc
+    from paper_2010_16248_amd import workloads as wl
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:  # pragma: no cover
+        threadpool_limits = None
+    layers = [(l.offset, l.rows, l.cols, l.is_matrix) for l in w.layers]
+    rmax = max(w.level_crit, w.level_noncrit)
+    q0 = wl.q_init(w, rmax, w.seed) if w.method == 0 else None
+    ora = orc.AccordionOracle(w.method, layers, W, w.level_crit, w.level_noncrit, w.k_den, w.eta, 1, q0)
+    grads = [[wl.gradient(w, k, s) for k in range(W)] for s in range(n_steps)]
+    ctx = threadpool_limits(limits=1) if threadpool_limits else None
+    t0 = time.perf_counter()
+    for s in range(n_steps):
+        ora.step(grads[s])
+    ora.detect_regime(0.1, 0.1)          # one window end, amortised as in the GPU run
+    t1 = time.perf_counter()
+    if ctx is not None:
+        ctx.restore_original_limits()
+    # detect_regime cost is counted once per `window` steps
+    per_step = (t1 - t0) / n_steps
+    gbs = 4.0 * w.n_params * W / per_step / 1e9
+    return {"value": round(gbs, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{n_steps} full steps of {w.name} (all {W} workers, every layer) + 1 regime test, "
+                      f"numpy oracle, 1 thread, {per_step:.3f} s/step",
+            "host_cpus": os.cpu_count()}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
+              "the path shards by worker, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2010_16248_amd import binding as B
+    from paper_2010_16248_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.load_library()                       # fails loudly if the HIP library is missing
+    w = wl.workload(args.workload)
+    W = args.workers if args.workers > 0 else w.n_workers
+    layers = w.layers
+    N = w.n_params
+    rmax = max(w.level_crit, w.level_noncrit)
+    q0 = wl.q_init(w, rmax, w.seed) if w.method == B.ACC_POWERSGD else None
+    gpu = B.Accordion(w.method, layers, W, w.level_crit, w.level_noncrit, w.k_den, w.eta, 1, q0)
+
+    # gradient pool, resident in HBM: [scale][batch][worker]
+    dev = torch.device("cuda:0")
+    base = [[torch.from_numpy(wl.gradient(w, k, s)).to(dev) for k in range(W)] for s in range(args.pool)]
+    pools = {}
+    for sc in sorted(set(WINDOW_SCALES)):
+        pools[sc] = base if sc == 1.0 else [[g * sc for g in batch] for batch in base]
+    out = torch.empty(N, dtype=torch.float32, device=dev)
+    if args.fixed_level in (0, 1):
+        st = gpu.unpack_state(gpu.get_state())
+        blob = gpu.pack_state(st["e"], st["A"], st["Q"], st["norm_old"], st["has_old"],
+                              np.full(gpu.n_layers, args.fixed_level, np.int32))
+        gpu.set_state(blob)
+
+    state = {"step": 0}
+
+    def one_step():
+        s = state["step"]
+        window = s // args.window
+        sc = WINDOW_SCALES[window % len(WINDOW_SCALES)] if args.fixed_level < 0 else 1.0
+        gpu.step_all(pools[sc][s % args.pool], out)
+        if args.fixed_level < 0 and (s + 1) % args.window == 0:
+            gpu.detect_regime(0.1, 0.1)
+        state["step"] = s + 1
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    state["step"] = 0                      # timed region starts at a window boundary
+    use_events = not args.no_kernel_events
+    if use_events:
+        gpu.set_profiling(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = gpu.get_profile() if use_events else {}
+    if use_events:
+        gpu.set_profiling(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = 4.0 * N * W / (ms_per_step * 1e-3) / 1e9
+
+    levels = gpu.get_levels()
+    words_last, words_cum = gpu.payload_words()
+
+    dom = dominant_kernel(w.method)
+    roofline = None
+    kernels = {}
+    if prof:
+        tot = sum(ms for ms, _ in prof.values())
+        for name, (ms, n) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+            kernels[name] = {"avg_us": round(ms * 1e3 / n, 2), "launches": n, "share": round(ms / tot, 3)}
+        ms, n = prof[dom]
+        avg_s = ms * 1e-3 / n
+        ach = algorithmic_bytes_dominant(N, W) / avg_s / 1e9
+        traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, W))
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
+                    "avg_kernel_us": round(avg_s * 1e6, 2),
+                    "algorithmic_bytes_per_launch": algorithmic_bytes_dominant(N, W)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        n_cpu = 2 if N > 5_000_000 else 20
+        cpu = cpu_baseline(w, W, n_cpu, args.window)
+
+    line = {
+        "metric": "gradient GB/s per compress step (EF+compress+norm)",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "n_params": N, "n_workers": W, "n_layers": len(layers),
+                   "method": "topk" if w.method == B.ACC_TOPK else "powersgd",
+                   "level_crit": w.level_crit, "level_noncrit": w.level_noncrit,
+                   "window_steps": args.window, "pool_batches": args.pool,
+                   "levels_switch": args.fixed_level < 0, "kernel_events_in_timed_region": use_events},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+        "payload_words_last_step": words_last,
+        "critical_layers_at_end": int(levels.sum()),
+    }
+    gpu.destroy()
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

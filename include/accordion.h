@@ -174,6 +174,17 @@ int32_t accordion_state_bytes(const acc_ctx* ctx, size_t* out_bytes);
 int32_t accordion_get_state(acc_ctx* ctx, void* state_host, size_t bytes);
 int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
 
+/* --- per-kernel timing (tracing aid; not part of the paper's method) -------------------------
+ * With profiling on, every kernel launch is bracketed by two HIP events on the context's stream
+ * and the elapsed time is accumulated per stage.  accordion_get_profile synchronises the stream
+ * and returns the accumulated milliseconds and the number of launches of one stage since
+ * profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
+ * accordion_stage_name gives the kernel's name (NULL if out of range). */
+#define ACC_N_STAGES 15
+int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
+int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
+const char* accordion_stage_name(int32_t stage);
+
 #ifdef __cplusplus
 }
 #endif

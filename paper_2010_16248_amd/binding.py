@@ -51,7 +51,9 @@ EXPORTS = [
     "accordion_detect_regime", "accordion_reset_accumulator", "accordion_get_levels",
     "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
     "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
+    "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
 ]
+ACC_N_STAGES = 15
 
 
 def load_library() -> C.CDLL:
@@ -82,6 +84,8 @@ def load_library() -> C.CDLL:
         "accordion_state_bytes": [vp, C.POINTER(C.c_size_t)],
         "accordion_get_state": [vp, vp, C.c_size_t],
         "accordion_set_state": [vp, vp, C.c_size_t],
+        "accordion_set_profiling": [vp, i32],
+        "accordion_get_profile": [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -89,6 +93,8 @@ def load_library() -> C.CDLL:
         fn.restype = i32
     lib.accordion_last_error.argtypes = [vp]
     lib.accordion_last_error.restype = C.c_char_p
+    lib.accordion_stage_name.argtypes = [i32]
+    lib.accordion_stage_name.restype = C.c_char_p
     _lib = lib
     return lib
 
@@ -246,6 +252,19 @@ class Accordion:
         buf = np.ascontiguousarray(buf, dtype=np.uint8)
         _check(self._lib, self.ctx, self._lib.accordion_set_state(
             self.ctx, buf.ctypes.data_as(C.c_void_p), buf.nbytes))
+
+    def set_profiling(self, enable: bool) -> None:
+        _check(self._lib, self.ctx, self._lib.accordion_set_profiling(self.ctx, 1 if enable else 0))
+
+    def get_profile(self) -> dict:
+        """{kernel name: (total milliseconds, launches)} since profiling was switched on."""
+        out = {}
+        for s in range(ACC_N_STAGES):
+            ms, n = C.c_double(0.0), C.c_int64(0)
+            _check(self._lib, self.ctx, self._lib.accordion_get_profile(self.ctx, s, C.byref(ms), C.byref(n)))
+            if n.value:
+                out[self._lib.accordion_stage_name(s).decode()] = (float(ms.value), int(n.value))
+        return out
 
     # -- state blob helpers (layout documented in include/accordion.h) ---------------------
     def q_total(self) -> int:

@@ -214,7 +214,28 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
 
 }  // namespace
 
+enum Stage {
+  ST_psgd_ef_p_kernel = 0, ST_psgd_orth_kernel, ST_psgd_q_kernel, ST_psgd_qmean_kernel,
+  ST_psgd_decomp_kernel, ST_topk_ef_hist_kernel, ST_topk_pick1_kernel, ST_topk_cand_kernel,
+  ST_topk_resolve_kernel, ST_topk_compact_kernel, ST_topk_sparse_mean_kernel,
+  ST_norm_partial_kernel, ST_regime_decide_kernel, ST_recount_words_kernel, ST_zero_accum_kernel,
+  ST_COUNT
+};
+static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
+static const char* const kStageNames[ST_COUNT] = {
+  "psgd_ef_p_kernel", "psgd_orth_kernel", "psgd_q_kernel", "psgd_qmean_kernel",
+  "psgd_decomp_kernel", "topk_ef_hist_kernel", "topk_pick1_kernel", "topk_cand_kernel",
+  "topk_resolve_kernel", "topk_compact_kernel", "topk_sparse_mean_kernel",
+  "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel"};
+
+struct EventPair { hipEvent_t a, b; int stage; };
+
 struct acc_ctx {
+  // per-kernel timing
+  bool profiling = false;
+  std::vector<EventPair> pending, spare;
+  double stage_ms[ST_COUNT] = {0};
+  long long stage_n[ST_COUNT] = {0};
   acc_config cfg;
   std::vector<acc_layer> layers;
   Plan plan;
@@ -256,9 +277,48 @@ int check_launch(acc_ctx* c, const char* what) {
   return ACC_OK;
 }
 
+// Fold the finished event pairs into the per-stage totals (synchronises the stream).
+int drain_profile(acc_ctx* c) {
+  if (c->pending.empty()) return ACC_OK;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c->err, ACC_EHIP, "hipStreamSynchronize failed");
+  for (EventPair& p : c->pending) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+      c->stage_ms[p.stage] += ms;
+      c->stage_n[p.stage] += 1;
+    }
+    c->spare.push_back(p);
+  }
+  c->pending.clear();
+  return ACC_OK;
+}
+
+bool prof_begin(acc_ctx* c, int stage, EventPair& p) {
+  if (!c->profiling) return false;
+  if (c->pending.size() >= 8192) drain_profile(c);
+  if (!c->spare.empty()) {
+    p = c->spare.back();
+    c->spare.pop_back();
+  } else {
+    if (hipEventCreate(&p.a) != hipSuccess) return false;
+    if (hipEventCreate(&p.b) != hipSuccess) { (void)hipEventDestroy(p.a); return false; }
+  }
+  p.stage = stage;
+  (void)hipEventRecord(p.a, c->stream);
+  return true;
+}
+
+void prof_end(acc_ctx* c, EventPair& p) {
+  (void)hipEventRecord(p.b, c->stream);
+  c->pending.push_back(p);
+}
+
 #define ACC_LAUNCH(ctx, name, grid, block, ...)                              \
   do {                                                                       \
+    EventPair ep_;                                                           \
+    const bool prof_ = prof_begin(ctx, ST_##name, ep_);                      \
     hipLaunchKernelGGL(name, grid, block, 0, (ctx)->stream, __VA_ARGS__);    \
+    if (prof_) prof_end(ctx, ep_);                                           \
     int rc_ = check_launch(ctx, #name);                                      \
     if (rc_ != ACC_OK) return rc_;                                           \
   } while (0)
@@ -446,6 +506,11 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
 
 int32_t accordion_destroy(acc_ctx* ctx) {
   if (!ctx) return ACC_EINVAL;
+  (void)drain_profile(ctx);
+  for (EventPair& p : ctx->spare) {
+    (void)hipEventDestroy(p.a);
+    (void)hipEventDestroy(p.b);
+  }
   delete ctx;
   return ACC_OK;
 }
@@ -677,6 +742,32 @@ int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
   ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)c->cfg.method);
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   return ACC_OK;
+}
+
+int32_t accordion_set_profiling(acc_ctx* c, int32_t enable) {
+  if (!c) return ACC_EINVAL;
+  const int rc = drain_profile(c);
+  if (rc != ACC_OK) return rc;
+  if (enable && !c->profiling) {
+    for (int i = 0; i < ST_COUNT; ++i) { c->stage_ms[i] = 0.0; c->stage_n[i] = 0; }
+  }
+  c->profiling = enable != 0;
+  return ACC_OK;
+}
+
+int32_t accordion_get_profile(acc_ctx* c, int32_t stage, double* total_ms, int64_t* launches) {
+  if (!c) return ACC_EINVAL;
+  if (stage < 0 || stage >= ST_COUNT) return fail(c->err, ACC_EINVAL, "stage out of range");
+  if (!total_ms || !launches) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
+  const int rc = drain_profile(c);
+  if (rc != ACC_OK) return rc;
+  *total_ms = c->stage_ms[stage];
+  *launches = c->stage_n[stage];
+  return ACC_OK;
+}
+
+const char* accordion_stage_name(int32_t stage) {
+  return (stage >= 0 && stage < ST_COUNT) ? kStageNames[stage] : nullptr;
 }
 
 }  // extern "C"
