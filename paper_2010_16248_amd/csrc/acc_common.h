@@ -13,6 +13,7 @@ constexpr int kQuadIters = (kTile / 4 + 1 + kFlatThreads - 1) / kFlatThreads;  /
 constexpr int kMatRows = 64;             // matrix tile: 64 rows x 256 columns
 constexpr int kMatCols = 256;
 constexpr int kHistBins = 2048;          // 11 key bits per radix level
+constexpr int kSegCap = 1024;           // candidate slots per flat tile (TopK)
 constexpr int kMaxW = 32;
 constexpr int kMaxRank = 4;
 
@@ -35,8 +36,6 @@ struct LayerDev {
   int64_t ppart_off;     // into one worker's P partials (n_colchunks * rows * rmax)
   int64_t qpart_off;     // into one worker's Q partials (n_rowblocks * cols * rmax)
   int64_t pay_off;       // into one worker's payload arrays (entries)
-  int64_t cand_off;      // into one worker's candidate list (entries)
-  int64_t cand_cap;      // capacity of that list for this layer
   int64_t vec_off;       // into the 1-D mean buffer (PowerSGD, 1-D layers)
 };
 
@@ -49,13 +48,15 @@ struct SelState {
   uint32_t b1;        // level-1 bin (key bits 30..20) that holds the k-th largest key
   uint32_t above1;    // entries in bins above b1 (all selected)
   uint32_t c1;        // entries in bin b1 (candidates)
-  uint32_t mode;      // 0: candidates are in the list; 1: candidates are re-read from Delta
-  uint32_t cand_cnt;  // fill counter of the candidate list
+  uint32_t mode;      // 0: candidates are in the tiles' segments; 1: a segment overflowed,
+                      //    candidates are re-read from Delta
+  uint32_t b2;        // level-2 bin (key bits 19..9) within b1
+  uint32_t above2;    // candidates in level-2 bins above b2
   uint32_t T;         // exact threshold key (the k-th largest)
   uint32_t ktie;      // how many entries with key == T are selected (lowest indices first)
   uint32_t alleq;     // 1: every entry with key == T is selected
   uint32_t k;         // kept count used by this step
-  uint32_t pad[3];
+  uint32_t pad[2];
 };
 
 struct GradPtrs { const float* p[kMaxW]; };
@@ -86,9 +87,13 @@ struct Ws {
   float* Qpart;  int64_t qpart_stride;
   float* vecmean;
   // TopK
-  uint32_t* hist1;             // W x L x kHistBins
+  uint32_t* hist1;             // W x L x kHistBins, zero between steps
+  uint32_t* hist2;             // W x L x kHistBins, zero between steps
+  uint32_t* hist3;             // W x L x 512, zero between steps
+  uint32_t* done;              // 4 x W x L arrival counters, zero between kernels
   SelState* sel;               // W x L
-  uint2* cand;   int64_t cand_stride;
+  uint2* cand;                 // W x n_ftiles x kSegCap candidate slots (key, layer-local index)
+  uint32_t* cand_n;            // W x n_ftiles candidates found per tile
   uint32_t* gt_cnt;            // W x tile_stride
   uint32_t* eq_cnt;
   uint32_t* sel_off;

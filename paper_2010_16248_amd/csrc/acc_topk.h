@@ -1,20 +1,27 @@
 // TopK kernels: exact per-layer selection of the k entries with the largest |Delta|
-// (ties: lower flat index) by a three-level radix select on the 31 magnitude bits.
+// (ties: lower flat index) by a three-level radix select on the 31 magnitude bits
+// (11 + 11 + 9).  Every kernel is tile-parallel (one workgroup per 8192-element tile and
+// worker).  The per-(worker, layer) decisions (which bin holds the k-th largest) are
+// recomputed by every workgroup of the layer from the layer's global histogram at the start
+// of the next kernel: that costs an 8 KB L2 read per workgroup and needs neither an extra
+// launch nor a device-scope fence (which on this multi-die part writes back the whole L2).
 //
-//   pass A  topk_ef_hist     Delta = g + e (in place), A += g (worker 0), level-1 histogram
-//                            of key bits 30..20 per (worker, layer)
-//   S1      topk_pick1       bin b1 that holds the k-th largest key
-//   pass B  topk_cand        per tile: count of entries above b1; entries in b1 appended to
-//                            a candidate list (key, index) when the bin is small enough
-//   R       topk_resolve     one workgroup per (worker, layer): levels 2 and 3 over the
-//                            candidates give the exact threshold key T and the number of
-//                            ties to take; per-tile counts and their exclusive scans
-//   pass E  topk_compact     ordered compaction of the selected entries into the payload
-//                            (index ascending) and zeroing of those entries in e
-//   K6      topk_sparse_mean dense mean of the W payloads
+//   A  topk_ef_hist      Delta = g + e (in place), A += g (worker 0), level-1 histogram
+//                        (key bits 30..20) per (worker, layer)
+//   B  topk_cand         [bin b1 of the k-th largest]  count of entries above b1 per tile;
+//                        entries in b1 (candidates) go to the tile's segment as (key, index);
+//                        level-2 histogram of the candidates (bits 19..9)
+//   C  topk_level3       [bin b2]  candidates above b2 counted per tile; level-3 histogram
+//                        (bits 8..0) of those in b2
+//   D  topk_count        [threshold key T, tie quota]  per tile: candidates above T and
+//                        candidates equal to T
+//   E  topk_compact      [sums over the preceding tiles]  ordered compaction of the selected
+//                        entries into the payload (index ascending), zeroing them in e
+//   K6 topk_sparse_mean  dense mean of the W payloads
 //
-// All cross-workgroup combination is by integer atomics or by fixed-order scans, so every
-// output is bit-reproducible.
+// Cross-workgroup combination is by integer atomics and fixed-order sums only, so every
+// output is bit-reproducible.  A segment holds kSegCap candidates; if a tile has more (huge
+// tie classes: zeros, constants) the layer falls back to re-reading Delta in C and D.
 #pragma once
 #include "acc_common.h"
 
@@ -24,7 +31,74 @@ __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// ---- pass A ---------------------------------------------------------------------------------
+// LDS histogram add with a fast path for a wave whose valid lanes all hit one bin.
+__device__ __forceinline__ void hist_add(uint32_t* hist, bool valid, uint32_t bin, int lane) {
+  const uint32_t b = valid ? bin : 0xffffffffu;
+  const uint32_t fb = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
+  const uint64_t act = __ballot(valid);
+  const uint64_t same = __ballot(valid && b == fb);
+  if (act != 0 && same == act) {
+    if (lane == (int)__builtin_ctzll(act)) atomicAdd(&hist[fb], (uint32_t)__popcll(act));
+  } else if (valid) {
+    atomicAdd(&hist[bin], 1u);
+  }
+}
+
+__device__ __forceinline__ void hist_flush(const uint32_t* hist, uint32_t* gh, int nbins) {
+  for (int b = threadIdx.x; b < nbins; b += kFlatThreads) {
+    const uint32_t h = hist[b];
+    if (h) atomicAdd(&gh[b], h);
+  }
+}
+
+// Copies a layer's global histogram into LDS, zero-padded to kHistBins.  Ends with a barrier.
+__device__ __forceinline__ void hist_load(uint32_t* hist, const uint32_t* gh, int nbins) {
+  for (int b = threadIdx.x; b < kHistBins; b += kFlatThreads) hist[b] = (b < nbins) ? gh[b] : 0u;
+  __syncthreads();
+}
+
+__device__ __forceinline__ void hist_clear_global(uint32_t* gh, int nbins) {
+  for (int b = threadIdx.x; b < nbins; b += kFlatThreads) gh[b] = 0u;
+}
+
+// hist: kHistBins counts in LDS.  Finds the largest bin b with count(bins >= b) >= k.
+// Result in out[0..2] (LDS, zeroed by the caller before a barrier): bin, entries above the
+// bin, entries in the bin.  256 threads; two barriers; every thread calls it.
+__device__ __forceinline__ void pick_bin(const uint32_t* hist, uint32_t k, uint32_t* out,
+                                         uint32_t* scratch) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  uint32_t h[8];
+  uint32_t part = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { h[i] = hist[tid * 8 + i]; part += h[i]; }
+  const uint32_t suf = wave_incl_suffix_u32(part, lane);
+  if (lane == 0) scratch[wave] = suf;            // wave total
+  __syncthreads();
+  uint32_t run = suf - part;                     // entries in bins of later threads of my wave
+  for (int v = wave + 1; v < 4; ++v) run += scratch[v];
+#pragma unroll
+  for (int i = 7; i >= 0; --i) {
+    if (run < k && run + h[i] >= k) {
+      out[0] = (uint32_t)(tid * 8 + i);
+      out[1] = run;
+      out[2] = h[i];
+    }
+    run += h[i];
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* red) {
+  v = wave_sum_u32(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+// ---- A ----------------------------------------------------------------------------------------
 
 __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const GradPtrs gp, int w0) {
   __shared__ uint32_t hist[kHistBins];
@@ -59,294 +133,197 @@ __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const Gr
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const bool valid = qa && (base + c >= tg.lo) && (base + c < tg.hi);
-      const uint32_t bin = valid ? (key_of(comp(d, c)) >> 20) : 0xffffffffu;
-      // a wave whose valid lanes all fall in one bin (zeros, constants) adds once
-      const uint32_t fb = (uint32_t)__builtin_amdgcn_readfirstlane((int)bin);
-      const uint64_t act = __ballot(valid);
-      const uint64_t same = __ballot(valid && bin == fb);
-      if (act != 0 && same == act) {
-        if (lane == 0) atomicAdd(&hist[fb], (uint32_t)__popcll(act));
-      } else if (valid) {
-        atomicAdd(&hist[bin], 1u);
-      }
+      hist_add(hist, valid, key_of(comp(d, c)) >> 20, lane);
     }
   }
   __syncthreads();
-  uint32_t* gh = ws.hist1 + ((int64_t)w * ws.L + ft.layer) * kHistBins;
-  for (int b = tid; b < kHistBins; b += kFlatThreads) {
-    const uint32_t h = hist[b];
-    if (h) atomicAdd(&gh[b], h);
-  }
+  const int64_t wl = (int64_t)w * ws.L + ft.layer;
+  uint32_t* gh = ws.hist1 + wl * kHistBins;
+  hist_flush(hist, gh, kHistBins);
+  if (ft.start == 0 && tid == 0) ws.sel[wl].mode = 0;    // B raises it on segment overflow
 }
 
-// ---- picking the bin that holds the k-th largest --------------------------------------------
-// hist: kHistBins counts in LDS.  Finds the largest bin b with count(bins >= b) >= k.
-// Result in out[0..2] (LDS): bin, entries above the bin, entries in the bin.  Needs >= 256
-// threads; scratch: 4 words.  Contains two barriers; every thread of the workgroup calls it.
-__device__ __forceinline__ void pick_bin(const uint32_t* hist, uint32_t k, uint32_t* out,
-                                         uint32_t* scratch) {
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  uint32_t h[8];
-  uint32_t part = 0;
-  if (tid < 256) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) { h[i] = hist[tid * 8 + i]; part += h[i]; }
-  }
-  uint32_t suf = 0;
-  if (tid < 256) {
-    suf = wave_incl_suffix_u32(part, lane);      // lanes of waves 0..3 are all active here
-    if (lane == 0) scratch[wave] = suf;          // wave total
-  }
-  __syncthreads();
-  if (tid < 256) {
-    uint32_t above = suf - part;                 // threads after me in my wave
-    for (int v = wave + 1; v < 4; ++v) above += scratch[v];
-    uint32_t run = above;
-#pragma unroll
-    for (int i = 7; i >= 0; --i) {
-      if (run < k && run + h[i] >= k) {
-        out[0] = (uint32_t)(tid * 8 + i);
-        out[1] = run;
-        out[2] = h[i];
-      }
-      run += h[i];
-    }
-  }
-  __syncthreads();
-}
-
-__global__ __launch_bounds__(256) void topk_pick1_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3];
-  __shared__ uint32_t scratch[4];
-  const int w = w0 + blockIdx.y;
-  const int li = blockIdx.x;
-  const int tid = threadIdx.x;
-  const LayerDev& L = ws.layers[li];
-  uint32_t* gh = ws.hist1 + ((int64_t)w * ws.L + li) * kHistBins;
-  for (int b = tid; b < kHistBins; b += kFlatThreads) {
-    hist[b] = gh[b];
-    gh[b] = 0;                                   // ready for the next step
-  }
-  if (tid < 3) out[tid] = 0;
-  __syncthreads();
-  const uint32_t k = (uint32_t)L.k[ws.level[li]];
-  pick_bin(hist, k, out, scratch);
-  if (tid == 0) {
-    SelState s;
-    s.b1 = out[0];
-    s.above1 = out[1];
-    s.c1 = out[2];
-    s.mode = ((int64_t)out[2] <= L.cand_cap) ? 0u : 1u;
-    s.cand_cnt = 0;
-    s.T = 0; s.ktie = 0; s.alleq = 0;
-    s.k = k;
-    s.pad[0] = s.pad[1] = s.pad[2] = 0;
-    ws.sel[(int64_t)w * ws.L + li] = s;
-  }
-}
-
-// ---- pass B ---------------------------------------------------------------------------------
-
-__global__ __launch_bounds__(256) void topk_cand_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t wsum[2][4];
-  __shared__ uint32_t list_base;
-  const int w = w0 + blockIdx.y;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const FlatTile ft = ws.ftiles[blockIdx.x];
-  const LayerDev& L = ws.layers[ft.layer];
-  const TileGeom tg = tile_geom(L, ft);
-  SelState* sp = ws.sel + (int64_t)w * ws.L + ft.layer;
-  const uint32_t b1 = sp->b1;
-  const uint32_t mode = sp->mode;
-  const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-
-  float4 d[kQuadIters];
-  uint32_t ngt = 0, ncand = 0;
-#pragma unroll
-  for (int j = 0; j < kQuadIters; ++j) {
-    const int q = j * kFlatThreads + tid;
-    const int64_t base = tg.a0 + 4 * (int64_t)q;
-    d[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (q < tg.nquads) d[j] = ld_quad(e, base, tg.lo, tg.hi);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const bool valid = (q < tg.nquads) && (base + c >= tg.lo) && (base + c < tg.hi);
-      const uint32_t bin = key_of(comp(d[j], c)) >> 20;
-      ngt += (valid && bin > b1) ? 1u : 0u;
-      ncand += (valid && bin == b1) ? 1u : 0u;
-    }
-  }
-  const uint32_t incl = wave_incl_scan_u32(ncand, lane);
-  const uint32_t gsum = wave_sum_u32(ngt);
-  if (lane == 63) wsum[0][wave] = incl;
-  if (lane == 0) wsum[1][wave] = gsum;
-  __syncthreads();
-  const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
-  uint32_t before = 0, total = 0;
-#pragma unroll
-  for (int v = 0; v < 4; ++v) {
-    if (v < wave) before += wsum[0][v];
-    total += wsum[0][v];
-  }
-  if (tid == 0) {
-    ws.gt_cnt[tslot] = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
-    ws.eq_cnt[tslot] = 0;
-    list_base = (mode == 0 && total > 0) ? atomicAdd(&sp->cand_cnt, total) : 0u;
-  }
-  __syncthreads();
-  if (mode != 0) return;
-  uint32_t pos = list_base + before + (incl - ncand);
-  uint2* list = ws.cand + (int64_t)w * ws.cand_stride + L.cand_off;
-#pragma unroll
-  for (int j = 0; j < kQuadIters; ++j) {
-    const int q = j * kFlatThreads + tid;
-    const int64_t base = tg.a0 + 4 * (int64_t)q;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const bool valid = (q < tg.nquads) && (base + c >= tg.lo) && (base + c < tg.hi);
-      const uint32_t key = key_of(comp(d[j], c));
-      if (valid && (key >> 20) == b1) {
-        if ((int64_t)pos < L.cand_cap) list[pos] = make_uint2(key, (uint32_t)(base + c - L.offset));
-        ++pos;
-      }
-    }
-  }
-}
-
-// ---- R: resolve the exact threshold, per-tile counts, scans ---------------------------------
-
-constexpr int kResolveThreads = 1024;
-
-// Exclusive prefix sum over the 1024 threads; *total = sum.  Two barriers.
-__device__ __forceinline__ uint32_t block_excl_scan_1024(uint32_t v, uint32_t* wtot, uint32_t* total) {
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const uint32_t incl = wave_incl_scan_u32(v, lane);
-  __syncthreads();                               // wtot may still be read from the last call
-  if (lane == 63) wtot[wave] = incl;
-  __syncthreads();
-  uint32_t before = 0, tot = 0;
-  for (int i = 0; i < kResolveThreads / kWave; ++i) {
-    const uint32_t t = wtot[i];
-    if (i < wave) before += t;
-    tot += t;
-  }
-  *total = tot;
-  return before + incl - v;
-}
+// ---- candidates of one tile: from its segment, or re-read from Delta -------------------------
 
 template <class F>
-__device__ __forceinline__ void for_each_candidate(const Ws& ws, const LayerDev& L, int w, uint32_t mode,
-                                                   uint32_t b1, uint32_t ncand, F f) {
+__device__ __forceinline__ void for_tile_candidates(const Ws& ws, const LayerDev& L, const FlatTile& ft,
+                                                    const TileGeom& tg, int w, int tile_id, uint32_t mode,
+                                                    uint32_t b1, F f) {
   const int tid = threadIdx.x;
   if (mode == 0) {
-    const uint2* list = ws.cand + (int64_t)w * ws.cand_stride + L.cand_off;
-    for (uint32_t i = tid; i < ncand; i += kResolveThreads) {
-      const uint2 c = list[i];
+    const int64_t slot = (int64_t)w * ws.n_ftiles + tile_id;
+    const uint32_t cn = min(ws.cand_n[slot], (uint32_t)kSegCap);
+    const uint2* seg = ws.cand + slot * kSegCap;
+    for (uint32_t i = tid; i < cn; i += kFlatThreads) {
+      const uint2 c = seg[i];
       f(c.x, c.y);
     }
   } else {
-    const float* e = ws.e + (int64_t)w * ws.e_stride + L.offset;
-    const int64_t n = (int64_t)L.rows * L.cols;
-    for (int64_t i = tid; i < n; i += kResolveThreads) {
-      const uint32_t key = key_of(e[i]);
-      if ((key >> 20) == b1) f(key, (uint32_t)i);
+    const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+    for (int q = tid; q < tg.nquads; q += kFlatThreads) {
+      const int64_t base = tg.a0 + 4 * (int64_t)q;
+      const float4 d = ld_quad(e, base, tg.lo, tg.hi);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool valid = (base + c >= tg.lo) && (base + c < tg.hi);
+        const uint32_t key = key_of(comp(d, c));
+        if (valid && (key >> 20) == b1) f(key, (uint32_t)(base + c - L.offset));
+      }
     }
   }
 }
 
-__global__ __launch_bounds__(1024) void topk_resolve_kernel(const Ws ws, int w0) {
+// ---- B ----------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void topk_cand_kernel(const Ws ws, int w0) {
   __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3];
-  __shared__ uint32_t scratch[4];
-  __shared__ uint32_t wtot[kResolveThreads / kWave];
+  __shared__ uint32_t out[3], scratch[4], red[4], s_cn;
   const int w = w0 + blockIdx.y;
-  const int li = blockIdx.x;
   const int tid = threadIdx.x;
-  const LayerDev& L = ws.layers[li];
-  SelState* sp = ws.sel + (int64_t)w * ws.L + li;
-  const uint32_t b1 = sp->b1, above1 = sp->above1, c1 = sp->c1, mode = sp->mode, k = sp->k;
-  const uint32_t ncand = (mode == 0) ? min(c1, (uint32_t)min((int64_t)0x7fffffff, L.cand_cap)) : c1;
-
-  // level 2: key bits 19..9 of the candidates
-  for (int b = tid; b < kHistBins; b += kResolveThreads) hist[b] = 0;
+  const int lane = tid & 63;
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  const TileGeom tg = tile_geom(L, ft);
+  const int64_t wl = (int64_t)w * ws.L + ft.layer;
+  SelState* sp = ws.sel + wl;
+  const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  const int64_t slot = (int64_t)w * ws.n_ftiles + blockIdx.x;
+  uint2* seg = ws.cand + slot * kSegCap;
+  // the bin that holds the k-th largest key of this (worker, layer)
   if (tid < 3) out[tid] = 0;
+  hist_load(hist, ws.hist1 + wl * kHistBins, kHistBins);
+  const uint32_t k = (uint32_t)L.k[ws.level[ft.layer]];
+  pick_bin(hist, k, out, scratch);
+  const uint32_t b1 = out[0];
+  if (ft.start == 0 && tid == 0) {
+    sp->b1 = out[0]; sp->above1 = out[1]; sp->c1 = out[2]; sp->k = k;
+  }
+  for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0;
+  if (tid == 0) s_cn = 0;
   __syncthreads();
-  for_each_candidate(ws, L, w, mode, b1, ncand,
-                     [&](uint32_t key, uint32_t) { atomicAdd(&hist[(key >> 9) & 0x7ffu], 1u); });
-  __syncthreads();
-  const uint32_t k1 = k - above1;
-  pick_bin(hist, k1, out, scratch);
-  const uint32_t b2 = out[0], above2 = out[1];
-  __syncthreads();
+  uint32_t ngt = 0;
+#pragma unroll 3
+  for (int j = 0; j < kQuadIters; ++j) {
+    const int q = j * kFlatThreads + tid;
+    const bool qa = q < tg.nquads;
+    const int64_t base = tg.a0 + 4 * (int64_t)q;
+    float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (qa) d = ld_quad(e, base, tg.lo, tg.hi);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bool valid = qa && (base + c >= tg.lo) && (base + c < tg.hi);
+      const uint32_t key = key_of(comp(d, c));
+      const uint32_t bin = key >> 20;
+      ngt += (valid && bin > b1) ? 1u : 0u;
+      const bool cand = valid && bin == b1;
+      const uint64_t m = __ballot(cand);
+      if (m != 0) {                                      // wave-uniform
+        hist_add(hist, cand, (key >> 9) & 0x7ffu, lane);
+        uint32_t wbase = 0;
+        if (lane == (int)__builtin_ctzll(m)) wbase = atomicAdd(&s_cn, (uint32_t)__popcll(m));
+        wbase = (uint32_t)__shfl((int)wbase, (int)__builtin_ctzll(m), kWave);
+        const uint32_t pos = wbase + lanes_below(m, lane);
+        if (cand && pos < (uint32_t)kSegCap) seg[pos] = make_uint2(key, (uint32_t)(base + c - L.offset));
+      }
+    }
+  }
+  const uint32_t gsum = block_sum_u32(ngt, red);         // barriers: s_cn is final afterwards
+  const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
+  if (tid == 0) {
+    ws.gt_cnt[tslot] = gsum;
+    ws.eq_cnt[tslot] = 0;
+    ws.cand_n[slot] = s_cn;
+    if (s_cn > (uint32_t)kSegCap) sp->mode = 1;          // segment overflow: re-read path
+  }
+  uint32_t* gh = ws.hist2 + wl * kHistBins;
+  hist_flush(hist, gh, kHistBins);
+}
 
-  // level 3: key bits 8..0 of the candidates in (b1, b2)
-  for (int b = tid; b < kHistBins; b += kResolveThreads) hist[b] = 0;
+// ---- C ----------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void topk_level3_kernel(const Ws ws, int w0) {
+  __shared__ uint32_t hist[kHistBins];
+  __shared__ uint32_t out[3], scratch[4], red[4];
+  const int w = w0 + blockIdx.y;
+  const int tid = threadIdx.x;
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  const TileGeom tg = tile_geom(L, ft);
+  const int64_t wl = (int64_t)w * ws.L + ft.layer;
+  SelState* sp = ws.sel + wl;
+  const uint32_t b1 = sp->b1, mode = sp->mode;
+  // level-2 bin of the k-th largest: k - above1 are still needed from bin b1
   if (tid < 3) out[tid] = 0;
+  hist_load(hist, ws.hist2 + wl * kHistBins, kHistBins);
+  pick_bin(hist, sp->k - sp->above1, out, scratch);
+  const uint32_t b2 = out[0];
+  if (ft.start == 0) {
+    if (tid == 0) { sp->b2 = out[0]; sp->above2 = out[1]; }
+    hist_clear_global(ws.hist1 + wl * kHistBins, kHistBins);   // every reader of hist1 is done
+  }
+  for (int b = tid; b < 512; b += kFlatThreads) hist[b] = 0;
   __syncthreads();
-  for_each_candidate(ws, L, w, mode, b1, ncand, [&](uint32_t key, uint32_t) {
-    if (((key >> 9) & 0x7ffu) == b2) atomicAdd(&hist[key & 0x1ffu], 1u);
+  uint32_t ngt = 0;
+  for_tile_candidates(ws, L, ft, tg, w, blockIdx.x, mode, b1, [&](uint32_t key, uint32_t) {
+    const uint32_t bb = (key >> 9) & 0x7ffu;
+    if (bb > b2) ++ngt;
+    else if (bb == b2) atomicAdd(&hist[key & 0x1ffu], 1u);
   });
-  __syncthreads();
-  const uint32_t k2 = k1 - above2;
+  const uint32_t gsum = block_sum_u32(ngt, red);
+  const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
+  if (tid == 0) ws.gt_cnt[tslot] += gsum;
+  uint32_t* gh = ws.hist3 + wl * 512;
+  hist_flush(hist, gh, 512);
+}
+
+// ---- D ----------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void topk_count_kernel(const Ws ws, int w0) {
+  __shared__ uint32_t hist[kHistBins];
+  __shared__ uint32_t out[3], scratch[4], red[4];
+  const int w = w0 + blockIdx.y;
+  const int tid = threadIdx.x;
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  const TileGeom tg = tile_geom(L, ft);
+  const int64_t wl = (int64_t)w * ws.L + ft.layer;
+  SelState* sp = ws.sel + wl;
+  const uint32_t b1 = sp->b1, b2 = sp->b2, mode = sp->mode;
+  // exact threshold: k - above1 - above2 are still needed from bin (b1, b2)
+  if (tid < 3) out[tid] = 0;
+  hist_load(hist, ws.hist3 + wl * 512, 512);
+  const uint32_t k2 = sp->k - sp->above1 - sp->above2;
   pick_bin(hist, k2, out, scratch);
-  const uint32_t b3 = out[0], above3 = out[1], c3 = out[2];
-  const uint32_t T = (b1 << 20) | (b2 << 9) | b3;
-  const uint32_t ktie = k2 - above3;             // 1 <= ktie <= c3
-  if (tid == 0) {
-    sp->T = T;
-    sp->ktie = ktie;
-    sp->alleq = (ktie == c3) ? 1u : 0u;
+  const uint32_t T = (b1 << 20) | (b2 << 9) | out[0];
+  if (ft.start == 0) {
+    if (tid == 0) {
+      sp->T = T;
+      sp->ktie = k2 - out[1];                            // 1 <= ktie <= entries equal to T
+      sp->alleq = (k2 - out[1] == out[2]) ? 1u : 0u;
+    }
+    hist_clear_global(ws.hist2 + wl * kHistBins, kHistBins);
   }
-
-  // per-tile counts of candidates above / equal to T
-  uint32_t* gt = ws.gt_cnt + (int64_t)w * ws.tile_stride + L.toff;
-  uint32_t* eq = ws.eq_cnt + (int64_t)w * ws.tile_stride + L.toff;
-  for_each_candidate(ws, L, w, mode, b1, ncand, [&](uint32_t key, uint32_t idx) {
-    const uint32_t t = idx >> kTileShift;
-    if ((int)t < L.ntiles) {
-      if (key > T) atomicAdd(&gt[t], 1u);
-      else if (key == T) atomicAdd(&eq[t], 1u);
+  uint32_t ngt = 0, neq = 0;
+  for_tile_candidates(ws, L, ft, tg, w, blockIdx.x, mode, b1, [&](uint32_t key, uint32_t) {
+    if (((key >> 9) & 0x7ffu) == b2) {                   // bins above b2 were counted in C
+      if (key > T) ++ngt;
+      else if (key == T) ++neq;
     }
   });
-  __threadfence();
-  __syncthreads();
-
-  // exclusive scans over the layer's tiles: ties before a tile, selected before a tile
-  uint32_t* eqo = ws.eq_off + (int64_t)w * ws.tile_stride + L.toff;
-  uint32_t* selo = ws.sel_off + (int64_t)w * ws.tile_stride + L.toff;
-  uint32_t carry_eq = 0, carry_sel = 0;
-  for (int t0 = 0; t0 < L.ntiles; t0 += kResolveThreads) {
-    const int t = t0 + tid;
-    const uint32_t ne = (t < L.ntiles) ? ld_agent(&eq[t]) : 0u;
-    const uint32_t ng = (t < L.ntiles) ? ld_agent(&gt[t]) : 0u;
-    uint32_t tot_eq, tot_sel;
-    const uint32_t eq_ex = carry_eq + block_excl_scan_1024(ne, wtot, &tot_eq);
-    const uint32_t take = (eq_ex >= ktie) ? 0u : min(ne, ktie - eq_ex);
-    const uint32_t sel_ex = carry_sel + block_excl_scan_1024(ng + take, wtot, &tot_sel);
-    if (t < L.ntiles) {
-      eqo[t] = eq_ex;
-      selo[t] = sel_ex;
-    }
-    carry_eq += tot_eq;
-    carry_sel += tot_sel;
-  }
+  const uint32_t gsum = block_sum_u32(ngt, red);
+  const uint32_t esum = block_sum_u32(neq, red);
+  const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
   if (tid == 0) {
-    eqo[L.ntiles] = carry_eq;
-    selo[L.ntiles] = carry_sel;
+    ws.gt_cnt[tslot] += gsum;
+    ws.eq_cnt[tslot] = esum;
   }
 }
 
-// ---- pass E ---------------------------------------------------------------------------------
+// ---- E ----------------------------------------------------------------------------------------
 
 __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) {
   __shared__ uint32_t cnt[kQuadIters][4];
+  __shared__ uint32_t red[4];
   const int w = w0 + blockIdx.y;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -354,11 +331,25 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
-  const SelState* sp = ws.sel + (int64_t)w * ws.L + ft.layer;
+  const int64_t wl = (int64_t)w * ws.L + ft.layer;
+  const SelState* sp = ws.sel + wl;
   const uint32_t T = sp->T, ktie = sp->ktie, alleq = sp->alleq, kk = sp->k;
-  const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
-  const uint32_t eq_base = ws.eq_off[tslot];
-  const uint32_t sel_base = ws.sel_off[tslot];
+  // ties and selected entries in the tiles before mine.  The tie quota is used up in index
+  // order, so the tiles before mine took min(ktie, ties before me) ties in total.
+  const int my_t = ft.start >> kTileShift;
+  const int64_t tbase = (int64_t)w * ws.tile_stride + L.toff;
+  uint32_t s_eq = 0, s_gt = 0;
+  for (int t = tid; t < my_t; t += kFlatThreads) {
+    s_eq += ws.eq_cnt[tbase + t];
+    s_gt += ws.gt_cnt[tbase + t];
+  }
+  const uint32_t eq_base = block_sum_u32(s_eq, red);
+  const uint32_t sel_base = block_sum_u32(s_gt, red) + min(ktie, eq_base);
+  if (tid == 0) {
+    ws.sel_off[tbase + my_t] = sel_base;                 // read by the payload mean
+    if (my_t == L.ntiles - 1) ws.sel_off[tbase + L.ntiles] = kk;
+  }
+  if (ft.start == 0) hist_clear_global(ws.hist3 + wl * 512, 512);
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
 
   float4 d[kQuadIters];
@@ -473,7 +464,7 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
   }
 }
 
-// ---- K6: dense mean of the W payloads ------------------------------------------------------
+// ---- K6: dense mean of the W payloads --------------------------------------------------------
 
 __global__ __launch_bounds__(256) void topk_sparse_mean_kernel(const Ws ws, float* __restrict__ out) {
   __shared__ float acc[kTile];

@@ -38,13 +38,13 @@ struct Plan {
   int32_t rmax = 0;
   int64_t N = 0, e_stride = 0;
   int64_t q_total = 0, p_total = 0, ppart_stride = 0, qpart_stride = 0, vec_total = 0;
-  int64_t pay_stride = 0, cand_stride = 0, tile_stride = 0;
+  int64_t pay_stride = 0, tile_stride = 0;
   // workspace regions
   Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
   Region r_A, r_e, r_norm_part;
   Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean;
-  Region r_hist1, r_sel, r_cand, r_gt, r_eq, r_seloff, r_eqoff, r_payidx, r_payval;
+  Region r_hist1, r_hist2, r_hist3, r_done, r_sel, r_cand, r_candn, r_gt, r_eq, r_seloff, r_eqoff, r_payidx, r_payval;
   int64_t total_bytes = 0;
 };
 
@@ -160,9 +160,6 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
       d.k[1] = kof(c->k_num_crit);
       d.pay_off = p.pay_stride;
       p.pay_stride += std::max(d.k[0], d.k[1]);
-      d.cand_off = p.cand_stride;
-      d.cand_cap = std::min<int64_t>(n, std::max<int64_t>(n / 8, 4096));
-      p.cand_stride += d.cand_cap;
     }
   }
   p.tile_stride = ntile + nl;
@@ -199,8 +196,12 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     reg(p.r_vecmean, 4 * p.vec_total);
   } else {
     reg(p.r_hist1, 4 * (int64_t)kHistBins * nl * W);
+    reg(p.r_hist2, 4 * (int64_t)kHistBins * nl * W);
+    reg(p.r_hist3, 4 * (int64_t)512 * nl * W);
+    reg(p.r_done, 4 * (int64_t)4 * nl * W);
     reg(p.r_sel, (int64_t)sizeof(SelState) * nl * W);
-    reg(p.r_cand, 8 * p.cand_stride * W);
+    reg(p.r_cand, 8 * (int64_t)kSegCap * ntile * W);
+    reg(p.r_candn, 4 * ntile * W);
     reg(p.r_gt, 4 * p.tile_stride * W);
     reg(p.r_eq, 4 * p.tile_stride * W);
     reg(p.r_seloff, 4 * p.tile_stride * W);
@@ -216,16 +217,16 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
 
 enum Stage {
   ST_psgd_ef_p_kernel = 0, ST_psgd_orth_kernel, ST_psgd_q_kernel, ST_psgd_qmean_kernel,
-  ST_psgd_decomp_kernel, ST_topk_ef_hist_kernel, ST_topk_pick1_kernel, ST_topk_cand_kernel,
-  ST_topk_resolve_kernel, ST_topk_compact_kernel, ST_topk_sparse_mean_kernel,
+  ST_psgd_decomp_kernel, ST_topk_ef_hist_kernel, ST_topk_cand_kernel, ST_topk_level3_kernel,
+  ST_topk_count_kernel, ST_topk_compact_kernel, ST_topk_sparse_mean_kernel,
   ST_norm_partial_kernel, ST_regime_decide_kernel, ST_recount_words_kernel, ST_zero_accum_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
 static const char* const kStageNames[ST_COUNT] = {
   "psgd_ef_p_kernel", "psgd_orth_kernel", "psgd_q_kernel", "psgd_qmean_kernel",
-  "psgd_decomp_kernel", "topk_ef_hist_kernel", "topk_pick1_kernel", "topk_cand_kernel",
-  "topk_resolve_kernel", "topk_compact_kernel", "topk_sparse_mean_kernel",
+  "psgd_decomp_kernel", "topk_ef_hist_kernel", "topk_cand_kernel", "topk_level3_kernel",
+  "topk_count_kernel", "topk_compact_kernel", "topk_sparse_mean_kernel",
   "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
@@ -332,9 +333,9 @@ int launch_phase0(acc_ctx* c, int w0, int nw) {
     if (gx > 0) ACC_LAUNCH(c, psgd_ef_p_kernel, dim3(gx, nw), dim3(256), ws, c->grads, w0);
   } else {
     ACC_LAUNCH(c, topk_ef_hist_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, c->grads, w0);
-    ACC_LAUNCH(c, topk_pick1_kernel, dim3(ws.L, nw), dim3(256), ws, w0);
     ACC_LAUNCH(c, topk_cand_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
-    ACC_LAUNCH(c, topk_resolve_kernel, dim3(ws.L, nw), dim3(kResolveThreads), ws, w0);
+    ACC_LAUNCH(c, topk_level3_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
+    ACC_LAUNCH(c, topk_count_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
     ACC_LAUNCH(c, topk_compact_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
   }
   return ACC_OK;
@@ -455,9 +456,12 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.vecmean = at<float>(c, p.r_vecmean);
   } else {
     ws.hist1 = at<uint32_t>(c, p.r_hist1);
+    ws.hist2 = at<uint32_t>(c, p.r_hist2);
+    ws.hist3 = at<uint32_t>(c, p.r_hist3);
+    ws.done = at<uint32_t>(c, p.r_done);
     ws.sel = at<SelState>(c, p.r_sel);
     ws.cand = at<uint2>(c, p.r_cand);
-    ws.cand_stride = p.cand_stride;
+    ws.cand_n = at<uint32_t>(c, p.r_candn);
     ws.gt_cnt = at<uint32_t>(c, p.r_gt);
     ws.eq_cnt = at<uint32_t>(c, p.r_eq);
     ws.sel_off = at<uint32_t>(c, p.r_seloff);
