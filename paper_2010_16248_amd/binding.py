@@ -21,7 +21,9 @@ ACC_MAX_RANK = 4
 
 _STATUS = {0: "ACC_OK", 1: "ACC_EINVAL", 2: "ACC_ESTATE", 3: "ACC_ENOSPACE", 4: "ACC_EHIP"}
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaccordion.so")
+# ACCORDION_LIB selects another build of the same library (e.g. one with extra checks)
+LIB_PATH = os.environ.get("ACCORDION_LIB") or os.path.join(
+    os.path.dirname(os.path.abspath(__file__)), "libaccordion.so")
 
 
 class acc_layer(C.Structure):

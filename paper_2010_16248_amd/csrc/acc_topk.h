@@ -189,6 +189,14 @@ __global__ __launch_bounds__(256) void topk_cand_kernel(const Ws ws, int w0) {
   const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
   const int64_t slot = (int64_t)w * ws.n_ftiles + blockIdx.x;
   uint2* seg = ws.cand + slot * kSegCap;
+  // the tile's data is requested first so that its latency overlaps the bin search
+  float4 d[kQuadIters];
+#pragma unroll
+  for (int j = 0; j < kQuadIters; ++j) {
+    const int q = j * kFlatThreads + tid;
+    d[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (q < tg.nquads) d[j] = ld_quad(e, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi);
+  }
   // the bin that holds the k-th largest key of this (worker, layer)
   if (tid < 3) out[tid] = 0;
   hist_load(hist, ws.hist1 + wl * kHistBins, kHistBins);
@@ -202,28 +210,35 @@ __global__ __launch_bounds__(256) void topk_cand_kernel(const Ws ws, int w0) {
   if (tid == 0) s_cn = 0;
   __syncthreads();
   uint32_t ngt = 0;
-#pragma unroll 3
+#pragma unroll
   for (int j = 0; j < kQuadIters; ++j) {
     const int q = j * kFlatThreads + tid;
-    const bool qa = q < tg.nquads;
     const int64_t base = tg.a0 + 4 * (int64_t)q;
-    float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (qa) d = ld_quad(e, base, tg.lo, tg.hi);
+    uint32_t key[4];
+    bool cand[4];
+    uint64_t m[4];
+    uint32_t tot = 0;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const bool valid = qa && (base + c >= tg.lo) && (base + c < tg.hi);
-      const uint32_t key = key_of(comp(d, c));
-      const uint32_t bin = key >> 20;
+      const bool valid = (q < tg.nquads) && (base + c >= tg.lo) && (base + c < tg.hi);
+      key[c] = key_of(comp(d[j], c));
+      const uint32_t bin = key[c] >> 20;
       ngt += (valid && bin > b1) ? 1u : 0u;
-      const bool cand = valid && bin == b1;
-      const uint64_t m = __ballot(cand);
-      if (m != 0) {                                      // wave-uniform
-        hist_add(hist, cand, (key >> 9) & 0x7ffu, lane);
-        uint32_t wbase = 0;
-        if (lane == (int)__builtin_ctzll(m)) wbase = atomicAdd(&s_cn, (uint32_t)__popcll(m));
-        wbase = (uint32_t)__shfl((int)wbase, (int)__builtin_ctzll(m), kWave);
-        const uint32_t pos = wbase + lanes_below(m, lane);
-        if (cand && pos < (uint32_t)kSegCap) seg[pos] = make_uint2(key, (uint32_t)(base + c - L.offset));
+      cand[c] = valid && bin == b1;
+      m[c] = __ballot(cand[c]);
+      tot += (uint32_t)__popcll(m[c]);
+    }
+    if (tot != 0) {                                      // wave-uniform
+      uint32_t wbase = 0;
+      if (lane == 0) wbase = atomicAdd(&s_cn, tot);      // one reservation per wave and iteration
+      wbase = (uint32_t)__builtin_amdgcn_readfirstlane((int)wbase);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        hist_add(hist, cand[c], (key[c] >> 9) & 0x7ffu, lane);
+        const uint32_t pos = wbase + lanes_below(m[c], lane);
+        if (cand[c] && pos < (uint32_t)kSegCap)
+          seg[pos] = make_uint2(key[c], (uint32_t)(base + c - L.offset));
+        wbase += (uint32_t)__popcll(m[c]);
       }
     }
   }
@@ -235,8 +250,7 @@ __global__ __launch_bounds__(256) void topk_cand_kernel(const Ws ws, int w0) {
     ws.cand_n[slot] = s_cn;
     if (s_cn > (uint32_t)kSegCap) sp->mode = 1;          // segment overflow: re-read path
   }
-  uint32_t* gh = ws.hist2 + wl * kHistBins;
-  hist_flush(hist, gh, kHistBins);
+  hist_flush(hist, ws.hist2 + wl * kHistBins, kHistBins);
 }
 
 // ---- C ----------------------------------------------------------------------------------------
@@ -321,21 +335,36 @@ __global__ __launch_bounds__(256) void topk_count_kernel(const Ws ws, int w0) {
 
 // ---- E ----------------------------------------------------------------------------------------
 
+// A wave owns a contiguous quarter of the tile, so ranks and payload positions advance by
+// wave-uniform running counters; index order = (wave, iteration, lane, component).
+constexpr int kWaveQuadIters = ((kTile / 4 + 1 + 3) / 4 + kWave - 1) / kWave;   // 9
+
 __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t cnt[kQuadIters][4];
+  __shared__ uint32_t wcnt[2][4];
   __shared__ uint32_t red[4];
   const int w = w0 + blockIdx.y;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   const SelState* sp = ws.sel + wl;
+  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  const int qw = (tg.nquads + 3) >> 2;                   // quads per wave
+  const int qbeg = wave * qw;
+  const int qend = min(qbeg + qw, tg.nquads);
+  float4 d[kWaveQuadIters];
+#pragma unroll
+  for (int j = 0; j < kWaveQuadIters; ++j) {
+    const int q = qbeg + j * kWave + lane;
+    d[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (q < qend) d[j] = ld_quad(e, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi);
+  }
   const uint32_t T = sp->T, ktie = sp->ktie, alleq = sp->alleq, kk = sp->k;
   // ties and selected entries in the tiles before mine.  The tie quota is used up in index
-  // order, so the tiles before mine took min(ktie, ties before me) ties in total.
+  // order, so everything before a point took min(ktie, ties before that point) ties in total.
   const int my_t = ft.start >> kTileShift;
   const int64_t tbase = (int64_t)w * ws.tile_stride + L.toff;
   uint32_t s_eq = 0, s_gt = 0;
@@ -344,115 +373,79 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
     s_gt += ws.gt_cnt[tbase + t];
   }
   const uint32_t eq_base = block_sum_u32(s_eq, red);
-  const uint32_t sel_base = block_sum_u32(s_gt, red) + min(ktie, eq_base);
+  const uint32_t gt_base = block_sum_u32(s_gt, red);
   if (tid == 0) {
-    ws.sel_off[tbase + my_t] = sel_base;                 // read by the payload mean
+    ws.sel_off[tbase + my_t] = gt_base + min(ktie, eq_base);   // read by the payload mean
     if (my_t == L.ntiles - 1) ws.sel_off[tbase + L.ntiles] = kk;
   }
   if (ft.start == 0) hist_clear_global(ws.hist3 + wl * 512, 512);
-  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
 
-  float4 d[kQuadIters];
+  // pass 1: entries above T and equal to T in my wave's quarter
+  uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
-  for (int j = 0; j < kQuadIters; ++j) {
-    const int q = j * kFlatThreads + tid;
-    d[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (q < tg.nquads) d[j] = ld_quad(e, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi);
-  }
-  // bit (4*j + c) of selm: element c of quad j of this thread is selected
-  uint64_t selm = 0;
-  if (alleq) {
-#pragma unroll
-    for (int j = 0; j < kQuadIters; ++j) {
-      const int q = j * kFlatThreads + tid;
-      const int64_t base = tg.a0 + 4 * (int64_t)q;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bool valid = (q < tg.nquads) && (base + c >= tg.lo) && (base + c < tg.hi);
-        if (valid && key_of(comp(d[j], c)) >= T) selm |= 1ull << (4 * j + c);
-      }
-    }
-  } else {
-    // rank of every tie in index order: (iteration j, wave, lane, component)
-    uint32_t pre[kQuadIters];                    // ties of this wave before my lane in iteration j
-#pragma unroll
-    for (int j = 0; j < kQuadIters; ++j) {
-      const int q = j * kFlatThreads + tid;
-      const int64_t base = tg.a0 + 4 * (int64_t)q;
-      uint32_t below = 0, wtotal = 0;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bool valid = (q < tg.nquads) && (base + c >= tg.lo) && (base + c < tg.hi);
-        const uint64_t m = __ballot(valid && key_of(comp(d[j], c)) == T);
-        below += lanes_below(m, lane);
-        wtotal += (uint32_t)__popcll(m);
-      }
-      pre[j] = below;
-      if (lane == 0) cnt[j][wave] = wtotal;
-    }
-    __syncthreads();
-    uint32_t run = eq_base;
-#pragma unroll
-    for (int j = 0; j < kQuadIters; ++j) {
-      uint32_t mine = run;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const uint32_t cv = cnt[j][v];
-        if (v < wave) mine += cv;
-        run += cv;
-      }
-      const int q = j * kFlatThreads + tid;
-      const int64_t base = tg.a0 + 4 * (int64_t)q;
-      uint32_t rank = mine + pre[j];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bool valid = (q < tg.nquads) && (base + c >= tg.lo) && (base + c < tg.hi);
-        const uint32_t key = key_of(comp(d[j], c));
-        if (valid) {
-          if (key > T) {
-            selm |= 1ull << (4 * j + c);
-          } else if (key == T) {
-            if (rank < ktie) selm |= 1ull << (4 * j + c);
-            ++rank;
-          }
-        }
-      }
-    }
-    __syncthreads();                             // cnt is reused below
-  }
-  // positions of the selected entries, same order
-  uint32_t pre[kQuadIters];
-#pragma unroll
-  for (int j = 0; j < kQuadIters; ++j) {
-    uint32_t below = 0, wtotal = 0;
+  for (int j = 0; j < kWaveQuadIters; ++j) {
+    const int q = qbeg + j * kWave + lane;
+    const int64_t base = tg.a0 + 4 * (int64_t)q;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const uint64_t m = __ballot((selm >> (4 * j + c)) & 1ull);
-      below += lanes_below(m, lane);
-      wtotal += (uint32_t)__popcll(m);
+      const bool valid = (q < qend) && (base + c >= tg.lo) && (base + c < tg.hi);
+      const uint32_t key = key_of(comp(d[j], c));
+      n_gt += (uint32_t)__popcll(__ballot(valid && key > T));
+      n_eq += (uint32_t)__popcll(__ballot(valid && key == T));
     }
-    pre[j] = below;
-    if (lane == 0) cnt[j][wave] = wtotal;
   }
+  if (lane == 0) { wcnt[0][wave] = n_eq; wcnt[1][wave] = n_gt; }
   __syncthreads();
+  uint32_t eq_run = eq_base, gt_before = gt_base;
+  for (int v = 0; v < wave; ++v) { eq_run += wcnt[0][v]; gt_before += wcnt[1][v]; }
+  uint32_t pos_run = gt_before + min(ktie, eq_run);
+
+  // pass 2: ranks of the ties, positions of the selected entries, writes
   int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
   float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
-  uint32_t run = sel_base;
 #pragma unroll
-  for (int j = 0; j < kQuadIters; ++j) {
-    uint32_t mine = run;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const uint32_t cv = cnt[j][v];
-      if (v < wave) mine += cv;
-      run += cv;
-    }
-    const int q = j * kFlatThreads + tid;
+  for (int j = 0; j < kWaveQuadIters; ++j) {
+    const int q = qbeg + j * kWave + lane;
     const int64_t base = tg.a0 + 4 * (int64_t)q;
-    uint32_t pos = mine + pre[j];
+    bool sel[4];
+    uint32_t key[4];
+    bool valid[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      if ((selm >> (4 * j + c)) & 1ull) {
+      valid[c] = (q < qend) && (base + c >= tg.lo) && (base + c < tg.hi);
+      key[c] = key_of(comp(d[j], c));
+    }
+    if (alleq) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) sel[c] = valid[c] && key[c] >= T;
+    } else {
+      uint32_t below = 0, total = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint64_t m = __ballot(valid[c] && key[c] == T);
+        below += lanes_below(m, lane);
+        total += (uint32_t)__popcll(m);
+      }
+      uint32_t rank = eq_run + below;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool iseq = valid[c] && key[c] == T;
+        sel[c] = valid[c] && (key[c] > T || (iseq && rank < ktie));
+        rank += iseq ? 1u : 0u;
+      }
+      eq_run += total;
+    }
+    uint32_t below = 0, total = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint64_t m = __ballot(sel[c]);
+      below += lanes_below(m, lane);
+      total += (uint32_t)__popcll(m);
+    }
+    uint32_t pos = pos_run + below;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (sel[c]) {
         if (pos < kk) {                          // always true for consistent state
           pidx[pos] = (int32_t)(base + c - L.offset);
           pval[pos] = comp(d[j], c);
@@ -461,6 +454,7 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
         ++pos;
       }
     }
+    pos_run += total;
   }
 }
 
