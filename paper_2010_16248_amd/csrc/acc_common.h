@@ -13,7 +13,8 @@ constexpr int kQuadIters = (kTile / 4 + 1 + kFlatThreads - 1) / kFlatThreads;  /
 constexpr int kMatRows = 64;             // matrix tile: 64 rows x 256 columns
 constexpr int kMatCols = 256;
 constexpr int kHistBins = 2048;          // 11 key bits per radix level
-constexpr int kSegCap = 1024;           // candidate slots per flat tile (TopK)
+constexpr int kSubCap = 256;             // candidate slots per wave quarter of a flat tile (TopK)
+constexpr int kSegCap = 4 * kSubCap;    // candidate slots per flat tile
 constexpr int kMaxW = 32;
 constexpr int kMaxRank = 4;
 
@@ -90,14 +91,14 @@ struct Ws {
   uint32_t* hist1;             // W x L x kHistBins, zero between steps
   uint32_t* hist2;             // W x L x kHistBins, zero between steps
   uint32_t* hist3;             // W x L x 512, zero between steps
-  uint32_t* done;              // 4 x W x L arrival counters, zero between kernels
   SelState* sel;               // W x L
-  uint2* cand;                 // W x n_ftiles x kSegCap candidate slots (key, layer-local index)
-  uint32_t* cand_n;            // W x n_ftiles candidates found per tile
-  uint32_t* gt_cnt;            // W x tile_stride
-  uint32_t* eq_cnt;
-  uint32_t* sel_off;
-  uint32_t* eq_off;
+  uint2* cand;                 // W x n_ftiles x 4 x kSubCap candidate slots (key, layer-local index)
+  uint32_t* cand_n;            // W x n_ftiles x 4 candidates found per wave quarter
+  uint32_t* gt4;               // W x n_ftiles x 4 entries above the threshold per wave quarter
+  uint32_t* eq4;               // W x n_ftiles x 4 entries equal to the threshold per wave quarter
+  uint32_t* gt_cnt;            // W x tile_stride, per tile
+  uint32_t* eq_cnt;            // W x tile_stride, per tile
+  uint32_t* sel_off;           // W x tile_stride, payload position of a tile's first entry
   int64_t tile_stride;
   int32_t* pay_idx;  float* pay_val;  int64_t pay_stride;
   int64_t N;

@@ -20,8 +20,9 @@
 //   K6 topk_sparse_mean  dense mean of the W payloads
 //
 // Cross-workgroup combination is by integer atomics and fixed-order sums only, so every
-// output is bit-reproducible.  A segment holds kSegCap candidates; if a tile has more (huge
-// tie classes: zeros, constants) the layer falls back to re-reading Delta in C and D.
+// output is bit-reproducible.  A wave quarter's segment holds kSubCap candidates; if a quarter
+// has more (huge tie classes: zeros, constants) the layer falls back to re-reading Delta in C
+// and D.
 #pragma once
 #include "acc_common.h"
 
@@ -143,31 +144,57 @@ __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const Gr
   if (ft.start == 0 && tid == 0) ws.sel[wl].mode = 0;    // B raises it on segment overflow
 }
 
-// ---- candidates of one tile: from its segment, or re-read from Delta -------------------------
+// ---- wave quarters ------------------------------------------------------------------------------
+// In kernels B..E wave v of the workgroup owns the contiguous quarter [v*qw, (v+1)*qw) of the
+// tile's 16-byte groups, so every count, candidate list and running offset is wave-local
+// (scalar registers, no barriers, no atomics) and index order is (wave, iteration, lane,
+// component).
 
+struct WaveSpan { int qbeg, qend; };
+
+__device__ __forceinline__ WaveSpan wave_span(const TileGeom& tg, int wave) {
+  const int qw = (tg.nquads + 3) >> 2;
+  WaveSpan s;
+  s.qbeg = wave * qw;
+  s.qend = min(s.qbeg + qw, tg.nquads);
+  return s;
+}
+
+__device__ __forceinline__ float4 ld_span(const float* __restrict__ e, const TileGeom& tg,
+                                          const WaveSpan& sp, int q) {
+  if (q < sp.qend) return ld_quad(e, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi);
+  return make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// Candidates (entries in level-1 bin b1) of my wave's quarter: from the quarter's segment, or,
+// after a segment overflow, re-read from Delta.  f(key, valid) is called by all 64 lanes
+// together (valid marks the lanes that hold a candidate).
 template <class F>
-__device__ __forceinline__ void for_tile_candidates(const Ws& ws, const LayerDev& L, const FlatTile& ft,
-                                                    const TileGeom& tg, int w, int tile_id, uint32_t mode,
+__device__ __forceinline__ void for_wave_candidates(const Ws& ws, const LayerDev& L, const TileGeom& tg,
+                                                    int w, int tile_id, int wave, int lane, uint32_t mode,
                                                     uint32_t b1, F f) {
-  const int tid = threadIdx.x;
   if (mode == 0) {
-    const int64_t slot = (int64_t)w * ws.n_ftiles + tile_id;
-    const uint32_t cn = min(ws.cand_n[slot], (uint32_t)kSegCap);
-    const uint2* seg = ws.cand + slot * kSegCap;
-    for (uint32_t i = tid; i < cn; i += kFlatThreads) {
-      const uint2 c = seg[i];
-      f(c.x, c.y);
+    const int64_t slot4 = ((int64_t)w * ws.n_ftiles + tile_id) * 4 + wave;
+    const uint32_t cn = min(ws.cand_n[slot4], (uint32_t)kSubCap);
+    const uint2* seg = ws.cand + slot4 * kSubCap;
+    for (uint32_t i0 = 0; i0 < cn; i0 += kWave) {          // cn is wave-uniform
+      const uint32_t i = i0 + lane;
+      const bool valid = i < cn;
+      const uint32_t key = valid ? seg[i].x : 0u;
+      f(key, valid);
     }
   } else {
     const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-    for (int q = tid; q < tg.nquads; q += kFlatThreads) {
+    const WaveSpan sp = wave_span(tg, wave);
+    for (int q0 = sp.qbeg; q0 < sp.qend; q0 += kWave) {
+      const int q = q0 + lane;
       const int64_t base = tg.a0 + 4 * (int64_t)q;
-      const float4 d = ld_quad(e, base, tg.lo, tg.hi);
+      const float4 d = ld_span(e, tg, sp, q);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const bool valid = (base + c >= tg.lo) && (base + c < tg.hi);
+        const bool valid = (q < sp.qend) && (base + c >= tg.lo) && (base + c < tg.hi);
         const uint32_t key = key_of(comp(d, c));
-        if (valid && (key >> 20) == b1) f(key, (uint32_t)(base + c - L.offset));
+        f(key, valid && (key >> 20) == b1);
       }
     }
   }
@@ -177,26 +204,22 @@ __device__ __forceinline__ void for_tile_candidates(const Ws& ws, const LayerDev
 
 __global__ __launch_bounds__(256) void topk_cand_kernel(const Ws ws, int w0) {
   __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3], scratch[4], red[4], s_cn;
+  __shared__ uint32_t out[3], scratch[4];
+  __shared__ uint2 stage[4][kSubCap];
   const int w = w0 + blockIdx.y;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
+  const WaveSpan span = wave_span(tg, wave);
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   SelState* sp = ws.sel + wl;
   const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-  const int64_t slot = (int64_t)w * ws.n_ftiles + blockIdx.x;
-  uint2* seg = ws.cand + slot * kSegCap;
-  // the tile's data is requested first so that its latency overlaps the bin search
-  float4 d[kQuadIters];
-#pragma unroll
-  for (int j = 0; j < kQuadIters; ++j) {
-    const int q = j * kFlatThreads + tid;
-    d[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (q < tg.nquads) d[j] = ld_quad(e, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi);
-  }
+  const int64_t slot4 = ((int64_t)w * ws.n_ftiles + blockIdx.x) * 4 + wave;
+  // the first data is requested before the bin search so that the two latencies overlap
+  float4 cur = ld_span(e, tg, span, span.qbeg + lane);
   // the bin that holds the k-th largest key of this (worker, layer)
   if (tid < 3) out[tid] = 0;
   hist_load(hist, ws.hist1 + wl * kHistBins, kHistBins);
@@ -207,49 +230,58 @@ __global__ __launch_bounds__(256) void topk_cand_kernel(const Ws ws, int w0) {
     sp->b1 = out[0]; sp->above1 = out[1]; sp->c1 = out[2]; sp->k = k;
   }
   for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0;
-  if (tid == 0) s_cn = 0;
   __syncthreads();
-  uint32_t ngt = 0;
-#pragma unroll
-  for (int j = 0; j < kQuadIters; ++j) {
-    const int q = j * kFlatThreads + tid;
+  uint32_t n_gt = 0, n_c = 0;                              // wave-uniform
+  for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
+    const int q = q0 + lane;
+    const float4 nxt = ld_span(e, tg, span, q + kWave);
     const int64_t base = tg.a0 + 4 * (int64_t)q;
-    uint32_t key[4];
-    bool cand[4];
-    uint64_t m[4];
-    uint32_t tot = 0;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const bool valid = (q < tg.nquads) && (base + c >= tg.lo) && (base + c < tg.hi);
-      key[c] = key_of(comp(d[j], c));
-      const uint32_t bin = key[c] >> 20;
-      ngt += (valid && bin > b1) ? 1u : 0u;
-      cand[c] = valid && bin == b1;
-      m[c] = __ballot(cand[c]);
-      tot += (uint32_t)__popcll(m[c]);
+      const bool valid = (q < span.qend) && (base + c >= tg.lo) && (base + c < tg.hi);
+      const uint32_t key = key_of(comp(cur, c));
+      const uint32_t bin = key >> 20;
+      n_gt += (uint32_t)__popcll(__ballot(valid && bin > b1));
+      const bool cand = valid && bin == b1;
+      const uint64_t m = __ballot(cand);
+      if (m != 0) {
+        const uint32_t pos = n_c + lanes_below(m, lane);
+        if (cand && pos < (uint32_t)kSubCap)
+          stage[wave][pos] = make_uint2(key, (uint32_t)(base + c - L.offset));
+        n_c += (uint32_t)__popcll(m);
+      }
     }
-    if (tot != 0) {                                      // wave-uniform
-      uint32_t wbase = 0;
-      if (lane == 0) wbase = atomicAdd(&s_cn, tot);      // one reservation per wave and iteration
-      wbase = (uint32_t)__builtin_amdgcn_readfirstlane((int)wbase);
+    cur = nxt;
+  }
+  if (lane == 0) {
+    ws.gt4[slot4] = n_gt;
+    ws.cand_n[slot4] = n_c;
+    if (n_c > (uint32_t)kSubCap) sp->mode = 1;             // segment overflow: re-read path
+  }
+  __syncthreads();                                         // staged candidates are visible
+  if (n_c <= (uint32_t)kSubCap) {
+    // level-2 histogram and the segment from the compacted list (coalesced stores)
+    uint2* seg = ws.cand + slot4 * kSubCap;
+    for (uint32_t i = lane; i < n_c; i += kWave) {
+      const uint2 c = stage[wave][i];
+      atomicAdd(&hist[(c.x >> 9) & 0x7ffu], 1u);
+      seg[i] = c;
+    }
+  } else {
+    // more candidates than slots (huge tie class): the histogram still has to count them all
+    for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
+      const int q = q0 + lane;
+      const int64_t base = tg.a0 + 4 * (int64_t)q;
+      const float4 d = ld_span(e, tg, span, q);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        hist_add(hist, cand[c], (key[c] >> 9) & 0x7ffu, lane);
-        const uint32_t pos = wbase + lanes_below(m[c], lane);
-        if (cand[c] && pos < (uint32_t)kSegCap)
-          seg[pos] = make_uint2(key[c], (uint32_t)(base + c - L.offset));
-        wbase += (uint32_t)__popcll(m[c]);
+        const bool valid = (q < span.qend) && (base + c >= tg.lo) && (base + c < tg.hi);
+        const uint32_t key = key_of(comp(d, c));
+        hist_add(hist, valid && (key >> 20) == b1, (key >> 9) & 0x7ffu, lane);
       }
     }
   }
-  const uint32_t gsum = block_sum_u32(ngt, red);         // barriers: s_cn is final afterwards
-  const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
-  if (tid == 0) {
-    ws.gt_cnt[tslot] = gsum;
-    ws.eq_cnt[tslot] = 0;
-    ws.cand_n[slot] = s_cn;
-    if (s_cn > (uint32_t)kSegCap) sp->mode = 1;          // segment overflow: re-read path
-  }
+  __syncthreads();
   hist_flush(hist, ws.hist2 + wl * kHistBins, kHistBins);
 }
 
@@ -257,9 +289,11 @@ __global__ __launch_bounds__(256) void topk_cand_kernel(const Ws ws, int w0) {
 
 __global__ __launch_bounds__(256) void topk_level3_kernel(const Ws ws, int w0) {
   __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3], scratch[4], red[4];
+  __shared__ uint32_t out[3], scratch[4];
   const int w = w0 + blockIdx.y;
   const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
@@ -277,26 +311,27 @@ __global__ __launch_bounds__(256) void topk_level3_kernel(const Ws ws, int w0) {
   }
   for (int b = tid; b < 512; b += kFlatThreads) hist[b] = 0;
   __syncthreads();
-  uint32_t ngt = 0;
-  for_tile_candidates(ws, L, ft, tg, w, blockIdx.x, mode, b1, [&](uint32_t key, uint32_t) {
+  uint32_t n_gt = 0;
+  for_wave_candidates(ws, L, tg, w, blockIdx.x, wave, lane, mode, b1, [&](uint32_t key, bool valid) {
     const uint32_t bb = (key >> 9) & 0x7ffu;
-    if (bb > b2) ++ngt;
-    else if (bb == b2) atomicAdd(&hist[key & 0x1ffu], 1u);
+    n_gt += (uint32_t)__popcll(__ballot(valid && bb > b2));
+    if (valid && bb == b2) atomicAdd(&hist[key & 0x1ffu], 1u);
   });
-  const uint32_t gsum = block_sum_u32(ngt, red);
-  const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
-  if (tid == 0) ws.gt_cnt[tslot] += gsum;
-  uint32_t* gh = ws.hist3 + wl * 512;
-  hist_flush(hist, gh, 512);
+  const int64_t slot4 = ((int64_t)w * ws.n_ftiles + blockIdx.x) * 4 + wave;
+  if (lane == 0) ws.gt4[slot4] += n_gt;
+  __syncthreads();
+  hist_flush(hist, ws.hist3 + wl * 512, 512);
 }
 
 // ---- D ----------------------------------------------------------------------------------------
 
 __global__ __launch_bounds__(256) void topk_count_kernel(const Ws ws, int w0) {
   __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3], scratch[4], red[4];
+  __shared__ uint32_t out[3], scratch[4], tot[2][4];
   const int w = w0 + blockIdx.y;
   const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
@@ -312,35 +347,36 @@ __global__ __launch_bounds__(256) void topk_count_kernel(const Ws ws, int w0) {
   if (ft.start == 0) {
     if (tid == 0) {
       sp->T = T;
-      sp->ktie = k2 - out[1];                            // 1 <= ktie <= entries equal to T
+      sp->ktie = k2 - out[1];                              // 1 <= ktie <= entries equal to T
       sp->alleq = (k2 - out[1] == out[2]) ? 1u : 0u;
     }
     hist_clear_global(ws.hist2 + wl * kHistBins, kHistBins);
   }
-  uint32_t ngt = 0, neq = 0;
-  for_tile_candidates(ws, L, ft, tg, w, blockIdx.x, mode, b1, [&](uint32_t key, uint32_t) {
-    if (((key >> 9) & 0x7ffu) == b2) {                   // bins above b2 were counted in C
-      if (key > T) ++ngt;
-      else if (key == T) ++neq;
-    }
+  uint32_t n_gt = 0, n_eq = 0;
+  for_wave_candidates(ws, L, tg, w, blockIdx.x, wave, lane, mode, b1, [&](uint32_t key, bool valid) {
+    const bool in_b2 = valid && ((key >> 9) & 0x7ffu) == b2;   // bins above b2 were counted in C
+    n_gt += (uint32_t)__popcll(__ballot(in_b2 && key > T));
+    n_eq += (uint32_t)__popcll(__ballot(in_b2 && key == T));
   });
-  const uint32_t gsum = block_sum_u32(ngt, red);
-  const uint32_t esum = block_sum_u32(neq, red);
-  const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
+  const int64_t slot4 = ((int64_t)w * ws.n_ftiles + blockIdx.x) * 4 + wave;
+  if (lane == 0) {
+    const uint32_t g = ws.gt4[slot4] + n_gt;
+    ws.gt4[slot4] = g;
+    ws.eq4[slot4] = n_eq;
+    tot[0][wave] = g;
+    tot[1][wave] = n_eq;
+  }
+  __syncthreads();
   if (tid == 0) {
-    ws.gt_cnt[tslot] += gsum;
-    ws.eq_cnt[tslot] = esum;
+    const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
+    ws.gt_cnt[tslot] = tot[0][0] + tot[0][1] + tot[0][2] + tot[0][3];
+    ws.eq_cnt[tslot] = tot[1][0] + tot[1][1] + tot[1][2] + tot[1][3];
   }
 }
 
 // ---- E ----------------------------------------------------------------------------------------
 
-// A wave owns a contiguous quarter of the tile, so ranks and payload positions advance by
-// wave-uniform running counters; index order = (wave, iteration, lane, component).
-constexpr int kWaveQuadIters = ((kTile / 4 + 1 + 3) / 4 + kWave - 1) / kWave;   // 9
-
 __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t wcnt[2][4];
   __shared__ uint32_t red[4];
   const int w = w0 + blockIdx.y;
   const int tid = threadIdx.x;
@@ -349,21 +385,13 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
+  const WaveSpan span = wave_span(tg, wave);
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   const SelState* sp = ws.sel + wl;
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-  const int qw = (tg.nquads + 3) >> 2;                   // quads per wave
-  const int qbeg = wave * qw;
-  const int qend = min(qbeg + qw, tg.nquads);
-  float4 d[kWaveQuadIters];
-#pragma unroll
-  for (int j = 0; j < kWaveQuadIters; ++j) {
-    const int q = qbeg + j * kWave + lane;
-    d[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (q < qend) d[j] = ld_quad(e, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi);
-  }
+  float4 cur = ld_span(e, tg, span, span.qbeg + lane);
   const uint32_t T = sp->T, ktie = sp->ktie, alleq = sp->alleq, kk = sp->k;
-  // ties and selected entries in the tiles before mine.  The tie quota is used up in index
+  // ties and selected entries before my wave's quarter.  The tie quota is used up in index
   // order, so everything before a point took min(ktie, ties before that point) ties in total.
   const int my_t = ft.start >> kTileShift;
   const int64_t tbase = (int64_t)w * ws.tile_stride + L.toff;
@@ -379,41 +407,24 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
     if (my_t == L.ntiles - 1) ws.sel_off[tbase + L.ntiles] = kk;
   }
   if (ft.start == 0) hist_clear_global(ws.hist3 + wl * 512, 512);
-
-  // pass 1: entries above T and equal to T in my wave's quarter
-  uint32_t n_gt = 0, n_eq = 0;
-#pragma unroll
-  for (int j = 0; j < kWaveQuadIters; ++j) {
-    const int q = qbeg + j * kWave + lane;
-    const int64_t base = tg.a0 + 4 * (int64_t)q;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const bool valid = (q < qend) && (base + c >= tg.lo) && (base + c < tg.hi);
-      const uint32_t key = key_of(comp(d[j], c));
-      n_gt += (uint32_t)__popcll(__ballot(valid && key > T));
-      n_eq += (uint32_t)__popcll(__ballot(valid && key == T));
-    }
-  }
-  if (lane == 0) { wcnt[0][wave] = n_eq; wcnt[1][wave] = n_gt; }
-  __syncthreads();
+  const int64_t slot4 = ((int64_t)w * ws.n_ftiles + blockIdx.x) * 4;
   uint32_t eq_run = eq_base, gt_before = gt_base;
-  for (int v = 0; v < wave; ++v) { eq_run += wcnt[0][v]; gt_before += wcnt[1][v]; }
+  for (int v = 0; v < wave; ++v) { eq_run += ws.eq4[slot4 + v]; gt_before += ws.gt4[slot4 + v]; }
   uint32_t pos_run = gt_before + min(ktie, eq_run);
 
-  // pass 2: ranks of the ties, positions of the selected entries, writes
   int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
   float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
-#pragma unroll
-  for (int j = 0; j < kWaveQuadIters; ++j) {
-    const int q = qbeg + j * kWave + lane;
+  for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
+    const int q = q0 + lane;
+    const float4 nxt = ld_span(e, tg, span, q + kWave);
     const int64_t base = tg.a0 + 4 * (int64_t)q;
     bool sel[4];
     uint32_t key[4];
     bool valid[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      valid[c] = (q < qend) && (base + c >= tg.lo) && (base + c < tg.hi);
-      key[c] = key_of(comp(d[j], c));
+      valid[c] = (q < span.qend) && (base + c >= tg.lo) && (base + c < tg.hi);
+      key[c] = key_of(comp(cur, c));
     }
     if (alleq) {
 #pragma unroll
@@ -442,19 +453,22 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
       below += lanes_below(m, lane);
       total += (uint32_t)__popcll(m);
     }
-    uint32_t pos = pos_run + below;
+    if (total != 0) {
+      uint32_t pos = pos_run + below;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      if (sel[c]) {
-        if (pos < kk) {                          // always true for consistent state
-          pidx[pos] = (int32_t)(base + c - L.offset);
-          pval[pos] = comp(d[j], c);
+      for (int c = 0; c < 4; ++c) {
+        if (sel[c]) {
+          if (pos < kk) {                          // always true for consistent state
+            pidx[pos] = (int32_t)(base + c - L.offset);
+            pval[pos] = comp(cur, c);
+          }
+          e[base + c] = 0.f;
+          ++pos;
         }
-        e[base + c] = 0.f;
-        ++pos;
       }
+      pos_run += total;
     }
-    pos_run += total;
+    cur = nxt;
   }
 }
 

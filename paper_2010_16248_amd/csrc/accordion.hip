@@ -44,7 +44,7 @@ struct Plan {
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
   Region r_A, r_e, r_norm_part;
   Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean;
-  Region r_hist1, r_hist2, r_hist3, r_done, r_sel, r_cand, r_candn, r_gt, r_eq, r_seloff, r_eqoff, r_payidx, r_payval;
+  Region r_hist1, r_hist2, r_hist3, r_sel, r_cand, r_candn, r_gt4, r_eq4, r_gt, r_eq, r_seloff, r_payidx, r_payval;
   int64_t total_bytes = 0;
 };
 
@@ -198,14 +198,14 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     reg(p.r_hist1, 4 * (int64_t)kHistBins * nl * W);
     reg(p.r_hist2, 4 * (int64_t)kHistBins * nl * W);
     reg(p.r_hist3, 4 * (int64_t)512 * nl * W);
-    reg(p.r_done, 4 * (int64_t)4 * nl * W);
     reg(p.r_sel, (int64_t)sizeof(SelState) * nl * W);
     reg(p.r_cand, 8 * (int64_t)kSegCap * ntile * W);
-    reg(p.r_candn, 4 * ntile * W);
+    reg(p.r_candn, 4 * 4 * ntile * W);
+    reg(p.r_gt4, 4 * 4 * ntile * W);
+    reg(p.r_eq4, 4 * 4 * ntile * W);
     reg(p.r_gt, 4 * p.tile_stride * W);
     reg(p.r_eq, 4 * p.tile_stride * W);
     reg(p.r_seloff, 4 * p.tile_stride * W);
-    reg(p.r_eqoff, 4 * p.tile_stride * W);
     reg(p.r_payidx, 4 * p.pay_stride * W);
     reg(p.r_payval, 4 * p.pay_stride * W);
   }
@@ -458,14 +458,14 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.hist1 = at<uint32_t>(c, p.r_hist1);
     ws.hist2 = at<uint32_t>(c, p.r_hist2);
     ws.hist3 = at<uint32_t>(c, p.r_hist3);
-    ws.done = at<uint32_t>(c, p.r_done);
     ws.sel = at<SelState>(c, p.r_sel);
     ws.cand = at<uint2>(c, p.r_cand);
     ws.cand_n = at<uint32_t>(c, p.r_candn);
+    ws.gt4 = at<uint32_t>(c, p.r_gt4);
+    ws.eq4 = at<uint32_t>(c, p.r_eq4);
     ws.gt_cnt = at<uint32_t>(c, p.r_gt);
     ws.eq_cnt = at<uint32_t>(c, p.r_eq);
     ws.sel_off = at<uint32_t>(c, p.r_seloff);
-    ws.eq_off = at<uint32_t>(c, p.r_eqoff);
     ws.pay_idx = at<int32_t>(c, p.r_payidx);
     ws.pay_val = at<float>(c, p.r_payval);
     ws.pay_stride = p.pay_stride;
