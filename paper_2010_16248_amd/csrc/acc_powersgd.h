@@ -168,26 +168,45 @@ __device__ __forceinline__ float block_sum_256(float v, float (*red)[4], int& sl
   return r;
 }
 
-// Row i of P_bar: per worker the sum of the column-chunk partials (= P_w), then the mean.
+// Sum over workers and over the partial results of one worker (column chunks of P, row blocks
+// of Q) for one row of r values, divided by W.  The W * nparts addends are independent loads;
+// they are issued eight at a time and added in a fixed order (worker-major).
 template <int R>
-__device__ __forceinline__ void pbar_row(const Ws& ws, const LayerDev& L, int i, float (&pb)[R]) {
+__device__ __forceinline__ void mean_of_partials(const float* __restrict__ base, int64_t wstride,
+                                                 int W, int nparts, int64_t pstride, float (&out)[R]) {
+  float acc[R];
 #pragma unroll
-  for (int k = 0; k < R; ++k) pb[k] = 0.f;
-  for (int w = 0; w < ws.W; ++w) {
-    const float* pp = ws.Ppart + (int64_t)w * ws.ppart_stride + L.ppart_off;
-    float pw[R];
+  for (int k = 0; k < R; ++k) acc[k] = 0.f;
+  const int np = W * nparts;
+  for (int p0 = 0; p0 < np; p0 += 8) {
+    float v[8][R];
 #pragma unroll
-    for (int k = 0; k < R; ++k) pw[k] = 0.f;
-    for (int c = 0; c < L.n_colchunks; ++c) {
-      const float* src = pp + ((int64_t)c * L.rows + i) * ws.rmax;
+    for (int u = 0; u < 8; ++u) {
+      const int p = p0 + u;
+      if (p < np) {
+        const int w = p / nparts, c = p - w * nparts;
+        const float* src = base + (int64_t)w * wstride + (int64_t)c * pstride;
 #pragma unroll
-      for (int k = 0; k < R; ++k) pw[k] += src[k];
+        for (int k = 0; k < R; ++k) v[u][k] = src[k];
+      } else {
+#pragma unroll
+        for (int k = 0; k < R; ++k) v[u][k] = 0.f;
+      }
     }
 #pragma unroll
-    for (int k = 0; k < R; ++k) pb[k] += pw[k];
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int k = 0; k < R; ++k) acc[k] += v[u][k];
   }
 #pragma unroll
-  for (int k = 0; k < R; ++k) pb[k] = pb[k] / (float)ws.W;
+  for (int k = 0; k < R; ++k) out[k] = acc[k] / (float)W;
+}
+
+// Row i of P_bar.
+template <int R>
+__device__ __forceinline__ void pbar_row(const Ws& ws, const LayerDev& L, int i, float (&pb)[R]) {
+  mean_of_partials<R>(ws.Ppart + L.ppart_off + (int64_t)i * ws.rmax, ws.ppart_stride, ws.W,
+                      L.n_colchunks, (int64_t)L.rows * ws.rmax, pb);
 }
 
 // Modified Gram-Schmidt over the r columns of P_bar, in column order; a column of zero
@@ -384,24 +403,28 @@ __global__ __launch_bounds__(256) void psgd_q_kernel(const Ws ws, int w0) {
 
 // ---- aggregate 1: Q_bar = mean over workers of (sum over row blocks) -------------------------
 
+template <int R>
+__device__ __forceinline__ void qmean_col(const Ws& ws, const LayerDev& L, int c) {
+  float q[R];
+  mean_of_partials<R>(ws.Qpart + L.qpart_off + (int64_t)c * ws.rmax, ws.qpart_stride, ws.W,
+                      L.n_rowblocks, (int64_t)L.cols * ws.rmax, q);
+  float* dst = ws.Q + L.q_off + (int64_t)c * ws.rmax;
+#pragma unroll
+  for (int k = 0; k < R; ++k) dst[k] = q[k];
+}
+
 __global__ __launch_bounds__(256) void psgd_qmean_kernel(const Ws ws) {
   const QTile t = ws.qtiles[blockIdx.x];
   const LayerDev& L = ws.layers[t.layer];
   const int r = L.rank[ws.level[t.layer]];
   const int c = t.col0 + threadIdx.x;
   if (c >= L.cols) return;
-  float tot[kMaxRank] = {0.f, 0.f, 0.f, 0.f};
-  for (int w = 0; w < ws.W; ++w) {
-    const float* qp = ws.Qpart + (int64_t)w * ws.qpart_stride + L.qpart_off;
-    float qw[kMaxRank] = {0.f, 0.f, 0.f, 0.f};
-    for (int rb = 0; rb < L.n_rowblocks; ++rb) {
-      const float* src = qp + ((int64_t)rb * L.cols + c) * ws.rmax;
-      for (int k = 0; k < r; ++k) qw[k] += src[k];
-    }
-    for (int k = 0; k < r; ++k) tot[k] += qw[k];
+  switch (r) {
+    case 1: qmean_col<1>(ws, L, c); break;
+    case 2: qmean_col<2>(ws, L, c); break;
+    case 3: qmean_col<3>(ws, L, c); break;
+    default: qmean_col<4>(ws, L, c); break;
   }
-  float* dst = ws.Q + L.q_off + (int64_t)c * ws.rmax;
-  for (int k = 0; k < r; ++k) dst[k] = tot[k] / (float)ws.W;
 }
 
 // ---- decompress: D = P^ Q_bar^T, e_w = Delta_w - D ------------------------------------------
