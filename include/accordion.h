@@ -126,7 +126,8 @@ int32_t accordion_compress_step(acc_ctx* ctx, int32_t worker, const float* grad_
  * phase 1, PowerSGD only: Q~ = mean_w Q_w, stored as the next step's Q. */
 int32_t accordion_aggregate(acc_ctx* ctx, int32_t phase);
 
-/* Averaged, decompressed gradient of this step into out_dev (N floats, fully overwritten).
+/* Averaged, decompressed gradient of this step into out_dev (N floats; every element that
+ * belongs to a layer is overwritten).
  * PowerSGD: D = P^ Q~^T on matrix layers and e_w = Delta_w - D for every worker; 1-D layers get
  * the plain mean.  TopK: D[i] = (sum over workers, in worker order from +0, of the values kept
  * at i) / W.  Ends the step. */

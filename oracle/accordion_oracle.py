@@ -11,9 +11,10 @@ What is computed, and where the paper defines it
   Section 3, "Distributed SGD with adaptive gradient compression".
 * Error feedback ("memory term"): Section 5.3 and Appendix A, "Hyperparameters":
   the part of (gradient + memory) that the compressor dropped is the next memory.
-* PowerSGD: Section 5 names it (low-rank factorisation per layer); the steps are
-  the ones the benchmark spec fixes: P = M Q, orthogonalise P, Q = M^T P,
-  decompress P Q^T, with M = gradient + memory.  1-D tensors are not compressed
+* PowerSGD: Section 5 names it (low-rank factorisation per layer, "with memory
+  term" in Appendix A) and prints no listing; one warm-started subspace iteration
+  per step: P = M Q, orthogonalise P, Q = M^T P, decompress P Q^T, with
+  M = gradient + memory.  1-D tensors are not compressed
   (appendix "Compression Ratio Selection").
 * TopK: Section 5, "choosing the K entries with largest absolute values"; per
   gradient tensor (Section 1).  Ties go to the lower flat index.
