@@ -30,7 +30,10 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this file (summaries under profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# Key: (workload, W, dominant kernel).
+MEASURED_TRAFFIC_BYTES = {
+    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 629287817,    # profiles/hbm_traffic_resnet18_topk.md
+}
 
 # scale of the gradients per window, cycled: makes the norm ratio cross eta = 0.5 so that both
 # levels are used while timing (decisions: critical, not, critical, not, ...)
@@ -51,6 +54,8 @@ def parse():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events in the timed region")
     ap.add_argument("--fixed-level", type=int, default=-1, help="0/1: never switch, use this level")
+    ap.add_argument("--probe-mib", type=int, default=1024,
+                    help="size of the plain-copy probe (MiB read and MiB written per launch); 0: skip")
     return ap.parse_args()
 
 
@@ -142,6 +147,27 @@ def main():
                               np.full(gpu.n_layers, args.fixed_level, np.int32))
         gpu.set_state(blob)
 
+    # plain copy of known size: the copy bandwidth this machine reaches, and the kernel that calibrates
+    # FETCH_SIZE / WRITE_SIZE in a rocprofv3 --pmc run of this file
+    copy_probe = None
+    if args.probe_mib > 0:
+        n = args.probe_mib * (1 << 20) // 4
+        src = torch.full((n,), 1.0, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            B.probe_copy(dst, src)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        ev0.record()
+        for _ in range(reps):
+            B.probe_copy(dst, src)
+        ev1.record()
+        torch.cuda.synchronize()
+        us = ev0.elapsed_time(ev1) * 1e3 / reps
+        copy_probe = {"bytes_read": 4 * n, "bytes_written": 4 * n, "avg_us": round(us, 2),
+                      "GB/s": round(8.0 * n / us / 1e3, 1)}
+        del src, dst
+
     state = {"step": 0}
 
     def one_step():
@@ -185,7 +211,7 @@ def main():
         ms, n = prof[dom]
         avg_s = ms * 1e-3 / n
         ach = algorithmic_bytes_dominant(N, W) / avg_s / 1e9
-        traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, W))
+        traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, W, dom))
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
                     "avg_kernel_us": round(avg_s * 1e6, 2),
@@ -208,6 +234,7 @@ def main():
                    "levels_switch": args.fixed_level < 0, "kernel_events_in_timed_region": use_events},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "copy_probe": copy_probe,
         "kernels": kernels,
         "payload_words_last_step": words_last,
         "critical_layers_at_end": int(levels.sum()),

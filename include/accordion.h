@@ -186,6 +186,14 @@ int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
 int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
 const char* accordion_stage_name(int32_t stage);
 
+/* --- measurement aid (not part of the paper's method) ---------------------------------------
+ * Plain streaming copy dst_dev[0..n) = src_dev[0..n) (n floats, a positive multiple of 4; both
+ * DEVICE pointers, 16-byte aligned, not overlapping) enqueued on hip_stream.  It moves exactly
+ * 4n bytes in and 4n bytes out, which calibrates the memory counters of a profiler run and
+ * gives the copy bandwidth the memory system reaches.  Needs no context.
+ * Errors: ACC_EINVAL, ACC_EHIP (message via accordion_last_error(NULL)). */
+int32_t accordion_probe_copy(float* dst_dev, const float* src_dev, int64_t n, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -54,6 +54,7 @@ EXPORTS = [
     "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
     "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
+    "accordion_probe_copy",
 ]
 ACC_N_STAGES = 15
 
@@ -88,6 +89,7 @@ def load_library() -> C.CDLL:
         "accordion_set_state": [vp, vp, C.c_size_t],
         "accordion_set_profiling": [vp, i32],
         "accordion_get_profile": [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)],
+        "accordion_probe_copy": [vp, vp, i64, vp],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -140,6 +142,15 @@ def accordion_workspace_bytes(cfg: acc_config) -> int:
     out = C.c_size_t(0)
     _check(lib, None, lib.accordion_workspace_bytes(C.byref(cfg), C.byref(out)))
     return int(out.value)
+
+
+def probe_copy(dst, src) -> None:
+    """accordion_probe_copy on two device tensors of equal size, on torch's current stream."""
+    import torch
+    lib = load_library()
+    stream = torch.cuda.current_stream().cuda_stream
+    _check(lib, None, lib.accordion_probe_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
+                                               src.numel(), C.c_void_p(stream)))
 
 
 class Accordion:

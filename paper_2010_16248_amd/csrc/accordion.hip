@@ -215,6 +215,25 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
 
 }  // namespace
 
+// Plain streaming copy used to calibrate hardware counters and to measure the copy bandwidth
+// the memory system reaches: 256 threads, four 16-byte groups per thread, loads before stores.
+constexpr int kProbeQuadsPerThread = 4;
+__global__ __launch_bounds__(256) void probe_copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src,
+                                                         int64_t nquads) {
+  const int64_t base = (int64_t)blockIdx.x * (256 * kProbeQuadsPerThread) + threadIdx.x;
+  float4 v[kProbeQuadsPerThread];
+#pragma unroll
+  for (int i = 0; i < kProbeQuadsPerThread; ++i) {
+    const int64_t q = base + (int64_t)i * 256;
+    if (q < nquads) v[i] = src[q];
+  }
+#pragma unroll
+  for (int i = 0; i < kProbeQuadsPerThread; ++i) {
+    const int64_t q = base + (int64_t)i * 256;
+    if (q < nquads) dst[q] = v[i];
+  }
+}
+
 enum Stage {
   ST_psgd_ef_p_kernel = 0, ST_psgd_orth_kernel, ST_psgd_q_kernel, ST_psgd_qmean_kernel,
   ST_psgd_decomp_kernel, ST_topk_ef_hist_kernel, ST_topk_cand_kernel, ST_topk_level3_kernel,
@@ -772,6 +791,20 @@ int32_t accordion_get_profile(acc_ctx* c, int32_t stage, double* total_ms, int64
 
 const char* accordion_stage_name(int32_t stage) {
   return (stage >= 0 && stage < ST_COUNT) ? kStageNames[stage] : nullptr;
+}
+
+int32_t accordion_probe_copy(float* dst_dev, const float* src_dev, int64_t n, void* hip_stream) {
+  if (!dst_dev || !src_dev) return fail(g_init_error, ACC_EINVAL, "probe_copy: pointer is NULL");
+  if (misaligned(dst_dev) || misaligned(src_dev)) return fail(g_init_error, ACC_EINVAL, "probe_copy: pointer is not 16-byte aligned");
+  if (n <= 0 || n % 4 != 0 || n > (int64_t(1) << 36)) return fail(g_init_error, ACC_EINVAL, "probe_copy: n must be a positive multiple of 4");
+  const int64_t nquads = n / 4;
+  const int64_t per_block = 256 * kProbeQuadsPerThread;
+  const int64_t blocks = (nquads + per_block - 1) / per_block;
+  if (blocks > (int64_t(1) << 31) - 1) return fail(g_init_error, ACC_EINVAL, "probe_copy: n too large");
+  hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     reinterpret_cast<float4*>(dst_dev), reinterpret_cast<const float4*>(src_dev), nquads);
+  if (hipGetLastError() != hipSuccess) return fail(g_init_error, ACC_EHIP, "probe_copy: launch failed");
+  return ACC_OK;
 }
 
 }  // extern "C"
