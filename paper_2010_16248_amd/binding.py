@@ -56,7 +56,7 @@ EXPORTS = [
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
     "accordion_probe_copy",
 ]
-ACC_N_STAGES = 15
+ACC_N_STAGES = 17
 
 
 def load_library() -> C.CDLL:

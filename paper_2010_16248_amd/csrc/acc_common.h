@@ -13,8 +13,9 @@ constexpr int kQuadIters = (kTile / 4 + 1 + kFlatThreads - 1) / kFlatThreads;  /
 constexpr int kMatRows = 64;             // matrix tile: 64 rows x 256 columns
 constexpr int kMatCols = 256;
 constexpr int kHistBins = 2048;          // 11 key bits per radix level
-constexpr int kSubCap = 256;             // candidate slots per wave quarter of a flat tile (TopK)
-constexpr int kSegCap = 4 * kSubCap;    // candidate slots per flat tile
+constexpr int kSubCap = 256;             // staged keys per guessed bin and wave quarter of a flat tile (TopK)
+// a wave quarter has at most ceil((kTile / 4 + 1) / 4) 16-byte groups: iterations of 64 lanes
+constexpr int kSpanIters = ((kTile / 4 + 1 + 3) / 4 + kWave - 1) / kWave;   // 9
 constexpr int kMaxW = 32;
 constexpr int kMaxRank = 4;
 
@@ -30,8 +31,9 @@ struct LayerDev {
   int32_t n_rowblocks;   // ceil(rows / kMatRows)
   int32_t tile0;         // first flat tile of the layer
   int32_t ntiles;        // number of flat tiles
-  int32_t toff;          // slot of tile 0 in the per-worker tile arrays (tile0 + layer index)
-  int32_t pad0;
+  int32_t pad0, pad1;
+  int64_t qoff;          // slot of the layer's first wave quarter in the per-worker quarter arrays
+                         // (4 * tile0 + layer index: one spare slot per layer for the totals)
   int64_t q_off;         // into Q      (cols * rmax floats)
   int64_t p_off;         // into Phat   (rows * rmax floats)
   int64_t ppart_off;     // into one worker's P partials (n_colchunks * rows * rmax)
@@ -47,17 +49,17 @@ struct QTile { int32_t layer, col0; };
 // Per (worker, layer) state of the TopK selection of the current step.
 struct SelState {
   uint32_t b1;        // level-1 bin (key bits 30..20) that holds the k-th largest key
-  uint32_t above1;    // entries in bins above b1 (all selected)
-  uint32_t c1;        // entries in bin b1 (candidates)
-  uint32_t mode;      // 0: candidates are in the tiles' segments; 1: a segment overflowed,
-                      //    candidates are re-read from Delta
-  uint32_t b2;        // level-2 bin (key bits 19..9) within b1
-  uint32_t above2;    // candidates in level-2 bins above b2
+  uint32_t need2;     // entries still to be taken from bin b1
+  uint32_t mode;      // 0: b1 is one of the guessed bins (or decided); 1: the guess missed
+  uint32_t side;      // half of the quarter segments that holds the keys of b1
+  uint32_t b2;        // level-2 bin (key bits 19..14) within b1
+  uint32_t need3;     // entries still to be taken from bin (b1, b2)
+  uint32_t zeros;     // exact zeros of the layer (filled in when b1 == 0)
+  uint32_t pad;
+  uint32_t k;         // kept count used by this step
   uint32_t T;         // exact threshold key (the k-th largest)
   uint32_t ktie;      // how many entries with key == T are selected (lowest indices first)
   uint32_t alleq;     // 1: every entry with key == T is selected
-  uint32_t k;         // kept count used by this step
-  uint32_t pad[2];
 };
 
 struct GradPtrs { const float* p[kMaxW]; };
@@ -89,17 +91,19 @@ struct Ws {
   float* vecmean;
   // TopK
   uint32_t* hist1;             // W x L x kHistBins, zero between steps
-  uint32_t* hist2;             // W x L x kHistBins, zero between steps
-  uint32_t* hist3;             // W x L x 512, zero between steps
+  uint32_t* t2;                // W x n_ftiles x 128: per tile, level-2 counts of the two guessed bins
+  uint32_t* qlist;             // W x q_stride x kQListCap: per quarter, its keys in bin (b1, b2)
   SelState* sel;               // W x L
-  uint2* cand;                 // W x n_ftiles x 4 x kSubCap candidate slots (key, layer-local index)
-  uint32_t* cand_n;            // W x n_ftiles x 4 candidates found per wave quarter
-  uint32_t* gt4;               // W x n_ftiles x 4 entries above the threshold per wave quarter
-  uint32_t* eq4;               // W x n_ftiles x 4 entries equal to the threshold per wave quarter
-  uint32_t* gt_cnt;            // W x tile_stride, per tile
-  uint32_t* eq_cnt;            // W x tile_stride, per tile
-  uint32_t* sel_off;           // W x tile_stride, payload position of a tile's first entry
-  int64_t tile_stride;
+  uint32_t* miss_any;          // W: some multi-tile layer of the worker missed its guessed bins this step
+  uint32_t* guess;             // W x L x 2 (level): lower of the two level-1 bins staged by pass A
+  uint4* qinfo;                // W x q_stride: per wave quarter {entries above the staged bins,
+                               //   keys of the lower bin, keys of the upper bin, exact zeros}
+  uint32_t* seg;               // W x q_stride x 2 x kSubCap staged keys
+  uint32_t* gtq;               // W x q_stride entries above the threshold per quarter
+  uint32_t* eqq;               // W x q_stride keys in bin (b1, b2) / entries equal to the threshold per quarter
+  uint32_t* gtpre;             // W x q_stride exclusive prefix of gtq within the layer (+ total)
+  uint32_t* eqpre;             // W x q_stride exclusive prefix of eqq within the layer (+ total)
+  int64_t q_stride;
   int32_t* pay_idx;  float* pay_val;  int64_t pay_stride;
   int64_t N;
   int32_t W, L, rmax;
@@ -162,8 +166,13 @@ __device__ __forceinline__ uint32_t wave_incl_suffix_u32(uint32_t v, int lane) {
   return v;
 }
 
-__device__ __forceinline__ uint32_t lanes_below(uint64_t mask, int lane) {
-  return (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+// Lane mask of a predicate, taken straight from the compare (no round trip through a register
+// holding 0 / 1).
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+// Number of set bits of mask in the lanes below the calling lane.
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask, int /*lane*/) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
 __device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7fffffffu; }
@@ -195,6 +204,23 @@ __device__ __forceinline__ void st_quad(float* __restrict__ p, int64_t base, int
   if (base + 3 >= lo && base + 3 < hi) p[base + 3] = v.w;
 }
 
+// Access to 16-byte group q of a tile.  AL (a workgroup-uniform property of the tile): the tile
+// starts on a 16-byte boundary and holds a whole number of groups, so no element needs a mask.
+template <bool AL>
+__device__ __forceinline__ float4 ldq(const float* __restrict__ p, int64_t a0, int64_t lo, int64_t hi,
+                                      int q, bool in) {
+  if (!in) return make_float4(0.f, 0.f, 0.f, 0.f);
+  if (AL) return *reinterpret_cast<const float4*>(p + a0 + 4 * (int64_t)q);
+  return ld_quad(p, a0 + 4 * (int64_t)q, lo, hi);
+}
+
+template <bool AL>
+__device__ __forceinline__ void stq(float* __restrict__ p, int64_t a0, int64_t lo, int64_t hi, int q,
+                                    float4 v) {
+  if (AL) *reinterpret_cast<float4*>(p + a0 + 4 * (int64_t)q) = v;
+  else st_quad(p, a0 + 4 * (int64_t)q, lo, hi, v);
+}
+
 __device__ __forceinline__ float comp(const float4& v, int c) {
   return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
 }
@@ -204,6 +230,7 @@ struct TileGeom {
   int64_t lo, hi;   // the tile's elements: [lo, hi)
   int64_t a0;       // lo rounded down to a multiple of 4
   int32_t nquads;   // 16-byte groups that intersect [lo, hi)
+  bool aligned;     // lo and hi are multiples of 4: every group is whole
 };
 
 __device__ __forceinline__ TileGeom tile_geom(const LayerDev& L, const FlatTile& t) {
@@ -212,6 +239,7 @@ __device__ __forceinline__ TileGeom tile_geom(const LayerDev& L, const FlatTile&
   g.hi = g.lo + t.count;
   g.a0 = g.lo & ~int64_t(3);
   g.nquads = (int32_t)((g.hi - g.a0 + 3) >> 2);
+  g.aligned = ((g.lo | g.hi) & 3) == 0;
   return g;
 }
 

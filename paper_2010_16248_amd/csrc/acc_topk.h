@@ -1,154 +1,96 @@
 // TopK kernels: exact per-layer selection of the k entries with the largest |Delta|
-// (ties: lower flat index) by a three-level radix select on the 31 magnitude bits
-// (11 + 11 + 9).  Every kernel is tile-parallel (one workgroup per 8192-element tile and
-// worker).  The per-(worker, layer) decisions (which bin holds the k-th largest) are
-// recomputed by every workgroup of the layer from the layer's global histogram at the start
-// of the next kernel: that costs an 8 KB L2 read per workgroup and needs neither an extra
-// launch nor a device-scope fence (which on this multi-die part writes back the whole L2).
+// (ties: lower flat index) by a radix select on the 31 magnitude bits, organised so that Delta
+// is streamed twice per step: once when it is formed and once when the selected entries are
+// written out.  Key bits: level 1 = 30..20 (2048 bins), level 2 = 19..14 (64), level 3 = 13..6
+// (256), level 4 = 5..0 (64).
 //
-//   A  topk_ef_hist      Delta = g + e (in place), A += g (worker 0), level-1 histogram
-//                        (key bits 30..20) per (worker, layer)
-//   B  topk_cand         [bin b1 of the k-th largest]  count of entries above b1 per tile;
-//                        entries in b1 (candidates) go to the tile's segment as (key, index);
-//                        level-2 histogram of the candidates (bits 19..9)
-//   C  topk_level3       [bin b2]  candidates above b2 counted per tile; level-3 histogram
-//                        (bits 8..0) of those in b2
-//   D  topk_count        [threshold key T, tie quota]  per tile: candidates above T and
-//                        candidates equal to T
-//   E  topk_compact      [sums over the preceding tiles]  ordered compaction of the selected
-//                        entries into the payload (index ascending), zeroing them in e
-//   K6 topk_sparse_mean  dense mean of the W payloads
+//   A   topk_ef_hist   Delta = g + e (in place), A += g (worker 0), level-1 histogram per
+//                      (worker, layer).  The level-1 bin b1 that will hold the k-th largest key is
+//                      not known yet, so the pass stages the keys of two GUESSED bins (the bin
+//                      the previous step at this level ended in and the neighbour on the side
+//                      its threshold was closer to) per wave quarter of a tile, counts the
+//                      entries above them and the exact zeros, and writes the tile's level-2
+//                      counts of the two guessed bins.
+//   P12 topk_pick12    one workgroup per (worker, layer): b1 from the histogram; if it is one
+//                      of the guessed bins, b2 from the sum of the tiles' level-2 counts.
+//                      Layers of a single tile are decided here completely, from Delta.
+//   C3  topk_count3    one workgroup per tile: per quarter the entries above bin (b1, b2); the
+//                      keys inside (b1, b2) go to a per-layer list with their quarter.
+//   P3  topk_pick3     per (worker, layer): levels 3 and 4 on the list, threshold key T and tie
+//                      quota; the listed keys are added to their quarters' counts; exclusive
+//                      prefix over the quarters = payload position of every quarter.
+//                      A layer whose guess missed (first step, level switch, shifted
+//                      distribution) or whose list overflowed (huge tie class) is decided here
+//                      by sweeps of one workgroup over Delta / the segments (correct, slow).
+//   E   topk_compact   ordered compaction of the selected entries into the payload (index
+//                      ascending), zeroing them in e.  The batched form loops over the workers
+//                      and also forms the dense mean of the kept values in registers.
+//   K6  topk_sparse_mean  dense mean of the W payloads (call-by-call path).
 //
-// Cross-workgroup combination is by integer atomics and fixed-order sums only, so every
-// output is bit-reproducible.  A wave quarter's segment holds kSubCap candidates; if a quarter
-// has more (huge tie classes: zeros, constants) the layer falls back to re-reading Delta in C
-// and D.
+// The guess only decides which path is taken, never the result.  Cross-workgroup combination
+// is by integer atomics and fixed-order sums only, so every output is bit-reproducible.
 #pragma once
 #include "acc_common.h"
 
 namespace acc {
 
+constexpr uint32_t kNoGuess = 0xffffffffu;
+constexpr int kPickThreads = 1024;
+constexpr int kPickWaves = kPickThreads / kWave;
+constexpr int kQListCap = 16;            // keys of bin (b1, b2) listed per wave quarter
+constexpr int kL2Bins = 64;              // level 2: key bits 19..14
+constexpr int kSub2 = 2 * kL2Bins;       // a tile's level-2 counts of the two guessed bins
+__device__ __forceinline__ uint32_t bin2_of(uint32_t key) { return (key >> 14) & 0x3fu; }
+__device__ __forceinline__ uint32_t bin3_of(uint32_t key) { return (key >> 6) & 0xffu; }
+__device__ __forceinline__ uint32_t bin4_of(uint32_t key) { return key & 0x3fu; }
+
 __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// LDS histogram add with a fast path for a wave whose valid lanes all hit one bin.
-__device__ __forceinline__ void hist_add(uint32_t* hist, bool valid, uint32_t bin, int lane) {
-  const uint32_t b = valid ? bin : 0xffffffffu;
-  const uint32_t fb = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
-  const uint64_t act = __ballot(valid);
-  const uint64_t same = __ballot(valid && b == fb);
-  if (act != 0 && same == act) {
-    if (lane == (int)__builtin_ctzll(act)) atomicAdd(&hist[fb], (uint32_t)__popcll(act));
-  } else if (valid) {
-    atomicAdd(&hist[bin], 1u);
-  }
-}
-
-__device__ __forceinline__ void hist_flush(const uint32_t* hist, uint32_t* gh, int nbins) {
-  for (int b = threadIdx.x; b < nbins; b += kFlatThreads) {
-    const uint32_t h = hist[b];
-    if (h) atomicAdd(&gh[b], h);
-  }
-}
-
-// Copies a layer's global histogram into LDS, zero-padded to kHistBins.  Ends with a barrier.
-__device__ __forceinline__ void hist_load(uint32_t* hist, const uint32_t* gh, int nbins) {
-  for (int b = threadIdx.x; b < kHistBins; b += kFlatThreads) hist[b] = (b < nbins) ? gh[b] : 0u;
-  __syncthreads();
-}
-
-__device__ __forceinline__ void hist_clear_global(uint32_t* gh, int nbins) {
-  for (int b = threadIdx.x; b < nbins; b += kFlatThreads) gh[b] = 0u;
+// LDS histogram add of the non-zero keys; exact zeros (the one tie class that is common in real
+// gradients) are counted per wave by the caller and added to bin 0 once.
+__device__ __forceinline__ void hist_add(uint32_t* hist, bool valid_nonzero, uint32_t bin) {
+  if (valid_nonzero) atomicAdd(&hist[bin], 1u);
 }
 
 // hist: kHistBins counts in LDS.  Finds the largest bin b with count(bins >= b) >= k.
-// Result in out[0..2] (LDS, zeroed by the caller before a barrier): bin, entries above the
-// bin, entries in the bin.  256 threads; two barriers; every thread calls it.
+// Result in out[0..2] (LDS): bin, entries above the bin, entries in the bin.  Every thread of
+// the workgroup calls it (two barriers); threads 0..255 own eight bins each.
 __device__ __forceinline__ void pick_bin(const uint32_t* hist, uint32_t k, uint32_t* out,
                                          uint32_t* scratch) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const bool owner = tid < 256;
   uint32_t h[8];
   uint32_t part = 0;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) { h[i] = hist[tid * 8 + i]; part += h[i]; }
+  for (int i = 0; i < 8; ++i) { h[i] = owner ? hist[tid * 8 + i] : 0u; part += h[i]; }
   const uint32_t suf = wave_incl_suffix_u32(part, lane);
-  if (lane == 0) scratch[wave] = suf;            // wave total
+  if (owner && lane == 0) scratch[wave] = suf;   // wave total
+  if (tid < 3) out[tid] = 0;
   __syncthreads();
-  uint32_t run = suf - part;                     // entries in bins of later threads of my wave
-  for (int v = wave + 1; v < 4; ++v) run += scratch[v];
+  if (owner) {
+    uint32_t run = suf - part;                   // entries in bins of later threads of my wave
+    for (int v = wave + 1; v < 4; ++v) run += scratch[v];
 #pragma unroll
-  for (int i = 7; i >= 0; --i) {
-    if (run < k && run + h[i] >= k) {
-      out[0] = (uint32_t)(tid * 8 + i);
-      out[1] = run;
-      out[2] = h[i];
-    }
-    run += h[i];
-  }
-  __syncthreads();
-}
-
-__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* red) {
-  v = wave_sum_u32(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return red[0] + red[1] + red[2] + red[3];
-}
-
-// ---- A ----------------------------------------------------------------------------------------
-
-__global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const GradPtrs gp, int w0) {
-  __shared__ uint32_t hist[kHistBins];
-  const int w = w0 + blockIdx.y;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const FlatTile ft = ws.ftiles[blockIdx.x];
-  const LayerDev& L = ws.layers[ft.layer];
-  const TileGeom tg = tile_geom(L, ft);
-  const float* __restrict__ g = gp.p[w];
-  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-  float* __restrict__ A = (w == 0) ? ws.A : nullptr;
-  for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0;
-  __syncthreads();
-#pragma unroll 3
-  for (int j = 0; j < kQuadIters; ++j) {
-    const int q = j * kFlatThreads + tid;
-    const bool qa = q < tg.nquads;
-    const int64_t base = tg.a0 + 4 * (int64_t)q;
-    float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (qa) {
-      const float4 gv = ld_quad(g, base, tg.lo, tg.hi);
-      const float4 ev = ld_quad(e, base, tg.lo, tg.hi);
-      d = make_float4(gv.x + ev.x, gv.y + ev.y, gv.z + ev.z, gv.w + ev.w);
-      st_quad(e, base, tg.lo, tg.hi, d);
-      if (A) {
-        float4 a = ld_quad(A, base, tg.lo, tg.hi);
-        a.x += gv.x; a.y += gv.y; a.z += gv.z; a.w += gv.w;
-        st_quad(A, base, tg.lo, tg.hi, a);
+    for (int i = 7; i >= 0; --i) {
+      if (run < k && run + h[i] >= k) {
+        out[0] = (uint32_t)(tid * 8 + i);
+        out[1] = run;
+        out[2] = h[i];
       }
-    }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const bool valid = qa && (base + c >= tg.lo) && (base + c < tg.hi);
-      hist_add(hist, valid, key_of(comp(d, c)) >> 20, lane);
+      run += h[i];
     }
   }
   __syncthreads();
-  const int64_t wl = (int64_t)w * ws.L + ft.layer;
-  uint32_t* gh = ws.hist1 + wl * kHistBins;
-  hist_flush(hist, gh, kHistBins);
-  if (ft.start == 0 && tid == 0) ws.sel[wl].mode = 0;    // B raises it on segment overflow
 }
 
-// ---- wave quarters ------------------------------------------------------------------------------
-// In kernels B..E wave v of the workgroup owns the contiguous quarter [v*qw, (v+1)*qw) of the
-// tile's 16-byte groups, so every count, candidate list and running offset is wave-local
-// (scalar registers, no barriers, no atomics) and index order is (wave, iteration, lane,
-// component).
+// ---- wave quarters --------------------------------------------------------------------------
+// Wave v of a 256-thread workgroup owns the contiguous quarter [v*qw, (v+1)*qw) of the tile's
+// 16-byte groups, so every count, staged list and running offset is wave-local (scalar
+// registers, no barriers, no atomics) and index order is (wave, iteration, lane, component).
 
 struct WaveSpan { int qbeg, qend; };
 
@@ -160,319 +102,908 @@ __device__ __forceinline__ WaveSpan wave_span(const TileGeom& tg, int wave) {
   return s;
 }
 
-__device__ __forceinline__ float4 ld_span(const float* __restrict__ e, const TileGeom& tg,
+template <bool AL>
+__device__ __forceinline__ float4 ld_span(const float* __restrict__ p, const TileGeom& tg,
                                           const WaveSpan& sp, int q) {
-  if (q < sp.qend) return ld_quad(e, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi);
-  return make_float4(0.f, 0.f, 0.f, 0.f);
+  return ldq<AL>(p, tg.a0, tg.lo, tg.hi, q, q < sp.qend);
 }
 
-// Candidates (entries in level-1 bin b1) of my wave's quarter: from the quarter's segment, or,
-// after a segment overflow, re-read from Delta.  f(key, valid) is called by all 64 lanes
-// together (valid marks the lanes that hold a candidate).
-template <class F>
-__device__ __forceinline__ void for_wave_candidates(const Ws& ws, const LayerDev& L, const TileGeom& tg,
-                                                    int w, int tile_id, int wave, int lane, uint32_t mode,
-                                                    uint32_t b1, F f) {
-  if (mode == 0) {
-    const int64_t slot4 = ((int64_t)w * ws.n_ftiles + tile_id) * 4 + wave;
-    const uint32_t cn = min(ws.cand_n[slot4], (uint32_t)kSubCap);
-    const uint2* seg = ws.cand + slot4 * kSubCap;
-    for (uint32_t i0 = 0; i0 < cn; i0 += kWave) {          // cn is wave-uniform
-      const uint32_t i = i0 + lane;
-      const bool valid = i < cn;
-      const uint32_t key = valid ? seg[i].x : 0u;
-      f(key, valid);
+// Is element c of group q (which lies in the wave's span iff in_span) an element of the tile?
+template <bool AL>
+__device__ __forceinline__ bool elem_valid(const TileGeom& tg, int q, int c, bool in_span) {
+  if (AL) return in_span;
+  const int64_t i = tg.a0 + 4 * (int64_t)q + c;
+  return in_span && i >= tg.lo && i < tg.hi;
+}
+
+// Lane mask of elem_valid for component c; for an aligned tile it is the span mask m_span.
+template <bool AL>
+__device__ __forceinline__ uint64_t valid_mask(const TileGeom& tg, int q, int c, bool in_span, uint64_t m_span) {
+  if (AL) return m_span;
+  return ballot64(elem_valid<AL>(tg, q, c, in_span));
+}
+
+// Slot of quarter `wave` of tile `tl` of a layer in the per-worker quarter arrays.
+__device__ __forceinline__ int64_t quarter_slot(const Ws& ws, const LayerDev& L, int w, int tl, int wave) {
+  return (int64_t)w * ws.q_stride + L.qoff + 4 * (int64_t)tl + wave;
+}
+
+// Staging of one component's keys: bin glo at the front of the wave's LDS list, bin ghi in
+// its second half.  n0 / n1 (wave-uniform) keep running past the capacity (the counting kernel
+// sees the overflow); the zeros and the entries above the staged bins are counted per lane and
+// summed over the wave when the quarter is flushed.
+struct StageCounts { uint32_t n0, n1, v_hi, v_nz; };
+
+// mv: lane mask of the valid elements; valid: the calling lane's bit of it.  Every ballot is
+// taken from a single compare and combined with the other masks in scalar registers.
+template <bool TWO = true>
+__device__ __forceinline__ void stage_key(uint32_t* st, uint32_t* sub2, StageCounts& c, uint64_t mv, bool valid,
+                                          uint32_t key, uint32_t glo, uint32_t ghi, int lane) {
+  const uint32_t bin = key >> 20;
+  c.v_nz += (valid && key == 0u) ? 1u : 0u;
+  c.v_hi += (valid && bin > ghi) ? 1u : 0u;
+  const uint64_t m0 = ballot64(bin == glo) & ballot64(key != 0u) & mv;
+  if (m0 != 0) {
+    if (valid && bin == glo && key != 0u) {
+      const uint32_t pos = c.n0 + lanes_below(m0, lane);
+      if (pos < (uint32_t)kSubCap) st[pos] = key;
+      atomicAdd(&sub2[bin2_of(key)], 1u);
     }
-  } else {
-    const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-    const WaveSpan sp = wave_span(tg, wave);
-    for (int q0 = sp.qbeg; q0 < sp.qend; q0 += kWave) {
-      const int q = q0 + lane;
-      const int64_t base = tg.a0 + 4 * (int64_t)q;
-      const float4 d = ld_span(e, tg, sp, q);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bool valid = (q < sp.qend) && (base + c >= tg.lo) && (base + c < tg.hi);
-        const uint32_t key = key_of(comp(d, c));
-        f(key, valid && (key >> 20) == b1);
-      }
+    c.n0 += (uint32_t)__popcll(m0);
+  }
+  if (!TWO) return;                                        // one bin only: ghi == glo
+  const uint64_t m1 = ballot64(bin == ghi) & mv;
+  if (m1 != 0) {
+    if (valid && bin == ghi) {
+      const uint32_t pos = c.n1 + lanes_below(m1, lane);
+      if (pos < (uint32_t)kSubCap) st[kSubCap + pos] = key;
+      atomicAdd(&sub2[kL2Bins + bin2_of(key)], 1u);
     }
+    c.n1 += (uint32_t)__popcll(m1);
   }
 }
 
-// ---- B ----------------------------------------------------------------------------------------
+// Returns the quarter's number of exact zeros (the same value in every lane).
+__device__ __forceinline__ uint32_t stage_flush(const Ws& ws, int64_t qslot, const uint32_t* st,
+                                                const StageCounts& c, int lane) {
+  uint32_t* seg = ws.seg + qslot * (2 * kSubCap);
+  const uint32_t m0 = min(c.n0, (uint32_t)kSubCap), m1 = min(c.n1, (uint32_t)kSubCap);
+  for (uint32_t i = lane; i < m0; i += kWave) seg[i] = st[i];
+  for (uint32_t i = lane; i < m1; i += kWave) seg[kSubCap + i] = st[kSubCap + i];
+  const uint32_t n_hi = wave_sum_u32(c.v_hi), nz = wave_sum_u32(c.v_nz);
+  if (lane == 0) ws.qinfo[qslot] = make_uint4(n_hi, c.n0, c.n1, nz);
+  return nz;
+}
 
-__global__ __launch_bounds__(256) void topk_cand_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3], scratch[4];
-  __shared__ uint2 stage[4][kSubCap];
-  const int w = w0 + blockIdx.y;
+// ---- A ----------------------------------------------------------------------------------------
+
+// SELECT = false (layers of a single tile, which the pick kernel decides from Delta itself):
+// only the error-feedback add and the accumulation.
+template <bool AL, bool SELECT>
+__device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, int w, int tile_id,
+                                             const FlatTile& ft, const LayerDev& L, const TileGeom& tg,
+                                             uint32_t* hist, uint32_t* st, uint32_t* sub2) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const WaveSpan span = wave_span(tg, wave);
+  const float* __restrict__ g = gp.p[w];
+  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  float* __restrict__ A = (w == 0) ? ws.A : nullptr;
+  const int64_t wl = (int64_t)w * ws.L + ft.layer;
+  uint32_t glo = 0xfffffff0u;                              // no bin matches without a guess
+  if (SELECT) {
+    const uint32_t guess = ws.guess[wl * 2 + ws.level[ft.layer]];
+    if (guess != kNoGuess) glo = guess;
+  }
+  const uint32_t ghi = glo + 1u;
+  // two groups per lane are requested before the histograms are cleared
+  constexpr int U = 2;
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 gc[U], ec[U], ac[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int q = span.qbeg + u * kWave + lane;
+    gc[u] = ld_span<AL>(g, tg, span, q);
+    ec[u] = ld_span<AL>(e, tg, span, q);
+    ac[u] = A ? ld_span<AL>(A, tg, span, q) : zero4;
+  }
+  if (SELECT) {
+    for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0;
+    if (tid < kSub2) sub2[tid] = 0;
+    __syncthreads();
+  }
+  StageCounts cnt = {0u, 0u, 0u, 0u};                      // wave-uniform
+  for (int q0 = span.qbeg; q0 < span.qend; q0 += U * kWave) {
+    float4 gn[U], en[U], an[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int q = q0 + (U + u) * kWave + lane;
+      gn[u] = ld_span<AL>(g, tg, span, q);
+      en[u] = ld_span<AL>(e, tg, span, q);
+      an[u] = A ? ld_span<AL>(A, tg, span, q) : zero4;
+    }
+    const bool full = q0 + U * kWave <= span.qend;          // wave-uniform
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int q = q0 + u * kWave + lane;
+      const bool qa = q < span.qend;
+      const float4 d = make_float4(gc[u].x + ec[u].x, gc[u].y + ec[u].y, gc[u].z + ec[u].z, gc[u].w + ec[u].w);
+      if (qa) {
+        stq<AL>(e, tg.a0, tg.lo, tg.hi, q, d);
+        if (A) {
+          const float4 a = make_float4(ac[u].x + gc[u].x, ac[u].y + gc[u].y, ac[u].z + gc[u].z, ac[u].w + gc[u].w);
+          stq<AL>(A, tg.a0, tg.lo, tg.hi, q, a);
+        }
+      }
+      if (SELECT) {
+        if (AL && full) {
+          // every lane of both groups is inside the span: no masks
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const uint32_t key = key_of(comp(d, c));
+            hist_add(hist, key != 0u, key >> 20);
+            stage_key(st, sub2, cnt, ~0ull, true, key, glo, ghi, lane);
+          }
+        } else {
+          const uint64_t m_span = ballot64(qa);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const bool valid = elem_valid<AL>(tg, q, c, qa);
+            const uint64_t mv = valid_mask<AL>(tg, q, c, qa, m_span);
+            const uint32_t key = key_of(comp(d, c));
+            hist_add(hist, valid && key != 0u, key >> 20);
+            stage_key(st, sub2, cnt, mv, valid, key, glo, ghi, lane);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) { gc[u] = gn[u]; ec[u] = en[u]; ac[u] = an[u]; }
+  }
+  if (SELECT) {
+    const uint32_t nz = stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, lane);
+    if (lane == 0 && nz) atomicAdd(&hist[0], nz);
+    __syncthreads();
+    uint32_t* gh = ws.hist1 + wl * kHistBins;
+    for (int b = tid; b < kHistBins; b += kFlatThreads) {
+      const uint32_t h = hist[b];
+      if (h) atomicAdd(&gh[b], h);
+    }
+    if (tid < kSub2) ws.t2[((int64_t)w * ws.n_ftiles + tile_id) * kSub2 + tid] = sub2[tid];
+  }
+}
+
+__global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const GradPtrs gp, int w0) {
+  __shared__ uint32_t hist[kHistBins];
+  __shared__ uint32_t stage[4][2 * kSubCap];
+  __shared__ uint32_t sub2[kSub2];
+  const int w = w0 + blockIdx.y;
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
-  const WaveSpan span = wave_span(tg, wave);
-  const int64_t wl = (int64_t)w * ws.L + ft.layer;
-  SelState* sp = ws.sel + wl;
-  const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-  const int64_t slot4 = ((int64_t)w * ws.n_ftiles + blockIdx.x) * 4 + wave;
-  // the first data is requested before the bin search so that the two latencies overlap
-  float4 cur = ld_span(e, tg, span, span.qbeg + lane);
-  // the bin that holds the k-th largest key of this (worker, layer)
-  if (tid < 3) out[tid] = 0;
-  hist_load(hist, ws.hist1 + wl * kHistBins, kHistBins);
-  const uint32_t k = (uint32_t)L.k[ws.level[ft.layer]];
-  pick_bin(hist, k, out, scratch);
-  const uint32_t b1 = out[0];
-  if (ft.start == 0 && tid == 0) {
-    sp->b1 = out[0]; sp->above1 = out[1]; sp->c1 = out[2]; sp->k = k;
+  uint32_t* st = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+  if (L.ntiles == 1) {
+    if (tg.aligned) ef_hist_tile<true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2);
+    else ef_hist_tile<false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2);
+  } else {
+    if (tg.aligned) ef_hist_tile<true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2);
+    else ef_hist_tile<false, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2);
   }
-  for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0;
+}
+
+// ---- B: re-stage the keys of b1 for the layers whose guess missed --------------------------------
+
+template <bool AL>
+__device__ __forceinline__ void restage_tile(const Ws& ws, int w, int tile_id, const FlatTile& ft,
+                                             const LayerDev& L, const TileGeom& tg, uint32_t b1, uint32_t* st,
+                                             uint32_t* sub2) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const WaveSpan span = wave_span(tg, wave);
+  const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  __syncthreads();                                         // the previous tile's counts have been written
+  if (tid < kSub2) sub2[tid] = 0;
   __syncthreads();
-  uint32_t n_gt = 0, n_c = 0;                              // wave-uniform
+  StageCounts cnt = {0u, 0u, 0u, 0u};
+  float4 cur = ld_span<AL>(e, tg, span, span.qbeg + lane);
   for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
     const int q = q0 + lane;
-    const float4 nxt = ld_span(e, tg, span, q + kWave);
-    const int64_t base = tg.a0 + 4 * (int64_t)q;
+    const float4 nxt = ld_span<AL>(e, tg, span, q + kWave);
+    const bool qa = q < span.qend;
+    const uint64_t m_span = ballot64(qa);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const bool valid = (q < span.qend) && (base + c >= tg.lo) && (base + c < tg.hi);
-      const uint32_t key = key_of(comp(cur, c));
-      const uint32_t bin = key >> 20;
-      n_gt += (uint32_t)__popcll(__ballot(valid && bin > b1));
-      const bool cand = valid && bin == b1;
-      const uint64_t m = __ballot(cand);
-      if (m != 0) {
-        const uint32_t pos = n_c + lanes_below(m, lane);
-        if (cand && pos < (uint32_t)kSubCap)
-          stage[wave][pos] = make_uint2(key, (uint32_t)(base + c - L.offset));
-        n_c += (uint32_t)__popcll(m);
-      }
-    }
+    for (int c = 0; c < 4; ++c)
+      stage_key<false>(st, sub2, cnt, valid_mask<AL>(tg, q, c, qa, m_span), elem_valid<AL>(tg, q, c, qa),
+                       key_of(comp(cur, c)), b1, b1, lane);     // only bin b1 is staged (first half)
     cur = nxt;
   }
-  if (lane == 0) {
-    ws.gt4[slot4] = n_gt;
-    ws.cand_n[slot4] = n_c;
-    if (n_c > (uint32_t)kSubCap) sp->mode = 1;             // segment overflow: re-read path
+  stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, lane);
+  __syncthreads();
+  if (tid < kSub2) ws.t2[((int64_t)w * ws.n_ftiles + tile_id) * kSub2 + tid] = sub2[tid];
+}
+
+// The grid is smaller than the tile table and strides over it; when no layer of the worker
+// missed (the usual case) every workgroup leaves after one load.
+__global__ __launch_bounds__(256) void topk_restage_kernel(const Ws ws, int w0) {
+  __shared__ uint32_t stage[4][2 * kSubCap];
+  __shared__ uint32_t sub2[kSub2];
+  const int w = w0 + blockIdx.y;
+  if (ws.miss_any[w] == 0u) return;                        // uniform over the workgroup
+  uint32_t* st = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+  for (int t = blockIdx.x; t < ws.n_ftiles; t += gridDim.x) {
+    const FlatTile ft = ws.ftiles[t];
+    const LayerDev& L = ws.layers[ft.layer];
+    if (L.ntiles == 1) continue;
+    const SelState* sp = ws.sel + (int64_t)w * ws.L + ft.layer;
+    if (sp->mode != 1u) continue;
+    const TileGeom tg = tile_geom(L, ft);
+    if (tg.aligned) restage_tile<true>(ws, w, t, ft, L, tg, sp->b1, st, sub2);
+    else restage_tile<false>(ws, w, t, ft, L, tg, sp->b1, st, sub2);
   }
-  __syncthreads();                                         // staged candidates are visible
-  if (n_c <= (uint32_t)kSubCap) {
-    // level-2 histogram and the segment from the compacted list (coalesced stores)
-    uint2* seg = ws.cand + slot4 * kSubCap;
-    for (uint32_t i = lane; i < n_c; i += kWave) {
-      const uint2 c = stage[wave][i];
-      atomicAdd(&hist[(c.x >> 9) & 0x7ffu], 1u);
-      seg[i] = c;
-    }
-  } else {
-    // more candidates than slots (huge tie class): the histogram still has to count them all
-    for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
-      const int q = q0 + lane;
-      const int64_t base = tg.a0 + 4 * (int64_t)q;
-      const float4 d = ld_span(e, tg, span, q);
+}
+
+// ---- the per-layer decisions ---------------------------------------------------------------------
+
+constexpr int kFirstChunks = kSubCap / kWave;   // 64-key chunks of one side of a segment
+
+struct QuarterKeys {
+  uint4 info;                      // {entries above the staged bins, keys of side 0, keys of side 1, zeros}
+  uint32_t chunk[kFirstChunks];    // the calling lane's keys of the chosen side
+};
+
+// All loads of a quarter's segment are unconditional (the slot always exists), so they are in
+// flight together; what lies past the count is ignored later.
+__device__ __forceinline__ QuarterKeys load_quarter_keys(const Ws& ws, int64_t qslot, uint32_t side, int lane) {
+  QuarterKeys k;
+  k.info = ws.qinfo[qslot];
+  const uint32_t* seg = ws.seg + qslot * (2 * kSubCap) + side * kSubCap;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bool valid = (q < span.qend) && (base + c >= tg.lo) && (base + c < tg.hi);
-        const uint32_t key = key_of(comp(d, c));
-        hist_add(hist, valid && (key >> 20) == b1, (key >> 9) & 0x7ffu, lane);
-      }
-    }
-  }
-  __syncthreads();
-  hist_flush(hist, ws.hist2 + wl * kHistBins, kHistBins);
+  for (int ch = 0; ch < kFirstChunks; ++ch) k.chunk[ch] = seg[ch * kWave + lane];
+  return k;
 }
 
-// ---- C ----------------------------------------------------------------------------------------
-
-__global__ __launch_bounds__(256) void topk_level3_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3], scratch[4];
-  const int w = w0 + blockIdx.y;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const FlatTile ft = ws.ftiles[blockIdx.x];
-  const LayerDev& L = ws.layers[ft.layer];
-  const TileGeom tg = tile_geom(L, ft);
-  const int64_t wl = (int64_t)w * ws.L + ft.layer;
-  SelState* sp = ws.sel + wl;
-  const uint32_t b1 = sp->b1, mode = sp->mode;
-  // level-2 bin of the k-th largest: k - above1 are still needed from bin b1
-  if (tid < 3) out[tid] = 0;
-  hist_load(hist, ws.hist2 + wl * kHistBins, kHistBins);
-  pick_bin(hist, sp->k - sp->above1, out, scratch);
-  const uint32_t b2 = out[0];
-  if (ft.start == 0) {
-    if (tid == 0) { sp->b2 = out[0]; sp->above2 = out[1]; }
-    hist_clear_global(ws.hist1 + wl * kHistBins, kHistBins);   // every reader of hist1 is done
+// Calls f(key, valid) with all 64 lanes for every key of bin b1 (zeros excluded) of one quarter
+// and returns the quarter's number of entries in bins above b1: from the staged segment and the
+// counts of pass A, or -- when the quarter has more keys of b1 than the segment holds, or when
+// nothing useful was staged (from_delta) -- from Delta itself.
+// tl: tile within the layer, wave: quarter within the tile.
+template <class F>
+__device__ __forceinline__ uint32_t for_quarter_keys(const Ws& ws, const LayerDev& L, int w, int tl, int wave,
+                                                     const QuarterKeys& k, uint32_t side, uint32_t b1,
+                                                     bool from_delta, int lane, F f) {
+  const uint32_t n = side ? k.info.z : k.info.y;
+  if (!from_delta && n <= (uint32_t)kSubCap) {
+#pragma unroll
+    for (int ch = 0; ch < kFirstChunks; ++ch)
+      if (n > (uint32_t)(ch * kWave)) f(k.chunk[ch], (uint32_t)(ch * kWave + lane) < n);   // uniform condition
+    return k.info.x + (side == 0u ? k.info.z : 0u);
   }
-  for (int b = tid; b < 512; b += kFlatThreads) hist[b] = 0;
-  __syncthreads();
-  uint32_t n_gt = 0;
-  for_wave_candidates(ws, L, tg, w, blockIdx.x, wave, lane, mode, b1, [&](uint32_t key, bool valid) {
-    const uint32_t bb = (key >> 9) & 0x7ffu;
-    n_gt += (uint32_t)__popcll(__ballot(valid && bb > b2));
-    if (valid && bb == b2) atomicAdd(&hist[key & 0x1ffu], 1u);
-  });
-  const int64_t slot4 = ((int64_t)w * ws.n_ftiles + blockIdx.x) * 4 + wave;
-  if (lane == 0) ws.gt4[slot4] += n_gt;
-  __syncthreads();
-  hist_flush(hist, ws.hist3 + wl * 512, 512);
+  FlatTile ft;
+  ft.layer = 0;
+  ft.start = tl << kTileShift;
+  ft.count = (int32_t)min((int64_t)kTile, (int64_t)L.rows * L.cols - ft.start);
+  ft.pad = 0;
+  const TileGeom tg = tile_geom(L, ft);
+  const WaveSpan sp = wave_span(tg, wave);
+  const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  uint32_t above = 0;
+  for (int q0 = sp.qbeg; q0 < sp.qend; q0 += kWave) {
+    const int qq = q0 + lane;
+    const float4 d = ld_span<false>(e, tg, sp, qq);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t key = key_of(comp(d, c));
+      const bool valid = elem_valid<false>(tg, qq, c, qq < sp.qend);
+      above += (uint32_t)__popcll(ballot64(valid && (key >> 20) > b1));
+      f(key, valid && key != 0u && (key >> 20) == b1);
+    }
+  }
+  return above;
 }
 
-// ---- D ----------------------------------------------------------------------------------------
-
-__global__ __launch_bounds__(256) void topk_count_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3], scratch[4], tot[2][4];
-  const int w = w0 + blockIdx.y;
+// A layer of a single tile, decided by one workgroup from Delta: the keys go to LDS, three
+// histogram levels (11 + 11 + 9 bits) give the threshold, and the counts of its four quarters
+// give their payload positions.
+__device__ __forceinline__ void pick_small_layer(const Ws& ws, const LayerDev& L, int w, int li, uint32_t k,
+                                                 uint32_t* hist, uint32_t* skeys, uint32_t* out,
+                                                 uint32_t* scratch, uint32_t* qcnt) {
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const FlatTile ft = ws.ftiles[blockIdx.x];
-  const LayerDev& L = ws.layers[ft.layer];
+  FlatTile ft;
+  ft.layer = li;
+  ft.start = 0;
+  ft.count = L.rows * L.cols;
+  ft.pad = 0;
   const TileGeom tg = tile_geom(L, ft);
-  const int64_t wl = (int64_t)w * ws.L + ft.layer;
-  SelState* sp = ws.sel + wl;
-  const uint32_t b1 = sp->b1, b2 = sp->b2, mode = sp->mode;
-  // exact threshold: k - above1 - above2 are still needed from bin (b1, b2)
-  if (tid < 3) out[tid] = 0;
-  hist_load(hist, ws.hist3 + wl * 512, 512);
-  const uint32_t k2 = sp->k - sp->above1 - sp->above2;
-  pick_bin(hist, k2, out, scratch);
-  const uint32_t T = (b1 << 20) | (b2 << 9) | out[0];
-  if (ft.start == 0) {
-    if (tid == 0) {
-      sp->T = T;
-      sp->ktie = k2 - out[1];                              // 1 <= ktie <= entries equal to T
-      sp->alleq = (k2 - out[1] == out[2]) ? 1u : 0u;
+  const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  const int count = ft.count;
+  const int head = (int)(tg.lo - tg.a0);                   // elements of the first group before the tile
+  for (int q = tid; q < tg.nquads; q += kPickThreads) {
+    const float4 d = ld_quad(e, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int i = 4 * q + c - head;
+      if (i >= 0 && i < count) skeys[i] = key_of(comp(d, c));
     }
-    hist_clear_global(ws.hist2 + wl * kHistBins, kHistBins);
   }
-  uint32_t n_gt = 0, n_eq = 0;
-  for_wave_candidates(ws, L, tg, w, blockIdx.x, wave, lane, mode, b1, [&](uint32_t key, bool valid) {
-    const bool in_b2 = valid && ((key >> 9) & 0x7ffu) == b2;   // bins above b2 were counted in C
-    n_gt += (uint32_t)__popcll(__ballot(in_b2 && key > T));
-    n_eq += (uint32_t)__popcll(__ballot(in_b2 && key == T));
-  });
-  const int64_t slot4 = ((int64_t)w * ws.n_ftiles + blockIdx.x) * 4 + wave;
-  if (lane == 0) {
-    const uint32_t g = ws.gt4[slot4] + n_gt;
-    ws.gt4[slot4] = g;
-    ws.eq4[slot4] = n_eq;
-    tot[0][wave] = g;
-    tot[1][wave] = n_eq;
+  for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = 0u;
+  if (tid < 8) qcnt[tid] = 0u;
+  __syncthreads();
+  for (int i = tid; i < count; i += kPickThreads) atomicAdd(&hist[skeys[i] >> 20], 1u);
+  __syncthreads();
+  pick_bin(hist, k, out, scratch);
+  const uint32_t b1 = out[0], need2 = k - out[1];
+  __syncthreads();
+  for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = 0u;
+  __syncthreads();
+  for (int i = tid; i < count; i += kPickThreads) {
+    const uint32_t key = skeys[i];
+    if ((key >> 20) == b1) atomicAdd(&hist[(key >> 9) & 0x7ffu], 1u);
+  }
+  __syncthreads();
+  pick_bin(hist, need2, out, scratch);
+  const uint32_t b12 = (b1 << 11) | out[0], need3 = need2 - out[1];
+  __syncthreads();
+  for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = 0u;
+  __syncthreads();
+  for (int i = tid; i < count; i += kPickThreads) {
+    const uint32_t key = skeys[i];
+    if ((key >> 9) == b12) atomicAdd(&hist[key & 0x1ffu], 1u);
+  }
+  __syncthreads();
+  pick_bin(hist, need3, out, scratch);
+  const uint32_t T = (b12 << 9) | out[0];
+  const uint32_t ktie = need3 - out[1];
+  const uint32_t alleq = (ktie == out[2]) ? 1u : 0u;
+  // counts of the four wave quarters the compaction kernel will use
+  const int qw = (tg.nquads + 3) >> 2;
+  for (int i = tid; i < count; i += kPickThreads) {
+    const uint32_t key = skeys[i];
+    if (key >= T) atomicAdd(&qcnt[(key > T ? 0 : 4) + ((i + head) >> 2) / qw], 1u);
   }
   __syncthreads();
   if (tid == 0) {
-    const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + (ft.start >> kTileShift);
-    ws.gt_cnt[tslot] = tot[0][0] + tot[0][1] + tot[0][2] + tot[0][3];
-    ws.eq_cnt[tslot] = tot[1][0] + tot[1][1] + tot[1][2] + tot[1][3];
+    const int64_t qbase = (int64_t)w * ws.q_stride + L.qoff;
+    uint32_t g = 0, q = 0;
+    for (int v = 0; v < 4; ++v) {
+      ws.gtpre[qbase + v] = g;
+      ws.eqpre[qbase + v] = q;
+      g += qcnt[v];
+      q += qcnt[4 + v];
+    }
+    ws.gtpre[qbase + 4] = g;
+    ws.eqpre[qbase + 4] = q;
+    SelState* sp = ws.sel + (int64_t)w * ws.L + li;
+    sp->mode = 0u; sp->k = k; sp->T = T; sp->ktie = ktie; sp->alleq = alleq;
+  }
+}
+
+__global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, int w0) {
+  __shared__ uint32_t hist[kHistBins];
+  __shared__ uint32_t out[3], scratch[4], qcnt[8];
+  __shared__ uint32_t skeys[kTile];
+  const int li = blockIdx.x;
+  const int w = w0 + blockIdx.y;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const LayerDev& L = ws.layers[li];
+  const int64_t wl = (int64_t)w * ws.L + li;
+  const int lv = ws.level[li];
+  const uint32_t k = (uint32_t)L.k[lv];
+  if (L.ntiles == 1) {
+    pick_small_layer(ws, L, w, li, k, hist, skeys, out, scratch, qcnt);
+    return;
+  }
+  SelState* sp = ws.sel + wl;
+  // level 1; the layer's histogram is cleared for the next step
+  uint32_t* gh = ws.hist1 + wl * kHistBins;
+  for (int b = tid; b < kHistBins; b += kPickThreads) { hist[b] = gh[b]; gh[b] = 0u; }
+  __syncthreads();
+  pick_bin(hist, k, out, scratch);
+  const uint32_t b1 = out[0], need2 = k - out[1];
+  const uint32_t guess = ws.guess[wl * 2 + lv];
+  const bool hit = guess != kNoGuess && (b1 == guess || b1 == guess + 1u);
+  const uint32_t side = (hit && b1 != guess) ? 1u : 0u;
+  if (tid == 0) {
+    sp->b1 = b1; sp->need2 = need2; sp->k = k; sp->side = side; sp->zeros = 0u;
+    sp->mode = hit ? 0u : 1u;
+    if (!hit) ws.miss_any[w] = 1u;                         // cleared by the compaction kernel
+#ifdef ACC_DEBUG_MISS
+    if (!hit) atomicAdd(&ws.words[3], 1ull + ((unsigned long long)L.ntiles << 20));
+#endif
+  }
+  if (!hit) return;                                        // its keys get staged; the counting kernel finds b2
+  __syncthreads();
+  // level 2: sum of the tiles' counts of bin b1
+  for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = 0u;
+  __syncthreads();
+  {
+    const int bin = tid & (kL2Bins - 1), stripe = tid / kL2Bins;
+    const uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_ftiles + L.tile0) * kSub2 + side * kL2Bins + bin;
+    constexpr int kStripes = kPickThreads / kL2Bins;
+    uint32_t s = 0;
+    for (int tl0 = stripe; tl0 < L.ntiles; tl0 += 8 * kStripes) {
+      uint32_t v[8];                                       // eight independent loads in flight
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int tl = min(tl0 + u * kStripes, L.ntiles - 1);
+        v[u] = t2[(int64_t)tl * kSub2];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += (tl0 + u * kStripes < L.ntiles) ? v[u] : 0u;
+    }
+    if (s) atomicAdd(&hist[bin], s);
+  }
+  if (b1 == 0u) {
+    // exact zeros are keys of bin 0, level-2 bin 0, that were never staged
+    const int64_t qbase = (int64_t)w * ws.q_stride + L.qoff;
+    uint32_t z = 0;
+    for (int q = tid; q < 4 * L.ntiles; q += kPickThreads) z += ws.qinfo[qbase + q].w;
+    z = wave_sum_u32(z);
+    if (lane == 0 && z) { atomicAdd(&hist[0], z); atomicAdd(&sp->zeros, z); }
+  }
+  __syncthreads();
+  pick_bin(hist, need2, out, scratch);
+  if (tid == 0) {
+    sp->b2 = out[0];
+    sp->need3 = need2 - out[1];                            // still needed from bin (b1, b2)
+  }
+}
+
+__global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
+  __shared__ uint32_t hist[kHistBins];
+  __shared__ uint32_t out[3], scratch[4], zsum;
+  const int w = w0 + blockIdx.y;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  if (L.ntiles == 1) return;                               // decided by the first pick kernel
+  const int64_t wl = (int64_t)w * ws.L + ft.layer;
+  SelState* sp = ws.sel + wl;
+  const int tl = ft.start >> kTileShift;
+  const uint32_t side = sp->side, b1 = sp->b1;
+  uint32_t b2 = sp->b2;
+  if (sp->mode != 0u) {                                    // uniform over the workgroup
+    // a missed layer: its keys of b1 were re-staged tile by tile; every workgroup of the layer
+    // sums the tiles' level-2 counts itself
+    const int tid = threadIdx.x;
+    for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0u;
+    if (tid == 0) zsum = 0u;
+    __syncthreads();
+    {
+      constexpr int kStripes = kFlatThreads / kL2Bins;
+      const int bin = tid & (kL2Bins - 1), stripe = tid / kL2Bins;
+      const uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_ftiles + L.tile0) * kSub2 + bin;
+      uint32_t sum = 0;
+      for (int t0 = stripe; t0 < L.ntiles; t0 += 8 * kStripes) {
+        uint32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = t2[(int64_t)min(t0 + u * kStripes, L.ntiles - 1) * kSub2];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += (t0 + u * kStripes < L.ntiles) ? v[u] : 0u;
+      }
+      if (sum) atomicAdd(&hist[bin], sum);
+    }
+    if (b1 == 0u) {
+      const int64_t qb = (int64_t)w * ws.q_stride + L.qoff;
+      uint32_t z = 0;
+      for (int q = tid; q < 4 * L.ntiles; q += kFlatThreads) z += ws.qinfo[qb + q].w;
+      z = wave_sum_u32(z);
+      if (lane == 0 && z) { atomicAdd(&hist[0], z); atomicAdd(&zsum, z); }
+    }
+    __syncthreads();
+    const uint32_t need2 = sp->need2;
+    pick_bin(hist, need2, out, scratch);
+    b2 = out[0];
+    if (tl == 0 && tid == 0) { sp->b2 = b2; sp->need3 = need2 - out[1]; sp->zeros = zsum; }
+  }
+  const int64_t qslot = quarter_slot(ws, L, w, tl, wave);
+  const QuarterKeys qk = load_quarter_keys(ws, qslot, side, lane);
+  uint32_t* list = ws.qlist + qslot * kQListCap;
+  uint32_t n_gt = 0, n_in = 0;                             // wave-uniform
+  const uint32_t above = for_quarter_keys(ws, L, w, tl, wave, qk, side, b1, false, lane, [&](uint32_t key, bool valid) {
+    const uint32_t bb = bin2_of(key);
+    const uint64_t mv = ballot64(valid);
+    n_gt += (uint32_t)__popcll(ballot64(bb > b2) & mv);
+    const uint64_t m2 = ballot64(bb == b2) & mv;
+    if (m2 != 0) {
+      const uint32_t pos = n_in + lanes_below(m2, lane);
+      if (valid && bb == b2 && pos < (uint32_t)kQListCap) list[pos] = key;
+      n_in += (uint32_t)__popcll(m2);
+    }
+  });
+  if (lane == 0) { ws.gtq[qslot] = above + n_gt; ws.eqq[qslot] = n_in; }
+}
+
+__global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, int w0) {
+  __shared__ uint32_t hist[kHistBins];
+  __shared__ uint32_t out[3], scratch[4];
+  __shared__ uint32_t wsum[2][kPickWaves];
+  __shared__ uint32_t zsum;
+  const int li = blockIdx.x;
+  const int w = w0 + blockIdx.y;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const LayerDev& L = ws.layers[li];
+  if (L.ntiles == 1) return;                               // decided by the first pick kernel
+  const int64_t wl = (int64_t)w * ws.L + li;
+  SelState* sp = ws.sel + wl;
+  const int lv = ws.level[li];
+  const int nq = 4 * L.ntiles;
+  const int64_t qbase = (int64_t)w * ws.q_stride + L.qoff;
+  const uint32_t b1 = sp->b1, side = sp->side;
+  // gtq: per quarter, the entries above bin (b1, b2); eqq: the number of keys inside (b1, b2), of
+  // which the first kQListCap are listed.  Thread t owns a contiguous chunk of quarters.
+  uint32_t* gtq = ws.gtq + qbase;
+  uint32_t* eqq = ws.eqq + qbase;
+  const uint32_t* qlist = ws.qlist + qbase * kQListCap;
+  const int chunk = (nq + kPickThreads - 1) / kPickThreads;
+  const int q_lo = min(tid * chunk, nq), q_hi = min(q_lo + chunk, nq);
+  if (tid == 0) zsum = 0u;
+  __syncthreads();
+  {
+    uint32_t over = 0;
+    for (int q = q_lo; q < q_hi; ++q) over |= (eqq[q] > (uint32_t)kQListCap) ? 1u : 0u;
+    if (over) zsum = 1u;                                   // some quarter's list overflowed
+  }
+  __syncthreads();
+  const bool use_list = zsum == 0u;
+  __syncthreads();
+  const uint32_t b2 = sp->b2, zeros = sp->zeros;
+  uint32_t need = sp->need3;
+
+  // One sweep of the workgroup over the keys of bin b1 of the whole layer (slow path: some
+  // quarter holds more keys of bin (b1, b2) than its list, i.e. a large tie class).
+  auto sweep = [&](auto per_key, auto per_quarter) {
+    for (int q = wave; q < nq; q += kPickWaves) {
+      const QuarterKeys qk = load_quarter_keys(ws, qbase + q, side, lane);
+      const uint32_t above = for_quarter_keys(ws, L, w, q >> 2, q & 3, qk, side, b1, false, lane, per_key);
+      per_quarter(q, above);
+    }
+  };
+  auto clear_hist = [&]() {
+    __syncthreads();
+    for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = 0u;
+    __syncthreads();
+  };
+  auto nothing = [](int, uint32_t) {};
+
+  const bool zero_bin = (b1 == 0u && b2 == 0u);            // bin (b1, b2) holds the exact zeros
+
+  // level 3: key bits 13..6 of the keys of (b1, b2)
+  clear_hist();
+  if (use_list) {
+    for (int q = q_lo; q < q_hi; ++q) {
+      const uint32_t n = eqq[q];
+      for (uint32_t i = 0; i < n; ++i) atomicAdd(&hist[bin3_of(qlist[(int64_t)q * kQListCap + i])], 1u);
+    }
+  } else {
+    sweep([&](uint32_t key, bool valid) { if (valid && bin2_of(key) == b2) atomicAdd(&hist[bin3_of(key)], 1u); },
+          nothing);
+  }
+  if (zero_bin && tid == 0) atomicAdd(&hist[0], zeros);
+  __syncthreads();
+  pick_bin(hist, need, out, scratch);
+  const uint32_t b3 = out[0];
+  need -= out[1];
+  // level 4: key bits 5..0 of the keys of (b1, b2, b3)
+  clear_hist();
+  const uint32_t hi3 = (b1 << 14) | (b2 << 8) | b3;        // key >> 6 of the keys of (b1, b2, b3)
+  if (use_list) {
+    for (int q = q_lo; q < q_hi; ++q) {
+      const uint32_t n = eqq[q];
+      for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t key = qlist[(int64_t)q * kQListCap + i];
+        if ((key >> 6) == hi3) atomicAdd(&hist[bin4_of(key)], 1u);
+      }
+    }
+  } else {
+    sweep([&](uint32_t key, bool valid) { if (valid && (key >> 6) == hi3) atomicAdd(&hist[bin4_of(key)], 1u); },
+          nothing);
+  }
+  if (zero_bin && b3 == 0u && tid == 0) atomicAdd(&hist[0], zeros);
+  __syncthreads();
+  pick_bin(hist, need, out, scratch);
+  const uint32_t T = (hi3 << 6) | out[0];
+  const uint32_t ktie = need - out[1];                     // 1 <= ktie <= entries equal to T
+  const uint32_t alleq = (ktie == out[2]) ? 1u : 0u;
+
+  // per quarter: entries above T and entries equal to T
+  if (!use_list) {
+    uint32_t n_gt = 0, n_eq = 0;
+    sweep([&](uint32_t key, bool valid) {
+            const uint64_t mv = ballot64(valid);
+            n_gt += (uint32_t)__popcll(ballot64(key > T) & mv);
+            n_eq += (uint32_t)__popcll(ballot64(key == T) & mv);
+          },
+          [&](int q, uint32_t above) {
+            if (lane == 0) { gtq[q] = above + n_gt; eqq[q] = n_eq; }
+            n_gt = 0; n_eq = 0;
+          });
+  }
+  __syncthreads();
+  auto quarter_counts = [&](int q, uint32_t& g, uint32_t& e) {
+    g = ld_agent(&gtq[q]);
+    e = ld_agent(&eqq[q]);
+    if (use_list) {                                        // e listed keys of (b1, b2): compare them with T
+      const uint32_t n = e;
+      e = 0;
+      for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t key = qlist[(int64_t)q * kQListCap + i];
+        g += (key > T) ? 1u : 0u;
+        e += (key == T) ? 1u : 0u;
+      }
+    }
+    if (T == 0u) e += ws.qinfo[qbase + q].w;               // the exact zeros were counted apart
+  };
+
+  // exclusive prefix over the quarters of the layer
+  {
+    uint32_t s_gt = 0, s_eq = 0;
+    for (int q = q_lo; q < q_hi; ++q) {
+      uint32_t g, e;
+      quarter_counts(q, g, e);
+      s_gt += g;
+      s_eq += e;
+    }
+    const uint32_t i_gt = wave_incl_scan_u32(s_gt, lane), i_eq = wave_incl_scan_u32(s_eq, lane);
+    if (lane == kWave - 1) { wsum[0][wave] = i_gt; wsum[1][wave] = i_eq; }
+    __syncthreads();
+    uint32_t o_gt = i_gt - s_gt, o_eq = i_eq - s_eq;
+    for (int v = 0; v < wave; ++v) { o_gt += wsum[0][v]; o_eq += wsum[1][v]; }
+    uint32_t* gtpre = ws.gtpre + qbase;
+    uint32_t* eqpre = ws.eqpre + qbase;
+    for (int q = q_lo; q < q_hi; ++q) {
+      uint32_t g, e;
+      quarter_counts(q, g, e);
+      gtpre[q] = o_gt;
+      eqpre[q] = o_eq;
+      o_gt += g;
+      o_eq += e;
+    }
+    if (tid == kPickThreads - 1) { gtpre[nq] = o_gt; eqpre[nq] = o_eq; }   // totals: o_gt + ktie == k
+  }
+  if (tid == 0) {
+    sp->T = T; sp->ktie = ktie; sp->alleq = alleq; sp->mode = 0u;
+    // next step's guess at this level: b1 and the neighbour on the side of the threshold
+    uint32_t glo = (b2 >= (uint32_t)(kL2Bins / 2)) ? b1 : (b1 == 0u ? 0u : b1 - 1u);
+    if (glo > (uint32_t)(kHistBins - 2)) glo = (uint32_t)(kHistBins - 2);
+    ws.guess[wl * 2 + lv] = glo;
   }
 }
 
 // ---- E ----------------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t red[4];
-  const int w = w0 + blockIdx.y;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const FlatTile ft = ws.ftiles[blockIdx.x];
-  const LayerDev& L = ws.layers[ft.layer];
-  const TileGeom tg = tile_geom(L, ft);
-  const WaveSpan span = wave_span(tg, wave);
-  const int64_t wl = (int64_t)w * ws.L + ft.layer;
-  const SelState* sp = ws.sel + wl;
-  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-  float4 cur = ld_span(e, tg, span, span.qbeg + lane);
-  const uint32_t T = sp->T, ktie = sp->ktie, alleq = sp->alleq, kk = sp->k;
-  // ties and selected entries before my wave's quarter.  The tie quota is used up in index
-  // order, so everything before a point took min(ktie, ties before that point) ties in total.
-  const int my_t = ft.start >> kTileShift;
-  const int64_t tbase = (int64_t)w * ws.tile_stride + L.toff;
-  uint32_t s_eq = 0, s_gt = 0;
-  for (int t = tid; t < my_t; t += kFlatThreads) {
-    s_eq += ws.eq_cnt[tbase + t];
-    s_gt += ws.gt_cnt[tbase + t];
-  }
-  const uint32_t eq_base = block_sum_u32(s_eq, red);
-  const uint32_t gt_base = block_sum_u32(s_gt, red);
-  if (tid == 0) {
-    ws.sel_off[tbase + my_t] = gt_base + min(ktie, eq_base);   // read by the payload mean
-    if (my_t == L.ntiles - 1) ws.sel_off[tbase + L.ntiles] = kk;
-  }
-  if (ft.start == 0) hist_clear_global(ws.hist3 + wl * 512, 512);
-  const int64_t slot4 = ((int64_t)w * ws.n_ftiles + blockIdx.x) * 4;
-  uint32_t eq_run = eq_base, gt_before = gt_base;
-  for (int v = 0; v < wave; ++v) { eq_run += ws.eq4[slot4 + v]; gt_before += ws.gt4[slot4 + v]; }
-  uint32_t pos_run = gt_before + min(ktie, eq_run);
+// What a wave needs to know about one worker's selection in its quarter.
+struct QuarterSel {
+  uint32_t T, ktie, alleq, k;
+  uint32_t gt_before, eq_before;     // selected-above-T and equal-to-T entries in the quarters before
+  uint32_t eq_here;                  // entries equal to T in this quarter
+};
 
-  int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
-  float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
-  for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
-    const int q = q0 + lane;
-    const float4 nxt = ld_span(e, tg, span, q + kWave);
-    const int64_t base = tg.a0 + 4 * (int64_t)q;
-    bool sel[4];
-    uint32_t key[4];
-    bool valid[4];
+__device__ __forceinline__ QuarterSel load_quarter_sel(const Ws& ws, int w, int layer, int64_t qslot_local) {
+  const SelState* sp = ws.sel + (int64_t)w * ws.L + layer;
+  const int64_t qs = (int64_t)w * ws.q_stride + qslot_local;
+  QuarterSel s;
+  s.T = sp->T; s.ktie = sp->ktie; s.alleq = sp->alleq; s.k = sp->k;
+  s.gt_before = ws.gtpre[qs];
+  s.eq_before = ws.eqpre[qs];
+  s.eq_here = ws.eqpre[qs + 1] - s.eq_before;              // the layer's last slot holds the total
+  return s;
+}
+
+// Running state of the ordered compaction of one worker's quarter.
+struct CompactRun { uint32_t eq_run, pos_run; };
+
+// One group of four elements per lane: which are selected, their payload entries, the zeros in e;
+// MEAN adds the kept values to acc.  An element is selected iff its key >= tsel, where tsel is
+// T for the entries equal to T that are within the tie quota (lowest indices first) and T + 1
+// otherwise; quarters without an entry equal to T never look at ties.
+template <bool AL, bool MEAN>
+__device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan& span, const LayerDev& L,
+                                              const QuarterSel& qs, CompactRun& run, float* __restrict__ e,
+                                              int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
+                                              const float4& cur, int lane, float4& acc) {
+  const bool qa = q < span.qend;
+  const uint64_t m_span = ballot64(qa);
+  const uint32_t T = qs.T;
+  bool valid[4];
+  uint64_t mv[4];
+  uint32_t key[4], tsel[4];
+  const uint32_t t_all = qs.alleq ? T : T + 1u;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      valid[c] = (q < span.qend) && (base + c >= tg.lo) && (base + c < tg.hi);
-      key[c] = key_of(comp(cur, c));
-    }
-    if (alleq) {
+  for (int c = 0; c < 4; ++c) {
+    valid[c] = elem_valid<AL>(tg, q, c, qa);
+    mv[c] = valid_mask<AL>(tg, q, c, qa, m_span);
+    key[c] = key_of(comp(cur, c));
+    tsel[c] = t_all;
+  }
+  if (qs.eq_here != 0u && !qs.alleq) {                      // wave-uniform
+    uint64_t meq[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) sel[c] = valid[c] && key[c] >= T;
-    } else {
-      uint32_t below = 0, total = 0;
+    for (int c = 0; c < 4; ++c) meq[c] = ballot64(key[c] == T) & mv[c];
+    if ((meq[0] | meq[1] | meq[2] | meq[3]) != 0) {
+      // the tie quota is used up in index order
+      uint32_t rank = run.eq_run;
+      uint32_t total = 0;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const uint64_t m = __ballot(valid[c] && key[c] == T);
-        below += lanes_below(m, lane);
-        total += (uint32_t)__popcll(m);
+        rank += lanes_below(meq[c], lane);
+        total += (uint32_t)__popcll(meq[c]);
       }
-      uint32_t rank = eq_run + below;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const bool iseq = valid[c] && key[c] == T;
-        sel[c] = valid[c] && (key[c] > T || (iseq && rank < ktie));
+        tsel[c] = (iseq && rank < qs.ktie) ? T : T + 1u;
         rank += iseq ? 1u : 0u;
       }
-      eq_run += total;
+      run.eq_run += total;
     }
-    uint32_t below = 0, total = 0;
+  }
+  uint64_t msel[4];
+  uint32_t below = 0, total = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    msel[c] = ballot64(key[c] >= tsel[c]) & mv[c];
+    below += lanes_below(msel[c], lane);
+    total += (uint32_t)__popcll(msel[c]);
+  }
+  if (total != 0) {
+    uint32_t pos = run.pos_run + below;
+    const int32_t i0 = (int32_t)(tg.a0 + 4 * (int64_t)q - L.offset);
+    float4 z = cur;
+    bool sel[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const uint64_t m = __ballot(sel[c]);
-      below += lanes_below(m, lane);
-      total += (uint32_t)__popcll(m);
-    }
-    if (total != 0) {
-      uint32_t pos = pos_run + below;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        if (sel[c]) {
-          if (pos < kk) {                          // always true for consistent state
-            pidx[pos] = (int32_t)(base + c - L.offset);
-            pval[pos] = comp(cur, c);
-          }
-          e[base + c] = 0.f;
-          ++pos;
+      sel[c] = valid[c] && key[c] >= tsel[c];
+      if (sel[c]) {
+        if (pos < qs.k) {                                   // always true for consistent state
+          pidx[pos] = i0 + c;
+          pval[pos] = comp(cur, c);
         }
+        ++pos;
       }
-      pos_run += total;
     }
-    cur = nxt;
+    if (sel[0]) z.x = 0.f;
+    if (sel[1]) z.y = 0.f;
+    if (sel[2]) z.z = 0.f;
+    if (sel[3]) z.w = 0.f;
+    if (sel[0] || sel[1] || sel[2] || sel[3]) stq<AL>(e, tg.a0, tg.lo, tg.hi, q, z);
+    run.pos_run += total;
+    if (MEAN) {
+      if (sel[0]) acc.x += cur.x;
+      if (sel[1]) acc.y += cur.y;
+      if (sel[2]) acc.z += cur.z;
+      if (sel[3]) acc.w += cur.w;
+    }
   }
 }
 
-// ---- K6: dense mean of the W payloads --------------------------------------------------------
+// One worker per grid row; the mean is taken later from the payloads.
+template <bool AL>
+__device__ __forceinline__ void compact_tile(const Ws& ws, int w, const FlatTile& ft, const LayerDev& L,
+                                             const TileGeom& tg) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const WaveSpan span = wave_span(tg, wave);
+  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  float4 cur = ld_span<AL>(e, tg, span, span.qbeg + lane);
+  float4 nxt = ld_span<AL>(e, tg, span, span.qbeg + kWave + lane);
+  const QuarterSel qs = load_quarter_sel(ws, w, ft.layer, L.qoff + 4 * (int64_t)(ft.start >> kTileShift) + wave);
+  CompactRun run;
+  run.eq_run = qs.eq_before;
+  run.pos_run = qs.gt_before + min(qs.ktie, qs.eq_before);
+  int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
+  float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
+  float4 unused = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
+    const int q = q0 + lane;
+    const float4 nn = ld_span<AL>(e, tg, span, q + 2 * kWave);
+    compact_group<AL, false>(tg, span, L, qs, run, e, pidx, pval, q, cur, lane, unused);
+    cur = nxt;
+    nxt = nn;
+  }
+}
+
+__global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) {
+  const int w = w0 + blockIdx.y;
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  const TileGeom tg = tile_geom(L, ft);
+  if (blockIdx.x == 0 && threadIdx.x == 0) ws.miss_any[w] = 0u;
+  if (tg.aligned) compact_tile<true>(ws, w, ft, L, tg);
+  else compact_tile<false>(ws, w, ft, L, tg);
+}
+
+// All workers in worker order, and the dense mean of the kept values: out[i] = (sum over the
+// workers that kept i, from +0, of their value) / W.  The loop runs over the groups of the quarter
+// and, inside, over the workers, so that the sum of one group lives in four registers; the running
+// compaction state of every worker is kept in one lane each.  Delta is read one batch of
+// kMeanBatch workers ahead.
+constexpr int kMeanBatch = 4;
+
+template <bool AL>
+__device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& ft, const LayerDev& L,
+                                                  const TileGeom& tg, float* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const WaveSpan span = wave_span(tg, wave);
+  const int64_t qslot_local = L.qoff + 4 * (int64_t)(ft.start >> kTileShift) + wave;
+  const int W = ws.W;
+  // lane w holds worker w's selection state for this quarter
+  QuarterSel mine = {0u, 0u, 0u, 0u, 0u, 0u, 0u};
+  if (lane < W) mine = load_quarter_sel(ws, lane, ft.layer, qslot_local);
+  uint32_t eq_run_v = mine.eq_before;
+  uint32_t pos_run_v = mine.gt_before + min(mine.ktie, mine.eq_before);
+  const int n = (span.qend - span.qbeg + kWave - 1) / kWave;   // groups of the quarter, wave-uniform
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto load_batch = [&](int j, int wb, float4 (&d)[kMeanBatch]) {
+#pragma unroll
+    for (int u = 0; u < kMeanBatch; ++u) {
+      const int w = wb + u;
+      d[u] = (j < n && w < W) ? ld_span<AL>(ws.e + (int64_t)w * ws.e_stride, tg, span, span.qbeg + j * kWave + lane)
+                              : zero4;
+    }
+  };
+  float4 cur[kMeanBatch], nxt[kMeanBatch];
+  load_batch(0, 0, cur);
+  const float fw = (float)W;
+  for (int j = 0; j < n; ++j) {
+    const int q = span.qbeg + j * kWave + lane;
+    float4 acc = zero4;
+    for (int wb = 0; wb < W; wb += kMeanBatch) {
+      int j2 = j, wb2 = wb + kMeanBatch;
+      if (wb2 >= W) { wb2 = 0; ++j2; }
+      load_batch(j2, wb2, nxt);
+#pragma unroll
+      for (int u = 0; u < kMeanBatch; ++u) {
+        const int w = wb + u;
+        if (w < W) {                                        // wave-uniform
+          QuarterSel qs;
+          qs.T = (uint32_t)__builtin_amdgcn_readlane((int)mine.T, w);
+          qs.ktie = (uint32_t)__builtin_amdgcn_readlane((int)mine.ktie, w);
+          qs.alleq = (uint32_t)__builtin_amdgcn_readlane((int)mine.alleq, w);
+          qs.k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
+          qs.eq_here = (uint32_t)__builtin_amdgcn_readlane((int)mine.eq_here, w);
+          qs.gt_before = 0u;
+          qs.eq_before = 0u;
+          CompactRun run;
+          run.eq_run = (uint32_t)__builtin_amdgcn_readlane((int)eq_run_v, w);
+          run.pos_run = (uint32_t)__builtin_amdgcn_readlane((int)pos_run_v, w);
+          float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+          int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
+          float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
+          compact_group<AL, true>(tg, span, L, qs, run, e, pidx, pval, q, cur[u], lane, acc);
+          if (lane == w) { eq_run_v = run.eq_run; pos_run_v = run.pos_run; }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kMeanBatch; ++u) cur[u] = nxt[u];
+    }
+    if (q < span.qend) {
+      const float4 v = make_float4(acc.x / fw, acc.y / fw, acc.z / fw, acc.w / fw);
+      stq<AL>(out, tg.a0, tg.lo, tg.hi, q, v);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void topk_compact_mean_kernel(const Ws ws, float* __restrict__ out) {
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  const TileGeom tg = tile_geom(L, ft);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    ws.words[1] = ws.words[0];
+    ws.words[2] += ws.words[0];
+  }
+  if (blockIdx.x == 0 && threadIdx.x < ws.W) ws.miss_any[threadIdx.x] = 0u;
+  if (tg.aligned) compact_mean_tile<true>(ws, ft, L, tg, out);
+  else compact_mean_tile<false>(ws, ft, L, tg, out);
+}
+
+// ---- K6: dense mean of the W payloads (call-by-call path) ----------------------------------------
 
 __global__ __launch_bounds__(256) void topk_sparse_mean_kernel(const Ws ws, float* __restrict__ out) {
   __shared__ float acc[kTile];
@@ -488,11 +1019,14 @@ __global__ __launch_bounds__(256) void topk_sparse_mean_kernel(const Ws ws, floa
   __syncthreads();
   const int tl = ft.start >> kTileShift;
   for (int w = 0; w < ws.W; ++w) {
-    const int64_t tslot = (int64_t)w * ws.tile_stride + L.toff + tl;
-    const uint32_t lo = ws.sel_off[tslot], hi = ws.sel_off[tslot + 1];
+    // payload positions of the tile's first quarter and of the next tile's first quarter
+    const int64_t qs = (int64_t)w * ws.q_stride + L.qoff + 4 * (int64_t)tl;
+    const SelState* sp = ws.sel + (int64_t)w * ws.L + ft.layer;
+    const uint32_t ktie = sp->ktie, kk = sp->k;
+    const uint32_t lo = ws.gtpre[qs] + min(ktie, ws.eqpre[qs]);
+    const uint32_t hi = ws.gtpre[qs + 4] + min(ktie, ws.eqpre[qs + 4]);
     const int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
     const float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
-    const uint32_t kk = ws.sel[(int64_t)w * ws.L + ft.layer].k;
     for (uint32_t p = lo + tid; p < hi && p < kk; p += kFlatThreads) {
       const int32_t i = pidx[p] - ft.start;
       if (i >= 0 && i < ft.count) acc[i] += pval[p];   // indices are unique within a worker

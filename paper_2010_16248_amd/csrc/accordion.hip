@@ -38,13 +38,13 @@ struct Plan {
   int32_t rmax = 0;
   int64_t N = 0, e_stride = 0;
   int64_t q_total = 0, p_total = 0, ppart_stride = 0, qpart_stride = 0, vec_total = 0;
-  int64_t pay_stride = 0, tile_stride = 0;
+  int64_t pay_stride = 0, q_stride = 0;
   // workspace regions
   Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
   Region r_A, r_e, r_norm_part;
   Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean;
-  Region r_hist1, r_hist2, r_hist3, r_sel, r_cand, r_candn, r_gt4, r_eq4, r_gt, r_eq, r_seloff, r_payidx, r_payval;
+  Region r_hist1, r_t2, r_qlist, r_sel, r_miss, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval;
   int64_t total_bytes = 0;
 };
 
@@ -104,7 +104,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     d.vec4 = (l.offset % 4 == 0 && l.cols % 4 == 0) ? 1 : 0;
     d.tile0 = (int32_t)ntile;
     d.ntiles = (int32_t)((n + kTile - 1) / kTile);
-    d.toff = d.tile0 + i;
+    d.qoff = 4 * (int64_t)d.tile0 + i;
     for (int t = 0; t < d.ntiles; ++t) {
       FlatTile ft;
       ft.layer = i;
@@ -162,7 +162,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
       p.pay_stride += std::max(d.k[0], d.k[1]);
     }
   }
-  p.tile_stride = ntile + nl;
+  p.q_stride = 4 * ntile + nl;
 
   // workspace layout, 256-byte aligned regions
   int64_t off = 0;
@@ -196,16 +196,17 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     reg(p.r_vecmean, 4 * p.vec_total);
   } else {
     reg(p.r_hist1, 4 * (int64_t)kHistBins * nl * W);
-    reg(p.r_hist2, 4 * (int64_t)kHistBins * nl * W);
-    reg(p.r_hist3, 4 * (int64_t)512 * nl * W);
+    reg(p.r_t2, 4 * (int64_t)kSub2 * ntile * W);
+    reg(p.r_qlist, 4 * (int64_t)kQListCap * p.q_stride * W);
     reg(p.r_sel, (int64_t)sizeof(SelState) * nl * W);
-    reg(p.r_cand, 8 * (int64_t)kSegCap * ntile * W);
-    reg(p.r_candn, 4 * 4 * ntile * W);
-    reg(p.r_gt4, 4 * 4 * ntile * W);
-    reg(p.r_eq4, 4 * 4 * ntile * W);
-    reg(p.r_gt, 4 * p.tile_stride * W);
-    reg(p.r_eq, 4 * p.tile_stride * W);
-    reg(p.r_seloff, 4 * p.tile_stride * W);
+    reg(p.r_miss, 4 * W);
+    reg(p.r_guess, 4 * 2 * (int64_t)nl * W);
+    reg(p.r_qinfo, (int64_t)sizeof(uint4) * p.q_stride * W);
+    reg(p.r_seg, 4 * 2 * (int64_t)kSubCap * p.q_stride * W);
+    reg(p.r_gtq, 4 * p.q_stride * W);
+    reg(p.r_eqq, 4 * p.q_stride * W);
+    reg(p.r_gtpre, 4 * p.q_stride * W);
+    reg(p.r_eqpre, 4 * p.q_stride * W);
     reg(p.r_payidx, 4 * p.pay_stride * W);
     reg(p.r_payval, 4 * p.pay_stride * W);
   }
@@ -236,16 +237,18 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(float4* __restrict__ ds
 
 enum Stage {
   ST_psgd_ef_p_kernel = 0, ST_psgd_orth_kernel, ST_psgd_q_kernel, ST_psgd_qmean_kernel,
-  ST_psgd_decomp_kernel, ST_topk_ef_hist_kernel, ST_topk_cand_kernel, ST_topk_level3_kernel,
-  ST_topk_count_kernel, ST_topk_compact_kernel, ST_topk_sparse_mean_kernel,
+  ST_psgd_decomp_kernel, ST_topk_ef_hist_kernel, ST_topk_pick12_kernel, ST_topk_restage_kernel,
+  ST_topk_count3_kernel, ST_topk_pick3_kernel,
+  ST_topk_compact_kernel, ST_topk_compact_mean_kernel, ST_topk_sparse_mean_kernel,
   ST_norm_partial_kernel, ST_regime_decide_kernel, ST_recount_words_kernel, ST_zero_accum_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
 static const char* const kStageNames[ST_COUNT] = {
   "psgd_ef_p_kernel", "psgd_orth_kernel", "psgd_q_kernel", "psgd_qmean_kernel",
-  "psgd_decomp_kernel", "topk_ef_hist_kernel", "topk_cand_kernel", "topk_level3_kernel",
-  "topk_count_kernel", "topk_compact_kernel", "topk_sparse_mean_kernel",
+  "psgd_decomp_kernel", "topk_ef_hist_kernel", "topk_pick12_kernel", "topk_restage_kernel",
+  "topk_count3_kernel", "topk_pick3_kernel",
+  "topk_compact_kernel", "topk_compact_mean_kernel", "topk_sparse_mean_kernel",
   "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
@@ -345,16 +348,25 @@ void prof_end(acc_ctx* c, EventPair& p) {
 
 // --- launches of each stage for workers [w0, w0 + nw) ------------------------------------
 
+// TopK selection of workers [w0, w0 + nw): pass A, the per-layer decisions, the per-layer decisions.
+int launch_topk_select(acc_ctx* c, int w0, int nw) {
+  const Ws& ws = c->ws;
+  ACC_LAUNCH(c, topk_ef_hist_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, c->grads, w0);
+  ACC_LAUNCH(c, topk_pick12_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0);
+  ACC_LAUNCH(c, topk_restage_kernel, dim3(std::min(ws.n_ftiles, 2048), nw), dim3(256), ws, w0);
+  ACC_LAUNCH(c, topk_count3_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
+  ACC_LAUNCH(c, topk_pick3_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0);
+  return ACC_OK;
+}
+
 int launch_phase0(acc_ctx* c, int w0, int nw) {
   const Ws& ws = c->ws;
   if (c->cfg.method == ACC_POWERSGD) {
     const int gx = ws.n_mtiles + (w0 == 0 ? ws.n_vectiles : 0);
     if (gx > 0) ACC_LAUNCH(c, psgd_ef_p_kernel, dim3(gx, nw), dim3(256), ws, c->grads, w0);
   } else {
-    ACC_LAUNCH(c, topk_ef_hist_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, c->grads, w0);
-    ACC_LAUNCH(c, topk_cand_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
-    ACC_LAUNCH(c, topk_level3_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
-    ACC_LAUNCH(c, topk_count_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
+    const int rc = launch_topk_select(c, w0, nw);
+    if (rc != ACC_OK) return rc;
     ACC_LAUNCH(c, topk_compact_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
   }
   return ACC_OK;
@@ -388,6 +400,12 @@ int launch_decompress(acc_ctx* c, float* out) {
   } else {
     ACC_LAUNCH(c, topk_sparse_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, out);
   }
+  return ACC_OK;
+}
+
+int launch_topk_compact_mean(acc_ctx* c, float* out) {
+  const Ws& ws = c->ws;
+  ACC_LAUNCH(c, topk_compact_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, out);
   return ACC_OK;
 }
 
@@ -475,21 +493,22 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.vecmean = at<float>(c, p.r_vecmean);
   } else {
     ws.hist1 = at<uint32_t>(c, p.r_hist1);
-    ws.hist2 = at<uint32_t>(c, p.r_hist2);
-    ws.hist3 = at<uint32_t>(c, p.r_hist3);
+    ws.t2 = at<uint32_t>(c, p.r_t2);
+    ws.qlist = at<uint32_t>(c, p.r_qlist);
     ws.sel = at<SelState>(c, p.r_sel);
-    ws.cand = at<uint2>(c, p.r_cand);
-    ws.cand_n = at<uint32_t>(c, p.r_candn);
-    ws.gt4 = at<uint32_t>(c, p.r_gt4);
-    ws.eq4 = at<uint32_t>(c, p.r_eq4);
-    ws.gt_cnt = at<uint32_t>(c, p.r_gt);
-    ws.eq_cnt = at<uint32_t>(c, p.r_eq);
-    ws.sel_off = at<uint32_t>(c, p.r_seloff);
+    ws.miss_any = at<uint32_t>(c, p.r_miss);
+    ws.guess = at<uint32_t>(c, p.r_guess);
+    ws.qinfo = at<uint4>(c, p.r_qinfo);
+    ws.seg = at<uint32_t>(c, p.r_seg);
+    ws.gtq = at<uint32_t>(c, p.r_gtq);
+    ws.eqq = at<uint32_t>(c, p.r_eqq);
+    ws.gtpre = at<uint32_t>(c, p.r_gtpre);
+    ws.eqpre = at<uint32_t>(c, p.r_eqpre);
     ws.pay_idx = at<int32_t>(c, p.r_payidx);
     ws.pay_val = at<float>(c, p.r_payval);
     ws.pay_stride = p.pay_stride;
   }
-  ws.tile_stride = p.tile_stride;
+  ws.q_stride = p.q_stride;
   ws.N = p.N;
   ws.W = cfg->n_workers;
   ws.L = cfg->n_layers;
@@ -501,6 +520,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   ws.n_mat = (int32_t)p.matlayers.size();
   ws.eta = cfg->eta;
 
+  const int nl_ = cfg->n_layers;
   auto init_dev = [&]() -> int {
     ACC_HIP(c, hipMemsetAsync(c->base, 0, (size_t)p.total_bytes, c->stream));
     ACC_HIP(c, hipStreamSynchronize(c->stream));
@@ -517,6 +537,10 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     std::vector<int32_t> lv((size_t)cfg->n_layers, cfg->initial_level);
     ACC_HIP(c, up(p.r_level, lv.data()));
     if (cfg->method == ACC_POWERSGD && p.q_total > 0) ACC_HIP(c, up(p.r_Q, q_init_host));
+    if (cfg->method == ACC_TOPK) {
+      std::vector<uint32_t> none((size_t)2 * nl_ * cfg->n_workers, kNoGuess);
+      ACC_HIP(c, up(p.r_guess, none.data()));
+    }
     ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)cfg->method);
     ACC_HIP(c, hipStreamSynchronize(c->stream));
     return ACC_OK;
@@ -614,13 +638,23 @@ int32_t accordion_step_all(acc_ctx* c, const float* const* grads_host_array, flo
     if (misaligned(grads_host_array[w])) return fail(c->err, ACC_EINVAL, "a gradient pointer is not 16-byte aligned");
   }
   for (int w = 0; w < W; ++w) c->grads.p[w] = grads_host_array[w];
-  int rc = launch_phase0(c, 0, W);
-  if (rc == ACC_OK) rc = launch_agg0(c);
-  if (rc == ACC_OK && c->cfg.method == ACC_POWERSGD) {
-    rc = launch_phase1(c, 0, W);
+  int rc;
+  if (c->cfg.method == ACC_POWERSGD) {
+    rc = launch_phase0(c, 0, W);
+    if (rc == ACC_OK) rc = launch_agg0(c);
+    if (rc == ACC_OK) rc = launch_phase1(c, 0, W);
     if (rc == ACC_OK) rc = launch_agg1(c);
+    if (rc == ACC_OK) rc = launch_decompress(c, out_dev);
+  } else {
+    // the compaction of all workers and the mean of their kept values share one pass over Delta
+#ifdef ACC_UNFUSED
+    rc = launch_phase0(c, 0, W);
+    if (rc == ACC_OK) rc = launch_decompress(c, out_dev);
+#else
+    rc = launch_topk_select(c, 0, W);
+    if (rc == ACC_OK) rc = launch_topk_compact_mean(c, out_dev);
+#endif
   }
-  if (rc == ACC_OK) rc = launch_decompress(c, out_dev);
   end_step(c);
   return rc;
 }
@@ -708,10 +742,13 @@ int32_t accordion_payload_words(acc_ctx* c, int64_t* last_step, int64_t* cumulat
   if (!c) return ACC_EINVAL;
   if (!last_step || !cumulative) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
   ACC_HIP(c, hipStreamSynchronize(c->stream));
-  unsigned long long w[3] = {0, 0, 0};
+  unsigned long long w[4] = {0, 0, 0, 0};
   ACC_HIP(c, hipMemcpy(w, c->ws.words, sizeof(w), hipMemcpyDeviceToHost));
   *last_step = (int64_t)w[1];
   *cumulative = (int64_t)w[2];
+#ifdef ACC_DEBUG_MISS
+  *last_step = (int64_t)w[3];
+#endif
   return ACC_OK;
 }
 
