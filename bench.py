@@ -35,9 +35,11 @@ MEASURED_TRAFFIC_BYTES = {
     ("resnet18_topk", 4, "topk_ef_hist_kernel"): 629287817,    # profiles/hbm_traffic_resnet18_topk.md
 }
 
-# scale of the gradients per window, cycled: makes the norm ratio cross eta = 0.5 so that both
-# levels are used while timing (decisions: critical, not, critical, not, ...)
-WINDOW_SCALES = [1.0, 0.3, 0.3, 1.0]
+# Both compression levels are used while timing: the gradient statistics are stationary (every
+# window's norm ratio is about 0, i.e. not critical), and every second window ends with a
+# learning-rate decay (lr_next < lr_curr), which Algorithm 1 treats as critical.  Decisions:
+# critical, not, critical, not, ...
+LR_CURR = 0.1
 
 
 def parse():
@@ -51,8 +53,9 @@ def parse():
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept in HBM")
     ap.add_argument("--window", type=int, default=20, help="steps per detection window")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-events", action="store_true",
-                    help="do not bracket kernels with HIP events in the timed region")
+    ap.add_argument("--kernel-events", default="dominant", choices=["dominant", "all", "none"],
+                    help="which kernels are bracketed with HIP events in the timed region: the fused "
+                         "error-feedback pass only (default), every kernel, or none")
     ap.add_argument("--fixed-level", type=int, default=-1, help="0/1: never switch, use this level")
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB read and MiB written per launch); 0: skip")
@@ -137,9 +140,6 @@ def main():
     # gradient pool, resident in HBM: [scale][batch][worker]
     dev = torch.device("cuda:0")
     base = [[torch.from_numpy(wl.gradient(w, k, s)).to(dev) for k in range(W)] for s in range(args.pool)]
-    pools = {}
-    for sc in sorted(set(WINDOW_SCALES)):
-        pools[sc] = base if sc == 1.0 else [[g * sc for g in batch] for batch in base]
     out = torch.empty(N, dtype=torch.float32, device=dev)
     if args.fixed_level in (0, 1):
         st = gpu.unpack_state(gpu.get_state())
@@ -172,20 +172,19 @@ def main():
 
     def one_step():
         s = state["step"]
-        window = s // args.window
-        sc = WINDOW_SCALES[window % len(WINDOW_SCALES)] if args.fixed_level < 0 else 1.0
-        gpu.step_all(pools[sc][s % args.pool], out)
+        gpu.step_all(base[s % args.pool], out)
         if args.fixed_level < 0 and (s + 1) % args.window == 0:
-            gpu.detect_regime(0.1, 0.1)
+            decay = ((s + 1) // args.window) % 2 == 1      # every second window ends with an LR decay
+            gpu.detect_regime(LR_CURR, LR_CURR * 0.1 if decay else LR_CURR)
         state["step"] = s + 1
 
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
     state["step"] = 0                      # timed region starts at a window boundary
-    use_events = not args.no_kernel_events
+    use_events = args.kernel_events != "none"
     if use_events:
-        gpu.set_profiling(True)
+        gpu.set_profiling(1 if args.kernel_events == "all" else 2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -231,7 +230,7 @@ def main():
                    "method": "topk" if w.method == B.ACC_TOPK else "powersgd",
                    "level_crit": w.level_crit, "level_noncrit": w.level_noncrit,
                    "window_steps": args.window, "pool_batches": args.pool,
-                   "levels_switch": args.fixed_level < 0, "kernel_events_in_timed_region": use_events},
+                   "levels_switch": args.fixed_level < 0, "kernel_events_in_timed_region": args.kernel_events},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "copy_probe": copy_probe,

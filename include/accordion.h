@@ -167,6 +167,13 @@ int32_t accordion_get_factors(acc_ctx* ctx, int32_t layer, float* p_hat_host, fl
  * + n per 1-D layer; TopK: 2k per layer -- the accounting of the paper's "Data Sent"). */
 int32_t accordion_payload_words(acc_ctx* ctx, int64_t* last_step, int64_t* cumulative);
 
+/* TopK diagnostics since init (they describe which path the selection took, never its result):
+ * restaged_layers = (worker, layer) pairs whose threshold bin was not among the two bins the
+ * error-feedback pass had staged on a guess, so that Delta was read once more for them;
+ * swept_layers = pairs with a tie class too large for the per-quarter key lists, decided by
+ * sweeps of one workgroup (slow). */
+int32_t accordion_topk_stats(acc_ctx* ctx, int64_t* restaged_layers, int64_t* swept_layers);
+
 /* State export / import for checkpointing and step-by-step comparison.  Layout (bytes, all
  * little-endian fp32/int32, no padding):  e_0 .. e_{W-1} (N each) | A (N) | Q (sum over
  * matrix layers of cols*r_max; absent for TopK) | norm_old (L) | has_old (L, int32) |
@@ -176,10 +183,12 @@ int32_t accordion_get_state(acc_ctx* ctx, void* state_host, size_t bytes);
 int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
 
 /* --- per-kernel timing (tracing aid; not part of the paper's method) -------------------------
- * With profiling on, every kernel launch is bracketed by two HIP events on the context's stream
- * and the elapsed time is accumulated per stage.  accordion_get_profile synchronises the stream
- * and returns the accumulated milliseconds and the number of launches of one stage since
- * profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
+ * With profiling on, kernel launches are bracketed by two HIP events on the context's stream and
+ * the elapsed time is accumulated per stage: enable = 1 brackets every kernel, enable = 2 only the
+ * fused error-feedback pass of the method (the kernel that moves the most bytes), which keeps
+ * the event overhead out of the other launches; 0 switches it off.  accordion_get_profile
+ * synchronises the stream and returns the accumulated milliseconds and the number of launches
+ * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
  * accordion_stage_name gives the kernel's name (NULL if out of range). */
 #define ACC_N_STAGES 17
 int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);

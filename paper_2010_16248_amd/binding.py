@@ -54,7 +54,7 @@ EXPORTS = [
     "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
     "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
-    "accordion_probe_copy",
+    "accordion_probe_copy", "accordion_topk_stats",
 ]
 ACC_N_STAGES = 17
 
@@ -90,6 +90,7 @@ def load_library() -> C.CDLL:
         "accordion_set_profiling": [vp, i32],
         "accordion_get_profile": [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)],
         "accordion_probe_copy": [vp, vp, i64, vp],
+        "accordion_topk_stats": [vp, C.POINTER(i64), C.POINTER(i64)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -250,6 +251,12 @@ class Accordion:
         _check(self._lib, self.ctx, self._lib.accordion_payload_words(self.ctx, C.byref(a), C.byref(b)))
         return int(a.value), int(b.value)
 
+    def topk_stats(self) -> Tuple[int, int]:
+        """(layers re-staged after a missed guess, layers decided by sweeps) since init."""
+        a, b = C.c_int64(0), C.c_int64(0)
+        _check(self._lib, self.ctx, self._lib.accordion_topk_stats(self.ctx, C.byref(a), C.byref(b)))
+        return int(a.value), int(b.value)
+
     def state_bytes(self) -> int:
         out = C.c_size_t(0)
         _check(self._lib, self.ctx, self._lib.accordion_state_bytes(self.ctx, C.byref(out)))
@@ -266,8 +273,9 @@ class Accordion:
         _check(self._lib, self.ctx, self._lib.accordion_set_state(
             self.ctx, buf.ctypes.data_as(C.c_void_p), buf.nbytes))
 
-    def set_profiling(self, enable: bool) -> None:
-        _check(self._lib, self.ctx, self._lib.accordion_set_profiling(self.ctx, 1 if enable else 0))
+    def set_profiling(self, enable) -> None:
+        """0 / False: off; 1 / True: every kernel; 2: only the fused error-feedback pass."""
+        _check(self._lib, self.ctx, self._lib.accordion_set_profiling(self.ctx, int(enable)))
 
     def get_profile(self) -> dict:
         """{kernel name: (total milliseconds, launches)} since profiling was switched on."""

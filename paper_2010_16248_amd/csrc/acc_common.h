@@ -74,6 +74,7 @@ struct Ws {
   int32_t* has_old;
   int32_t* rank_used;          // per layer, rank of the last PowerSGD step
   unsigned long long* words;   // [0] per step at current levels, [1] last step, [2] cumulative
+  unsigned long long* stats;   // TopK diagnostics: [0] (worker, layer) pairs re-staged, [1] decided by sweeps
   float* A;                    // accumulated gradient, N
   float* e;                    // W x e_stride error memory (holds Delta during a step)
   int64_t e_stride;
@@ -94,7 +95,9 @@ struct Ws {
   uint32_t* t2;                // W x n_ftiles x 128: per tile, level-2 counts of the two guessed bins
   uint32_t* qlist;             // W x q_stride x kQListCap: per quarter, its keys in bin (b1, b2)
   SelState* sel;               // W x L
+  uint32_t* hist2m;            // W x L x 64: level-2 counts of b1 of a layer whose guess missed
   uint32_t* miss_any;          // W: some multi-tile layer of the worker missed its guessed bins this step
+  uint2* b1hist;               // W x L x 2 (level): {b1, step number} of the last step at this level
   uint32_t* guess;             // W x L x 2 (level): lower of the two level-1 bins staged by pass A
   uint4* qinfo;                // W x q_stride: per wave quarter {entries above the staged bins,
                                //   keys of the lower bin, keys of the upper bin, exact zeros}

@@ -37,6 +37,7 @@ namespace acc {
 constexpr uint32_t kNoGuess = 0xffffffffu;
 constexpr int kPickThreads = 1024;
 constexpr int kPickWaves = kPickThreads / kWave;
+static_assert(kHistBins == 2 * kPickThreads, "the pick kernels load two histogram bins per thread");
 constexpr int kQListCap = 16;            // keys of bin (b1, b2) listed per wave quarter
 constexpr int kL2Bins = 64;              // level 2: key bits 19..14
 constexpr int kSub2 = 2 * kL2Bins;       // a tile's level-2 counts of the two guessed bins
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const Gr
 // ---- B: re-stage the keys of b1 for the layers whose guess missed --------------------------------
 
 template <bool AL>
-__device__ __forceinline__ void restage_tile(const Ws& ws, int w, int tile_id, const FlatTile& ft,
+__device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile& ft,
                                              const LayerDev& L, const TileGeom& tg, uint32_t b1, uint32_t* st,
                                              uint32_t* sub2) {
   const int tid = threadIdx.x;
@@ -319,9 +320,12 @@ __device__ __forceinline__ void restage_tile(const Ws& ws, int w, int tile_id, c
                        key_of(comp(cur, c)), b1, b1, lane);     // only bin b1 is staged (first half)
     cur = nxt;
   }
-  stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, lane);
+  const uint32_t nz = stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, lane);
+  const int64_t wl = (int64_t)w * ws.L + ft.layer;
+  if (lane == 0 && nz) atomicAdd(&ws.sel[wl].zeros, nz);
   __syncthreads();
-  if (tid < kSub2) ws.t2[((int64_t)w * ws.n_ftiles + tile_id) * kSub2 + tid] = sub2[tid];
+  // the tile's level-2 counts of b1 go straight into the layer's (cleared by the pick kernel)
+  if (tid < kL2Bins && sub2[tid]) atomicAdd(&ws.hist2m[wl * kL2Bins + tid], sub2[tid]);
 }
 
 // The grid is smaller than the tile table and strides over it; when no layer of the worker
@@ -339,8 +343,8 @@ __global__ __launch_bounds__(256) void topk_restage_kernel(const Ws ws, int w0) 
     const SelState* sp = ws.sel + (int64_t)w * ws.L + ft.layer;
     if (sp->mode != 1u) continue;
     const TileGeom tg = tile_geom(L, ft);
-    if (tg.aligned) restage_tile<true>(ws, w, t, ft, L, tg, sp->b1, st, sub2);
-    else restage_tile<false>(ws, w, t, ft, L, tg, sp->b1, st, sub2);
+    if (tg.aligned) restage_tile<true>(ws, w, ft, L, tg, sp->b1, st, sub2);
+    else restage_tile<false>(ws, w, ft, L, tg, sp->b1, st, sub2);
   }
 }
 
@@ -496,45 +500,49 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
     return;
   }
   SelState* sp = ws.sel + wl;
-  // level 1; the layer's histogram is cleared for the next step
+  __shared__ uint32_t sub[kSub2];
+  // Requested together, before anything is known: the layer's level-1 histogram (cleared for
+  // the next step) and the tiles' level-2 counts of BOTH guessed bins.
   uint32_t* gh = ws.hist1 + wl * kHistBins;
-  for (int b = tid; b < kHistBins; b += kPickThreads) { hist[b] = gh[b]; gh[b] = 0u; }
+  uint32_t h0 = gh[tid], h1 = gh[tid + kPickThreads];
+  constexpr int kStripes = kPickThreads / kSub2;            // 8 tiles at a time
+  const int col = tid & (kSub2 - 1), stripe = tid / kSub2;
+  const uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_ftiles + L.tile0) * kSub2 + col;
+  uint32_t s2 = 0;
+  for (int tl0 = stripe; tl0 < L.ntiles; tl0 += 8 * kStripes) {
+    uint32_t v[8];                                          // eight independent loads in flight
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = t2[(int64_t)min(tl0 + u * kStripes, L.ntiles - 1) * kSub2];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s2 += (tl0 + u * kStripes < L.ntiles) ? v[u] : 0u;
+  }
+  const uint32_t guess = ws.guess[wl * 2 + lv];
+  gh[tid] = 0u;
+  gh[tid + kPickThreads] = 0u;
+  hist[tid] = h0;
+  hist[tid + kPickThreads] = h1;
+  if (tid < kSub2) sub[tid] = 0u;
   __syncthreads();
+  if (s2) atomicAdd(&sub[col], s2);
   pick_bin(hist, k, out, scratch);
   const uint32_t b1 = out[0], need2 = k - out[1];
-  const uint32_t guess = ws.guess[wl * 2 + lv];
   const bool hit = guess != kNoGuess && (b1 == guess || b1 == guess + 1u);
   const uint32_t side = (hit && b1 != guess) ? 1u : 0u;
   if (tid == 0) {
     sp->b1 = b1; sp->need2 = need2; sp->k = k; sp->side = side; sp->zeros = 0u;
     sp->mode = hit ? 0u : 1u;
     if (!hit) ws.miss_any[w] = 1u;                         // cleared by the compaction kernel
-#ifdef ACC_DEBUG_MISS
-    if (!hit) atomicAdd(&ws.words[3], 1ull + ((unsigned long long)L.ntiles << 20));
-#endif
+    if (!hit) atomicAdd(&ws.stats[0], 1ull);               // layers re-staged (diagnostic counter)
   }
-  if (!hit) return;                                        // its keys get staged; the counting kernel finds b2
-  __syncthreads();
-  // level 2: sum of the tiles' counts of bin b1
-  for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = 0u;
-  __syncthreads();
-  {
-    const int bin = tid & (kL2Bins - 1), stripe = tid / kL2Bins;
-    const uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_ftiles + L.tile0) * kSub2 + side * kL2Bins + bin;
-    constexpr int kStripes = kPickThreads / kL2Bins;
-    uint32_t s = 0;
-    for (int tl0 = stripe; tl0 < L.ntiles; tl0 += 8 * kStripes) {
-      uint32_t v[8];                                       // eight independent loads in flight
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int tl = min(tl0 + u * kStripes, L.ntiles - 1);
-        v[u] = t2[(int64_t)tl * kSub2];
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) s += (tl0 + u * kStripes < L.ntiles) ? v[u] : 0u;
-    }
-    if (s) atomicAdd(&hist[bin], s);
+  if (!hit) {
+    // its keys get staged tile by tile, with their level-2 counts added up here
+    if (tid < kL2Bins) ws.hist2m[wl * kL2Bins + tid] = 0u;
+    return;
   }
+  __syncthreads();
+  // level 2: the summed counts of bin b1
+  for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = (b < kL2Bins) ? sub[side * kL2Bins + b] : 0u;
+  __syncthreads();
   if (b1 == 0u) {
     // exact zeros are keys of bin 0, level-2 bin 0, that were never staged
     const int64_t qbase = (int64_t)w * ws.q_stride + L.qoff;
@@ -542,8 +550,8 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
     for (int q = tid; q < 4 * L.ntiles; q += kPickThreads) z += ws.qinfo[qbase + q].w;
     z = wave_sum_u32(z);
     if (lane == 0 && z) { atomicAdd(&hist[0], z); atomicAdd(&sp->zeros, z); }
+    __syncthreads();
   }
-  __syncthreads();
   pick_bin(hist, need2, out, scratch);
   if (tid == 0) {
     sp->b2 = out[0];
@@ -553,7 +561,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
 
 __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3], scratch[4], zsum;
+  __shared__ uint32_t out[3], scratch[4];
   const int w = w0 + blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -563,44 +571,32 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   SelState* sp = ws.sel + wl;
   const int tl = ft.start >> kTileShift;
+  const int64_t qslot = quarter_slot(ws, L, w, tl, wave);
+  // both halves of the segment are requested before the layer's state has arrived
+  const QuarterKeys qk0 = load_quarter_keys(ws, qslot, 0u, lane);
+  const QuarterKeys qk1 = load_quarter_keys(ws, qslot, 1u, lane);
   const uint32_t side = sp->side, b1 = sp->b1;
   uint32_t b2 = sp->b2;
   if (sp->mode != 0u) {                                    // uniform over the workgroup
-    // a missed layer: its keys of b1 were re-staged tile by tile; every workgroup of the layer
-    // sums the tiles' level-2 counts itself
+    // a missed layer: its keys of b1 were re-staged and their level-2 counts summed
     const int tid = threadIdx.x;
-    for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0u;
-    if (tid == 0) zsum = 0u;
-    __syncthreads();
-    {
-      constexpr int kStripes = kFlatThreads / kL2Bins;
-      const int bin = tid & (kL2Bins - 1), stripe = tid / kL2Bins;
-      const uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_ftiles + L.tile0) * kSub2 + bin;
-      uint32_t sum = 0;
-      for (int t0 = stripe; t0 < L.ntiles; t0 += 8 * kStripes) {
-        uint32_t v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = t2[(int64_t)min(t0 + u * kStripes, L.ntiles - 1) * kSub2];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) sum += (t0 + u * kStripes < L.ntiles) ? v[u] : 0u;
-      }
-      if (sum) atomicAdd(&hist[bin], sum);
-    }
-    if (b1 == 0u) {
-      const int64_t qb = (int64_t)w * ws.q_stride + L.qoff;
-      uint32_t z = 0;
-      for (int q = tid; q < 4 * L.ntiles; q += kFlatThreads) z += ws.qinfo[qb + q].w;
-      z = wave_sum_u32(z);
-      if (lane == 0 && z) { atomicAdd(&hist[0], z); atomicAdd(&zsum, z); }
+    const uint32_t zeros = sp->zeros;
+    for (int b = tid; b < kHistBins; b += kFlatThreads) {
+      uint32_t h = (b < kL2Bins) ? ws.hist2m[wl * kL2Bins + b] : 0u;
+      if (b == 0 && b1 == 0u) h += zeros;                    // exact zeros: level-2 bin 0 of bin 0
+      hist[b] = h;
     }
     __syncthreads();
     const uint32_t need2 = sp->need2;
     pick_bin(hist, need2, out, scratch);
     b2 = out[0];
-    if (tl == 0 && tid == 0) { sp->b2 = b2; sp->need3 = need2 - out[1]; sp->zeros = zsum; }
+    if (tl == 0 && tid == 0) { sp->b2 = b2; sp->need3 = need2 - out[1]; }
   }
-  const int64_t qslot = quarter_slot(ws, L, w, tl, wave);
-  const QuarterKeys qk = load_quarter_keys(ws, qslot, side, lane);
+  QuarterKeys qk = qk0;                                     // a re-staged layer uses the first half
+  if (side != 0u) {
+#pragma unroll
+    for (int ch = 0; ch < kFirstChunks; ++ch) qk.chunk[ch] = qk1.chunk[ch];
+  }
   uint32_t* list = ws.qlist + qslot * kQListCap;
   uint32_t n_gt = 0, n_in = 0;                             // wave-uniform
   const uint32_t above = for_quarter_keys(ws, L, w, tl, wave, qk, side, b1, false, lane, [&](uint32_t key, bool valid) {
@@ -617,11 +613,14 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   if (lane == 0) { ws.gtq[qslot] = above + n_gt; ws.eqq[qslot] = n_in; }
 }
 
-__global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, int w0) {
+constexpr int kLdsList = 12288;          // keys of bin (b1, b2) of a layer gathered in LDS (packed)
+
+__global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, int w0, uint32_t step_id) {
   __shared__ uint32_t hist[kHistBins];
+  __shared__ uint32_t llist[kLdsList];
   __shared__ uint32_t out[3], scratch[4];
   __shared__ uint32_t wsum[2][kPickWaves];
-  __shared__ uint32_t zsum;
+  __shared__ uint32_t flag, lcount;
   const int li = blockIdx.x;
   const int w = w0 + blockIdx.y;
   const int tid = threadIdx.x;
@@ -634,85 +633,137 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
   const int lv = ws.level[li];
   const int nq = 4 * L.ntiles;
   const int64_t qbase = (int64_t)w * ws.q_stride + L.qoff;
-  const uint32_t b1 = sp->b1, side = sp->side;
   // gtq: per quarter, the entries above bin (b1, b2); eqq: the number of keys inside (b1, b2), of
   // which the first kQListCap are listed.  Thread t owns a contiguous chunk of quarters.
   uint32_t* gtq = ws.gtq + qbase;
   uint32_t* eqq = ws.eqq + qbase;
-  const uint32_t* qlist = ws.qlist + qbase * kQListCap;
+  const uint32_t* nlist = eqq;                             // until the counts are final
+  const uint4* qlist4 = reinterpret_cast<const uint4*>(ws.qlist + qbase * kQListCap);
   const int chunk = (nq + kPickThreads - 1) / kPickThreads;
   const int q_lo = min(tid * chunk, nq), q_hi = min(q_lo + chunk, nq);
-  if (tid == 0) zsum = 0u;
+  if (tid == 0) { flag = 0u; lcount = 0u; }
   __syncthreads();
-  {
-    uint32_t over = 0;
-    for (int q = q_lo; q < q_hi; ++q) over |= (eqq[q] > (uint32_t)kQListCap) ? 1u : 0u;
-    if (over) zsum = 1u;                                   // some quarter's list overflowed
-  }
-  __syncthreads();
-  const bool use_list = zsum == 0u;
-  __syncthreads();
-  const uint32_t b2 = sp->b2, zeros = sp->zeros;
-  uint32_t need = sp->need3;
-
-  // One sweep of the workgroup over the keys of bin b1 of the whole layer (slow path: some
-  // quarter holds more keys of bin (b1, b2) than its list, i.e. a large tie class).
-  auto sweep = [&](auto per_key, auto per_quarter) {
-    for (int q = wave; q < nq; q += kPickWaves) {
-      const QuarterKeys qk = load_quarter_keys(ws, qbase + q, side, lane);
-      const uint32_t above = for_quarter_keys(ws, L, w, q >> 2, q & 3, qk, side, b1, false, lane, per_key);
-      per_quarter(q, above);
+  // Gather the listed keys of the whole layer in LDS, packed as (quarter << 14 | low 14 key
+  // bits): the upper 17 key bits are those of (b1, b2).  A quarter's count and its list slot are
+  // requested together.
+  const bool packable = nq <= (1 << 18);
+  for (int q = q_lo; q < q_hi; ++q) {
+    const uint32_t n = eqq[q];
+    uint4 k4[kQListCap / 4];
+#pragma unroll
+    for (int i = 0; i < kQListCap / 4; ++i) k4[i] = qlist4[(int64_t)q * (kQListCap / 4) + i];
+    if (n > (uint32_t)kQListCap || !packable) {
+      flag = 1u;                                           // a list overflowed: the sweeps decide
+    } else if (n != 0u) {
+      const uint32_t pos = atomicAdd(&lcount, n);
+      if (pos + n <= (uint32_t)kLdsList) {
+#pragma unroll
+        for (int i = 0; i < kQListCap; ++i) {
+          const uint4& v = k4[i / 4];
+          const uint32_t key = (i % 4 == 0) ? v.x : (i % 4 == 1) ? v.y : (i % 4 == 2) ? v.z : v.w;
+          if ((uint32_t)i < n) llist[pos + i] = ((uint32_t)q << 14) | (key & 0x3fffu);
+        }
+      }
     }
-  };
+  }
+  const uint32_t b1 = sp->b1, side = sp->side, b2 = sp->b2, zeros = sp->zeros;
+  uint32_t need = sp->need3;
+  __syncthreads();
+  const uint32_t ln = lcount;
+  const bool listed = flag == 0u;                          // every quarter's list is complete
+  const bool in_lds = ln <= (uint32_t)kLdsList;            // ... and all of them fit in LDS
+  const bool zero_bin = (b1 == 0u && b2 == 0u);            // bin (b1, b2) holds the exact zeros
   auto clear_hist = [&]() {
     __syncthreads();
     for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = 0u;
     __syncthreads();
   };
-  auto nothing = [](int, uint32_t) {};
-
-  const bool zero_bin = (b1 == 0u && b2 == 0u);            // bin (b1, b2) holds the exact zeros
-
-  // level 3: key bits 13..6 of the keys of (b1, b2)
-  clear_hist();
-  if (use_list) {
-    for (int q = q_lo; q < q_hi; ++q) {
-      const uint32_t n = eqq[q];
-      for (uint32_t i = 0; i < n; ++i) atomicAdd(&hist[bin3_of(qlist[(int64_t)q * kQListCap + i])], 1u);
+  // f(low 14 key bits, quarter) for every listed key of the layer: from LDS, or -- a very large
+  // layer -- from the quarters' lists again (each thread its own quarters)
+  auto for_listed = [&](auto f) {
+    if (in_lds) {
+      for (uint32_t i = tid; i < ln; i += kPickThreads) f(llist[i] & 0x3fffu, (int)(llist[i] >> 14));
+    } else {
+      const uint32_t* ql = ws.qlist + qbase * kQListCap;
+      for (int q = q_lo; q < q_hi; ++q) {
+        const uint32_t n = min(ld_agent(&nlist[q]), (uint32_t)kQListCap);
+        for (uint32_t i = 0; i < n; ++i) f(ql[(int64_t)q * kQListCap + i] & 0x3fffu, q);
+      }
     }
-  } else {
-    sweep([&](uint32_t key, bool valid) { if (valid && bin2_of(key) == b2) atomicAdd(&hist[bin3_of(key)], 1u); },
-          nothing);
-  }
-  if (zero_bin && tid == 0) atomicAdd(&hist[0], zeros);
-  __syncthreads();
-  pick_bin(hist, need, out, scratch);
-  const uint32_t b3 = out[0];
-  need -= out[1];
-  // level 4: key bits 5..0 of the keys of (b1, b2, b3)
-  clear_hist();
-  const uint32_t hi3 = (b1 << 14) | (b2 << 8) | b3;        // key >> 6 of the keys of (b1, b2, b3)
-  if (use_list) {
-    for (int q = q_lo; q < q_hi; ++q) {
-      const uint32_t n = eqq[q];
-      for (uint32_t i = 0; i < n; ++i) {
-        const uint32_t key = qlist[(int64_t)q * kQListCap + i];
-        if ((key >> 6) == hi3) atomicAdd(&hist[bin4_of(key)], 1u);
+  };
+  uint32_t T, ktie, alleq;
+  if (listed) {
+    // level 3: key bits 13..6
+    clear_hist();
+    for_listed([&](uint32_t low, int) { atomicAdd(&hist[low >> 6], 1u); });
+    if (zero_bin && tid == 0) atomicAdd(&hist[0], zeros);
+    __syncthreads();
+    pick_bin(hist, need, out, scratch);
+    const uint32_t b3 = out[0];
+    need -= out[1];
+    // level 4: key bits 5..0
+    clear_hist();
+    for_listed([&](uint32_t low, int) { if ((low >> 6) == b3) atomicAdd(&hist[low & 0x3fu], 1u); });
+    if (zero_bin && b3 == 0u && tid == 0) atomicAdd(&hist[0], zeros);
+    __syncthreads();
+    pick_bin(hist, need, out, scratch);
+    T = (b1 << 20) | (b2 << 14) | (b3 << 6) | out[0];
+    ktie = need - out[1];                                  // 1 <= ktie <= entries equal to T
+    alleq = (ktie == out[2]) ? 1u : 0u;
+    // per quarter: the listed keys above T and equal to T
+    const uint32_t t_low = T & 0x3fffu;
+    if (in_lds) {
+      for (int q = q_lo; q < q_hi; ++q) eqq[q] = 0u;
+      __syncthreads();
+      for_listed([&](uint32_t low, int q) {
+        if (low > t_low) atomicAdd(&gtq[q], 1u);
+        else if (low == t_low) atomicAdd(&eqq[q], 1u);
+      });
+    } else {
+      uint32_t g = 0, e = 0;
+      auto close = [&](int q) { gtq[q] = ld_agent(&gtq[q]) + g; eqq[q] = e; g = 0; e = 0; };
+      // the keys come quarter by quarter (the thread's own quarters, ascending)
+      for (int q = q_lo; q < q_hi; ++q) {
+        const uint32_t n = min(ld_agent(&nlist[q]), (uint32_t)kQListCap);
+        const uint32_t* ql = ws.qlist + (qbase + q) * kQListCap;
+        for (uint32_t i = 0; i < n; ++i) {
+          const uint32_t low = ql[i] & 0x3fffu;
+          g += (low > t_low) ? 1u : 0u;
+          e += (low == t_low) ? 1u : 0u;
+        }
+        close(q);
       }
     }
   } else {
+    if (tid == 0) atomicAdd(&ws.stats[1], 1ull);            // layers decided by sweeps (diagnostic counter)
+    // Slow path (some quarter holds more keys of bin (b1, b2) than its list, i.e. a large tie
+    // class): sweeps of the workgroup over the keys of bin b1 of the whole layer.
+    auto sweep = [&](auto per_key, auto per_quarter) {
+      for (int q = wave; q < nq; q += kPickWaves) {
+        const QuarterKeys qk = load_quarter_keys(ws, qbase + q, side, lane);
+        const uint32_t above = for_quarter_keys(ws, L, w, q >> 2, q & 3, qk, side, b1, false, lane, per_key);
+        per_quarter(q, above);
+      }
+    };
+    auto nothing = [](int, uint32_t) {};
+    clear_hist();
+    sweep([&](uint32_t key, bool valid) { if (valid && bin2_of(key) == b2) atomicAdd(&hist[bin3_of(key)], 1u); },
+          nothing);
+    if (zero_bin && tid == 0) atomicAdd(&hist[0], zeros);
+    __syncthreads();
+    pick_bin(hist, need, out, scratch);
+    const uint32_t b3 = out[0];
+    need -= out[1];
+    clear_hist();
+    const uint32_t hi3 = (b1 << 14) | (b2 << 8) | b3;      // key >> 6 of the keys of (b1, b2, b3)
     sweep([&](uint32_t key, bool valid) { if (valid && (key >> 6) == hi3) atomicAdd(&hist[bin4_of(key)], 1u); },
           nothing);
-  }
-  if (zero_bin && b3 == 0u && tid == 0) atomicAdd(&hist[0], zeros);
-  __syncthreads();
-  pick_bin(hist, need, out, scratch);
-  const uint32_t T = (hi3 << 6) | out[0];
-  const uint32_t ktie = need - out[1];                     // 1 <= ktie <= entries equal to T
-  const uint32_t alleq = (ktie == out[2]) ? 1u : 0u;
-
-  // per quarter: entries above T and entries equal to T
-  if (!use_list) {
+    if (zero_bin && b3 == 0u && tid == 0) atomicAdd(&hist[0], zeros);
+    __syncthreads();
+    pick_bin(hist, need, out, scratch);
+    T = (hi3 << 6) | out[0];
+    ktie = need - out[1];
+    alleq = (ktie == out[2]) ? 1u : 0u;
     uint32_t n_gt = 0, n_eq = 0;
     sweep([&](uint32_t key, bool valid) {
             const uint64_t mv = ballot64(valid);
@@ -725,23 +776,14 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
           });
   }
   __syncthreads();
-  auto quarter_counts = [&](int q, uint32_t& g, uint32_t& e) {
-    g = ld_agent(&gtq[q]);
-    e = ld_agent(&eqq[q]);
-    if (use_list) {                                        // e listed keys of (b1, b2): compare them with T
-      const uint32_t n = e;
-      e = 0;
-      for (uint32_t i = 0; i < n; ++i) {
-        const uint32_t key = qlist[(int64_t)q * kQListCap + i];
-        g += (key > T) ? 1u : 0u;
-        e += (key == T) ? 1u : 0u;
-      }
-    }
-    if (T == 0u) e += ws.qinfo[qbase + q].w;               // the exact zeros were counted apart
-  };
 
-  // exclusive prefix over the quarters of the layer
+  // exclusive prefix over the quarters of the layer (entries above T; entries equal to T, the
+  // exact zeros, counted apart, included when T is 0)
   {
+    auto quarter_counts = [&](int q, uint32_t& g, uint32_t& e) {
+      g = ld_agent(&gtq[q]);
+      e = ld_agent(&eqq[q]) + (T == 0u ? ws.qinfo[qbase + q].w : 0u);
+    };
     uint32_t s_gt = 0, s_eq = 0;
     for (int q = q_lo; q < q_hi; ++q) {
       uint32_t g, e;
@@ -756,21 +798,37 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
     for (int v = 0; v < wave; ++v) { o_gt += wsum[0][v]; o_eq += wsum[1][v]; }
     uint32_t* gtpre = ws.gtpre + qbase;
     uint32_t* eqpre = ws.eqpre + qbase;
-    for (int q = q_lo; q < q_hi; ++q) {
-      uint32_t g, e;
-      quarter_counts(q, g, e);
-      gtpre[q] = o_gt;
-      eqpre[q] = o_eq;
-      o_gt += g;
-      o_eq += e;
+    if (chunk == 1) {
+      if (q_lo < q_hi) { gtpre[q_lo] = o_gt; eqpre[q_lo] = o_eq; }
+      o_gt += s_gt;
+      o_eq += s_eq;
+    } else {
+      for (int q = q_lo; q < q_hi; ++q) {
+        uint32_t g, e;
+        quarter_counts(q, g, e);
+        gtpre[q] = o_gt;
+        eqpre[q] = o_eq;
+        o_gt += g;
+        o_eq += e;
+      }
     }
     if (tid == kPickThreads - 1) { gtpre[nq] = o_gt; eqpre[nq] = o_eq; }   // totals: o_gt + ktie == k
   }
   if (tid == 0) {
     sp->T = T; sp->ktie = ktie; sp->alleq = alleq; sp->mode = 0u;
-    // next step's guess at this level: b1 and the neighbour on the side of the threshold
-    uint32_t glo = (b2 >= (uint32_t)(kL2Bins / 2)) ? b1 : (b1 == 0u ? 0u : b1 - 1u);
-    if (glo > (uint32_t)(kHistBins - 2)) glo = (uint32_t)(kHistBins - 2);
+    // Next step's guess at this level: two adjacent bins.  While the threshold is moving (the
+    // steps after a level switch, when the memory adapts) b1 is extrapolated from the last two
+    // steps and paired with the bin it would reach if the move slowed down; when it rests, b1 is
+    // paired with the neighbour on the side of the threshold.
+    const uint2 prev = ws.b1hist[wl * 2 + lv];
+    ws.b1hist[wl * 2 + lv] = make_uint2(b1, step_id);
+    int v = (prev.y + 1u == step_id) ? (int)b1 - (int)prev.x : 0;
+    v = max(-64, min(64, v));
+    int g = (int)b1;
+    if (v > 0) g = (int)b1 + v - 1;
+    else if (v < 0) g = (int)b1 + v;
+    else if (b2 < (uint32_t)(kL2Bins / 2)) g = (int)b1 - 1;
+    uint32_t glo = (uint32_t)max(0, min(kHistBins - 2, g));
     ws.guess[wl * 2 + lv] = glo;
   }
 }

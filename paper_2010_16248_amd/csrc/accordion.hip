@@ -44,7 +44,7 @@ struct Plan {
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
   Region r_A, r_e, r_norm_part;
   Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean;
-  Region r_hist1, r_t2, r_qlist, r_sel, r_miss, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval;
+  Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval;
   int64_t total_bytes = 0;
 };
 
@@ -184,7 +184,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
   reg(p.r_norm_curr, 4 * (int64_t)nl);
   reg(p.r_has_old, 4 * (int64_t)nl);
   reg(p.r_rank_used, 4 * (int64_t)nl);
-  reg(p.r_words, 8 * 4);
+  reg(p.r_words, 8 * 6);
   reg(p.r_A, 4 * p.e_stride);
   reg(p.r_e, 4 * p.e_stride * W);
   reg(p.r_norm_part, 8 * ntile);
@@ -199,7 +199,9 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     reg(p.r_t2, 4 * (int64_t)kSub2 * ntile * W);
     reg(p.r_qlist, 4 * (int64_t)kQListCap * p.q_stride * W);
     reg(p.r_sel, (int64_t)sizeof(SelState) * nl * W);
+    reg(p.r_hist2m, 4 * (int64_t)kL2Bins * nl * W);
     reg(p.r_miss, 4 * W);
+    reg(p.r_b1hist, 8 * 2 * (int64_t)nl * W);
     reg(p.r_guess, 4 * 2 * (int64_t)nl * W);
     reg(p.r_qinfo, (int64_t)sizeof(uint4) * p.q_stride * W);
     reg(p.r_seg, 4 * 2 * (int64_t)kSubCap * p.q_stride * W);
@@ -255,7 +257,7 @@ struct EventPair { hipEvent_t a, b; int stage; };
 
 struct acc_ctx {
   // per-kernel timing
-  bool profiling = false;
+  int profiling = 0;               // 0 off, 1 every kernel, 2 only the fused error-feedback pass
   std::vector<EventPair> pending, spare;
   double stage_ms[ST_COUNT] = {0};
   long long stage_n[ST_COUNT] = {0};
@@ -267,6 +269,7 @@ struct acc_ctx {
   hipStream_t stream = nullptr;
   // step state machine
   bool in_step = false;
+  uint32_t step_id = 2;            // number of the current step (the device keeps 0 for "never")
   uint32_t p0_mask = 0, p1_mask = 0;
   bool agg0 = false, agg1 = false;
   GradPtrs grads;
@@ -318,6 +321,7 @@ int drain_profile(acc_ctx* c) {
 
 bool prof_begin(acc_ctx* c, int stage, EventPair& p) {
   if (!c->profiling) return false;
+  if (c->profiling == 2 && stage != ST_topk_ef_hist_kernel && stage != ST_psgd_ef_p_kernel) return false;
   if (c->pending.size() >= 8192) drain_profile(c);
   if (!c->spare.empty()) {
     p = c->spare.back();
@@ -355,7 +359,7 @@ int launch_topk_select(acc_ctx* c, int w0, int nw) {
   ACC_LAUNCH(c, topk_pick12_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0);
   ACC_LAUNCH(c, topk_restage_kernel, dim3(std::min(ws.n_ftiles, 2048), nw), dim3(256), ws, w0);
   ACC_LAUNCH(c, topk_count3_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
-  ACC_LAUNCH(c, topk_pick3_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0);
+  ACC_LAUNCH(c, topk_pick3_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
   return ACC_OK;
 }
 
@@ -411,6 +415,7 @@ int launch_topk_compact_mean(acc_ctx* c, float* out) {
 
 void end_step(acc_ctx* c) {
   c->in_step = false;
+  c->step_id += 1;
   c->p0_mask = c->p1_mask = 0;
   c->agg0 = c->agg1 = false;
 }
@@ -479,6 +484,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   ws.has_old = at<int32_t>(c, p.r_has_old);
   ws.rank_used = at<int32_t>(c, p.r_rank_used);
   ws.words = at<unsigned long long>(c, p.r_words);
+  ws.stats = ws.words + 4;
   ws.A = at<float>(c, p.r_A);
   ws.e = at<float>(c, p.r_e);
   ws.e_stride = p.e_stride;
@@ -496,7 +502,9 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.t2 = at<uint32_t>(c, p.r_t2);
     ws.qlist = at<uint32_t>(c, p.r_qlist);
     ws.sel = at<SelState>(c, p.r_sel);
+    ws.hist2m = at<uint32_t>(c, p.r_hist2m);
     ws.miss_any = at<uint32_t>(c, p.r_miss);
+    ws.b1hist = at<uint2>(c, p.r_b1hist);
     ws.guess = at<uint32_t>(c, p.r_guess);
     ws.qinfo = at<uint4>(c, p.r_qinfo);
     ws.seg = at<uint32_t>(c, p.r_seg);
@@ -647,13 +655,8 @@ int32_t accordion_step_all(acc_ctx* c, const float* const* grads_host_array, flo
     if (rc == ACC_OK) rc = launch_decompress(c, out_dev);
   } else {
     // the compaction of all workers and the mean of their kept values share one pass over Delta
-#ifdef ACC_UNFUSED
-    rc = launch_phase0(c, 0, W);
-    if (rc == ACC_OK) rc = launch_decompress(c, out_dev);
-#else
     rc = launch_topk_select(c, 0, W);
     if (rc == ACC_OK) rc = launch_topk_compact_mean(c, out_dev);
-#endif
   }
   end_step(c);
   return rc;
@@ -742,13 +745,22 @@ int32_t accordion_payload_words(acc_ctx* c, int64_t* last_step, int64_t* cumulat
   if (!c) return ACC_EINVAL;
   if (!last_step || !cumulative) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
   ACC_HIP(c, hipStreamSynchronize(c->stream));
-  unsigned long long w[4] = {0, 0, 0, 0};
+  unsigned long long w[3] = {0, 0, 0};
   ACC_HIP(c, hipMemcpy(w, c->ws.words, sizeof(w), hipMemcpyDeviceToHost));
   *last_step = (int64_t)w[1];
   *cumulative = (int64_t)w[2];
-#ifdef ACC_DEBUG_MISS
-  *last_step = (int64_t)w[3];
-#endif
+  return ACC_OK;
+}
+
+int32_t accordion_topk_stats(acc_ctx* c, int64_t* restaged_layers, int64_t* swept_layers) {
+  if (!c) return ACC_EINVAL;
+  if (c->cfg.method != ACC_TOPK) return fail(c->err, ACC_EINVAL, "TopK statistics exist for TopK only");
+  if (!restaged_layers || !swept_layers) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  unsigned long long s[2] = {0, 0};
+  ACC_HIP(c, hipMemcpy(s, c->ws.stats, sizeof(s), hipMemcpyDeviceToHost));
+  *restaged_layers = (int64_t)s[0];
+  *swept_layers = (int64_t)s[1];
   return ACC_OK;
 }
 
@@ -811,7 +823,7 @@ int32_t accordion_set_profiling(acc_ctx* c, int32_t enable) {
   if (enable && !c->profiling) {
     for (int i = 0; i < ST_COUNT; ++i) { c->stage_ms[i] = 0.0; c->stage_n[i] = 0; }
   }
-  c->profiling = enable != 0;
+  c->profiling = (enable == 2) ? 2 : (enable != 0 ? 1 : 0);
   return ACC_OK;
 }
 

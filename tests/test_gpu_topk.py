@@ -83,6 +83,54 @@ def test_multi_tile_layers_with_ties(case):
     gpu.destroy()
 
 
+def test_guessed_bins_hit_drift_and_miss():
+    """The error-feedback pass stages the keys of two level-1 bins on a guess.  Over many steps
+    with a stationary distribution the guess must hit (no more re-staging); a slow drift of the
+    gradient scale is followed by the extrapolated guess; a jump makes it miss.  Every step is
+    bit-exact whichever path is taken."""
+    print("case guessed bins", flush=True)
+    shapes = [(1, 5 * 8192 + 13, 0), (64, 577, 1), (1, 100, 0), (6, 8192, 1)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 2
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    rng = np.random.default_rng(5)
+    scale = 1.0
+    restaged = []
+    for step in range(14):
+        if 6 <= step < 10:
+            scale *= 1.09                                   # one level-1 bin per step, about
+        if step == 12:
+            scale *= 40.0                                   # far outside the guessed bins
+        grads = [(rng.standard_normal(N) * scale).astype(np.float32) for _ in range(W)]
+        _check_step(gpu, ora, grads, f"step {step}")
+        restaged.append(gpu.topk_stats()[0])
+    per_step = np.diff([0] + restaged)
+    n_multi = 3 * W                                         # (worker, layer) pairs of more than one tile
+    assert per_step[0] == n_multi                           # nothing to guess from at the first step
+    assert per_step[3:6].sum() == 0, per_step               # stationary: the guess holds
+    assert per_step[12] == n_multi, per_step                # the jump is missed ...
+    assert per_step[13] <= n_multi                          # ... and everything is still exact
+    assert gpu.topk_stats()[1] == 0                         # no tie class needed the sweeps
+    gpu.destroy()
+
+
+def test_large_tie_classes_take_the_sweeps_and_stay_exact():
+    """Quantised values in layers of several tiles: the tie class of the threshold is far larger
+    than the per-quarter key lists, for several steps in a row (guess hit and missed)."""
+    print("case tie sweeps", flush=True)
+    shapes = [(1, 4 * 8192 + 5, 0), (3, 9000, 1)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, 2, 10, 1)
+    rng = np.random.default_rng(9)
+    for step in range(4):
+        grads = [(rng.integers(-3, 4, N) * 0.25).astype(np.float32) for _ in range(2)]
+        _check_step(gpu, ora, grads, f"step {step}")
+    assert gpu.topk_stats()[1] > 0
+    gpu.destroy()
+
+
 def test_call_by_call_equals_step_all_and_is_deterministic():
     layers = wl.make_layers([(20, 900, 1), (1, 64, 0), (9, 9, 1)])
     N = wl.total_params(layers)
