@@ -189,6 +189,7 @@ def main():
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
+    gpu.flush()                            # PowerSGD: the last step's residual is written out
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = gpu.get_profile() if use_events else {}

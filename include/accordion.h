@@ -128,8 +128,8 @@ int32_t accordion_aggregate(acc_ctx* ctx, int32_t phase);
 
 /* Averaged, decompressed gradient of this step into out_dev (N floats; every element that
  * belongs to a layer is overwritten).
- * PowerSGD: D = P^ Q~^T on matrix layers and e_w = Delta_w - D for every worker; 1-D layers get
- * the plain mean.  TopK: D[i] = (sum over workers, in worker order from +0, of the values kept
+ * PowerSGD: D = P^ Q~^T on matrix layers (the residual e_w = Delta_w - D of every worker becomes
+ * the error memory, see accordion_flush); 1-D layers get the plain mean.  TopK: D[i] = (sum over workers, in worker order from +0, of the values kept
  * at i) / W.  Ends the step. */
 int32_t accordion_decompress(acc_ctx* ctx, float* out_dev);
 
@@ -142,6 +142,12 @@ int32_t accordion_step_all(acc_ctx* ctx, const float* const* grads_host_array, f
  * critical <=> no previous norm, previous norm 0, |old - c| / old >= eta, or lr_next < lr_curr;
  * level <- critical; old <- c; A <- 0.  Only between steps (else ACC_ESTATE). */
 int32_t accordion_detect_regime(acc_ctx* ctx, float lr_curr, float lr_next);
+
+/* PowerSGD keeps Delta_w in the error memory at the end of a step and forms the residual
+ * e_w = Delta_w - D in the first pass of the next step (one read and one write of the matrix
+ * saved per worker and step).  accordion_flush writes the residual out now; accordion_get_state
+ * does so by itself.  Only between steps (else ACC_ESTATE).  No effect for TopK. */
+int32_t accordion_flush(acc_ctx* ctx);
 
 /* A <- 0 without a decision (to measure one epoch out of several, Sec. 5.1 "Hyperparameters"). */
 int32_t accordion_reset_accumulator(acc_ctx* ctx);
@@ -190,7 +196,7 @@ int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
  * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
  * accordion_stage_name gives the kernel's name (NULL if out of range). */
-#define ACC_N_STAGES 17
+#define ACC_N_STAGES 18
 int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
 int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
 const char* accordion_stage_name(int32_t stage);

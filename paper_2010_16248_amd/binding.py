@@ -54,9 +54,9 @@ EXPORTS = [
     "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
     "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
-    "accordion_probe_copy", "accordion_topk_stats",
+    "accordion_probe_copy", "accordion_topk_stats", "accordion_flush",
 ]
-ACC_N_STAGES = 17
+ACC_N_STAGES = 18
 
 
 def load_library() -> C.CDLL:
@@ -79,6 +79,7 @@ def load_library() -> C.CDLL:
         "accordion_step_all": [vp, C.POINTER(vp), vp],
         "accordion_detect_regime": [vp, f32, f32],
         "accordion_reset_accumulator": [vp],
+        "accordion_flush": [vp],
         "accordion_get_levels": [vp, vp],
         "accordion_get_norms": [vp, vp, vp],
         "accordion_get_payload": [vp, i32, i32, vp, vp, i64, C.POINTER(i64)],
@@ -207,6 +208,9 @@ class Accordion:
 
     def detect_regime(self, lr_curr: float, lr_next: float) -> None:
         _check(self._lib, self.ctx, self._lib.accordion_detect_regime(self.ctx, lr_curr, lr_next))
+
+    def flush(self) -> None:
+        _check(self._lib, self.ctx, self._lib.accordion_flush(self.ctx))
 
     def reset_accumulator(self) -> None:
         _check(self._lib, self.ctx, self._lib.accordion_reset_accumulator(self.ctx))

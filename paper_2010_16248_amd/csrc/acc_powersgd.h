@@ -3,6 +3,12 @@
 // (2r flop per 4-byte element), so the kernels stream the matrix once per pass with 16-byte
 // accesses and keep the thin factor in registers; no MFMA.
 //
+// The residual e_w = Delta_w - P^ Q~^T of a step is not written by that step: the error memory
+// keeps Delta_w, and the next step's first pass forms e_w on the fly from the previous factors
+// (which are still in place: Q~ is the warm start, P^ is overwritten only later in the step)
+// before it adds the new gradient.  That saves one read and one write of the matrix per worker
+// and step.  psgd_residual_kernel makes the memory explicit when somebody wants to look at it.
+//
 // Matrix tile: 64 rows x 256 columns, one workgroup of 4 waves.  A lane owns 4 columns
 // (vec4 layers: 4 adjacent columns, one 16-byte access per row; other layers: columns
 // lane, lane+64, lane+128, lane+192, 4-byte accesses).  A wave owns rows wave, wave+4, ...
@@ -51,23 +57,37 @@ __device__ __forceinline__ void store_row(float* __restrict__ p, int64_t rowbase
 
 // ---- phase 0: Delta = g + e (in place of e), A += g (worker 0), P partial = Delta Q ---------
 
+// One entry of P^ Q~^T: sum_k p[k] q[k] over all kMaxRank columns, where the caller has set p[k]
+// to 0 beyond the rank in use (a product with 0 leaves the sum as it is).  Every kernel that
+// needs an entry of D forms it with this one expression, so that they agree bit for bit.
+__device__ __forceinline__ float low_rank_entry(const float (&p)[kMaxRank], const float (&q)[kMaxRank]) {
+  float s = p[0] * q[0];
+  s = fmaf(p[1], q[1], s);
+  s = fmaf(p[2], q[2], s);
+  s = fmaf(p[3], q[3], s);
+  return s;
+}
+
+// rp > 0: the memory still holds the previous step's Delta; its residual is Delta - P^ Q~^T with
+// the previous P^ (rows in ws.Phat) and Q~ (= the warm start, first rp columns).
 template <int R, bool V4>
 __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const float* __restrict__ g,
-                          float* __restrict__ e, float* __restrict__ A, float* __restrict__ ppart) {
+                          float* __restrict__ e, float* __restrict__ A, float* __restrict__ ppart, int rp) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int col[4]; bool cm[4];
   lane_cols<V4>(t.col0, lane, L.cols, col, cm);
-  float q[4][R];
+  float q[4][kMaxRank];
 #pragma unroll
   for (int v = 0; v < 4; ++v)
 #pragma unroll
-    for (int k = 0; k < R; ++k)
-      q[v][k] = cm[v] ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
+    for (int k = 0; k < kMaxRank; ++k)
+      q[v][k] = (cm[v] && k < ws.rmax) ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
 
   const int row_end = min(t.row0 + kMatRows, L.rows);
   const int chunk = t.col0 / kMatCols;
-  constexpr int B = 4;   // rows in flight per wave
+  const float* __restrict__ ph = ws.Phat + L.p_off;
+  constexpr int B = 2;   // rows in flight per wave (more rows cost registers and occupancy)
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float gd[B][4], ed[B][4], ad[B][4];
 #pragma unroll
@@ -85,6 +105,13 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
       const int i = i0 + 4 * b;
       if (i < row_end) {                       // wave-uniform
         const int64_t rb = L.offset + (int64_t)i * L.cols;
+        if (rp > 0) {                          // wave-uniform: the pending residual first
+          float pp[kMaxRank];
+#pragma unroll
+          for (int k = 0; k < kMaxRank; ++k) pp[k] = (k < rp) ? ph[(int64_t)i * ws.rmax + k] : 0.f;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) ed[b][v] = ed[b][v] - low_rank_entry(pp, q[v]);
+        }
         float d[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) d[v] = gd[b][v] + ed[b][v];
@@ -113,7 +140,8 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
   }
 }
 
-__global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradPtrs gp, int w0) {
+// pending: bit w set = worker w's memory holds the previous Delta (see the top of this file)
+__global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradPtrs gp, int w0, uint32_t pending) {
   const int w = w0 + blockIdx.y;
   const float* __restrict__ g = gp.p[w];
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
@@ -136,20 +164,21 @@ __global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradP
   const MatTile t = ws.mtiles[blockIdx.x];
   const LayerDev& L = ws.layers[t.layer];
   const int r = L.rank[ws.level[t.layer]];
+  const int rp = ((pending >> w) & 1u) ? ws.rank_used[t.layer] : 0;   // rank of the previous step's factors
   float* ppart = ws.Ppart + (int64_t)w * ws.ppart_stride;
   if (L.vec4) {
     switch (r) {
-      case 1: ef_p_tile<1, true>(ws, L, t, g, e, A, ppart); break;
-      case 2: ef_p_tile<2, true>(ws, L, t, g, e, A, ppart); break;
-      case 3: ef_p_tile<3, true>(ws, L, t, g, e, A, ppart); break;
-      default: ef_p_tile<4, true>(ws, L, t, g, e, A, ppart); break;
+      case 1: ef_p_tile<1, true>(ws, L, t, g, e, A, ppart, rp); break;
+      case 2: ef_p_tile<2, true>(ws, L, t, g, e, A, ppart, rp); break;
+      case 3: ef_p_tile<3, true>(ws, L, t, g, e, A, ppart, rp); break;
+      default: ef_p_tile<4, true>(ws, L, t, g, e, A, ppart, rp); break;
     }
   } else {
     switch (r) {
-      case 1: ef_p_tile<1, false>(ws, L, t, g, e, A, ppart); break;
-      case 2: ef_p_tile<2, false>(ws, L, t, g, e, A, ppart); break;
-      case 3: ef_p_tile<3, false>(ws, L, t, g, e, A, ppart); break;
-      default: ef_p_tile<4, false>(ws, L, t, g, e, A, ppart); break;
+      case 1: ef_p_tile<1, false>(ws, L, t, g, e, A, ppart, rp); break;
+      case 2: ef_p_tile<2, false>(ws, L, t, g, e, A, ppart, rp); break;
+      case 3: ef_p_tile<3, false>(ws, L, t, g, e, A, ppart, rp); break;
+      default: ef_p_tile<4, false>(ws, L, t, g, e, A, ppart, rp); break;
     }
   }
 }
@@ -427,92 +456,92 @@ __global__ __launch_bounds__(256) void psgd_qmean_kernel(const Ws ws) {
   }
 }
 
-// ---- decompress: D = P^ Q_bar^T, e_w = Delta_w - D ------------------------------------------
+// ---- decompress: D = P^ Q_bar^T (the residual stays implicit) ----------------------------------
 
-template <int R, bool V4>
+// RESIDUAL = false: writes D of the tile to out.  RESIDUAL = true: e = Delta - D in place.
+template <bool RESIDUAL, bool V4>
 __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, float* __restrict__ e,
-                            float* __restrict__ out) {
+                            float* __restrict__ out, int r) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int col[4]; bool cm[4];
   lane_cols<V4>(t.col0, lane, L.cols, col, cm);
-  float q[4][R];
+  float q[4][kMaxRank];
 #pragma unroll
   for (int v = 0; v < 4; ++v)
 #pragma unroll
-    for (int k = 0; k < R; ++k)
-      q[v][k] = cm[v] ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
+    for (int k = 0; k < kMaxRank; ++k)
+      q[v][k] = (cm[v] && k < ws.rmax) ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
   const int row_end = min(t.row0 + kMatRows, L.rows);
   const float* __restrict__ ph = ws.Phat + L.p_off;
   constexpr int B = 4;
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float d[B][4];
+    if (RESIDUAL) {
 #pragma unroll
-    for (int b = 0; b < B; ++b) {
-      const int i = i0 + 4 * b;
-      if (i < row_end) load_row<V4>(e, L.offset + (int64_t)i * L.cols, col, cm, d[b]);
+      for (int b = 0; b < B; ++b) {
+        const int i = i0 + 4 * b;
+        if (i < row_end) load_row<V4>(e, L.offset + (int64_t)i * L.cols, col, cm, d[b]);
+      }
     }
 #pragma unroll
     for (int b = 0; b < B; ++b) {
       const int i = i0 + 4 * b;
       if (i < row_end) {
         const int64_t rb = L.offset + (int64_t)i * L.cols;
-        float p[R];
+        float p[kMaxRank];
 #pragma unroll
-        for (int k = 0; k < R; ++k) p[k] = ph[(int64_t)i * ws.rmax + k];
-        float D[4], res[4];
+        for (int k = 0; k < kMaxRank; ++k) p[k] = (k < r) ? ph[(int64_t)i * ws.rmax + k] : 0.f;
+        float D[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          float s = p[0] * q[v][0];
+        for (int v = 0; v < 4; ++v) D[v] = low_rank_entry(p, q[v]);
+        if (RESIDUAL) {
+          float res[4];
 #pragma unroll
-          for (int k = 1; k < R; ++k) s = fmaf(p[k], q[v][k], s);
-          D[v] = s;
-          res[v] = d[b][v] - s;
+          for (int v = 0; v < 4; ++v) res[v] = d[b][v] - D[v];
+          store_row<V4>(e, rb, col, cm, res);
+        } else {
+          store_row<V4>(out, rb, col, cm, D);
         }
-        store_row<V4>(e, rb, col, cm, res);
-        if (out) store_row<V4>(out, rb, col, cm, D);
       }
     }
   }
 }
 
+// The averaged decompressed gradient: D on matrix layers, the plain mean on 1-D layers (which keep
+// no memory: their e is cleared for every worker).
 __global__ __launch_bounds__(256) void psgd_decomp_kernel(const Ws ws, float* __restrict__ out) {
-  const int w = blockIdx.y;
-  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-  if (blockIdx.x == 0 && w == 0 && threadIdx.x == 0) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
     ws.words[1] = ws.words[0];
     ws.words[2] += ws.words[0];
   }
   if ((int)blockIdx.x >= ws.n_mtiles) {
-    // 1-D layers: the plain mean goes out, no memory is kept
     const FlatTile ft = ws.ftiles[ws.vectiles[blockIdx.x - ws.n_mtiles]];
     const LayerDev& L = ws.layers[ft.layer];
     for (int i = threadIdx.x; i < ft.count; i += kFlatThreads) {
       const int64_t a = L.offset + ft.start + i;
-      e[a] = 0.f;
-      if (w == 0) out[a] = ws.vecmean[L.vec_off + ft.start + i];
+      for (int w = 0; w < ws.W; ++w) ws.e[(int64_t)w * ws.e_stride + a] = 0.f;
+      out[a] = ws.vecmean[L.vec_off + ft.start + i];
     }
     return;
   }
   const MatTile t = ws.mtiles[blockIdx.x];
   const LayerDev& L = ws.layers[t.layer];
-  const int r = L.rank[ws.level[t.layer]];
-  float* o = (w == 0) ? out : nullptr;
-  if (L.vec4) {
-    switch (r) {
-      case 1: decomp_tile<1, true>(ws, L, t, e, o); break;
-      case 2: decomp_tile<2, true>(ws, L, t, e, o); break;
-      case 3: decomp_tile<3, true>(ws, L, t, e, o); break;
-      default: decomp_tile<4, true>(ws, L, t, e, o); break;
-    }
-  } else {
-    switch (r) {
-      case 1: decomp_tile<1, false>(ws, L, t, e, o); break;
-      case 2: decomp_tile<2, false>(ws, L, t, e, o); break;
-      case 3: decomp_tile<3, false>(ws, L, t, e, o); break;
-      default: decomp_tile<4, false>(ws, L, t, e, o); break;
-    }
-  }
+  const int r = ws.rank_used[t.layer];                     // written by the orthogonalisation of this step
+  if (L.vec4) decomp_tile<false, true>(ws, L, t, nullptr, out, r);
+  else decomp_tile<false, false>(ws, L, t, nullptr, out, r);
+}
+
+// e_w = Delta_w - D for the workers whose bit is set in `pending`, in place.
+__global__ __launch_bounds__(256) void psgd_residual_kernel(const Ws ws, uint32_t pending) {
+  const int w = blockIdx.y;
+  if (((pending >> w) & 1u) == 0u) return;
+  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  const MatTile t = ws.mtiles[blockIdx.x];
+  const LayerDev& L = ws.layers[t.layer];
+  const int r = ws.rank_used[t.layer];
+  if (L.vec4) decomp_tile<true, true>(ws, L, t, e, nullptr, r);
+  else decomp_tile<true, false>(ws, L, t, e, nullptr, r);
 }
 
 }  // namespace acc

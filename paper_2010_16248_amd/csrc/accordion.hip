@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(float4* __restrict__ ds
 
 enum Stage {
   ST_psgd_ef_p_kernel = 0, ST_psgd_orth_kernel, ST_psgd_q_kernel, ST_psgd_qmean_kernel,
-  ST_psgd_decomp_kernel, ST_topk_ef_hist_kernel, ST_topk_pick12_kernel, ST_topk_restage_kernel,
+  ST_psgd_decomp_kernel, ST_psgd_residual_kernel, ST_topk_ef_hist_kernel, ST_topk_pick12_kernel, ST_topk_restage_kernel,
   ST_topk_count3_kernel, ST_topk_pick3_kernel,
   ST_topk_compact_kernel, ST_topk_compact_mean_kernel, ST_topk_sparse_mean_kernel,
   ST_norm_partial_kernel, ST_regime_decide_kernel, ST_recount_words_kernel, ST_zero_accum_kernel,
@@ -248,7 +248,7 @@ enum Stage {
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
 static const char* const kStageNames[ST_COUNT] = {
   "psgd_ef_p_kernel", "psgd_orth_kernel", "psgd_q_kernel", "psgd_qmean_kernel",
-  "psgd_decomp_kernel", "topk_ef_hist_kernel", "topk_pick12_kernel", "topk_restage_kernel",
+  "psgd_decomp_kernel", "psgd_residual_kernel", "topk_ef_hist_kernel", "topk_pick12_kernel", "topk_restage_kernel",
   "topk_count3_kernel", "topk_pick3_kernel",
   "topk_compact_kernel", "topk_compact_mean_kernel", "topk_sparse_mean_kernel",
   "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel"};
@@ -271,6 +271,9 @@ struct acc_ctx {
   bool in_step = false;
   uint32_t step_id = 2;            // number of the current step (the device keeps 0 for "never")
   uint32_t p0_mask = 0, p1_mask = 0;
+  // PowerSGD: workers whose error memory still holds the last step's Delta (the residual
+  // Delta - P^ Q~^T is formed by the next step's first pass, or by materialise())
+  uint32_t pending_mask = 0;
   bool agg0 = false, agg1 = false;
   GradPtrs grads;
   char err[256];
@@ -367,7 +370,8 @@ int launch_phase0(acc_ctx* c, int w0, int nw) {
   const Ws& ws = c->ws;
   if (c->cfg.method == ACC_POWERSGD) {
     const int gx = ws.n_mtiles + (w0 == 0 ? ws.n_vectiles : 0);
-    if (gx > 0) ACC_LAUNCH(c, psgd_ef_p_kernel, dim3(gx, nw), dim3(256), ws, c->grads, w0);
+    if (gx > 0) ACC_LAUNCH(c, psgd_ef_p_kernel, dim3(gx, nw), dim3(256), ws, c->grads, w0, c->pending_mask);
+    for (int w = w0; w < w0 + nw; ++w) c->pending_mask &= ~(1u << w);
   } else {
     const int rc = launch_topk_select(c, w0, nw);
     if (rc != ACC_OK) return rc;
@@ -400,7 +404,8 @@ int launch_agg1(acc_ctx* c) {
 int launch_decompress(acc_ctx* c, float* out) {
   const Ws& ws = c->ws;
   if (c->cfg.method == ACC_POWERSGD) {
-    ACC_LAUNCH(c, psgd_decomp_kernel, dim3(ws.n_mtiles + ws.n_vectiles, ws.W), dim3(256), ws, out);
+    ACC_LAUNCH(c, psgd_decomp_kernel, dim3(ws.n_mtiles + ws.n_vectiles), dim3(256), ws, out);
+    c->pending_mask = all_workers_mask(c);
   } else {
     ACC_LAUNCH(c, topk_sparse_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, out);
   }
@@ -410,6 +415,15 @@ int launch_decompress(acc_ctx* c, float* out) {
 int launch_topk_compact_mean(acc_ctx* c, float* out) {
   const Ws& ws = c->ws;
   ACC_LAUNCH(c, topk_compact_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, out);
+  return ACC_OK;
+}
+
+// Make the error memory explicit: e_w = Delta_w - D for the workers whose residual is pending.
+int materialise(acc_ctx* c) {
+  if (c->cfg.method != ACC_POWERSGD || c->pending_mask == 0) return ACC_OK;
+  const Ws& ws = c->ws;
+  if (ws.n_mtiles > 0) ACC_LAUNCH(c, psgd_residual_kernel, dim3(ws.n_mtiles, ws.W), dim3(256), ws, c->pending_mask);
+  c->pending_mask = 0;
   return ACC_OK;
 }
 
@@ -672,6 +686,12 @@ int32_t accordion_detect_regime(acc_ctx* c, float lr_curr, float lr_next) {
   return ACC_OK;
 }
 
+int32_t accordion_flush(acc_ctx* c) {
+  if (!c) return ACC_EINVAL;
+  if (c->in_step) return fail(c->err, ACC_ESTATE, "flush inside a step");
+  return materialise(c);
+}
+
 int32_t accordion_reset_accumulator(acc_ctx* c) {
   if (!c) return ACC_EINVAL;
   if (c->in_step) return fail(c->err, ACC_ESTATE, "reset_accumulator inside a step");
@@ -794,6 +814,8 @@ int32_t accordion_get_state(acc_ctx* c, void* state_host, size_t bytes) {
   if (!state_host) return fail(c->err, ACC_EINVAL, "state_host is NULL");
   if (c->in_step) return fail(c->err, ACC_ESTATE, "get_state inside a step");
   if (bytes < state_bytes_of(c)) return fail(c->err, ACC_ENOSPACE, "state buffer too small");
+  const int rc = materialise(c);
+  if (rc != ACC_OK) return rc;
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   return state_copy(c, static_cast<char*>(state_host), true);
 }
@@ -811,6 +833,7 @@ int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   const int32_t rc = state_copy(c, const_cast<char*>(static_cast<const char*>(state_host)), false);
   if (rc != ACC_OK) return rc;
+  c->pending_mask = 0;                                       // the memory just written is explicit
   ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)c->cfg.method);
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   return ACC_OK;

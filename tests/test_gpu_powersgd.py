@@ -130,6 +130,42 @@ def test_zero_gradient_gives_zero_columns_not_nan():
     gpu.destroy()
 
 
+def test_deferred_residual_equals_explicit_residual():
+    """The library leaves Delta in the error memory and forms the residual in the next step's
+    first pass.  A run that reads the state after every step (which writes the residual out)
+    and a run that never looks must end in the same bits, across a rank switch (the pending
+    residual then has another rank than the new step) and with vectors and ragged shapes."""
+    print("case deferred residual", flush=True)
+    shapes = [(70, 300, 1), (1, 33, 0), (64, 259, 1), (5, 1000, 1), (1, 7, 0)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 3
+    rng = np.random.default_rng(17)
+    grads = [[(rng.standard_normal(N) * 0.01).astype(np.float32) for _ in range(W)] for _ in range(6)]
+    q0 = wl.q_init(layers, 4, 5)
+    finals = []
+    for look in (True, False, False):
+        gpu = B.Accordion(B.ACC_POWERSGD, H.layer_tuples(layers), W, 4, 1, 100, 0.5, 0, q0)
+        outs = []
+        for step in range(6):
+            out = H.dev_out(N)
+            gpu.step_all([H.to_dev(g) for g in grads[step]], out)
+            outs.append(out.cpu().numpy())
+            if look:
+                gpu.get_state()
+            if step == 2:
+                gpu.detect_regime(0.1, 0.01)                 # LR decay: critical, rank 1 -> 4
+        if not look and len(finals) == 2:
+            gpu.flush()                                      # explicit flush, then read
+        finals.append((outs, gpu.get_state().copy()))
+        assert gpu.get_levels().sum() == len(shapes)
+        gpu.destroy()
+    for outs, st in finals[1:]:
+        for a, b in zip(outs, finals[0][0]):
+            H.assert_bits_equal(a, b, "decompressed gradient")
+        assert np.array_equal(st, finals[0][1])
+
+
 def test_call_by_call_equals_step_all_and_is_deterministic():
     shapes = [(70, 300, 1), (1, 77, 0), (33, 64, 1)]
     layers = wl.make_layers(shapes)
