@@ -185,134 +185,143 @@ __global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradP
 
 // ---- aggregate 0: P_bar = mean over workers (and column chunks), Gram-Schmidt -----------
 
-// Sum over the 256 threads of a workgroup, same value for every thread.  `slot` alternates
-// between calls so that one barrier per call is enough.
-__device__ __forceinline__ float block_sum_256(float v, float (*red)[4], int& slot) {
+constexpr int kOrthThreads = 1024;
+constexpr int kOrthWaves = kOrthThreads / kWave;
+
+// Sum over the threads of the orthogonalisation workgroup, same value for every thread.  `slot`
+// alternates between calls so that one barrier per call is enough.
+// Only the first nwaves waves of the workgroup are still running (the others have left).
+__device__ __forceinline__ float block_sum_orth(float v, float (*red)[kOrthWaves], int& slot, int nwaves) {
   v = wave_sum(v);
+  if (nwaves == 1) return v;
   const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) red[slot][wave] = v;
   __syncthreads();
-  const float r = (red[slot][0] + red[slot][1]) + (red[slot][2] + red[slot][3]);
+  float r = 0.f;
+  for (int i = 0; i < nwaves; ++i) r += red[slot][i];
   slot ^= 1;
   return r;
 }
 
 // Sum over workers and over the partial results of one worker (column chunks of P, row blocks
 // of Q) for one row of r values, divided by W.  The W * nparts addends are independent loads;
-// they are issued eight at a time and added in a fixed order (worker-major).
+// they are issued eight at a time (unconditionally, from clamped addresses, so that all eight are
+// in flight together) and added in a fixed order (worker-major).  The calling thread takes the
+// addends first, first + stride, ...
 template <int R>
-__device__ __forceinline__ void mean_of_partials(const float* __restrict__ base, int64_t wstride,
-                                                 int W, int nparts, int64_t pstride, float (&out)[R]) {
-  float acc[R];
+__device__ __forceinline__ void sum_of_partials(const float* __restrict__ base, int64_t wstride, int W,
+                                                int nparts, int64_t pstride, int first, int stride,
+                                                float (&acc)[R]) {
 #pragma unroll
   for (int k = 0; k < R; ++k) acc[k] = 0.f;
   const int np = W * nparts;
-  for (int p0 = 0; p0 < np; p0 += 8) {
+  for (int p0 = first; p0 < np; p0 += 8 * stride) {
     float v[8][R];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const int p = p0 + u;
-      if (p < np) {
-        const int w = p / nparts, c = p - w * nparts;
-        const float* src = base + (int64_t)w * wstride + (int64_t)c * pstride;
+      const int p = min(p0 + u * stride, np - 1);
+      const int w = p / nparts, c = p - w * nparts;
+      const float* src = base + (int64_t)w * wstride + (int64_t)c * pstride;
 #pragma unroll
-        for (int k = 0; k < R; ++k) v[u][k] = src[k];
-      } else {
-#pragma unroll
-        for (int k = 0; k < R; ++k) v[u][k] = 0.f;
-      }
+      for (int k = 0; k < R; ++k) v[u][k] = src[k];
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u)
 #pragma unroll
-      for (int k = 0; k < R; ++k) acc[k] += v[u][k];
+      for (int k = 0; k < R; ++k) acc[k] += (p0 + u * stride < np) ? v[u][k] : 0.f;
   }
-#pragma unroll
-  for (int k = 0; k < R; ++k) out[k] = acc[k] / (float)W;
 }
 
-// Row i of P_bar.
 template <int R>
-__device__ __forceinline__ void pbar_row(const Ws& ws, const LayerDev& L, int i, float (&pb)[R]) {
-  mean_of_partials<R>(ws.Ppart + L.ppart_off + (int64_t)i * ws.rmax, ws.ppart_stride, ws.W,
-                      L.n_colchunks, (int64_t)L.rows * ws.rmax, pb);
+__device__ __forceinline__ void mean_of_partials(const float* __restrict__ base, int64_t wstride,
+                                                 int W, int nparts, int64_t pstride, float (&out)[R]) {
+  sum_of_partials<R>(base, wstride, W, nparts, pstride, 0, 1, out);
+#pragma unroll
+  for (int k = 0; k < R; ++k) out[k] = out[k] / (float)W;
 }
 
 // Modified Gram-Schmidt over the r columns of P_bar, in column order; a column of zero
-// length stays zero.  Layers of up to 1024 rows live in registers (4 rows per thread),
+// length stays zero.  Layers of up to kOrthThreads rows live in registers, one row per thread
+// (short layers: several threads share the partial sums of a row and one of them keeps it);
 // taller ones in global memory (each thread only ever touches its own rows).
 template <int R>
-__device__ void orth_layer(const Ws& ws, const LayerDev& L, float (*red)[4]) {
+__device__ void orth_layer(const Ws& ws, const LayerDev& L, float (*red)[kOrthWaves], float* psum) {
   const int n = L.rows;
   const int tid = threadIdx.x;
   float* ph = ws.Phat + L.p_off;
+  const float* pbase = ws.Ppart + L.ppart_off;
+  const int64_t pstride = (int64_t)L.rows * ws.rmax;
+  const float fw = (float)ws.W;
   int slot = 0;
-  if (n <= 4 * kFlatThreads) {
-    float v[4][R];
+  if (n <= kOrthThreads) {
+    int tpr = 1;                                            // threads per row, workgroup-uniform
+    while (tpr < 16 && 2 * tpr * n <= kOrthThreads) tpr *= 2;
+    const int rows_pad = kOrthThreads / tpr;                // >= n; thread t: row t % rows_pad, share t / rows_pad
+    const int row = tid & (rows_pad - 1), sub = tid / rows_pad;
+    float part[R];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int i = s * kFlatThreads + tid;
-      if (i < n) {
-        pbar_row<R>(ws, L, i, v[s]);
-      } else {
+    for (int k = 0; k < R; ++k) part[k] = 0.f;
+    if (row < n)
+      sum_of_partials<R>(pbase + (int64_t)row * ws.rmax, ws.ppart_stride, ws.W, L.n_colchunks, pstride, sub, tpr,
+                         part);
 #pragma unroll
-        for (int k = 0; k < R; ++k) v[s][k] = 0.f;
-      }
+    for (int k = 0; k < R; ++k) psum[tid * kMaxRank + k] = part[k];
+    __syncthreads();
+    if (tid >= rows_pad) return;                            // whole waves (rows_pad is a multiple of 64)
+    const int nwaves = rows_pad / kWave;
+    const bool holder = row < n;
+    float v[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) v[k] = 0.f;
+    if (holder) {
+      for (int j = 0; j < tpr; ++j)
+#pragma unroll
+        for (int k = 0; k < R; ++k) v[k] += psum[(j * rows_pad + tid) * kMaxRank + k];
+#pragma unroll
+      for (int k = 0; k < R; ++k) v[k] = v[k] / fw;
     }
 #pragma unroll
     for (int k = 0; k < R; ++k) {
 #pragma unroll
       for (int j = 0; j < R; ++j) {
         if (j < k) {
-          float d = 0.f;
-#pragma unroll
-          for (int s = 0; s < 4; ++s) d = fmaf(v[s][j], v[s][k], d);
-          d = block_sum_256(d, red, slot);
-#pragma unroll
-          for (int s = 0; s < 4; ++s) v[s][k] = fmaf(-d, v[s][j], v[s][k]);
+          const float d = block_sum_orth(v[j] * v[k], red, slot, nwaves);
+          v[k] = fmaf(-d, v[j], v[k]);
         }
       }
-      float nn = 0.f;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) nn = fmaf(v[s][k], v[s][k], nn);
-      nn = block_sum_256(nn, red, slot);
+      const float nn = block_sum_orth(v[k] * v[k], red, slot, nwaves);
       const float nrm = sqrtf(nn);
-#pragma unroll
-      for (int s = 0; s < 4; ++s) v[s][k] = (nrm > 0.f) ? v[s][k] / nrm : 0.f;
+      v[k] = (nrm > 0.f) ? v[k] / nrm : 0.f;
     }
+    if (holder) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int i = s * kFlatThreads + tid;
-      if (i < n) {
-#pragma unroll
-        for (int k = 0; k < R; ++k) ph[(int64_t)i * ws.rmax + k] = v[s][k];
-      }
+      for (int k = 0; k < R; ++k) ph[(int64_t)row * ws.rmax + k] = v[k];
     }
   } else {
-    for (int i = tid; i < n; i += kFlatThreads) {
+    for (int i = tid; i < n; i += kOrthThreads) {
       float pb[R];
-      pbar_row<R>(ws, L, i, pb);
+      mean_of_partials<R>(pbase + (int64_t)i * ws.rmax, ws.ppart_stride, ws.W, L.n_colchunks, pstride, pb);
 #pragma unroll
       for (int k = 0; k < R; ++k) ph[(int64_t)i * ws.rmax + k] = pb[k];
     }
     for (int k = 0; k < R; ++k) {
       for (int j = 0; j < k; ++j) {
         float d = 0.f;
-        for (int i = tid; i < n; i += kFlatThreads)
+        for (int i = tid; i < n; i += kOrthThreads)
           d = fmaf(ph[(int64_t)i * ws.rmax + j], ph[(int64_t)i * ws.rmax + k], d);
-        d = block_sum_256(d, red, slot);
-        for (int i = tid; i < n; i += kFlatThreads)
+        d = block_sum_orth(d, red, slot, kOrthWaves);
+        for (int i = tid; i < n; i += kOrthThreads)
           ph[(int64_t)i * ws.rmax + k] =
               fmaf(-d, ph[(int64_t)i * ws.rmax + j], ph[(int64_t)i * ws.rmax + k]);
       }
       float nn = 0.f;
-      for (int i = tid; i < n; i += kFlatThreads) {
+      for (int i = tid; i < n; i += kOrthThreads) {
         const float x = ph[(int64_t)i * ws.rmax + k];
         nn = fmaf(x, x, nn);
       }
-      nn = block_sum_256(nn, red, slot);
+      nn = block_sum_orth(nn, red, slot, kOrthWaves);
       const float nrm = sqrtf(nn);
-      for (int i = tid; i < n; i += kFlatThreads) {
+      for (int i = tid; i < n; i += kOrthThreads) {
         const float x = ph[(int64_t)i * ws.rmax + k];
         ph[(int64_t)i * ws.rmax + k] = (nrm > 0.f) ? x / nrm : 0.f;
       }
@@ -320,13 +329,14 @@ __device__ void orth_layer(const Ws& ws, const LayerDev& L, float (*red)[4]) {
   }
 }
 
-__global__ __launch_bounds__(256) void psgd_orth_kernel(const Ws ws, const GradPtrs gp) {
-  __shared__ float red[2][4];
+__global__ __launch_bounds__(kOrthThreads) void psgd_orth_kernel(const Ws ws, const GradPtrs gp) {
+  __shared__ float red[2][kOrthWaves];
+  __shared__ float psum[kOrthThreads * kMaxRank];
   if ((int)blockIdx.x >= ws.n_mat) {
     // 1-D layers are sent raw: mean over workers in worker order
     const FlatTile ft = ws.ftiles[ws.vectiles[blockIdx.x - ws.n_mat]];
     const LayerDev& L = ws.layers[ft.layer];
-    for (int i = threadIdx.x; i < ft.count; i += kFlatThreads) {
+    for (int i = threadIdx.x; i < ft.count; i += kOrthThreads) {
       const int64_t a = L.offset + ft.start + i;
       float s = gp.p[0][a];
       for (int w = 1; w < ws.W; ++w) s += gp.p[w][a];
@@ -339,10 +349,10 @@ __global__ __launch_bounds__(256) void psgd_orth_kernel(const Ws ws, const GradP
   const int r = L.rank[ws.level[li]];
   if (threadIdx.x == 0) ws.rank_used[li] = r;
   switch (r) {
-    case 1: orth_layer<1>(ws, L, red); break;
-    case 2: orth_layer<2>(ws, L, red); break;
-    case 3: orth_layer<3>(ws, L, red); break;
-    default: orth_layer<4>(ws, L, red); break;
+    case 1: orth_layer<1>(ws, L, red, psum); break;
+    case 2: orth_layer<2>(ws, L, red, psum); break;
+    case 3: orth_layer<3>(ws, L, red, psum); break;
+    default: orth_layer<4>(ws, L, red, psum); break;
   }
 }
 

@@ -384,7 +384,7 @@ int launch_agg0(acc_ctx* c) {
   const Ws& ws = c->ws;
   if (c->cfg.method == ACC_POWERSGD) {
     const int gx = ws.n_mat + ws.n_vectiles;
-    if (gx > 0) ACC_LAUNCH(c, psgd_orth_kernel, dim3(gx), dim3(256), ws, c->grads);
+    if (gx > 0) ACC_LAUNCH(c, psgd_orth_kernel, dim3(gx), dim3(kOrthThreads), ws, c->grads);
   }
   return ACC_OK;
 }
