@@ -53,7 +53,7 @@ def parse():
                     choices=["tiny_powersgd", "resnet18_topk", "resnet18_powersgd", "vgg19_powersgd", "lstm_topk"])
     ap.add_argument("--workers", type=int, default=0, help="override W of the workload")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept in HBM")
-    ap.add_argument("--window", type=int, default=20, help="steps per detection window")
+    ap.add_argument("--window", type=int, default=50, help="steps per detection window")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-events", default="dominant", choices=["dominant", "all", "none"],
                     help="which kernels are bracketed with HIP events in the timed region: the fused "

@@ -861,7 +861,7 @@ struct CompactRun { uint32_t eq_run, pos_run; };
 // T for the entries equal to T that are within the tie quota (lowest indices first) and T + 1
 // otherwise; quarters without an entry equal to T never look at ties.
 template <bool AL, bool MEAN>
-__device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan& span, const LayerDev& L,
+__device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan& span, int64_t layer_offset,
                                               const QuarterSel& qs, CompactRun& run, float* __restrict__ e,
                                               int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
                                               const float4& cur, int lane, float4& acc) {
@@ -911,7 +911,7 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
   }
   if (total != 0) {
     uint32_t pos = run.pos_run + below;
-    const int32_t i0 = (int32_t)(tg.a0 + 4 * (int64_t)q - L.offset);
+    const int32_t i0 = (int32_t)(tg.a0 + 4 * (int64_t)q - layer_offset);
     float4 z = cur;
     bool sel[4];
 #pragma unroll
@@ -956,11 +956,12 @@ __device__ __forceinline__ void compact_tile(const Ws& ws, int w, const FlatTile
   run.pos_run = qs.gt_before + min(qs.ktie, qs.eq_before);
   int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
   float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
+  const int64_t layer_offset = L.offset;                   // by value: nothing is re-read inside the loop
   float4 unused = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
     const int q = q0 + lane;
     const float4 nn = ld_span<AL>(e, tg, span, q + 2 * kWave);
-    compact_group<AL, false>(tg, span, L, qs, run, e, pidx, pval, q, cur, lane, unused);
+    compact_group<AL, false>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, unused);
     cur = nxt;
     nxt = nn;
   }
@@ -991,6 +992,12 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   const WaveSpan span = wave_span(tg, wave);
   const int64_t qslot_local = L.qoff + 4 * (int64_t)(ft.start >> kTileShift) + wave;
   const int W = ws.W;
+  // everything the loop needs from the layer and the workspace, by value (a reference into global
+  // memory would be re-read after every store, and that wait would drain the loads in flight)
+  const int64_t layer_offset = L.offset, pay_off = L.pay_off, e_stride = ws.e_stride, pay_stride = ws.pay_stride;
+  float* const e_base = ws.e;
+  int32_t* const pay_idx = ws.pay_idx;
+  float* const pay_val = ws.pay_val;
   // lane w holds worker w's selection state for this quarter
   QuarterSel mine = {0u, 0u, 0u, 0u, 0u, 0u, 0u};
   if (lane < W) mine = load_quarter_sel(ws, lane, ft.layer, qslot_local);
@@ -1002,7 +1009,7 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
 #pragma unroll
     for (int u = 0; u < kMeanBatch; ++u) {
       const int w = wb + u;
-      d[u] = (j < n && w < W) ? ld_span<AL>(ws.e + (int64_t)w * ws.e_stride, tg, span, span.qbeg + j * kWave + lane)
+      d[u] = (j < n && w < W) ? ld_span<AL>(e_base + (int64_t)w * e_stride, tg, span, span.qbeg + j * kWave + lane)
                               : zero4;
     }
   };
@@ -1031,10 +1038,10 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
           CompactRun run;
           run.eq_run = (uint32_t)__builtin_amdgcn_readlane((int)eq_run_v, w);
           run.pos_run = (uint32_t)__builtin_amdgcn_readlane((int)pos_run_v, w);
-          float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-          int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
-          float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
-          compact_group<AL, true>(tg, span, L, qs, run, e, pidx, pval, q, cur[u], lane, acc);
+          float* __restrict__ e = e_base + (int64_t)w * e_stride;
+          int32_t* pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
+          float* pval = pay_val + (int64_t)w * pay_stride + pay_off;
+          compact_group<AL, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur[u], lane, acc);
           if (lane == w) { eq_run_v = run.eq_run; pos_run_v = run.pos_run; }
         }
       }
