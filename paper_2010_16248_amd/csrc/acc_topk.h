@@ -49,10 +49,11 @@ __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// LDS histogram add of the non-zero keys; exact zeros (the one tie class that is common in real
-// gradients) are counted per wave by the caller and added to bin 0 once.
-__device__ __forceinline__ void hist_add(uint32_t* hist, bool valid_nonzero, uint32_t bin) {
-  if (valid_nonzero) atomicAdd(&hist[bin], 1u);
+// LDS histogram add.  Keys of bin 0 (the exact zeros -- the one tie class that is common in real
+// gradients -- and the smallest denormals) are left out: their number is the layer's size minus
+// the other bins.
+__device__ __forceinline__ void hist_add(uint32_t* hist, bool valid_not_bin0, uint32_t bin) {
+  if (valid_not_bin0) atomicAdd(&hist[bin], 1u);
 }
 
 // hist: kHistBins counts in LDS.  Finds the largest bin b with count(bins >= b) >= k.
@@ -129,50 +130,62 @@ __device__ __forceinline__ int64_t quarter_slot(const Ws& ws, const LayerDev& L,
   return (int64_t)w * ws.q_stride + L.qoff + 4 * (int64_t)tl + wave;
 }
 
-// Staging of one component's keys: bin glo at the front of the wave's LDS list, bin ghi in
-// its second half.  n0 / n1 (wave-uniform) keep running past the capacity (the counting kernel
-// sees the overflow); the zeros and the entries above the staged bins are counted per lane and
-// summed over the wave when the quarter is flushed.
-struct StageCounts { uint32_t n0, n1, v_hi, v_nz; };
+// Staging of one component's keys in the wave's LDS list (the keys of both guessed bins share
+// one list: a key carries its bin).  The counts keep running past the capacity (the counting
+// kernel sees the overflow).  n_in, n1: wave-uniform; v_hi, v_nz: per lane, summed over the
+// wave when the quarter is flushed.
+struct StageCounts { uint32_t n_in, n1, v_hi, v_nz; };
 
-// mv: lane mask of the valid elements; valid: the calling lane's bit of it.  Every ballot is
-// taken from a single compare and combined with the other masks in scalar registers.
-template <bool TWO = true>
-__device__ __forceinline__ void stage_key(uint32_t* st, uint32_t* sub2, StageCounts& c, uint64_t mv, bool valid,
-                                          uint32_t key, uint32_t glo, uint32_t ghi, int lane) {
+constexpr int kSegCap = 2 * kSubCap;     // staged keys per wave quarter
+
+// Pass A: keys of the bins glo and glo + 1 (glo >= 1, so a staged key is never an exact zero;
+// zeros are not counted here: a threshold in bin 0 counts as a missed guess and the re-staging
+// pass counts them).  mv: lane mask of the valid elements; valid: the calling lane's bit of it.
+// Every ballot is taken from a single compare and combined with the other masks in scalar
+// registers.
+__device__ __forceinline__ void stage_two_bins(uint32_t* st, uint32_t* sub2, StageCounts& c, uint64_t mv,
+                                               bool valid, uint32_t key, uint32_t glo, int lane) {
   const uint32_t bin = key >> 20;
-  c.v_nz += (valid && key == 0u) ? 1u : 0u;
-  c.v_hi += (valid && bin > ghi) ? 1u : 0u;
-  const uint64_t m0 = ballot64(bin == glo) & ballot64(key != 0u) & mv;
-  if (m0 != 0) {
-    if (valid && bin == glo && key != 0u) {
-      const uint32_t pos = c.n0 + lanes_below(m0, lane);
-      if (pos < (uint32_t)kSubCap) st[pos] = key;
-      atomicAdd(&sub2[bin2_of(key)], 1u);
+  const uint32_t rel = bin - glo;                          // 0 / 1 for the staged bins
+  c.v_hi += (valid && (int32_t)rel > 1) ? 1u : 0u;
+  c.n1 += (uint32_t)__popcll(ballot64(rel == 1u) & mv);
+  const uint64_t m = ballot64(rel <= 1u) & mv;
+  if (m != 0) {
+    if (valid && rel <= 1u) {
+      const uint32_t pos = c.n_in + lanes_below(m, lane);
+      if (pos < (uint32_t)kSegCap) st[pos] = key;
+      atomicAdd(&sub2[rel * kL2Bins + bin2_of(key)], 1u);
     }
-    c.n0 += (uint32_t)__popcll(m0);
-  }
-  if (!TWO) return;                                        // one bin only: ghi == glo
-  const uint64_t m1 = ballot64(bin == ghi) & mv;
-  if (m1 != 0) {
-    if (valid && bin == ghi) {
-      const uint32_t pos = c.n1 + lanes_below(m1, lane);
-      if (pos < (uint32_t)kSubCap) st[kSubCap + pos] = key;
-      atomicAdd(&sub2[kL2Bins + bin2_of(key)], 1u);
-    }
-    c.n1 += (uint32_t)__popcll(m1);
+    c.n_in += (uint32_t)__popcll(m);
   }
 }
 
-// Returns the quarter's number of exact zeros (the same value in every lane).
+// The re-staging pass: the keys of bin b1 alone, exact zeros left out and counted.
+__device__ __forceinline__ void stage_one_bin(uint32_t* st, uint32_t* sub2, StageCounts& c, uint64_t mv,
+                                              bool valid, uint32_t key, uint32_t b1, int lane) {
+  const uint32_t bin = key >> 20;
+  c.v_nz += (valid && key == 0u) ? 1u : 0u;
+  c.v_hi += (valid && bin > b1) ? 1u : 0u;
+  const uint64_t m = ballot64(bin == b1) & ballot64(key != 0u) & mv;
+  if (m != 0) {
+    if (valid && bin == b1 && key != 0u) {
+      const uint32_t pos = c.n_in + lanes_below(m, lane);
+      if (pos < (uint32_t)kSegCap) st[pos] = key;
+      atomicAdd(&sub2[bin2_of(key)], 1u);
+    }
+    c.n_in += (uint32_t)__popcll(m);
+  }
+}
+
+// qinfo of the quarter: {entries above the staged bins, staged keys, of which in the upper bin,
+// exact zeros}.  Returns the number of exact zeros (the same value in every lane).
 __device__ __forceinline__ uint32_t stage_flush(const Ws& ws, int64_t qslot, const uint32_t* st,
                                                 const StageCounts& c, int lane) {
-  uint32_t* seg = ws.seg + qslot * (2 * kSubCap);
-  const uint32_t m0 = min(c.n0, (uint32_t)kSubCap), m1 = min(c.n1, (uint32_t)kSubCap);
-  for (uint32_t i = lane; i < m0; i += kWave) seg[i] = st[i];
-  for (uint32_t i = lane; i < m1; i += kWave) seg[kSubCap + i] = st[kSubCap + i];
+  uint32_t* seg = ws.seg + qslot * kSegCap;
+  const uint32_t m = min(c.n_in, (uint32_t)kSegCap);
+  for (uint32_t i = lane; i < m; i += kWave) seg[i] = st[i];
   const uint32_t n_hi = wave_sum_u32(c.v_hi), nz = wave_sum_u32(c.v_nz);
-  if (lane == 0) ws.qinfo[qslot] = make_uint4(n_hi, c.n0, c.n1, nz);
+  if (lane == 0) ws.qinfo[qslot] = make_uint4(n_hi, c.n_in, c.n1, nz);
   return nz;
 }
 
@@ -192,12 +205,11 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
   float* __restrict__ A = (w == 0) ? ws.A : nullptr;
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
-  uint32_t glo = 0xfffffff0u;                              // no bin matches without a guess
+  uint32_t glo = 0x7ffffff0u;                              // no bin matches without a guess
   if (SELECT) {
     const uint32_t guess = ws.guess[wl * 2 + ws.level[ft.layer]];
-    if (guess != kNoGuess) glo = guess;
+    if (guess != kNoGuess) glo = max(guess, 1u);
   }
-  const uint32_t ghi = glo + 1u;
   // two groups per lane are requested before the histograms are cleared
   constexpr int U = 2;
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -243,8 +255,8 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const uint32_t key = key_of(comp(d, c));
-            hist_add(hist, key != 0u, key >> 20);
-            stage_key(st, sub2, cnt, ~0ull, true, key, glo, ghi, lane);
+            hist_add(hist, (key >> 20) != 0u, key >> 20);
+            stage_two_bins(st, sub2, cnt, ~0ull, true, key, glo, lane);
           }
         } else {
           const uint64_t m_span = ballot64(qa);
@@ -253,8 +265,8 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
             const bool valid = elem_valid<AL>(tg, q, c, qa);
             const uint64_t mv = valid_mask<AL>(tg, q, c, qa, m_span);
             const uint32_t key = key_of(comp(d, c));
-            hist_add(hist, valid && key != 0u, key >> 20);
-            stage_key(st, sub2, cnt, mv, valid, key, glo, ghi, lane);
+            hist_add(hist, valid && (key >> 20) != 0u, key >> 20);
+            stage_two_bins(st, sub2, cnt, mv, valid, key, glo, lane);
           }
         }
       }
@@ -263,10 +275,9 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
     for (int u = 0; u < U; ++u) { gc[u] = gn[u]; ec[u] = en[u]; ac[u] = an[u]; }
   }
   if (SELECT) {
-    const uint32_t nz = stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, lane);
-    if (lane == 0 && nz) atomicAdd(&hist[0], nz);
+    stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, lane);
     __syncthreads();
-    uint32_t* gh = ws.hist1 + wl * kHistBins;
+    uint32_t* gh = ws.hist1 + wl * kHistBins;                // bin 0 stays empty: the pick kernel derives it
     for (int b = tid; b < kHistBins; b += kFlatThreads) {
       const uint32_t h = hist[b];
       if (h) atomicAdd(&gh[b], h);
@@ -316,8 +327,8 @@ __device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile
     const uint64_t m_span = ballot64(qa);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
-      stage_key<false>(st, sub2, cnt, valid_mask<AL>(tg, q, c, qa, m_span), elem_valid<AL>(tg, q, c, qa),
-                       key_of(comp(cur, c)), b1, b1, lane);     // only bin b1 is staged (first half)
+      stage_one_bin(st, sub2, cnt, valid_mask<AL>(tg, q, c, qa, m_span), elem_valid<AL>(tg, q, c, qa),
+                    key_of(comp(cur, c)), b1, lane);
     cur = nxt;
   }
   const uint32_t nz = stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, lane);
@@ -350,19 +361,19 @@ __global__ __launch_bounds__(256) void topk_restage_kernel(const Ws ws, int w0) 
 
 // ---- the per-layer decisions ---------------------------------------------------------------------
 
-constexpr int kFirstChunks = kSubCap / kWave;   // 64-key chunks of one side of a segment
+constexpr int kFirstChunks = kSegCap / kWave;   // 64-key chunks of a segment
 
 struct QuarterKeys {
-  uint4 info;                      // {entries above the staged bins, keys of side 0, keys of side 1, zeros}
-  uint32_t chunk[kFirstChunks];    // the calling lane's keys of the chosen side
+  uint4 info;                      // {entries above the staged bins, staged keys, of which upper bin, zeros}
+  uint32_t chunk[kFirstChunks];    // the calling lane's staged keys
 };
 
 // All loads of a quarter's segment are unconditional (the slot always exists), so they are in
 // flight together; what lies past the count is ignored later.
-__device__ __forceinline__ QuarterKeys load_quarter_keys(const Ws& ws, int64_t qslot, uint32_t side, int lane) {
+__device__ __forceinline__ QuarterKeys load_quarter_keys(const Ws& ws, int64_t qslot, int lane) {
   QuarterKeys k;
   k.info = ws.qinfo[qslot];
-  const uint32_t* seg = ws.seg + qslot * (2 * kSubCap) + side * kSubCap;
+  const uint32_t* seg = ws.seg + qslot * kSegCap;
 #pragma unroll
   for (int ch = 0; ch < kFirstChunks; ++ch) k.chunk[ch] = seg[ch * kWave + lane];
   return k;
@@ -370,18 +381,20 @@ __device__ __forceinline__ QuarterKeys load_quarter_keys(const Ws& ws, int64_t q
 
 // Calls f(key, valid) with all 64 lanes for every key of bin b1 (zeros excluded) of one quarter
 // and returns the quarter's number of entries in bins above b1: from the staged segment and the
-// counts of pass A, or -- when the quarter has more keys of b1 than the segment holds, or when
+// counts of pass A, or -- when the quarter has more staged keys than the segment holds, or when
 // nothing useful was staged (from_delta) -- from Delta itself.
-// tl: tile within the layer, wave: quarter within the tile.
+// side: b1 is the lower (0) or the upper (1) of the staged bins; tl: tile within the layer,
+// wave: quarter within the tile.
 template <class F>
 __device__ __forceinline__ uint32_t for_quarter_keys(const Ws& ws, const LayerDev& L, int w, int tl, int wave,
                                                      const QuarterKeys& k, uint32_t side, uint32_t b1,
                                                      bool from_delta, int lane, F f) {
-  const uint32_t n = side ? k.info.z : k.info.y;
-  if (!from_delta && n <= (uint32_t)kSubCap) {
+  const uint32_t n = k.info.y;
+  if (!from_delta && n <= (uint32_t)kSegCap) {
 #pragma unroll
     for (int ch = 0; ch < kFirstChunks; ++ch)
-      if (n > (uint32_t)(ch * kWave)) f(k.chunk[ch], (uint32_t)(ch * kWave + lane) < n);   // uniform condition
+      if (n > (uint32_t)(ch * kWave))                                                       // uniform condition
+        f(k.chunk[ch], (uint32_t)(ch * kWave + lane) < n && (k.chunk[ch] >> 20) == b1);
     return k.info.x + (side == 0u ? k.info.z : 0u);
   }
   FlatTile ft;
@@ -501,6 +514,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   }
   SelState* sp = ws.sel + wl;
   __shared__ uint32_t sub[kSub2];
+  __shared__ uint32_t nb0;
   // Requested together, before anything is known: the layer's level-1 histogram (cleared for
   // the next step) and the tiles' level-2 counts of BOTH guessed bins.
   uint32_t* gh = ws.hist1 + wl * kHistBins;
@@ -522,12 +536,22 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   hist[tid] = h0;
   hist[tid + kPickThreads] = h1;
   if (tid < kSub2) sub[tid] = 0u;
+  if (tid == 0) nb0 = 0u;
   __syncthreads();
   if (s2) atomicAdd(&sub[col], s2);
+  {
+    // bin 0 (exact zeros and the smallest denormals) was not histogrammed: the rest of the layer
+    const uint32_t part = wave_sum_u32(h0 + h1 - (tid == 0 ? h0 : 0u));
+    if (lane == 0 && part) atomicAdd(&nb0, part);
+  }
+  __syncthreads();
+  if (tid == 0) hist[0] = (uint32_t)((int64_t)L.rows * L.cols) - nb0;
+  __syncthreads();
   pick_bin(hist, k, out, scratch);
   const uint32_t b1 = out[0], need2 = k - out[1];
-  const bool hit = guess != kNoGuess && (b1 == guess || b1 == guess + 1u);
-  const uint32_t side = (hit && b1 != guess) ? 1u : 0u;
+  const uint32_t glo = max(guess, 1u);                     // the bins pass A staged: glo, glo + 1
+  const bool hit = guess != kNoGuess && b1 != 0u && (b1 == glo || b1 == glo + 1u);
+  const uint32_t side = hit ? b1 - glo : 0u;
   if (tid == 0) {
     sp->b1 = b1; sp->need2 = need2; sp->k = k; sp->side = side; sp->zeros = 0u;
     sp->mode = hit ? 0u : 1u;
@@ -540,18 +564,9 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
     return;
   }
   __syncthreads();
-  // level 2: the summed counts of bin b1
+  // level 2: the summed counts of bin b1 (a threshold in bin 0 never gets here)
   for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = (b < kL2Bins) ? sub[side * kL2Bins + b] : 0u;
   __syncthreads();
-  if (b1 == 0u) {
-    // exact zeros are keys of bin 0, level-2 bin 0, that were never staged
-    const int64_t qbase = (int64_t)w * ws.q_stride + L.qoff;
-    uint32_t z = 0;
-    for (int q = tid; q < 4 * L.ntiles; q += kPickThreads) z += ws.qinfo[qbase + q].w;
-    z = wave_sum_u32(z);
-    if (lane == 0 && z) { atomicAdd(&hist[0], z); atomicAdd(&sp->zeros, z); }
-    __syncthreads();
-  }
   pick_bin(hist, need2, out, scratch);
   if (tid == 0) {
     sp->b2 = out[0];
@@ -572,9 +587,8 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   SelState* sp = ws.sel + wl;
   const int tl = ft.start >> kTileShift;
   const int64_t qslot = quarter_slot(ws, L, w, tl, wave);
-  // both halves of the segment are requested before the layer's state has arrived
-  const QuarterKeys qk0 = load_quarter_keys(ws, qslot, 0u, lane);
-  const QuarterKeys qk1 = load_quarter_keys(ws, qslot, 1u, lane);
+  // the segment is requested before the layer's state has arrived
+  const QuarterKeys qk = load_quarter_keys(ws, qslot, lane);
   const uint32_t side = sp->side, b1 = sp->b1;
   uint32_t b2 = sp->b2;
   if (sp->mode != 0u) {                                    // uniform over the workgroup
@@ -591,11 +605,6 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
     pick_bin(hist, need2, out, scratch);
     b2 = out[0];
     if (tl == 0 && tid == 0) { sp->b2 = b2; sp->need3 = need2 - out[1]; }
-  }
-  QuarterKeys qk = qk0;                                     // a re-staged layer uses the first half
-  if (side != 0u) {
-#pragma unroll
-    for (int ch = 0; ch < kFirstChunks; ++ch) qk.chunk[ch] = qk1.chunk[ch];
   }
   uint32_t* list = ws.qlist + qslot * kQListCap;
   uint32_t n_gt = 0, n_in = 0;                             // wave-uniform
@@ -740,7 +749,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
     // class): sweeps of the workgroup over the keys of bin b1 of the whole layer.
     auto sweep = [&](auto per_key, auto per_quarter) {
       for (int q = wave; q < nq; q += kPickWaves) {
-        const QuarterKeys qk = load_quarter_keys(ws, qbase + q, side, lane);
+        const QuarterKeys qk = load_quarter_keys(ws, qbase + q, lane);
         const uint32_t above = for_quarter_keys(ws, L, w, q >> 2, q & 3, qk, side, b1, false, lane, per_key);
         per_quarter(q, above);
       }
