@@ -21,6 +21,9 @@ What is computed, and where the paper defines it
 * Accumulated per-layer gradient, its norm, the critical-regime test and the two
   levels: Section 4.2 (equation and Algorithm 1), "Computational and memory
   overhead".
+* The optimizer that consumes the averaged decompressed gradient: SGD with
+  Nesterov momentum 0.9 (Appendix A, table "Hyperparameters") applied to the
+  update rule of Section 3.
 
 Precision: operands and stored state are fp32 (the paper's implementation is
 fp32 PyTorch); every contraction, norm and orthogonalisation is evaluated in fp64
@@ -28,6 +31,9 @@ on those fp32 operands and rounded to fp32 where it is stored.  The error-feedba
 add, the TopK comparison and the regime decision are taken in fp32, because they
 decide integers (which entries are kept, which level is used) and both sides must
 decide in the same precision.
+
+The optimizer update is taken in fp32, one rounding per multiplication and per
+addition, in the order written in nesterov_update.
 
 Pins: tests/test_oracle_*.py check every function below against brute force on
 tiny inputs, library QR/SVD, closed forms, the paper's printed "Data Sent"
@@ -162,6 +168,30 @@ def regime_is_critical(old, curr, has_old: bool, eta, lr_curr, lr_next) -> bool:
     return bool(F32(ratio) >= F32(eta))
 
 
+def nesterov_update(w: np.ndarray, v: np.ndarray, d: np.ndarray, lr, momentum,
+                    weight_decay=0.0) -> Tuple[np.ndarray, np.ndarray]:
+    """One step of SGD with Nesterov momentum on the averaged decompressed gradient d
+    (Appendix A, table "Hyperparameters": optimizer Nesterov, momentum 0.9; Section 3:
+    w_{k+1} = w_k - gamma_k * mean_i C(g_i), here with the momentum term):
+
+        d' = d + lambda * w          (only if lambda != 0; the paper names no weight decay)
+        v  = mu * v + d'             (velocity, zero before the first step)
+        w  = w - gamma * (d' + mu * v)
+
+    Every product and every sum is rounded to fp32 on its own, in this order.
+    Returns (w, v) after the step."""
+    w = np.asarray(w, dtype=F32)
+    v = np.asarray(v, dtype=F32)
+    d = np.asarray(d, dtype=F32)
+    lr, mu, lam = F32(lr), F32(momentum), F32(weight_decay)
+    if lam != F32(0.0):
+        d = (d + (lam * w).astype(F32)).astype(F32)
+    v_new = ((mu * v).astype(F32) + d).astype(F32)
+    look = (d + (mu * v_new).astype(F32)).astype(F32)
+    w_new = (w - (lr * look).astype(F32)).astype(F32)
+    return w_new, v_new
+
+
 # ---------------------------------------------------------------------------
 # the whole path as a state machine
 # ---------------------------------------------------------------------------
@@ -265,6 +295,17 @@ class AccordionOracle:
         self.words_last = words
         self.words_cum += words
         return out
+
+    def step_update(self, grads: Sequence[np.ndarray], w: np.ndarray, v: np.ndarray, lr,
+                    momentum, weight_decay=0.0) -> np.ndarray:
+        """One training step followed by the optimizer: the averaged decompressed gradient
+        of step() drives nesterov_update on every element that belongs to a layer; w and v
+        (N, fp32) are changed in place.  Returns the averaged gradient."""
+        d = self.step(grads)
+        for off, rows, cols, _ in self.layers:
+            sl = slice(off, off + rows * cols)
+            w[sl], v[sl] = nesterov_update(w[sl], v[sl], d[sl], lr, momentum, weight_decay)
+        return d
 
     # -- end of a window -----------------------------------------------------
     def detect_regime(self, lr_curr: float, lr_next: float) -> np.ndarray:
