@@ -58,6 +58,9 @@ def parse():
     ap.add_argument("--kernel-events", default="dominant", choices=["dominant", "all", "none"],
                     help="which kernels are bracketed with HIP events in the timed region: the fused "
                          "error-feedback pass only (default), every kernel, or none")
+    ap.add_argument("--fused-update", action="store_true",
+                    help="end every step with the fused Nesterov-momentum update of weights and velocity "
+                         "(accordion_step_all_update) instead of storing the averaged gradient")
     ap.add_argument("--fixed-level", type=int, default=-1, help="0/1: never switch, use this level")
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB read and MiB written per launch); 0: skip")
@@ -143,6 +146,10 @@ def main():
     dev = torch.device("cuda:0")
     base = [[torch.from_numpy(wl.gradient(w, k, s)).to(dev) for k in range(W)] for s in range(args.pool)]
     out = torch.empty(N, dtype=torch.float32, device=dev)
+    weights = velocity = None
+    if args.fused_update:
+        weights = torch.full((N,), 0.01, dtype=torch.float32, device=dev)
+        velocity = torch.zeros(N, dtype=torch.float32, device=dev)
     if args.fixed_level in (0, 1):
         st = gpu.unpack_state(gpu.get_state())
         blob = gpu.pack_state(st["e"], st["A"], st["Q"], st["norm_old"], st["has_old"],
@@ -174,7 +181,10 @@ def main():
 
     def one_step():
         s = state["step"]
-        gpu.step_all(base[s % args.pool], out)
+        if args.fused_update:
+            gpu.step_all_update(base[s % args.pool], weights, velocity, LR_CURR, 0.9, 0.0)
+        else:
+            gpu.step_all(base[s % args.pool], out)
         if args.fixed_level < 0 and (s + 1) % args.window == 0:
             decay = ((s + 1) // args.window) % 2 == 1      # every second window ends with an LR decay
             gpu.detect_regime(LR_CURR, LR_CURR * 0.1 if decay else LR_CURR)
@@ -233,7 +243,8 @@ def main():
                    "method": "topk" if w.method == B.ACC_TOPK else "powersgd",
                    "level_crit": w.level_crit, "level_noncrit": w.level_noncrit,
                    "window_steps": args.window, "pool_batches": args.pool,
-                   "levels_switch": args.fixed_level < 0, "kernel_events_in_timed_region": args.kernel_events},
+                   "levels_switch": args.fixed_level < 0,
+                   "sink": "nesterov update of weights and velocity" if args.fused_update else "averaged gradient stored", "kernel_events_in_timed_region": args.kernel_events},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "copy_probe": copy_probe,

@@ -138,6 +138,27 @@ int32_t accordion_decompress(acc_ctx* ctx, float* out_dev);
  * pointers (N floats each).  Same results as the call-by-call sequence. */
 int32_t accordion_step_all(acc_ctx* ctx, const float* const* grads_host_array, float* out_dev);
 
+/* The optimizer that consumes the averaged decompressed gradient, fused into the pass that would
+ * store it: SGD with Nesterov momentum (App. A, table "Hyperparameters": Nesterov, momentum 0.9)
+ * on the update rule of Sec. 3.  With D as accordion_decompress defines it, for every element
+ * that belongs to a layer (others are not touched):
+ *     d = D + weight_decay * w   (only if weight_decay != 0; the paper names none)
+ *     v = momentum * v + d
+ *     w = w - lr * (d + momentum * v)
+ * in fp32, every product and every sum rounded on its own, in this order.  D itself is not
+ * stored anywhere (4 bytes per element written and read again saved).
+ * weights_dev, velocity_dev: N floats each, DEVICE, 16-byte aligned, distinct, owned by the
+ * caller; the velocity starts at zero.  lr, momentum, weight_decay: finite, >= 0.
+ * accordion_decompress_update takes the place of accordion_decompress in the call-by-call
+ * sequence, accordion_step_all_update that of accordion_step_all; state machine, effects on the
+ * error memory and the accumulator, and errors are theirs (plus ACC_EINVAL for the arguments
+ * above, checked before anything is launched). */
+int32_t accordion_decompress_update(acc_ctx* ctx, float* weights_dev, float* velocity_dev, float lr,
+                                    float momentum, float weight_decay);
+int32_t accordion_step_all_update(acc_ctx* ctx, const float* const* grads_host_array,
+                                  float* weights_dev, float* velocity_dev, float lr, float momentum,
+                                  float weight_decay);
+
 /* End of a window (Sec. 4.2; Algorithm 1): c_l = ||A_l||_2 (fp64 sum, fp32 result), per layer
  * critical <=> no previous norm, previous norm 0, |old - c| / old >= eta, or lr_next < lr_curr;
  * level <- critical; old <- c; A <- 0.  Only between steps (else ACC_ESTATE). */
@@ -196,7 +217,7 @@ int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
  * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
  * accordion_stage_name gives the kernel's name (NULL if out of range). */
-#define ACC_N_STAGES 18
+#define ACC_N_STAGES 21
 int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
 int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
 const char* accordion_stage_name(int32_t stage);

@@ -50,13 +50,14 @@ _lib = None
 EXPORTS = [
     "accordion_workspace_bytes", "accordion_init", "accordion_destroy", "accordion_last_error",
     "accordion_compress_step", "accordion_aggregate", "accordion_decompress", "accordion_step_all",
+    "accordion_decompress_update", "accordion_step_all_update",
     "accordion_detect_regime", "accordion_reset_accumulator", "accordion_get_levels",
     "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
     "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
     "accordion_probe_copy", "accordion_topk_stats", "accordion_flush",
 ]
-ACC_N_STAGES = 18
+ACC_N_STAGES = 21
 
 
 def load_library() -> C.CDLL:
@@ -77,6 +78,8 @@ def load_library() -> C.CDLL:
         "accordion_aggregate": [vp, i32],
         "accordion_decompress": [vp, vp],
         "accordion_step_all": [vp, C.POINTER(vp), vp],
+        "accordion_decompress_update": [vp, vp, vp, f32, f32, f32],
+        "accordion_step_all_update": [vp, C.POINTER(vp), vp, vp, f32, f32, f32],
         "accordion_detect_regime": [vp, f32, f32],
         "accordion_reset_accumulator": [vp],
         "accordion_flush": [vp],
@@ -205,6 +208,16 @@ class Accordion:
         arr = (C.c_void_p * len(grads))(*[g.data_ptr() for g in grads])
         _check(self._lib, self.ctx,
                self._lib.accordion_step_all(self.ctx, arr, C.c_void_p(out.data_ptr())))
+
+    def decompress_update(self, weights, velocity, lr: float, momentum: float, weight_decay: float = 0.0) -> None:
+        _check(self._lib, self.ctx, self._lib.accordion_decompress_update(
+            self.ctx, C.c_void_p(weights.data_ptr()), C.c_void_p(velocity.data_ptr()), lr, momentum, weight_decay))
+
+    def step_all_update(self, grads: Sequence, weights, velocity, lr: float, momentum: float,
+                        weight_decay: float = 0.0) -> None:
+        arr = (C.c_void_p * len(grads))(*[g.data_ptr() for g in grads])
+        _check(self._lib, self.ctx, self._lib.accordion_step_all_update(
+            self.ctx, arr, C.c_void_p(weights.data_ptr()), C.c_void_p(velocity.data_ptr()), lr, momentum, weight_decay))
 
     def detect_regime(self, lr_curr: float, lr_next: float) -> None:
         _check(self._lib, self.ctx, self._lib.accordion_detect_regime(self.ctx, lr_curr, lr_next))

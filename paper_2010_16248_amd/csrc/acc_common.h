@@ -224,6 +224,34 @@ __device__ __forceinline__ void stq(float* __restrict__ p, int64_t a0, int64_t l
   else st_quad(p, a0 + 4 * (int64_t)q, lo, hi, v);
 }
 
+// ---- where the averaged decompressed gradient goes -------------------------------------------
+// Either it is written to `out`, or it is consumed on the spot by SGD with Nesterov momentum
+// (Appendix A, table "Hyperparameters"; update rule of Section 3) on the weights `wt` and the
+// velocity `vel`, and never stored.
+struct Sink {
+  float* out;
+  float* wt;
+  float* vel;
+  float lr, mu, wd;
+};
+
+// d' = d + wd w (if wd != 0);  v = mu v + d';  w = w - lr (d' + mu v).  Every product and every sum
+// is rounded on its own (the library is built with floating-point contraction off), so that the
+// result has one definite value.
+__device__ __forceinline__ void nesterov(float d, float& w, float& v, float lr, float mu, float wd) {
+  if (wd != 0.f) d = d + wd * w;
+  v = mu * v + d;
+  const float look = d + mu * v;
+  w = w - lr * look;
+}
+
+__device__ __forceinline__ void nesterov4(const float4& d, float4& w, float4& v, const Sink& s) {
+  nesterov(d.x, w.x, v.x, s.lr, s.mu, s.wd);
+  nesterov(d.y, w.y, v.y, s.lr, s.mu, s.wd);
+  nesterov(d.z, w.z, v.z, s.lr, s.mu, s.wd);
+  nesterov(d.w, w.w, v.w, s.lr, s.mu, s.wd);
+}
+
 __device__ __forceinline__ float comp(const float4& v, int c) {
   return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w));
 }

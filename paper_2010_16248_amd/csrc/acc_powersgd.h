@@ -468,10 +468,13 @@ __global__ __launch_bounds__(256) void psgd_qmean_kernel(const Ws ws) {
 
 // ---- decompress: D = P^ Q_bar^T (the residual stays implicit) ----------------------------------
 
-// RESIDUAL = false: writes D of the tile to out.  RESIDUAL = true: e = Delta - D in place.
-template <bool RESIDUAL, bool V4>
+// MODE 0: writes D of the tile to sink.out.  MODE 1: e = Delta - D in place.  MODE 2: D drives the
+// optimizer step on sink.wt / sink.vel and is not stored.
+template <int MODE, bool V4>
 __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, float* __restrict__ e,
-                            float* __restrict__ out, int r) {
+                            const Sink& sink, int r) {
+  constexpr bool RESIDUAL = MODE == 1;
+  constexpr bool UPD = MODE == 2;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int col[4]; bool cm[4];
@@ -486,12 +489,16 @@ __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, f
   const float* __restrict__ ph = ws.Phat + L.p_off;
   constexpr int B = 4;
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
-    float d[B][4];
-    if (RESIDUAL) {
+    float d[B][4], vv[UPD ? B : 1][4];
+    if (RESIDUAL || UPD) {
 #pragma unroll
       for (int b = 0; b < B; ++b) {
         const int i = i0 + 4 * b;
-        if (i < row_end) load_row<V4>(e, L.offset + (int64_t)i * L.cols, col, cm, d[b]);
+        if (i < row_end) {
+          const int64_t rb = L.offset + (int64_t)i * L.cols;
+          load_row<V4>(UPD ? sink.wt : e, rb, col, cm, d[b]);
+          if (UPD) load_row<V4>(sink.vel, rb, col, cm, vv[UPD ? b : 0]);
+        }
       }
     }
 #pragma unroll
@@ -510,8 +517,13 @@ __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, f
 #pragma unroll
           for (int v = 0; v < 4; ++v) res[v] = d[b][v] - D[v];
           store_row<V4>(e, rb, col, cm, res);
+        } else if (UPD) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) nesterov(D[v], d[b][v], vv[UPD ? b : 0][v], sink.lr, sink.mu, sink.wd);
+          store_row<V4>(sink.wt, rb, col, cm, d[b]);
+          store_row<V4>(sink.vel, rb, col, cm, vv[UPD ? b : 0]);
         } else {
-          store_row<V4>(out, rb, col, cm, D);
+          store_row<V4>(sink.out, rb, col, cm, D);
         }
       }
     }
@@ -520,7 +532,8 @@ __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, f
 
 // The averaged decompressed gradient: D on matrix layers, the plain mean on 1-D layers (which keep
 // no memory: their e is cleared for every worker).
-__global__ __launch_bounds__(256) void psgd_decomp_kernel(const Ws ws, float* __restrict__ out) {
+template <bool UPD>
+__device__ __forceinline__ void decomp_body(const Ws& ws, const Sink& sink) {
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     ws.words[1] = ws.words[0];
     ws.words[2] += ws.words[0];
@@ -531,15 +544,32 @@ __global__ __launch_bounds__(256) void psgd_decomp_kernel(const Ws ws, float* __
     for (int i = threadIdx.x; i < ft.count; i += kFlatThreads) {
       const int64_t a = L.offset + ft.start + i;
       for (int w = 0; w < ws.W; ++w) ws.e[(int64_t)w * ws.e_stride + a] = 0.f;
-      out[a] = ws.vecmean[L.vec_off + ft.start + i];
+      const float d = ws.vecmean[L.vec_off + ft.start + i];
+      if (UPD) {
+        float wv = sink.wt[a], vv = sink.vel[a];
+        nesterov(d, wv, vv, sink.lr, sink.mu, sink.wd);
+        sink.wt[a] = wv;
+        sink.vel[a] = vv;
+      } else {
+        sink.out[a] = d;
+      }
     }
     return;
   }
   const MatTile t = ws.mtiles[blockIdx.x];
   const LayerDev& L = ws.layers[t.layer];
   const int r = ws.rank_used[t.layer];                     // written by the orthogonalisation of this step
-  if (L.vec4) decomp_tile<false, true>(ws, L, t, nullptr, out, r);
-  else decomp_tile<false, false>(ws, L, t, nullptr, out, r);
+  if (L.vec4) decomp_tile<UPD ? 2 : 0, true>(ws, L, t, nullptr, sink, r);
+  else decomp_tile<UPD ? 2 : 0, false>(ws, L, t, nullptr, sink, r);
+}
+
+__global__ __launch_bounds__(256) void psgd_decomp_kernel(const Ws ws, const Sink sink) {
+  decomp_body<false>(ws, sink);
+}
+
+// The same pass with the optimizer step in place of the store of D.
+__global__ __launch_bounds__(256) void psgd_decomp_update_kernel(const Ws ws, const Sink sink) {
+  decomp_body<true>(ws, sink);
 }
 
 // e_w = Delta_w - D for the workers whose bit is set in `pending`, in place.
@@ -550,8 +580,9 @@ __global__ __launch_bounds__(256) void psgd_residual_kernel(const Ws ws, uint32_
   const MatTile t = ws.mtiles[blockIdx.x];
   const LayerDev& L = ws.layers[t.layer];
   const int r = ws.rank_used[t.layer];
-  if (L.vec4) decomp_tile<true, true>(ws, L, t, e, nullptr, r);
-  else decomp_tile<true, false>(ws, L, t, e, nullptr, r);
+  const Sink none = {nullptr, nullptr, nullptr, 0.f, 0.f, 0.f};
+  if (L.vec4) decomp_tile<1, true>(ws, L, t, e, none, r);
+  else decomp_tile<1, false>(ws, L, t, e, none, r);
 }
 
 }  // namespace acc

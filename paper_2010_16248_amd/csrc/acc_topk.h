@@ -993,9 +993,11 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
 // kMeanBatch workers ahead.
 constexpr int kMeanBatch = 4;
 
-template <bool AL>
+// UPD: the mean is not written out but drives the optimizer step on the weights and the velocity
+// (read at the top of a group, so that they arrive while the workers are compacted).
+template <bool AL, bool UPD>
 __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& ft, const LayerDev& L,
-                                                  const TileGeom& tg, float* __restrict__ out) {
+                                                  const TileGeom& tg, const Sink sink) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const WaveSpan span = wave_span(tg, wave);
@@ -1028,6 +1030,11 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   for (int j = 0; j < n; ++j) {
     const int q = span.qbeg + j * kWave + lane;
     float4 acc = zero4;
+    float4 wq = zero4, vq = zero4;
+    if (UPD) {
+      wq = ld_span<AL>(sink.wt, tg, span, q);
+      vq = ld_span<AL>(sink.vel, tg, span, q);
+    }
     for (int wb = 0; wb < W; wb += kMeanBatch) {
       int j2 = j, wb2 = wb + kMeanBatch;
       if (wb2 >= W) { wb2 = 0; ++j2; }
@@ -1059,12 +1066,19 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
     }
     if (q < span.qend) {
       const float4 v = make_float4(acc.x / fw, acc.y / fw, acc.z / fw, acc.w / fw);
-      stq<AL>(out, tg.a0, tg.lo, tg.hi, q, v);
+      if (UPD) {
+        nesterov4(v, wq, vq, sink);
+        stq<AL>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
+        stq<AL>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
+      } else {
+        stq<AL>(sink.out, tg.a0, tg.lo, tg.hi, q, v);
+      }
     }
   }
 }
 
-__global__ __launch_bounds__(256) void topk_compact_mean_kernel(const Ws ws, float* __restrict__ out) {
+template <bool UPD>
+__device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink) {
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
@@ -1073,13 +1087,23 @@ __global__ __launch_bounds__(256) void topk_compact_mean_kernel(const Ws ws, flo
     ws.words[2] += ws.words[0];
   }
   if (blockIdx.x == 0 && threadIdx.x < ws.W) ws.miss_any[threadIdx.x] = 0u;
-  if (tg.aligned) compact_mean_tile<true>(ws, ft, L, tg, out);
-  else compact_mean_tile<false>(ws, ft, L, tg, out);
+  if (tg.aligned) compact_mean_tile<true, UPD>(ws, ft, L, tg, sink);
+  else compact_mean_tile<false, UPD>(ws, ft, L, tg, sink);
+}
+
+__global__ __launch_bounds__(256) void topk_compact_mean_kernel(const Ws ws, const Sink sink) {
+  compact_mean_body<false>(ws, sink);
+}
+
+// The same pass with the optimizer step in place of the store of the mean.
+__global__ __launch_bounds__(256) void topk_compact_update_kernel(const Ws ws, const Sink sink) {
+  compact_mean_body<true>(ws, sink);
 }
 
 // ---- K6: dense mean of the W payloads (call-by-call path) ----------------------------------------
 
-__global__ __launch_bounds__(256) void topk_sparse_mean_kernel(const Ws ws, float* __restrict__ out) {
+template <bool UPD>
+__device__ __forceinline__ void sparse_mean_body(const Ws& ws, const Sink& sink) {
   __shared__ float acc[kTile];
   const int tid = threadIdx.x;
   const FlatTile ft = ws.ftiles[blockIdx.x];
@@ -1116,8 +1140,24 @@ __global__ __launch_bounds__(256) void topk_sparse_mean_kernel(const Ws ws, floa
     v.y = (i0 + 1 >= 0 && i0 + 1 < ft.count) ? acc[i0 + 1] / fw : 0.f;
     v.z = (i0 + 2 >= 0 && i0 + 2 < ft.count) ? acc[i0 + 2] / fw : 0.f;
     v.w = (i0 + 3 >= 0 && i0 + 3 < ft.count) ? acc[i0 + 3] / fw : 0.f;
-    st_quad(out, base, tg.lo, tg.hi, v);
+    if (UPD) {
+      float4 wq = ld_quad(sink.wt, base, tg.lo, tg.hi);
+      float4 vq = ld_quad(sink.vel, base, tg.lo, tg.hi);
+      nesterov4(v, wq, vq, sink);
+      st_quad(sink.wt, base, tg.lo, tg.hi, wq);
+      st_quad(sink.vel, base, tg.lo, tg.hi, vq);
+    } else {
+      st_quad(sink.out, base, tg.lo, tg.hi, v);
+    }
   }
+}
+
+__global__ __launch_bounds__(256) void topk_sparse_mean_kernel(const Ws ws, const Sink sink) {
+  sparse_mean_body<false>(ws, sink);
+}
+
+__global__ __launch_bounds__(256) void topk_sparse_update_kernel(const Ws ws, const Sink sink) {
+  sparse_mean_body<true>(ws, sink);
 }
 
 }  // namespace acc

@@ -243,6 +243,7 @@ enum Stage {
   ST_topk_count3_kernel, ST_topk_pick3_kernel,
   ST_topk_compact_kernel, ST_topk_compact_mean_kernel, ST_topk_sparse_mean_kernel,
   ST_norm_partial_kernel, ST_regime_decide_kernel, ST_recount_words_kernel, ST_zero_accum_kernel,
+  ST_psgd_decomp_update_kernel, ST_topk_compact_update_kernel, ST_topk_sparse_update_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
@@ -251,7 +252,8 @@ static const char* const kStageNames[ST_COUNT] = {
   "psgd_decomp_kernel", "psgd_residual_kernel", "topk_ef_hist_kernel", "topk_pick12_kernel", "topk_restage_kernel",
   "topk_count3_kernel", "topk_pick3_kernel",
   "topk_compact_kernel", "topk_compact_mean_kernel", "topk_sparse_mean_kernel",
-  "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel"};
+  "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel",
+  "psgd_decomp_update_kernel", "topk_compact_update_kernel", "topk_sparse_update_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
 
@@ -401,20 +403,39 @@ int launch_agg1(acc_ctx* c) {
   return ACC_OK;
 }
 
-int launch_decompress(acc_ctx* c, float* out) {
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+Sink sink_out(float* out) { return Sink{out, nullptr, nullptr, 0.f, 0.f, 0.f}; }
+
+// sink.wt != nullptr: the optimizer step consumes the averaged gradient instead of a store.
+int launch_decompress(acc_ctx* c, const Sink& sink) {
   const Ws& ws = c->ws;
   if (c->cfg.method == ACC_POWERSGD) {
-    ACC_LAUNCH(c, psgd_decomp_kernel, dim3(ws.n_mtiles + ws.n_vectiles), dim3(256), ws, out);
+    const dim3 grid(ws.n_mtiles + ws.n_vectiles);
+    if (sink.wt) ACC_LAUNCH(c, psgd_decomp_update_kernel, grid, dim3(256), ws, sink);
+    else ACC_LAUNCH(c, psgd_decomp_kernel, grid, dim3(256), ws, sink);
     c->pending_mask = all_workers_mask(c);
   } else {
-    ACC_LAUNCH(c, topk_sparse_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, out);
+    if (sink.wt) ACC_LAUNCH(c, topk_sparse_update_kernel, dim3(ws.n_ftiles), dim3(256), ws, sink);
+    else ACC_LAUNCH(c, topk_sparse_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, sink);
   }
   return ACC_OK;
 }
 
-int launch_topk_compact_mean(acc_ctx* c, float* out) {
+int launch_topk_compact_mean(acc_ctx* c, const Sink& sink) {
   const Ws& ws = c->ws;
-  ACC_LAUNCH(c, topk_compact_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, out);
+  if (sink.wt) ACC_LAUNCH(c, topk_compact_update_kernel, dim3(ws.n_ftiles), dim3(256), ws, sink);
+  else ACC_LAUNCH(c, topk_compact_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, sink);
+  return ACC_OK;
+}
+
+// Arguments of the optimizer step: finite hyper-parameters, two distinct aligned device buffers.
+int check_sgd(acc_ctx* c, const float* w, const float* v, float lr, float mu, float wd) {
+  if (!w || !v) return fail(c->err, ACC_EINVAL, "weights_dev or velocity_dev is NULL");
+  if (misaligned(w) || misaligned(v)) return fail(c->err, ACC_EINVAL, "weights_dev / velocity_dev is not 16-byte aligned");
+  if (w == v) return fail(c->err, ACC_EINVAL, "weights_dev and velocity_dev are the same buffer");
+  if (!(std::isfinite(lr) && std::isfinite(mu) && std::isfinite(wd)) || lr < 0.f || mu < 0.f || wd < 0.f)
+    return fail(c->err, ACC_EINVAL, "lr, momentum and weight_decay must be finite and not negative");
   return ACC_OK;
 }
 
@@ -433,8 +454,6 @@ void end_step(acc_ctx* c) {
   c->p0_mask = c->p1_mask = 0;
   c->agg0 = c->agg1 = false;
 }
-
-bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 size_t state_bytes_of(const acc_ctx* c) {
   const Plan& p = c->plan;
@@ -636,23 +655,32 @@ int32_t accordion_aggregate(acc_ctx* c, int32_t phase) {
   return fail(c->err, ACC_EINVAL, "phase must be 0 or 1");
 }
 
-int32_t accordion_decompress(acc_ctx* c, float* out_dev) {
-  if (!c) return ACC_EINVAL;
-  if (!out_dev) return fail(c->err, ACC_EINVAL, "out_dev is NULL");
-  if (misaligned(out_dev)) return fail(c->err, ACC_EINVAL, "out_dev is not 16-byte aligned");
+static int32_t decompress_into(acc_ctx* c, const Sink& sink) {
   if (c->cfg.method == ACC_POWERSGD ? !c->agg1 : !c->agg0)
     return fail(c->err, ACC_ESTATE, "decompress before the aggregation of this step is complete");
-  const int rc = launch_decompress(c, out_dev);
+  const int rc = launch_decompress(c, sink);
   if (rc != ACC_OK) return rc;
   end_step(c);
   return ACC_OK;
 }
 
-int32_t accordion_step_all(acc_ctx* c, const float* const* grads_host_array, float* out_dev) {
+int32_t accordion_decompress(acc_ctx* c, float* out_dev) {
   if (!c) return ACC_EINVAL;
-  if (!grads_host_array) return fail(c->err, ACC_EINVAL, "grads_host_array is NULL");
   if (!out_dev) return fail(c->err, ACC_EINVAL, "out_dev is NULL");
   if (misaligned(out_dev)) return fail(c->err, ACC_EINVAL, "out_dev is not 16-byte aligned");
+  return decompress_into(c, sink_out(out_dev));
+}
+
+int32_t accordion_decompress_update(acc_ctx* c, float* weights_dev, float* velocity_dev, float lr,
+                                    float momentum, float weight_decay) {
+  if (!c) return ACC_EINVAL;
+  const int rc = check_sgd(c, weights_dev, velocity_dev, lr, momentum, weight_decay);
+  if (rc != ACC_OK) return rc;
+  return decompress_into(c, Sink{nullptr, weights_dev, velocity_dev, lr, momentum, weight_decay});
+}
+
+static int32_t step_all_into(acc_ctx* c, const float* const* grads_host_array, const Sink& sink) {
+  if (!grads_host_array) return fail(c->err, ACC_EINVAL, "grads_host_array is NULL");
   if (c->in_step) return fail(c->err, ACC_ESTATE, "a call-by-call step is in flight");
   const int W = c->cfg.n_workers;
   for (int w = 0; w < W; ++w) {
@@ -666,14 +694,29 @@ int32_t accordion_step_all(acc_ctx* c, const float* const* grads_host_array, flo
     if (rc == ACC_OK) rc = launch_agg0(c);
     if (rc == ACC_OK) rc = launch_phase1(c, 0, W);
     if (rc == ACC_OK) rc = launch_agg1(c);
-    if (rc == ACC_OK) rc = launch_decompress(c, out_dev);
+    if (rc == ACC_OK) rc = launch_decompress(c, sink);
   } else {
     // the compaction of all workers and the mean of their kept values share one pass over Delta
     rc = launch_topk_select(c, 0, W);
-    if (rc == ACC_OK) rc = launch_topk_compact_mean(c, out_dev);
+    if (rc == ACC_OK) rc = launch_topk_compact_mean(c, sink);
   }
   end_step(c);
   return rc;
+}
+
+int32_t accordion_step_all(acc_ctx* c, const float* const* grads_host_array, float* out_dev) {
+  if (!c) return ACC_EINVAL;
+  if (!out_dev) return fail(c->err, ACC_EINVAL, "out_dev is NULL");
+  if (misaligned(out_dev)) return fail(c->err, ACC_EINVAL, "out_dev is not 16-byte aligned");
+  return step_all_into(c, grads_host_array, sink_out(out_dev));
+}
+
+int32_t accordion_step_all_update(acc_ctx* c, const float* const* grads_host_array, float* weights_dev,
+                                  float* velocity_dev, float lr, float momentum, float weight_decay) {
+  if (!c) return ACC_EINVAL;
+  const int rc = check_sgd(c, weights_dev, velocity_dev, lr, momentum, weight_decay);
+  if (rc != ACC_OK) return rc;
+  return step_all_into(c, grads_host_array, Sink{nullptr, weights_dev, velocity_dev, lr, momentum, weight_decay});
 }
 
 int32_t accordion_detect_regime(acc_ctx* c, float lr_curr, float lr_next) {

@@ -1,0 +1,187 @@
+"""GPU parity of the fused optimizer step (accordion_step_all_update /
+accordion_decompress_update) against the oracle's step_update, through the C ABI.
+
+TopK: weights and velocity are bit-exact (the averaged gradient is, and the update is a fixed
+sequence of individually rounded fp32 operations).  PowerSGD: the decompressed gradient agrees
+with the oracle to 1e-5 relative per layer, so the update is compared (a) bit for bit against
+the same update applied on the CPU to the library's own stored D, and (b) against the oracle to
+the tolerance D carries over: |dw| <= lr (1 + mu) |dD|, |dv| <= |dD| per step."""
+import numpy as np
+import pytest
+
+from oracle import accordion_oracle as orc
+from paper_2010_16248_amd import binding as B
+from paper_2010_16248_amd import workloads as wl
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+LR, MU = 0.4, 0.9
+
+
+def _layer_mask(layers, n):
+    m = np.zeros(n, bool)
+    for off, r, c, _ in H.layer_tuples(layers):
+        m[off:off + r * c] = True
+    return m
+
+
+@pytest.mark.parametrize("wd", [0.0, 5e-4])
+def test_topk_fused_update_is_bit_exact(wd):
+    """Ragged misaligned layers (some elements of the flat buffers belong to no layer and must
+    not be touched), layers of several tiles with ragged tails, W = 3, five steps so that the
+    velocity and the error memory both feed back."""
+    print(f"case topk update wd={wd}", flush=True)
+    small = wl.random_layers(seed=21, n_layers=9, max_rows=30, max_cols=200)
+    base = max(l.offset + l.rows * l.cols for l in small)
+    base = (base + 7) // 4 * 4 + 1                                   # a misaligned start
+    big = [(base, 1, 3 * 8192 + 77, 0), (base + 3 * 8192 + 77 + 2, 37, 1001, 1)]
+    layers = H.layer_tuples(small) + big
+    N = big[1][0] + 37 * 1001                                        # gaps inside, none behind
+    W = 3
+    gpu = B.Accordion(B.ACC_TOPK, layers, W, 10, 1, 100, 0.5, 1, None)
+    assert gpu.n_params == N
+    ora = orc.AccordionOracle(orc.TOPK, layers, W, 10, 1, 100, 0.5, 1, None)
+    ora.N = N
+    ora.e = np.zeros((W, N), np.float32)
+    ora.A = np.zeros(N, np.float32)
+    rng = np.random.default_rng(2)
+    w_ref = rng.standard_normal(N).astype(np.float32)
+    v_ref = np.zeros(N, np.float32)
+    w_dev, v_dev = H.to_dev(w_ref), H.to_dev(v_ref)
+    outside = ~_layer_mask(layers, N)
+    assert outside.any()
+    w0 = w_ref.copy()
+    for step in range(5):
+        grads = [rng.standard_normal(N).astype(np.float32) for _ in range(W)]
+        ora.step_update(grads, w_ref, v_ref, LR, MU, wd)
+        gpu.step_all_update([H.to_dev(g) for g in grads], w_dev, v_dev, LR, MU, wd)
+        H.assert_bits_equal(w_dev.cpu().numpy(), w_ref, f"step {step}: weights")
+        H.assert_bits_equal(v_dev.cpu().numpy(), v_ref, f"step {step}: velocity")
+    assert np.array_equal(w_ref[outside], w0[outside])
+    st = gpu.unpack_state(gpu.get_state())
+    inside = ~outside                                                # the gaps carry no state
+    H.assert_bits_equal(st["e"][:, inside], ora.e[:, inside], "residual")
+    H.assert_bits_equal(st["A"][inside], ora.A[inside], "accumulator")
+    assert np.all(st["A"][outside] == 0) and np.all(st["e"][:, outside] == 0)
+    assert gpu.payload_words() == (ora.words_last, ora.words_cum)
+    gpu.destroy()
+
+
+def test_topk_call_by_call_update_equals_the_batched_one():
+    layers = wl.make_layers([(20, 900, 1), (1, 64, 0), (9, 9, 1), (1, 2 * 8192 + 3, 0)])
+    N = wl.total_params(layers)
+    W = 2
+    rng = np.random.default_rng(8)
+    grads = [[rng.standard_normal(N).astype(np.float32) for _ in range(W)] for _ in range(3)]
+    w0 = rng.standard_normal(N).astype(np.float32)
+    results = []
+    for mode in ("all", "calls"):
+        gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+        w_dev, v_dev = H.to_dev(w0), H.to_dev(np.zeros(N, np.float32))
+        w_ref, v_ref = w0.copy(), np.zeros(N, np.float32)
+        for step in range(3):
+            dg = [H.to_dev(g) for g in grads[step]]
+            if mode == "all":
+                gpu.step_all_update(dg, w_dev, v_dev, LR, MU, 1e-4)
+            else:
+                for w in range(W):
+                    gpu.compress_step(w, dg[w], 0)
+                gpu.aggregate(0)
+                gpu.decompress_update(w_dev, v_dev, LR, MU, 1e-4)
+            ora.step_update(grads[step], w_ref, v_ref, LR, MU, 1e-4)
+            H.assert_bits_equal(w_dev.cpu().numpy(), w_ref, f"{mode} step {step}: weights")
+            H.assert_bits_equal(v_dev.cpu().numpy(), v_ref, f"{mode} step {step}: velocity")
+        results.append(gpu.get_state().copy())
+        gpu.destroy()
+    assert np.array_equal(results[0], results[1])
+
+
+@pytest.mark.parametrize("mode", ["all", "calls"])
+def test_powersgd_fused_update(mode):
+    """Tiny configuration plus a 1-D layer and a matrix with a ragged column tail; teacher-forced
+    like the other PowerSGD comparisons."""
+    print(f"case powersgd update {mode}", flush=True)
+    layers = wl.make_layers([(64, 576, 1), (1, 300, 0), (33, 1030, 1), (10, 512, 1), (1, 7, 0)])
+    lt = H.layer_tuples(layers)
+    N = wl.total_params(layers)
+    W = 2
+    rng = np.random.default_rng(12)
+    q0 = rng.standard_normal(sum(c for (_, r, c, m) in lt if m) * 4).astype(np.float32)
+    gpu, ora = H.make_pair(B.ACC_POWERSGD, layers, W, 4, 2, 100, 0.5, 1, q0)
+    twin = B.Accordion(B.ACC_POWERSGD, lt, W, 4, 2, 100, 0.5, 1, q0)     # stores D for check (a)
+    w0 = rng.standard_normal(N).astype(np.float32)
+    w_dev, v_dev = H.to_dev(w0), H.to_dev(np.zeros(N, np.float32))
+    w_ref, v_ref = w0.copy(), np.zeros(N, np.float32)
+    out = H.dev_out(N)
+    wd = 1e-4
+    for step in range(4):
+        if step == 2:
+            ora.level[:] = 0                                               # rank 2 on the carried Q
+        blob = H.oracle_state_blob(gpu, ora)
+        gpu.set_state(blob)
+        twin.set_state(blob)
+        grads = [(rng.standard_normal(N) * 0.01).astype(np.float32) for _ in range(W)]
+        dg = [H.to_dev(g) for g in grads]
+        # teacher forcing of the optimizer state too
+        w_dev.copy_(H.to_dev(w_ref)); v_dev.copy_(H.to_dev(v_ref))
+        w_before, v_before = w_ref.copy(), v_ref.copy()
+        twin.step_all(dg, out)
+        if mode == "all":
+            gpu.step_all_update(dg, w_dev, v_dev, LR, MU, wd)
+        else:
+            for w in range(W):
+                gpu.compress_step(w, dg[w], 0)
+            gpu.aggregate(0)
+            for w in range(W):
+                gpu.compress_step(w, None, 1)
+            gpu.aggregate(1)
+            gpu.decompress_update(w_dev, v_dev, LR, MU, wd)
+        d_ref = ora.step_update(grads, w_ref, v_ref, LR, MU, wd)
+        got_w, got_v, d_gpu = w_dev.cpu().numpy(), v_dev.cpu().numpy(), out.cpu().numpy()
+        # (a) the same update on the library's own D, on the CPU: bit for bit
+        for off, r, c, _ in lt:
+            sl = slice(off, off + r * c)
+            ew, ev = orc.nesterov_update(w_before[sl], v_before[sl], d_gpu[sl], LR, MU, wd)
+            H.assert_bits_equal(got_w[sl], ew, f"step {step}: weights from the stored D")
+            H.assert_bits_equal(got_v[sl], ev, f"step {step}: velocity from the stored D")
+            # (b) against the oracle, to what D's tolerance carries over
+            dd = np.linalg.norm(d_gpu[sl].astype(np.float64) - d_ref[sl])
+            assert dd <= 1e-5 * np.linalg.norm(d_ref[sl]) + 1e-12
+            eps = 4 * np.finfo(np.float32).eps
+            assert np.linalg.norm(got_v[sl].astype(np.float64) - v_ref[sl]) <= dd + eps * np.linalg.norm(v_ref[sl])
+            assert np.linalg.norm(got_w[sl].astype(np.float64) - w_ref[sl]) <= \
+                LR * (1 + MU) * dd + eps * np.linalg.norm(w_ref[sl])
+        # error memory and accumulator are what the unfused step leaves
+        assert np.array_equal(gpu.get_state(), twin.get_state())
+    gpu.destroy()
+    twin.destroy()
+
+
+def test_update_argument_errors_touch_nothing():
+    layers = wl.make_layers([(4, 10, 1)])
+    gpu, _ = H.make_pair(B.ACC_TOPK, layers, 1, 50, 10)
+    g = H.to_dev(np.ones(40, np.float32))
+    w = H.to_dev(np.ones(44, np.float32))
+    v = H.to_dev(np.zeros(44, np.float32))
+    bad = [
+        dict(weights=w, velocity=w, lr=0.1, momentum=0.9),                # same buffer
+        dict(weights=w[1:], velocity=v, lr=0.1, momentum=0.9),            # misaligned
+        dict(weights=w, velocity=v, lr=-0.1, momentum=0.9),
+        dict(weights=w, velocity=v, lr=0.1, momentum=float("nan")),
+        dict(weights=w, velocity=v, lr=0.1, momentum=0.9, weight_decay=float("inf")),
+    ]
+    for kw in bad:
+        with pytest.raises(B.AccordionError) as ei:
+            gpu.step_all_update([g], **kw)
+        assert ei.value.status == B.ACC_EINVAL
+    with pytest.raises(B.AccordionError) as ei:
+        gpu.decompress_update(w, v, 0.1, 0.9)                             # no step in flight
+    assert ei.value.status == B.ACC_ESTATE
+    assert np.all(w.cpu().numpy() == 1.0) and np.all(v.cpu().numpy() == 0.0)
+    assert gpu.payload_words() == (0, 0)
+    # and the good call: k = 20 of 40 equal entries -> the first 20 move by lr (1 + mu)
+    gpu.step_all_update([g], w, v, 0.5, 0.5)
+    ww = w.cpu().numpy()
+    assert np.all(ww[:20] == 1.0 - 0.5 * 1.5) and np.all(ww[20:] == 1.0)
+    gpu.destroy()
