@@ -21,6 +21,12 @@ What is computed, and where the paper defines it
 * Accumulated per-layer gradient, its norm, the critical-regime test and the two
   levels: Section 4.2 (equation and Algorithm 1), "Computational and memory
   overhead".
+* Batch-size mode (Section 3 "Distributed SGD with adaptive batch size"; Section
+  4.2: the same algorithm switching B_low / B_high on the gradient of the whole
+  model; Section 5.1 "Hyperparameters": learning rate scaled in the same ratio;
+  Appendix A "Additional Details for Batch Size experiment": the large batch is
+  several backward passes accumulated before one exchange, and the batch size is
+  only allowed to grow).
 * The optimizer that consumes the averaged decompressed gradient: SGD with
   Nesterov momentum 0.9 (Appendix A, table "Hyperparameters") applied to the
   update rule of Section 3.
@@ -336,3 +342,107 @@ class AccordionOracle:
             else:
                 total += 2 * self.layer_k(li)
         return total
+
+
+# ---------------------------------------------------------------------------
+# batch-size mode
+# ---------------------------------------------------------------------------
+
+class BatchSizeOracle:
+    """Accordion switching the batch size instead of the compression level.
+
+    One call of micro_step() is one backward pass of every worker on a micro-batch of
+    B_low samples.  Inside a critical regime (level 1) every micro-step is exchanged
+    (batch B_low); outside (level 0) `multiplier` = floor(B_high / B_low) micro-steps
+    are summed locally first and exchanged once (batch B_high), so that the workers
+    communicate `multiplier` times less (Section 3).  The exchanged gradient is the
+    mean over workers and accumulated micro-steps; the learning rate of that update is
+    the base rate times the number of micro-steps in it (Section 5.1).
+
+    The detector looks at the whole model (Section 4.2): A sums worker 0's raw
+    micro-batch gradients over the window, one norm over all layers, Algorithm 1 once.
+    monotone (Appendix A): once the large batch is reached the level never returns.
+
+    fp32 state; sums in the order written (micro-steps in time order, workers in index
+    order starting from worker 0's sum), one division by W * (micro-steps)."""
+
+    def __init__(self, layers, n_workers: int, multiplier: int, eta: float = 0.5,
+                 initial_level: int = 1, monotone: bool = True):
+        self.layers = [tuple(int(v) for v in l) for l in layers]
+        self.W = int(n_workers)
+        self.M = int(multiplier)
+        assert self.M >= 1
+        self.eta = F32(eta)
+        self.monotone = bool(monotone)
+        self.N = max(off + r * c for (off, r, c, _) in self.layers)
+        self.mask = np.zeros(self.N, dtype=bool)
+        for off, r, c, _ in self.layers:
+            self.mask[off:off + r * c] = True
+        self.S = np.zeros((self.W, self.N), dtype=F32)
+        self.A = np.zeros(self.N, dtype=F32)
+        self.j = 0                       # micro-steps summed since the last exchange
+        self.level = int(initial_level)
+        self.norm_old = F32(0.0)
+        self.norm_curr = F32(0.0)
+        self.norm_prev = F32(0.0)
+        self.has_old = 0
+        self.words_last = 0              # floats one worker sent in the last micro-step
+        self.words_cum = 0
+        self.exchanges = 0
+        self.n_model = int(self.mask.sum())
+
+    def micro_step(self, grads: Sequence[np.ndarray]):
+        """Returns (D, n_micro): the averaged gradient of the batch that this micro-step
+        completed and the number of micro-steps in it, or (None, 0) if nothing was
+        exchanged.  Elements outside every layer are zero in D."""
+        assert len(grads) == self.W
+        m = self.mask
+        self.A[m] = (self.A[m] + grads[0][m].astype(F32)).astype(F32)
+        for w in range(self.W):
+            if self.j == 0:
+                self.S[w, m] = grads[w][m].astype(F32)
+            else:
+                self.S[w, m] = (self.S[w, m] + grads[w][m].astype(F32)).astype(F32)
+        self.j += 1
+        target = 1 if self.level == 1 else self.M
+        if self.j < target:
+            self.words_last = 0
+            return None, 0
+        acc = self.S[0].copy()
+        for w in range(1, self.W):
+            acc = (acc + self.S[w]).astype(F32)
+        d = (acc / F32(self.W * self.j)).astype(F32)
+        d[~m] = F32(0.0)
+        n_micro = self.j
+        self.j = 0
+        self.words_last = self.n_model           # dense all-reduce of the whole model
+        self.words_cum += self.n_model
+        self.exchanges += 1
+        return d, n_micro
+
+    def micro_step_update(self, grads, w: np.ndarray, v: np.ndarray, lr, momentum,
+                          weight_decay=0.0) -> int:
+        """micro_step followed, when a batch was completed, by the optimizer step with the
+        learning rate lr * (micro-steps in the batch), the product rounded to fp32.
+        Returns the number of micro-steps in the applied batch (0: no update)."""
+        d, n_micro = self.micro_step(grads)
+        if d is None:
+            return 0
+        lr_eff = F32(F32(lr) * F32(n_micro))
+        m = self.mask
+        w[m], v[m] = nesterov_update(w[m], v[m], d[m], lr_eff, momentum, weight_decay)
+        return n_micro
+
+    def detect_regime(self, lr_curr: float, lr_next: float) -> int:
+        c = layer_norm(self.A[self.mask])
+        crit = regime_is_critical(self.norm_old, c, bool(self.has_old), self.eta, lr_curr, lr_next)
+        new_level = 1 if crit else 0
+        if self.monotone and self.level == 0:
+            new_level = 0                         # the batch size is only allowed to grow
+        self.level = new_level
+        self.norm_prev = self.norm_old
+        self.norm_curr = c
+        self.norm_old = c
+        self.has_old = 1
+        self.A[:] = F32(0.0)
+        return self.level
