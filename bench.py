@@ -50,7 +50,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18_topk",
-                    choices=["tiny_powersgd", "resnet18_topk", "resnet18_powersgd", "vgg19_powersgd", "lstm_topk"])
+                    choices=["tiny_powersgd", "resnet18_topk", "resnet18_powersgd", "vgg19_powersgd", "lstm_topk",
+                             "resnet18_batch"])
     ap.add_argument("--workers", type=int, default=0, help="override W of the workload")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept in HBM")
     ap.add_argument("--window", type=int, default=50, help="steps per detection window")
@@ -69,6 +70,8 @@ def parse():
 
 def dominant_kernel(method):
     from paper_2010_16248_amd import binding as B
+    if method == B.ACC_BATCH:
+        return "batch_micro_kernel"
     return "topk_ef_hist_kernel" if method == B.ACC_TOPK else "psgd_ef_p_kernel"
 
 
@@ -76,6 +79,13 @@ def algorithmic_bytes_dominant(n_params, W):
     """Fused error-feedback pass: per worker read g and e, write Delta (12 B / element); worker 0
     also reads and writes the accumulator (8 B / element)."""
     return n_params * (12 * W + 8)
+
+
+def algorithmic_bytes_batch(n_model, W, micro_steps, exchanges):
+    """Batch-size mode, total over `micro_steps` launches that completed `exchanges` batches: every
+    micro-step reads W gradients and reads and writes the accumulator; a batch of n micro-steps
+    writes and re-reads the W running sums n - 1 times; every completed batch writes D."""
+    return n_model * ((4 * W + 8) * micro_steps + 8 * W * (micro_steps - exchanges) + 4 * exchanges)
 
 
 def algorithmic_bytes_step(w, layers, W, levels_k_or_r):
@@ -99,6 +109,8 @@ def cpu_baseline(w, W, n_steps, window):
     except Exception:  # pragma: no cover
         threadpool_limits = None
     layers = [(l.offset, l.rows, l.cols, l.is_matrix) for l in w.layers]
+    if w.method == 2:
+        return cpu_baseline_batch(w, W, layers, orc, wl, threadpool_limits)
     rmax = max(w.level_crit, w.level_noncrit)
     q0 = wl.q_init(w, rmax, w.seed) if w.method == 0 else None
     ora = orc.AccordionOracle(w.method, layers, W, w.level_crit, w.level_noncrit, w.k_den, w.eta, 1, q0)
@@ -117,6 +129,27 @@ def cpu_baseline(w, W, n_steps, window):
     return {"value": round(gbs, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"{n_steps} full steps of {w.name} (all {W} workers, every layer) + 1 regime test, "
                       f"numpy oracle, 1 thread, {per_step:.3f} s/step",
+            "host_cpus": os.cpu_count()}
+
+
+def cpu_baseline_batch(w, W, layers, orc, wl, threadpool_limits):
+    """Batch-size mode: one full large batch (multiplier micro-steps) + one whole-model test."""
+    ora = orc.BatchSizeOracle(layers, W, w.batch_multiplier, w.eta, 0, True)
+    n_steps = w.batch_multiplier
+    grads = [[wl.gradient(w, k, s % 3) for k in range(W)] for s in range(n_steps)]
+    ctx = threadpool_limits(limits=1) if threadpool_limits else None
+    t0 = time.perf_counter()
+    for s in range(n_steps):
+        ora.micro_step(grads[s])
+    ora.detect_regime(0.1, 0.1)
+    t1 = time.perf_counter()
+    if ctx is not None:
+        ctx.restore_original_limits()
+    per_step = (t1 - t0) / n_steps
+    return {"value": round(4.0 * w.n_params * W / per_step / 1e9, 4), "unit": "GB/s", "cores": 1,
+            "kind": "oracle",
+            "sample": f"{n_steps} micro-steps (one large batch) of {w.name}, all {W} workers + 1 whole-model "
+                      f"regime test, numpy oracle, 1 thread, {per_step:.3f} s/micro-step",
             "host_cpus": os.cpu_count()}
 
 
@@ -140,7 +173,9 @@ def main():
     N = w.n_params
     rmax = max(w.level_crit, w.level_noncrit)
     q0 = wl.q_init(w, rmax, w.seed) if w.method == B.ACC_POWERSGD else None
-    gpu = B.Accordion(w.method, layers, W, w.level_crit, w.level_noncrit, w.k_den, w.eta, 1, q0)
+    is_batch = w.method == B.ACC_BATCH
+    gpu = B.Accordion(w.method, layers, W, w.level_crit, w.level_noncrit, w.k_den, w.eta, 1, q0,
+                      batch_multiplier=w.batch_multiplier)
 
     # gradient pool, resident in HBM: [scale][batch][worker]
     dev = torch.device("cuda:0")
@@ -153,7 +188,7 @@ def main():
     if args.fixed_level in (0, 1):
         st = gpu.unpack_state(gpu.get_state())
         blob = gpu.pack_state(st["e"], st["A"], st["Q"], st["norm_old"], st["has_old"],
-                              np.full(gpu.n_layers, args.fixed_level, np.int32))
+                              np.full(gpu.n_layers, args.fixed_level, np.int32), 0)
         gpu.set_state(blob)
 
     # plain copy of known size: the copy bandwidth this machine reaches, and the kernel that calibrates
@@ -186,7 +221,9 @@ def main():
         else:
             gpu.step_all(base[s % args.pool], out)
         if args.fixed_level < 0 and (s + 1) % args.window == 0:
-            decay = ((s + 1) // args.window) % 2 == 1      # every second window ends with an LR decay
+            # every second window ends with an LR decay (not in batch-size mode, where the large
+            # batch, once reached, is kept: the timed region is the steady state)
+            decay = ((s + 1) // args.window) % 2 == 1 and not is_batch
             gpu.detect_regime(LR_CURR, LR_CURR * 0.1 if decay else LR_CURR)
         state["step"] = s + 1
 
@@ -198,6 +235,7 @@ def main():
     if use_events:
         gpu.set_profiling(1 if args.kernel_events == "all" else 2)
     torch.cuda.synchronize()
+    bs0 = gpu.batch_status() if is_batch else None
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
@@ -220,14 +258,24 @@ def main():
         tot = sum(ms for ms, _ in prof.values())
         for name, (ms, n) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
             kernels[name] = {"avg_us": round(ms * 1e3 / n, 2), "launches": n, "share": round(ms / tot, 3)}
+        if is_batch and args.fused_update:
+            dom = "batch_micro_update_kernel"
         ms, n = prof[dom]
         avg_s = ms * 1e-3 / n
-        ach = algorithmic_bytes_dominant(N, W) / avg_s / 1e9
+        if is_batch:
+            bs1 = gpu.batch_status()
+            steps_t, exch_t = bs1["micro_steps"] - bs0["micro_steps"], bs1["exchanges"] - bs0["exchanges"]
+            alg_bytes = algorithmic_bytes_batch(N, W, steps_t, exch_t) // max(1, steps_t)
+            if args.fused_update:
+                alg_bytes += 12 * N * exch_t // max(1, steps_t)     # w, v read and written, no D store
+        else:
+            alg_bytes = algorithmic_bytes_dominant(N, W)
+        ach = alg_bytes / avg_s / 1e9
         traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, W, dom))
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
                     "avg_kernel_us": round(avg_s * 1e6, 2),
-                    "algorithmic_bytes_per_launch": algorithmic_bytes_dominant(N, W)}
+                    "algorithmic_bytes_per_launch": alg_bytes}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -240,7 +288,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "n_params": N, "n_workers": W, "n_layers": len(layers),
-                   "method": "topk" if w.method == B.ACC_TOPK else "powersgd",
+                   "method": {B.ACC_TOPK: "topk", B.ACC_POWERSGD: "powersgd", B.ACC_BATCH: "batch"}[w.method],
+                   "batch_multiplier": w.batch_multiplier,
                    "level_crit": w.level_crit, "level_noncrit": w.level_noncrit,
                    "window_steps": args.window, "pool_batches": args.pool,
                    "levels_switch": args.fixed_level < 0,

@@ -59,10 +59,11 @@ enum {
   ACC_EHIP = 4       /* a HIP runtime call failed */
 };
 
-enum { ACC_POWERSGD = 0, ACC_TOPK = 1 };
+enum { ACC_POWERSGD = 0, ACC_TOPK = 1, ACC_BATCH = 2 };
 
 #define ACC_MAX_WORKERS 32
 #define ACC_MAX_RANK 4
+#define ACC_MAX_BATCH_MULTIPLIER 65536
 
 typedef struct acc_layer {
   int64_t offset;     /* first element of the layer in the flat buffers */
@@ -83,6 +84,8 @@ typedef struct acc_config {
   int32_t k_den;
   float   eta;                 /* detection threshold of Sec. 4.2; the paper uses 0.5 */
   int32_t initial_level;       /* level before the first decision: 1 = critical, 0 = not */
+  int32_t batch_multiplier;    /* ACC_BATCH: floor(B_high / B_low) in [1, ACC_MAX_BATCH_MULTIPLIER]; else ignored */
+  int32_t batch_monotone;      /* ACC_BATCH: 1 = once the large batch is chosen it is kept (App. A) */
 } acc_config;
 
 typedef struct acc_ctx acc_ctx;
@@ -159,6 +162,32 @@ int32_t accordion_step_all_update(acc_ctx* ctx, const float* const* grads_host_a
                                   float* weights_dev, float* velocity_dev, float lr, float momentum,
                                   float weight_decay);
 
+/* --- batch-size mode (method = ACC_BATCH) ----------------------------------------------------
+ * Accordion switching the batch size instead of a compression level (Sec. 3 "Distributed SGD
+ * with adaptive batch size"; Sec. 4.2: same algorithm, on the gradient of the whole model;
+ * App. A "Additional Details for Batch Size experiment": the large batch is several backward
+ * passes summed before one exchange).  One accordion_step_all / accordion_step_all_update call
+ * is one MICRO-STEP: every worker's gradient of a micro-batch of B_low samples.
+ *     A += g_0;   S_w = g_w (first micro-step of a batch) or S_w + g_w      (S_w lives where the
+ *                                                                            error memory does)
+ *     a batch is complete after 1 micro-step at level 1 (critical: batch B_low) and after
+ *     batch_multiplier micro-steps at level 0 (batch B_high); then, with n = micro-steps in it,
+ *     D = (S_0 + S_1 + ... + S_{W-1}) / (W n)   in fp32, in this order, one division.
+ * accordion_step_all writes D to out_dev when the micro-step completes a batch and leaves
+ * out_dev untouched otherwise; accordion_step_all_update applies the optimizer step then, with
+ * the learning rate lr * n (Sec. 5.1: the rate grows in the ratio of the batch), and leaves
+ * weights and velocity untouched otherwise.  The level and the micro-step count live on the
+ * device: no host round trip decides whether a batch is complete; accordion_batch_status tells.
+ * accordion_detect_regime: one norm over all layers' accumulated gradient, Algorithm 1 once; with
+ * batch_monotone a level that has reached 0 stays 0.  accordion_payload_words counts n_model
+ * floats (the dense all-reduce) per completed batch and none otherwise.
+ * The call-by-call entry points return ACC_EINVAL for this method.  State layout: S_0..S_{W-1}
+ * | A | pending micro-steps (int32) | norm_old (L) | has_old (L) | level (L, all equal); the
+ * sums are meaningful only while pending > 0. */
+int32_t accordion_batch_status(acc_ctx* ctx, int32_t* level, int32_t* pending_micro_steps,
+                               int32_t* last_batch_micro_steps, int64_t* exchanges,
+                               int64_t* micro_steps);
+
 /* End of a window (Sec. 4.2; Algorithm 1): c_l = ||A_l||_2 (fp64 sum, fp32 result), per layer
  * critical <=> no previous norm, previous norm 0, |old - c| / old >= eta, or lr_next < lr_curr;
  * level <- critical; old <- c; A <- 0.  Only between steps (else ACC_ESTATE). */
@@ -217,7 +246,7 @@ int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
  * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
  * accordion_stage_name gives the kernel's name (NULL if out of range). */
-#define ACC_N_STAGES 21
+#define ACC_N_STAGES 24
 int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
 int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
 const char* accordion_stage_name(int32_t stage);

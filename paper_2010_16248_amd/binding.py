@@ -15,7 +15,7 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 ACC_OK, ACC_EINVAL, ACC_ESTATE, ACC_ENOSPACE, ACC_EHIP = 0, 1, 2, 3, 4
-ACC_POWERSGD, ACC_TOPK = 0, 1
+ACC_POWERSGD, ACC_TOPK, ACC_BATCH = 0, 1, 2
 ACC_MAX_WORKERS = 32
 ACC_MAX_RANK = 4
 
@@ -36,7 +36,8 @@ class acc_config(C.Structure):
                 ("layers", C.POINTER(acc_layer)), ("n_params", C.c_int64),
                 ("n_workers", C.c_int32), ("rank_crit", C.c_int32), ("rank_noncrit", C.c_int32),
                 ("k_num_crit", C.c_int32), ("k_num_noncrit", C.c_int32), ("k_den", C.c_int32),
-                ("eta", C.c_float), ("initial_level", C.c_int32)]
+                ("eta", C.c_float), ("initial_level", C.c_int32),
+                ("batch_multiplier", C.c_int32), ("batch_monotone", C.c_int32)]
 
 
 class AccordionError(RuntimeError):
@@ -50,14 +51,14 @@ _lib = None
 EXPORTS = [
     "accordion_workspace_bytes", "accordion_init", "accordion_destroy", "accordion_last_error",
     "accordion_compress_step", "accordion_aggregate", "accordion_decompress", "accordion_step_all",
-    "accordion_decompress_update", "accordion_step_all_update",
+    "accordion_decompress_update", "accordion_step_all_update", "accordion_batch_status",
     "accordion_detect_regime", "accordion_reset_accumulator", "accordion_get_levels",
     "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
     "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
     "accordion_probe_copy", "accordion_topk_stats", "accordion_flush",
 ]
-ACC_N_STAGES = 21
+ACC_N_STAGES = 24
 
 
 def load_library() -> C.CDLL:
@@ -79,6 +80,8 @@ def load_library() -> C.CDLL:
         "accordion_decompress": [vp, vp],
         "accordion_step_all": [vp, C.POINTER(vp), vp],
         "accordion_decompress_update": [vp, vp, vp, f32, f32, f32],
+        "accordion_batch_status": [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                   C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
         "accordion_step_all_update": [vp, C.POINTER(vp), vp, vp, f32, f32, f32],
         "accordion_detect_regime": [vp, f32, f32],
         "accordion_reset_accumulator": [vp],
@@ -110,7 +113,8 @@ def load_library() -> C.CDLL:
 
 def make_config(method: int, layers: Sequence, n_workers: int, level_crit: int, level_noncrit: int,
                 k_den: int = 100, eta: float = 0.5, initial_level: int = 1,
-                n_params: Optional[int] = None) -> Tuple[acc_config, object]:
+                n_params: Optional[int] = None, batch_multiplier: int = 1,
+                batch_monotone: int = 1) -> Tuple[acc_config, object]:
     """Build an acc_config; returns (config, keep_alive) -- the layer array must outlive the
     calls that read it.  layers: objects with offset/rows/cols/is_matrix or 4-tuples."""
     arr = (acc_layer * max(1, len(layers)))()
@@ -125,9 +129,12 @@ def make_config(method: int, layers: Sequence, n_workers: int, level_crit: int, 
     cfg.layers = C.cast(arr, C.POINTER(acc_layer))
     cfg.n_params = end if n_params is None else n_params
     cfg.n_workers = n_workers
+    cfg.batch_multiplier, cfg.batch_monotone = batch_multiplier, batch_monotone
     if method == ACC_POWERSGD:
         cfg.rank_crit, cfg.rank_noncrit = level_crit, level_noncrit
         cfg.k_num_crit = cfg.k_num_noncrit = cfg.k_den = 1
+    elif method == ACC_BATCH:
+        cfg.rank_crit = cfg.rank_noncrit = cfg.k_num_crit = cfg.k_num_noncrit = cfg.k_den = 1
     else:
         cfg.rank_crit = cfg.rank_noncrit = 1
         cfg.k_num_crit, cfg.k_num_noncrit, cfg.k_den = level_crit, level_noncrit, k_den
@@ -163,13 +170,15 @@ class Accordion:
 
     def __init__(self, method: int, layers: Sequence, n_workers: int, level_crit: int,
                  level_noncrit: int, k_den: int = 100, eta: float = 0.5, initial_level: int = 1,
-                 q_init: Optional[np.ndarray] = None, device: str = "cuda:0"):
+                 q_init: Optional[np.ndarray] = None, device: str = "cuda:0",
+                 batch_multiplier: int = 1, batch_monotone: int = 1):
         import torch  # device memory and the stream handle only
 
         self._lib = load_library()
         self._torch = torch
         self.cfg, self._keep = make_config(method, layers, n_workers, level_crit, level_noncrit,
-                                           k_den, eta, initial_level)
+                                           k_den, eta, initial_level, None, batch_multiplier,
+                                           batch_monotone)
         self.method, self.n_workers, self.n_layers = method, n_workers, len(layers)
         self.n_params = int(self.cfg.n_params)
         self.layers = [(l.offset, l.rows, l.cols, l.is_matrix) if hasattr(l, "offset") else tuple(l)
@@ -218,6 +227,14 @@ class Accordion:
         arr = (C.c_void_p * len(grads))(*[g.data_ptr() for g in grads])
         _check(self._lib, self.ctx, self._lib.accordion_step_all_update(
             self.ctx, arr, C.c_void_p(weights.data_ptr()), C.c_void_p(velocity.data_ptr()), lr, momentum, weight_decay))
+
+    def batch_status(self) -> dict:
+        lv, pend, last = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        ex, ms = C.c_int64(0), C.c_int64(0)
+        _check(self._lib, self.ctx, self._lib.accordion_batch_status(
+            self.ctx, C.byref(lv), C.byref(pend), C.byref(last), C.byref(ex), C.byref(ms)))
+        return dict(level=lv.value, pending=pend.value, last_batch=last.value, exchanges=ex.value,
+                    micro_steps=ms.value)
 
     def detect_regime(self, lr_curr: float, lr_next: float) -> None:
         _check(self._lib, self.ctx, self._lib.accordion_detect_regime(self.ctx, lr_curr, lr_next))
@@ -319,16 +336,21 @@ class Accordion:
         A = f[pos:pos + N]; pos += N
         qt = self.q_total()
         Q = f[pos:pos + qt]; pos += qt
+        pending = None
+        if self.method == ACC_BATCH:
+            pending = int(buf.view(np.int32)[pos]); pos += 1
         norm_old = f[pos:pos + L]; pos += L
         has_old = buf.view(np.int32)[pos:pos + L]; pos += L
         level = buf.view(np.int32)[pos:pos + L]; pos += L
-        return dict(e=e, A=A, Q=Q, norm_old=norm_old, has_old=has_old, level=level)
+        return dict(e=e, A=A, Q=Q, norm_old=norm_old, has_old=has_old, level=level, pending=pending)
 
-    def pack_state(self, e, A, Q, norm_old, has_old, level) -> np.ndarray:
+    def pack_state(self, e, A, Q, norm_old, has_old, level, pending: int = 0) -> np.ndarray:
         parts = [np.ascontiguousarray(e, np.float32).reshape(-1).view(np.uint8),
                  np.ascontiguousarray(A, np.float32).view(np.uint8)]
         if self.method == ACC_POWERSGD:
             parts.append(np.ascontiguousarray(Q, np.float32).reshape(-1).view(np.uint8))
+        if self.method == ACC_BATCH:
+            parts.append(np.array([pending], np.int32).view(np.uint8))
         parts += [np.ascontiguousarray(norm_old, np.float32).view(np.uint8),
                   np.ascontiguousarray(has_old, np.int32).view(np.uint8),
                   np.ascontiguousarray(level, np.int32).view(np.uint8)]

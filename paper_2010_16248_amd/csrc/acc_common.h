@@ -108,6 +108,10 @@ struct Ws {
   uint32_t* eqpre;             // W x q_stride exclusive prefix of eqq within the layer (+ total)
   int64_t q_stride;
   int32_t* pay_idx;  float* pay_val;  int64_t pay_stride;
+  // batch-size mode
+  uint32_t* bstate;            // two slots of four words, used alternately (micro-step parity)
+  int32_t bmult, bmono;        // micro-steps per large batch; 1: the batch only grows
+  int64_t n_model;             // elements that belong to a layer
   int64_t N;
   int32_t W, L, rmax;
   int32_t n_ftiles, n_mtiles, n_qtiles, n_vectiles, n_mat;

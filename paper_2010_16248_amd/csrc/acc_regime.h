@@ -68,6 +68,10 @@ __global__ __launch_bounds__(64) void regime_decide_kernel(const Ws ws, float lr
 // Floats one worker sends per step at the current levels (the paper's "Data Sent" unit).
 __global__ __launch_bounds__(256) void recount_words_kernel(const Ws ws, int method) {
   __shared__ unsigned long long red[256];
+  if (method == 2) {                        // batch-size mode: an exchange is the dense model
+    if (threadIdx.x == 0) ws.words[0] = (unsigned long long)ws.n_model;
+    return;
+  }
   unsigned long long s = 0;
   for (int li = threadIdx.x; li < ws.L; li += 256) {
     const LayerDev& L = ws.layers[li];

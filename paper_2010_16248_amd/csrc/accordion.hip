@@ -16,6 +16,7 @@
 #include "acc_powersgd.h"
 #include "acc_regime.h"
 #include "acc_topk.h"
+#include "acc_batch.h"
 
 using namespace acc;
 
@@ -42,7 +43,8 @@ struct Plan {
   // workspace regions
   Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
-  Region r_A, r_e, r_norm_part;
+  Region r_A, r_e, r_norm_part, r_bstate;
+  int64_t n_model = 0;   // elements that belong to a layer
   Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean;
   Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval;
   int64_t total_bytes = 0;
@@ -55,7 +57,8 @@ int fail(char* buf, int code, const char* msg) {
 
 int make_plan(const acc_config* c, Plan& p, char* err) {
   if (!c) return fail(err, ACC_EINVAL, "config is NULL");
-  if (c->method != ACC_POWERSGD && c->method != ACC_TOPK) return fail(err, ACC_EINVAL, "unknown method");
+  if (c->method != ACC_POWERSGD && c->method != ACC_TOPK && c->method != ACC_BATCH)
+    return fail(err, ACC_EINVAL, "unknown method");
   if (c->n_layers <= 0 || c->n_layers > (1 << 20)) return fail(err, ACC_EINVAL, "n_layers out of range");
   if (!c->layers) return fail(err, ACC_EINVAL, "layers is NULL");
   if (c->n_workers < 1 || c->n_workers > ACC_MAX_WORKERS) return fail(err, ACC_EINVAL, "n_workers out of range");
@@ -65,6 +68,10 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
   if (c->method == ACC_POWERSGD) {
     if (c->rank_crit < 1 || c->rank_crit > ACC_MAX_RANK || c->rank_noncrit < 1 || c->rank_noncrit > ACC_MAX_RANK)
       return fail(err, ACC_EINVAL, "rank out of [1, ACC_MAX_RANK]");
+  } else if (c->method == ACC_BATCH) {
+    if (c->batch_multiplier < 1 || c->batch_multiplier > ACC_MAX_BATCH_MULTIPLIER)
+      return fail(err, ACC_EINVAL, "batch_multiplier out of [1, ACC_MAX_BATCH_MULTIPLIER]");
+    if (c->batch_monotone != 0 && c->batch_monotone != 1) return fail(err, ACC_EINVAL, "batch_monotone must be 0 or 1");
   } else {
     if (c->k_den < 1 || c->k_num_crit < 1 || c->k_num_noncrit < 1 || c->k_num_crit > c->k_den ||
         c->k_num_noncrit > c->k_den)
@@ -114,6 +121,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
       p.ftiles.push_back(ft);
     }
     ntile += d.ntiles;
+    p.n_model += n;
     if (ntile > (int64_t(1) << 30)) return fail(err, ACC_EINVAL, "too many tiles");
     if (c->method == ACC_POWERSGD) {
       if (d.is_matrix) {
@@ -151,7 +159,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
         p.vec_total += n;
         for (int t = 0; t < d.ntiles; ++t) p.vectiles.push_back(d.tile0 + t);
       }
-    } else {
+    } else if (c->method == ACC_TOPK) {
       auto kof = [&](int num) {
         const int64_t k = ((int64_t)n * num + c->k_den - 1) / c->k_den;
         return (int32_t)std::max<int64_t>(1, std::min<int64_t>(n, k));
@@ -188,13 +196,14 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
   reg(p.r_A, 4 * p.e_stride);
   reg(p.r_e, 4 * p.e_stride * W);
   reg(p.r_norm_part, 8 * ntile);
+  reg(p.r_bstate, 4 * 8);
   if (c->method == ACC_POWERSGD) {
     reg(p.r_Q, 4 * p.q_total);
     reg(p.r_Phat, 4 * p.p_total);
     reg(p.r_Ppart, 4 * p.ppart_stride * W);
     reg(p.r_Qpart, 4 * p.qpart_stride * W);
     reg(p.r_vecmean, 4 * p.vec_total);
-  } else {
+  } else if (c->method == ACC_TOPK) {
     reg(p.r_hist1, 4 * (int64_t)kHistBins * nl * W);
     reg(p.r_t2, 4 * (int64_t)kSub2 * ntile * W);
     reg(p.r_qlist, 4 * (int64_t)kQListCap * p.q_stride * W);
@@ -244,6 +253,7 @@ enum Stage {
   ST_topk_compact_kernel, ST_topk_compact_mean_kernel, ST_topk_sparse_mean_kernel,
   ST_norm_partial_kernel, ST_regime_decide_kernel, ST_recount_words_kernel, ST_zero_accum_kernel,
   ST_psgd_decomp_update_kernel, ST_topk_compact_update_kernel, ST_topk_sparse_update_kernel,
+  ST_batch_micro_kernel, ST_batch_micro_update_kernel, ST_batch_decide_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
@@ -253,7 +263,8 @@ static const char* const kStageNames[ST_COUNT] = {
   "topk_count3_kernel", "topk_pick3_kernel",
   "topk_compact_kernel", "topk_compact_mean_kernel", "topk_sparse_mean_kernel",
   "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel",
-  "psgd_decomp_update_kernel", "topk_compact_update_kernel", "topk_sparse_update_kernel"};
+  "psgd_decomp_update_kernel", "topk_compact_update_kernel", "topk_sparse_update_kernel",
+  "batch_micro_kernel", "batch_micro_update_kernel", "batch_decide_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
 
@@ -326,7 +337,9 @@ int drain_profile(acc_ctx* c) {
 
 bool prof_begin(acc_ctx* c, int stage, EventPair& p) {
   if (!c->profiling) return false;
-  if (c->profiling == 2 && stage != ST_topk_ef_hist_kernel && stage != ST_psgd_ef_p_kernel) return false;
+  if (c->profiling == 2 && stage != ST_topk_ef_hist_kernel && stage != ST_psgd_ef_p_kernel &&
+      stage != ST_batch_micro_kernel && stage != ST_batch_micro_update_kernel)
+    return false;
   if (c->pending.size() >= 8192) drain_profile(c);
   if (!c->spare.empty()) {
     p = c->spare.back();
@@ -422,6 +435,18 @@ int launch_decompress(acc_ctx* c, const Sink& sink) {
   return ACC_OK;
 }
 
+const char* const kBatchCallByCall =
+    "batch-size mode has no call-by-call sequence: use accordion_step_all / accordion_step_all_update";
+
+// One micro-step of the batch-size mode for all workers (c->grads is set).
+int launch_batch_micro(acc_ctx* c, const Sink& sink) {
+  const Ws& ws = c->ws;
+  const uint32_t parity = c->step_id & 1u;
+  if (sink.wt) ACC_LAUNCH(c, batch_micro_update_kernel, dim3(ws.n_ftiles), dim3(256), ws, c->grads, sink, parity);
+  else ACC_LAUNCH(c, batch_micro_kernel, dim3(ws.n_ftiles), dim3(256), ws, c->grads, sink, parity);
+  return ACC_OK;
+}
+
 int launch_topk_compact_mean(acc_ctx* c, const Sink& sink) {
   const Ws& ws = c->ws;
   if (sink.wt) ACC_LAUNCH(c, topk_compact_update_kernel, dim3(ws.n_ftiles), dim3(256), ws, sink);
@@ -458,7 +483,8 @@ void end_step(acc_ctx* c) {
 size_t state_bytes_of(const acc_ctx* c) {
   const Plan& p = c->plan;
   const size_t L = (size_t)c->cfg.n_layers;
-  return 4 * ((size_t)p.N * (size_t)(c->cfg.n_workers + 1) + (size_t)p.q_total + 3 * L);
+  return 4 * ((size_t)p.N * (size_t)(c->cfg.n_workers + 1) + (size_t)p.q_total + 3 * L +
+              (c->cfg.method == ACC_BATCH ? 1u : 0u));
 }
 
 }  // namespace
@@ -530,7 +556,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.Qpart = at<float>(c, p.r_Qpart);
     ws.qpart_stride = p.qpart_stride;
     ws.vecmean = at<float>(c, p.r_vecmean);
-  } else {
+  } else if (cfg->method == ACC_TOPK) {
     ws.hist1 = at<uint32_t>(c, p.r_hist1);
     ws.t2 = at<uint32_t>(c, p.r_t2);
     ws.qlist = at<uint32_t>(c, p.r_qlist);
@@ -549,6 +575,10 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.pay_val = at<float>(c, p.r_payval);
     ws.pay_stride = p.pay_stride;
   }
+  ws.bstate = at<uint32_t>(c, p.r_bstate);
+  ws.bmult = cfg->method == ACC_BATCH ? cfg->batch_multiplier : 1;
+  ws.bmono = cfg->method == ACC_BATCH ? cfg->batch_monotone : 0;
+  ws.n_model = p.n_model;
   ws.q_stride = p.q_stride;
   ws.N = p.N;
   ws.W = cfg->n_workers;
@@ -607,6 +637,7 @@ const char* accordion_last_error(const acc_ctx* ctx) { return ctx ? ctx->err : g
 
 int32_t accordion_compress_step(acc_ctx* c, int32_t worker, const float* grad_dev, int32_t phase) {
   if (!c) return ACC_EINVAL;
+  if (c->cfg.method == ACC_BATCH) return fail(c->err, ACC_EINVAL, kBatchCallByCall);
   if (worker < 0 || worker >= c->cfg.n_workers) return fail(c->err, ACC_EINVAL, "worker out of range");
   const uint32_t bit = 1u << worker;
   if (phase == 0) {
@@ -635,6 +666,7 @@ int32_t accordion_compress_step(acc_ctx* c, int32_t worker, const float* grad_de
 
 int32_t accordion_aggregate(acc_ctx* c, int32_t phase) {
   if (!c) return ACC_EINVAL;
+  if (c->cfg.method == ACC_BATCH) return fail(c->err, ACC_EINVAL, kBatchCallByCall);
   if (phase == 0) {
     if (c->agg0) return fail(c->err, ACC_ESTATE, "aggregate(0) already done");
     if (c->p0_mask != all_workers_mask(c)) return fail(c->err, ACC_ESTATE, "aggregate(0) needs phase 0 of every worker");
@@ -656,6 +688,7 @@ int32_t accordion_aggregate(acc_ctx* c, int32_t phase) {
 }
 
 static int32_t decompress_into(acc_ctx* c, const Sink& sink) {
+  if (c->cfg.method == ACC_BATCH) return fail(c->err, ACC_EINVAL, kBatchCallByCall);
   if (c->cfg.method == ACC_POWERSGD ? !c->agg1 : !c->agg0)
     return fail(c->err, ACC_ESTATE, "decompress before the aggregation of this step is complete");
   const int rc = launch_decompress(c, sink);
@@ -689,7 +722,9 @@ static int32_t step_all_into(acc_ctx* c, const float* const* grads_host_array, c
   }
   for (int w = 0; w < W; ++w) c->grads.p[w] = grads_host_array[w];
   int rc;
-  if (c->cfg.method == ACC_POWERSGD) {
+  if (c->cfg.method == ACC_BATCH) {
+    rc = launch_batch_micro(c, sink);
+  } else if (c->cfg.method == ACC_POWERSGD) {
     rc = launch_phase0(c, 0, W);
     if (rc == ACC_OK) rc = launch_agg0(c);
     if (rc == ACC_OK) rc = launch_phase1(c, 0, W);
@@ -724,6 +759,10 @@ int32_t accordion_detect_regime(acc_ctx* c, float lr_curr, float lr_next) {
   if (c->in_step) return fail(c->err, ACC_ESTATE, "detect_regime inside a step");
   const Ws& ws = c->ws;
   ACC_LAUNCH(c, norm_partial_kernel, dim3(ws.n_ftiles), dim3(256), ws);
+  if (c->cfg.method == ACC_BATCH) {
+    ACC_LAUNCH(c, batch_decide_kernel, dim3(1), dim3(256), ws, lr_curr, lr_next);
+    return ACC_OK;
+  }
   ACC_LAUNCH(c, regime_decide_kernel, dim3(ws.L), dim3(64), ws, lr_curr, lr_next);
   ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), ws, (int)c->cfg.method);
   return ACC_OK;
@@ -827,6 +866,25 @@ int32_t accordion_topk_stats(acc_ctx* c, int64_t* restaged_layers, int64_t* swep
   return ACC_OK;
 }
 
+int32_t accordion_batch_status(acc_ctx* c, int32_t* level, int32_t* pending_micro_steps,
+                               int32_t* last_batch_micro_steps, int64_t* exchanges, int64_t* micro_steps) {
+  if (!c) return ACC_EINVAL;
+  if (c->cfg.method != ACC_BATCH) return fail(c->err, ACC_EINVAL, "batch status exists for the batch-size mode only");
+  if (!level || !pending_micro_steps || !last_batch_micro_steps || !exchanges || !micro_steps)
+    return fail(c->err, ACC_EINVAL, "host pointer is NULL");
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  uint32_t slot[4] = {0, 0, 0, 0};
+  unsigned long long s[2] = {0, 0};
+  ACC_HIP(c, hipMemcpy(slot, c->ws.bstate + 4 * (c->step_id & 1u), sizeof(slot), hipMemcpyDeviceToHost));
+  ACC_HIP(c, hipMemcpy(s, c->ws.stats, sizeof(s), hipMemcpyDeviceToHost));
+  ACC_HIP(c, hipMemcpy(level, c->ws.level, 4, hipMemcpyDeviceToHost));
+  *pending_micro_steps = (int32_t)slot[0];
+  *last_batch_micro_steps = (int32_t)slot[1];
+  *exchanges = (int64_t)s[0];
+  *micro_steps = (int64_t)s[1];
+  return ACC_OK;
+}
+
 int32_t accordion_state_bytes(const acc_ctx* c, size_t* out_bytes) {
   if (!c || !out_bytes) return ACC_EINVAL;
   *out_bytes = state_bytes_of(c);
@@ -846,6 +904,8 @@ static int32_t state_copy(acc_ctx* c, char* host, bool to_host) {
   for (int w = 0; w < c->cfg.n_workers; ++w) ACC_HIP(c, cp(c->ws.e + (size_t)w * p.e_stride, N4));
   ACC_HIP(c, cp(c->ws.A, N4));
   if (c->cfg.method == ACC_POWERSGD) ACC_HIP(c, cp(c->ws.Q, 4 * (size_t)p.q_total));
+  // batch-size mode: micro-steps summed so far, in the slot the next micro-step reads
+  if (c->cfg.method == ACC_BATCH) ACC_HIP(c, cp(c->ws.bstate + 4 * (c->step_id & 1u), 4));
   ACC_HIP(c, cp(c->ws.norm_old, L4));
   ACC_HIP(c, cp(c->ws.has_old, L4));
   ACC_HIP(c, cp(c->ws.level, L4));
@@ -873,6 +933,13 @@ int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
   const int32_t* lv = reinterpret_cast<const int32_t*>(static_cast<const char*>(state_host) + state_bytes_of(c) - 4 * L);
   for (size_t i = 0; i < L; ++i)
     if (lv[i] != 0 && lv[i] != 1) return fail(c->err, ACC_EINVAL, "state holds a level other than 0 or 1");
+  if (c->cfg.method == ACC_BATCH) {
+    for (size_t i = 1; i < L; ++i)
+      if (lv[i] != lv[0]) return fail(c->err, ACC_EINVAL, "batch-size mode has one level for the whole model");
+    const int32_t* jp = reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(lv) - 8 * L - 4);
+    if (*jp < 0 || *jp >= c->cfg.batch_multiplier)
+      return fail(c->err, ACC_EINVAL, "state holds a micro-step count outside [0, batch_multiplier)");
+  }
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   const int32_t rc = state_copy(c, const_cast<char*>(static_cast<const char*>(state_host)), false);
   if (rc != ACC_OK) return rc;

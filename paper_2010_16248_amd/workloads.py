@@ -25,6 +25,7 @@ SEED_BASE = 20101624
 
 METHOD_POWERSGD = 0
 METHOD_TOPK = 1
+METHOD_BATCH = 2
 
 
 @dataclass(frozen=True)
@@ -138,6 +139,7 @@ class Workload:
     seed: int = SEED_BASE
     window_scale_even: Sequence[float] = field(default_factory=list)
     window_scale_odd: Sequence[float] = field(default_factory=list)
+    batch_multiplier: int = 1     # batch-size mode: floor(B_high / B_low)
 
     @property
     def layers(self) -> List[Layer]:
@@ -168,11 +170,15 @@ def workload(name: str) -> Workload:
                         dist="lstm", window_steps=100, n_windows=3, seed=SEED_BASE + 5,
                         window_scale_even=[1.00, 0.40, 0.38],
                         window_scale_odd=[1.00, 0.40, 0.38])
+    if name == "resnet18_batch":
+        # batch-size mode: B_low = 512, B_high = 4096 (Section 5); a "step" is one micro-batch
+        return Workload(name, METHOD_BATCH, resnet18_shapes(), 4, 1, 1,
+                        window_steps=20, n_windows=3, seed=SEED_BASE + 6, batch_multiplier=8)
     raise KeyError(name)
 
 
 WORKLOAD_NAMES = ["tiny_powersgd", "resnet18_topk", "resnet18_powersgd",
-                  "vgg19_powersgd", "lstm_topk"]
+                  "vgg19_powersgd", "lstm_topk", "resnet18_batch"]
 
 
 # --------------------------------------------------------------------------

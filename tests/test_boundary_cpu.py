@@ -79,6 +79,22 @@ def test_invalid_layers_and_ranks(lib):
     assert lib.accordion_workspace_bytes(C.byref(cfg), None) == B.ACC_EINVAL
 
 
+def test_batch_size_mode_config(lib):
+    out = C.c_size_t(0)
+    cfg, keep = _cfg(method=B.ACC_BATCH, batch_multiplier=8)
+    assert lib.accordion_workspace_bytes(C.byref(cfg), C.byref(out)) == B.ACC_OK
+    # W sums + accumulator + tables: far smaller than the TopK workspace of the same model
+    cfgt, keept = _cfg()
+    assert 0 < out.value < B.accordion_workspace_bytes(cfgt)
+    for bad in (0, -1, 65537):
+        cfg, keep = _cfg(method=B.ACC_BATCH, batch_multiplier=bad)
+        assert lib.accordion_workspace_bytes(C.byref(cfg), C.byref(out)) == B.ACC_EINVAL
+        assert "batch_multiplier" in lib.accordion_last_error(None).decode()
+    cfg, keep = _cfg(method=B.ACC_BATCH, batch_multiplier=8, batch_monotone=2)
+    assert lib.accordion_workspace_bytes(C.byref(cfg), C.byref(out)) == B.ACC_EINVAL
+    assert lib.accordion_batch_status(None, None, None, None, None, None) == B.ACC_EINVAL
+
+
 def test_init_rejects_null_and_small_workspace_without_a_gpu(lib):
     cfg, keep = _cfg()
     ctx = C.c_void_p(None)
