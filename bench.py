@@ -51,7 +51,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18_topk",
                     choices=["tiny_powersgd", "resnet18_topk", "resnet18_powersgd", "vgg19_powersgd", "lstm_topk",
-                             "resnet18_batch"])
+                             "resnet18_batch", "resnet18_topk_k99", "lstm_topk_k99"])
     ap.add_argument("--workers", type=int, default=0, help="override W of the workload")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept in HBM")
     ap.add_argument("--window", type=int, default=50, help="steps per detection window")

@@ -214,6 +214,18 @@ int32_t accordion_get_norms(acc_ctx* ctx, float* old_host, float* curr_host);
  * Errors: ACC_ENOSPACE if capacity < k (count_out is still set). */
 int32_t accordion_get_payload(acc_ctx* ctx, int32_t worker, int32_t layer, int32_t* idx_host,
                               float* val_host, int64_t capacity, int64_t* count_out);
+/* How a TopK layer's payload is laid out at a level (host-only arithmetic, no GPU needed).  The
+ * paper's own runs keep K = 99 % inside critical regimes (Sec. 5.3, TopK tables), where a list of
+ * (index, value) pairs costs 1.98 n floats -- more than the dense tensor.  A layer that keeps more
+ * than half of its n entries therefore sends its k values in index order plus the n - k indices
+ * of the dropped entries: n floats, never more than dense.  format: ACC_PAYLOAD_INDEX_VALUE
+ * (2 k <= n; words = 2 k) or ACC_PAYLOAD_VALUES_HOLES (2 k > n; words = n); kept = k.
+ * accordion_get_payload decodes either layout to (index, value); accordion_payload_words keeps
+ * the paper's accounting of 2 k floats per layer. */
+enum { ACC_PAYLOAD_INDEX_VALUE = 0, ACC_PAYLOAD_VALUES_HOLES = 1 };
+int32_t accordion_payload_format(const acc_config* cfg, int32_t layer, int32_t level, int32_t* format,
+                                 int64_t* kept, int64_t* words);
+
 /* PowerSGD factors of a matrix layer from the last step: p_hat_host rows x r and q_host
  * cols x r (row-major, r = *rank_out, the rank that step used); room for ACC_MAX_RANK
  * columns each is required. */

@@ -51,7 +51,7 @@ _lib = None
 EXPORTS = [
     "accordion_workspace_bytes", "accordion_init", "accordion_destroy", "accordion_last_error",
     "accordion_compress_step", "accordion_aggregate", "accordion_decompress", "accordion_step_all",
-    "accordion_decompress_update", "accordion_step_all_update", "accordion_batch_status",
+    "accordion_decompress_update", "accordion_step_all_update", "accordion_batch_status", "accordion_payload_format",
     "accordion_detect_regime", "accordion_reset_accumulator", "accordion_get_levels",
     "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
     "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
@@ -80,6 +80,8 @@ def load_library() -> C.CDLL:
         "accordion_decompress": [vp, vp],
         "accordion_step_all": [vp, C.POINTER(vp), vp],
         "accordion_decompress_update": [vp, vp, vp, f32, f32, f32],
+        "accordion_payload_format": [C.POINTER(acc_config), C.c_int32, C.c_int32, C.POINTER(C.c_int32),
+                                     C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
         "accordion_batch_status": [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                    C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
         "accordion_step_all_update": [vp, C.POINTER(vp), vp, vp, f32, f32, f32],
@@ -154,6 +156,18 @@ def accordion_workspace_bytes(cfg: acc_config) -> int:
     out = C.c_size_t(0)
     _check(lib, None, lib.accordion_workspace_bytes(C.byref(cfg), C.byref(out)))
     return int(out.value)
+
+
+def payload_format(cfg: acc_config, layer: int, level: int) -> Tuple[int, int, int]:
+    """(format, kept, words) of a TopK layer at a level; host arithmetic only."""
+    lib = load_library()
+    fmt, kept, words = C.c_int32(0), C.c_int64(0), C.c_int64(0)
+    _check(lib, None, lib.accordion_payload_format(C.byref(cfg), layer, level, C.byref(fmt), C.byref(kept),
+                                                   C.byref(words)))
+    return fmt.value, kept.value, words.value
+
+
+ACC_PAYLOAD_INDEX_VALUE, ACC_PAYLOAD_VALUES_HOLES = 0, 1
 
 
 def probe_copy(dst, src) -> None:

@@ -844,9 +844,16 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
 
 // ---- E ----------------------------------------------------------------------------------------
 
+// Payload format of a layer of n entries that keeps k (static per level): more than half kept =>
+// the values go out dense-in-order and the indices name the n - k holes (none if k = n).
+__device__ __host__ __forceinline__ bool payload_has_holes(uint32_t n, uint32_t k) { return 2ull * k > n; }
+
 // What a wave needs to know about one worker's selection in its quarter.
 struct QuarterSel {
   uint32_t T, ktie, alleq, k;
+  uint32_t holes, nholes;            // holes = 0: payload = (index, value) of the kept entries; 1: the
+                                     // layer keeps more than half: payload = the k values in index
+                                     // order + the nholes = n - k indices of the dropped entries
   uint32_t gt_before, eq_before;     // selected-above-T and equal-to-T entries in the quarters before
   uint32_t eq_here;                  // entries equal to T in this quarter
 };
@@ -856,6 +863,9 @@ __device__ __forceinline__ QuarterSel load_quarter_sel(const Ws& ws, int w, int 
   const int64_t qs = (int64_t)w * ws.q_stride + qslot_local;
   QuarterSel s;
   s.T = sp->T; s.ktie = sp->ktie; s.alleq = sp->alleq; s.k = sp->k;
+  const uint32_t n_layer = (uint32_t)ws.layers[layer].rows * (uint32_t)ws.layers[layer].cols;
+  s.holes = payload_has_holes(n_layer, s.k) ? 1u : 0u;
+  s.nholes = n_layer - min(s.k, n_layer);
   s.gt_before = ws.gtpre[qs];
   s.eq_before = ws.eqpre[qs];
   s.eq_here = ws.eqpre[qs + 1] - s.eq_before;              // the layer's last slot holds the total
@@ -918,7 +928,8 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
     below += lanes_below(msel[c], lane);
     total += (uint32_t)__popcll(msel[c]);
   }
-  if (total != 0) {
+  const bool holes = qs.holes != 0u;                        // wave-uniform
+  if (total != 0 || holes) {
     uint32_t pos = run.pos_run + below;
     const int32_t i0 = (int32_t)(tg.a0 + 4 * (int64_t)q - layer_offset);
     float4 z = cur;
@@ -928,10 +939,14 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
       sel[c] = valid[c] && key[c] >= tsel[c];
       if (sel[c]) {
         if (pos < qs.k) {                                   // always true for consistent state
-          pidx[pos] = i0 + c;
+          if (!holes) pidx[pos] = i0 + c;
           pval[pos] = comp(cur, c);
         }
         ++pos;
+      } else if (holes && valid[c]) {
+        // dropped entry number (index - kept before it) of the layer
+        const uint32_t hp = (uint32_t)(i0 + c) - pos;
+        if (hp < qs.nholes) pidx[hp] = i0 + c;              // always true for consistent state
       }
     }
     if (sel[0]) z.x = 0.f;
@@ -1010,7 +1025,7 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   int32_t* const pay_idx = ws.pay_idx;
   float* const pay_val = ws.pay_val;
   // lane w holds worker w's selection state for this quarter
-  QuarterSel mine = {0u, 0u, 0u, 0u, 0u, 0u, 0u};
+  QuarterSel mine = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
   if (lane < W) mine = load_quarter_sel(ws, lane, ft.layer, qslot_local);
   uint32_t eq_run_v = mine.eq_before;
   uint32_t pos_run_v = mine.gt_before + min(mine.ktie, mine.eq_before);
@@ -1048,6 +1063,8 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
           qs.ktie = (uint32_t)__builtin_amdgcn_readlane((int)mine.ktie, w);
           qs.alleq = (uint32_t)__builtin_amdgcn_readlane((int)mine.alleq, w);
           qs.k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
+          qs.holes = (uint32_t)__builtin_amdgcn_readlane((int)mine.holes, w);
+          qs.nholes = (uint32_t)__builtin_amdgcn_readlane((int)mine.nholes, w);
           qs.eq_here = (uint32_t)__builtin_amdgcn_readlane((int)mine.eq_here, w);
           qs.gt_before = 0u;
           qs.eq_before = 0u;
@@ -1105,6 +1122,7 @@ __global__ __launch_bounds__(256) void topk_compact_update_kernel(const Ws ws, c
 template <bool UPD>
 __device__ __forceinline__ void sparse_mean_body(const Ws& ws, const Sink& sink) {
   __shared__ float acc[kTile];
+  __shared__ uint16_t hole[kTile];                         // tile-local offsets of the dropped entries
   const int tid = threadIdx.x;
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
@@ -1125,9 +1143,34 @@ __device__ __forceinline__ void sparse_mean_body(const Ws& ws, const Sink& sink)
     const uint32_t hi = ws.gtpre[qs + 4] + min(ktie, ws.eqpre[qs + 4]);
     const int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
     const float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
-    for (uint32_t p = lo + tid; p < hi && p < kk; p += kFlatThreads) {
-      const int32_t i = pidx[p] - ft.start;
-      if (i >= 0 && i < ft.count) acc[i] += pval[p];   // indices are unique within a worker
+    const uint32_t n_layer = (uint32_t)L.rows * (uint32_t)L.cols;
+    const uint32_t nholes = n_layer - min(kk, n_layer);
+    if (!payload_has_holes(n_layer, kk)) {
+      for (uint32_t p = lo + tid; p < hi && p < kk; p += kFlatThreads) {
+        const int32_t i = pidx[p] - ft.start;
+        if (i >= 0 && i < ft.count) acc[i] += pval[p];   // indices are unique within a worker
+      }
+    } else {
+      // values in index order + hole list: the tile's entries are kept entries lo .. hi-1 and
+      // holes (start - lo) .. (start + count - hi) - 1; entry i of the tile is kept entry
+      // lo + i - (holes of the tile before i)
+      const uint32_t h0 = (uint32_t)ft.start - lo;
+      const uint32_t nh = nholes ? min((uint32_t)ft.count - (hi - lo), (uint32_t)kTile) : 0u;
+      for (uint32_t t = tid; t < nh; t += kFlatThreads) {
+        const uint32_t hp = min(h0 + t, nholes - 1u);
+        hole[t] = (uint16_t)min((uint32_t)max(pidx[hp] - ft.start, 0), (uint32_t)(kTile - 1));
+      }
+      __syncthreads();
+      for (int i = tid; i < ft.count; i += kFlatThreads) {
+        uint32_t a = 0, b = nh;                              // first hole >= i
+        while (a < b) {
+          const uint32_t m = (a + b) >> 1;
+          if ((int)hole[m] < i) a = m + 1; else b = m;
+        }
+        const bool is_hole = a < nh && (int)hole[a] == i;
+        const uint32_t p = lo + (uint32_t)i - a;
+        if (!is_hole && p < kk) acc[i] += pval[p];
+      }
     }
     __syncthreads();                             // workers are added in order
   }

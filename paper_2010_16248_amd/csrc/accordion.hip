@@ -815,8 +815,43 @@ int32_t accordion_get_payload(acc_ctx* c, int32_t worker, int32_t layer, int32_t
   if (k == 0) return ACC_OK;
   if (!idx_host || !val_host) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
   const size_t o = (size_t)worker * c->plan.pay_stride + L.pay_off;
-  ACC_HIP(c, hipMemcpy(idx_host, c->ws.pay_idx + o, 4 * (size_t)k, hipMemcpyDeviceToHost));
   ACC_HIP(c, hipMemcpy(val_host, c->ws.pay_val + o, 4 * (size_t)k, hipMemcpyDeviceToHost));
+  const uint32_t n = (uint32_t)L.rows * (uint32_t)L.cols;
+  const uint32_t nholes = n - (uint32_t)k;
+  if (!payload_has_holes(n, (uint32_t)k)) {
+    ACC_HIP(c, hipMemcpy(idx_host, c->ws.pay_idx + o, 4 * (size_t)k, hipMemcpyDeviceToHost));
+    return ACC_OK;
+  }
+  // values + holes: the kept indices are the complement of the (ascending) hole list
+  std::vector<int32_t> holes(nholes);
+  if (nholes > 0)
+    ACC_HIP(c, hipMemcpy(holes.data(), c->ws.pay_idx + o, 4 * (size_t)nholes, hipMemcpyDeviceToHost));
+  int64_t out_pos = 0;
+  uint32_t h = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (h < nholes && holes[h] == (int32_t)i) { ++h; continue; }
+    if (out_pos < k) idx_host[out_pos] = (int32_t)i;
+    ++out_pos;
+  }
+  if (out_pos != k || h != nholes) return fail(c->err, ACC_EHIP, "hole list of the payload is inconsistent");
+  return ACC_OK;
+}
+
+int32_t accordion_payload_format(const acc_config* cfg, int32_t layer, int32_t level, int32_t* format,
+                                 int64_t* kept, int64_t* words) {
+  if (!cfg || !format || !kept || !words) return fail(g_init_error, ACC_EINVAL, "NULL argument");
+  Plan p;
+  const int rc = make_plan(cfg, p, g_init_error);
+  if (rc != ACC_OK) return rc;
+  if (cfg->method != ACC_TOPK) return fail(g_init_error, ACC_EINVAL, "payload formats exist for TopK only");
+  if (layer < 0 || layer >= cfg->n_layers) return fail(g_init_error, ACC_EINVAL, "layer out of range");
+  if (level != 0 && level != 1) return fail(g_init_error, ACC_EINVAL, "level must be 0 or 1");
+  const LayerDev& L = p.layers[layer];
+  const uint32_t n = (uint32_t)L.rows * (uint32_t)L.cols, k = (uint32_t)L.k[level];
+  const bool holes = payload_has_holes(n, k);
+  *format = holes ? ACC_PAYLOAD_VALUES_HOLES : ACC_PAYLOAD_INDEX_VALUE;
+  *kept = k;
+  *words = holes ? (int64_t)n : 2 * (int64_t)k;
   return ACC_OK;
 }
 

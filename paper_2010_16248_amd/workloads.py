@@ -170,6 +170,17 @@ def workload(name: str) -> Workload:
                         dist="lstm", window_steps=100, n_windows=3, seed=SEED_BASE + 5,
                         window_scale_even=[1.00, 0.40, 0.38],
                         window_scale_odd=[1.00, 0.40, 0.38])
+    if name == "resnet18_topk_k99":
+        # the levels the paper itself trains with (Section 5.3, TopK tables): K 99 % inside
+        # critical regimes, K 25 % outside; ResNet-18 with 100 classes
+        return Workload(name, METHOD_TOPK, resnet18_shapes(100), 4, 99, 25,
+                        dist="laplace", window_steps=20, n_windows=3, seed=SEED_BASE + 7)
+    if name == "lstm_topk_k99":
+        # K 99 % / 2 % on the LSTM set (appendix figure of the language model)
+        return Workload(name, METHOD_TOPK, lstm_shapes(), 4, 99, 2,
+                        dist="lstm", window_steps=100, n_windows=3, seed=SEED_BASE + 8,
+                        window_scale_even=[1.00, 0.40, 0.38],
+                        window_scale_odd=[1.00, 0.40, 0.38])
     if name == "resnet18_batch":
         # batch-size mode: B_low = 512, B_high = 4096 (Section 5); a "step" is one micro-batch
         return Workload(name, METHOD_BATCH, resnet18_shapes(), 4, 1, 1,
@@ -178,7 +189,8 @@ def workload(name: str) -> Workload:
 
 
 WORKLOAD_NAMES = ["tiny_powersgd", "resnet18_topk", "resnet18_powersgd",
-                  "vgg19_powersgd", "lstm_topk", "resnet18_batch"]
+                  "vgg19_powersgd", "lstm_topk", "resnet18_batch", "resnet18_topk_k99",
+                  "lstm_topk_k99"]
 
 
 # --------------------------------------------------------------------------

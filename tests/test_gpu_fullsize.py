@@ -33,6 +33,19 @@ def test_resnet18_topk_both_levels():
     gpu.destroy()
 
 
+def test_resnet18_topk_at_the_papers_levels_k99_and_k25():
+    """K = 99 % (values + holes layout on every layer) and K = 25 % on the 100-class ResNet-18."""
+    print("case resnet18_topk_k99 full size", flush=True)
+    w = wl.workload("resnet18_topk_k99")
+    W = 2
+    gpu, ora = H.make_pair(B.ACC_TOPK, w.layers, W, w.level_crit, w.level_noncrit, w.k_den)
+    _check_step(gpu, ora, [wl.gradient(w, k, 0) for k in range(W)], "K99 step 0")
+    assert ora.words_last == 22215916
+    _set_levels(gpu, ora, 0)
+    _check_step(gpu, ora, [wl.gradient(w, k, 1) for k in range(W)], "K25 step 1")
+    gpu.destroy()
+
+
 def test_resnet18_powersgd_rank4_and_rank1_four_workers():
     print("case resnet18_powersgd full size", flush=True)
     w = wl.workload("resnet18_powersgd")

@@ -131,6 +131,55 @@ def test_large_tie_classes_take_the_sweeps_and_stay_exact():
     gpu.destroy()
 
 
+@pytest.mark.parametrize("crit,noncrit", [(99, 60), (100, 51)])
+def test_high_keep_ratios_use_the_values_and_holes_layout(crit, noncrit):
+    """The paper's own K = 99 % level: layers that keep more than half store values in index
+    order plus the indices of the dropped entries.  Batched and call-by-call paths, layers of
+    several tiles at misaligned offsets, heavy ties; the decoded payload, the mean, the residual
+    and the layout rule itself are compared with the oracle."""
+    print(f"case hole layout {crit}/{noncrit}", flush=True)
+    shapes = [(1, 3 * 8192 + 77, 0), (37, 1001, 1), (1, 5, 0), (3, 8192, 1), (1, 1, 0), (1, 2, 0)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 2
+    rng = np.random.default_rng([crit, noncrit])
+    for mode in ("all", "calls"):
+        gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, crit, noncrit)
+        for li, l in enumerate(layers):
+            for level, num in ((1, crit), (0, noncrit)):
+                fmt, kept, words = B.payload_format(gpu.cfg, li, level)
+                k = orc.k_from_fraction(l.numel, num, 100)
+                assert kept == k and words == orc.payload_words_packed(l.numel, k)
+                assert fmt == (B.ACC_PAYLOAD_VALUES_HOLES if 2 * k > l.numel else B.ACC_PAYLOAD_INDEX_VALUE)
+        for step in range(4):
+            if step == 2:
+                ora.level[:] = 0
+                gpu.set_state(H.oracle_state_blob(gpu, ora))
+            if step % 2:
+                grads = [(rng.integers(-3, 4, N) * 0.25).astype(np.float32) for _ in range(W)]
+            else:
+                grads = [rng.standard_normal(N).astype(np.float32) for _ in range(W)]
+            if mode == "all":
+                _check_step(gpu, ora, grads, f"{mode} step {step}")
+            else:
+                out_ref = ora.step(grads)
+                dg = [H.to_dev(g) for g in grads]
+                out = H.dev_out(N)
+                for w in range(W):
+                    gpu.compress_step(w, dg[w], 0)
+                gpu.aggregate(0)
+                gpu.decompress(out)
+                H.assert_bits_equal(out.cpu().numpy(), out_ref, f"{mode} step {step}: mean")
+                for w in range(W):
+                    for li in range(gpu.n_layers):
+                        idx, val = gpu.get_payload(w, li)
+                        assert np.array_equal(idx, ora.payload[(w, li)][0])
+                        H.assert_bits_equal(val, ora.payload[(w, li)][1], "values")
+                st = gpu.unpack_state(gpu.get_state())
+                H.assert_bits_equal(st["e"], ora.e, f"{mode} step {step}: residual")
+        gpu.destroy()
+
+
 def test_call_by_call_equals_step_all_and_is_deterministic():
     layers = wl.make_layers([(20, 900, 1), (1, 64, 0), (9, 9, 1)])
     N = wl.total_params(layers)

@@ -133,3 +133,37 @@ def test_topk_step_state_machine():
     out2 = o.step([np.zeros(10, np.float32), np.zeros(10, np.float32)])
     assert o.payload[(0, 0)][0].tolist() == [0, 1, 5]    # delta = [1,0,0,0,0,-1]: 1, then tie 0s: idx1; -1
     assert o.payload[(0, 0)][1].tolist() == [1.0, 0.0, -1.0]
+
+
+# ---- payload layout at high keep ratios (the paper's K = 99 % level) ---------------------------
+
+def test_payload_layout_never_exceeds_the_dense_tensor_and_round_trips():
+    rng = np.random.default_rng(77)
+    for n in (1, 2, 7, 64, 1001):
+        x = rng.standard_normal(n).astype(np.float32)
+        for k in sorted({1, max(1, n // 4), max(1, n // 2), max(1, n // 2 + 1), max(1, (99 * n + 99) // 100), n}):
+            kept, vals = orc.topk_select(x, k)
+            layout = orc.payload_layout(n, kept, vals)
+            words = orc.payload_words_packed(n, k)
+            assert words == len(layout[1]) + len(layout[2])
+            assert words <= n or 2 * k <= n                  # never more than dense once k > n/2
+            assert words <= 2 * k
+            assert layout[0] == ("values_holes" if 2 * k > n else "index_value")
+            idx, v = orc.payload_decode(n, layout)
+            assert np.array_equal(idx, kept) and np.array_equal(v, vals)
+    # K = 100 %: exactly the dense tensor, no indices at all
+    kept, vals = orc.topk_select(x, len(x))
+    kind, holes, v = orc.payload_layout(len(x), kept, vals)
+    assert kind == "values_holes" and len(holes) == 0 and np.array_equal(v, x)
+
+
+def test_payload_words_at_the_papers_levels():
+    """ResNet-18 (100 classes) at K = 99 %: every layer keeps more than half, so the message is
+    the model size, against 1.98x that for (index, value) pairs; at K = 25 % pairs stay."""
+    from paper_2010_16248_amd import workloads as wl
+    sizes = [r * c for r, c, _ in wl.resnet18_shapes(100)]
+    k99 = [orc.k_from_fraction(n, 99, 100) for n in sizes]
+    k25 = [orc.k_from_fraction(n, 25, 100) for n in sizes]
+    assert sum(orc.payload_words_packed(n, k) for n, k in zip(sizes, k99)) == 11220132
+    assert sum(2 * k for k in k99) == 22215916
+    assert sum(orc.payload_words_packed(n, k) for n, k in zip(sizes, k25)) == sum(2 * k for k in k25)
