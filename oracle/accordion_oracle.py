@@ -27,6 +27,8 @@ What is computed, and where the paper defines it
   Appendix A "Additional Details for Batch Size experiment": the large batch is
   several backward passes accumulated before one exchange, and the batch size is
   only allowed to grow).
+* Overlap of the Top-K supports of two stochastic gradients: Section 4.3
+  ("Relationship between gradient compression and adaptive batch-size").
 * The optimizer that consumes the averaged decompressed gradient: SGD with
   Nesterov momentum 0.9 (Appendix A, table "Hyperparameters") applied to the
   update rule of Section 3.
@@ -168,6 +170,13 @@ def payload_decode(n: int, layout):
     mask = np.ones(int(n), dtype=bool)
     mask[idx] = False
     return np.flatnonzero(mask).astype(np.int32), values
+
+
+def support_overlap(idx_a: np.ndarray, idx_b: np.ndarray) -> int:
+    """Number of coordinates two kept-index sets have in common (Section 4.3: the overlap in
+    coordinates of the Top-10 % entries of a pair of stochastic gradients).  The overlap
+    fraction the paper plots is this count over k."""
+    return int(np.intersect1d(np.asarray(idx_a), np.asarray(idx_b), assume_unique=True).size)
 
 
 def sparse_mean(n: int, payloads: Sequence[Tuple[np.ndarray, np.ndarray]], n_workers: int) -> np.ndarray:

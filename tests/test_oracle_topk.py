@@ -167,3 +167,38 @@ def test_payload_words_at_the_papers_levels():
     assert sum(orc.payload_words_packed(n, k) for n, k in zip(sizes, k99)) == 11220132
     assert sum(2 * k for k in k99) == 22215916
     assert sum(orc.payload_words_packed(n, k) for n, k in zip(sizes, k25)) == sum(2 * k for k in k25)
+
+
+# ---- overlap of Top-K supports (Section 4.3) ---------------------------------------------------
+
+def test_support_overlap_against_python_sets_and_special_cases():
+    rng = np.random.default_rng(5)
+    for n, k in ((10, 3), (100, 10), (1000, 100), (50, 50)):
+        a, _ = orc.topk_select(rng.standard_normal(n).astype(np.float32), k)
+        b, _ = orc.topk_select(rng.standard_normal(n).astype(np.float32), k)
+        assert orc.support_overlap(a, b) == len(set(a.tolist()) & set(b.tolist()))
+        assert orc.support_overlap(a, a) == k                          # identical gradients
+        assert orc.support_overlap(a, b) == orc.support_overlap(b, a)
+    assert orc.support_overlap(np.array([0, 2, 4]), np.array([1, 3, 5])) == 0
+    assert orc.support_overlap(np.array([], np.int32), np.array([1, 3])) == 0
+
+
+def test_support_overlap_statistics():
+    """Independent supports overlap in k^2 / n coordinates on average (hypergeometric mean);
+    gradients that are a common sparse mean of large magnitude plus dense small noise -- the
+    model of the Section 4.3 equation -- overlap almost completely."""
+    rng = np.random.default_rng(6)
+    n, k = 20000, 2000
+    counts = []
+    for _ in range(20):
+        a, _ = orc.topk_select(rng.standard_normal(n).astype(np.float32), k)
+        b, _ = orc.topk_select(rng.standard_normal(n).astype(np.float32), k)
+        counts.append(orc.support_overlap(a, b))
+    assert abs(np.mean(counts) - k * k / n) < 4 * np.sqrt(k * k / n * 0.9 * 0.9 / 20) + 1
+    mean = np.zeros(n)
+    mean[rng.choice(n, k, replace=False)] = rng.choice([-1.0, 1.0], k) * 5.0
+    ga = (mean + 0.3 * rng.standard_normal(n)).astype(np.float32)
+    gb = (mean + 0.3 * rng.standard_normal(n)).astype(np.float32)
+    a, _ = orc.topk_select(ga, k)
+    b, _ = orc.topk_select(gb, k)
+    assert orc.support_overlap(a, b) > 0.9 * k
