@@ -242,6 +242,16 @@ int32_t accordion_payload_words(acc_ctx* ctx, int64_t* last_step, int64_t* cumul
  * sweeps of one workgroup (slow). */
 int32_t accordion_topk_stats(acc_ctx* ctx, int64_t* restaged_layers, int64_t* swept_layers);
 
+/* Overlap of the kept coordinates of two workers in the last step (Sec. 4.3: how much the
+ * Top-K supports of a pair of stochastic gradients overlap; the paper reports > 90 % for
+ * Top-10 %).  TopK only, between steps, after at least one step (else ACC_ESTATE).
+ * common_host[l] = number of coordinates of layer l that both workers kept; kept_host[l] = k of
+ * that step; n_layers entries each.  The overlap fraction is sum(common) / sum(kept).  With error
+ * feedback the kept sets are those of gradient + memory; on the first step after init they are
+ * those of the gradients themselves.  Synchronises the stream. */
+int32_t accordion_topk_overlap(acc_ctx* ctx, int32_t worker_a, int32_t worker_b, int64_t* common_host,
+                               int64_t* kept_host);
+
 /* State export / import for checkpointing and step-by-step comparison.  Layout (bytes, all
  * little-endian fp32/int32, no padding):  e_0 .. e_{W-1} (N each) | A (N) | Q (sum over
  * matrix layers of cols*r_max; absent for TopK) | norm_old (L) | has_old (L, int32) |
@@ -258,7 +268,7 @@ int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
  * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
  * accordion_stage_name gives the kernel's name (NULL if out of range). */
-#define ACC_N_STAGES 24
+#define ACC_N_STAGES 26
 int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
 int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
 const char* accordion_stage_name(int32_t stage);

@@ -51,14 +51,14 @@ _lib = None
 EXPORTS = [
     "accordion_workspace_bytes", "accordion_init", "accordion_destroy", "accordion_last_error",
     "accordion_compress_step", "accordion_aggregate", "accordion_decompress", "accordion_step_all",
-    "accordion_decompress_update", "accordion_step_all_update", "accordion_batch_status", "accordion_payload_format",
+    "accordion_decompress_update", "accordion_step_all_update", "accordion_batch_status", "accordion_topk_overlap", "accordion_payload_format",
     "accordion_detect_regime", "accordion_reset_accumulator", "accordion_get_levels",
     "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
     "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
     "accordion_probe_copy", "accordion_topk_stats", "accordion_flush",
 ]
-ACC_N_STAGES = 24
+ACC_N_STAGES = 26
 
 
 def load_library() -> C.CDLL:
@@ -82,6 +82,7 @@ def load_library() -> C.CDLL:
         "accordion_decompress_update": [vp, vp, vp, f32, f32, f32],
         "accordion_payload_format": [C.POINTER(acc_config), C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                      C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
+        "accordion_topk_overlap": [vp, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
         "accordion_batch_status": [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                    C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
         "accordion_step_all_update": [vp, C.POINTER(vp), vp, vp, f32, f32, f32],
@@ -241,6 +242,14 @@ class Accordion:
         arr = (C.c_void_p * len(grads))(*[g.data_ptr() for g in grads])
         _check(self._lib, self.ctx, self._lib.accordion_step_all_update(
             self.ctx, arr, C.c_void_p(weights.data_ptr()), C.c_void_p(velocity.data_ptr()), lr, momentum, weight_decay))
+
+    def topk_overlap(self, worker_a: int, worker_b: int) -> Tuple[np.ndarray, np.ndarray]:
+        common = np.zeros(self.n_layers, np.int64)
+        kept = np.zeros(self.n_layers, np.int64)
+        _check(self._lib, self.ctx, self._lib.accordion_topk_overlap(
+            self.ctx, worker_a, worker_b, common.ctypes.data_as(C.POINTER(C.c_int64)),
+            kept.ctypes.data_as(C.POINTER(C.c_int64))))
+        return common, kept
 
     def batch_status(self) -> dict:
         lv, pend, last = C.c_int32(0), C.c_int32(0), C.c_int32(0)

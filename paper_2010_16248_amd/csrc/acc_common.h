@@ -108,6 +108,7 @@ struct Ws {
   uint32_t* eqpre;             // W x q_stride exclusive prefix of eqq within the layer (+ total)
   int64_t q_stride;
   int32_t* pay_idx;  float* pay_val;  int64_t pay_stride;
+  unsigned long long* overlap; // L per-layer counters of the overlap read-back
   // batch-size mode
   uint32_t* bstate;            // two slots of four words, used alternately (micro-step parity)
   int32_t bmult, bmono;        // micro-steps per large batch; 1: the batch only grows

@@ -1203,4 +1203,65 @@ __global__ __launch_bounds__(256) void topk_sparse_update_kernel(const Ws ws, co
   sparse_mean_body<true>(ws, sink);
 }
 
+// ---- overlap of two workers' kept sets (Section 4.3) ---------------------------------------------
+// Per layer, the number of coordinates both workers kept in the last step.  One workgroup per flat
+// tile: worker a's index list of the tile (kept entries, or the holes when the layer keeps more than
+// half) is marked in an LDS bit set, worker b's list is tested against it; for hole lists
+// |kept_a & kept_b| = count - |holes_a| - |holes_b| + |holes_a & holes_b|.  Integer atomics on the
+// per-layer counters (which the caller has cleared): the result does not depend on their order.
+__global__ __launch_bounds__(256) void topk_overlap_kernel(const Ws ws, int wa, int wb,
+                                                           unsigned long long* __restrict__ common) {
+  __shared__ uint32_t bits[kTile / 32];
+  __shared__ uint32_t hits;
+  const int tid = threadIdx.x;
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  for (int i = tid; i < kTile / 32; i += kFlatThreads) bits[i] = 0u;
+  if (tid == 0) hits = 0u;
+  __syncthreads();
+  const int tl = ft.start >> kTileShift;
+  const uint32_t n_layer = (uint32_t)L.rows * (uint32_t)L.cols;
+  uint32_t listed[2];
+  bool holes = false;
+  for (int side = 0; side < 2; ++side) {
+    const int w = side == 0 ? wa : wb;
+    const int64_t qs = (int64_t)w * ws.q_stride + L.qoff + 4 * (int64_t)tl;
+    const SelState* sp = ws.sel + (int64_t)w * ws.L + ft.layer;
+    const uint32_t ktie = sp->ktie, kk = sp->k;
+    const uint32_t lo = ws.gtpre[qs] + min(ktie, ws.eqpre[qs]);
+    const uint32_t hi = ws.gtpre[qs + 4] + min(ktie, ws.eqpre[qs + 4]);
+    const int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
+    holes = payload_has_holes(n_layer, kk);
+    uint32_t p0 = lo, p1 = min(hi, kk);
+    if (holes) {                                             // the tile's part of the hole list
+      const uint32_t nholes = n_layer - min(kk, n_layer);
+      p0 = min((uint32_t)ft.start - lo, nholes);
+      p1 = min((uint32_t)(ft.start + ft.count) - hi, nholes);
+    }
+    listed[side] = p1 > p0 ? p1 - p0 : 0u;
+    uint32_t mine = 0;
+    for (uint32_t p = p0 + tid; p < p1; p += kFlatThreads) {
+      const int32_t i = pidx[p] - ft.start;
+      if (i >= 0 && i < ft.count) {
+        if (side == 0) atomicOr(&bits[i >> 5], 1u << (i & 31));
+        else mine += (bits[i >> 5] >> (i & 31)) & 1u;
+      }
+    }
+    if (side == 1) {
+      mine = wave_sum_u32(mine);
+      if ((tid & 63) == 0 && mine) atomicAdd(&hits, mine);
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const uint32_t both = holes ? (uint32_t)ft.count - listed[0] - listed[1] + hits : hits;
+    if (both) atomicAdd(&common[ft.layer], (unsigned long long)both);
+  }
+}
+
+__global__ __launch_bounds__(256) void zero_u64_kernel(unsigned long long* __restrict__ p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0ull;
+}
+
 }  // namespace acc

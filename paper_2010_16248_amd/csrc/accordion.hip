@@ -46,7 +46,7 @@ struct Plan {
   Region r_A, r_e, r_norm_part, r_bstate;
   int64_t n_model = 0;   // elements that belong to a layer
   Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean;
-  Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval;
+  Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval, r_overlap;
   int64_t total_bytes = 0;
 };
 
@@ -220,6 +220,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     reg(p.r_eqpre, 4 * p.q_stride * W);
     reg(p.r_payidx, 4 * p.pay_stride * W);
     reg(p.r_payval, 4 * p.pay_stride * W);
+    reg(p.r_overlap, 8 * (int64_t)nl);
   }
   p.total_bytes = off;
   return ACC_OK;
@@ -254,6 +255,7 @@ enum Stage {
   ST_norm_partial_kernel, ST_regime_decide_kernel, ST_recount_words_kernel, ST_zero_accum_kernel,
   ST_psgd_decomp_update_kernel, ST_topk_compact_update_kernel, ST_topk_sparse_update_kernel,
   ST_batch_micro_kernel, ST_batch_micro_update_kernel, ST_batch_decide_kernel,
+  ST_topk_overlap_kernel, ST_zero_u64_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
@@ -264,7 +266,8 @@ static const char* const kStageNames[ST_COUNT] = {
   "topk_compact_kernel", "topk_compact_mean_kernel", "topk_sparse_mean_kernel",
   "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel",
   "psgd_decomp_update_kernel", "topk_compact_update_kernel", "topk_sparse_update_kernel",
-  "batch_micro_kernel", "batch_micro_update_kernel", "batch_decide_kernel"};
+  "batch_micro_kernel", "batch_micro_update_kernel", "batch_decide_kernel",
+  "topk_overlap_kernel", "zero_u64_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
 
@@ -574,6 +577,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.pay_idx = at<int32_t>(c, p.r_payidx);
     ws.pay_val = at<float>(c, p.r_payval);
     ws.pay_stride = p.pay_stride;
+    ws.overlap = at<unsigned long long>(c, p.r_overlap);
   }
   ws.bstate = at<uint32_t>(c, p.r_bstate);
   ws.bmult = cfg->method == ACC_BATCH ? cfg->batch_multiplier : 1;
@@ -898,6 +902,31 @@ int32_t accordion_topk_stats(acc_ctx* c, int64_t* restaged_layers, int64_t* swep
   ACC_HIP(c, hipMemcpy(s, c->ws.stats, sizeof(s), hipMemcpyDeviceToHost));
   *restaged_layers = (int64_t)s[0];
   *swept_layers = (int64_t)s[1];
+  return ACC_OK;
+}
+
+int32_t accordion_topk_overlap(acc_ctx* c, int32_t worker_a, int32_t worker_b, int64_t* common_host,
+                               int64_t* kept_host) {
+  if (!c) return ACC_EINVAL;
+  if (c->cfg.method != ACC_TOPK) return fail(c->err, ACC_EINVAL, "overlaps exist for TopK only");
+  if (worker_a < 0 || worker_a >= c->cfg.n_workers || worker_b < 0 || worker_b >= c->cfg.n_workers)
+    return fail(c->err, ACC_EINVAL, "worker out of range");
+  if (!common_host || !kept_host) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
+  if (c->in_step) return fail(c->err, ACC_ESTATE, "overlap inside a step");
+  if (c->step_id == 2) return fail(c->err, ACC_ESTATE, "no step has run yet: there are no payloads");
+  const Ws& ws = c->ws;
+  const int L = ws.L;
+  ACC_LAUNCH(c, zero_u64_kernel, dim3((L + 255) / 256), dim3(256), ws.overlap, L);
+  ACC_LAUNCH(c, topk_overlap_kernel, dim3(ws.n_ftiles), dim3(256), ws, (int)worker_a, (int)worker_b, ws.overlap);
+  ACC_HIP(c, hipStreamSynchronize(c->stream));
+  std::vector<unsigned long long> cnt((size_t)L);
+  std::vector<SelState> sel((size_t)L);
+  ACC_HIP(c, hipMemcpy(cnt.data(), ws.overlap, 8 * (size_t)L, hipMemcpyDeviceToHost));
+  ACC_HIP(c, hipMemcpy(sel.data(), ws.sel + (size_t)worker_a * L, sizeof(SelState) * (size_t)L, hipMemcpyDeviceToHost));
+  for (int i = 0; i < L; ++i) {
+    common_host[i] = (int64_t)cnt[(size_t)i];
+    kept_host[i] = (int64_t)sel[(size_t)i].k;
+  }
   return ACC_OK;
 }
 

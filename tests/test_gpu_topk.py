@@ -180,6 +180,42 @@ def test_high_keep_ratios_use_the_values_and_holes_layout(crit, noncrit):
         gpu.destroy()
 
 
+@pytest.mark.parametrize("crit", [10, 99])
+def test_support_overlap_matches_the_oracle(crit):
+    """Per-layer overlap of the kept coordinates of pairs of workers (Section 4.3), for (index,
+    value) payloads (K 10 %) and for values + holes payloads (K 99 %); gradients built as a
+    common sparse mean plus dense noise, plus one pure-noise worker."""
+    print(f"case overlap K={crit}", flush=True)
+    shapes = [(1, 3 * 8192 + 77, 0), (37, 1001, 1), (1, 5, 0), (3, 8192, 1), (1, 1, 0)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 3
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, crit, 1)
+    with pytest.raises(B.AccordionError) as ei:
+        gpu.topk_overlap(0, 1)                               # no payloads yet
+    assert ei.value.status == B.ACC_ESTATE
+    rng = np.random.default_rng(crit)
+    mean = np.zeros(N)
+    hot = rng.choice(N, N // 10, replace=False)
+    mean[hot] = rng.choice([-1.0, 1.0], hot.size) * 5.0
+    for step in range(2):
+        grads = [(mean + 0.3 * rng.standard_normal(N)).astype(np.float32) for _ in range(2)]
+        grads.append(rng.standard_normal(N).astype(np.float32))
+        _check_step(gpu, ora, grads, f"step {step}")
+        for a, b in ((0, 1), (1, 2), (2, 0), (1, 1)):
+            common, kept = gpu.topk_overlap(a, b)
+            for li, l in enumerate(layers):
+                assert kept[li] == ora.layer_k(li)
+                ref = orc.support_overlap(ora.payload[(a, li)][0], ora.payload[(b, li)][0])
+                assert common[li] == ref, (step, a, b, li, common[li], ref)
+        common, kept = gpu.topk_overlap(0, 1)
+        if crit == 10 and step == 0:
+            assert common.sum() > 0.9 * kept.sum()           # the paper's "> 90 %" under its model
+    with pytest.raises(B.AccordionError):
+        gpu.topk_overlap(0, 3)
+    gpu.destroy()
+
+
 def test_call_by_call_equals_step_all_and_is_deterministic():
     layers = wl.make_layers([(20, 900, 1), (1, 64, 0), (9, 9, 1)])
     N = wl.total_params(layers)
