@@ -29,6 +29,9 @@ What is computed, and where the paper defines it
   only allowed to grow).
 * Overlap of the Top-K supports of two stochastic gradients: Section 4.3
   ("Relationship between gradient compression and adaptive batch-size").
+* The comparison detector (Section 5.5 "Comparison with Prior Work"): the mean to
+  standard deviation ratio (MSDR) of the gradients; when it has dropped by a given
+  fraction the compression is reduced.
 * The optimizer that consumes the averaged decompressed gradient: SGD with
   Nesterov momentum 0.9 (Appendix A, table "Hyperparameters") applied to the
   update rule of Section 3.
@@ -42,6 +45,10 @@ decide in the same precision.
 
 The optimizer update is taken in fp32, one rounding per multiplication and per
 addition, in the order written in nesterov_update.
+
+The MSDR rule is this build's reading of the one sentence the paper spends on the
+comparison method (see msdr_should_switch): "parity unpinned" for the rule; the
+statistic itself is pinned.
 
 Pins: tests/test_oracle_*.py check every function below against brute force on
 tiny inputs, library QR/SVD, closed forms, the paper's printed "Data Sent"
@@ -196,6 +203,36 @@ def layer_norm(a: np.ndarray) -> np.float32:
     return F32(math.sqrt(float(np.dot(x, x))))
 
 
+def msdr(grads: Sequence[np.ndarray]) -> np.float32:
+    """Mean to standard deviation ratio of T gradients of one layer (Section 5.5), written
+    out as the definition: || mean_t g_t ||_2 over sqrt( mean_t || g_t - mean ||_2^2 ), in
+    fp64 on the fp32 inputs; +inf when the gradients do not vary at all."""
+    g = np.stack([np.asarray(x, dtype=F64).reshape(-1) for x in grads])
+    mean = g.mean(axis=0)
+    var = float(np.mean(np.sum((g - mean) ** 2, axis=1)))
+    num = math.sqrt(float(np.dot(mean, mean)))
+    return F32(np.inf) if var <= 0.0 else F32(num / math.sqrt(var))
+
+
+def msdr_streaming(sum_vec: np.ndarray, sum_sq: float, t: int) -> np.float32:
+    """The same ratio from what a detector can keep without storing the gradients: the
+    element-wise sum of the T gradients (the accumulator of Section 4.2), the sum of their
+    squared norms and T:  mean_t ||g_t - m||^2 = (sum_t ||g_t||^2) / T - ||m||^2."""
+    a = np.asarray(sum_vec, dtype=F64).reshape(-1)
+    mu2 = float(np.dot(a, a)) / (float(t) * float(t))
+    var = float(sum_sq) / float(t) - mu2
+    return F32(np.inf) if var <= 0.0 else F32(math.sqrt(mu2 / var))
+
+
+def msdr_should_switch(ref, m, has_ref: bool, delta) -> bool:
+    """Reading of Section 5.5's description of the comparison method: once the ratio has
+    dropped by the fraction delta relative to its value at the last switch (or at the first
+    window), the layer moves to the more accurate level, and it never moves back.  fp32."""
+    if not has_ref:
+        return False
+    return bool(F32(m) <= F32(F32(F32(1.0) - F32(delta)) * F32(ref)))
+
+
 def regime_is_critical(old, curr, has_old: bool, eta, lr_curr, lr_next) -> bool:
     """Algorithm 1 / the Section 4.2 criterion, in fp32:
     critical  <=>  | ||D_old|| - ||D_curr|| | / ||D_old|| >= eta   or   lr_next < lr_curr.
@@ -252,7 +289,8 @@ class AccordionOracle:
 
     def __init__(self, method: int, layers, n_workers: int, level_crit: int,
                  level_noncrit: int, k_den: int = 100, eta: float = 0.5,
-                 initial_level: int = 1, q_init: np.ndarray | None = None):
+                 initial_level: int = 1, q_init: np.ndarray | None = None,
+                 detector: str = "norm"):
         self.method = int(method)
         self.layers = [tuple(int(v) for v in l) for l in layers]
         self.W = int(n_workers)
@@ -277,6 +315,10 @@ class AccordionOracle:
                     blk = c * self.r_max
                     self.Q[li] = np.array(q_init[pos:pos + blk], dtype=F32).reshape(c, self.r_max).copy()
                     pos += blk
+        assert detector in ("norm", "msdr")
+        self.detector = detector
+        self.sq = np.zeros(nl, dtype=F64)       # msdr: sum over the window of ||g_0||^2 per layer
+        self.T = 0                              # msdr: steps in the window
         self.words_last = 0
         self.words_cum = 0
         # intermediates of the last step, kept for comparison
@@ -304,6 +346,11 @@ class AccordionOracle:
         out = np.zeros(self.N, dtype=F32)
         # accumulate the raw gradient of worker 0 (the deciding node, Section 3 "Goals")
         self.A = (self.A + grads[0].astype(F32)).astype(F32)
+        if self.detector == "msdr":
+            for li, (off, rows, cols, _) in enumerate(self.layers):
+                g0 = grads[0][off:off + rows * cols].astype(F64)
+                self.sq[li] += float(np.dot(g0, g0))
+            self.T += 1
         delta = [ef_add(grads[w], self.e[w]) for w in range(self.W)]
         words = 0
         self.P_hat, self.Q_bar, self.payload = {}, {}, {}
@@ -357,6 +404,8 @@ class AccordionOracle:
         """Norm of each layer's accumulated gradient, Algorithm 1 per layer, then
         curr -> old and the accumulator restarts.  Returns the new level vector
         (1 = critical)."""
+        if self.detector == "msdr":
+            return self._detect_msdr()
         for li, (off, rows, cols, _) in enumerate(self.layers):
             c = layer_norm(self.A[off:off + rows * cols])
             crit = regime_is_critical(self.norm_old[li], c, bool(self.has_old[li]),
@@ -369,8 +418,28 @@ class AccordionOracle:
         self.A[:] = F32(0.0)
         return self.level.copy()
 
+    def _detect_msdr(self) -> np.ndarray:
+        """Window end with the comparison detector: norm_curr holds the window's ratio,
+        norm_old the reference (the ratio at the last switch, or of the first window)."""
+        for li, (off, rows, cols, _) in enumerate(self.layers):
+            m = msdr_streaming(self.A[off:off + rows * cols], self.sq[li], max(self.T, 1))
+            self.norm_prev[li] = self.norm_old[li]
+            self.norm_curr[li] = m
+            if not self.has_old[li]:
+                self.norm_old[li] = m
+                self.has_old[li] = 1
+            elif msdr_should_switch(self.norm_old[li], m, True, self.eta):
+                self.level[li] = 1
+                self.norm_old[li] = m
+        self.A[:] = F32(0.0)
+        self.sq[:] = 0.0
+        self.T = 0
+        return self.level.copy()
+
     def reset_accumulator(self) -> None:
         self.A[:] = F32(0.0)
+        self.sq[:] = 0.0
+        self.T = 0
 
     def words_per_step(self) -> int:
         """Floats one worker sends per step at the current levels."""
