@@ -61,6 +61,20 @@ enum {
 
 enum { ACC_POWERSGD = 0, ACC_TOPK = 1, ACC_BATCH = 2 };
 
+/* Which statistic accordion_detect_regime decides on.  ACC_DETECT_NORM: the paper's own test
+ * (Sec. 4.2, Algorithm 1).  ACC_DETECT_MSDR: the comparison method of Sec. 5.5 -- per layer, the
+ * mean to standard deviation ratio of worker 0's gradients over the window,
+ *     m = || mean_t g_t || / sqrt( mean_t || g_t - mean ||^2 )
+ * (from the accumulator, the sum of the squared gradient norms and the step count; fp64, result
+ * fp32; +inf if the gradients did not vary).  The paper describes its use in one sentence; the
+ * reading taken here: the first window's m is the reference; once m <= (1 - eta) * reference the
+ * layer moves to the *_crit level (less compression) for good and m becomes the reference.
+ * lr_curr / lr_next play no role.  accordion_get_norms then returns the reference the last decision
+ * compared against (old_host) and m (curr_host).  One extra pass over worker 0's gradient per step.
+ * accordion_set_state restarts the window sums (import state at a window end).  Not available
+ * for ACC_BATCH; eta must be below 1. */
+enum { ACC_DETECT_NORM = 0, ACC_DETECT_MSDR = 1 };
+
 #define ACC_MAX_WORKERS 32
 #define ACC_MAX_RANK 4
 #define ACC_MAX_BATCH_MULTIPLIER 65536
@@ -86,6 +100,7 @@ typedef struct acc_config {
   int32_t initial_level;       /* level before the first decision: 1 = critical, 0 = not */
   int32_t batch_multiplier;    /* ACC_BATCH: floor(B_high / B_low) in [1, ACC_MAX_BATCH_MULTIPLIER]; else ignored */
   int32_t batch_monotone;      /* ACC_BATCH: 1 = once the large batch is chosen it is kept (App. A) */
+  int32_t detector;            /* ACC_DETECT_NORM (0, the paper's) or ACC_DETECT_MSDR */
 } acc_config;
 
 typedef struct acc_ctx acc_ctx;
@@ -268,7 +283,7 @@ int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
  * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
  * accordion_stage_name gives the kernel's name (NULL if out of range). */
-#define ACC_N_STAGES 26
+#define ACC_N_STAGES 28
 int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
 int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
 const char* accordion_stage_name(int32_t stage);

@@ -37,7 +37,8 @@ class acc_config(C.Structure):
                 ("n_workers", C.c_int32), ("rank_crit", C.c_int32), ("rank_noncrit", C.c_int32),
                 ("k_num_crit", C.c_int32), ("k_num_noncrit", C.c_int32), ("k_den", C.c_int32),
                 ("eta", C.c_float), ("initial_level", C.c_int32),
-                ("batch_multiplier", C.c_int32), ("batch_monotone", C.c_int32)]
+                ("batch_multiplier", C.c_int32), ("batch_monotone", C.c_int32),
+                ("detector", C.c_int32)]
 
 
 class AccordionError(RuntimeError):
@@ -58,7 +59,7 @@ EXPORTS = [
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
     "accordion_probe_copy", "accordion_topk_stats", "accordion_flush",
 ]
-ACC_N_STAGES = 26
+ACC_N_STAGES = 28
 
 
 def load_library() -> C.CDLL:
@@ -117,7 +118,7 @@ def load_library() -> C.CDLL:
 def make_config(method: int, layers: Sequence, n_workers: int, level_crit: int, level_noncrit: int,
                 k_den: int = 100, eta: float = 0.5, initial_level: int = 1,
                 n_params: Optional[int] = None, batch_multiplier: int = 1,
-                batch_monotone: int = 1) -> Tuple[acc_config, object]:
+                batch_monotone: int = 1, detector: int = 0) -> Tuple[acc_config, object]:
     """Build an acc_config; returns (config, keep_alive) -- the layer array must outlive the
     calls that read it.  layers: objects with offset/rows/cols/is_matrix or 4-tuples."""
     arr = (acc_layer * max(1, len(layers)))()
@@ -133,6 +134,7 @@ def make_config(method: int, layers: Sequence, n_workers: int, level_crit: int, 
     cfg.n_params = end if n_params is None else n_params
     cfg.n_workers = n_workers
     cfg.batch_multiplier, cfg.batch_monotone = batch_multiplier, batch_monotone
+    cfg.detector = detector
     if method == ACC_POWERSGD:
         cfg.rank_crit, cfg.rank_noncrit = level_crit, level_noncrit
         cfg.k_num_crit = cfg.k_num_noncrit = cfg.k_den = 1
@@ -169,6 +171,7 @@ def payload_format(cfg: acc_config, layer: int, level: int) -> Tuple[int, int, i
 
 
 ACC_PAYLOAD_INDEX_VALUE, ACC_PAYLOAD_VALUES_HOLES = 0, 1
+ACC_DETECT_NORM, ACC_DETECT_MSDR = 0, 1
 
 
 def probe_copy(dst, src) -> None:
@@ -186,14 +189,14 @@ class Accordion:
     def __init__(self, method: int, layers: Sequence, n_workers: int, level_crit: int,
                  level_noncrit: int, k_den: int = 100, eta: float = 0.5, initial_level: int = 1,
                  q_init: Optional[np.ndarray] = None, device: str = "cuda:0",
-                 batch_multiplier: int = 1, batch_monotone: int = 1):
+                 batch_multiplier: int = 1, batch_monotone: int = 1, detector: int = 0):
         import torch  # device memory and the stream handle only
 
         self._lib = load_library()
         self._torch = torch
         self.cfg, self._keep = make_config(method, layers, n_workers, level_crit, level_noncrit,
                                            k_den, eta, initial_level, None, batch_multiplier,
-                                           batch_monotone)
+                                           batch_monotone, detector)
         self.method, self.n_workers, self.n_layers = method, n_workers, len(layers)
         self.n_params = int(self.cfg.n_params)
         self.layers = [(l.offset, l.rows, l.cols, l.is_matrix) if hasattr(l, "offset") else tuple(l)

@@ -73,12 +73,14 @@ struct Ws {
   float* norm_curr;
   int32_t* has_old;
   int32_t* rank_used;          // per layer, rank of the last PowerSGD step
-  unsigned long long* words;   // [0] per step at current levels, [1] last step, [2] cumulative
+  unsigned long long* words;   // [0] per step at current levels, [1] last step, [2] cumulative,
+                               // [3] steps in the current detection window (MSDR detector)
   unsigned long long* stats;   // TopK diagnostics: [0] (worker, layer) pairs re-staged, [1] decided by sweeps
   float* A;                    // accumulated gradient, N
   float* e;                    // W x e_stride error memory (holds Delta during a step)
   int64_t e_stride;
   double* norm_part;           // per flat tile
+  double* sq_part;             // per flat tile: sum over the window of ||g_0||^2 (MSDR detector)
   const FlatTile* ftiles;
   const MatTile* mtiles;
   const QTile* qtiles;

@@ -36,6 +36,10 @@ __global__ __launch_bounds__(256) void zero_accum_kernel(const Ws ws) {
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int q = threadIdx.x; q < tg.nquads; q += kFlatThreads)
     st_quad(ws.A, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi, zero);
+  if (threadIdx.x == 0) {                                   // the MSDR detector's window sums too
+    if (ws.sq_part) ws.sq_part[blockIdx.x] = 0.0;
+    if (blockIdx.x == 0) ws.words[3] = 0ull;
+  }
 }
 
 // One wave per layer: c = sqrt(sum of the layer's tile partials), then Algorithm 1 in fp32:
@@ -65,9 +69,73 @@ __global__ __launch_bounds__(64) void regime_decide_kernel(const Ws ws, float lr
   }
 }
 
+// ---- comparison detector: mean to standard deviation ratio (Section 5.5) -----------------------
+
+// Per flat tile: sq_part[tile] += sum of squares of worker 0's gradient (fp64; one workgroup owns
+// a tile, the order inside is fixed: the running sums are reproducible).  Block 0 counts the step.
+__global__ __launch_bounds__(256) void msdr_sq_kernel(const Ws ws, const float* __restrict__ g0) {
+  __shared__ double red[4];
+  const int tid = threadIdx.x;
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  const TileGeom tg = tile_geom(L, ft);
+  double s = 0.0;
+  for (int q = tid; q < tg.nquads; q += kFlatThreads) {
+    const float4 a = ld_quad(g0, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi);
+    s += (double)a.x * (double)a.x;
+    s += (double)a.y * (double)a.y;
+    s += (double)a.z * (double)a.z;
+    s += (double)a.w * (double)a.w;
+  }
+  s = wave_sum_f64(s);
+  if ((tid & 63) == 0) red[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) {
+    ws.sq_part[blockIdx.x] += (red[0] + red[1]) + (red[2] + red[3]);
+    if (blockIdx.x == 0) ws.words[3] += 1ull;               // steps in the window
+  }
+}
+
+// One wave per layer, after norm_partial_kernel: with a = sum of the layer's tile partials of
+// ||A||^2, q = sum of its sq_part and T steps,  m = sqrt( (a / T^2) / (q / T - a / T^2) )  (+inf
+// when the gradients did not vary).  First window: m becomes the reference.  Later: once
+// m <= (1 - eta) * reference the layer moves to the accurate level (1) for good and m becomes
+// the reference.  norm_curr = m, norm_old = reference.  The window's sums are cleared.
+__global__ __launch_bounds__(64) void msdr_decide_kernel(const Ws ws) {
+  const int li = blockIdx.x;
+  const int lane = threadIdx.x;
+  const LayerDev& L = ws.layers[li];
+  double a = 0.0, q = 0.0;
+  for (int t = lane; t < L.ntiles; t += kWave) {
+    a += ws.norm_part[L.tile0 + t];
+    q += ws.sq_part[L.tile0 + t];
+    ws.sq_part[L.tile0 + t] = 0.0;
+  }
+  a = wave_sum_f64(a);
+  q = wave_sum_f64(q);
+  if (lane == 0) {
+    const unsigned long long steps = ws.words[3];
+    const double T = steps ? (double)steps : 1.0;
+    const double mu2 = a / (T * T);
+    const double var = q / T - mu2;
+    const float m = var <= 0.0 ? __builtin_inff() : (float)sqrt(mu2 / var);
+    const float ref = ws.norm_old[li];
+    ws.norm_prev[li] = ref;
+    ws.norm_curr[li] = m;
+    if (ws.has_old[li] == 0) {
+      ws.norm_old[li] = m;
+      ws.has_old[li] = 1;
+    } else if (m <= (1.0f - ws.eta) * ref) {
+      ws.level[li] = 1;
+      ws.norm_old[li] = m;
+    }
+  }
+}
+
 // Floats one worker sends per step at the current levels (the paper's "Data Sent" unit).
 __global__ __launch_bounds__(256) void recount_words_kernel(const Ws ws, int method) {
   __shared__ unsigned long long red[256];
+  if (threadIdx.x == 0) ws.words[3] = 0ull;                 // a new detection window starts
   if (method == 2) {                        // batch-size mode: an exchange is the dense model
     if (threadIdx.x == 0) ws.words[0] = (unsigned long long)ws.n_model;
     return;

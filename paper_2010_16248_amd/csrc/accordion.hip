@@ -43,7 +43,7 @@ struct Plan {
   // workspace regions
   Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
-  Region r_A, r_e, r_norm_part, r_bstate;
+  Region r_A, r_e, r_norm_part, r_sq_part, r_bstate;
   int64_t n_model = 0;   // elements that belong to a layer
   Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean;
   Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval, r_overlap;
@@ -65,6 +65,10 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
   if (c->n_params <= 0 || c->n_params > (int64_t(1) << 40)) return fail(err, ACC_EINVAL, "n_params out of range");
   if (!(c->eta >= 0.0f) || !std::isfinite(c->eta)) return fail(err, ACC_EINVAL, "eta must be finite and >= 0");
   if (c->initial_level != 0 && c->initial_level != 1) return fail(err, ACC_EINVAL, "initial_level must be 0 or 1");
+  if (c->detector != ACC_DETECT_NORM && c->detector != ACC_DETECT_MSDR) return fail(err, ACC_EINVAL, "unknown detector");
+  if (c->detector == ACC_DETECT_MSDR && c->method == ACC_BATCH)
+    return fail(err, ACC_EINVAL, "the MSDR detector is not available in batch-size mode");
+  if (c->detector == ACC_DETECT_MSDR && !(c->eta < 1.0f)) return fail(err, ACC_EINVAL, "MSDR detector: eta must be below 1");
   if (c->method == ACC_POWERSGD) {
     if (c->rank_crit < 1 || c->rank_crit > ACC_MAX_RANK || c->rank_noncrit < 1 || c->rank_noncrit > ACC_MAX_RANK)
       return fail(err, ACC_EINVAL, "rank out of [1, ACC_MAX_RANK]");
@@ -196,6 +200,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
   reg(p.r_A, 4 * p.e_stride);
   reg(p.r_e, 4 * p.e_stride * W);
   reg(p.r_norm_part, 8 * ntile);
+  reg(p.r_sq_part, c->detector == ACC_DETECT_MSDR ? 8 * ntile : 0);
   reg(p.r_bstate, 4 * 8);
   if (c->method == ACC_POWERSGD) {
     reg(p.r_Q, 4 * p.q_total);
@@ -255,7 +260,7 @@ enum Stage {
   ST_norm_partial_kernel, ST_regime_decide_kernel, ST_recount_words_kernel, ST_zero_accum_kernel,
   ST_psgd_decomp_update_kernel, ST_topk_compact_update_kernel, ST_topk_sparse_update_kernel,
   ST_batch_micro_kernel, ST_batch_micro_update_kernel, ST_batch_decide_kernel,
-  ST_topk_overlap_kernel, ST_zero_u64_kernel,
+  ST_topk_overlap_kernel, ST_zero_u64_kernel, ST_msdr_sq_kernel, ST_msdr_decide_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
@@ -267,7 +272,7 @@ static const char* const kStageNames[ST_COUNT] = {
   "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel",
   "psgd_decomp_update_kernel", "topk_compact_update_kernel", "topk_sparse_update_kernel",
   "batch_micro_kernel", "batch_micro_update_kernel", "batch_decide_kernel",
-  "topk_overlap_kernel", "zero_u64_kernel"};
+  "topk_overlap_kernel", "zero_u64_kernel", "msdr_sq_kernel", "msdr_decide_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
 
@@ -384,8 +389,20 @@ int launch_topk_select(acc_ctx* c, int w0, int nw) {
   return ACC_OK;
 }
 
+// The MSDR detector also needs the squared norm of worker 0's raw gradient of every step.
+int launch_detector_feed(acc_ctx* c, int w0) {
+  const Ws& ws = c->ws;
+  if (c->cfg.detector == ACC_DETECT_MSDR && w0 == 0)
+    ACC_LAUNCH(c, msdr_sq_kernel, dim3(ws.n_ftiles), dim3(256), ws, c->grads.p[0]);
+  return ACC_OK;
+}
+
 int launch_phase0(acc_ctx* c, int w0, int nw) {
   const Ws& ws = c->ws;
+  {
+    const int rc = launch_detector_feed(c, w0);
+    if (rc != ACC_OK) return rc;
+  }
   if (c->cfg.method == ACC_POWERSGD) {
     const int gx = ws.n_mtiles + (w0 == 0 ? ws.n_vectiles : 0);
     if (gx > 0) ACC_LAUNCH(c, psgd_ef_p_kernel, dim3(gx, nw), dim3(256), ws, c->grads, w0, c->pending_mask);
@@ -551,6 +568,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   ws.e = at<float>(c, p.r_e);
   ws.e_stride = p.e_stride;
   ws.norm_part = at<double>(c, p.r_norm_part);
+  ws.sq_part = p.r_sq_part.bytes > 0 ? at<double>(c, p.r_sq_part) : nullptr;
   if (cfg->method == ACC_POWERSGD) {
     ws.Q = at<float>(c, p.r_Q);
     ws.Phat = at<float>(c, p.r_Phat);
@@ -736,7 +754,8 @@ static int32_t step_all_into(acc_ctx* c, const float* const* grads_host_array, c
     if (rc == ACC_OK) rc = launch_decompress(c, sink);
   } else {
     // the compaction of all workers and the mean of their kept values share one pass over Delta
-    rc = launch_topk_select(c, 0, W);
+    rc = launch_detector_feed(c, 0);
+    if (rc == ACC_OK) rc = launch_topk_select(c, 0, W);
     if (rc == ACC_OK) rc = launch_topk_compact_mean(c, sink);
   }
   end_step(c);
@@ -767,7 +786,8 @@ int32_t accordion_detect_regime(acc_ctx* c, float lr_curr, float lr_next) {
     ACC_LAUNCH(c, batch_decide_kernel, dim3(1), dim3(256), ws, lr_curr, lr_next);
     return ACC_OK;
   }
-  ACC_LAUNCH(c, regime_decide_kernel, dim3(ws.L), dim3(64), ws, lr_curr, lr_next);
+  if (c->cfg.detector == ACC_DETECT_MSDR) ACC_LAUNCH(c, msdr_decide_kernel, dim3(ws.L), dim3(64), ws);
+  else ACC_LAUNCH(c, regime_decide_kernel, dim3(ws.L), dim3(64), ws, lr_curr, lr_next);
   ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), ws, (int)c->cfg.method);
   return ACC_OK;
 }
@@ -1008,6 +1028,8 @@ int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
   const int32_t rc = state_copy(c, const_cast<char*>(static_cast<const char*>(state_host)), false);
   if (rc != ACC_OK) return rc;
   c->pending_mask = 0;                                       // the memory just written is explicit
+  if (c->plan.r_sq_part.bytes > 0)                           // the MSDR window restarts with the import
+    ACC_HIP(c, hipMemset(c->ws.sq_part, 0, (size_t)c->plan.r_sq_part.bytes));
   ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)c->cfg.method);
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   return ACC_OK;
