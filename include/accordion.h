@@ -120,6 +120,20 @@ int32_t accordion_workspace_bytes(const acc_config* cfg, size_t* out_bytes);
 int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t workspace_bytes,
                        const float* q_init_host, void* hip_stream, acc_ctx** out);
 
+/* Enqueue all later work of this context on another HIP stream (NULL = the default stream).
+ * Only between steps (else ACC_ESTATE).  The library does not order the two streams: the caller
+ * makes the new stream wait for what the old one still has in flight.
+ * HIP graphs: accordion_step_all, accordion_step_all_update and accordion_detect_regime only
+ * launch kernels (no allocation, no memset, no synchronisation, per-kernel timing off), so a
+ * caller may capture them on the context's stream and replay the graph.  What the host passes by
+ * value is frozen into the graph: the gradient / output pointers, lr, momentum, weight_decay,
+ * and the step number, which only steers the TopK bin guess (never a result) -- except in
+ * batch-size mode, where it selects the slot of the micro-step count: capture an even number of
+ * micro-steps per graph there.  Everything else a step depends on (levels, ranks, kept counts,
+ * whether PowerSGD's residual is still pending) lives in device memory, so accordion_flush,
+ * accordion_get_state or accordion_detect_regime may run between replays. */
+int32_t accordion_set_stream(acc_ctx* ctx, void* hip_stream);
+
 /* Free the host-side context (the workspace stays the caller's). */
 int32_t accordion_destroy(acc_ctx* ctx);
 
@@ -283,7 +297,7 @@ int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
  * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
  * accordion_stage_name gives the kernel's name (NULL if out of range). */
-#define ACC_N_STAGES 28
+#define ACC_N_STAGES 29
 int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
 int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
 const char* accordion_stage_name(int32_t stage);

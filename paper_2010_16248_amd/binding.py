@@ -52,14 +52,14 @@ _lib = None
 EXPORTS = [
     "accordion_workspace_bytes", "accordion_init", "accordion_destroy", "accordion_last_error",
     "accordion_compress_step", "accordion_aggregate", "accordion_decompress", "accordion_step_all",
-    "accordion_decompress_update", "accordion_step_all_update", "accordion_batch_status", "accordion_topk_overlap", "accordion_payload_format",
+    "accordion_decompress_update", "accordion_step_all_update", "accordion_batch_status", "accordion_set_stream", "accordion_topk_overlap", "accordion_payload_format",
     "accordion_detect_regime", "accordion_reset_accumulator", "accordion_get_levels",
     "accordion_get_norms", "accordion_get_payload", "accordion_get_factors",
     "accordion_payload_words", "accordion_state_bytes", "accordion_get_state", "accordion_set_state",
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
     "accordion_probe_copy", "accordion_topk_stats", "accordion_flush",
 ]
-ACC_N_STAGES = 28
+ACC_N_STAGES = 29
 
 
 def load_library() -> C.CDLL:
@@ -84,6 +84,7 @@ def load_library() -> C.CDLL:
         "accordion_payload_format": [C.POINTER(acc_config), C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                      C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
         "accordion_topk_overlap": [vp, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
+        "accordion_set_stream": [vp, vp],
         "accordion_batch_status": [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                    C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
         "accordion_step_all_update": [vp, C.POINTER(vp), vp, vp, f32, f32, f32],
@@ -253,6 +254,11 @@ class Accordion:
             self.ctx, worker_a, worker_b, common.ctypes.data_as(C.POINTER(C.c_int64)),
             kept.ctypes.data_as(C.POINTER(C.c_int64))))
         return common, kept
+
+    def set_stream(self, cuda_stream: int) -> None:
+        """cuda_stream: the raw stream handle (torch.cuda.Stream.cuda_stream); 0 = default stream."""
+        _check(self._lib, self.ctx, self._lib.accordion_set_stream(self.ctx, C.c_void_p(cuda_stream)))
+        self.stream = cuda_stream
 
     def batch_status(self) -> dict:
         lv, pend, last = C.c_int32(0), C.c_int32(0), C.c_int32(0)

@@ -92,6 +92,7 @@ struct Ws {
   float* Ppart;  int64_t ppart_stride;
   float* Qpart;  int64_t qpart_stride;
   float* vecmean;
+  uint32_t* pending;           // one word: workers whose e still holds Delta (residual not formed yet)
   // TopK
   uint32_t* hist1;             // W x L x kHistBins, zero between steps
   uint32_t* t2;                // W x n_ftiles x 128: per tile, level-2 counts of the two guessed bins

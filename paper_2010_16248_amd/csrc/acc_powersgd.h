@@ -140,8 +140,11 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
   }
 }
 
-// pending: bit w set = worker w's memory holds the previous Delta (see the top of this file)
-__global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradPtrs gp, int w0, uint32_t pending) {
+// *ws.pending: bit w set = worker w's memory holds the previous Delta (see the top of this file).
+// The mask lives on the device (set by the decompress pass, cleared when the residual is written
+// out), so a captured graph of a step stays valid whatever happens between its replays.
+__global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradPtrs gp, int w0) {
+  const uint32_t pending = *ws.pending;
   const int w = w0 + blockIdx.y;
   const float* __restrict__ g = gp.p[w];
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
@@ -535,6 +538,7 @@ __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, f
 template <bool UPD>
 __device__ __forceinline__ void decomp_body(const Ws& ws, const Sink& sink) {
   if (blockIdx.x == 0 && threadIdx.x == 0) {
+    *ws.pending = ws.W == 32 ? 0xffffffffu : ((1u << ws.W) - 1u);   // every e_w now holds Delta_w
     ws.words[1] = ws.words[0];
     ws.words[2] += ws.words[0];
   }
@@ -572,8 +576,10 @@ __global__ __launch_bounds__(256) void psgd_decomp_update_kernel(const Ws ws, co
   decomp_body<true>(ws, sink);
 }
 
-// e_w = Delta_w - D for the workers whose bit is set in `pending`, in place.
-__global__ __launch_bounds__(256) void psgd_residual_kernel(const Ws ws, uint32_t pending) {
+// e_w = Delta_w - D for the workers whose bit is set in *ws.pending, in place; the caller clears
+// the mask with psgd_clear_pending_kernel afterwards.
+__global__ __launch_bounds__(256) void psgd_residual_kernel(const Ws ws) {
+  const uint32_t pending = *ws.pending;
   const int w = blockIdx.y;
   if (((pending >> w) & 1u) == 0u) return;
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
@@ -583,6 +589,10 @@ __global__ __launch_bounds__(256) void psgd_residual_kernel(const Ws ws, uint32_
   const Sink none = {nullptr, nullptr, nullptr, 0.f, 0.f, 0.f};
   if (L.vec4) decomp_tile<1, true>(ws, L, t, e, none, r);
   else decomp_tile<1, false>(ws, L, t, e, none, r);
+}
+
+__global__ void psgd_clear_pending_kernel(const Ws ws) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *ws.pending = 0u;
 }
 
 }  // namespace acc

@@ -45,7 +45,7 @@ struct Plan {
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
   Region r_A, r_e, r_norm_part, r_sq_part, r_bstate;
   int64_t n_model = 0;   // elements that belong to a layer
-  Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean;
+  Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean, r_pending;
   Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval, r_overlap;
   int64_t total_bytes = 0;
 };
@@ -208,6 +208,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     reg(p.r_Ppart, 4 * p.ppart_stride * W);
     reg(p.r_Qpart, 4 * p.qpart_stride * W);
     reg(p.r_vecmean, 4 * p.vec_total);
+    reg(p.r_pending, 4);
   } else if (c->method == ACC_TOPK) {
     reg(p.r_hist1, 4 * (int64_t)kHistBins * nl * W);
     reg(p.r_t2, 4 * (int64_t)kSub2 * ntile * W);
@@ -261,6 +262,7 @@ enum Stage {
   ST_psgd_decomp_update_kernel, ST_topk_compact_update_kernel, ST_topk_sparse_update_kernel,
   ST_batch_micro_kernel, ST_batch_micro_update_kernel, ST_batch_decide_kernel,
   ST_topk_overlap_kernel, ST_zero_u64_kernel, ST_msdr_sq_kernel, ST_msdr_decide_kernel,
+  ST_psgd_clear_pending_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
@@ -272,7 +274,8 @@ static const char* const kStageNames[ST_COUNT] = {
   "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel",
   "psgd_decomp_update_kernel", "topk_compact_update_kernel", "topk_sparse_update_kernel",
   "batch_micro_kernel", "batch_micro_update_kernel", "batch_decide_kernel",
-  "topk_overlap_kernel", "zero_u64_kernel", "msdr_sq_kernel", "msdr_decide_kernel"};
+  "topk_overlap_kernel", "zero_u64_kernel", "msdr_sq_kernel", "msdr_decide_kernel",
+  "psgd_clear_pending_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
 
@@ -292,9 +295,6 @@ struct acc_ctx {
   bool in_step = false;
   uint32_t step_id = 2;            // number of the current step (the device keeps 0 for "never")
   uint32_t p0_mask = 0, p1_mask = 0;
-  // PowerSGD: workers whose error memory still holds the last step's Delta (the residual
-  // Delta - P^ Q~^T is formed by the next step's first pass, or by materialise())
-  uint32_t pending_mask = 0;
   bool agg0 = false, agg1 = false;
   GradPtrs grads;
   char err[256];
@@ -378,7 +378,8 @@ void prof_end(acc_ctx* c, EventPair& p) {
 
 // --- launches of each stage for workers [w0, w0 + nw) ------------------------------------
 
-// TopK selection of workers [w0, w0 + nw): pass A, the per-layer decisions, the per-layer decisions.
+// TopK selection of workers [w0, w0 + nw): the fused error-feedback pass, then the per-layer decisions
+// (level-1/2 bins, re-staging after a missed guess, level-3/4 counts, threshold and prefixes).
 int launch_topk_select(acc_ctx* c, int w0, int nw) {
   const Ws& ws = c->ws;
   ACC_LAUNCH(c, topk_ef_hist_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, c->grads, w0);
@@ -405,8 +406,7 @@ int launch_phase0(acc_ctx* c, int w0, int nw) {
   }
   if (c->cfg.method == ACC_POWERSGD) {
     const int gx = ws.n_mtiles + (w0 == 0 ? ws.n_vectiles : 0);
-    if (gx > 0) ACC_LAUNCH(c, psgd_ef_p_kernel, dim3(gx, nw), dim3(256), ws, c->grads, w0, c->pending_mask);
-    for (int w = w0; w < w0 + nw; ++w) c->pending_mask &= ~(1u << w);
+    if (gx > 0) ACC_LAUNCH(c, psgd_ef_p_kernel, dim3(gx, nw), dim3(256), ws, c->grads, w0);
   } else {
     const int rc = launch_topk_select(c, w0, nw);
     if (rc != ACC_OK) return rc;
@@ -447,7 +447,6 @@ int launch_decompress(acc_ctx* c, const Sink& sink) {
     const dim3 grid(ws.n_mtiles + ws.n_vectiles);
     if (sink.wt) ACC_LAUNCH(c, psgd_decomp_update_kernel, grid, dim3(256), ws, sink);
     else ACC_LAUNCH(c, psgd_decomp_kernel, grid, dim3(256), ws, sink);
-    c->pending_mask = all_workers_mask(c);
   } else {
     if (sink.wt) ACC_LAUNCH(c, topk_sparse_update_kernel, dim3(ws.n_ftiles), dim3(256), ws, sink);
     else ACC_LAUNCH(c, topk_sparse_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, sink);
@@ -486,10 +485,10 @@ int check_sgd(acc_ctx* c, const float* w, const float* v, float lr, float mu, fl
 
 // Make the error memory explicit: e_w = Delta_w - D for the workers whose residual is pending.
 int materialise(acc_ctx* c) {
-  if (c->cfg.method != ACC_POWERSGD || c->pending_mask == 0) return ACC_OK;
+  if (c->cfg.method != ACC_POWERSGD) return ACC_OK;
   const Ws& ws = c->ws;
-  if (ws.n_mtiles > 0) ACC_LAUNCH(c, psgd_residual_kernel, dim3(ws.n_mtiles, ws.W), dim3(256), ws, c->pending_mask);
-  c->pending_mask = 0;
+  if (ws.n_mtiles > 0) ACC_LAUNCH(c, psgd_residual_kernel, dim3(ws.n_mtiles, ws.W), dim3(256), ws);
+  ACC_LAUNCH(c, psgd_clear_pending_kernel, dim3(1), dim3(64), ws);
   return ACC_OK;
 }
 
@@ -577,6 +576,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.Qpart = at<float>(c, p.r_Qpart);
     ws.qpart_stride = p.qpart_stride;
     ws.vecmean = at<float>(c, p.r_vecmean);
+    ws.pending = at<uint32_t>(c, p.r_pending);
   } else if (cfg->method == ACC_TOPK) {
     ws.hist1 = at<uint32_t>(c, p.r_hist1);
     ws.t2 = at<uint32_t>(c, p.r_t2);
@@ -775,6 +775,15 @@ int32_t accordion_step_all_update(acc_ctx* c, const float* const* grads_host_arr
   const int rc = check_sgd(c, weights_dev, velocity_dev, lr, momentum, weight_decay);
   if (rc != ACC_OK) return rc;
   return step_all_into(c, grads_host_array, Sink{nullptr, weights_dev, velocity_dev, lr, momentum, weight_decay});
+}
+
+int32_t accordion_set_stream(acc_ctx* c, void* hip_stream) {
+  if (!c) return ACC_EINVAL;
+  if (c->in_step) return fail(c->err, ACC_ESTATE, "set_stream inside a step");
+  const int rc = drain_profile(c);                           // pending timing events belong to the old stream
+  if (rc != ACC_OK) return rc;
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  return ACC_OK;
 }
 
 int32_t accordion_detect_regime(acc_ctx* c, float lr_curr, float lr_next) {
@@ -1027,7 +1036,8 @@ int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   const int32_t rc = state_copy(c, const_cast<char*>(static_cast<const char*>(state_host)), false);
   if (rc != ACC_OK) return rc;
-  c->pending_mask = 0;                                       // the memory just written is explicit
+  if (c->cfg.method == ACC_POWERSGD)                         // the memory just written is explicit
+    ACC_LAUNCH(c, psgd_clear_pending_kernel, dim3(1), dim3(64), c->ws);
   if (c->plan.r_sq_part.bytes > 0)                           // the MSDR window restarts with the import
     ACC_HIP(c, hipMemset(c->ws.sq_part, 0, (size_t)c->plan.r_sq_part.bytes));
   ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)c->cfg.method);
