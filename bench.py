@@ -62,6 +62,9 @@ def parse():
     ap.add_argument("--fused-update", action="store_true",
                     help="end every step with the fused Nesterov-momentum update of weights and velocity "
                          "(accordion_step_all_update) instead of storing the averaged gradient")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture one step per pool batch in a HIP graph (torch.cuda.CUDAGraph) and replay "
+                         "it; per-kernel events are off then")
     ap.add_argument("--fixed-level", type=int, default=-1, help="0/1: never switch, use this level")
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB read and MiB written per launch); 0: skip")
@@ -213,10 +216,18 @@ def main():
         del src, dst
 
     state = {"step": 0}
+    graphs = None
+    if args.hip_graph:
+        args.kernel_events = "none"
+        if is_batch and args.pool % 2:
+            print("bench.py: --hip-graph in batch-size mode needs an even --pool", file=sys.stderr)
+            sys.exit(2)
 
     def one_step():
         s = state["step"]
-        if args.fused_update:
+        if graphs is not None:
+            graphs[s % args.pool].replay()
+        elif args.fused_update:
             gpu.step_all_update(base[s % args.pool], weights, velocity, LR_CURR, 0.9, 0.0)
         else:
             gpu.step_all(base[s % args.pool], out)
@@ -230,6 +241,22 @@ def main():
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
+    if args.hip_graph:
+        # steady state reached: capture one step per pool batch on a side stream
+        side = torch.cuda.Stream()
+        gpu.set_stream(side.cuda_stream)
+        captured = []
+        for b in range(args.pool):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                if args.fused_update:
+                    gpu.step_all_update(base[b], weights, velocity, LR_CURR, 0.9, 0.0)
+                else:
+                    gpu.step_all(base[b], out)
+            captured.append(g)
+        graphs = captured
+        torch.cuda.synchronize()
+        gpu.set_stream(torch.cuda.current_stream().cuda_stream)   # replays and eager calls share a stream
     state["step"] = 0                      # timed region starts at a window boundary
     use_events = args.kernel_events != "none"
     if use_events:
@@ -292,7 +319,7 @@ def main():
                    "batch_multiplier": w.batch_multiplier,
                    "level_crit": w.level_crit, "level_noncrit": w.level_noncrit,
                    "window_steps": args.window, "pool_batches": args.pool,
-                   "levels_switch": args.fixed_level < 0,
+                   "levels_switch": args.fixed_level < 0, "hip_graph": bool(args.hip_graph),
                    "sink": "nesterov update of weights and velocity" if args.fused_update else "averaged gradient stored", "kernel_events_in_timed_region": args.kernel_events},
         "roofline": roofline,
         "cpu_baseline": cpu,
