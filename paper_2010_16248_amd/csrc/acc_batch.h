@@ -17,6 +17,12 @@
 namespace acc {
 
 constexpr int kBatchWorkers = 4;   // workers whose loads are in flight together
+// The gradients stream in (read once), so that the running sums, the accumulator and, in the
+// small-batch regime, the averaged gradient stay in the caches from one micro-step to the next:
+// 118 -> 95 us per micro-step on ResNet-18 shapes, W = 4.  Streaming the rest as well brings
+// nothing in the large-batch regime and costs 3 us in the small-batch one.
+constexpr bool kBatchStreamG = true;
+constexpr bool kBatchStream = false;
 
 // Slot layout (uint32 x 4): [0] micro-steps summed before this micro-step, [1] micro-steps of the
 // batch the previous micro-step completed (0: none), [2], [3] spare.
@@ -35,11 +41,11 @@ __device__ __forceinline__ void batch_tile(const Ws& ws, const GradPtrs& gp, con
   const float lr_eff = sink.lr * (float)(j + 1u);
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int q = threadIdx.x; q < tg.nquads; q += kFlatThreads) {
-    float4 a = ldq<AL>(A, tg.a0, tg.lo, tg.hi, q, true);
+    float4 a = ldq<AL, kBatchStream>(A, tg.a0, tg.lo, tg.hi, q, true);
     float4 wq = zero4, vq = zero4;
     if (UPD && exch) {
-      wq = ldq<AL>(sink.wt, tg.a0, tg.lo, tg.hi, q, true);
-      vq = ldq<AL>(sink.vel, tg.a0, tg.lo, tg.hi, q, true);
+      wq = ldq<AL, kBatchStream>(sink.wt, tg.a0, tg.lo, tg.hi, q, true);
+      vq = ldq<AL, kBatchStream>(sink.vel, tg.a0, tg.lo, tg.hi, q, true);
     }
     float4 acc = zero4;
     for (int wb = 0; wb < W; wb += kBatchWorkers) {
@@ -47,7 +53,7 @@ __device__ __forceinline__ void batch_tile(const Ws& ws, const GradPtrs& gp, con
 #pragma unroll
       for (int u = 0; u < kBatchWorkers; ++u) {
         const int w = min(wb + u, W - 1);                  // clamped: the loads go out unconditionally
-        g[u] = ldq<AL>(gp.p[w], tg.a0, tg.lo, tg.hi, q, true);
+        g[u] = ldq<AL, kBatchStreamG>(gp.p[w], tg.a0, tg.lo, tg.hi, q, true);
         s[u] = (j > 0u) ? ldq<AL>(S + (int64_t)w * e_stride, tg.a0, tg.lo, tg.hi, q, true) : zero4;
       }
 #pragma unroll
@@ -65,7 +71,7 @@ __device__ __forceinline__ void batch_tile(const Ws& ws, const GradPtrs& gp, con
         }
       }
     }
-    stq<AL>(A, tg.a0, tg.lo, tg.hi, q, a);
+    stq<AL, kBatchStream>(A, tg.a0, tg.lo, tg.hi, q, a);
     if (exch) {
       const float4 d = make_float4(acc.x / denom, acc.y / denom, acc.z / denom, acc.w / denom);
       if (UPD) {
@@ -73,10 +79,10 @@ __device__ __forceinline__ void batch_tile(const Ws& ws, const GradPtrs& gp, con
         nesterov(d.y, wq.y, vq.y, lr_eff, sink.mu, sink.wd);
         nesterov(d.z, wq.z, vq.z, lr_eff, sink.mu, sink.wd);
         nesterov(d.w, wq.w, vq.w, lr_eff, sink.mu, sink.wd);
-        stq<AL>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
-        stq<AL>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
+        stq<AL, kBatchStream>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
+        stq<AL, kBatchStream>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
       } else {
-        stq<AL>(sink.out, tg.a0, tg.lo, tg.hi, q, d);
+        stq<AL, kBatchStream>(sink.out, tg.a0, tg.lo, tg.hi, q, d);
       }
     }
   }

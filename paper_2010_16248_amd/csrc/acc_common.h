@@ -215,21 +215,41 @@ __device__ __forceinline__ void st_quad(float* __restrict__ p, int64_t base, int
   if (base + 3 >= lo && base + 3 < hi) p[base + 3] = v.w;
 }
 
+// Streaming ("non-temporal") 16-byte access: for data that this step reads or writes once and no
+// later kernel of the step touches (the gradients coming in, the averaged gradient and the payload
+// going out), so that it does not push the error memory out of the caches or sit there dirty
+// until the kernel ends.
+typedef float f4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld16_stream(const float* p) {
+  const f4v v = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st16_stream(float* p, const float4& v) {
+  f4v t;
+  t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+  __builtin_nontemporal_store(t, reinterpret_cast<f4v*>(p));
+}
+
 // Access to 16-byte group q of a tile.  AL (a workgroup-uniform property of the tile): the tile
 // starts on a 16-byte boundary and holds a whole number of groups, so no element needs a mask.
-template <bool AL>
+// STREAM: non-temporal access on the mask-free path (the masked path is rare and stays plain).
+template <bool AL, bool STREAM = false>
 __device__ __forceinline__ float4 ldq(const float* __restrict__ p, int64_t a0, int64_t lo, int64_t hi,
                                       int q, bool in) {
   if (!in) return make_float4(0.f, 0.f, 0.f, 0.f);
-  if (AL) return *reinterpret_cast<const float4*>(p + a0 + 4 * (int64_t)q);
+  if (AL) return STREAM ? ld16_stream(p + a0 + 4 * (int64_t)q) : *reinterpret_cast<const float4*>(p + a0 + 4 * (int64_t)q);
   return ld_quad(p, a0 + 4 * (int64_t)q, lo, hi);
 }
 
-template <bool AL>
+template <bool AL, bool STREAM = false>
 __device__ __forceinline__ void stq(float* __restrict__ p, int64_t a0, int64_t lo, int64_t hi, int q,
                                     float4 v) {
-  if (AL) *reinterpret_cast<float4*>(p + a0 + 4 * (int64_t)q) = v;
-  else st_quad(p, a0 + 4 * (int64_t)q, lo, hi, v);
+  if (AL) {
+    if (STREAM) st16_stream(p + a0 + 4 * (int64_t)q, v);
+    else *reinterpret_cast<float4*>(p + a0 + 4 * (int64_t)q) = v;
+  } else {
+    st_quad(p, a0 + 4 * (int64_t)q, lo, hi, v);
+  }
 }
 
 // ---- where the averaged decompressed gradient goes -------------------------------------------

@@ -26,12 +26,20 @@ __device__ __forceinline__ void lane_cols(int col0, int lane, int cols, int (&co
   }
 }
 
-template <bool V4>
+// Streaming access for what a step touches once, so that Delta stays in the caches between the
+// passes (first pass 119 -> 110 us on ResNet-18 shapes, W = 4).
+constexpr bool kPsgdStreamG = true;     // gradients: read once per step
+constexpr bool kPsgdStreamA = true;     // accumulator: read and written once per step
+constexpr bool kPsgdStreamOut = true;   // averaged gradient: written once, read by nobody here
+
+// STREAM: streaming (non-temporal) access on the 16-byte path, for data touched once per step.
+template <bool V4, bool STREAM = false>
 __device__ __forceinline__ void load_row(const float* __restrict__ p, int64_t rowbase,
                                          const int (&col)[4], const bool (&cm)[4], float (&d)[4]) {
   if (V4) {
     if (cm[0]) {
-      const float4 t = *reinterpret_cast<const float4*>(p + rowbase + col[0]);
+      const float4 t = STREAM ? ld16_stream(p + rowbase + col[0])
+                              : *reinterpret_cast<const float4*>(p + rowbase + col[0]);
       d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w;
     } else {
       d[0] = d[1] = d[2] = d[3] = 0.f;
@@ -42,12 +50,15 @@ __device__ __forceinline__ void load_row(const float* __restrict__ p, int64_t ro
   }
 }
 
-template <bool V4>
+template <bool V4, bool STREAM = false>
 __device__ __forceinline__ void store_row(float* __restrict__ p, int64_t rowbase,
                                           const int (&col)[4], const bool (&cm)[4],
                                           const float (&d)[4]) {
   if (V4) {
-    if (cm[0]) *reinterpret_cast<float4*>(p + rowbase + col[0]) = make_float4(d[0], d[1], d[2], d[3]);
+    if (cm[0]) {
+      if (STREAM) st16_stream(p + rowbase + col[0], make_float4(d[0], d[1], d[2], d[3]));
+      else *reinterpret_cast<float4*>(p + rowbase + col[0]) = make_float4(d[0], d[1], d[2], d[3]);
+    }
   } else {
 #pragma unroll
     for (int v = 0; v < 4; ++v)
@@ -95,9 +106,9 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
       const int i = i0 + 4 * b;
       if (i < row_end) {
         const int64_t rb = L.offset + (int64_t)i * L.cols;
-        load_row<V4>(g, rb, col, cm, gd[b]);
+        load_row<V4, kPsgdStreamG>(g, rb, col, cm, gd[b]);
         load_row<V4>(e, rb, col, cm, ed[b]);
-        if (A) load_row<V4>(A, rb, col, cm, ad[b]);
+        if (A) load_row<V4, kPsgdStreamA>(A, rb, col, cm, ad[b]);
       }
     }
 #pragma unroll
@@ -119,7 +130,7 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
         if (A) {
 #pragma unroll
           for (int v = 0; v < 4; ++v) ad[b][v] += gd[b][v];
-          store_row<V4>(A, rb, col, cm, ad[b]);
+          store_row<V4, kPsgdStreamA>(A, rb, col, cm, ad[b]);
         }
         float acc[R];
 #pragma unroll
@@ -499,8 +510,8 @@ __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, f
         const int i = i0 + 4 * b;
         if (i < row_end) {
           const int64_t rb = L.offset + (int64_t)i * L.cols;
-          load_row<V4>(UPD ? sink.wt : e, rb, col, cm, d[b]);
-          if (UPD) load_row<V4>(sink.vel, rb, col, cm, vv[UPD ? b : 0]);
+          load_row<V4, UPD>(UPD ? sink.wt : e, rb, col, cm, d[b]);   // weights, velocity: once per step
+          if (UPD) load_row<V4, true>(sink.vel, rb, col, cm, vv[UPD ? b : 0]);
         }
       }
     }
@@ -523,10 +534,10 @@ __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, f
         } else if (UPD) {
 #pragma unroll
           for (int v = 0; v < 4; ++v) nesterov(D[v], d[b][v], vv[UPD ? b : 0][v], sink.lr, sink.mu, sink.wd);
-          store_row<V4>(sink.wt, rb, col, cm, d[b]);
-          store_row<V4>(sink.vel, rb, col, cm, vv[UPD ? b : 0]);
+          store_row<V4, true>(sink.wt, rb, col, cm, d[b]);
+          store_row<V4, true>(sink.vel, rb, col, cm, vv[UPD ? b : 0]);
         } else {
-          store_row<V4>(sink.out, rb, col, cm, D);
+          store_row<V4, kPsgdStreamOut>(sink.out, rb, col, cm, D);
         }
       }
     }

@@ -104,10 +104,19 @@ __device__ __forceinline__ WaveSpan wave_span(const TileGeom& tg, int wave) {
   return s;
 }
 
-template <bool AL>
+// What is accessed with streaming loads / stores (measured on ResNet-18 shapes, W = 4: the fused
+// error-feedback pass drops from 123 to 103 us when the gradients stream in, because the error
+// memory then stays in the caches for the compaction).
+constexpr bool kStreamG = true;      // gradients: read once per step
+constexpr bool kStreamA = true;      // accumulator: read and written once per step
+constexpr bool kStreamOut = true;    // averaged gradient: written once, read by nobody here
+// Delta stays plain: streaming its store in the first pass changes nothing, and streaming its load
+// in the compaction (which then writes the same lines) costs 30 us.
+
+template <bool AL, bool STREAM = false>
 __device__ __forceinline__ float4 ld_span(const float* __restrict__ p, const TileGeom& tg,
                                           const WaveSpan& sp, int q) {
-  return ldq<AL>(p, tg.a0, tg.lo, tg.hi, q, q < sp.qend);
+  return ldq<AL, STREAM>(p, tg.a0, tg.lo, tg.hi, q, q < sp.qend);
 }
 
 // Is element c of group q (which lies in the wave's span iff in_span) an element of the tile?
@@ -217,9 +226,9 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int q = span.qbeg + u * kWave + lane;
-    gc[u] = ld_span<AL>(g, tg, span, q);
+    gc[u] = ld_span<AL, kStreamG>(g, tg, span, q);
     ec[u] = ld_span<AL>(e, tg, span, q);
-    ac[u] = A ? ld_span<AL>(A, tg, span, q) : zero4;
+    ac[u] = A ? ld_span<AL, kStreamA>(A, tg, span, q) : zero4;
   }
   if (SELECT) {
     for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0;
@@ -232,9 +241,9 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int q = q0 + (U + u) * kWave + lane;
-      gn[u] = ld_span<AL>(g, tg, span, q);
+      gn[u] = ld_span<AL, kStreamG>(g, tg, span, q);
       en[u] = ld_span<AL>(e, tg, span, q);
-      an[u] = A ? ld_span<AL>(A, tg, span, q) : zero4;
+      an[u] = A ? ld_span<AL, kStreamA>(A, tg, span, q) : zero4;
     }
     const bool full = q0 + U * kWave <= span.qend;          // wave-uniform
 #pragma unroll
@@ -246,7 +255,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
         stq<AL>(e, tg.a0, tg.lo, tg.hi, q, d);
         if (A) {
           const float4 a = make_float4(ac[u].x + gc[u].x, ac[u].y + gc[u].y, ac[u].z + gc[u].z, ac[u].w + gc[u].w);
-          stq<AL>(A, tg.a0, tg.lo, tg.hi, q, a);
+          stq<AL, kStreamA>(A, tg.a0, tg.lo, tg.hi, q, a);
         }
       }
       if (SELECT) {
@@ -872,18 +881,23 @@ __device__ __forceinline__ QuarterSel load_quarter_sel(const Ws& ws, int w, int 
   return s;
 }
 
+constexpr int kGroupList = 4 * kWave;   // payload entries one group of a wave can produce
+
 // Running state of the ordered compaction of one worker's quarter.
 struct CompactRun { uint32_t eq_run, pos_run; };
 
 // One group of four elements per lane: which are selected, their payload entries, the zeros in e;
-// MEAN adds the kept values to acc.  An element is selected iff its key >= tsel, where tsel is
+// MEAN adds the kept values to acc.  The payload entries of the group are first put in order into
+// a list in LDS that belongs to the wave (stg, 256 entries), then written out by consecutive lanes
+// to consecutive addresses: stores of single words scattered over the lanes of four instructions
+// cost a quarter of this kernel's time.  An element is selected iff its key >= tsel, where tsel is
 // T for the entries equal to T that are within the tie quota (lowest indices first) and T + 1
 // otherwise; quarters without an entry equal to T never look at ties.
 template <bool AL, bool MEAN>
 __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan& span, int64_t layer_offset,
                                               const QuarterSel& qs, CompactRun& run, float* __restrict__ e,
                                               int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
-                                              const float4& cur, int lane, float4& acc) {
+                                              const float4& cur, int lane, float4& acc, uint2* stg) {
   const bool qa = q < span.qend;
   const uint64_t m_span = ballot64(qa);
   const uint32_t T = qs.T;
@@ -930,7 +944,7 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
   }
   const bool holes = qs.holes != 0u;                        // wave-uniform
   if (total != 0 || holes) {
-    uint32_t pos = run.pos_run + below;
+    uint32_t local = below;                                 // place in the group's list
     const int32_t i0 = (int32_t)(tg.a0 + 4 * (int64_t)q - layer_offset);
     float4 z = cur;
     bool sel[4];
@@ -938,17 +952,26 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
     for (int c = 0; c < 4; ++c) {
       sel[c] = valid[c] && key[c] >= tsel[c];
       if (sel[c]) {
-        if (pos < qs.k) {                                   // always true for consistent state
-          if (!holes) pidx[pos] = i0 + c;
-          pval[pos] = comp(cur, c);
-        }
-        ++pos;
+        stg[local] = make_uint2((uint32_t)(i0 + c), __float_as_uint(comp(cur, c)));
+        ++local;
       } else if (holes && valid[c]) {
         // dropped entry number (index - kept before it) of the layer
-        const uint32_t hp = (uint32_t)(i0 + c) - pos;
+        const uint32_t hp = (uint32_t)(i0 + c) - (run.pos_run + local);
         if (hp < qs.nholes) pidx[hp] = i0 + c;              // always true for consistent state
       }
     }
+    __builtin_amdgcn_wave_barrier();                        // the list is complete (LDS is in order per wave)
+#pragma unroll 1
+    for (uint32_t t = lane; t < total; t += kWave) {        // total <= 256: at most four rounds
+      const uint2 pr = stg[t];
+      const uint32_t pos = run.pos_run + t;
+      if (pos < qs.k) {                                     // always true for consistent state
+        // streaming stores: nothing in this step reads the payload again
+        if (!holes) __builtin_nontemporal_store((int32_t)pr.x, &pidx[pos]);
+        __builtin_nontemporal_store(__uint_as_float(pr.y), &pval[pos]);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
     if (sel[0]) z.x = 0.f;
     if (sel[1]) z.y = 0.f;
     if (sel[2]) z.z = 0.f;
@@ -967,7 +990,7 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
 // One worker per grid row; the mean is taken later from the payloads.
 template <bool AL>
 __device__ __forceinline__ void compact_tile(const Ws& ws, int w, const FlatTile& ft, const LayerDev& L,
-                                             const TileGeom& tg) {
+                                             const TileGeom& tg, uint2* stg) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const WaveSpan span = wave_span(tg, wave);
@@ -985,7 +1008,7 @@ __device__ __forceinline__ void compact_tile(const Ws& ws, int w, const FlatTile
   for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
     const int q = q0 + lane;
     const float4 nn = ld_span<AL>(e, tg, span, q + 2 * kWave);
-    compact_group<AL, false>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, unused);
+    compact_group<AL, false>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, unused, stg);
     cur = nxt;
     nxt = nn;
   }
@@ -997,8 +1020,10 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
   if (blockIdx.x == 0 && threadIdx.x == 0) ws.miss_any[w] = 0u;
-  if (tg.aligned) compact_tile<true>(ws, w, ft, L, tg);
-  else compact_tile<false>(ws, w, ft, L, tg);
+  __shared__ uint2 stage[4][kGroupList];
+  uint2* stg = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+  if (tg.aligned) compact_tile<true>(ws, w, ft, L, tg, stg);
+  else compact_tile<false>(ws, w, ft, L, tg, stg);
 }
 
 // All workers in worker order, and the dense mean of the kept values: out[i] = (sum over the
@@ -1012,7 +1037,7 @@ constexpr int kMeanBatch = 4;
 // (read at the top of a group, so that they arrive while the workers are compacted).
 template <bool AL, bool UPD>
 __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& ft, const LayerDev& L,
-                                                  const TileGeom& tg, const Sink sink) {
+                                                  const TileGeom& tg, const Sink sink, uint2* stg) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const WaveSpan span = wave_span(tg, wave);
@@ -1047,8 +1072,8 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
     float4 acc = zero4;
     float4 wq = zero4, vq = zero4;
     if (UPD) {
-      wq = ld_span<AL>(sink.wt, tg, span, q);
-      vq = ld_span<AL>(sink.vel, tg, span, q);
+      wq = ld_span<AL, true>(sink.wt, tg, span, q);        // weights and velocity: once per step
+      vq = ld_span<AL, true>(sink.vel, tg, span, q);
     }
     for (int wb = 0; wb < W; wb += kMeanBatch) {
       int j2 = j, wb2 = wb + kMeanBatch;
@@ -1074,7 +1099,7 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
           float* __restrict__ e = e_base + (int64_t)w * e_stride;
           int32_t* pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
           float* pval = pay_val + (int64_t)w * pay_stride + pay_off;
-          compact_group<AL, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur[u], lane, acc);
+          compact_group<AL, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur[u], lane, acc, stg);
           if (lane == w) { eq_run_v = run.eq_run; pos_run_v = run.pos_run; }
         }
       }
@@ -1085,10 +1110,10 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
       const float4 v = make_float4(acc.x / fw, acc.y / fw, acc.z / fw, acc.w / fw);
       if (UPD) {
         nesterov4(v, wq, vq, sink);
-        stq<AL>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
-        stq<AL>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
+        stq<AL, true>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
+        stq<AL, true>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
       } else {
-        stq<AL>(sink.out, tg.a0, tg.lo, tg.hi, q, v);
+        stq<AL, kStreamOut>(sink.out, tg.a0, tg.lo, tg.hi, q, v);
       }
     }
   }
@@ -1104,8 +1129,10 @@ __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink
     ws.words[2] += ws.words[0];
   }
   if (blockIdx.x == 0 && threadIdx.x < ws.W) ws.miss_any[threadIdx.x] = 0u;
-  if (tg.aligned) compact_mean_tile<true, UPD>(ws, ft, L, tg, sink);
-  else compact_mean_tile<false, UPD>(ws, ft, L, tg, sink);
+  __shared__ uint2 stage[4][kGroupList];
+  uint2* stg = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+  if (tg.aligned) compact_mean_tile<true, UPD>(ws, ft, L, tg, sink, stg);
+  else compact_mean_tile<false, UPD>(ws, ft, L, tg, sink, stg);
 }
 
 __global__ __launch_bounds__(256) void topk_compact_mean_kernel(const Ws ws, const Sink sink) {
