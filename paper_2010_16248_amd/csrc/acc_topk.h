@@ -35,6 +35,10 @@
 namespace acc {
 
 constexpr uint32_t kNoGuess = 0xffffffffu;
+// Guess "the threshold lies in bin 0" (exact zeros and the smallest denormals: sparse gradients of
+// which more is kept than is non-zero).  The first pass then stages bin 0 the way the re-staging
+// pass does: non-zero keys listed, exact zeros counted.
+constexpr uint32_t kGuessZero = 0xfffffffeu;
 constexpr int kPickThreads = 1024;
 constexpr int kPickWaves = kPickThreads / kWave;
 static_assert(kHistBins == 2 * kPickThreads, "the pick kernels load two histogram bins per thread");
@@ -201,11 +205,11 @@ __device__ __forceinline__ uint32_t stage_flush(const Ws& ws, int64_t qslot, con
 // ---- A ----------------------------------------------------------------------------------------
 
 // SELECT = false (layers of a single tile, which the pick kernel decides from Delta itself):
-// only the error-feedback add and the accumulation.
-template <bool AL, bool SELECT>
+// only the error-feedback add and the accumulation.  ZB: the guess is kGuessZero.
+template <bool AL, bool SELECT, bool ZB>
 __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, int w, int tile_id,
                                              const FlatTile& ft, const LayerDev& L, const TileGeom& tg,
-                                             uint32_t* hist, uint32_t* st, uint32_t* sub2) {
+                                             uint32_t* hist, uint32_t* st, uint32_t* sub2, uint32_t guess) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -215,10 +219,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   float* __restrict__ A = (w == 0) ? ws.A : nullptr;
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   uint32_t glo = 0x7ffffff0u;                              // no bin matches without a guess
-  if (SELECT) {
-    const uint32_t guess = ws.guess[wl * 2 + ws.level[ft.layer]];
-    if (guess != kNoGuess) glo = max(guess, 1u);
-  }
+  if (SELECT && !ZB && guess != kNoGuess) glo = max(guess, 1u);
   // two groups per lane are requested before the histograms are cleared
   constexpr int U = 2;
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -265,7 +266,8 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
           for (int c = 0; c < 4; ++c) {
             const uint32_t key = key_of(comp(d, c));
             hist_add(hist, (key >> 20) != 0u, key >> 20);
-            stage_two_bins(st, sub2, cnt, ~0ull, true, key, glo, lane);
+            if (ZB) stage_one_bin(st, sub2, cnt, ~0ull, true, key, 0u, lane);
+            else stage_two_bins(st, sub2, cnt, ~0ull, true, key, glo, lane);
           }
         } else {
           const uint64_t m_span = ballot64(qa);
@@ -275,7 +277,8 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
             const uint64_t mv = valid_mask<AL>(tg, q, c, qa, m_span);
             const uint32_t key = key_of(comp(d, c));
             hist_add(hist, valid && (key >> 20) != 0u, key >> 20);
-            stage_two_bins(st, sub2, cnt, mv, valid, key, glo, lane);
+            if (ZB) stage_one_bin(st, sub2, cnt, mv, valid, key, 0u, lane);
+            else stage_two_bins(st, sub2, cnt, mv, valid, key, glo, lane);
           }
         }
       }
@@ -305,11 +308,17 @@ __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const Gr
   const TileGeom tg = tile_geom(L, ft);
   uint32_t* st = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
   if (L.ntiles == 1) {
-    if (tg.aligned) ef_hist_tile<true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2);
-    else ef_hist_tile<false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2);
+    if (tg.aligned) ef_hist_tile<true, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, kNoGuess);
+    else ef_hist_tile<false, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, kNoGuess);
   } else {
-    if (tg.aligned) ef_hist_tile<true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2);
-    else ef_hist_tile<false, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2);
+    const uint32_t guess = ws.guess[((int64_t)w * ws.L + ft.layer) * 2 + ws.level[ft.layer]];
+    if (guess == kGuessZero) {                               // uniform over the workgroup
+      if (tg.aligned) ef_hist_tile<true, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, guess);
+      else ef_hist_tile<false, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, guess);
+    } else {
+      if (tg.aligned) ef_hist_tile<true, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, guess);
+      else ef_hist_tile<false, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, guess);
+    }
   }
 }
 
@@ -559,13 +568,26 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   pick_bin(hist, k, out, scratch);
   const uint32_t b1 = out[0], need2 = k - out[1];
   const uint32_t glo = max(guess, 1u);                     // the bins pass A staged: glo, glo + 1
-  const bool hit = guess != kNoGuess && b1 != 0u && (b1 == glo || b1 == glo + 1u);
+  const bool hit = guess != kNoGuess && guess != kGuessZero && b1 != 0u && (b1 == glo || b1 == glo + 1u);
+  // bin 0 guessed and found: pass A left what the re-staging pass would (mode 2: staged already)
+  const bool zhit = guess == kGuessZero && b1 == 0u;
   const uint32_t side = hit ? b1 - glo : 0u;
   if (tid == 0) {
     sp->b1 = b1; sp->need2 = need2; sp->k = k; sp->side = side; sp->zeros = 0u;
-    sp->mode = hit ? 0u : 1u;
-    if (!hit) ws.miss_any[w] = 1u;                         // cleared by the compaction kernel
-    if (!hit) atomicAdd(&ws.stats[0], 1ull);               // layers re-staged (diagnostic counter)
+    sp->mode = hit ? 0u : (zhit ? 2u : 1u);
+    if (!hit && !zhit) ws.miss_any[w] = 1u;                // cleared by the compaction kernel
+    if (!hit && !zhit) atomicAdd(&ws.stats[0], 1ull);      // layers re-staged (diagnostic counter)
+  }
+  if (zhit) {
+    // level-2 counts of the non-zero keys of bin 0 (summed over the tiles above); the rest of
+    // bin 0 are exact zeros
+    if (tid < kL2Bins) ws.hist2m[wl * kL2Bins + tid] = sub[tid];
+    if (tid == 0) {
+      uint32_t nnz0 = 0;
+      for (int b = 0; b < kL2Bins; ++b) nnz0 += sub[b];
+      sp->zeros = hist[0] - min(nnz0, hist[0]);
+    }
+    return;
   }
   if (!hit) {
     // its keys get staged tile by tile, with their level-2 counts added up here
@@ -847,7 +869,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
     else if (v < 0) g = (int)b1 + v;
     else if (b2 < (uint32_t)(kL2Bins / 2)) g = (int)b1 - 1;
     uint32_t glo = (uint32_t)max(0, min(kHistBins - 2, g));
-    ws.guess[wl * 2 + lv] = glo;
+    ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero : glo;
   }
 }
 

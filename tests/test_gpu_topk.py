@@ -115,6 +115,38 @@ def test_guessed_bins_hit_drift_and_miss():
     gpu.destroy()
 
 
+def test_threshold_among_exact_zeros_is_guessed_too():
+    """Sparse gradients of which more is kept than is non-zero (the embedding of a language
+    model): the threshold is zero.  After the first step the error-feedback pass stages bin 0
+    itself (non-zero keys listed, zeros counted), so nothing is re-staged; a dense step in
+    between is a miss and everything stays exact."""
+    print("case zero-bin guess", flush=True)
+    shapes = [(1, 5 * 8192 + 13, 0), (64, 577, 1)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 2
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    rng = np.random.default_rng(15)
+    restaged = []
+    for step in range(7):
+        dense = step == 4
+        grads = []
+        for _ in range(W):
+            g = rng.standard_normal(N)
+            if not dense:
+                g *= rng.random(N) < 0.03                   # 3 % non-zero, 10 % kept
+            grads.append(g.astype(np.float32))
+        _check_step(gpu, ora, grads, f"step {step}")
+        restaged.append(gpu.topk_stats()[0])
+    per_step = np.diff([0] + restaged)
+    n_multi = 2 * W
+    assert per_step[0] == n_multi                           # nothing to guess from
+    assert per_step[1:4].sum() == 0, per_step               # bin 0 guessed and found
+    assert per_step[4] == n_multi, per_step                 # the dense step misses
+    assert per_step[6] == 0, per_step
+    gpu.destroy()
+
+
 def test_large_tie_classes_take_the_sweeps_and_stay_exact():
     """Quantised values in layers of several tiles: the tie class of the threshold is far larger
     than the per-quarter key lists, for several steps in a row (guess hit and missed)."""
