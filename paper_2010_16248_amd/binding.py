@@ -70,6 +70,10 @@ def load_library() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with "
                            "`python -m paper_2010_16248_amd.build` (there is no fallback path)")
+    # The caller's device memory and streams come from PyTorch, which ships its own HIP runtime:
+    # that runtime has to be the one already in the process when the library is loaded, or the
+    # library binds to a second copy that sees no device.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
     sig = {
