@@ -386,7 +386,7 @@ __device__ void q_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const 
     for (int k = 0; k < R; ++k) acc[v][k] = 0.f;
   const int row_end = min(t.row0 + kMatRows, L.rows);
   const float* __restrict__ ph = ws.Phat + L.p_off;
-  constexpr int B = 4;
+  constexpr int B = 4;   // rows in flight per wave (8 is no faster, 16 is slower)
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float d[B][4];
 #pragma unroll
