@@ -98,7 +98,7 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
   const int row_end = min(t.row0 + kMatRows, L.rows);
   const int chunk = t.col0 / kMatCols;
   const float* __restrict__ ph = ws.Phat + L.p_off;
-  constexpr int B = 2;   // rows in flight per wave (more rows cost registers and occupancy)
+  constexpr int B = 2;   // rows in flight per wave (one row is as fast; more rows cost registers and occupancy)
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float gd[B][4], ed[B][4], ad[B][4];
 #pragma unroll
