@@ -115,3 +115,61 @@ def test_lstm_topk_two_workers_dense_tie_class():
     _set_levels(gpu, ora, 0)
     _check_step(gpu, ora, [wl.gradient(w, k, 1) for k in range(W)], "K1 step 1")
     gpu.destroy()
+
+
+def test_lstm_topk_sixteen_workers_by_properties():
+    """The LSTM set in the configuration bench.py times (W = 16, K = 10 %), where the oracle
+    would take minutes: one step from an empty memory is checked through properties that pin
+    the result completely.  Per worker and layer: k entries are kept; kept values + residual
+    give back the gradient bit for bit (compressed + residual = gradient + old residual); no
+    dropped entry is larger in magnitude than a kept one, and among the entries equal to the
+    smallest kept magnitude the kept ones have the lowest indices; the averaged output is the
+    fp32 sum of the kept values in worker order divided by W."""
+    import torch
+    print("case lstm_topk W=16 properties", flush=True)
+    w = wl.workload("lstm_topk")
+    W = w.n_workers
+    assert W == 16
+    lt = H.layer_tuples(w.layers)
+    gpu = B.Accordion(B.ACC_TOPK, lt, W, w.level_crit, w.level_noncrit, w.k_den)
+    N = gpu.n_params
+    grads = [H.to_dev(wl.gradient(w, k, 0)) for k in range(W)]
+    out = H.dev_out(N)
+    gpu.step_all(grads, out)
+    torch.cuda.synchronize()
+    acc = torch.zeros(N, dtype=torch.float32, device="cuda:0")
+    e_all = torch.from_numpy(gpu.unpack_state(gpu.get_state())["e"])   # host, W x N
+    for k in range(W):
+        e_w = e_all[k].to("cuda:0")
+        recon = e_w.clone()
+        dense = torch.zeros(N, dtype=torch.float32, device="cuda:0")
+        for li, (off, rows, cols, _) in enumerate(lt):
+            n = rows * cols
+            kk = max(1, -((-n * w.level_crit) // w.k_den))
+            idx, val = gpu.get_payload(k, li)
+            assert idx.size == kk and np.all(np.diff(idx) > 0) and idx[0] >= 0 and idx[-1] < n
+            ti = torch.from_numpy(idx.astype(np.int64)).to("cuda:0") + off
+            tv = torch.from_numpy(val).to("cuda:0")
+            assert bool(torch.all(e_w[ti] == 0))                 # kept entries left the memory
+            recon[ti] = tv
+            dense[ti] = tv
+            layer_e = e_w[off:off + n].abs()
+            t_min = tv.abs().min()
+            assert bool(layer_e.max() <= t_min), (k, li)
+            # ties at the smallest kept magnitude: lower index wins
+            kept_tie = ti[tv.abs() == t_min]
+            drop_tie = torch.nonzero(layer_e == t_min).flatten() + off
+            if t_min > 0 and drop_tie.numel():
+                assert int(kept_tie.max()) < int(drop_tie.min()), (k, li)
+            if t_min == 0:                                       # zeros: every non-zero is kept, then index order
+                assert int(torch.count_nonzero(layer_e)) == 0
+                zero_kept = ti[tv == 0]
+                zero_drop = torch.nonzero(grads[k][off:off + n] == 0).flatten() + off
+                if zero_kept.numel() and zero_drop.numel() > zero_kept.numel():
+                    assert int(zero_kept.max()) == int(zero_drop[zero_kept.numel() - 1])
+        assert torch.equal(recon.view(torch.int32), grads[k].view(torch.int32)), f"worker {k}: invariant"
+        acc = acc + dense                                        # worker order, from +0
+        del e_w, recon, dense
+    ref = acc / float(W)
+    assert torch.equal(out.view(torch.int32), ref.view(torch.int32)), "mean"
+    gpu.destroy()
