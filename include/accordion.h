@@ -222,10 +222,12 @@ int32_t accordion_batch_status(acc_ctx* ctx, int32_t* level, int32_t* pending_mi
  * level <- critical; old <- c; A <- 0.  Only between steps (else ACC_ESTATE). */
 int32_t accordion_detect_regime(acc_ctx* ctx, float lr_curr, float lr_next);
 
-/* PowerSGD keeps Delta_w in the error memory at the end of a step and forms the residual
- * e_w = Delta_w - D in the first pass of the next step (one read and one write of the matrix
- * saved per worker and step).  accordion_flush writes the residual out now; accordion_get_state
- * does so by itself.  Only between steps (else ACC_ESTATE).  No effect for TopK. */
+/* The batched entry points (accordion_step_all, accordion_step_all_update) keep Delta_w in the
+ * error memory at the end of a step and form the residual in the first pass of the next step:
+ * PowerSGD e_w = Delta_w - D from the stored factors, TopK e_w = Delta_w with the kept entries
+ * dropped, from the stored thresholds and tie counts (one write of the memory saved per worker
+ * and step).  accordion_flush writes the residual out now; accordion_get_state does so by itself.
+ * Only between steps (else ACC_ESTATE).  The call-by-call TopK path writes it directly. */
 int32_t accordion_flush(acc_ctx* ctx);
 
 /* A <- 0 without a decision (to measure one epoch out of several, Sec. 5.1 "Hyperparameters"). */
@@ -297,7 +299,7 @@ int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
  * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
  * accordion_stage_name gives the kernel's name (NULL if out of range). */
-#define ACC_N_STAGES 29
+#define ACC_N_STAGES 31
 int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
 int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
 const char* accordion_stage_name(int32_t stage);

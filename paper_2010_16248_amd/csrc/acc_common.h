@@ -112,6 +112,7 @@ struct Ws {
   int64_t q_stride;
   int32_t* pay_idx;  float* pay_val;  int64_t pay_stride;
   unsigned long long* overlap; // L per-layer counters of the overlap read-back
+  uint32_t* tpending;          // one word: workers whose e still holds Delta with the kept entries in it
   // batch-size mode
   uint32_t* bstate;            // two slots of four words, used alternately (micro-step parity)
   int32_t bmult, bmono;        // micro-steps per large batch; 1: the batch only grows

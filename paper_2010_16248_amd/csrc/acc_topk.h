@@ -202,6 +202,77 @@ __device__ __forceinline__ uint32_t stage_flush(const Ws& ws, int64_t qslot, con
   return nz;
 }
 
+// Thresholds of the four elements a lane holds of one group: an element is selected iff its key
+// >= tsel.  That is T + 1 (or T when every entry equal to T is selected), except for the entries
+// equal to T that are within the tie quota ktie, counted in index order over the layer: eq_run is
+// the number of entries equal to T before this group (advanced here); quarters without an entry
+// equal to T (eq_here == 0) never look at ties.  mv: lane masks of the valid elements per
+// component; valid: the calling lane's bits of them.
+__device__ __forceinline__ void group_thresholds(uint32_t T, uint32_t ktie, uint32_t alleq, uint32_t eq_here,
+                                                 uint32_t& eq_run, const uint32_t (&key)[4],
+                                                 const bool (&valid)[4], const uint64_t (&mv)[4], int lane,
+                                                 uint32_t (&tsel)[4]) {
+  const uint32_t t_all = alleq ? T : T + 1u;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) tsel[c] = t_all;
+  if (eq_here != 0u && !alleq) {                            // wave-uniform
+    uint64_t meq[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) meq[c] = ballot64(key[c] == T) & mv[c];
+    if ((meq[0] | meq[1] | meq[2] | meq[3]) != 0) {
+      // the tie quota is used up in index order
+      uint32_t rank = eq_run;
+      uint32_t total = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        rank += lanes_below(meq[c], lane);
+        total += (uint32_t)__popcll(meq[c]);
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool iseq = valid[c] && key[c] == T;
+        tsel[c] = (iseq && rank < ktie) ? T : T + 1u;
+        rank += iseq ? 1u : 0u;
+      }
+      eq_run += total;
+    }
+  }
+}
+
+// The selection of the previous step as the next pass over Delta needs it to zero the kept
+// entries (the residual is not written by the compaction of the batched path: see tpending).
+struct PrevSel { uint32_t T, ktie, alleq, eq_here, eq_run; };
+
+__device__ __forceinline__ PrevSel load_prev_sel(const Ws& ws, int64_t wl, int64_t qslot) {
+  const SelState* sp = ws.sel + wl;
+  PrevSel p;
+  p.T = sp->T; p.ktie = sp->ktie; p.alleq = sp->alleq;
+  p.eq_run = ws.eqpre[qslot];
+  p.eq_here = ws.eqpre[qslot + 1] - p.eq_run;             // the layer's last slot holds the total
+  return p;
+}
+
+// d with the entries the previous step kept set to zero (q: the group, qa: inside the wave's span).
+template <bool AL>
+__device__ __forceinline__ float4 drop_kept(const TileGeom& tg, int q, bool qa, uint64_t m_span, PrevSel& ps,
+                                            float4 d, int lane) {
+  uint32_t key[4], tsel[4];
+  bool valid[4];
+  uint64_t mv[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    valid[c] = elem_valid<AL>(tg, q, c, qa);
+    mv[c] = valid_mask<AL>(tg, q, c, qa, m_span);
+    key[c] = key_of(comp(d, c));
+  }
+  group_thresholds(ps.T, ps.ktie, ps.alleq, ps.eq_here, ps.eq_run, key, valid, mv, lane, tsel);
+  if (valid[0] && key[0] >= tsel[0]) d.x = 0.f;
+  if (valid[1] && key[1] >= tsel[1]) d.y = 0.f;
+  if (valid[2] && key[2] >= tsel[2]) d.z = 0.f;
+  if (valid[3] && key[3] >= tsel[3]) d.w = 0.f;
+  return d;
+}
+
 // ---- A ----------------------------------------------------------------------------------------
 
 // SELECT = false (layers of a single tile, which the pick kernel decides from Delta itself):
@@ -220,6 +291,10 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   uint32_t glo = 0x7ffffff0u;                              // no bin matches without a guess
   if (SELECT && !ZB && guess != kNoGuess) glo = max(guess, 1u);
+  // the batched path leaves Delta of the previous step in e: its kept entries are dropped here
+  const bool pend = ((*ws.tpending >> w) & 1u) != 0u;      // uniform over the workgroup
+  PrevSel ps = {0u, 0u, 0u, 0u, 0u};
+  if (pend) ps = load_prev_sel(ws, wl, quarter_slot(ws, L, w, ft.start >> kTileShift, wave));
   // two groups per lane are requested before the histograms are cleared
   constexpr int U = 2;
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -251,6 +326,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
     for (int u = 0; u < U; ++u) {
       const int q = q0 + u * kWave + lane;
       const bool qa = q < span.qend;
+      if (pend) ec[u] = drop_kept<AL>(tg, q, qa, ballot64(qa), ps, ec[u], lane);
       const float4 d = make_float4(gc[u].x + ec[u].x, gc[u].y + ec[u].y, gc[u].z + ec[u].z, gc[u].w + ec[u].w);
       if (qa) {
         stq<AL>(e, tg.a0, tg.lo, tg.hi, q, d);
@@ -915,7 +991,7 @@ struct CompactRun { uint32_t eq_run, pos_run; };
 // cost a quarter of this kernel's time.  An element is selected iff its key >= tsel, where tsel is
 // T for the entries equal to T that are within the tie quota (lowest indices first) and T + 1
 // otherwise; quarters without an entry equal to T never look at ties.
-template <bool AL, bool MEAN>
+template <bool AL, bool MEAN, bool DEFER>
 __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan& span, int64_t layer_offset,
                                               const QuarterSel& qs, CompactRun& run, float* __restrict__ e,
                                               int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
@@ -926,36 +1002,13 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
   bool valid[4];
   uint64_t mv[4];
   uint32_t key[4], tsel[4];
-  const uint32_t t_all = qs.alleq ? T : T + 1u;
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     valid[c] = elem_valid<AL>(tg, q, c, qa);
     mv[c] = valid_mask<AL>(tg, q, c, qa, m_span);
     key[c] = key_of(comp(cur, c));
-    tsel[c] = t_all;
   }
-  if (qs.eq_here != 0u && !qs.alleq) {                      // wave-uniform
-    uint64_t meq[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) meq[c] = ballot64(key[c] == T) & mv[c];
-    if ((meq[0] | meq[1] | meq[2] | meq[3]) != 0) {
-      // the tie quota is used up in index order
-      uint32_t rank = run.eq_run;
-      uint32_t total = 0;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        rank += lanes_below(meq[c], lane);
-        total += (uint32_t)__popcll(meq[c]);
-      }
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bool iseq = valid[c] && key[c] == T;
-        tsel[c] = (iseq && rank < qs.ktie) ? T : T + 1u;
-        rank += iseq ? 1u : 0u;
-      }
-      run.eq_run += total;
-    }
-  }
+  group_thresholds(T, qs.ktie, qs.alleq, qs.eq_here, run.eq_run, key, valid, mv, lane, tsel);
   uint64_t msel[4];
   uint32_t below = 0, total = 0;
 #pragma unroll
@@ -998,7 +1051,8 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
     if (sel[1]) z.y = 0.f;
     if (sel[2]) z.z = 0.f;
     if (sel[3]) z.w = 0.f;
-    if (sel[0] || sel[1] || sel[2] || sel[3]) stq<AL>(e, tg.a0, tg.lo, tg.hi, q, z);
+    // DEFER: the zeros are not written; the next pass over Delta drops the kept entries itself
+    if (!DEFER && (sel[0] || sel[1] || sel[2] || sel[3])) stq<AL>(e, tg.a0, tg.lo, tg.hi, q, z);
     run.pos_run += total;
     if (MEAN) {
       if (sel[0]) acc.x += cur.x;
@@ -1030,7 +1084,7 @@ __device__ __forceinline__ void compact_tile(const Ws& ws, int w, const FlatTile
   for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
     const int q = q0 + lane;
     const float4 nn = ld_span<AL>(e, tg, span, q + 2 * kWave);
-    compact_group<AL, false>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, unused, stg);
+    compact_group<AL, false, false>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, unused, stg);
     cur = nxt;
     nxt = nn;
   }
@@ -1041,7 +1095,10 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
-  if (blockIdx.x == 0 && threadIdx.x == 0) ws.miss_any[w] = 0u;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    ws.miss_any[w] = 0u;
+    atomicAnd(ws.tpending, ~(1u << w));                    // this path writes the residual itself
+  }
   __shared__ uint2 stage[4][kGroupList];
   uint2* stg = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
   if (tg.aligned) compact_tile<true>(ws, w, ft, L, tg, stg);
@@ -1122,7 +1179,7 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
           float* __restrict__ e = e_base + (int64_t)w * e_stride;
           int32_t* pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
           float* pval = pay_val + (int64_t)w * pay_stride + pay_off;
-          compact_group<AL, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur[u], lane, acc, stg);
+          compact_group<AL, true, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur[u], lane, acc, stg);
           if (lane == w) { eq_run_v = run.eq_run; pos_run_v = run.pos_run; }
         }
       }
@@ -1152,6 +1209,8 @@ __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink
     ws.words[2] += ws.words[0];
   }
   if (blockIdx.x == 0 && threadIdx.x < ws.W) ws.miss_any[threadIdx.x] = 0u;
+  // every e_w keeps Delta_w: the kept entries are dropped by the next pass over it
+  if (blockIdx.x == 0 && threadIdx.x == 0) *ws.tpending = ws.W == 32 ? 0xffffffffu : ((1u << ws.W) - 1u);
   __shared__ uint2 stage[4][kGroupList];
   uint2* stg = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
   if (tg.aligned) compact_mean_tile<true, UPD>(ws, ft, L, tg, sink, stg);
@@ -1251,6 +1310,40 @@ __global__ __launch_bounds__(256) void topk_sparse_mean_kernel(const Ws ws, cons
 
 __global__ __launch_bounds__(256) void topk_sparse_update_kernel(const Ws ws, const Sink sink) {
   sparse_mean_body<true>(ws, sink);
+}
+
+// ---- the residual written out on demand --------------------------------------------------------
+// e_w = Delta_w with the kept entries zeroed, for the workers whose bit is set in *ws.tpending
+// (accordion_flush / accordion_get_state); the caller clears the mask afterwards.
+template <bool AL>
+__device__ __forceinline__ void residual_tile(const Ws& ws, int w, const FlatTile& ft, const LayerDev& L,
+                                              const TileGeom& tg) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const WaveSpan span = wave_span(tg, wave);
+  float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+  PrevSel ps = load_prev_sel(ws, (int64_t)w * ws.L + ft.layer, quarter_slot(ws, L, w, ft.start >> kTileShift, wave));
+  for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
+    const int q = q0 + lane;
+    const bool qa = q < span.qend;
+    const float4 d = ld_span<AL>(e, tg, span, q);
+    const float4 z = drop_kept<AL>(tg, q, qa, ballot64(qa), ps, d, lane);
+    if (qa && (z.x != d.x || z.y != d.y || z.z != d.z || z.w != d.w)) stq<AL>(e, tg.a0, tg.lo, tg.hi, q, z);
+  }
+}
+
+__global__ __launch_bounds__(256) void topk_residual_kernel(const Ws ws) {
+  const int w = blockIdx.y;
+  if (((*ws.tpending >> w) & 1u) == 0u) return;
+  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const LayerDev& L = ws.layers[ft.layer];
+  const TileGeom tg = tile_geom(L, ft);
+  if (tg.aligned) residual_tile<true>(ws, w, ft, L, tg);
+  else residual_tile<false>(ws, w, ft, L, tg);
+}
+
+__global__ void topk_clear_pending_kernel(const Ws ws) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *ws.tpending = 0u;
 }
 
 // ---- overlap of two workers' kept sets (Section 4.3) ---------------------------------------------

@@ -46,7 +46,7 @@ struct Plan {
   Region r_A, r_e, r_norm_part, r_sq_part, r_bstate;
   int64_t n_model = 0;   // elements that belong to a layer
   Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean, r_pending;
-  Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval, r_overlap;
+  Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval, r_overlap, r_tpending;
   int64_t total_bytes = 0;
 };
 
@@ -227,6 +227,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     reg(p.r_payidx, 4 * p.pay_stride * W);
     reg(p.r_payval, 4 * p.pay_stride * W);
     reg(p.r_overlap, 8 * (int64_t)nl);
+    reg(p.r_tpending, 4);
   }
   p.total_bytes = off;
   return ACC_OK;
@@ -262,7 +263,7 @@ enum Stage {
   ST_psgd_decomp_update_kernel, ST_topk_compact_update_kernel, ST_topk_sparse_update_kernel,
   ST_batch_micro_kernel, ST_batch_micro_update_kernel, ST_batch_decide_kernel,
   ST_topk_overlap_kernel, ST_zero_u64_kernel, ST_msdr_sq_kernel, ST_msdr_decide_kernel,
-  ST_psgd_clear_pending_kernel,
+  ST_psgd_clear_pending_kernel, ST_topk_residual_kernel, ST_topk_clear_pending_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
@@ -275,7 +276,7 @@ static const char* const kStageNames[ST_COUNT] = {
   "psgd_decomp_update_kernel", "topk_compact_update_kernel", "topk_sparse_update_kernel",
   "batch_micro_kernel", "batch_micro_update_kernel", "batch_decide_kernel",
   "topk_overlap_kernel", "zero_u64_kernel", "msdr_sq_kernel", "msdr_decide_kernel",
-  "psgd_clear_pending_kernel"};
+  "psgd_clear_pending_kernel", "topk_residual_kernel", "topk_clear_pending_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
 
@@ -485,8 +486,13 @@ int check_sgd(acc_ctx* c, const float* w, const float* v, float lr, float mu, fl
 
 // Make the error memory explicit: e_w = Delta_w - D for the workers whose residual is pending.
 int materialise(acc_ctx* c) {
-  if (c->cfg.method != ACC_POWERSGD) return ACC_OK;
   const Ws& ws = c->ws;
+  if (c->cfg.method == ACC_TOPK) {
+    ACC_LAUNCH(c, topk_residual_kernel, dim3(ws.n_ftiles, ws.W), dim3(256), ws);
+    ACC_LAUNCH(c, topk_clear_pending_kernel, dim3(1), dim3(64), ws);
+    return ACC_OK;
+  }
+  if (c->cfg.method != ACC_POWERSGD) return ACC_OK;
   if (ws.n_mtiles > 0) ACC_LAUNCH(c, psgd_residual_kernel, dim3(ws.n_mtiles, ws.W), dim3(256), ws);
   ACC_LAUNCH(c, psgd_clear_pending_kernel, dim3(1), dim3(64), ws);
   return ACC_OK;
@@ -596,6 +602,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.pay_val = at<float>(c, p.r_payval);
     ws.pay_stride = p.pay_stride;
     ws.overlap = at<unsigned long long>(c, p.r_overlap);
+    ws.tpending = at<uint32_t>(c, p.r_tpending);
   }
   ws.bstate = at<uint32_t>(c, p.r_bstate);
   ws.bmult = cfg->method == ACC_BATCH ? cfg->batch_multiplier : 1;
@@ -1038,6 +1045,7 @@ int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
   if (rc != ACC_OK) return rc;
   if (c->cfg.method == ACC_POWERSGD)                         // the memory just written is explicit
     ACC_LAUNCH(c, psgd_clear_pending_kernel, dim3(1), dim3(64), c->ws);
+  if (c->cfg.method == ACC_TOPK) ACC_LAUNCH(c, topk_clear_pending_kernel, dim3(1), dim3(64), c->ws);
   if (c->plan.r_sq_part.bytes > 0)                           // the MSDR window restarts with the import
     ACC_HIP(c, hipMemset(c->ws.sq_part, 0, (size_t)c->plan.r_sq_part.bytes));
   ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)c->cfg.method);

@@ -24,8 +24,9 @@ def test_resnet18_topk_both_levels():
     w = wl.workload("resnet18_topk")
     W = 2
     gpu, ora = H.make_pair(B.ACC_TOPK, w.layers, W, w.level_crit, w.level_noncrit, w.k_den)
-    for step in range(2):                                   # K = 10 %
-        _check_step(gpu, ora, [wl.gradient(w, k, step) for k in range(W)], f"K10 step {step}")
+    for step in range(2):                                   # K = 10 %; the second step takes the deferred route
+        _check_step(gpu, ora, [wl.gradient(w, k, step) for k in range(W)], f"K10 step {step}",
+                    check_state=(step == 1))
     assert ora.words_last == 2 * 1117426
     _set_levels(gpu, ora, 0)                                # K = 1 %
     _check_step(gpu, ora, [wl.gradient(w, k, 2) for k in range(W)], "K1 step 2")

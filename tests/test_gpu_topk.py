@@ -10,7 +10,11 @@ from tests import helpers as H
 pytestmark = pytest.mark.gpu
 
 
-def _check_step(gpu, ora, grads, tag):
+def _check_step(gpu, ora, grads, tag, check_state=True):
+    """One batched step on both sides; mean and payloads always compared.  check_state=False
+    leaves the library's memory alone (reading it writes the residual out, which the batched
+    path otherwise defers to the next step's first pass): the deferred route is then the one
+    the next step takes."""
     out_ref = ora.step(grads)
     dg = [H.to_dev(g) for g in grads]
     out = H.dev_out(gpu.n_params)
@@ -22,10 +26,12 @@ def _check_step(gpu, ora, grads, tag):
             ri, rv = ora.payload[(w, li)]
             assert np.array_equal(idx, ri), f"{tag}: indices worker {w} layer {li}"
             H.assert_bits_equal(val, rv, f"{tag}: values worker {w} layer {li}")
+    assert gpu.payload_words() == (ora.words_last, ora.words_cum)
+    if not check_state:
+        return
     st = gpu.unpack_state(gpu.get_state())
     H.assert_bits_equal(st["e"], ora.e, f"{tag}: residual")
     H.assert_bits_equal(st["A"], ora.A, f"{tag}: accumulator")
-    assert gpu.payload_words() == (ora.words_last, ora.words_cum)
 
 
 def _case_values(rng, case, n):
@@ -53,7 +59,7 @@ def test_ragged_misaligned_layers(crit, noncrit, den):
     rng = np.random.default_rng(1)
     for step in range(3):
         grads = [rng.standard_normal(N).astype(np.float32) for _ in range(3)]
-        _check_step(gpu, ora, grads, f"step {step}")
+        _check_step(gpu, ora, grads, f"step {step}", check_state=(step == 2))
     # switch every layer to the other level by hand and go on
     blob = H.oracle_state_blob(gpu, ora)
     ora.level[:] = 0
@@ -62,7 +68,7 @@ def test_ragged_misaligned_layers(crit, noncrit, den):
     gpu.set_state(blob)
     for step in range(2):
         grads = [rng.standard_normal(N).astype(np.float32) for _ in range(3)]
-        _check_step(gpu, ora, grads, f"noncrit step {step}")
+        _check_step(gpu, ora, grads, f"noncrit step {step}", check_state=(step == 1))
     gpu.destroy()
 
 
@@ -77,9 +83,9 @@ def test_multi_tile_layers_with_ties(case):
     N = wl.total_params(layers)
     gpu, ora = H.make_pair(B.ACC_TOPK, layers, 2, 10, 1)
     rng = np.random.default_rng([7, len(case)])
-    for step in range(2):
+    for step in range(4):                                    # state read after steps 1 and 3 only
         grads = [_case_values(rng, case, N).astype(np.float32) for _ in range(2)]
-        _check_step(gpu, ora, grads, f"{case} step {step}")
+        _check_step(gpu, ora, grads, f"{case} step {step}", check_state=(step % 2 == 1))
     gpu.destroy()
 
 
@@ -103,7 +109,7 @@ def test_guessed_bins_hit_drift_and_miss():
         if step == 12:
             scale *= 40.0                                   # far outside the guessed bins
         grads = [(rng.standard_normal(N) * scale).astype(np.float32) for _ in range(W)]
-        _check_step(gpu, ora, grads, f"step {step}")
+        _check_step(gpu, ora, grads, f"step {step}", check_state=(step % 3 == 2 or step == 13))
         restaged.append(gpu.topk_stats()[0])
     per_step = np.diff([0] + restaged)
     n_multi = 3 * W                                         # (worker, layer) pairs of more than one tile
@@ -136,7 +142,7 @@ def test_threshold_among_exact_zeros_is_guessed_too():
             if not dense:
                 g *= rng.random(N) < 0.03                   # 3 % non-zero, 10 % kept
             grads.append(g.astype(np.float32))
-        _check_step(gpu, ora, grads, f"step {step}")
+        _check_step(gpu, ora, grads, f"step {step}", check_state=(step in (3, 6)))
         restaged.append(gpu.topk_stats()[0])
     per_step = np.diff([0] + restaged)
     n_multi = 2 * W
@@ -158,7 +164,7 @@ def test_large_tie_classes_take_the_sweeps_and_stay_exact():
     rng = np.random.default_rng(9)
     for step in range(4):
         grads = [(rng.integers(-3, 4, N) * 0.25).astype(np.float32) for _ in range(2)]
-        _check_step(gpu, ora, grads, f"step {step}")
+        _check_step(gpu, ora, grads, f"step {step}", check_state=(step in (1, 3)))
     assert gpu.topk_stats()[1] > 0
     gpu.destroy()
 
@@ -192,7 +198,7 @@ def test_high_keep_ratios_use_the_values_and_holes_layout(crit, noncrit):
             else:
                 grads = [rng.standard_normal(N).astype(np.float32) for _ in range(W)]
             if mode == "all":
-                _check_step(gpu, ora, grads, f"{mode} step {step}")
+                _check_step(gpu, ora, grads, f"{mode} step {step}", check_state=(step in (1, 3)))
             else:
                 out_ref = ora.step(grads)
                 dg = [H.to_dev(g) for g in grads]
