@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0
 # of this file (summaries under profiles/); None until measured for a workload.
 # Key: (workload, W, dominant kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 647753344,      # profiles/hbm_traffic_resnet18_topk.md
-    ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635951018,     # profiles/hbm_traffic_resnet18_powersgd.md
-    ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416747795,        # profiles/hbm_traffic_vgg19_powersgd.md
+    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 648641334,      # profiles/hbm_traffic_resnet18_topk.md
+    ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635927304,     # profiles/hbm_traffic_resnet18_powersgd.md
+    ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416744227,        # profiles/hbm_traffic_vgg19_powersgd.md
 }
 
 # Both compression levels are used while timing: the gradient statistics are stationary (every
