@@ -283,6 +283,46 @@ def test_call_by_call_equals_step_all_and_is_deterministic():
         assert np.array_equal(st, results[0][1])
 
 
+def test_batched_and_call_by_call_steps_interleave():
+    """The batched path leaves the residual to the next step's first pass; the call-by-call
+    path writes it itself.  Any interleaving of the two, with workers compressed in any order,
+    gives the oracle's payloads, means and (read once at the end) memory."""
+    print("case mixed paths", flush=True)
+    layers = wl.make_layers([(1, 2 * 8192 + 31, 0), (20, 900, 1), (1, 64, 0)])
+    N = wl.total_params(layers)
+    W = 3
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    rng = np.random.default_rng(21)
+    out = H.dev_out(N)
+    for step, mode in enumerate(["all", "calls", "all", "all", "calls", "calls", "all"]):
+        if step % 2:
+            grads = [(rng.integers(-3, 4, N) * 0.25).astype(np.float32) for _ in range(W)]
+        else:
+            grads = [rng.standard_normal(N).astype(np.float32) for _ in range(W)]
+        if mode == "all":
+            _check_step(gpu, ora, grads, f"step {step} {mode}", check_state=False)
+            continue
+        out_ref = ora.step(grads)
+        dg = [H.to_dev(g) for g in grads]
+        for w in (1, 2, 0):
+            gpu.compress_step(w, dg[w], 0)
+        gpu.aggregate(0)
+        gpu.decompress(out)
+        H.assert_bits_equal(out.cpu().numpy(), out_ref, f"step {step} {mode}: mean")
+        for w in range(W):
+            for li in range(gpu.n_layers):
+                idx, val = gpu.get_payload(w, li)
+                assert np.array_equal(idx, ora.payload[(w, li)][0]), f"step {step}: indices"
+                H.assert_bits_equal(val, ora.payload[(w, li)][1], f"step {step}: values")
+    st = gpu.unpack_state(gpu.get_state())
+    H.assert_bits_equal(st["e"], ora.e, "residual at the end")
+    H.assert_bits_equal(st["A"], ora.A, "accumulator at the end")
+    gpu.flush()                                             # nothing pending any more: a no-op
+    assert np.array_equal(gpu.get_state(), gpu.pack_state(st["e"], st["A"], None, st["norm_old"],
+                                                          st["has_old"], st["level"]))
+    gpu.destroy()
+
+
 def test_state_machine_errors_come_from_the_host():
     layers = wl.make_layers([(4, 10, 1)])
     gpu, _ = H.make_pair(B.ACC_TOPK, layers, 2, 50, 10)
