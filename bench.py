@@ -160,7 +160,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
-              "the path shards by worker, see DESIGN.md", file=sys.stderr)
+              "the path would shard by worker (one data-parallel worker per GPU)", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2010_16248_amd import binding as B
