@@ -323,6 +323,26 @@ def test_batched_and_call_by_call_steps_interleave():
     gpu.destroy()
 
 
+def test_set_state_overrides_a_pending_residual():
+    """Importing a state while the residual of the last batched step is still pending must take
+    the imported memory as it is (nothing of the old step may be dropped from it)."""
+    layers = wl.make_layers([(1, 8192 + 77, 0), (12, 50, 1)])
+    N = wl.total_params(layers)
+    W = 2
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    rng = np.random.default_rng(33)
+    for step in range(2):                                   # the second step leaves its residual pending
+        grads = [rng.standard_normal(N).astype(np.float32) for _ in range(W)]
+        _check_step(gpu, ora, grads, f"step {step}", check_state=False)
+    ora.e[:] = rng.standard_normal((W, N)).astype(np.float32)   # a memory from elsewhere
+    ora.A[:] = 0
+    gpu.set_state(H.oracle_state_blob(gpu, ora))
+    for step in range(2):
+        grads = [rng.standard_normal(N).astype(np.float32) for _ in range(W)]
+        _check_step(gpu, ora, grads, f"after import, step {step}", check_state=(step == 1))
+    gpu.destroy()
+
+
 def test_state_machine_errors_come_from_the_host():
     layers = wl.make_layers([(4, 10, 1)])
     gpu, _ = H.make_pair(B.ACC_TOPK, layers, 2, 50, 10)
