@@ -37,6 +37,14 @@ MEASURED_TRAFFIC_BYTES = {
     ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416744227,        # profiles/hbm_traffic_vgg19_powersgd.md
 }
 
+# Counted traffic of all kernels of one step (sum of the per-kernel averages in the same summaries;
+# kernels that run once per window or on demand left out).  Key: (workload, W).
+MEASURED_STEP_TRAFFIC_BYTES = {
+    ("resnet18_topk", 4): 648641334 + 271286539 + 47400793 + 16774368 + 4664759 + 2292559,
+    ("resnet18_powersgd", 4): 635927304 + 191292948 + 12202811 + 3365133 + 47509184,
+    ("vgg19_powersgd", 1): 416744227 + 88423742 + 6228142 + 1781383 + 86512973,
+}
+
 # Both compression levels are used while timing: the gradient statistics are stationary (every
 # window's norm ratio is about 0, i.e. not critical), and every second window ends with a
 # learning-rate decay (lr_next < lr_curr), which Algorithm 1 treats as critical.  Decisions:
@@ -97,7 +105,7 @@ def algorithmic_bytes_step(w, layers, W, levels_k_or_r):
     N = sum(l.numel for l in layers)
     if w.method == B.ACC_TOPK:
         kept = sum(levels_k_or_r)
-        return 12 * N * W + 8 * N + 2 * 8 * kept * W + 4 * N
+        return 12 * N * W + 8 * N + 8 * kept * W + 4 * N
     mat = sum(l.numel for l in layers if l.is_matrix)
     vec = N - mat
     return 24 * mat * W + 8 * N + 4 * N + 4 * vec * W
@@ -304,6 +312,17 @@ def main():
                     "avg_kernel_us": round(avg_s * 1e6, 2),
                     "algorithmic_bytes_per_launch": alg_bytes}
 
+    # the whole step: bytes the method must move (one read / write of each operand per pass, the
+    # payload at the level of the last step) and the traffic counted by rocprofv3 for all kernels
+    step_bw = None
+    if not is_batch:
+        alg = algorithmic_bytes_step(w, layers, W, [words_last // 2])
+        cnt = MEASURED_STEP_TRAFFIC_BYTES.get((args.workload, W))
+        step_bw = {"algorithmic_bytes": alg, "algorithmic_GB/s": round(alg / (ms_per_step * 1e-3) / 1e9, 1),
+                   "counted_bytes": cnt,
+                   "counted_GB/s": round(cnt / (ms_per_step * 1e-3) / 1e9, 1) if cnt else None,
+                   "counted_frac_of_peak": round(cnt / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if cnt else None}
+
     cpu = None
     if not args.no_cpu_baseline:
         n_cpu = 2 if N > 5_000_000 else 20
@@ -322,6 +341,7 @@ def main():
                    "levels_switch": args.fixed_level < 0, "hip_graph": bool(args.hip_graph),
                    "sink": "nesterov update of weights and velocity" if args.fused_update else "averaged gradient stored", "kernel_events_in_timed_region": args.kernel_events},
         "roofline": roofline,
+        "step_bandwidth": step_bw,
         "cpu_baseline": cpu,
         "copy_probe": copy_probe,
         "kernels": kernels,
