@@ -486,21 +486,29 @@ __global__ __launch_bounds__(256) void psgd_qmean_kernel(const Ws ws) {
 // optimizer step on sink.wt / sink.vel and is not stored.
 template <int MODE, bool V4>
 __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, float* __restrict__ e,
-                            const Sink& sink, int r) {
+                            const Sink& sink, int r, float (*ps)[kMaxRank]) {
   constexpr bool RESIDUAL = MODE == 1;
   constexpr bool UPD = MODE == 2;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int col[4]; bool cm[4];
   lane_cols<V4>(t.col0, lane, L.cols, col, cm);
+  const int row_end = min(t.row0 + kMatRows, L.rows);
+  const float* __restrict__ ph = ws.Phat + L.p_off;
+  // the tile's 64 rows of P^ (zero-padded to four columns) go to LDS with one load per thread,
+  // requested together with Q's rows: the row loop then waits for no global load of its own
+  {
+    const int pr = threadIdx.x >> 2, pk = threadIdx.x & 3;
+    const int i = t.row0 + pr;
+    ps[pr][pk] = (i < row_end && pk < r) ? ph[(int64_t)i * ws.rmax + pk] : 0.f;
+  }
   float q[4][kMaxRank];
 #pragma unroll
   for (int v = 0; v < 4; ++v)
 #pragma unroll
     for (int k = 0; k < kMaxRank; ++k)
       q[v][k] = (cm[v] && k < ws.rmax) ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
-  const int row_end = min(t.row0 + kMatRows, L.rows);
-  const float* __restrict__ ph = ws.Phat + L.p_off;
+  __syncthreads();
   constexpr int B = 4;
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float d[B][4], vv[UPD ? B : 1][4];
@@ -522,7 +530,7 @@ __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, f
         const int64_t rb = L.offset + (int64_t)i * L.cols;
         float p[kMaxRank];
 #pragma unroll
-        for (int k = 0; k < kMaxRank; ++k) p[k] = (k < r) ? ph[(int64_t)i * ws.rmax + k] : 0.f;
+        for (int k = 0; k < kMaxRank; ++k) p[k] = ps[i - t.row0][k];
         float D[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) D[v] = low_rank_entry(p, q[v]);
@@ -548,6 +556,7 @@ __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, f
 // no memory: their e is cleared for every worker).
 template <bool UPD>
 __device__ __forceinline__ void decomp_body(const Ws& ws, const Sink& sink) {
+  __shared__ float ps[kMatRows][kMaxRank];
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     *ws.pending = ws.W == 32 ? 0xffffffffu : ((1u << ws.W) - 1u);   // every e_w now holds Delta_w
     ws.words[1] = ws.words[0];
@@ -574,8 +583,8 @@ __device__ __forceinline__ void decomp_body(const Ws& ws, const Sink& sink) {
   const MatTile t = ws.mtiles[blockIdx.x];
   const LayerDev& L = ws.layers[t.layer];
   const int r = ws.rank_used[t.layer];                     // written by the orthogonalisation of this step
-  if (L.vec4) decomp_tile<UPD ? 2 : 0, true>(ws, L, t, nullptr, sink, r);
-  else decomp_tile<UPD ? 2 : 0, false>(ws, L, t, nullptr, sink, r);
+  if (L.vec4) decomp_tile<UPD ? 2 : 0, true>(ws, L, t, nullptr, sink, r, ps);
+  else decomp_tile<UPD ? 2 : 0, false>(ws, L, t, nullptr, sink, r, ps);
 }
 
 __global__ __launch_bounds__(256) void psgd_decomp_kernel(const Ws ws, const Sink sink) {
@@ -598,8 +607,9 @@ __global__ __launch_bounds__(256) void psgd_residual_kernel(const Ws ws) {
   const LayerDev& L = ws.layers[t.layer];
   const int r = ws.rank_used[t.layer];
   const Sink none = {nullptr, nullptr, nullptr, 0.f, 0.f, 0.f};
-  if (L.vec4) decomp_tile<1, true>(ws, L, t, e, none, r);
-  else decomp_tile<1, false>(ws, L, t, e, none, r);
+  __shared__ float ps[kMatRows][kMaxRank];
+  if (L.vec4) decomp_tile<1, true>(ws, L, t, e, none, r, ps);
+  else decomp_tile<1, false>(ws, L, t, e, none, r, ps);
 }
 
 __global__ void psgd_clear_pending_kernel(const Ws ws) {
