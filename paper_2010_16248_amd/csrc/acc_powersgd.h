@@ -83,11 +83,19 @@ __device__ __forceinline__ float low_rank_entry(const float (&p)[kMaxRank], cons
 // the previous P^ (rows in ws.Phat) and Q~ (= the warm start, first rp columns).
 template <int R, bool V4>
 __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const float* __restrict__ g,
-                          float* __restrict__ e, float* __restrict__ A, float* __restrict__ ppart, int rp) {
+                          float* __restrict__ e, float* __restrict__ A, float* __restrict__ ppart, int rp,
+                          float (*ps)[kMaxRank]) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int col[4]; bool cm[4];
   lane_cols<V4>(t.col0, lane, L.cols, col, cm);
+  if (rp > 0) {
+    // the previous P^ rows of the tile (zero-padded) go to LDS with one load per thread, requested
+    // together with Q's rows, so that the row loop waits for no load of theirs
+    const int pr = threadIdx.x >> 2, pk = threadIdx.x & 3;
+    const int i = t.row0 + pr;
+    ps[pr][pk] = (i < L.rows && pk < rp) ? ws.Phat[L.p_off + (int64_t)i * ws.rmax + pk] : 0.f;
+  }
   float q[4][kMaxRank];
 #pragma unroll
   for (int v = 0; v < 4; ++v)
@@ -95,9 +103,9 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
     for (int k = 0; k < kMaxRank; ++k)
       q[v][k] = (cm[v] && k < ws.rmax) ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
 
+  if (rp > 0) __syncthreads();                             // uniform over the workgroup
   const int row_end = min(t.row0 + kMatRows, L.rows);
   const int chunk = t.col0 / kMatCols;
-  const float* __restrict__ ph = ws.Phat + L.p_off;
   constexpr int B = 2;   // rows in flight per wave (one row is as fast; more rows cost registers and occupancy)
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float gd[B][4], ed[B][4], ad[B][4];
@@ -119,7 +127,7 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
         if (rp > 0) {                          // wave-uniform: the pending residual first
           float pp[kMaxRank];
 #pragma unroll
-          for (int k = 0; k < kMaxRank; ++k) pp[k] = (k < rp) ? ph[(int64_t)i * ws.rmax + k] : 0.f;
+          for (int k = 0; k < kMaxRank; ++k) pp[k] = ps[i - t.row0][k];
 #pragma unroll
           for (int v = 0; v < 4; ++v) ed[b][v] = ed[b][v] - low_rank_entry(pp, q[v]);
         }
@@ -155,6 +163,7 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
 // The mask lives on the device (set by the decompress pass, cleared when the residual is written
 // out), so a captured graph of a step stays valid whatever happens between its replays.
 __global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradPtrs gp, int w0) {
+  __shared__ float ps[kMatRows][kMaxRank];
   const uint32_t pending = *ws.pending;
   const int w = w0 + blockIdx.y;
   const float* __restrict__ g = gp.p[w];
@@ -182,17 +191,17 @@ __global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradP
   float* ppart = ws.Ppart + (int64_t)w * ws.ppart_stride;
   if (L.vec4) {
     switch (r) {
-      case 1: ef_p_tile<1, true>(ws, L, t, g, e, A, ppart, rp); break;
-      case 2: ef_p_tile<2, true>(ws, L, t, g, e, A, ppart, rp); break;
-      case 3: ef_p_tile<3, true>(ws, L, t, g, e, A, ppart, rp); break;
-      default: ef_p_tile<4, true>(ws, L, t, g, e, A, ppart, rp); break;
+      case 1: ef_p_tile<1, true>(ws, L, t, g, e, A, ppart, rp, ps); break;
+      case 2: ef_p_tile<2, true>(ws, L, t, g, e, A, ppart, rp, ps); break;
+      case 3: ef_p_tile<3, true>(ws, L, t, g, e, A, ppart, rp, ps); break;
+      default: ef_p_tile<4, true>(ws, L, t, g, e, A, ppart, rp, ps); break;
     }
   } else {
     switch (r) {
-      case 1: ef_p_tile<1, false>(ws, L, t, g, e, A, ppart, rp); break;
-      case 2: ef_p_tile<2, false>(ws, L, t, g, e, A, ppart, rp); break;
-      case 3: ef_p_tile<3, false>(ws, L, t, g, e, A, ppart, rp); break;
-      default: ef_p_tile<4, false>(ws, L, t, g, e, A, ppart, rp); break;
+      case 1: ef_p_tile<1, false>(ws, L, t, g, e, A, ppart, rp, ps); break;
+      case 2: ef_p_tile<2, false>(ws, L, t, g, e, A, ppart, rp, ps); break;
+      case 3: ef_p_tile<3, false>(ws, L, t, g, e, A, ppart, rp, ps); break;
+      default: ef_p_tile<4, false>(ws, L, t, g, e, A, ppart, rp, ps); break;
     }
   }
 }
@@ -374,18 +383,24 @@ __global__ __launch_bounds__(kOrthThreads) void psgd_orth_kernel(const Ws ws, co
 
 template <int R, bool V4>
 __device__ void q_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const float* __restrict__ e,
-                       float* __restrict__ qpart, float (*red)[16][64]) {
+                       float* __restrict__ qpart, float (*red)[16][64], float (*ps)[kMaxRank]) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int col[4]; bool cm[4];
   lane_cols<V4>(t.col0, lane, L.cols, col, cm);
+  {
+    // the tile's rows of P^ go to LDS with one load per thread
+    const int pr = threadIdx.x >> 2, pk = threadIdx.x & 3;
+    const int i = t.row0 + pr;
+    ps[pr][pk] = (i < L.rows && pk < R) ? ws.Phat[L.p_off + (int64_t)i * ws.rmax + pk] : 0.f;
+  }
+  __syncthreads();
   float acc[4][R];
 #pragma unroll
   for (int v = 0; v < 4; ++v)
 #pragma unroll
     for (int k = 0; k < R; ++k) acc[v][k] = 0.f;
   const int row_end = min(t.row0 + kMatRows, L.rows);
-  const float* __restrict__ ph = ws.Phat + L.p_off;
   constexpr int B = 4;   // rows in flight per wave (8 is no faster, 16 is slower)
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float d[B][4];
@@ -400,7 +415,7 @@ __device__ void q_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const 
       if (i < row_end) {
         float p[R];
 #pragma unroll
-        for (int k = 0; k < R; ++k) p[k] = ph[(int64_t)i * ws.rmax + k];
+        for (int k = 0; k < R; ++k) p[k] = ps[i - t.row0][k];
 #pragma unroll
         for (int v = 0; v < 4; ++v)
 #pragma unroll
@@ -431,6 +446,7 @@ __device__ void q_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const 
 
 __global__ __launch_bounds__(256) void psgd_q_kernel(const Ws ws, int w0) {
   __shared__ float red[4][16][64];
+  __shared__ float ps[kMatRows][kMaxRank];
   const int w = w0 + blockIdx.y;
   const MatTile t = ws.mtiles[blockIdx.x];
   const LayerDev& L = ws.layers[t.layer];
@@ -439,17 +455,17 @@ __global__ __launch_bounds__(256) void psgd_q_kernel(const Ws ws, int w0) {
   float* qpart = ws.Qpart + (int64_t)w * ws.qpart_stride;
   if (L.vec4) {
     switch (r) {
-      case 1: q_tile<1, true>(ws, L, t, e, qpart, red); break;
-      case 2: q_tile<2, true>(ws, L, t, e, qpart, red); break;
-      case 3: q_tile<3, true>(ws, L, t, e, qpart, red); break;
-      default: q_tile<4, true>(ws, L, t, e, qpart, red); break;
+      case 1: q_tile<1, true>(ws, L, t, e, qpart, red, ps); break;
+      case 2: q_tile<2, true>(ws, L, t, e, qpart, red, ps); break;
+      case 3: q_tile<3, true>(ws, L, t, e, qpart, red, ps); break;
+      default: q_tile<4, true>(ws, L, t, e, qpart, red, ps); break;
     }
   } else {
     switch (r) {
-      case 1: q_tile<1, false>(ws, L, t, e, qpart, red); break;
-      case 2: q_tile<2, false>(ws, L, t, e, qpart, red); break;
-      case 3: q_tile<3, false>(ws, L, t, e, qpart, red); break;
-      default: q_tile<4, false>(ws, L, t, e, qpart, red); break;
+      case 1: q_tile<1, false>(ws, L, t, e, qpart, red, ps); break;
+      case 2: q_tile<2, false>(ws, L, t, e, qpart, red, ps); break;
+      case 3: q_tile<3, false>(ws, L, t, e, qpart, red, ps); break;
+      default: q_tile<4, false>(ws, L, t, e, qpart, red, ps); break;
     }
   }
 }
