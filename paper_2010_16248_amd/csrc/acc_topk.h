@@ -291,11 +291,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   uint32_t glo = 0x7ffffff0u;                              // no bin matches without a guess
   if (SELECT && !ZB && guess != kNoGuess) glo = max(guess, 1u);
-  // the batched path leaves Delta of the previous step in e: its kept entries are dropped here
-  const bool pend = ((*ws.tpending >> w) & 1u) != 0u;      // uniform over the workgroup
-  PrevSel ps = {0u, 0u, 0u, 0u, 0u};
-  if (pend) ps = load_prev_sel(ws, wl, quarter_slot(ws, L, w, ft.start >> kTileShift, wave));
-  // two groups per lane are requested before the histograms are cleared
+  // two groups per lane are requested before anything else
   constexpr int U = 2;
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
   float4 gc[U], ec[U], ac[U];
@@ -306,6 +302,11 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
     ec[u] = ld_span<AL>(e, tg, span, q);
     ac[u] = A ? ld_span<AL, kStreamA>(A, tg, span, q) : zero4;
   }
+  // the batched path leaves Delta of the previous step in e: its kept entries are dropped here.
+  // The previous selection is requested whether or not it is needed, so that its loads do not
+  // wait for the load of the mask.
+  PrevSel ps = load_prev_sel(ws, wl, quarter_slot(ws, L, w, ft.start >> kTileShift, wave));
+  const bool pend = ((*ws.tpending >> w) & 1u) != 0u;      // uniform over the workgroup
   if (SELECT) {
     for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0;
     if (tid < kSub2) sub2[tid] = 0;
