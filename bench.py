@@ -32,17 +32,17 @@ HBM_PEAK_GBS = 8000.0
 # of this file (summaries under profiles/); None until measured for a workload.
 # Key: (workload, W, dominant kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 648641334,      # profiles/hbm_traffic_resnet18_topk.md
-    ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635927304,     # profiles/hbm_traffic_resnet18_powersgd.md
-    ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416744227,        # profiles/hbm_traffic_vgg19_powersgd.md
+    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 648666319,      # profiles/hbm_traffic_resnet18_topk.md
+    ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635821219,     # profiles/hbm_traffic_resnet18_powersgd.md
+    ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416690931,        # profiles/hbm_traffic_vgg19_powersgd.md
 }
 
 # Counted traffic of all kernels of one step (sum of the per-kernel averages in the same summaries;
 # kernels that run once per window or on demand left out).  Key: (workload, W).
 MEASURED_STEP_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4): 648641334 + 271286539 + 47400793 + 16774368 + 4664759 + 2292559,
-    ("resnet18_powersgd", 4): 635927304 + 191292948 + 12202811 + 3365133 + 47509184,
-    ("vgg19_powersgd", 1): 416744227 + 88423742 + 6228142 + 1781383 + 86512973,
+    ("resnet18_topk", 4): 648666319 + 271295755 + 47391782 + 16779488 + 4665373 + 2288668,
+    ("resnet18_powersgd", 4): 635821219 + 191291310 + 12204859 + 3375373 + 47522599,
+    ("vgg19_powersgd", 1): 416690931 + 88422805 + 6230189 + 1791623 + 86575641,
 }
 
 # Both compression levels are used while timing: the gradient statistics are stationary (every
