@@ -66,6 +66,28 @@ __device__ __forceinline__ void store_row(float* __restrict__ p, int64_t rowbase
   }
 }
 
+// The rows of Q (zero-padded to kMaxRank columns) of the four columns a lane owns.  With
+// rmax = 4 a row is one aligned 16-byte load (q_off is then a multiple of four floats); sixteen
+// single-word loads at a 64-byte stride between lanes kept the texture path busy for longer than
+// the rows of the tile themselves.
+__device__ __forceinline__ void load_q_rows(const Ws& ws, const LayerDev& L, const int (&col)[4],
+                                            const bool (&cm)[4], float (&q)[4][kMaxRank]) {
+  if (ws.rmax == kMaxRank) {                                // uniform
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (cm[v]) t = *reinterpret_cast<const float4*>(ws.Q + L.q_off + (int64_t)col[v] * kMaxRank);
+      q[v][0] = t.x; q[v][1] = t.y; q[v][2] = t.z; q[v][3] = t.w;
+    }
+    return;
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int k = 0; k < kMaxRank; ++k)
+      q[v][k] = (cm[v] && k < ws.rmax) ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
+}
+
 // ---- phase 0: Delta = g + e (in place of e), A += g (worker 0), P partial = Delta Q ---------
 
 // One entry of P^ Q~^T: sum_k p[k] q[k] over all kMaxRank columns, where the caller has set p[k]
@@ -97,11 +119,7 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
     ps[pr][pk] = (i < L.rows && pk < rp) ? ws.Phat[L.p_off + (int64_t)i * ws.rmax + pk] : 0.f;
   }
   float q[4][kMaxRank];
-#pragma unroll
-  for (int v = 0; v < 4; ++v)
-#pragma unroll
-    for (int k = 0; k < kMaxRank; ++k)
-      q[v][k] = (cm[v] && k < ws.rmax) ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
+  load_q_rows(ws, L, col, cm, q);
 
   if (rp > 0) __syncthreads();                             // uniform over the workgroup
   const int row_end = min(t.row0 + kMatRows, L.rows);
@@ -519,11 +537,7 @@ __device__ void decomp_tile(const Ws& ws, const LayerDev& L, const MatTile& t, f
     ps[pr][pk] = (i < row_end && pk < r) ? ph[(int64_t)i * ws.rmax + pk] : 0.f;
   }
   float q[4][kMaxRank];
-#pragma unroll
-  for (int v = 0; v < 4; ++v)
-#pragma unroll
-    for (int k = 0; k < kMaxRank; ++k)
-      q[v][k] = (cm[v] && k < ws.rmax) ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
+  load_q_rows(ws, L, col, cm, q);
   __syncthreads();
   constexpr int B = 4;
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
