@@ -34,7 +34,7 @@ struct LayerDev {
   int32_t pad0, pad1;
   int64_t qoff;          // slot of the layer's first wave quarter in the per-worker quarter arrays
                          // (4 * tile0 + layer index: one spare slot per layer for the totals)
-  int64_t q_off;         // into Q      (cols * rmax floats)
+  int64_t q_off;         // into Q      (cols rows of kMaxRank floats, zero beyond rmax)
   int64_t p_off;         // into Phat   (rows * rmax floats)
   int64_t ppart_off;     // into one worker's P partials (n_colchunks * rows * rmax)
   int64_t qpart_off;     // into one worker's Q partials (n_rowblocks * cols * rmax)

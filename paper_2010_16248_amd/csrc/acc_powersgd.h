@@ -66,26 +66,17 @@ __device__ __forceinline__ void store_row(float* __restrict__ p, int64_t rowbase
   }
 }
 
-// The rows of Q (zero-padded to kMaxRank columns) of the four columns a lane owns.  With
-// rmax = 4 a row is one aligned 16-byte load (q_off is then a multiple of four floats); sixteen
-// single-word loads at a 64-byte stride between lanes kept the texture path busy for longer than
-// the rows of the tile themselves.
+// The rows of Q (kMaxRank floats each on the device, zero beyond rmax) of the four columns a lane
+// owns: one aligned 16-byte load per row.  (Sixteen single-word loads at a 64-byte stride between
+// lanes kept the texture path busy for longer than the rows of the tile themselves.)
 __device__ __forceinline__ void load_q_rows(const Ws& ws, const LayerDev& L, const int (&col)[4],
                                             const bool (&cm)[4], float (&q)[4][kMaxRank]) {
-  if (ws.rmax == kMaxRank) {                                // uniform
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (cm[v]) t = *reinterpret_cast<const float4*>(ws.Q + L.q_off + (int64_t)col[v] * kMaxRank);
-      q[v][0] = t.x; q[v][1] = t.y; q[v][2] = t.z; q[v][3] = t.w;
-    }
-    return;
+  for (int v = 0; v < 4; ++v) {
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (cm[v]) t = *reinterpret_cast<const float4*>(ws.Q + L.q_off + (int64_t)col[v] * kMaxRank);
+    q[v][0] = t.x; q[v][1] = t.y; q[v][2] = t.z; q[v][3] = t.w;
   }
-#pragma unroll
-  for (int v = 0; v < 4; ++v)
-#pragma unroll
-    for (int k = 0; k < kMaxRank; ++k)
-      q[v][k] = (cm[v] && k < ws.rmax) ? ws.Q[L.q_off + (int64_t)col[v] * ws.rmax + k] : 0.f;
 }
 
 // ---- phase 0: Delta = g + e (in place of e), A += g (worker 0), P partial = Delta Q ---------
@@ -495,7 +486,7 @@ __device__ __forceinline__ void qmean_col(const Ws& ws, const LayerDev& L, int c
   float q[R];
   mean_of_partials<R>(ws.Qpart + L.qpart_off + (int64_t)c * ws.rmax, ws.qpart_stride, ws.W,
                       L.n_rowblocks, (int64_t)L.cols * ws.rmax, q);
-  float* dst = ws.Q + L.q_off + (int64_t)c * ws.rmax;
+  float* dst = ws.Q + L.q_off + (int64_t)c * kMaxRank;    // rows of Q are kMaxRank floats apart
 #pragma unroll
   for (int k = 0; k < R; ++k) dst[k] = q[k];
 }

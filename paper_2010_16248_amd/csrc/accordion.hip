@@ -38,7 +38,9 @@ struct Plan {
   std::vector<int32_t> matlayers;
   int32_t rmax = 0;
   int64_t N = 0, e_stride = 0;
-  int64_t q_total = 0, p_total = 0, ppart_stride = 0, qpart_stride = 0, vec_total = 0;
+  int64_t q_total = 0;   // floats of Q in the caller's layout (rows of rmax floats)
+  int64_t q_dev = 0;     // floats of Q on the device: every row padded to kMaxRank floats
+  int64_t p_total = 0, ppart_stride = 0, qpart_stride = 0, vec_total = 0;
   int64_t pay_stride = 0, q_stride = 0;
   // workspace regions
   Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
@@ -134,8 +136,9 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
         d.rank[1] = std::max(1, std::min(c->rank_crit, cap));
         d.n_colchunks = (l.cols + kMatCols - 1) / kMatCols;
         d.n_rowblocks = (l.rows + kMatRows - 1) / kMatRows;
-        d.q_off = p.q_total;
+        d.q_off = p.q_dev;
         p.q_total += (int64_t)l.cols * p.rmax;
+        p.q_dev += (int64_t)l.cols * kMaxRank;
         d.p_off = p.p_total;
         p.p_total += (int64_t)l.rows * p.rmax;
         d.ppart_off = p.ppart_stride;
@@ -203,7 +206,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
   reg(p.r_sq_part, c->detector == ACC_DETECT_MSDR ? 8 * ntile : 0);
   reg(p.r_bstate, 4 * 8);
   if (c->method == ACC_POWERSGD) {
-    reg(p.r_Q, 4 * p.q_total);
+    reg(p.r_Q, 4 * p.q_dev);
     reg(p.r_Phat, 4 * p.p_total);
     reg(p.r_Ppart, 4 * p.ppart_stride * W);
     reg(p.r_Qpart, 4 * p.qpart_stride * W);
@@ -505,6 +508,27 @@ void end_step(acc_ctx* c) {
   c->agg0 = c->agg1 = false;
 }
 
+// Q between the caller's layout (every matrix layer's cols x rmax block, layers in order) and the
+// device layout (rows padded to kMaxRank floats, so that a row is one aligned 16-byte load).
+int copy_q(acc_ctx* c, float* host, bool to_host) {
+  const Plan& p = c->plan;
+  if (p.q_dev == 0) return ACC_OK;
+  std::vector<float> dev((size_t)p.q_dev, 0.f);
+  if (to_host) ACC_HIP(c, hipMemcpy(dev.data(), c->ws.Q, 4 * dev.size(), hipMemcpyDeviceToHost));
+  size_t hp = 0;
+  for (const int li : p.matlayers) {
+    const LayerDev& L = p.layers[(size_t)li];
+    for (int j = 0; j < L.cols; ++j)
+      for (int k = 0; k < p.rmax; ++k) {
+        float& d = dev[(size_t)L.q_off + (size_t)j * kMaxRank + k];
+        if (to_host) host[hp] = d; else d = host[hp];
+        ++hp;
+      }
+  }
+  if (!to_host) ACC_HIP(c, hipMemcpy(c->ws.Q, dev.data(), 4 * dev.size(), hipMemcpyHostToDevice));
+  return ACC_OK;
+}
+
 size_t state_bytes_of(const acc_ctx* c) {
   const Plan& p = c->plan;
   const size_t L = (size_t)c->cfg.n_layers;
@@ -636,7 +660,10 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ACC_HIP(c, up(p.r_matlayers, p.matlayers.data()));
     std::vector<int32_t> lv((size_t)cfg->n_layers, cfg->initial_level);
     ACC_HIP(c, up(p.r_level, lv.data()));
-    if (cfg->method == ACC_POWERSGD && p.q_total > 0) ACC_HIP(c, up(p.r_Q, q_init_host));
+    if (cfg->method == ACC_POWERSGD && p.q_total > 0) {
+      const int rq = copy_q(c, const_cast<float*>(q_init_host), false);
+      if (rq != ACC_OK) return rq;
+    }
     if (cfg->method == ACC_TOPK) {
       std::vector<uint32_t> none((size_t)2 * nl_ * cfg->n_workers, kNoGuess);
       ACC_HIP(c, up(p.r_guess, none.data()));
@@ -908,13 +935,13 @@ int32_t accordion_get_factors(acc_ctx* c, int32_t layer, float* p_hat_host, floa
   r = std::max(0, std::min(r, c->plan.rmax));
   *rank_out = r;
   const int rmax = c->plan.rmax;
-  std::vector<float> tp((size_t)L.rows * rmax), tq((size_t)L.cols * rmax);
+  std::vector<float> tp((size_t)L.rows * rmax), tq((size_t)L.cols * kMaxRank);
   ACC_HIP(c, hipMemcpy(tp.data(), c->ws.Phat + L.p_off, 4 * tp.size(), hipMemcpyDeviceToHost));
   ACC_HIP(c, hipMemcpy(tq.data(), c->ws.Q + L.q_off, 4 * tq.size(), hipMemcpyDeviceToHost));
   for (int i = 0; i < L.rows; ++i)
     for (int k = 0; k < r; ++k) p_hat_host[(size_t)i * r + k] = tp[(size_t)i * rmax + k];
   for (int j = 0; j < L.cols; ++j)
-    for (int k = 0; k < r; ++k) q_host[(size_t)j * r + k] = tq[(size_t)j * rmax + k];
+    for (int k = 0; k < r; ++k) q_host[(size_t)j * r + k] = tq[(size_t)j * kMaxRank + k];
   return ACC_OK;
 }
 
@@ -1003,7 +1030,11 @@ static int32_t state_copy(acc_ctx* c, char* host, bool to_host) {
   };
   for (int w = 0; w < c->cfg.n_workers; ++w) ACC_HIP(c, cp(c->ws.e + (size_t)w * p.e_stride, N4));
   ACC_HIP(c, cp(c->ws.A, N4));
-  if (c->cfg.method == ACC_POWERSGD) ACC_HIP(c, cp(c->ws.Q, 4 * (size_t)p.q_total));
+  if (c->cfg.method == ACC_POWERSGD) {
+    const int rq = copy_q(c, reinterpret_cast<float*>(host), to_host);
+    if (rq != ACC_OK) return rq;
+    host += 4 * (size_t)p.q_total;
+  }
   // batch-size mode: micro-steps summed so far, in the slot the next micro-step reads
   if (c->cfg.method == ACC_BATCH) ACC_HIP(c, cp(c->ws.bstate + 4 * (c->step_id & 1u), 4));
   ACC_HIP(c, cp(c->ws.norm_old, L4));
