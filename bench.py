@@ -33,16 +33,16 @@ HBM_PEAK_GBS = 8000.0
 # Key: (workload, W, dominant kernel).
 MEASURED_TRAFFIC_BYTES = {
     ("resnet18_topk", 4, "topk_ef_hist_kernel"): 648666319,      # profiles/hbm_traffic_resnet18_topk.md
-    ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635821219,     # profiles/hbm_traffic_resnet18_powersgd.md
-    ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416690931,        # profiles/hbm_traffic_vgg19_powersgd.md
+    ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635204002,     # profiles/hbm_traffic_resnet18_powersgd.md
+    ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416681771,        # profiles/hbm_traffic_vgg19_powersgd.md
 }
 
 # Counted traffic of all kernels of one step (sum of the per-kernel averages in the same summaries;
 # kernels that run once per window or on demand left out).  Key: (workload, W).
 MEASURED_STEP_TRAFFIC_BYTES = {
     ("resnet18_topk", 4): 648666319 + 271295755 + 47391782 + 16779488 + 4665373 + 2288668,
-    ("resnet18_powersgd", 4): 635821219 + 191291310 + 12204859 + 3375373 + 47522599,
-    ("vgg19_powersgd", 1): 416690931 + 88422805 + 6230189 + 1791623 + 86575641,
+    ("resnet18_powersgd", 4): 635204002 + 191300968 + 12184368 + 3354890 + 47512869,
+    ("vgg19_powersgd", 1): 416681771 + 88425656 + 6209709 + 1771143 + 86578303,
 }
 
 # Both compression levels are used while timing: the gradient statistics are stationary (every
@@ -318,6 +318,9 @@ def main():
     if not is_batch:
         alg = algorithmic_bytes_step(w, layers, W, [words_last // 2])
         cnt = MEASURED_STEP_TRAFFIC_BYTES.get((args.workload, W))
+        if args.fused_update:                # weights and velocity read and written instead of D written
+            alg += 12 * N
+            cnt = None                       # counted for the storing sink only
         step_bw = {"algorithmic_bytes": alg, "algorithmic_GB/s": round(alg / (ms_per_step * 1e-3) / 1e9, 1),
                    "counted_bytes": cnt,
                    "counted_GB/s": round(cnt / (ms_per_step * 1e-3) / 1e9, 1) if cnt else None,
