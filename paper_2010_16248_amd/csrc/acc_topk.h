@@ -372,6 +372,13 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
       if (h) atomicAdd(&gh[b], h);
     }
     if (tid < kSub2) ws.t2[((int64_t)w * ws.n_ftiles + tile_id) * kSub2 + tid] = sub2[tid];
+#ifdef ACC_EXP_FENCE
+    __syncthreads();
+    if (tid == 0) {
+      __threadfence();
+      atomicAdd(&ws.overlap[ft.layer], 1ull);
+    }
+#endif
   }
 }
 
@@ -981,22 +988,30 @@ __device__ __forceinline__ QuarterSel load_quarter_sel(const Ws& ws, int w, int 
 }
 
 constexpr int kGroupList = 4 * kWave;   // payload entries one group of a wave can produce
+// A wave's staging list in LDS: kStgStride indices, then kStgStride values.  Slots kGroupList and up
+// take the writes of the lanes' unselected elements (one slot per lane, never read), so that the
+// staging needs no branches.
+constexpr int kStgStride = kGroupList + kWave;
+constexpr int kStgWords = 2 * kStgStride;
 
 // Running state of the ordered compaction of one worker's quarter.
 struct CompactRun { uint32_t eq_run, pos_run; };
 
 // One group of four elements per lane: which are selected, their payload entries, the zeros in e;
 // MEAN adds the kept values to acc.  The payload entries of the group are first put in order into
-// a list in LDS that belongs to the wave (stg, 256 entries), then written out by consecutive lanes
-// to consecutive addresses: stores of single words scattered over the lanes of four instructions
-// cost a quarter of this kernel's time.  An element is selected iff its key >= tsel, where tsel is
-// T for the entries equal to T that are within the tie quota (lowest indices first) and T + 1
-// otherwise; quarters without an entry equal to T never look at ties.
-template <bool AL, bool MEAN, bool DEFER>
-__device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan& span, int64_t layer_offset,
-                                              const QuarterSel& qs, CompactRun& run, float* __restrict__ e,
-                                              int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
-                                              const float4& cur, int lane, float4& acc, uint2* stg) {
+// the wave's list in LDS, then written out by consecutive lanes to consecutive addresses: stores
+// of single words scattered over the lanes of four instructions cost a quarter of this kernel's
+// time.  An element is selected iff its key >= tsel, where tsel is T for the entries equal to T
+// that are within the tie quota (lowest indices first) and T + 1 otherwise; quarters without an
+// entry equal to T never look at ties.  HOLES: the layer keeps more than half of its entries (the
+// values go out dense, the indices name the dropped entries).
+// The pass is bound by the number of vector instructions per group, not by memory: everything
+// per element is kept free of branches.
+template <bool AL, bool MEAN, bool DEFER, bool HOLES>
+__device__ __forceinline__ void compact_group_t(const TileGeom& tg, const WaveSpan& span, int64_t layer_offset,
+                                                const QuarterSel& qs, CompactRun& run, float* __restrict__ e,
+                                                int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
+                                                const float4& cur, int lane, float4& acc, uint32_t* stg) {
   const bool qa = q < span.qend;
   const uint64_t m_span = ballot64(qa);
   const uint32_t T = qs.T;
@@ -1015,59 +1030,80 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     msel[c] = ballot64(key[c] >= tsel[c]) & mv[c];
-    below += lanes_below(msel[c], lane);
+    below = __builtin_amdgcn_mbcnt_hi((uint32_t)(msel[c] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)msel[c], below));
     total += (uint32_t)__popcll(msel[c]);
   }
-  const bool holes = qs.holes != 0u;                        // wave-uniform
-  if (total != 0 || holes) {
-    uint32_t local = below;                                 // place in the group's list
+  if (total != 0 || HOLES) {                                // wave-uniform
     const int32_t i0 = (int32_t)(tg.a0 + 4 * (int64_t)q - layer_offset);
-    float4 z = cur;
     bool sel[4];
+    uint32_t place[4];                                      // of element c in the group's list, if selected
+    uint32_t local = below;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      sel[c] = valid[c] && key[c] >= tsel[c];
-      if (sel[c]) {
-        stg[local] = make_uint2((uint32_t)(i0 + c), __float_as_uint(comp(cur, c)));
-        ++local;
-      } else if (holes && valid[c]) {
+      sel[c] = valid[c] && key[c] >= tsel[c];               // the lane's bit of msel[c]
+      place[c] = local;
+      local += sel[c] ? 1u : 0u;
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t slot = sel[c] ? place[c] : (uint32_t)(kGroupList + lane);
+      if (!HOLES) stg[slot] = (uint32_t)(i0 + c);
+      stg[kStgStride + slot] = __float_as_uint(comp(cur, c));
+      if (HOLES && valid[c] && !sel[c]) {
         // dropped entry number (index - kept before it) of the layer
-        const uint32_t hp = (uint32_t)(i0 + c) - (run.pos_run + local);
+        const uint32_t hp = (uint32_t)(i0 + c) - (run.pos_run + place[c]);
         if (hp < qs.nholes) pidx[hp] = i0 + c;              // always true for consistent state
       }
     }
     __builtin_amdgcn_wave_barrier();                        // the list is complete (LDS is in order per wave)
 #pragma unroll 1
-    for (uint32_t t = lane; t < total; t += kWave) {        // total <= 256: at most four rounds
-      const uint2 pr = stg[t];
+    for (uint32_t t = lane; t < total; t += kWave) {        // total <= 256: at most four rounds, mostly one
+      const uint32_t ix = HOLES ? 0u : stg[t];
+      const uint32_t vb = stg[kStgStride + t];
       const uint32_t pos = run.pos_run + t;
       if (pos < qs.k) {                                     // always true for consistent state
-        // streaming stores: nothing in this step reads the payload again
-        if (!holes) __builtin_nontemporal_store((int32_t)pr.x, &pidx[pos]);
-        __builtin_nontemporal_store(__uint_as_float(pr.y), &pval[pos]);
+        // streaming stores: nothing in this step reads the payload again.  The byte offset is a
+        // 32-bit value (the payload of a worker is far below 4 GiB).
+        const uint32_t boff = pos << 2;
+        if (!HOLES) __builtin_nontemporal_store((int32_t)ix, (int32_t*)((char*)pidx + boff));
+        __builtin_nontemporal_store(__uint_as_float(vb), (float*)((char*)pval + boff));
       }
     }
     __builtin_amdgcn_wave_barrier();
-    if (sel[0]) z.x = 0.f;
-    if (sel[1]) z.y = 0.f;
-    if (sel[2]) z.z = 0.f;
-    if (sel[3]) z.w = 0.f;
     // DEFER: the zeros are not written; the next pass over Delta drops the kept entries itself
-    if (!DEFER && (sel[0] || sel[1] || sel[2] || sel[3])) stq<AL>(e, tg.a0, tg.lo, tg.hi, q, z);
+    if (!DEFER && (sel[0] || sel[1] || sel[2] || sel[3])) {
+      float4 z = cur;
+      if (sel[0]) z.x = 0.f;
+      if (sel[1]) z.y = 0.f;
+      if (sel[2]) z.z = 0.f;
+      if (sel[3]) z.w = 0.f;
+      stq<AL>(e, tg.a0, tg.lo, tg.hi, q, z);
+    }
     run.pos_run += total;
-    if (MEAN) {
-      if (sel[0]) acc.x += cur.x;
-      if (sel[1]) acc.y += cur.y;
-      if (sel[2]) acc.z += cur.z;
-      if (sel[3]) acc.w += cur.w;
+    if (MEAN) {                                             // acc is never -0, so adding +0 changes nothing
+      acc.x += sel[0] ? cur.x : 0.f;
+      acc.y += sel[1] ? cur.y : 0.f;
+      acc.z += sel[2] ? cur.z : 0.f;
+      acc.w += sel[3] ? cur.w : 0.f;
     }
   }
+}
+
+template <bool AL, bool MEAN, bool DEFER>
+__device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan& span, int64_t layer_offset,
+                                              const QuarterSel& qs, CompactRun& run, float* __restrict__ e,
+                                              int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
+                                              const float4& cur, int lane, float4& acc, uint32_t* stg) {
+  if (qs.holes != 0u)                                       // wave-uniform
+    compact_group_t<AL, MEAN, DEFER, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, acc, stg);
+  else
+    compact_group_t<AL, MEAN, DEFER, false>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, acc, stg);
 }
 
 // One worker per grid row; the mean is taken later from the payloads.
 template <bool AL>
 __device__ __forceinline__ void compact_tile(const Ws& ws, int w, const FlatTile& ft, const LayerDev& L,
-                                             const TileGeom& tg, uint2* stg) {
+                                             const TileGeom& tg, uint32_t* stg) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const WaveSpan span = wave_span(tg, wave);
@@ -1100,8 +1136,8 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
     ws.miss_any[w] = 0u;
     atomicAnd(ws.tpending, ~(1u << w));                    // this path writes the residual itself
   }
-  __shared__ uint2 stage[4][kGroupList];
-  uint2* stg = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+  __shared__ uint32_t stage[4][kStgWords];
+  uint32_t* stg = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
   if (tg.aligned) compact_tile<true>(ws, w, ft, L, tg, stg);
   else compact_tile<false>(ws, w, ft, L, tg, stg);
 }
@@ -1112,13 +1148,16 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
 // compaction state of every worker is kept in one lane each.  Delta is read one batch of
 // kMeanBatch workers ahead; one worker per batch keeps the kernel at 59 registers (seven waves per
 // SIMD), which beats deeper prefetch at 117 registers (four waves) by 8 % on ResNet-18 shapes.
-constexpr int kMeanBatch = 1;
+#ifndef ACC_MEAN_AHEAD
+#define ACC_MEAN_AHEAD 1
+#endif
+constexpr int kMeanAhead = ACC_MEAN_AHEAD;
 
 // UPD: the mean is not written out but drives the optimizer step on the weights and the velocity
 // (read at the top of a group, so that they arrive while the workers are compacted).
 template <bool AL, bool UPD>
 __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& ft, const LayerDev& L,
-                                                  const TileGeom& tg, const Sink sink, uint2* stg) {
+                                                  const TileGeom& tg, const Sink sink, uint32_t* stg) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const WaveSpan span = wave_span(tg, wave);
@@ -1137,17 +1176,21 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   uint32_t pos_run_v = mine.gt_before + min(mine.ktie, mine.eq_before);
   const int n = (span.qend - span.qbeg + kWave - 1) / kWave;   // groups of the quarter, wave-uniform
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-  auto load_batch = [&](int j, int wb, float4 (&d)[kMeanBatch]) {
-#pragma unroll
-    for (int u = 0; u < kMeanBatch; ++u) {
-      const int w = wb + u;
-      d[u] = (j < n && w < W) ? ld_span<AL>(e_base + (int64_t)w * e_stride, tg, span, span.qbeg + j * kWave + lane)
-                              : zero4;
-    }
+  // Delta is requested kMeanAhead (group, worker) steps ahead of its use
+  auto load_step = [&](int j, int w) {
+    return (j < n) ? ld_span<AL>(e_base + (int64_t)w * e_stride, tg, span, span.qbeg + j * kWave + lane) : zero4;
   };
-  float4 cur[kMeanBatch], nxt[kMeanBatch];
-  load_batch(0, 0, cur);
+  float4 pf[kMeanAhead];
+  int jn = 0, wn = 0;                                        // the next step to request
+#pragma unroll
+  for (int a = 0; a < kMeanAhead; ++a) {
+    pf[a] = load_step(jn, wn);
+    if (++wn == W) { wn = 0; ++jn; }
+  }
   const float fw = (float)W;
+  // x / W and x * (1 / W) are the same real number when W is a power of two, so both round alike
+  const bool pow2 = (W & (W - 1)) == 0;
+  const float rw = 1.0f / fw;
   for (int j = 0; j < n; ++j) {
     const int q = span.qbeg + j * kWave + lane;
     float4 acc = zero4;
@@ -1156,39 +1199,34 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
       wq = ld_span<AL, true>(sink.wt, tg, span, q);        // weights and velocity: once per step
       vq = ld_span<AL, true>(sink.vel, tg, span, q);
     }
-    for (int wb = 0; wb < W; wb += kMeanBatch) {
-      int j2 = j, wb2 = wb + kMeanBatch;
-      if (wb2 >= W) { wb2 = 0; ++j2; }
-      load_batch(j2, wb2, nxt);
+    for (int w = 0; w < W; ++w) {
+      const float4 cur = pf[0];
 #pragma unroll
-      for (int u = 0; u < kMeanBatch; ++u) {
-        const int w = wb + u;
-        if (w < W) {                                        // wave-uniform
-          QuarterSel qs;
-          qs.T = (uint32_t)__builtin_amdgcn_readlane((int)mine.T, w);
-          qs.ktie = (uint32_t)__builtin_amdgcn_readlane((int)mine.ktie, w);
-          qs.alleq = (uint32_t)__builtin_amdgcn_readlane((int)mine.alleq, w);
-          qs.k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
-          qs.holes = (uint32_t)__builtin_amdgcn_readlane((int)mine.holes, w);
-          qs.nholes = (uint32_t)__builtin_amdgcn_readlane((int)mine.nholes, w);
-          qs.eq_here = (uint32_t)__builtin_amdgcn_readlane((int)mine.eq_here, w);
-          qs.gt_before = 0u;
-          qs.eq_before = 0u;
-          CompactRun run;
-          run.eq_run = (uint32_t)__builtin_amdgcn_readlane((int)eq_run_v, w);
-          run.pos_run = (uint32_t)__builtin_amdgcn_readlane((int)pos_run_v, w);
-          float* __restrict__ e = e_base + (int64_t)w * e_stride;
-          int32_t* pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
-          float* pval = pay_val + (int64_t)w * pay_stride + pay_off;
-          compact_group<AL, true, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur[u], lane, acc, stg);
-          if (lane == w) { eq_run_v = run.eq_run; pos_run_v = run.pos_run; }
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < kMeanBatch; ++u) cur[u] = nxt[u];
+      for (int a = 0; a + 1 < kMeanAhead; ++a) pf[a] = pf[a + 1];
+      pf[kMeanAhead - 1] = load_step(jn, wn);
+      if (++wn == W) { wn = 0; ++jn; }
+      QuarterSel qs;
+      qs.T = (uint32_t)__builtin_amdgcn_readlane((int)mine.T, w);
+      qs.ktie = (uint32_t)__builtin_amdgcn_readlane((int)mine.ktie, w);
+      qs.alleq = (uint32_t)__builtin_amdgcn_readlane((int)mine.alleq, w);
+      qs.k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
+      qs.holes = (uint32_t)__builtin_amdgcn_readlane((int)mine.holes, w);
+      qs.nholes = (uint32_t)__builtin_amdgcn_readlane((int)mine.nholes, w);
+      qs.eq_here = (uint32_t)__builtin_amdgcn_readlane((int)mine.eq_here, w);
+      qs.gt_before = 0u;
+      qs.eq_before = 0u;
+      CompactRun run;
+      run.eq_run = (uint32_t)__builtin_amdgcn_readlane((int)eq_run_v, w);
+      run.pos_run = (uint32_t)__builtin_amdgcn_readlane((int)pos_run_v, w);
+      float* __restrict__ e = e_base + (int64_t)w * e_stride;
+      int32_t* pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
+      float* pval = pay_val + (int64_t)w * pay_stride + pay_off;
+      compact_group<AL, true, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, acc, stg);
+      if (lane == w) { eq_run_v = run.eq_run; pos_run_v = run.pos_run; }
     }
     if (q < span.qend) {
-      const float4 v = make_float4(acc.x / fw, acc.y / fw, acc.z / fw, acc.w / fw);
+      const float4 v = pow2 ? make_float4(acc.x * rw, acc.y * rw, acc.z * rw, acc.w * rw)
+                            : make_float4(acc.x / fw, acc.y / fw, acc.z / fw, acc.w / fw);
       if (UPD) {
         nesterov4(v, wq, vq, sink);
         stq<AL, true>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
@@ -1212,8 +1250,8 @@ __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink
   if (blockIdx.x == 0 && threadIdx.x < ws.W) ws.miss_any[threadIdx.x] = 0u;
   // every e_w keeps Delta_w: the kept entries are dropped by the next pass over it
   if (blockIdx.x == 0 && threadIdx.x == 0) *ws.tpending = ws.W == 32 ? 0xffffffffu : ((1u << ws.W) - 1u);
-  __shared__ uint2 stage[4][kGroupList];
-  uint2* stg = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+  __shared__ uint32_t stage[4][kStgWords];
+  uint32_t* stg = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
   if (tg.aligned) compact_mean_tile<true, UPD>(ws, ft, L, tg, sink, stg);
   else compact_mean_tile<false, UPD>(ws, ft, L, tg, sink, stg);
 }
