@@ -187,6 +187,20 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask, int /*lane*/) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// The calling lane's bit of a wave-uniform lane mask, as a predicate (the mask itself becomes the
+// condition of the instruction that uses it; no per-lane shift).
+__device__ __forceinline__ bool lane_bit(uint64_t mask) { return __builtin_amdgcn_inverse_ballot_w64(mask); }
+
+// A wave-uniform value, moved to a scalar register.
+__device__ __forceinline__ uint32_t rfl(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+
+// Keeps a lane mask in scalar registers across a join of control flow (otherwise the compiler
+// carries the predicate behind it per lane, as a 0 / 1 vector value it has to compare again).
+__device__ __forceinline__ uint64_t scalar_mask(uint64_t mask) {
+  asm volatile("" : "+s"(mask));
+  return mask;
+}
+
 __device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
 // ---- masked 16-byte access on a flat buffer ---------------------------------------

@@ -202,23 +202,35 @@ __device__ __forceinline__ uint32_t stage_flush(const Ws& ws, int64_t qslot, con
   return nz;
 }
 
-// Thresholds of the four elements a lane holds of one group: an element is selected iff its key
-// >= tsel.  That is T + 1 (or T when every entry equal to T is selected), except for the entries
-// equal to T that are within the tie quota ktie, counted in index order over the layer: eq_run is
-// the number of entries equal to T before this group (advanced here); quarters without an entry
-// equal to T (eq_here == 0) never look at ties.  mv: lane masks of the valid elements per
-// component; valid: the calling lane's bits of them.
-__device__ __forceinline__ void group_thresholds(uint32_t T, uint32_t ktie, uint32_t alleq, uint32_t eq_here,
-                                                 uint32_t& eq_run, const uint32_t (&key)[4],
-                                                 const bool (&valid)[4], const uint64_t (&mv)[4], int lane,
-                                                 uint32_t (&tsel)[4]) {
-  const uint32_t t_all = alleq ? T : T + 1u;
+// What every group of a quarter needs from the selection of its (worker, layer): t_all = T when
+// every entry equal to T is selected, else T + 1; ties: the quarter holds entries equal to T of
+// which only some are selected (then t_all = T + 1).  Both are wave-uniform.
+struct SelCommon { uint32_t t_all; bool ties; };
+struct SelTies { uint32_t T, ktie; };
+
+__device__ __forceinline__ SelCommon sel_common(uint32_t T, uint32_t alleq, uint32_t eq_here) {
+  SelCommon c;
+  c.t_all = alleq ? T : T + 1u;
+  c.ties = eq_here != 0u && alleq == 0u;
+  return c;
+}
+
+// Which of the four elements a lane holds of one group are selected, as lane masks per component:
+// the keys >= t_all and, where ties matter, the entries equal to T within the tie quota ktie,
+// counted in index order over the layer: eq_run is the number of entries equal to T before this
+// group (advanced here).  mv: lane masks of the valid elements per component; tie(): T and ktie,
+// fetched only when needed.
+template <class TieF>
+__device__ __forceinline__ void group_select(const SelCommon& sc, TieF tie, uint32_t& eq_run,
+                                             const uint32_t (&key)[4], const uint64_t (&mv)[4], int lane,
+                                             uint64_t (&msel)[4]) {
 #pragma unroll
-  for (int c = 0; c < 4; ++c) tsel[c] = t_all;
-  if (eq_here != 0u && !alleq) {                            // wave-uniform
+  for (int c = 0; c < 4; ++c) msel[c] = ballot64(key[c] >= sc.t_all) & mv[c];
+  if (sc.ties) {                                            // wave-uniform
+    const SelTies t = tie();
     uint64_t meq[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) meq[c] = ballot64(key[c] == T) & mv[c];
+    for (int c = 0; c < 4; ++c) meq[c] = ballot64(key[c] == t.T) & mv[c];
     if ((meq[0] | meq[1] | meq[2] | meq[3]) != 0) {
       // the tie quota is used up in index order
       uint32_t rank = eq_run;
@@ -230,25 +242,28 @@ __device__ __forceinline__ void group_thresholds(uint32_t T, uint32_t ktie, uint
       }
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const bool iseq = valid[c] && key[c] == T;
-        tsel[c] = (iseq && rank < ktie) ? T : T + 1u;
+        const bool iseq = lane_bit(meq[c]);
+        msel[c] |= ballot64(iseq && rank < t.ktie);
         rank += iseq ? 1u : 0u;
       }
       eq_run += total;
     }
   }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) msel[c] = scalar_mask(msel[c]);
 }
 
 // The selection of the previous step as the next pass over Delta needs it to zero the kept
 // entries (the residual is not written by the compaction of the batched path: see tpending).
-struct PrevSel { uint32_t T, ktie, alleq, eq_here, eq_run; };
+struct PrevSel { uint32_t T, ktie, eq_run; SelCommon sc; };
 
 __device__ __forceinline__ PrevSel load_prev_sel(const Ws& ws, int64_t wl, int64_t qslot) {
   const SelState* sp = ws.sel + wl;
   PrevSel p;
-  p.T = sp->T; p.ktie = sp->ktie; p.alleq = sp->alleq;
-  p.eq_run = ws.eqpre[qslot];
-  p.eq_here = ws.eqpre[qslot + 1] - p.eq_run;             // the layer's last slot holds the total
+  // wave-uniform values: into scalar registers, whatever kind of load fetched them
+  p.T = rfl(sp->T); p.ktie = rfl(sp->ktie);
+  p.eq_run = rfl(ws.eqpre[qslot]);
+  p.sc = sel_common(p.T, rfl(sp->alleq), rfl(ws.eqpre[qslot + 1]) - p.eq_run);   // the layer's last slot: the total
   return p;
 }
 
@@ -256,20 +271,18 @@ __device__ __forceinline__ PrevSel load_prev_sel(const Ws& ws, int64_t wl, int64
 template <bool AL>
 __device__ __forceinline__ float4 drop_kept(const TileGeom& tg, int q, bool qa, uint64_t m_span, PrevSel& ps,
                                             float4 d, int lane) {
-  uint32_t key[4], tsel[4];
-  bool valid[4];
-  uint64_t mv[4];
+  uint32_t key[4];
+  uint64_t mv[4], msel[4];
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
-    valid[c] = elem_valid<AL>(tg, q, c, qa);
     mv[c] = valid_mask<AL>(tg, q, c, qa, m_span);
     key[c] = key_of(comp(d, c));
   }
-  group_thresholds(ps.T, ps.ktie, ps.alleq, ps.eq_here, ps.eq_run, key, valid, mv, lane, tsel);
-  if (valid[0] && key[0] >= tsel[0]) d.x = 0.f;
-  if (valid[1] && key[1] >= tsel[1]) d.y = 0.f;
-  if (valid[2] && key[2] >= tsel[2]) d.z = 0.f;
-  if (valid[3] && key[3] >= tsel[3]) d.w = 0.f;
+  group_select(ps.sc, [&]() { SelTies t; t.T = ps.T; t.ktie = ps.ktie; return t; }, ps.eq_run, key, mv, lane, msel);
+  if (lane_bit(msel[0])) d.x = 0.f;
+  if (lane_bit(msel[1])) d.y = 0.f;
+  if (lane_bit(msel[2])) d.z = 0.f;
+  if (lane_bit(msel[3])) d.w = 0.f;
   return d;
 }
 
@@ -965,27 +978,35 @@ __device__ __host__ __forceinline__ bool payload_has_holes(uint32_t n, uint32_t 
 
 // What a wave needs to know about one worker's selection in its quarter.
 struct QuarterSel {
-  uint32_t T, ktie, alleq, k;
-  uint32_t holes, nholes;            // holes = 0: payload = (index, value) of the kept entries; 1: the
+  uint32_t T, ktie, k;
+  uint32_t t_all;                    // see SelCommon
+  uint32_t flags;                    // bit 0: ties matter in this quarter (see SelCommon); bit 1: the
                                      // layer keeps more than half: payload = the k values in index
                                      // order + the nholes = n - k indices of the dropped entries
+                                     // (else: payload = (index, value) of the kept entries)
+  uint32_t nholes;
   uint32_t gt_before, eq_before;     // selected-above-T and equal-to-T entries in the quarters before
-  uint32_t eq_here;                  // entries equal to T in this quarter
 };
 
 __device__ __forceinline__ QuarterSel load_quarter_sel(const Ws& ws, int w, int layer, int64_t qslot_local) {
   const SelState* sp = ws.sel + (int64_t)w * ws.L + layer;
   const int64_t qs = (int64_t)w * ws.q_stride + qslot_local;
   QuarterSel s;
-  s.T = sp->T; s.ktie = sp->ktie; s.alleq = sp->alleq; s.k = sp->k;
+  s.T = sp->T; s.ktie = sp->ktie; s.k = sp->k;
   const uint32_t n_layer = (uint32_t)ws.layers[layer].rows * (uint32_t)ws.layers[layer].cols;
-  s.holes = payload_has_holes(n_layer, s.k) ? 1u : 0u;
   s.nholes = n_layer - min(s.k, n_layer);
   s.gt_before = ws.gtpre[qs];
   s.eq_before = ws.eqpre[qs];
-  s.eq_here = ws.eqpre[qs + 1] - s.eq_before;              // the layer's last slot holds the total
+  const SelCommon sc = sel_common(s.T, sp->alleq, ws.eqpre[qs + 1] - s.eq_before);   // last slot: the total
+  s.t_all = sc.t_all;
+  s.flags = (sc.ties ? 1u : 0u) | (payload_has_holes(n_layer, s.k) ? 2u : 0u);
   return s;
 }
+
+// The part of it every group uses (wave-uniform) ...
+struct GroupSel { uint32_t t_all, k, flags; };
+// ... and the part only groups with ties or layers with a hole list use.
+struct GroupRare { uint32_t T, ktie, nholes; };
 
 constexpr int kGroupList = 4 * kWave;   // payload entries one group of a wave can produce
 // A wave's staging list in LDS: kStgStride indices, then kStgStride values.  Slots kGroupList and up
@@ -1001,103 +1022,118 @@ struct CompactRun { uint32_t eq_run, pos_run; };
 // MEAN adds the kept values to acc.  The payload entries of the group are first put in order into
 // the wave's list in LDS, then written out by consecutive lanes to consecutive addresses: stores
 // of single words scattered over the lanes of four instructions cost a quarter of this kernel's
-// time.  An element is selected iff its key >= tsel, where tsel is T for the entries equal to T
-// that are within the tie quota (lowest indices first) and T + 1 otherwise; quarters without an
-// entry equal to T never look at ties.  HOLES: the layer keeps more than half of its entries (the
+// time.  HOLES: the layer keeps more than half of its entries (the
 // values go out dense, the indices name the dropped entries).
 // The pass is bound by the number of vector instructions per group, not by memory: everything
 // per element is kept free of branches.
-template <bool AL, bool MEAN, bool DEFER, bool HOLES>
-__device__ __forceinline__ void compact_group_t(const TileGeom& tg, const WaveSpan& span, int64_t layer_offset,
-                                                const QuarterSel& qs, CompactRun& run, float* __restrict__ e,
-                                                int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
-                                                const float4& cur, int lane, float4& acc, uint32_t* stg) {
-  const bool qa = q < span.qend;
-  const uint64_t m_span = ballot64(qa);
-  const uint32_t T = qs.T;
-  bool valid[4];
-  uint64_t mv[4];
-  uint32_t key[4], tsel[4];
+// The second half of compact_group: the selection is known (msel: lane masks of the selected
+// elements per component, below: selected elements of the group in the lanes before this one,
+// total: in all lanes); mv: lane masks of the valid elements.
+template <bool AL, bool MEAN, bool DEFER, bool HOLES, class RareF>
+__device__ __forceinline__ void compact_selected(const TileGeom& tg, int64_t layer_offset, const GroupSel& gs,
+                                                 RareF rare, CompactRun& run, float* __restrict__ e,
+                                                 int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
+                                                 const float4& cur, int lane, float4& acc, uint32_t* stg,
+                                                 const uint64_t (&msel)[4], const uint64_t (&mv)[4],
+                                                 uint32_t below, uint32_t total) {
+  const int32_t i0 = (int32_t)(tg.a0 + 4 * (int64_t)q - layer_offset);
+  bool sel[4];
+  uint32_t place[4];                                        // of element c in the group's list, if selected
+  uint32_t local = below;
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
-    valid[c] = elem_valid<AL>(tg, q, c, qa);
-    mv[c] = valid_mask<AL>(tg, q, c, qa, m_span);
-    key[c] = key_of(comp(cur, c));
+    sel[c] = lane_bit(msel[c]);
+    place[c] = local;
+    local += sel[c] ? 1u : 0u;
   }
-  group_thresholds(T, qs.ktie, qs.alleq, qs.eq_here, run.eq_run, key, valid, mv, lane, tsel);
-  uint64_t msel[4];
-  uint32_t below = 0, total = 0;
+  uint32_t nholes = 0u;
+  if (HOLES) nholes = rare().nholes;
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
-    msel[c] = ballot64(key[c] >= tsel[c]) & mv[c];
-    below = __builtin_amdgcn_mbcnt_hi((uint32_t)(msel[c] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)msel[c], below));
-    total += (uint32_t)__popcll(msel[c]);
+    const uint32_t slot = sel[c] ? place[c] : (uint32_t)(kGroupList + lane);
+    if (!HOLES) stg[slot] = (uint32_t)(i0 + c);
+    stg[kStgStride + slot] = __float_as_uint(comp(cur, c));
+    if (HOLES && lane_bit(mv[c] & ~msel[c])) {
+      // dropped entry number (index - kept before it) of the layer
+      const uint32_t hp = (uint32_t)(i0 + c) - (run.pos_run + place[c]);
+      if (hp < nholes) pidx[hp] = i0 + c;                   // always true for consistent state
+    }
   }
-  if (total != 0 || HOLES) {                                // wave-uniform
-    const int32_t i0 = (int32_t)(tg.a0 + 4 * (int64_t)q - layer_offset);
-    bool sel[4];
-    uint32_t place[4];                                      // of element c in the group's list, if selected
-    uint32_t local = below;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      sel[c] = valid[c] && key[c] >= tsel[c];               // the lane's bit of msel[c]
-      place[c] = local;
-      local += sel[c] ? 1u : 0u;
+  __builtin_amdgcn_wave_barrier();                          // the list is complete (LDS is in order per wave)
+  auto flush = [&](uint32_t t) {
+    const uint32_t ix = HOLES ? 0u : stg[t];
+    const uint32_t vb = stg[kStgStride + t];
+    const uint32_t pos = run.pos_run + t;
+    if (t < total && pos < gs.k) {                          // pos < k: always true for consistent state
+      // streaming stores: nothing in this step reads the payload again.  The byte offset is a
+      // 32-bit value (the payload of a worker is far below 4 GiB).
+      const uint32_t boff = pos << 2;
+      if (!HOLES) __builtin_nontemporal_store((int32_t)ix, (int32_t*)((char*)pidx + boff));
+      __builtin_nontemporal_store(__uint_as_float(vb), (float*)((char*)pval + boff));
     }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const uint32_t slot = sel[c] ? place[c] : (uint32_t)(kGroupList + lane);
-      if (!HOLES) stg[slot] = (uint32_t)(i0 + c);
-      stg[kStgStride + slot] = __float_as_uint(comp(cur, c));
-      if (HOLES && valid[c] && !sel[c]) {
-        // dropped entry number (index - kept before it) of the layer
-        const uint32_t hp = (uint32_t)(i0 + c) - (run.pos_run + place[c]);
-        if (hp < qs.nholes) pidx[hp] = i0 + c;              // always true for consistent state
-      }
-    }
-    __builtin_amdgcn_wave_barrier();                        // the list is complete (LDS is in order per wave)
+  };
+  flush((uint32_t)lane);                                    // total <= 256: four rounds at most, mostly one
+  if (total > (uint32_t)kWave) {
 #pragma unroll 1
-    for (uint32_t t = lane; t < total; t += kWave) {        // total <= 256: at most four rounds, mostly one
-      const uint32_t ix = HOLES ? 0u : stg[t];
-      const uint32_t vb = stg[kStgStride + t];
-      const uint32_t pos = run.pos_run + t;
-      if (pos < qs.k) {                                     // always true for consistent state
-        // streaming stores: nothing in this step reads the payload again.  The byte offset is a
-        // 32-bit value (the payload of a worker is far below 4 GiB).
-        const uint32_t boff = pos << 2;
-        if (!HOLES) __builtin_nontemporal_store((int32_t)ix, (int32_t*)((char*)pidx + boff));
-        __builtin_nontemporal_store(__uint_as_float(vb), (float*)((char*)pval + boff));
-      }
-    }
-    __builtin_amdgcn_wave_barrier();
-    // DEFER: the zeros are not written; the next pass over Delta drops the kept entries itself
-    if (!DEFER && (sel[0] || sel[1] || sel[2] || sel[3])) {
-      float4 z = cur;
-      if (sel[0]) z.x = 0.f;
-      if (sel[1]) z.y = 0.f;
-      if (sel[2]) z.z = 0.f;
-      if (sel[3]) z.w = 0.f;
-      stq<AL>(e, tg.a0, tg.lo, tg.hi, q, z);
-    }
-    run.pos_run += total;
-    if (MEAN) {                                             // acc is never -0, so adding +0 changes nothing
-      acc.x += sel[0] ? cur.x : 0.f;
-      acc.y += sel[1] ? cur.y : 0.f;
-      acc.z += sel[2] ? cur.z : 0.f;
-      acc.w += sel[3] ? cur.w : 0.f;
-    }
+    for (uint32_t t0 = kWave; t0 < total; t0 += kWave) flush(t0 + lane);
+  }
+  __builtin_amdgcn_wave_barrier();
+  // DEFER: the zeros are not written; the next pass over Delta drops the kept entries itself
+  if (!DEFER && (sel[0] || sel[1] || sel[2] || sel[3])) {
+    float4 z = cur;
+    if (sel[0]) z.x = 0.f;
+    if (sel[1]) z.y = 0.f;
+    if (sel[2]) z.z = 0.f;
+    if (sel[3]) z.w = 0.f;
+    stq<AL>(e, tg.a0, tg.lo, tg.hi, q, z);
+  }
+  run.pos_run += total;
+  if (MEAN) {                                               // acc is never -0, so adding +0 changes nothing
+    acc.x += sel[0] ? cur.x : 0.f;
+    acc.y += sel[1] ? cur.y : 0.f;
+    acc.z += sel[2] ? cur.z : 0.f;
+    acc.w += sel[3] ? cur.w : 0.f;
   }
 }
 
-template <bool AL, bool MEAN, bool DEFER>
+// The selection is taken before the two payload layouts part ways, so that every compare sits next
+// to its ballot (a predicate that crosses a branch is carried as a 0 / 1 value per lane and
+// compared again) and only lane masks in scalar registers cross.
+template <bool AL, bool MEAN, bool DEFER, class RareF>
 __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan& span, int64_t layer_offset,
-                                              const QuarterSel& qs, CompactRun& run, float* __restrict__ e,
-                                              int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
+                                              const GroupSel& gs, RareF rare, CompactRun& run,
+                                              float* __restrict__ e, int32_t* __restrict__ pidx,
+                                              float* __restrict__ pval, int q, uint64_t m_span,
                                               const float4& cur, int lane, float4& acc, uint32_t* stg) {
-  if (qs.holes != 0u)                                       // wave-uniform
-    compact_group_t<AL, MEAN, DEFER, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, acc, stg);
-  else
-    compact_group_t<AL, MEAN, DEFER, false>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, acc, stg);
+  const bool qa = lane_bit(m_span);                         // m_span: the lanes whose group q is in the span
+  uint64_t mv[4], msel[4];
+  uint32_t key[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    mv[c] = valid_mask<AL>(tg, q, c, qa, m_span);
+    key[c] = key_of(comp(cur, c));
+  }
+  SelCommon sc;
+  sc.t_all = gs.t_all;
+  sc.ties = (gs.flags & 1u) != 0u;
+  group_select(sc, [&]() { const GroupRare r = rare(); SelTies t; t.T = r.T; t.ktie = r.ktie; return t; },
+               run.eq_run, key, mv, lane, msel);
+  uint32_t below = 0, total = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    below = __builtin_amdgcn_mbcnt_hi((uint32_t)(msel[c] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)msel[c], below));
+    total += (uint32_t)__popcll(msel[c]);
+  }
+  if ((gs.flags & 2u) != 0u) {                              // wave-uniform
+    uint64_t mvs[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) mvs[c] = scalar_mask(mv[c]);
+    compact_selected<AL, MEAN, DEFER, true>(tg, layer_offset, gs, rare, run, e, pidx, pval, q, cur, lane, acc, stg,
+                                            msel, mvs, below, total);
+  } else if (total != 0u) {
+    compact_selected<AL, MEAN, DEFER, false>(tg, layer_offset, gs, rare, run, e, pidx, pval, q, cur, lane, acc, stg,
+                                             msel, mv, below, total);
+  }
 }
 
 // One worker per grid row; the mean is taken later from the payloads.
@@ -1111,9 +1147,13 @@ __device__ __forceinline__ void compact_tile(const Ws& ws, int w, const FlatTile
   float4 cur = ld_span<AL>(e, tg, span, span.qbeg + lane);
   float4 nxt = ld_span<AL>(e, tg, span, span.qbeg + kWave + lane);
   const QuarterSel qs = load_quarter_sel(ws, w, ft.layer, L.qoff + 4 * (int64_t)(ft.start >> kTileShift) + wave);
+  // wave-uniform values: into scalar registers, whatever kind of load fetched them
   CompactRun run;
-  run.eq_run = qs.eq_before;
-  run.pos_run = qs.gt_before + min(qs.ktie, qs.eq_before);
+  run.eq_run = rfl(qs.eq_before);
+  run.pos_run = rfl(qs.gt_before + min(qs.ktie, qs.eq_before));
+  GroupSel gs;
+  gs.t_all = rfl(qs.t_all); gs.k = rfl(qs.k); gs.flags = rfl(qs.flags);
+  auto rare = [&]() { GroupRare r; r.T = rfl(qs.T); r.ktie = rfl(qs.ktie); r.nholes = rfl(qs.nholes); return r; };
   int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
   float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
   const int64_t layer_offset = L.offset;                   // by value: nothing is re-read inside the loop
@@ -1121,7 +1161,8 @@ __device__ __forceinline__ void compact_tile(const Ws& ws, int w, const FlatTile
   for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
     const int q = q0 + lane;
     const float4 nn = ld_span<AL>(e, tg, span, q + 2 * kWave);
-    compact_group<AL, false, false>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, unused, stg);
+    compact_group<AL, false, false>(tg, span, layer_offset, gs, rare, run, e, pidx, pval, q,
+                                    scalar_mask(ballot64(q < span.qend)), cur, lane, unused, stg);
     cur = nxt;
     nxt = nn;
   }
@@ -1145,21 +1186,17 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
 // All workers in worker order, and the dense mean of the kept values: out[i] = (sum over the
 // workers that kept i, from +0, of their value) / W.  The loop runs over the groups of the quarter
 // and, inside, over the workers, so that the sum of one group lives in four registers; the running
-// compaction state of every worker is kept in one lane each.  Delta is read one batch of
-// kMeanBatch workers ahead; one worker per batch keeps the kernel at 59 registers (seven waves per
-// SIMD), which beats deeper prefetch at 117 registers (four waves) by 8 % on ResNet-18 shapes.
-#ifndef ACC_MEAN_AHEAD
-#define ACC_MEAN_AHEAD 1
-#endif
-constexpr int kMeanAhead = ACC_MEAN_AHEAD;
+// compaction state of every worker is kept in one lane each.  The pass is bound by vector
+// instructions, not by latency: requesting Delta more than one (group, worker) step ahead only
+// adds instructions (+1 us per extra step on ResNet-18 shapes).
+constexpr int kMeanAhead = 1;
 
 // UPD: the mean is not written out but drives the optimizer step on the weights and the velocity
 // (read at the top of a group, so that they arrive while the workers are compacted).
 template <bool AL, bool UPD>
 __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& ft, const LayerDev& L,
-                                                  const TileGeom& tg, const Sink sink, uint32_t* stg) {
+                                                  const TileGeom& tg, const Sink sink, uint32_t* stg, int wave) {
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const WaveSpan span = wave_span(tg, wave);
   const int64_t qslot_local = L.qoff + 4 * (int64_t)(ft.start >> kTileShift) + wave;
   const int W = ws.W;
@@ -1170,10 +1207,17 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   int32_t* const pay_idx = ws.pay_idx;
   float* const pay_val = ws.pay_val;
   // lane w holds worker w's selection state for this quarter
-  QuarterSel mine = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+  QuarterSel mine = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
   if (lane < W) mine = load_quarter_sel(ws, lane, ft.layer, qslot_local);
   uint32_t eq_run_v = mine.eq_before;
   uint32_t pos_run_v = mine.gt_before + min(mine.ktie, mine.eq_before);
+  auto sel_of = [&](int w) {
+    GroupSel gs;
+    gs.t_all = (uint32_t)__builtin_amdgcn_readlane((int)mine.t_all, w);
+    gs.k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
+    gs.flags = (uint32_t)__builtin_amdgcn_readlane((int)mine.flags, w);
+    return gs;
+  };
   const int n = (span.qend - span.qbeg + kWave - 1) / kWave;   // groups of the quarter, wave-uniform
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
   // Delta is requested kMeanAhead (group, worker) steps ahead of its use
@@ -1193,35 +1237,36 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   const float rw = 1.0f / fw;
   for (int j = 0; j < n; ++j) {
     const int q = span.qbeg + j * kWave + lane;
+    const uint64_t m_span = scalar_mask(ballot64(q < span.qend));   // the same for every worker
     float4 acc = zero4;
     float4 wq = zero4, vq = zero4;
     if (UPD) {
       wq = ld_span<AL, true>(sink.wt, tg, span, q);        // weights and velocity: once per step
       vq = ld_span<AL, true>(sink.vel, tg, span, q);
     }
-    for (int w = 0; w < W; ++w) {
+    auto one_worker = [&](int w, const GroupSel& gs, CompactRun& run) {
       const float4 cur = pf[0];
 #pragma unroll
       for (int a = 0; a + 1 < kMeanAhead; ++a) pf[a] = pf[a + 1];
       pf[kMeanAhead - 1] = load_step(jn, wn);
       if (++wn == W) { wn = 0; ++jn; }
-      QuarterSel qs;
-      qs.T = (uint32_t)__builtin_amdgcn_readlane((int)mine.T, w);
-      qs.ktie = (uint32_t)__builtin_amdgcn_readlane((int)mine.ktie, w);
-      qs.alleq = (uint32_t)__builtin_amdgcn_readlane((int)mine.alleq, w);
-      qs.k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
-      qs.holes = (uint32_t)__builtin_amdgcn_readlane((int)mine.holes, w);
-      qs.nholes = (uint32_t)__builtin_amdgcn_readlane((int)mine.nholes, w);
-      qs.eq_here = (uint32_t)__builtin_amdgcn_readlane((int)mine.eq_here, w);
-      qs.gt_before = 0u;
-      qs.eq_before = 0u;
-      CompactRun run;
-      run.eq_run = (uint32_t)__builtin_amdgcn_readlane((int)eq_run_v, w);
-      run.pos_run = (uint32_t)__builtin_amdgcn_readlane((int)pos_run_v, w);
       float* __restrict__ e = e_base + (int64_t)w * e_stride;
       int32_t* pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
       float* pval = pay_val + (int64_t)w * pay_stride + pay_off;
-      compact_group<AL, true, true>(tg, span, layer_offset, qs, run, e, pidx, pval, q, cur, lane, acc, stg);
+      auto rare = [&]() {
+        GroupRare r;
+        r.T = (uint32_t)__builtin_amdgcn_readlane((int)mine.T, w);
+        r.ktie = (uint32_t)__builtin_amdgcn_readlane((int)mine.ktie, w);
+        r.nholes = (uint32_t)__builtin_amdgcn_readlane((int)mine.nholes, w);
+        return r;
+      };
+      compact_group<AL, true, true>(tg, span, layer_offset, gs, rare, run, e, pidx, pval, q, m_span, cur, lane, acc, stg);
+    };
+    for (int w = 0; w < W; ++w) {
+      CompactRun run;
+      run.eq_run = (uint32_t)__builtin_amdgcn_readlane((int)eq_run_v, w);
+      run.pos_run = (uint32_t)__builtin_amdgcn_readlane((int)pos_run_v, w);
+      one_worker(w, sel_of(w), run);
       if (lane == w) { eq_run_v = run.eq_run; pos_run_v = run.pos_run; }
     }
     if (q < span.qend) {
@@ -1238,9 +1283,15 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   }
 }
 
+// The waves of this pass are independent of each other (one quarter of a tile each), so the
+// workgroup can be smaller than a tile: kMeanWaves quarters per workgroup (two: 1 us faster than
+// four on ResNet-18 shapes, the same as one).
+constexpr int kMeanWaves = 2;
+constexpr int kMeanSplit = 4 / kMeanWaves;                  // workgroups per tile
+
 template <bool UPD>
 __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink) {
-  const FlatTile ft = ws.ftiles[blockIdx.x];
+  const FlatTile ft = ws.ftiles[blockIdx.x / kMeanSplit];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -1250,18 +1301,20 @@ __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink
   if (blockIdx.x == 0 && threadIdx.x < ws.W) ws.miss_any[threadIdx.x] = 0u;
   // every e_w keeps Delta_w: the kept entries are dropped by the next pass over it
   if (blockIdx.x == 0 && threadIdx.x == 0) *ws.tpending = ws.W == 32 ? 0xffffffffu : ((1u << ws.W) - 1u);
-  __shared__ uint32_t stage[4][kStgWords];
-  uint32_t* stg = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
-  if (tg.aligned) compact_mean_tile<true, UPD>(ws, ft, L, tg, sink, stg);
-  else compact_mean_tile<false, UPD>(ws, ft, L, tg, sink, stg);
+  __shared__ uint32_t stage[kMeanWaves][kStgWords];
+  const int lw = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint32_t* stg = stage[lw];
+  const int wave = (int)(blockIdx.x % kMeanSplit) * kMeanWaves + lw;   // the quarter of the tile
+  if (tg.aligned) compact_mean_tile<true, UPD>(ws, ft, L, tg, sink, stg, wave);
+  else compact_mean_tile<false, UPD>(ws, ft, L, tg, sink, stg, wave);
 }
 
-__global__ __launch_bounds__(256) void topk_compact_mean_kernel(const Ws ws, const Sink sink) {
+__global__ __launch_bounds__(kMeanWaves * kWave) void topk_compact_mean_kernel(const Ws ws, const Sink sink) {
   compact_mean_body<false>(ws, sink);
 }
 
 // The same pass with the optimizer step in place of the store of the mean.
-__global__ __launch_bounds__(256) void topk_compact_update_kernel(const Ws ws, const Sink sink) {
+__global__ __launch_bounds__(kMeanWaves * kWave) void topk_compact_update_kernel(const Ws ws, const Sink sink) {
   compact_mean_body<true>(ws, sink);
 }
 

@@ -472,8 +472,8 @@ int launch_batch_micro(acc_ctx* c, const Sink& sink) {
 
 int launch_topk_compact_mean(acc_ctx* c, const Sink& sink) {
   const Ws& ws = c->ws;
-  if (sink.wt) ACC_LAUNCH(c, topk_compact_update_kernel, dim3(ws.n_ftiles), dim3(256), ws, sink);
-  else ACC_LAUNCH(c, topk_compact_mean_kernel, dim3(ws.n_ftiles), dim3(256), ws, sink);
+  if (sink.wt) ACC_LAUNCH(c, topk_compact_update_kernel, dim3(ws.n_ftiles * kMeanSplit), dim3(kMeanWaves * kWave), ws, sink);
+  else ACC_LAUNCH(c, topk_compact_mean_kernel, dim3(ws.n_ftiles * kMeanSplit), dim3(kMeanWaves * kWave), ws, sink);
   return ACC_OK;
 }
 

@@ -89,6 +89,24 @@ def test_multi_tile_layers_with_ties(case):
     gpu.destroy()
 
 
+@pytest.mark.parametrize("W", [2, 3, 4, 8])
+def test_mean_of_subnormal_values_rounds_like_a_division(W):
+    """Kept values so small that their mean is subnormal: the mean must round exactly like the
+    oracle's division by W (for W a power of two the kernel multiplies by 1 / W, which is the same
+    real number), over several steps so that subnormal residuals feed back as well."""
+    print(f"case subnormal mean W={W}", flush=True)
+    layers = wl.make_layers([(1, 2 * 8192 + 31, 0), (9, 333, 1)])
+    N = wl.total_params(layers)
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 50, 10)
+    rng = np.random.default_rng([13, W])
+    tiny = np.float32(1.4e-45)
+    for step in range(3):
+        grads = [(rng.integers(-40, 41, N).astype(np.float32) * tiny) for _ in range(W)]
+        assert all(np.all(np.abs(g) < 1.2e-38) for g in grads)
+        _check_step(gpu, ora, grads, f"subnormal W={W} step {step}", check_state=(step == 2))
+    gpu.destroy()
+
+
 def test_guessed_bins_hit_drift_and_miss():
     """The error-feedback pass stages the keys of two level-1 bins on a guess.  Over many steps
     with a stationary distribution the guess must hit (no more re-staging); a slow drift of the
