@@ -256,6 +256,14 @@ __device__ __forceinline__ float4 ldq(const float* __restrict__ p, int64_t a0, i
   return ld_quad(p, a0 + 4 * (int64_t)q, lo, hi);
 }
 
+// Group q of a tile with AL, loaded whatever lane asks: the caller has clamped q into the tile
+// (0 <= q < nquads) and masks what it does with the value.  Costs an integer min / max where
+// the predicated load costs four moves of zeros and a branch around the load.
+template <bool STREAM = false>
+__device__ __forceinline__ float4 ldq_clamped(const float* __restrict__ p, int64_t a0, int q) {
+  return STREAM ? ld16_stream(p + a0 + 4 * (int64_t)q) : *reinterpret_cast<const float4*>(p + a0 + 4 * (int64_t)q);
+}
+
 template <bool AL, bool STREAM = false>
 __device__ __forceinline__ void stq(float* __restrict__ p, int64_t a0, int64_t lo, int64_t hi, int q,
                                     float4 v) {

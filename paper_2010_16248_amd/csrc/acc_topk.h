@@ -1249,8 +1249,11 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   const int n = (span.qend - span.qbeg + kWave - 1) / kWave;   // groups of the quarter, wave-uniform
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
   // Delta is requested kMeanAhead (group, worker) steps ahead of its use
+  // (past the end of the quarter an aligned tile re-reads its last group: nobody looks at it)
   auto load_step = [&](int j, int w) {
-    return (j < n) ? ld_span<AL>(e_base + (int64_t)w * e_stride, tg, span, span.qbeg + j * kWave + lane) : zero4;
+    const float* __restrict__ e = e_base + (int64_t)w * e_stride;
+    if (AL) return ldq_clamped(e, tg.a0, max(0, min(span.qbeg + j * kWave + lane, span.qend - 1)));
+    return (j < n) ? ld_span<AL>(e, tg, span, span.qbeg + j * kWave + lane) : zero4;
   };
   float4 pf[kMeanAhead];
   int jn = 0, wn = 0;                                        // the next step to request
