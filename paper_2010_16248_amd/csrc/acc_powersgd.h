@@ -240,25 +240,32 @@ __device__ __forceinline__ float block_sum_orth(float v, float (*red)[kOrthWaves
 // they are issued eight at a time (unconditionally, from clamped addresses, so that all eight are
 // in flight together) and added in a fixed order (worker-major).  The calling thread takes the
 // addends first, first + stride, ...
-template <int R>
+template <int R, int U = 8>
 __device__ __forceinline__ void sum_of_partials(const float* __restrict__ base, int64_t wstride, int W,
                                                 int nparts, int64_t pstride, int first, int stride,
-                                                float (&acc)[R]) {
+                                                float (&acc)[R], bool vec4 = false) {
 #pragma unroll
   for (int k = 0; k < R; ++k) acc[k] = 0.f;
   const int np = W * nparts;
-  for (int p0 = first; p0 < np; p0 += 8 * stride) {
-    float v[8][R];
+  for (int p0 = first; p0 < np; p0 += U * stride) {
+    float v[U][R];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int p = min(p0 + u * stride, np - 1);
       const int w = p / nparts, c = p - w * nparts;
       const float* src = base + (int64_t)w * wstride + (int64_t)c * pstride;
+      if (vec4) {                                           // rows of four floats, 16-byte aligned: one load
+        const float4 x = *reinterpret_cast<const float4*>(src);
+        const float xs[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
-      for (int k = 0; k < R; ++k) v[u][k] = src[k];
+        for (int k = 0; k < R; ++k) v[u][k] = xs[k];
+      } else {
+#pragma unroll
+        for (int k = 0; k < R; ++k) v[u][k] = src[k];
+      }
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int k = 0; k < R; ++k) acc[k] += (p0 + u * stride < np) ? v[u][k] : 0.f;
   }
@@ -276,6 +283,11 @@ __device__ __forceinline__ void mean_of_partials(const float* __restrict__ base,
 // length stays zero.  Layers of up to kOrthThreads rows live in registers, one row per thread
 // (short layers: several threads share the partial sums of a row and one of them keeps it);
 // taller ones in global memory (each thread only ever touches its own rows).
+#ifndef ACC_ORTH_LOADS
+#define ACC_ORTH_LOADS 12
+#endif
+constexpr int kOrthLoads = ACC_ORTH_LOADS;   // partial rows a thread has in flight
+
 template <int R>
 __device__ void orth_layer(const Ws& ws, const LayerDev& L, float (*red)[kOrthWaves], float* psum) {
   const int n = L.rows;
@@ -294,8 +306,8 @@ __device__ void orth_layer(const Ws& ws, const LayerDev& L, float (*red)[kOrthWa
 #pragma unroll
     for (int k = 0; k < R; ++k) part[k] = 0.f;
     if (row < n)
-      sum_of_partials<R>(pbase + (int64_t)row * ws.rmax, ws.ppart_stride, ws.W, L.n_colchunks, pstride, sub, tpr,
-                         part);
+      sum_of_partials<R, kOrthLoads>(pbase + (int64_t)row * ws.rmax, ws.ppart_stride, ws.W, L.n_colchunks, pstride,
+                                     sub, tpr, part, ws.rmax == 4);
 #pragma unroll
     for (int k = 0; k < R; ++k) psum[tid * kMaxRank + k] = part[k];
     __syncthreads();
