@@ -100,7 +100,7 @@ struct Ws {
   SelState* sel;               // W x L
   uint32_t* hist2m;            // W x L x 64: level-2 counts of b1 of a layer whose guess missed
   uint32_t* miss_any;          // W: some multi-tile layer of the worker missed its guessed bins this step
-  uint2* b1hist;               // W x L x 2 (level): {b1, step number} of the last step at this level
+  uint2* b1hist;               // W x L x 2 (level): {b1 | (last move + 64) << 16, step number} of the last step at this level
   uint32_t* guess;             // W x L x 2 (level): lower of the two level-1 bins staged by pass A
   uint4* qinfo;                // W x q_stride: per wave quarter {entries above the staged bins,
                                //   keys of the lower bin, keys of the upper bin, exact zeros}

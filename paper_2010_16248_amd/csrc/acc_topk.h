@@ -44,7 +44,11 @@ constexpr int kPickWaves = kPickThreads / kWave;
 static_assert(kHistBins == 2 * kPickThreads, "the pick kernels load two histogram bins per thread");
 constexpr int kQListCap = 16;            // keys of bin (b1, b2) listed per wave quarter
 constexpr int kL2Bins = 64;              // level 2: key bits 19..14
-constexpr int kSub2 = 2 * kL2Bins;       // a tile's level-2 counts of the two guessed bins
+#ifndef ACC_GUESS_BINS
+#define ACC_GUESS_BINS 3
+#endif
+constexpr int kGuessBins = ACC_GUESS_BINS;   // adjacent level-1 bins staged by the first pass
+constexpr int kSub2 = kGuessBins * kL2Bins;  // a tile's level-2 counts of the guessed bins
 __device__ __forceinline__ uint32_t bin2_of(uint32_t key) { return (key >> 14) & 0x3fu; }
 __device__ __forceinline__ uint32_t bin3_of(uint32_t key) { return (key >> 6) & 0xffu; }
 __device__ __forceinline__ uint32_t bin4_of(uint32_t key) { return key & 0x3fu; }
@@ -143,15 +147,15 @@ __device__ __forceinline__ int64_t quarter_slot(const Ws& ws, const LayerDev& L,
   return (int64_t)w * ws.q_stride + L.qoff + 4 * (int64_t)tl + wave;
 }
 
-// Staging of one component's keys in the wave's LDS list (the keys of both guessed bins share
-// one list: a key carries its bin).  The counts keep running past the capacity (the counting
-// kernel sees the overflow).  n_in, n1: wave-uniform; v_hi, v_nz: per lane, summed over the
-// wave when the quarter is flushed.
-struct StageCounts { uint32_t n_in, n1, v_hi, v_nz; };
+// Staging of one component's keys in the wave's LDS list (the keys of all guessed bins share
+// one list: a key carries its bin).  The count keeps running past the capacity (the counting
+// kernel sees the overflow).  n_in: wave-uniform; v_hi, v_nz: per lane, summed over the wave when
+// the quarter is flushed.
+struct StageCounts { uint32_t n_in, v_hi, v_nz; };
 
 constexpr int kSegCap = 2 * kSubCap;     // staged keys per wave quarter
 
-// Pass A: keys of the bins glo and glo + 1 (glo >= 1, so a staged key is never an exact zero;
+// Pass A: keys of the bins glo .. glo + kGuessBins - 1 (glo >= 1, so a staged key is never an exact zero;
 // zeros are not counted here: a threshold in bin 0 counts as a missed guess and the re-staging
 // pass counts them).  mv: lane mask of the valid elements; valid: the calling lane's bit of it.
 // Every ballot is taken from a single compare and combined with the other masks in scalar
@@ -159,12 +163,11 @@ constexpr int kSegCap = 2 * kSubCap;     // staged keys per wave quarter
 __device__ __forceinline__ void stage_two_bins(uint32_t* st, uint32_t* sub2, StageCounts& c, uint64_t mv,
                                                bool valid, uint32_t key, uint32_t glo, int lane) {
   const uint32_t bin = key >> 20;
-  const uint32_t rel = bin - glo;                          // 0 / 1 for the staged bins
-  c.v_hi += (valid && (int32_t)rel > 1) ? 1u : 0u;
-  c.n1 += (uint32_t)__popcll(ballot64(rel == 1u) & mv);
-  const uint64_t m = ballot64(rel <= 1u) & mv;
+  const uint32_t rel = bin - glo;                          // 0 .. kGuessBins - 1 for the staged bins
+  c.v_hi += (valid && (int32_t)rel > kGuessBins - 1) ? 1u : 0u;
+  const uint64_t m = ballot64(rel <= (uint32_t)(kGuessBins - 1)) & mv;
   if (m != 0) {
-    if (valid && rel <= 1u) {
+    if (valid && rel <= (uint32_t)(kGuessBins - 1)) {
       const uint32_t pos = c.n_in + lanes_below(m, lane);
       if (pos < (uint32_t)kSegCap) st[pos] = key;
       atomicAdd(&sub2[rel * kL2Bins + bin2_of(key)], 1u);
@@ -190,15 +193,27 @@ __device__ __forceinline__ void stage_one_bin(uint32_t* st, uint32_t* sub2, Stag
   }
 }
 
-// qinfo of the quarter: {entries above the staged bins, staged keys, of which in the upper bin,
-// exact zeros}.  Returns the number of exact zeros (the same value in every lane).
+// qinfo of the quarter: {entries above the staged bins, staged keys, of which in the bins glo + 1
+// (low half) and glo + 2 (high half; a quarter has 2048 entries), exact zeros}.  The staged keys
+// are counted per bin here, from the list, and not as they come (fewer instructions; when the
+// list overflowed the counts are not used: the quarter is read again from Delta).  glo: lowest
+// staged bin of pass A; the one-bin passes give the bin itself.  Returns the number of exact
+// zeros (the same value in every lane).
 __device__ __forceinline__ uint32_t stage_flush(const Ws& ws, int64_t qslot, const uint32_t* st,
-                                                const StageCounts& c, int lane) {
+                                                const StageCounts& c, uint32_t glo, int lane) {
   uint32_t* seg = ws.seg + qslot * kSegCap;
   const uint32_t m = min(c.n_in, (uint32_t)kSegCap);
-  for (uint32_t i = lane; i < m; i += kWave) seg[i] = st[i];
+  uint32_t v1 = 0, v2 = 0;
+  for (uint32_t i = lane; i < m; i += kWave) {
+    const uint32_t key = st[i];
+    seg[i] = key;
+    const uint32_t rel = (key >> 20) - glo;
+    v1 += (rel == 1u) ? 1u : 0u;
+    v2 += (rel == 2u) ? 1u : 0u;
+  }
+  const uint32_t n12 = wave_sum_u32(v1 | (v2 << 16));      // both sums stay below 2^16
   const uint32_t n_hi = wave_sum_u32(c.v_hi), nz = wave_sum_u32(c.v_nz);
-  if (lane == 0) ws.qinfo[qslot] = make_uint4(n_hi, c.n_in, c.n1, nz);
+  if (lane == 0) ws.qinfo[qslot] = make_uint4(n_hi, c.n_in, n12, nz);
   return nz;
 }
 
@@ -325,7 +340,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
     if (tid < kSub2) sub2[tid] = 0;
     __syncthreads();
   }
-  StageCounts cnt = {0u, 0u, 0u, 0u};                      // wave-uniform
+  StageCounts cnt = {0u, 0u, 0u};                          // n_in: wave-uniform
   for (int q0 = span.qbeg; q0 < span.qend; q0 += U * kWave) {
     float4 gn[U], en[U], an[U];
 #pragma unroll
@@ -377,7 +392,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
     for (int u = 0; u < U; ++u) { gc[u] = gn[u]; ec[u] = en[u]; ac[u] = an[u]; }
   }
   if (SELECT) {
-    stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, lane);
+    stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, ZB ? 0u : glo, lane);
     __syncthreads();
     uint32_t* gh = ws.hist1 + wl * kHistBins;                // bin 0 stays empty: the pick kernel derives it
     for (int b = tid; b < kHistBins; b += kFlatThreads) {
@@ -433,7 +448,7 @@ __device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile
   __syncthreads();                                         // the previous tile's counts have been written
   if (tid < kSub2) sub2[tid] = 0;
   __syncthreads();
-  StageCounts cnt = {0u, 0u, 0u, 0u};
+  StageCounts cnt = {0u, 0u, 0u};
   float4 cur = ld_span<AL>(e, tg, span, span.qbeg + lane);
   for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
     const int q = q0 + lane;
@@ -446,7 +461,7 @@ __device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile
                     key_of(comp(cur, c)), b1, lane);
     cur = nxt;
   }
-  const uint32_t nz = stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, lane);
+  const uint32_t nz = stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, b1, lane);
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   if (lane == 0 && nz) atomicAdd(&ws.sel[wl].zeros, nz);
   __syncthreads();
@@ -517,7 +532,9 @@ __device__ __forceinline__ uint32_t for_quarter_keys(const Ws& ws, const LayerDe
     for (int ch = 0; ch < kFirstChunks; ++ch)
       if (n > (uint32_t)(ch * kWave))                                                       // uniform condition
         f(k.chunk[ch], (uint32_t)(ch * kWave + lane) < n && (k.chunk[ch] >> 20) == b1);
-    return k.info.x + (side == 0u ? k.info.z : 0u);
+    // entries of the staged bins above b1: bins glo + 1 and glo + 2 are counted in the two halves of z
+    const uint32_t n1 = k.info.z & 0xffffu, n2 = k.info.z >> 16;
+    return k.info.x + (side == 0u ? n1 + n2 : (side == 1u ? n2 : 0u));
   }
   FlatTile ft;
   ft.layer = 0;
@@ -641,11 +658,11 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   // the next step) and the tiles' level-2 counts of BOTH guessed bins.
   uint32_t* gh = ws.hist1 + wl * kHistBins;
   uint32_t h0 = gh[tid], h1 = gh[tid + kPickThreads];
-  constexpr int kStripes = kPickThreads / kSub2;            // 8 tiles at a time
-  const int col = tid & (kSub2 - 1), stripe = tid / kSub2;
+  constexpr int kStripes = kPickThreads / kSub2;            // tiles summed side by side
+  const int col = tid % kSub2, stripe = tid / kSub2;
   const uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_ftiles + L.tile0) * kSub2 + col;
   uint32_t s2 = 0;
-  for (int tl0 = stripe; tl0 < L.ntiles; tl0 += 8 * kStripes) {
+  for (int tl0 = (stripe < kStripes ? stripe : L.ntiles); tl0 < L.ntiles; tl0 += 8 * kStripes) {
     uint32_t v[8];                                          // eight independent loads in flight
 #pragma unroll
     for (int u = 0; u < 8; ++u) v[u] = t2[(int64_t)min(tl0 + u * kStripes, L.ntiles - 1) * kSub2];
@@ -671,8 +688,8 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   __syncthreads();
   pick_bin(hist, k, out, scratch);
   const uint32_t b1 = out[0], need2 = k - out[1];
-  const uint32_t glo = max(guess, 1u);                     // the bins pass A staged: glo, glo + 1
-  const bool hit = guess != kNoGuess && guess != kGuessZero && b1 != 0u && (b1 == glo || b1 == glo + 1u);
+  const uint32_t glo = max(guess, 1u);                     // the bins pass A staged: glo .. glo + kGuessBins - 1
+  const bool hit = guess != kNoGuess && guess != kGuessZero && b1 != 0u && b1 >= glo && b1 - glo < (uint32_t)kGuessBins;
   // bin 0 guessed and found: pass A left what the re-staging pass would (mode 2: staged already)
   const bool zhit = guess == kGuessZero && b1 == 0u;
   const uint32_t side = hit ? b1 - glo : 0u;
@@ -981,19 +998,30 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
   }
   if (tid == 0) {
     sp->T = T; sp->ktie = ktie; sp->alleq = alleq; sp->mode = 0u;
-    // Next step's guess at this level: two adjacent bins.  While the threshold is moving (the
-    // steps after a level switch, when the memory adapts) b1 is extrapolated from the last two
-    // steps and paired with the bin it would reach if the move slowed down; when it rests, b1 is
-    // paired with the neighbour on the side of the threshold.
+    // Next step's guess at this level: kGuessBins adjacent bins.  While the threshold is moving
+    // (the steps after a level switch, when the memory adapts) b1 is extrapolated from the last
+    // two steps.  Three bins: the extrapolated bin and both neighbours.  Two bins: the extrapolated
+    // bin paired with the bin it would reach if the move slowed down, or, when it rests, with the
+    // neighbour on the side of the threshold.
+    // b1hist: (b1 | (last move + 64) << 16, step)
     const uint2 prev = ws.b1hist[wl * 2 + lv];
-    ws.b1hist[wl * 2 + lv] = make_uint2(b1, step_id);
-    int v = (prev.y + 1u == step_id) ? (int)b1 - (int)prev.x : 0;
+    const bool consecutive = prev.y + 1u == step_id;
+    int v = consecutive ? (int)b1 - (int)(prev.x & 0xffffu) : 0;
     v = max(-64, min(64, v));
+    const int pv = consecutive ? (int)(prev.x >> 16) - 64 : 0;   // the move before
+    ws.b1hist[wl * 2 + lv] = make_uint2(b1 | ((uint32_t)(v + 64) << 16), step_id);
     int g = (int)b1;
-    if (v > 0) g = (int)b1 + v - 1;
-    else if (v < 0) g = (int)b1 + v;
-    else if (b2 < (uint32_t)(kL2Bins / 2)) g = (int)b1 - 1;
-    uint32_t glo = (uint32_t)max(0, min(kHistBins - 2, g));
+    if (kGuessBins > 2) {
+      // a single step of one bin may well be taken back; larger moves and moves that go on in
+      // one direction are followed
+      const bool follow = v > 1 || v < -1 || (v != 0 && (v > 0) == (pv > 0) && pv != 0);
+      g = (int)b1 - 1 + (follow ? v : 0);
+    } else {
+      if (v > 0) g = (int)b1 + v - 1;
+      else if (v < 0) g = (int)b1 + v;
+      else if (b2 < (uint32_t)(kL2Bins / 2)) g = (int)b1 - 1;
+    }
+    uint32_t glo = (uint32_t)max(0, min(kHistBins - kGuessBins, g));
     ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero : glo;
   }
 }
