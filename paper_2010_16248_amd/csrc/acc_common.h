@@ -51,7 +51,7 @@ struct SelState {
   uint32_t b1;        // level-1 bin (key bits 30..20) that holds the k-th largest key
   uint32_t need2;     // entries still to be taken from bin b1
   uint32_t mode;      // 0: b1 is one of the guessed bins (or decided); 1: the guess missed
-  uint32_t side;      // half of the quarter segments that holds the keys of b1
+  uint32_t side;      // which of the guessed bins b1 is (0: the lowest)
   uint32_t b2;        // level-2 bin (key bits 19..14) within b1
   uint32_t need3;     // entries still to be taken from bin (b1, b2)
   uint32_t zeros;     // exact zeros of the layer (filled in when b1 == 0)
@@ -95,7 +95,7 @@ struct Ws {
   uint32_t* pending;           // one word: workers whose e still holds Delta (residual not formed yet)
   // TopK
   uint32_t* hist1;             // W x L x kHistBins, zero between steps
-  uint32_t* t2;                // W x n_ftiles x 128: per tile, level-2 counts of the two guessed bins
+  uint32_t* t2;                // W x n_ftiles x 192: per tile, level-2 counts of the guessed bins
   uint32_t* qlist;             // W x q_stride x kQListCap: per quarter, its keys in bin (b1, b2)
   SelState* sel;               // W x L
   uint32_t* hist2m;            // W x L x 64: level-2 counts of b1 of a layer whose guess missed

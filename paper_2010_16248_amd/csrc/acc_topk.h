@@ -6,11 +6,10 @@
 //
 //   A   topk_ef_hist   Delta = g + e (in place), A += g (worker 0), level-1 histogram per
 //                      (worker, layer).  The level-1 bin b1 that will hold the k-th largest key is
-//                      not known yet, so the pass stages the keys of two GUESSED bins (the bin
-//                      the previous step at this level ended in and the neighbour on the side
-//                      its threshold was closer to) per wave quarter of a tile, counts the
-//                      entries above them and the exact zeros, and writes the tile's level-2
-//                      counts of the two guessed bins.
+//                      not known yet, so the pass stages the keys of kGuessBins GUESSED adjacent
+//                      bins (around the bin the previous step at this level ended in) per wave
+//                      quarter of a tile, counts the entries above them and the exact zeros, and
+//                      writes the tile's level-2 counts of the guessed bins.
 //   P12 topk_pick12    one workgroup per (worker, layer): b1 from the histogram; if it is one
 //                      of the guessed bins, b2 from the sum of the tiles' level-2 counts.
 //                      Layers of a single tile are decided here completely, from Delta.
@@ -44,10 +43,7 @@ constexpr int kPickWaves = kPickThreads / kWave;
 static_assert(kHistBins == 2 * kPickThreads, "the pick kernels load two histogram bins per thread");
 constexpr int kQListCap = 16;            // keys of bin (b1, b2) listed per wave quarter
 constexpr int kL2Bins = 64;              // level 2: key bits 19..14
-#ifndef ACC_GUESS_BINS
-#define ACC_GUESS_BINS 3
-#endif
-constexpr int kGuessBins = ACC_GUESS_BINS;   // adjacent level-1 bins staged by the first pass
+constexpr int kGuessBins = 3;                // adjacent level-1 bins staged by the first pass (2 or 3)
 constexpr int kSub2 = kGuessBins * kL2Bins;  // a tile's level-2 counts of the guessed bins
 __device__ __forceinline__ uint32_t bin2_of(uint32_t key) { return (key >> 14) & 0x3fu; }
 __device__ __forceinline__ uint32_t bin3_of(uint32_t key) { return (key >> 6) & 0xffu; }
@@ -400,13 +396,6 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
       if (h) atomicAdd(&gh[b], h);
     }
     if (tid < kSub2) ws.t2[((int64_t)w * ws.n_ftiles + tile_id) * kSub2 + tid] = sub2[tid];
-#ifdef ACC_EXP_FENCE
-    __syncthreads();
-    if (tid == 0) {
-      __threadfence();
-      atomicAdd(&ws.overlap[ft.layer], 1ull);
-    }
-#endif
   }
 }
 
@@ -655,7 +644,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   __shared__ uint32_t sub[kSub2];
   __shared__ uint32_t nb0;
   // Requested together, before anything is known: the layer's level-1 histogram (cleared for
-  // the next step) and the tiles' level-2 counts of BOTH guessed bins.
+  // the next step) and the tiles' level-2 counts of ALL guessed bins.
   uint32_t* gh = ws.hist1 + wl * kHistBins;
   uint32_t h0 = gh[tid], h1 = gh[tid + kPickThreads];
   constexpr int kStripes = kPickThreads / kSub2;            // tiles summed side by side
