@@ -651,12 +651,13 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   const int col = tid % kSub2, stripe = tid / kSub2;
   const uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_ftiles + L.tile0) * kSub2 + col;
   uint32_t s2 = 0;
-  for (int tl0 = (stripe < kStripes ? stripe : L.ntiles); tl0 < L.ntiles; tl0 += 8 * kStripes) {
-    uint32_t v[8];                                          // eight independent loads in flight
+  constexpr int kT2Loads = 16;                              // independent loads in flight
+  for (int tl0 = (stripe < kStripes ? stripe : L.ntiles); tl0 < L.ntiles; tl0 += kT2Loads * kStripes) {
+    uint32_t v[kT2Loads];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = t2[(int64_t)min(tl0 + u * kStripes, L.ntiles - 1) * kSub2];
+    for (int u = 0; u < kT2Loads; ++u) v[u] = t2[(int64_t)min(tl0 + u * kStripes, L.ntiles - 1) * kSub2];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) s2 += (tl0 + u * kStripes < L.ntiles) ? v[u] : 0u;
+    for (int u = 0; u < kT2Loads; ++u) s2 += (tl0 + u * kStripes < L.ntiles) ? v[u] : 0u;
   }
   const uint32_t guess = ws.guess[wl * 2 + lv];
   gh[tid] = 0u;
@@ -794,6 +795,8 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
   const int chunk = (nq + kPickThreads - 1) / kPickThreads;
   const int q_lo = min(tid * chunk, nq), q_hi = min(q_lo + chunk, nq);
   if (tid == 0) { flag = 0u; lcount = 0u; }
+  // requested now, used by thread 0 at the very end (the guess for the next step)
+  const uint2 prev_hist = ws.b1hist[wl * 2 + lv];
   __syncthreads();
   // Gather the listed keys of the whole layer in LDS, packed as (quarter << 14 | low 14 key
   // bits): the upper 17 key bits are those of (b1, b2).  A quarter's count and its list slot are
@@ -993,7 +996,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
     // bin paired with the bin it would reach if the move slowed down, or, when it rests, with the
     // neighbour on the side of the threshold.
     // b1hist: (b1 | (last move + 64) << 16, step)
-    const uint2 prev = ws.b1hist[wl * 2 + lv];
+    const uint2 prev = prev_hist;
     const bool consecutive = prev.y + 1u == step_id;
     int v = consecutive ? (int)b1 - (int)(prev.x & 0xffffu) : 0;
     v = max(-64, min(64, v));
