@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # of this file (summaries under profiles/); None until measured for a workload.
 # Key: (workload, W, dominant kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 648679604,      # profiles/hbm_traffic_resnet18_topk.md
+    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 657229514,      # profiles/hbm_traffic_resnet18_topk.md
     ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635204002,     # profiles/hbm_traffic_resnet18_powersgd.md
     ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416681771,        # profiles/hbm_traffic_vgg19_powersgd.md
 }
@@ -40,7 +40,7 @@ MEASURED_TRAFFIC_BYTES = {
 # Counted traffic of all kernels of one step (sum of the per-kernel averages in the same summaries;
 # kernels that run once per window or on demand left out).  Key: (workload, W).
 MEASURED_STEP_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4): 648679604 + 271214746 + 21366708 + 16777430 + 4664347 + 2025698,
+    ("resnet18_topk", 4): 657229514 + 271199069 + 27513752 + 9418983 + 6065188 + 2031866,
     ("resnet18_powersgd", 4): 635204002 + 191300968 + 12184368 + 3354890 + 47512869,
     ("vgg19_powersgd", 1): 416681771 + 88425656 + 6209709 + 1771143 + 86578303,
 }
