@@ -32,17 +32,17 @@ HBM_PEAK_GBS = 8000.0
 # of this file (summaries under profiles/); None until measured for a workload.
 # Key: (workload, W, dominant kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 657229514,      # profiles/hbm_traffic_resnet18_topk.md
-    ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635204002,     # profiles/hbm_traffic_resnet18_powersgd.md
-    ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416681771,        # profiles/hbm_traffic_vgg19_powersgd.md
+    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 657220835,      # profiles/hbm_traffic_resnet18_topk.md
+    ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635250034,     # profiles/hbm_traffic_resnet18_powersgd.md
+    ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416681243,        # profiles/hbm_traffic_vgg19_powersgd.md
 }
 
 # Counted traffic of all kernels of one step (sum of the per-kernel averages in the same summaries;
 # kernels that run once per window or on demand left out).  Key: (workload, W).
 MEASURED_STEP_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4): 657229514 + 271199069 + 27513752 + 9418983 + 6065188 + 2031866,
-    ("resnet18_powersgd", 4): 635204002 + 191300968 + 12184368 + 3354890 + 47512869,
-    ("vgg19_powersgd", 1): 416681771 + 88425656 + 6209709 + 1771143 + 86578303,
+    ("resnet18_topk", 4): 657220835 + 271207022 + 27514566 + 9418981 + 6065187 + 2031865,
+    ("resnet18_powersgd", 4): 635250034 + 191304669 + 12184522 + 3387700 + 47511470,
+    ("vgg19_powersgd", 1): 416681243 + 88425680 + 6209777 + 1803930 + 86544871,
 }
 
 # Both compression levels are used while timing: the gradient statistics are stationary (every
@@ -64,9 +64,10 @@ def parse():
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches kept in HBM")
     ap.add_argument("--window", type=int, default=50, help="steps per detection window")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kernel-events", default="dominant", choices=["dominant", "all", "none"],
-                    help="which kernels are bracketed with HIP events in the timed region: the fused "
-                         "error-feedback pass only (default), every kernel, or none")
+    ap.add_argument("--kernel-events", default="sampled", choices=["sampled", "dominant", "all", "none"],
+                    help="which kernels are bracketed with HIP events in the timed region: every fourth "
+                         "launch of the fused error-feedback pass (default; a pair of events costs 5-7 us "
+                         "of stream time), every launch of it, every kernel, or none")
     ap.add_argument("--fused-update", action="store_true",
                     help="end every step with the fused Nesterov-momentum update of weights and velocity "
                          "(accordion_step_all_update) instead of storing the averaged gradient")
@@ -268,7 +269,7 @@ def main():
     state["step"] = 0                      # timed region starts at a window boundary
     use_events = args.kernel_events != "none"
     if use_events:
-        gpu.set_profiling(1 if args.kernel_events == "all" else 2)
+        gpu.set_profiling({"all": 1, "dominant": 2, "sampled": 3}[args.kernel_events])
     torch.cuda.synchronize()
     bs0 = gpu.batch_status() if is_batch else None
     t0 = time.perf_counter()
@@ -309,7 +310,7 @@ def main():
         traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, W, dom))
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
-                    "avg_kernel_us": round(avg_s * 1e6, 2),
+                    "avg_kernel_us": round(avg_s * 1e6, 2), "launches_timed": n,
                     "algorithmic_bytes_per_launch": alg_bytes}
 
     # the whole step: bytes the method must move (one read / write of each operand per pass, the

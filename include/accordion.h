@@ -295,7 +295,9 @@ int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
  * With profiling on, kernel launches are bracketed by two HIP events on the context's stream and
  * the elapsed time is accumulated per stage: enable = 1 brackets every kernel, enable = 2 only the
  * fused error-feedback pass of the method (the kernel that moves the most bytes), which keeps
- * the event overhead out of the other launches; 0 switches it off.  accordion_get_profile
+ * the event overhead out of the other launches, enable = 3 only every fourth launch of that pass
+ * (a pair of events costs 5 to 7 us of stream time, a few per cent of a step); 0 switches it
+ * off.  accordion_get_profile
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
  * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
  * accordion_stage_name gives the kernel's name (NULL if out of range). */

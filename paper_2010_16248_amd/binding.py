@@ -344,7 +344,8 @@ class Accordion:
             self.ctx, buf.ctypes.data_as(C.c_void_p), buf.nbytes))
 
     def set_profiling(self, enable) -> None:
-        """0 / False: off; 1 / True: every kernel; 2: only the fused error-feedback pass."""
+        """0 / False: off; 1 / True: every kernel; 2: only the fused error-feedback pass; 3: every
+        fourth launch of that pass."""
         _check(self._lib, self.ctx, self._lib.accordion_set_profiling(self.ctx, int(enable)))
 
     def get_profile(self) -> dict:

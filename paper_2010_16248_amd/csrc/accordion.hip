@@ -285,7 +285,8 @@ struct EventPair { hipEvent_t a, b; int stage; };
 
 struct acc_ctx {
   // per-kernel timing
-  int profiling = 0;               // 0 off, 1 every kernel, 2 only the fused error-feedback pass
+  int profiling = 0;               // 0 off, 1 every kernel, 2 only the fused error-feedback pass, 3 every fourth launch of it
+  uint32_t prof_tick = 0;          // launches of that pass seen in mode 3
   std::vector<EventPair> pending, spare;
   double stage_ms[ST_COUNT] = {0};
   long long stage_n[ST_COUNT] = {0};
@@ -349,9 +350,10 @@ int drain_profile(acc_ctx* c) {
 
 bool prof_begin(acc_ctx* c, int stage, EventPair& p) {
   if (!c->profiling) return false;
-  if (c->profiling == 2 && stage != ST_topk_ef_hist_kernel && stage != ST_psgd_ef_p_kernel &&
+  if (c->profiling >= 2 && stage != ST_topk_ef_hist_kernel && stage != ST_psgd_ef_p_kernel &&
       stage != ST_batch_micro_kernel && stage != ST_batch_micro_update_kernel)
     return false;
+  if (c->profiling == 3 && (c->prof_tick++ & 3u) != 0u) return false;
   if (c->pending.size() >= 8192) drain_profile(c);
   if (!c->spare.empty()) {
     p = c->spare.back();
@@ -1091,7 +1093,8 @@ int32_t accordion_set_profiling(acc_ctx* c, int32_t enable) {
   if (enable && !c->profiling) {
     for (int i = 0; i < ST_COUNT; ++i) { c->stage_ms[i] = 0.0; c->stage_n[i] = 0; }
   }
-  c->profiling = (enable == 2) ? 2 : (enable != 0 ? 1 : 0);
+  c->profiling = (enable == 2 || enable == 3) ? enable : (enable != 0 ? 1 : 0);
+  c->prof_tick = 0;
   return ACC_OK;
 }
 
