@@ -101,9 +101,9 @@ struct Ws {
   uint32_t* hist2m;            // W x L x 64: level-2 counts of b1 of a layer whose guess missed
   uint32_t* miss_any;          // W: some multi-tile layer of the worker missed its guessed bins this step
   uint2* b1hist;               // W x L x 2 (level): {b1 | (last move + 64) << 16, step number} of the last step at this level
-  uint32_t* guess;             // W x L x 2 (level): lower of the two level-1 bins staged by pass A
-  uint4* qinfo;                // W x q_stride: per wave quarter {entries above the staged bins,
-                               //   keys of the lower bin, keys of the upper bin, exact zeros}
+  uint32_t* guess;             // W x L x 2 (level): lowest of the adjacent level-1 bins staged by pass A
+  uint4* qinfo;                // W x q_stride: per wave quarter {entries above the staged bins, staged
+                               //   keys, of which in the second | third bin << 16, exact zeros}
   uint32_t* seg;               // W x q_stride x 2 x kSubCap staged keys
   uint32_t* gtq;               // W x q_stride entries above the threshold per quarter
   uint32_t* eqq;               // W x q_stride keys in bin (b1, b2) / entries equal to the threshold per quarter

@@ -156,7 +156,7 @@ constexpr int kSegCap = 2 * kSubCap;     // staged keys per wave quarter
 // pass counts them).  mv: lane mask of the valid elements; valid: the calling lane's bit of it.
 // Every ballot is taken from a single compare and combined with the other masks in scalar
 // registers.
-__device__ __forceinline__ void stage_two_bins(uint32_t* st, uint32_t* sub2, StageCounts& c, uint64_t mv,
+__device__ __forceinline__ void stage_guessed_bins(uint32_t* st, uint32_t* sub2, StageCounts& c, uint64_t mv,
                                                bool valid, uint32_t key, uint32_t glo, int lane) {
   const uint32_t bin = key >> 20;
   const uint32_t rel = bin - glo;                          // 0 .. kGuessBins - 1 for the staged bins
@@ -368,7 +368,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
             const uint32_t key = key_of(comp(d, c));
             hist_add(hist, (key >> 20) != 0u, key >> 20);
             if (ZB) stage_one_bin(st, sub2, cnt, ~0ull, true, key, 0u, lane);
-            else stage_two_bins(st, sub2, cnt, ~0ull, true, key, glo, lane);
+            else stage_guessed_bins(st, sub2, cnt, ~0ull, true, key, glo, lane);
           }
         } else {
           const uint64_t m_span = ballot64(qa);
@@ -379,7 +379,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
             const uint32_t key = key_of(comp(d, c));
             hist_add(hist, valid && (key >> 20) != 0u, key >> 20);
             if (ZB) stage_one_bin(st, sub2, cnt, mv, valid, key, 0u, lane);
-            else stage_two_bins(st, sub2, cnt, mv, valid, key, glo, lane);
+            else stage_guessed_bins(st, sub2, cnt, mv, valid, key, glo, lane);
           }
         }
       }
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(256) void topk_restage_kernel(const Ws ws, int w0) 
 constexpr int kFirstChunks = kSegCap / kWave;   // 64-key chunks of a segment
 
 struct QuarterKeys {
-  uint4 info;                      // {entries above the staged bins, staged keys, of which upper bin, zeros}
+  uint4 info;                      // {entries above the staged bins, staged keys, of which 2nd | 3rd bin << 16, zeros}
   uint32_t chunk[kFirstChunks];    // the calling lane's staged keys
 };
 
