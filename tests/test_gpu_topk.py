@@ -187,6 +187,31 @@ def test_large_tie_classes_take_the_sweeps_and_stay_exact():
     gpu.destroy()
 
 
+@pytest.mark.parametrize("n_tiles,k", [(225, 5000), (800, 20000)])
+def test_more_keys_around_the_threshold_than_the_pick_kernel_holds_in_lds(n_tiles, k):
+    """Twelve keys per wave quarter (2048 elements) lie in one level-2 cell of the key space
+    (16384 consecutive key values, so with many ties) and the threshold falls among them: every
+    quarter's list is complete, but the layer's lists together exceed what the last pick kernel
+    gathers in LDS (225 tiles: 10800 keys; 800 tiles: 38400 keys, and more quarters than it
+    counts in LDS), so it works from the lists in device memory.  Second step: no new gradient,
+    the threshold stays in the cell with fewer keys left."""
+    print(f"case long lists n_tiles={n_tiles} k={k}", flush=True)
+    n = n_tiles * 8192
+    layers = wl.make_layers([(1, n, 0)])
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, 1, k, k, n)
+    rng = np.random.default_rng([21, n_tiles])
+    g = rng.random(n).astype(np.float32) * np.float32(0.9)            # all below the cell
+    cell = np.uint32(0x3FC00000)                                      # 1.5f: the low 14 key bits are free
+    for q in range(4 * n_tiles):
+        pos = q * 2048 + rng.choice(2048, 12, replace=False)
+        g[pos] = (cell | rng.integers(0, 1 << 14, 12).astype(np.uint32)).view(np.float32)
+    g *= rng.choice(np.array([-1.0, 1.0], np.float32), n)
+    _check_step(gpu, ora, [g], "step 0", check_state=False)
+    _check_step(gpu, ora, [np.zeros(n, np.float32)], "step 1")
+    assert gpu.topk_stats()[1] == 0                                   # no list overflowed: no sweeps
+    gpu.destroy()
+
+
 @pytest.mark.parametrize("crit,noncrit", [(99, 60), (100, 51)])
 def test_high_keep_ratios_use_the_values_and_holes_layout(crit, noncrit):
     """The paper's own K = 99 % level: layers that keep more than half store values in index
