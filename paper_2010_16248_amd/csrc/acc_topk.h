@@ -764,13 +764,22 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   if (lane == 0) { ws.gtq[qslot] = above + n_gt; ws.eqq[qslot] = n_in; }
 }
 
-constexpr int kLdsList = 10240;          // keys of bin (b1, b2) of a layer gathered in LDS (packed)
-constexpr int kLdsQuarters = 3072;       // quarters of a layer whose counts are kept in LDS
+// Two sizes of the last pick kernel: kLdsList keys of bin (b1, b2) of a layer gathered in LDS
+// (packed), kLdsQuarters quarters of a layer whose counts are kept in LDS.  The small one (60 KB
+// of LDS) serves layers up to 6.3 M entries; a model with a larger layer gets the big one (152 KB,
+// one workgroup per compute unit), which serves layers up to 25 M entries from LDS.  Larger
+// layers, or more keys around the threshold, work from device memory (slower, same results).
+constexpr int kLdsList = 10240, kLdsQuarters = 3072;
+constexpr int kLdsListBig = 24576, kLdsQuartersBig = 12288;
+static_assert(2 * kLdsQuarters <= kLdsList && 2 * kLdsQuartersBig <= kLdsListBig,
+              "the prefixes of a layer are staged in the key list");
 
-__global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, int w0, uint32_t step_id) {
+template <int kLdsList, int kLdsQuarters>
+__device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_id) {
   __shared__ uint32_t hist[kHistBins];
   __shared__ uint32_t llist[kLdsList];
-  __shared__ uint32_t lcnt[kLdsQuarters];                  // per quarter: entries above T | equal to T << 16
+  // per quarter (2048 entries): entries above T | listed keys equal to T << 12 | exact zeros << 17
+  __shared__ uint32_t lcnt[kLdsQuarters];
   __shared__ uint32_t out[3], scratch[4];
   __shared__ uint32_t wsum[2][kPickWaves];
   __shared__ uint32_t flag, lcount;
@@ -797,6 +806,9 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
   if (tid == 0) { flag = 0u; lcount = 0u; }
   // requested now, used by thread 0 at the very end (the guess for the next step)
   const uint2 prev_hist = ws.b1hist[wl * 2 + lv];
+  const uint32_t b1 = sp->b1, side = sp->side, b2 = sp->b2, zeros = sp->zeros;
+  uint32_t need = sp->need3;
+  const bool zero_bin = (b1 == 0u && b2 == 0u);            // bin (b1, b2) holds the exact zeros
   __syncthreads();
   // Gather the listed keys of the whole layer in LDS, packed as (quarter << 14 | low 14 key
   // bits): the upper 17 key bits are those of (b1, b2).  A quarter's count and its list slot are
@@ -806,34 +818,70 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
   // quarter holds 2048 entries: 16 bits per count), which saves the round trips of global atomics
   // and of reading them back.
   const bool lds_q = nq <= kLdsQuarters;
-  for (int q = q_lo; q < q_hi; ++q) {
-    const uint32_t n = eqq[q];
-    const uint32_t g0 = gtq[q];
-    uint4 k4[kQListCap / 4];
+  // the exact zeros of a quarter count as equal to T when T turns out to be 0, which can only
+  // happen in the zero bin
+  const uint4* qinfo = ws.qinfo + qbase;
+  // Every lane of a wave calls this together (valid: the lane has a quarter): the wave's keys get
+  // one stretch of the list, reserved with one atomic per wave -- an atomic per quarter on the one
+  // counter costs 20 cycles each, one after the other (10 us for a layer of 2.4 M entries).
+  auto take_quarter = [&](int q, bool valid, uint32_t n, uint32_t g0, uint32_t zq,
+                          const uint4 (&k4)[kQListCap / 4]) {
+    if (valid && lds_q) lcnt[q] = g0 | (zq << 17);
+    const bool over = valid && (n > (uint32_t)kQListCap || !packable);
+    if (over) flag = 1u;                                   // a list overflowed: the sweeps decide
+    const uint32_t ne = (valid && !over) ? n : 0u;
+    const uint32_t incl = wave_incl_scan_u32(ne, lane);
+    const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+    if (total == 0u) return;                               // wave-uniform
+    uint32_t base = 0u;
+    if (lane == kWave - 1) base = atomicAdd(&lcount, total);
+    base = (uint32_t)__builtin_amdgcn_readlane((int)base, kWave - 1);
+    const uint32_t pos = base + incl - ne;
+    if (ne != 0u && pos + ne <= (uint32_t)kLdsList) {
 #pragma unroll
-    for (int i = 0; i < kQListCap / 4; ++i) k4[i] = qlist4[(int64_t)q * (kQListCap / 4) + i];
-    if (lds_q) lcnt[q] = g0;
-    if (n > (uint32_t)kQListCap || !packable) {
-      flag = 1u;                                           // a list overflowed: the sweeps decide
-    } else if (n != 0u) {
-      const uint32_t pos = atomicAdd(&lcount, n);
-      if (pos + n <= (uint32_t)kLdsList) {
-#pragma unroll
-        for (int i = 0; i < kQListCap; ++i) {
-          const uint4& v = k4[i / 4];
-          const uint32_t key = (i % 4 == 0) ? v.x : (i % 4 == 1) ? v.y : (i % 4 == 2) ? v.z : v.w;
-          if ((uint32_t)i < n) llist[pos + i] = ((uint32_t)q << 14) | (key & 0x3fffu);
-        }
+      for (int i = 0; i < kQListCap; ++i) {
+        const uint4& v = k4[i / 4];
+        const uint32_t key = (i % 4 == 0) ? v.x : (i % 4 == 1) ? v.y : (i % 4 == 2) ? v.z : v.w;
+        if ((uint32_t)i < ne) llist[pos + i] = ((uint32_t)q << 14) | (key & 0x3fffu);
       }
     }
+  };
+  // Consecutive threads take consecutive quarters (whole cache lines per request: with a chunk of
+  // quarters per thread the one compute unit that works on a large layer spends its time on
+  // requests, 388 lines per wave and round instead of 40), four rounds requested together, from
+  // clamped indices, so that every lane runs every round.  Of a quarter's list the first four keys
+  // come with its count; the rest only when the count reaches them.
+  constexpr int G = 4;
+  for (int q0 = 0; q0 < nq; q0 += G * kPickThreads) {
+    uint32_t n[G], g0[G], zq[G];
+    uint4 k4[G][kQListCap / 4];
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      const int q = min(q0 + u * kPickThreads + tid, nq - 1);
+      n[u] = eqq[q];
+      g0[u] = gtq[q];
+      zq[u] = zero_bin ? qinfo[q].w : 0u;
+      k4[u][0] = qlist4[(int64_t)q * (kQListCap / 4)];
+    }
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      const int qv = q0 + u * kPickThreads + tid, q = min(qv, nq - 1);
+#pragma unroll
+      for (int i = 1; i < kQListCap / 4; ++i)
+        k4[u][i] = (n[u] > (uint32_t)(4 * i) && n[u] <= (uint32_t)kQListCap) ? qlist4[(int64_t)q * (kQListCap / 4) + i]
+                                                                            : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      const int qv = q0 + u * kPickThreads + tid;
+      if (q0 + u * kPickThreads < nq)                       // uniform over the workgroup
+        take_quarter(min(qv, nq - 1), qv < nq, n[u], g0[u], zq[u], k4[u]);
+    }
   }
-  const uint32_t b1 = sp->b1, side = sp->side, b2 = sp->b2, zeros = sp->zeros;
-  uint32_t need = sp->need3;
   __syncthreads();
   const uint32_t ln = lcount;
   const bool listed = flag == 0u;                          // every quarter's list is complete
   const bool in_lds = ln <= (uint32_t)kLdsList;            // ... and all of them fit in LDS
-  const bool zero_bin = (b1 == 0u && b2 == 0u);            // bin (b1, b2) holds the exact zeros
   auto clear_hist = [&]() {
     __syncthreads();
     for (int b = tid; b < kHistBins; b += kPickThreads) hist[b] = 0u;
@@ -876,7 +924,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
     if (in_lds && lds_q) {
       for_listed([&](uint32_t low, int q) {
         if (low > t_low) atomicAdd(&lcnt[q], 1u);
-        else if (low == t_low) atomicAdd(&lcnt[q], 0x10000u);
+        else if (low == t_low) atomicAdd(&lcnt[q], 1u << 12);
       });
     } else if (in_lds) {
       for (int q = q_lo; q < q_hi; ++q) eqq[q] = 0u;
@@ -950,13 +998,13 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
     auto quarter_counts = [&](int q, uint32_t& g, uint32_t& e) {
       if (from_lds) {
         const uint32_t v = lcnt[q];
-        g = v & 0xffffu;
-        e = v >> 16;
+        g = v & 0xfffu;
+        e = ((v >> 12) & 0x1fu) + (T == 0u ? v >> 17 : 0u);
       } else {
         g = ld_agent(&gtq[q]);
         e = ld_agent(&eqq[q]);
+        if (T == 0u) e += qinfo[q].w;
       }
-      if (T == 0u) e += ws.qinfo[qbase + q].w;
     };
     uint32_t s_gt = 0, s_eq = 0;
     for (int q = q_lo; q < q_hi; ++q) {
@@ -976,6 +1024,24 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
       if (q_lo < q_hi) { gtpre[q_lo] = o_gt; eqpre[q_lo] = o_eq; }
       o_gt += s_gt;
       o_eq += s_eq;
+    } else if (from_lds) {
+      // the prefixes go through LDS (the key list is no longer needed; 2 nq <= its size) and out
+      // with consecutive threads on consecutive quarters: a chunk per thread would be one cache
+      // line per lane and store
+      __syncthreads();                                      // nobody reads the key list any more
+      for (int q = q_lo; q < q_hi; ++q) {
+        uint32_t g, e;
+        quarter_counts(q, g, e);
+        llist[q] = o_gt;
+        llist[nq + q] = o_eq;
+        o_gt += g;
+        o_eq += e;
+      }
+      __syncthreads();
+      for (int q = tid; q < nq; q += kPickThreads) {
+        gtpre[q] = llist[q];
+        eqpre[q] = llist[nq + q];
+      }
     } else {
       for (int q = q_lo; q < q_hi; ++q) {
         uint32_t g, e;
@@ -1016,6 +1082,15 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, i
     uint32_t glo = (uint32_t)max(0, min(kHistBins - kGuessBins, g));
     ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero : glo;
   }
+}
+
+__global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, int w0, uint32_t step_id) {
+  pick3_body<kLdsList, kLdsQuarters>(ws, w0, step_id);
+}
+
+// For models with a layer of more than kLdsQuarters quarters.
+__global__ __launch_bounds__(kPickThreads) void topk_pick3_big_kernel(const Ws ws, int w0, uint32_t step_id) {
+  pick3_body<kLdsListBig, kLdsQuartersBig>(ws, w0, step_id);
 }
 
 // ---- E ----------------------------------------------------------------------------------------

@@ -42,6 +42,7 @@ struct Plan {
   int64_t q_dev = 0;     // floats of Q on the device: every row padded to kMaxRank floats
   int64_t p_total = 0, ppart_stride = 0, qpart_stride = 0, vec_total = 0;
   int64_t pay_stride = 0, q_stride = 0;
+  bool pick3_big = false;   // TopK: some layer has more quarters than the small last pick kernel counts in LDS
   // workspace regions
   Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
@@ -127,6 +128,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
       p.ftiles.push_back(ft);
     }
     ntile += d.ntiles;
+    if (4 * (int64_t)d.ntiles > kLdsQuarters) p.pick3_big = true;
     p.n_model += n;
     if (ntile > (int64_t(1) << 30)) return fail(err, ACC_EINVAL, "too many tiles");
     if (c->method == ACC_POWERSGD) {
@@ -372,6 +374,7 @@ void prof_end(acc_ctx* c, EventPair& p) {
   c->pending.push_back(p);
 }
 
+#define ST_topk_pick3_big_kernel ST_topk_pick3_kernel   /* one stage, two sizes */
 #define ACC_LAUNCH(ctx, name, grid, block, ...)                              \
   do {                                                                       \
     EventPair ep_;                                                           \
@@ -392,7 +395,8 @@ int launch_topk_select(acc_ctx* c, int w0, int nw) {
   ACC_LAUNCH(c, topk_pick12_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0);
   ACC_LAUNCH(c, topk_restage_kernel, dim3(std::min(ws.n_ftiles, 2048), nw), dim3(256), ws, w0);
   ACC_LAUNCH(c, topk_count3_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
-  ACC_LAUNCH(c, topk_pick3_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
+  if (c->plan.pick3_big) ACC_LAUNCH(c, topk_pick3_big_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
+  else ACC_LAUNCH(c, topk_pick3_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
   return ACC_OK;
 }
 
