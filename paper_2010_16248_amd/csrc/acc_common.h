@@ -42,7 +42,9 @@ struct LayerDev {
   int64_t vec_off;       // into the 1-D mean buffer (PowerSGD, 1-D layers)
 };
 
-struct FlatTile { int32_t layer, start, count, pad; };
+// qslot0: slot of the tile's first wave quarter in a worker's per-quarter arrays (the layer's qoff +
+// 4 * tile within the layer), so that a kernel can request them before it has the layer's entry.
+struct FlatTile { int32_t layer, start, count, qslot0; };
 struct MatTile { int32_t layer, row0, col0, pad; };
 struct QTile { int32_t layer, col0; };
 

@@ -529,7 +529,7 @@ __device__ __forceinline__ uint32_t for_quarter_keys(const Ws& ws, const LayerDe
   ft.layer = 0;
   ft.start = tl << kTileShift;
   ft.count = (int32_t)min((int64_t)kTile, (int64_t)L.rows * L.cols - ft.start);
-  ft.pad = 0;
+  ft.qslot0 = 0;
   const TileGeom tg = tile_geom(L, ft);
   const WaveSpan sp = wave_span(tg, wave);
   const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
@@ -559,7 +559,7 @@ __device__ __forceinline__ void pick_small_layer(const Ws& ws, const LayerDev& L
   ft.layer = li;
   ft.start = 0;
   ft.count = L.rows * L.cols;
-  ft.pad = 0;
+  ft.qslot0 = 0;
   const TileGeom tg = tile_geom(L, ft);
   const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
   const int count = ft.count;
@@ -723,14 +723,14 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const FlatTile ft = ws.ftiles[blockIdx.x];
-  const LayerDev& L = ws.layers[ft.layer];
-  if (L.ntiles == 1) return;                               // decided by the first pick kernel
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   SelState* sp = ws.sel + wl;
   const int tl = ft.start >> kTileShift;
-  const int64_t qslot = quarter_slot(ws, L, w, tl, wave);
-  // the segment is requested before the layer's state has arrived
+  const int64_t qslot = (int64_t)w * ws.q_stride + ft.qslot0 + wave;
+  // the segment is requested before the layer's entry and its state have arrived
   const QuarterKeys qk = load_quarter_keys(ws, qslot, lane);
+  const LayerDev& L = ws.layers[ft.layer];
+  if (L.ntiles == 1) return;                               // decided by the first pick kernel
   const uint32_t side = sp->side, b1 = sp->b1;
   uint32_t b2 = sp->b2;
   if (sp->mode != 0u) {                                    // uniform over the workgroup

@@ -124,7 +124,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
       ft.layer = i;
       ft.start = t * kTile;
       ft.count = (int32_t)std::min<int64_t>(kTile, n - (int64_t)t * kTile);
-      ft.pad = 0;
+      ft.qslot0 = (int32_t)(d.qoff + 4 * (int64_t)t);
       p.ftiles.push_back(ft);
     }
     ntile += d.ntiles;
