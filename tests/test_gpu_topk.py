@@ -187,14 +187,15 @@ def test_large_tie_classes_take_the_sweeps_and_stay_exact():
     gpu.destroy()
 
 
-@pytest.mark.parametrize("n_tiles,k", [(225, 5000), (800, 20000)])
+@pytest.mark.parametrize("n_tiles,k", [(225, 5000), (800, 20000), (3100, 70000)])
 def test_more_keys_around_the_threshold_than_the_pick_kernel_holds_in_lds(n_tiles, k):
     """Twelve keys per wave quarter (2048 elements) lie in one level-2 cell of the key space
     (16384 consecutive key values, so with many ties) and the threshold falls among them: every
     quarter's list is complete, but the layer's lists together exceed what the last pick kernel
-    gathers in LDS (225 tiles: 10800 keys; 800 tiles: 38400 keys, and more quarters than it
-    counts in LDS), so it works from the lists in device memory.  Second step: no new gradient,
-    the threshold stays in the cell with fewer keys left."""
+    gathers in LDS (225 tiles: 10800 keys; 800 tiles: 38400 keys, the larger instantiation of the
+    kernel; 3100 tiles: 148800 keys and more quarters than even that one counts in LDS), so it
+    works from the lists in device memory.  Second step: no new gradient, the threshold stays in
+    the cell with fewer keys left."""
     print(f"case long lists n_tiles={n_tiles} k={k}", flush=True)
     n = n_tiles * 8192
     layers = wl.make_layers([(1, n, 0)])
