@@ -59,7 +59,7 @@ EXPORTS = [
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
     "accordion_probe_copy", "accordion_topk_stats", "accordion_flush",
 ]
-ACC_N_STAGES = 31
+ACC_N_STAGES = 32
 
 
 def load_library() -> C.CDLL:

@@ -766,15 +766,16 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
 
 // Two sizes of the last pick kernel: kLdsList keys of bin (b1, b2) of a layer gathered in LDS
 // (packed), kLdsQuarters quarters of a layer whose counts are kept in LDS.  The small one (60 KB
-// of LDS) serves layers up to 6.3 M entries; a model with a larger layer gets the big one (152 KB,
-// one workgroup per compute unit), which serves layers up to 25 M entries from LDS.  Larger
-// layers, or more keys around the threshold, work from device memory (slower, same results).
+// of LDS) takes the layers up to 6.3 M entries; the layers beyond that go to the big one (152 KB,
+// one workgroup per compute unit; launched only for models that have such a layer), which
+// serves up to 25 M entries from LDS.  Larger layers, or more keys around the threshold, work
+// from device memory (slower, same results).
 constexpr int kLdsList = 10240, kLdsQuarters = 3072;
 constexpr int kLdsListBig = 24576, kLdsQuartersBig = 12288;
 static_assert(2 * kLdsQuarters <= kLdsList && 2 * kLdsQuartersBig <= kLdsListBig,
               "the prefixes of a layer are staged in the key list");
 
-template <int kLdsList, int kLdsQuarters>
+template <int kLdsList, int kLdsQuarters, bool BIG>
 __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_id) {
   __shared__ uint32_t hist[kHistBins];
   __shared__ uint32_t llist[kLdsList];
@@ -790,10 +791,11 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const LayerDev& L = ws.layers[li];
   if (L.ntiles == 1) return;                               // decided by the first pick kernel
+  const int nq = 4 * L.ntiles;
+  if (BIG != (nq > acc::kLdsQuarters)) return;             // the other instantiation's layer
   const int64_t wl = (int64_t)w * ws.L + li;
   SelState* sp = ws.sel + wl;
   const int lv = ws.level[li];
-  const int nq = 4 * L.ntiles;
   const int64_t qbase = (int64_t)w * ws.q_stride + L.qoff;
   // gtq: per quarter, the entries above bin (b1, b2); eqq: the number of keys inside (b1, b2), of
   // which the first kQListCap are listed.  Thread t owns a contiguous chunk of quarters.
@@ -1085,12 +1087,12 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
 }
 
 __global__ __launch_bounds__(kPickThreads) void topk_pick3_kernel(const Ws ws, int w0, uint32_t step_id) {
-  pick3_body<kLdsList, kLdsQuarters>(ws, w0, step_id);
+  pick3_body<kLdsList, kLdsQuarters, false>(ws, w0, step_id);
 }
 
-// For models with a layer of more than kLdsQuarters quarters.
+// The layers of more than kLdsQuarters quarters.
 __global__ __launch_bounds__(kPickThreads) void topk_pick3_big_kernel(const Ws ws, int w0, uint32_t step_id) {
-  pick3_body<kLdsListBig, kLdsQuartersBig>(ws, w0, step_id);
+  pick3_body<kLdsListBig, kLdsQuartersBig, true>(ws, w0, step_id);
 }
 
 // ---- E ----------------------------------------------------------------------------------------

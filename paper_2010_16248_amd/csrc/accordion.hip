@@ -42,7 +42,7 @@ struct Plan {
   int64_t q_dev = 0;     // floats of Q on the device: every row padded to kMaxRank floats
   int64_t p_total = 0, ppart_stride = 0, qpart_stride = 0, vec_total = 0;
   int64_t pay_stride = 0, q_stride = 0;
-  bool pick3_big = false;   // TopK: some layer has more quarters than the small last pick kernel counts in LDS
+  bool pick3_big = false;   // TopK: some layer has more quarters than the small last pick kernel takes
   // workspace regions
   Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
@@ -269,6 +269,7 @@ enum Stage {
   ST_batch_micro_kernel, ST_batch_micro_update_kernel, ST_batch_decide_kernel,
   ST_topk_overlap_kernel, ST_zero_u64_kernel, ST_msdr_sq_kernel, ST_msdr_decide_kernel,
   ST_psgd_clear_pending_kernel, ST_topk_residual_kernel, ST_topk_clear_pending_kernel,
+  ST_topk_pick3_big_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
@@ -281,7 +282,8 @@ static const char* const kStageNames[ST_COUNT] = {
   "psgd_decomp_update_kernel", "topk_compact_update_kernel", "topk_sparse_update_kernel",
   "batch_micro_kernel", "batch_micro_update_kernel", "batch_decide_kernel",
   "topk_overlap_kernel", "zero_u64_kernel", "msdr_sq_kernel", "msdr_decide_kernel",
-  "psgd_clear_pending_kernel", "topk_residual_kernel", "topk_clear_pending_kernel"};
+  "psgd_clear_pending_kernel", "topk_residual_kernel", "topk_clear_pending_kernel",
+  "topk_pick3_big_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
 
@@ -374,7 +376,6 @@ void prof_end(acc_ctx* c, EventPair& p) {
   c->pending.push_back(p);
 }
 
-#define ST_topk_pick3_big_kernel ST_topk_pick3_kernel   /* one stage, two sizes */
 #define ACC_LAUNCH(ctx, name, grid, block, ...)                              \
   do {                                                                       \
     EventPair ep_;                                                           \
@@ -395,8 +396,8 @@ int launch_topk_select(acc_ctx* c, int w0, int nw) {
   ACC_LAUNCH(c, topk_pick12_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0);
   ACC_LAUNCH(c, topk_restage_kernel, dim3(std::min(ws.n_ftiles, 2048), nw), dim3(256), ws, w0);
   ACC_LAUNCH(c, topk_count3_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
+  ACC_LAUNCH(c, topk_pick3_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
   if (c->plan.pick3_big) ACC_LAUNCH(c, topk_pick3_big_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
-  else ACC_LAUNCH(c, topk_pick3_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
   return ACC_OK;
 }
 
