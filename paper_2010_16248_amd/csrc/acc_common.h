@@ -9,6 +9,7 @@ constexpr int kWave = 64;
 constexpr int kFlatThreads = 256;        // workgroup of every flat-tile kernel
 constexpr int kTile = 8192;              // elements per flat tile (power of two)
 constexpr int kTileShift = 13;
+constexpr int kT2Group = 16;             // TopK: consecutive tiles of a layer that add their level-2 counts into one slot
 constexpr int kQuadIters = (kTile / 4 + 1 + kFlatThreads - 1) / kFlatThreads;  // 9
 constexpr int kMatRows = 64;             // matrix tile: 64 rows x 256 columns
 constexpr int kMatCols = 256;
@@ -31,7 +32,8 @@ struct LayerDev {
   int32_t n_rowblocks;   // ceil(rows / kMatRows)
   int32_t tile0;         // first flat tile of the layer
   int32_t ntiles;        // number of flat tiles
-  int32_t pad0, pad1;
+  int32_t t2slot0;       // TopK: the layer's first slot in a worker's level-2 count array (one slot per kT2Group tiles)
+  int32_t pad1;
   int64_t qoff;          // slot of the layer's first wave quarter in the per-worker quarter arrays
                          // (4 * tile0 + layer index: one spare slot per layer for the totals)
   int64_t q_off;         // into Q      (cols rows of kMaxRank floats, zero beyond rmax)
@@ -97,7 +99,7 @@ struct Ws {
   uint32_t* pending;           // one word: workers whose e still holds Delta (residual not formed yet)
   // TopK
   uint32_t* hist1;             // W x L x kHistBins, zero between steps
-  uint32_t* t2;                // W x n_ftiles x 192: per tile, level-2 counts of the guessed bins
+  uint32_t* t2;                // W x n_t2slots x 192: level-2 counts of the guessed bins, summed over kT2Group tiles
   uint32_t* qlist;             // W x q_stride x kQListCap: per quarter, its keys in bin (b1, b2)
   SelState* sel;               // W x L
   uint32_t* hist2m;            // W x L x 64: level-2 counts of b1 of a layer whose guess missed
@@ -122,6 +124,7 @@ struct Ws {
   int64_t N;
   int32_t W, L, rmax;
   int32_t n_ftiles, n_mtiles, n_qtiles, n_vectiles, n_mat;
+  int32_t n_t2slots;           // TopK: slots of t2 per worker
   float eta;
 };
 

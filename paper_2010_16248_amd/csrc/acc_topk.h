@@ -395,7 +395,13 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
       const uint32_t h = hist[b];
       if (h) atomicAdd(&gh[b], h);
     }
-    if (tid < kSub2) ws.t2[((int64_t)w * ws.n_ftiles + tile_id) * kSub2 + tid] = sub2[tid];
+    // the tile's level-2 counts are added to the slot its group of kT2Group tiles shares (integer
+    // atomics; the pick kernel reads and clears the slots): one compute unit works on a whole
+    // layer there, and a slot per tile is 2 MB to read for a layer of 22 M entries
+    if (tid < kSub2 && sub2[tid] != 0u) {
+      const int slot = L.t2slot0 + (ft.start >> kTileShift) / kT2Group;
+      atomicAdd(&ws.t2[((int64_t)w * ws.n_t2slots + slot) * kSub2 + tid], sub2[tid]);
+    }
   }
 }
 
@@ -649,15 +655,22 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   uint32_t h0 = gh[tid], h1 = gh[tid + kPickThreads];
   constexpr int kStripes = kPickThreads / kSub2;            // tiles summed side by side
   const int col = tid % kSub2, stripe = tid / kSub2;
-  const uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_ftiles + L.tile0) * kSub2 + col;
+  uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_t2slots + L.t2slot0) * kSub2 + col;
+  const int nslots = (L.ntiles + kT2Group - 1) / kT2Group;
   uint32_t s2 = 0;
-  constexpr int kT2Loads = 16;                              // independent loads in flight
-  for (int tl0 = (stripe < kStripes ? stripe : L.ntiles); tl0 < L.ntiles; tl0 += kT2Loads * kStripes) {
+  constexpr int kT2Loads = 8;                               // independent loads in flight
+  for (int sl0 = (stripe < kStripes ? stripe : nslots); sl0 < nslots; sl0 += kT2Loads * kStripes) {
     uint32_t v[kT2Loads];
 #pragma unroll
-    for (int u = 0; u < kT2Loads; ++u) v[u] = t2[(int64_t)min(tl0 + u * kStripes, L.ntiles - 1) * kSub2];
+    for (int u = 0; u < kT2Loads; ++u) v[u] = t2[(int64_t)min(sl0 + u * kStripes, nslots - 1) * kSub2];
 #pragma unroll
-    for (int u = 0; u < kT2Loads; ++u) s2 += (tl0 + u * kStripes < L.ntiles) ? v[u] : 0u;
+    for (int u = 0; u < kT2Loads; ++u) {
+      const int sl = sl0 + u * kStripes;
+      if (sl < nslots) {
+        s2 += v[u];
+        t2[(int64_t)sl * kSub2] = 0u;                        // cleared for the next step
+      }
+    }
   }
   const uint32_t guess = ws.guess[wl * 2 + lv];
   gh[tid] = 0u;

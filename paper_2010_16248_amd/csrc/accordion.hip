@@ -42,6 +42,7 @@ struct Plan {
   int64_t q_dev = 0;     // floats of Q on the device: every row padded to kMaxRank floats
   int64_t p_total = 0, ppart_stride = 0, qpart_stride = 0, vec_total = 0;
   int64_t pay_stride = 0, q_stride = 0;
+  int64_t n_t2slots = 0;    // TopK: slots of level-2 counts per worker (one per kT2Group tiles of a layer)
   bool pick3_big = false;   // TopK: some layer has more quarters than the small last pick kernel takes
   // workspace regions
   Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
@@ -129,6 +130,8 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     }
     ntile += d.ntiles;
     if (4 * (int64_t)d.ntiles > kLdsQuarters) p.pick3_big = true;
+    d.t2slot0 = (int32_t)p.n_t2slots;
+    p.n_t2slots += (d.ntiles + kT2Group - 1) / kT2Group;
     p.n_model += n;
     if (ntile > (int64_t(1) << 30)) return fail(err, ACC_EINVAL, "too many tiles");
     if (c->method == ACC_POWERSGD) {
@@ -216,7 +219,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     reg(p.r_pending, 4);
   } else if (c->method == ACC_TOPK) {
     reg(p.r_hist1, 4 * (int64_t)kHistBins * nl * W);
-    reg(p.r_t2, 4 * (int64_t)kSub2 * ntile * W);
+    reg(p.r_t2, 4 * (int64_t)kSub2 * p.n_t2slots * W);
     reg(p.r_qlist, 4 * (int64_t)kQListCap * p.q_stride * W);
     reg(p.r_sel, (int64_t)sizeof(SelState) * nl * W);
     reg(p.r_hist2m, 4 * (int64_t)kL2Bins * nl * W);
@@ -645,6 +648,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   ws.L = cfg->n_layers;
   ws.rmax = p.rmax;
   ws.n_ftiles = (int32_t)p.ftiles.size();
+  ws.n_t2slots = (int32_t)p.n_t2slots;
   ws.n_mtiles = (int32_t)p.mtiles.size();
   ws.n_qtiles = (int32_t)p.qtiles.size();
   ws.n_vectiles = (int32_t)p.vectiles.size();
