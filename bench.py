@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # of this file (summaries under profiles/); None until measured for a workload.
 # Key: (workload, W, dominant kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 657220835,      # profiles/hbm_traffic_resnet18_topk.md
+    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 657244846,      # profiles/hbm_traffic_resnet18_topk.md
     ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635250034,     # profiles/hbm_traffic_resnet18_powersgd.md
     ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416681243,        # profiles/hbm_traffic_vgg19_powersgd.md
 }
@@ -40,7 +40,7 @@ MEASURED_TRAFFIC_BYTES = {
 # Counted traffic of all kernels of one step (sum of the per-kernel averages in the same summaries;
 # kernels that run once per window or on demand left out).  Key: (workload, W).
 MEASURED_STEP_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4): 657220835 + 271207022 + 27514566 + 9418981 + 6065187 + 2031865,
+    ("resnet18_topk", 4): 657244846 + 271195188 + 28079451 + 9426442 + 2454869 + 2102700,
     ("resnet18_powersgd", 4): 635250034 + 191304669 + 12184522 + 3387700 + 47511470,
     ("vgg19_powersgd", 1): 416681243 + 88425680 + 6209777 + 1803930 + 86544871,
 }
