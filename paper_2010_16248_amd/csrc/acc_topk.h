@@ -691,6 +691,19 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   __syncthreads();
   pick_bin(hist, k, out, scratch);
   const uint32_t b1 = out[0], need2 = k - out[1];
+  // The other level's guess, from the same histogram: the bin its k-th largest key would lie in
+  // in this step's Delta.  It serves the first step after a level switch, when the level's own
+  // history is stale (or missing); after that the threshold is followed as usual.
+  const uint32_t k_other = (uint32_t)L.k[1 - lv];
+  if (k_other != k) {                                      // uniform over the workgroup
+    __syncthreads();                                       // everybody has read out[]
+    pick_bin(hist, k_other, out, scratch);
+    if (tid == 0) {
+      const uint32_t bo = out[0];
+      ws.guess[wl * 2 + (1 - lv)] = (bo == 0u) ? kGuessZero : (uint32_t)max(0, min(kHistBins - kGuessBins, (int)bo - 1));
+    }
+    __syncthreads();
+  }
   const uint32_t glo = max(guess, 1u);                     // the bins pass A staged: glo .. glo + kGuessBins - 1
   const bool hit = guess != kNoGuess && guess != kGuessZero && b1 != 0u && b1 >= glo && b1 - glo < (uint32_t)kGuessBins;
   // bin 0 guessed and found: pass A left what the re-staging pass would (mode 2: staged already)

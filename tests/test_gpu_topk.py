@@ -139,6 +139,36 @@ def test_guessed_bins_hit_drift_and_miss():
     gpu.destroy()
 
 
+def test_a_level_switch_finds_its_bins_guessed_from_the_other_level():
+    """While a level runs, the bins of the other level's threshold are taken from the same
+    histogram, so the first step after a switch needs no second staging on a stationary
+    distribution (its own history at that level is missing or stale); results stay bit-exact."""
+    print("case level switch guess", flush=True)
+    shapes = [(1, 5 * 8192 + 13, 0), (64, 577, 1), (1, 100, 0), (6, 8192, 1)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 2
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    rng = np.random.default_rng(15)
+    restaged = []
+    for step in range(12):
+        if step in (2, 4, 8):                               # windows of 2, 2 and 4 steps
+            # no history: critical (K 10 % stays); stationary norms: non-critical (K 1 % from step
+            # 4); a learning-rate decay: critical (K 10 % again from step 8)
+            lr_next = 0.01 if step == 8 else 0.1
+            ref = ora.detect_regime(0.1, lr_next)
+            gpu.detect_regime(0.1, lr_next)
+            assert np.array_equal(gpu.get_levels(), ref)
+        grads = [rng.standard_normal(N).astype(np.float32) for _ in range(W)]
+        _check_step(gpu, ora, grads, f"step {step}", check_state=(step % 4 == 3))
+        restaged.append(gpu.topk_stats()[0])
+    per_step = np.diff([0] + restaged)
+    assert per_step[0] == 3 * W                             # nothing to guess from at the very first step
+    assert ora.level[0] == 1 and ora.words_cum > 0
+    assert per_step[4] == 0 and per_step[8] == 0, per_step  # the first steps at a new level
+    gpu.destroy()
+
+
 def test_threshold_among_exact_zeros_is_guessed_too():
     """Sparse gradients of which more is kept than is non-zero (the embedding of a language
     model): the threshold is zero.  After the first step the error-feedback pass stages bin 0
