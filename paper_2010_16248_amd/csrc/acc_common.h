@@ -289,6 +289,7 @@ struct Sink {
   float* wt;
   float* vel;
   float lr, mu, wd;
+  int32_t stream_wv;   // TopK: weights and velocity are accessed with streaming loads / stores
 };
 
 // d' = d + wd w (if wd != 0);  v = mu v + d';  w = w - lr (d' + mu v).  Every product and every sum

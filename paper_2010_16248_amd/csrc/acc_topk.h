@@ -1395,8 +1395,13 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
     float4 acc = zero4;
     float4 wq = zero4, vq = zero4;
     if (UPD) {
-      wq = ld_span<AL, true>(sink.wt, tg, span, q);        // weights and velocity: once per step
-      vq = ld_span<AL, true>(sink.vel, tg, span, q);
+      if (sink.stream_wv) {                                 // uniform: see stream_wv() on the host side
+        wq = ld_span<AL, true>(sink.wt, tg, span, q);
+        vq = ld_span<AL, true>(sink.vel, tg, span, q);
+      } else {
+        wq = ld_span<AL>(sink.wt, tg, span, q);
+        vq = ld_span<AL>(sink.vel, tg, span, q);
+      }
     }
     auto one_worker = [&](int w, const GroupSel& gs, CompactRun& run) {
       const float4 cur = pf[0];
@@ -1428,8 +1433,13 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
                             : make_float4(acc.x / fw, acc.y / fw, acc.z / fw, acc.w / fw);
       if (UPD) {
         nesterov4(v, wq, vq, sink);
-        stq<AL, true>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
-        stq<AL, true>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
+        if (sink.stream_wv) {
+          stq<AL, true>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
+          stq<AL, true>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
+        } else {
+          stq<AL>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
+          stq<AL>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
+        }
       } else {
         stq<AL, kStreamOut>(sink.out, tg.a0, tg.lo, tg.hi, q, v);
       }
