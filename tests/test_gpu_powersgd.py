@@ -36,8 +36,15 @@ def _forced_step(gpu, ora, grads, tag, tol=TOL):
             assert p_hat.shape == (rows, ranks[li]), tag
             errs = dict(P=H.rel_fro(p_hat, ora.P_hat[li]), Q=H.rel_fro(q_bar, ora.Q_bar[li]),
                         D=H.rel_fro(got[sl], out_ref[sl]))
+            # the residual is the difference Delta - D, so its error is D's: it is measured against
+            # the larger of |e| and |D| (a layer whose rank reaches its row count has D = Delta
+            # and a residual of rounding noise only)
+            d_norm = np.linalg.norm(out_ref[sl].astype(np.float64))
             for w in range(gpu.n_workers):
-                errs[f"e{w}"] = H.rel_fro(st["e"][w, sl], ora.e[w, sl])
+                e_ref = ora.e[w, sl].astype(np.float64)
+                num = np.linalg.norm(st["e"][w, sl].astype(np.float64) - e_ref)
+                den = max(np.linalg.norm(e_ref), d_norm)
+                errs[f"e{w}"] = num / den if den > 0 else num
             # the whole Q block (unused columns included) is the next warm start
             qblk = st["Q"][qpos:qpos + cols * rmax].reshape(cols, rmax)
             errs["Qstate"] = H.rel_fro(qblk, ora.Q[li])
