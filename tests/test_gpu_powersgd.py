@@ -122,6 +122,40 @@ def test_tall_layer_uses_the_memory_resident_orthogonalisation():
     gpu.destroy()
 
 
+def test_rank_that_reaches_the_row_count_reproduces_the_gradient():
+    """A 3 x 937 layer at rank 4 is capped to rank 3, which spans the whole row space: the
+    projection returns the mean gradient itself and leaves a residual of rounding noise.  Both
+    facts are checked against the input, then the step against the oracle."""
+    print("case full-rank layer", flush=True)
+    layers = wl.make_layers([(3, 937, 1), (1, 11, 0), (4, 50, 1)])
+    N = wl.total_params(layers)
+    W = 2
+    q0 = wl.q_init(layers, 4, 9)
+    gpu, ora = H.make_pair(B.ACC_POWERSGD, layers, W, 4, 2, 100, 0.5, 1, q0)
+    rng = np.random.default_rng(23)
+    for step in range(3):
+        grads = [(rng.standard_normal(N) * 0.1).astype(np.float32) for _ in range(W)]
+        e_before = ora.e.astype(np.float64).copy()
+        _forced_step(gpu, ora, grads, f"step {step}")
+        st = gpu.unpack_state(gpu.get_state())
+        for li in (0, 2):
+            off, rows, cols, _ = ora.layers[li]
+            sl = slice(off, off + rows * cols)
+            delta = [grads[w][sl].astype(np.float64) + e_before[w, sl] for w in range(W)]
+            mean = sum(delta) / W
+            p_hat, _ = gpu.get_factors(li)
+            assert p_hat.shape[1] == rows
+            # D = P^ Q~^T from the factors the library holds
+            p64, q64 = (a.astype(np.float64) for a in gpu.get_factors(li))
+            d = (p64 @ q64.T).ravel()
+            assert np.linalg.norm(d - mean) <= TOL * np.linalg.norm(mean)
+            for w in range(W):
+                # e_w = Delta_w - D: what is left of worker w is its distance to the mean
+                ref = delta[w] - mean
+                assert np.linalg.norm(st["e"][w, sl] - ref) <= TOL * np.linalg.norm(mean)
+    gpu.destroy()
+
+
 def test_zero_gradient_gives_zero_columns_not_nan():
     layers = wl.make_layers([(16, 32, 1)])
     q0 = wl.q_init(layers, 2, 7)
