@@ -1335,26 +1335,34 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
 }
 
 // All workers in worker order, and the dense mean of the kept values: out[i] = (sum over the
-// workers that kept i, from +0, of their value) / W.  The loop runs over the groups of the quarter
-// and, inside, over the workers, so that the sum of one group lives in four registers; the running
-// compaction state of every worker is kept in one lane each.  The pass is bound by vector
-// instructions, not by latency: requesting Delta more than one (group, worker) step ahead only
-// adds instructions (+1 us per extra step on ResNet-18 shapes).
-constexpr int kMeanAhead = 1;
+// workers that kept i, from +0, of their value) / W.  A wave takes its quarter in chunks of
+// kChunkGroups groups and, inside a chunk, worker by worker: the sums of a chunk live in registers,
+// a worker's selection state is fetched and its payload entries are written once per chunk (the
+// entries of a chunk are listed in LDS first), and the group a worker has just used is
+// requested for the next worker at once, so a chunk less a group is always in flight.  The
+// running compaction state of every worker is kept in one lane each.
+constexpr int kChunkGroups = 4;
+constexpr int kChunkCap = 2 * kGroupList;          // listed entries at which a wave writes its list out early
+constexpr int kChunkStride = kChunkCap + kWave;    // + one slot per lane for the unselected elements
+constexpr int kChunkWords = 2 * kChunkStride;      // indices, then values
 
 // UPD: the mean is not written out but drives the optimizer step on the weights and the velocity
-// (read at the top of a group, so that they arrive while the workers are compacted).
-template <bool AL, bool UPD>
+// (requested while the last worker of the chunk is compacted).
+// HOLES: the layer keeps more than half of its entries (static per level, the same for every worker).
+template <bool AL, bool UPD, bool HOLES>
 __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& ft, const LayerDev& L,
                                                   const TileGeom& tg, const Sink sink, uint32_t* stg, int wave) {
+  constexpr int G = kChunkGroups;
   const int lane = threadIdx.x & 63;
   const WaveSpan span = wave_span(tg, wave);
+  const int n = (span.qend - span.qbeg + kWave - 1) / kWave;   // groups of the quarter, wave-uniform
+  if (n <= 0) return;
   const int64_t qslot_local = L.qoff + 4 * (int64_t)(ft.start >> kTileShift) + wave;
   const int W = ws.W;
   // everything the loop needs from the layer and the workspace, by value (a reference into global
   // memory would be re-read after every store, and that wait would drain the loads in flight)
   const int64_t layer_offset = L.offset, pay_off = L.pay_off, e_stride = ws.e_stride, pay_stride = ws.pay_stride;
-  float* const e_base = ws.e;
+  const float* const e_base = ws.e;
   int32_t* const pay_idx = ws.pay_idx;
   float* const pay_val = ws.pay_val;
   // lane w holds worker w's selection state for this quarter
@@ -1362,56 +1370,49 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   if (lane < W) mine = load_quarter_sel(ws, lane, ft.layer, qslot_local);
   uint32_t eq_run_v = mine.eq_before;
   uint32_t pos_run_v = mine.gt_before + min(mine.ktie, mine.eq_before);
-  auto sel_of = [&](int w) {
-    GroupSel gs;
-    gs.t_all = (uint32_t)__builtin_amdgcn_readlane((int)mine.t_all, w);
-    gs.k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
-    gs.flags = (uint32_t)__builtin_amdgcn_readlane((int)mine.flags, w);
-    return gs;
-  };
-  const int n = (span.qend - span.qbeg + kWave - 1) / kWave;   // groups of the quarter, wave-uniform
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-  // Delta is requested kMeanAhead (group, worker) steps ahead of its use
-  // (past the end of the quarter an aligned tile re-reads its last group: nobody looks at it)
-  auto load_step = [&](int j, int w) {
-    const float* __restrict__ e = e_base + (int64_t)w * e_stride;
-    if (AL) return ldq_clamped(e, tg.a0, max(0, min(span.qbeg + j * kWave + lane, span.qend - 1)));
-    return (j < n) ? ld_span<AL>(e, tg, span, span.qbeg + j * kWave + lane) : zero4;
+  // group j of chunk c of worker w (past the end of the quarter an aligned tile re-reads its last
+  // group: nobody looks at it)
+  // q_end: the end of the span, or its begin for a request that nobody will look at (every lane
+  // then asks for the same 16 bytes, or for nothing)
+  auto load_group = [&](const float* __restrict__ e, int c, int j, int q_end) {
+    const int q = span.qbeg + (c * G + j) * kWave + lane;
+    if (AL) return ldq_clamped(e, tg.a0, min(q, max(q_end - 1, span.qbeg)));
+    return ldq<AL>(e, tg.a0, tg.lo, tg.hi, q, q < q_end);
   };
-  float4 pf[kMeanAhead];
-  int jn = 0, wn = 0;                                        // the next step to request
-#pragma unroll
-  for (int a = 0; a < kMeanAhead; ++a) {
-    pf[a] = load_step(jn, wn);
-    if (++wn == W) { wn = 0; ++jn; }
-  }
   const float fw = (float)W;
   // x / W and x * (1 / W) are the same real number when W is a power of two, so both round alike
   const bool pow2 = (W & (W - 1)) == 0;
   const float rw = 1.0f / fw;
-  for (int j = 0; j < n; ++j) {
-    const int q = span.qbeg + j * kWave + lane;
-    const uint64_t m_span = scalar_mask(ballot64(q < span.qend));   // the same for every worker
-    float4 acc = zero4;
-    float4 wq = zero4, vq = zero4;
-    if (UPD) {
-      if (sink.stream_wv) {                                 // uniform: see stream_wv() on the host side
-        wq = ld_span<AL, true>(sink.wt, tg, span, q);
-        vq = ld_span<AL, true>(sink.vel, tg, span, q);
-      } else {
-        wq = ld_span<AL>(sink.wt, tg, span, q);
-        vq = ld_span<AL>(sink.vel, tg, span, q);
-      }
-    }
-    auto one_worker = [&](int w, const GroupSel& gs, CompactRun& run) {
-      const float4 cur = pf[0];
+  const int n_chunks = (n + G - 1) / G;
+  float4 cur[G];
 #pragma unroll
-      for (int a = 0; a + 1 < kMeanAhead; ++a) pf[a] = pf[a + 1];
-      pf[kMeanAhead - 1] = load_step(jn, wn);
-      if (++wn == W) { wn = 0; ++jn; }
-      float* __restrict__ e = e_base + (int64_t)w * e_stride;
-      int32_t* pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
-      float* pval = pay_val + (int64_t)w * pay_stride + pay_off;
+  for (int j = 0; j < G; ++j) cur[j] = load_group(e_base, 0, j, span.qend);
+  for (int c = 0; c < n_chunks; ++c) {
+    uint64_t m_span[G];                                      // the same for every worker
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+      m_span[j] = scalar_mask(ballot64(span.qbeg + (c * G + j) * kWave + lane < span.qend));
+    const int32_t i0_chunk = (int32_t)(tg.a0 + 4 * (int64_t)(span.qbeg + c * G * kWave + lane) - layer_offset);
+    float4 acc[G], wq[G], vq[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) acc[j] = wq[j] = vq[j] = zero4;
+    for (int w = 0; w < W; ++w) {
+      // what the registers of a used group are loaded with: the same chunk of the next worker,
+      // after the last worker the next chunk of the first
+      // (after the last worker of the last chunk there is nothing to request, but a request behind
+      // a branch would make every wait for a group wait for all requests: see load_group)
+      const bool last_w = w + 1 == W;
+      const float* __restrict__ e_next = e_base + (int64_t)(last_w ? 0 : w + 1) * e_stride;
+      const int c_next = last_w ? min(c + 1, n_chunks - 1) : c;
+      const int q_end_next = (last_w && c + 1 == n_chunks) ? span.qbeg : span.qend;
+      SelCommon sc;
+      sc.t_all = (uint32_t)__builtin_amdgcn_readlane((int)mine.t_all, w);
+      const uint32_t k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
+      const uint32_t flags = (uint32_t)__builtin_amdgcn_readlane((int)mine.flags, w);
+      sc.ties = (flags & 1u) != 0u;
+      uint32_t eq_run = (uint32_t)__builtin_amdgcn_readlane((int)eq_run_v, w);
+      uint32_t pos_run = (uint32_t)__builtin_amdgcn_readlane((int)pos_run_v, w);
       auto rare = [&]() {
         GroupRare r;
         r.T = (uint32_t)__builtin_amdgcn_readlane((int)mine.T, w);
@@ -1419,29 +1420,119 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
         r.nholes = (uint32_t)__builtin_amdgcn_readlane((int)mine.nholes, w);
         return r;
       };
-      compact_group<AL, true, true>(tg, span, layer_offset, gs, rare, run, e, pidx, pval, q, m_span, cur, lane, acc, stg);
-    };
-    for (int w = 0; w < W; ++w) {
-      CompactRun run;
-      run.eq_run = (uint32_t)__builtin_amdgcn_readlane((int)eq_run_v, w);
-      run.pos_run = (uint32_t)__builtin_amdgcn_readlane((int)pos_run_v, w);
-      one_worker(w, sel_of(w), run);
-      if (lane == w) { eq_run_v = run.eq_run; pos_run_v = run.pos_run; }
-    }
-    if (q < span.qend) {
-      const float4 v = pow2 ? make_float4(acc.x * rw, acc.y * rw, acc.z * rw, acc.w * rw)
-                            : make_float4(acc.x / fw, acc.y / fw, acc.z / fw, acc.w / fw);
-      if (UPD) {
-        nesterov4(v, wq, vq, sink);
-        if (sink.stream_wv) {
-          stq<AL, true>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
-          stq<AL, true>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
-        } else {
-          stq<AL>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
-          stq<AL>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
+      int32_t* __restrict__ pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
+      float* __restrict__ pval = pay_val + (int64_t)w * pay_stride + pay_off;
+      uint32_t cnt = 0u;                                     // entries in the wave's list
+      // the list goes out by consecutive lanes to consecutive addresses, as streaming stores (nothing
+      // in this step reads the payload again); the byte offset is a 32-bit value (the payload of a
+      // worker is far below 4 GiB)
+      auto write_list = [&]() {
+        __builtin_amdgcn_wave_barrier();                     // the list is complete (LDS is in order per wave)
+#pragma unroll 1
+        for (uint32_t t0 = 0u; t0 < cnt; t0 += kWave) {
+          const uint32_t t = t0 + lane;
+          const uint32_t ix = HOLES ? 0u : stg[t];
+          const uint32_t vb = stg[kChunkStride + t];
+          const uint32_t pos = pos_run + t;
+          if (t < cnt && pos < k) {                          // pos < k: always true for consistent state
+            const uint32_t boff = pos << 2;
+            if (!HOLES) __builtin_nontemporal_store((int32_t)ix, (int32_t*)((char*)pidx + boff));
+            __builtin_nontemporal_store(__uint_as_float(vb), (float*)((char*)pval + boff));
+          }
         }
-      } else {
-        stq<AL, kStreamOut>(sink.out, tg.a0, tg.lo, tg.hi, q, v);
+        __builtin_amdgcn_wave_barrier();
+        pos_run += cnt;
+        cnt = 0u;
+      };
+      // a worker whose layout differs from the layer's (never, for consistent state) is left out
+      const bool layout_ok = ((flags & 2u) != 0u) == HOLES;
+#pragma unroll
+      for (int j = 0; j < G; ++j) {
+        if (c * G + j < n && layout_ok) {                    // wave-uniform
+          const int q = span.qbeg + (c * G + j) * kWave + lane;
+          const float4 d = cur[j];
+          const bool qa = lane_bit(m_span[j]);
+          uint64_t mv[4], msel[4];
+          uint32_t key[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            mv[x] = valid_mask<AL>(tg, q, x, qa, m_span[j]);
+            key[x] = key_of(comp(d, x));
+          }
+          group_select(sc, [&]() { const GroupRare r = rare(); SelTies t; t.T = r.T; t.ktie = r.ktie; return t; },
+                       eq_run, key, mv, lane, msel);
+          uint32_t below = 0u, total = 0u;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            below = __builtin_amdgcn_mbcnt_hi((uint32_t)(msel[x] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)msel[x], below));
+            total += (uint32_t)__popcll(msel[x]);
+          }
+          if (HOLES || total != 0u) {                        // wave-uniform
+            // the index of the lane's first element in the layer; hidden from the optimizer, which
+            // would otherwise keep the indices of all elements of a chunk in registers across the loop
+            // over the workers (sixteen registers, and one wave less per SIMD)
+            int32_t i0 = i0_chunk + 4 * j * kWave;
+            asm volatile("" : "+v"(i0));
+            uint32_t nholes = 0u;
+            if (HOLES) nholes = rare().nholes;
+            uint32_t place = cnt + below;                    // of the lane's next selected element in the list
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+              const bool sel = lane_bit(msel[x]);
+              const uint32_t slot = sel ? place : (uint32_t)(kChunkCap + lane);
+              if (!HOLES) stg[slot] = (uint32_t)(i0 + x);
+              stg[kChunkStride + slot] = __float_as_uint(comp(d, x));
+              if (HOLES && lane_bit(scalar_mask(mv[x]) & ~msel[x])) {
+                // dropped entry number (index - kept before it) of the layer
+                const uint32_t hp = (uint32_t)(i0 + x) - (pos_run + place);
+                if (hp < nholes) pidx[hp] = i0 + x;           // always true for consistent state
+              }
+              place += sel ? 1u : 0u;
+              // acc is never -0, so adding +0 changes nothing
+              if (x == 0) acc[j].x += sel ? d.x : 0.f;
+              if (x == 1) acc[j].y += sel ? d.y : 0.f;
+              if (x == 2) acc[j].z += sel ? d.z : 0.f;
+              if (x == 3) acc[j].w += sel ? d.w : 0.f;
+            }
+            cnt += total;
+          }
+        }
+        // the registers of the group are free: request what they hold next
+        cur[j] = load_group(e_next, c_next, j, q_end_next);
+        if (UPD && last_w) {                                 // the chunk's weights and velocity
+          const int q = span.qbeg + (c * G + j) * kWave + lane;
+          if (sink.stream_wv) {                               // uniform: see stream_wv() on the host side
+            wq[j] = ld_span<AL, true>(sink.wt, tg, span, q);
+            vq[j] = ld_span<AL, true>(sink.vel, tg, span, q);
+          } else {
+            wq[j] = ld_span<AL>(sink.wt, tg, span, q);
+            vq[j] = ld_span<AL>(sink.vel, tg, span, q);
+          }
+        }
+        if (j + 1 < G && cnt > (uint32_t)(kChunkCap - kGroupList)) write_list();   // room for one more group
+      }
+      write_list();
+      if (lane == w) { eq_run_v = eq_run; pos_run_v = pos_run; }
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int q = span.qbeg + (c * G + j) * kWave + lane;
+      if (q < span.qend) {
+        const float4 a = acc[j];
+        const float4 v = pow2 ? make_float4(a.x * rw, a.y * rw, a.z * rw, a.w * rw)
+                              : make_float4(a.x / fw, a.y / fw, a.z / fw, a.w / fw);
+        if (UPD) {
+          nesterov4(v, wq[j], vq[j], sink);
+          if (sink.stream_wv) {
+            stq<AL, true>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq[j]);
+            stq<AL, true>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq[j]);
+          } else {
+            stq<AL>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq[j]);
+            stq<AL>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq[j]);
+          }
+        } else {
+          stq<AL, kStreamOut>(sink.out, tg.a0, tg.lo, tg.hi, q, v);
+        }
       }
     }
   }
@@ -1465,12 +1556,20 @@ __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink
   if (blockIdx.x == 0 && threadIdx.x < ws.W) ws.miss_any[threadIdx.x] = 0u;
   // every e_w keeps Delta_w: the kept entries are dropped by the next pass over it
   if (blockIdx.x == 0 && threadIdx.x == 0) *ws.tpending = ws.W == 32 ? 0xffffffffu : ((1u << ws.W) - 1u);
-  __shared__ uint32_t stage[kMeanWaves][kStgWords];
+  __shared__ uint32_t stage[kMeanWaves][kChunkWords];
   const int lw = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t* stg = stage[lw];
   const int wave = (int)(blockIdx.x % kMeanSplit) * kMeanWaves + lw;   // the quarter of the tile
-  if (tg.aligned) compact_mean_tile<true, UPD>(ws, ft, L, tg, sink, stg, wave);
-  else compact_mean_tile<false, UPD>(ws, ft, L, tg, sink, stg, wave);
+  // the payload layout of the layer at its level (k is the same for every worker)
+  const uint32_t n_layer = (uint32_t)L.rows * (uint32_t)L.cols;
+  const bool holes = payload_has_holes(n_layer, min(rfl(ws.sel[ft.layer].k), n_layer));
+  if (holes) {
+    if (tg.aligned) compact_mean_tile<true, UPD, true>(ws, ft, L, tg, sink, stg, wave);
+    else compact_mean_tile<false, UPD, true>(ws, ft, L, tg, sink, stg, wave);
+  } else {
+    if (tg.aligned) compact_mean_tile<true, UPD, false>(ws, ft, L, tg, sink, stg, wave);
+    else compact_mean_tile<false, UPD, false>(ws, ft, L, tg, sink, stg, wave);
+  }
 }
 
 __global__ __launch_bounds__(kMeanWaves * kWave) void topk_compact_mean_kernel(const Ws ws, const Sink sink) {
