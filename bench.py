@@ -32,22 +32,22 @@ HBM_PEAK_GBS = 8000.0
 # of this file (summaries under profiles/); None until measured for a workload.
 # Key: (workload, W, dominant kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 657244846,      # profiles/hbm_traffic_resnet18_topk.md
+    ("resnet18_topk", 4, "topk_ef_hist_kernel"): 657244796,      # profiles/hbm_traffic_resnet18_topk.md
     ("resnet18_powersgd", 4, "psgd_ef_p_kernel"): 635250034,     # profiles/hbm_traffic_resnet18_powersgd.md
     ("vgg19_powersgd", 1, "psgd_ef_p_kernel"): 416681243,        # profiles/hbm_traffic_vgg19_powersgd.md
-    ("lstm_topk", 16, "topk_ef_hist_kernel"): 10615537092,       # profiles/hbm_traffic_lstm_topk.md
-    ("resnet18_topk_k99", 4, "topk_ef_hist_kernel"): 637198355,  # profiles/hbm_traffic_resnet18_topk_k99.md
+    ("lstm_topk", 16, "topk_ef_hist_kernel"): 10615536735,       # profiles/hbm_traffic_lstm_topk.md
+    ("resnet18_topk_k99", 4, "topk_ef_hist_kernel"): 637193697,  # profiles/hbm_traffic_resnet18_topk_k99.md
     ("resnet18_batch", 4, "batch_micro_kernel"): 313169661,      # profiles/hbm_traffic_resnet18_batch.md (levels switching)
 }
 
 # Counted traffic of all kernels of one step (sum of the per-kernel averages in the same summaries;
 # kernels that run once per window or on demand left out).  Key: (workload, W).
 MEASURED_STEP_TRAFFIC_BYTES = {
-    ("resnet18_topk", 4): 657244846 + 271195188 + 28079451 + 9426442 + 2454869 + 2102700,
+    ("resnet18_topk", 4): 657244796 + 267390242 + 28096254 + 9426446 + 2466338 + 2097376,
     ("resnet18_powersgd", 4): 635250034 + 191304669 + 12184522 + 3387700 + 47511470,
     ("vgg19_powersgd", 1): 416681243 + 88425680 + 6209777 + 1803930 + 86544871,
-    ("lstm_topk", 16): 10615537092 + 4293752083 + 453219090 + 143392484 + 30720369 + 11360915 + 4826527,
-    ("resnet18_topk_k99", 4): 637198355 + 435448780 + 19702025 + 5225137 + 2109251 + 2458556,
+    ("lstm_topk", 16): 10615536735 + 4250833287 + 453200928 + 143393238 + 30725046 + 11360930 + 4826538,
+    ("resnet18_topk_k99", 4): 637193697 + 436029832 + 19702033 + 5225139 + 2109252 + 2458557,
 }
 
 # Both compression levels are used while timing: the gradient statistics are stationary (every
