@@ -48,6 +48,35 @@ def _case_values(rng, case, n):
     raise KeyError(case)
 
 
+@pytest.mark.parametrize("W", [1, 3])
+def test_kept_entries_concentrated_in_a_few_quarters(W):
+    """K = 25 % and 45 % of layers whose large entries sit in one stretch: whole wave quarters
+    are kept, so a wave's list of payload entries fills up inside a chunk of groups and is
+    written out early, while other quarters keep nothing.  Aligned and misaligned layers, the
+    stretch at a different place for every worker."""
+    print(f"case concentrated W={W}", flush=True)
+    shapes = [(1, 5 * 8192, 0), (1, 3, 0), (3, 8192 + 1001, 1), (1, 2 * 8192 + 6, 0)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 45, 25)
+    rng = np.random.default_rng(77 + W)
+    for step in range(4):
+        if step == 2:
+            ora.level[:] = 0
+            gpu.set_state(H.oracle_state_blob(gpu, ora))
+        grads = []
+        for w in range(W):
+            g = rng.standard_normal(N) * 1e-3
+            for l in layers:
+                n = l.numel
+                lo = (n // 7) * ((w + step) % 5)
+                hi = min(n, lo + int(n * 0.4))
+                g[l.offset + lo:l.offset + hi] += np.sign(rng.standard_normal(hi - lo)) * (1.0 + rng.random(hi - lo))
+            grads.append(g.astype(np.float32))
+        _check_step(gpu, ora, grads, f"step {step}", check_state=(step % 2 == 1))
+    gpu.destroy()
+
+
 @pytest.mark.parametrize("crit,noncrit,den", [(10, 1, 100), (1, 1, 1), (1, 3, 1000), (99, 25, 100)])
 def test_ragged_misaligned_layers(crit, noncrit, den):
     """Many small layers at 16-byte-misaligned offsets, W = 3, several steps so that the
