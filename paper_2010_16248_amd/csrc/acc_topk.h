@@ -1169,22 +1169,22 @@ constexpr int kStgWords = 2 * kStgStride;
 // Running state of the ordered compaction of one worker's quarter.
 struct CompactRun { uint32_t eq_run, pos_run; };
 
-// One group of four elements per lane: which are selected, their payload entries, the zeros in e;
-// MEAN adds the kept values to acc.  The payload entries of the group are first put in order into
+// The compaction of the call-by-call path (one worker per grid row; the batched path has its own,
+// compact_mean_tile below).  One group of four elements per lane: which are selected, their
+// payload entries, the zeros in e.  The payload entries of the group are first put in order into
 // the wave's list in LDS, then written out by consecutive lanes to consecutive addresses: stores
 // of single words scattered over the lanes of four instructions cost a quarter of this kernel's
 // time.  HOLES: the layer keeps more than half of its entries (the
-// values go out dense, the indices name the dropped entries).
-// The pass is bound by the number of vector instructions per group, not by memory: everything
-// per element is kept free of branches.
+// values go out dense, the indices name the dropped entries).  Everything per element is kept
+// free of branches.
 // The second half of compact_group: the selection is known (msel: lane masks of the selected
 // elements per component, below: selected elements of the group in the lanes before this one,
 // total: in all lanes); mv: lane masks of the valid elements.
-template <bool AL, bool MEAN, bool DEFER, bool HOLES, class RareF>
+template <bool AL, bool HOLES, class RareF>
 __device__ __forceinline__ void compact_selected(const TileGeom& tg, int64_t layer_offset, const GroupSel& gs,
                                                  RareF rare, CompactRun& run, float* __restrict__ e,
                                                  int32_t* __restrict__ pidx, float* __restrict__ pval, int q,
-                                                 const float4& cur, int lane, float4& acc, uint32_t* stg,
+                                                 const float4& cur, int lane, uint32_t* stg,
                                                  const uint64_t (&msel)[4], const uint64_t (&mv)[4],
                                                  uint32_t below, uint32_t total) {
   const int32_t i0 = (int32_t)(tg.a0 + 4 * (int64_t)q - layer_offset);
@@ -1229,8 +1229,8 @@ __device__ __forceinline__ void compact_selected(const TileGeom& tg, int64_t lay
     for (uint32_t t0 = kWave; t0 < total; t0 += kWave) flush(t0 + lane);
   }
   __builtin_amdgcn_wave_barrier();
-  // DEFER: the zeros are not written; the next pass over Delta drops the kept entries itself
-  if (!DEFER && (sel[0] || sel[1] || sel[2] || sel[3])) {
+  // the residual: zeros where entries were kept
+  if (sel[0] || sel[1] || sel[2] || sel[3]) {
     float4 z = cur;
     if (sel[0]) z.x = 0.f;
     if (sel[1]) z.y = 0.f;
@@ -1239,23 +1239,17 @@ __device__ __forceinline__ void compact_selected(const TileGeom& tg, int64_t lay
     stq<AL>(e, tg.a0, tg.lo, tg.hi, q, z);
   }
   run.pos_run += total;
-  if (MEAN) {                                               // acc is never -0, so adding +0 changes nothing
-    acc.x += sel[0] ? cur.x : 0.f;
-    acc.y += sel[1] ? cur.y : 0.f;
-    acc.z += sel[2] ? cur.z : 0.f;
-    acc.w += sel[3] ? cur.w : 0.f;
-  }
 }
 
 // The selection is taken before the two payload layouts part ways, so that every compare sits next
 // to its ballot (a predicate that crosses a branch is carried as a 0 / 1 value per lane and
 // compared again) and only lane masks in scalar registers cross.
-template <bool AL, bool MEAN, bool DEFER, class RareF>
+template <bool AL, class RareF>
 __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan& span, int64_t layer_offset,
                                               const GroupSel& gs, RareF rare, CompactRun& run,
                                               float* __restrict__ e, int32_t* __restrict__ pidx,
                                               float* __restrict__ pval, int q, uint64_t m_span,
-                                              const float4& cur, int lane, float4& acc, uint32_t* stg) {
+                                              const float4& cur, int lane, uint32_t* stg) {
   const bool qa = lane_bit(m_span);                         // m_span: the lanes whose group q is in the span
   uint64_t mv[4], msel[4];
   uint32_t key[4];
@@ -1279,11 +1273,9 @@ __device__ __forceinline__ void compact_group(const TileGeom& tg, const WaveSpan
     uint64_t mvs[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) mvs[c] = scalar_mask(mv[c]);
-    compact_selected<AL, MEAN, DEFER, true>(tg, layer_offset, gs, rare, run, e, pidx, pval, q, cur, lane, acc, stg,
-                                            msel, mvs, below, total);
+    compact_selected<AL, true>(tg, layer_offset, gs, rare, run, e, pidx, pval, q, cur, lane, stg, msel, mvs, below, total);
   } else if (total != 0u) {
-    compact_selected<AL, MEAN, DEFER, false>(tg, layer_offset, gs, rare, run, e, pidx, pval, q, cur, lane, acc, stg,
-                                             msel, mv, below, total);
+    compact_selected<AL, false>(tg, layer_offset, gs, rare, run, e, pidx, pval, q, cur, lane, stg, msel, mv, below, total);
   }
 }
 
@@ -1308,12 +1300,11 @@ __device__ __forceinline__ void compact_tile(const Ws& ws, int w, const FlatTile
   int32_t* pidx = ws.pay_idx + (int64_t)w * ws.pay_stride + L.pay_off;
   float* pval = ws.pay_val + (int64_t)w * ws.pay_stride + L.pay_off;
   const int64_t layer_offset = L.offset;                   // by value: nothing is re-read inside the loop
-  float4 unused = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
     const int q = q0 + lane;
     const float4 nn = ld_span<AL>(e, tg, span, q + 2 * kWave);
-    compact_group<AL, false, false>(tg, span, layer_offset, gs, rare, run, e, pidx, pval, q,
-                                    scalar_mask(ballot64(q < span.qend)), cur, lane, unused, stg);
+    compact_group<AL>(tg, span, layer_offset, gs, rare, run, e, pidx, pval, q,
+                      scalar_mask(ballot64(q < span.qend)), cur, lane, stg);
     cur = nxt;
     nxt = nn;
   }
