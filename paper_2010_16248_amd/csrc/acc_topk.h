@@ -1330,8 +1330,9 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
 // kChunkGroups groups and, inside a chunk, worker by worker: the sums of a chunk live in registers,
 // a worker's selection state is fetched and its payload entries are written once per chunk (the
 // entries of a chunk are listed in LDS first), and the group a worker has just used is
-// requested for the next worker at once, so a chunk less a group is always in flight.  The
-// running compaction state of every worker is kept in one lane each.
+// requested for the next worker at once, so that it has the rest of the chunk's work to arrive
+// (the compiler waits for all requests at the top of a worker's turn).  The running compaction
+// state of every worker is kept in one lane each.
 constexpr int kChunkGroups = 4;
 constexpr int kChunkCap = 2 * kGroupList;          // listed entries at which a wave writes its list out early
 constexpr int kChunkStride = kChunkCap + kWave;    // + one slot per lane for the unselected elements
@@ -1362,10 +1363,10 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   uint32_t eq_run_v = mine.eq_before;
   uint32_t pos_run_v = mine.gt_before + min(mine.ktie, mine.eq_before);
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-  // group j of chunk c of worker w (past the end of the quarter an aligned tile re-reads its last
-  // group: nobody looks at it)
-  // q_end: the end of the span, or its begin for a request that nobody will look at (every lane
-  // then asks for the same 16 bytes, or for nothing)
+  // group j of chunk c of the worker whose memory is e (past the end of the quarter an aligned
+  // tile re-reads its last group: nobody looks at it).  q_end: the end of the span, or its begin
+  // for a request that nobody will look at (every lane then asks for the same 16 bytes, or for
+  // nothing)
   auto load_group = [&](const float* __restrict__ e, int c, int j, int q_end) {
     const int q = span.qbeg + (c * G + j) * kWave + lane;
     if (AL) return ldq_clamped(e, tg.a0, min(q, max(q_end - 1, span.qbeg)));
