@@ -26,12 +26,14 @@ def _layer_mask(layers, n):
     return m
 
 
-@pytest.mark.parametrize("wd", [0.0, 5e-4])
-def test_topk_fused_update_is_bit_exact(wd):
+@pytest.mark.parametrize("wd,crit,noncrit,initial", [(0.0, 10, 1, 1), (5e-4, 10, 1, 1), (5e-4, 99, 25, 1),
+                                                     (0.0, 99, 25, 0)])
+def test_topk_fused_update_is_bit_exact(wd, crit, noncrit, initial):
     """Ragged misaligned layers (some elements of the flat buffers belong to no layer and must
     not be touched), layers of several tiles with ragged tails, W = 3, five steps so that the
-    velocity and the error memory both feed back."""
-    print(f"case topk update wd={wd}", flush=True)
+    velocity and the error memory both feed back.  K 99 % is the values-and-holes payload layout,
+    which the fused kernel instantiates separately."""
+    print(f"case topk update wd={wd} K {crit}/{noncrit} level {initial}", flush=True)
     small = wl.random_layers(seed=21, n_layers=9, max_rows=30, max_cols=200)
     base = max(l.offset + l.rows * l.cols for l in small)
     base = (base + 7) // 4 * 4 + 1                                   # a misaligned start
@@ -39,9 +41,9 @@ def test_topk_fused_update_is_bit_exact(wd):
     layers = H.layer_tuples(small) + big
     N = big[1][0] + 37 * 1001                                        # gaps inside, none behind
     W = 3
-    gpu = B.Accordion(B.ACC_TOPK, layers, W, 10, 1, 100, 0.5, 1, None)
+    gpu = B.Accordion(B.ACC_TOPK, layers, W, crit, noncrit, 100, 0.5, initial, None)
     assert gpu.n_params == N
-    ora = orc.AccordionOracle(orc.TOPK, layers, W, 10, 1, 100, 0.5, 1, None)
+    ora = orc.AccordionOracle(orc.TOPK, layers, W, crit, noncrit, 100, 0.5, initial, None)
     ora.N = N
     ora.e = np.zeros((W, N), np.float32)
     ora.A = np.zeros(N, np.float32)
