@@ -1339,7 +1339,8 @@ constexpr int kChunkStride = kChunkCap + kWave;    // + one slot per lane for th
 constexpr int kChunkWords = 2 * kChunkStride;      // indices, then values
 
 // UPD: the mean is not written out but drives the optimizer step on the weights and the velocity
-// (requested while the last worker of the chunk is compacted).
+// (requested group by group once the chunk's sums are complete: requested earlier they cost
+// 32 registers across the last worker's turn and two waves of occupancy).
 // HOLES: the layer keeps more than half of its entries (static per level, the same for every worker).
 template <bool AL, bool UPD, bool HOLES>
 __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& ft, const LayerDev& L,
@@ -1491,16 +1492,6 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
         }
         // the registers of the group are free: request what they hold next
         cur[j] = load_group(e_next, c_next, j, q_end_next);
-        if (UPD && last_w) {                                 // the chunk's weights and velocity
-          const int q = span.qbeg + (c * G + j) * kWave + lane;
-          if (sink.stream_wv) {                               // uniform: see stream_wv() on the host side
-            wq[j] = ld_span<AL, true>(sink.wt, tg, span, q);
-            vq[j] = ld_span<AL, true>(sink.vel, tg, span, q);
-          } else {
-            wq[j] = ld_span<AL>(sink.wt, tg, span, q);
-            vq[j] = ld_span<AL>(sink.vel, tg, span, q);
-          }
-        }
         if (j + 1 < G && cnt > (uint32_t)(kChunkCap - kGroupList)) write_list();   // room for one more group
       }
       write_list();
@@ -1509,6 +1500,15 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const int q = span.qbeg + (c * G + j) * kWave + lane;
+      if (UPD) {                                           // the group's weights and velocity
+        if (sink.stream_wv) {                               // uniform: see stream_wv() on the host side
+          wq[j] = ld_span<AL, true>(sink.wt, tg, span, q);
+          vq[j] = ld_span<AL, true>(sink.vel, tg, span, q);
+        } else {
+          wq[j] = ld_span<AL>(sink.wt, tg, span, q);
+          vq[j] = ld_span<AL>(sink.vel, tg, span, q);
+        }
+      }
       if (q < span.qend) {
         const float4 a = acc[j];
         const float4 v = pow2 ? make_float4(a.x * rw, a.y * rw, a.z * rw, a.w * rw)
