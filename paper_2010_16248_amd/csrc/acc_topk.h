@@ -12,12 +12,13 @@
 //                      writes the tile's level-2 counts of the guessed bins.
 //   P12 topk_pick12    one workgroup per (worker, layer): b1 from the histogram; if it is one
 //                      of the guessed bins, b2 from the sum of the tiles' level-2 counts.
-//                      Layers of a single tile are decided here completely, from Delta.
 //   C3  topk_count3    one workgroup per tile: per quarter the entries above bin (b1, b2); the
 //                      keys inside (b1, b2) go to a per-layer list with their quarter.
 //   P3  topk_pick3     per (worker, layer): levels 3 and 4 on the list, threshold key T and tie
 //                      quota; the listed keys are added to their quarters' counts; exclusive
 //                      prefix over the quarters = payload position of every quarter.
+//                      Layers of a single tile, which skip the passes before, are decided here
+//                      completely, from Delta, by their own workgroups.
 //                      A layer whose guess missed (first step, level switch, shifted
 //                      distribution) or whose list overflowed (huge tie class) is decided here
 //                      by sweeps of one workgroup over Delta / the segments (correct, slow).
@@ -632,8 +633,7 @@ __device__ __forceinline__ void pick_small_layer(const Ws& ws, const LayerDev& L
 
 __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, int w0) {
   __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3], scratch[4], qcnt[8];
-  __shared__ uint32_t skeys[kTile];
+  __shared__ uint32_t out[3], scratch[4];
   const int li = blockIdx.x;
   const int w = w0 + blockIdx.y;
   const int tid = threadIdx.x;
@@ -642,10 +642,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   const int64_t wl = (int64_t)w * ws.L + li;
   const int lv = ws.level[li];
   const uint32_t k = (uint32_t)L.k[lv];
-  if (L.ntiles == 1) {
-    pick_small_layer(ws, L, w, li, k, hist, skeys, out, scratch, qcnt);
-    return;
-  }
+  if (L.ntiles == 1) return;                               // decided by the last pick kernel, from Delta
   SelState* sp = ws.sel + wl;
   __shared__ uint32_t sub[kSub2];
   __shared__ uint32_t nb0;
@@ -756,7 +753,7 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   // the segment is requested before the layer's entry and its state have arrived
   const QuarterKeys qk = load_quarter_keys(ws, qslot, lane);
   const LayerDev& L = ws.layers[ft.layer];
-  if (L.ntiles == 1) return;                               // decided by the first pick kernel
+  if (L.ntiles == 1) return;                               // decided by the last pick kernel
   const uint32_t side = sp->side, b1 = sp->b1;
   uint32_t b2 = sp->b2;
   if (sp->mode != 0u) {                                    // uniform over the workgroup
@@ -816,7 +813,14 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const LayerDev& L = ws.layers[li];
-  if (L.ntiles == 1) return;                               // decided by the first pick kernel
+  if (L.ntiles == 1) {
+    // A layer of a single tile needs none of the passes in between: its workgroup, idle otherwise,
+    // decides it here from Delta (in the first pick kernel, where this used to happen, these layers
+    // were the ones that kernel waited for: 3 us of every step).
+    static_assert(kLdsList >= kTile && 2 * kPickWaves >= 8, "the key list holds a tile's keys");
+    if (!BIG) pick_small_layer(ws, L, w, li, (uint32_t)L.k[ws.level[li]], hist, llist, out, scratch, &wsum[0][0]);
+    return;
+  }
   const int nq = 4 * L.ntiles;
   if (BIG != (nq > acc::kLdsQuarters)) return;             // the other instantiation's layer
   const int64_t wl = (int64_t)w * ws.L + li;
