@@ -299,9 +299,10 @@ int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
  * (a pair of events costs 5 to 7 us of stream time, a few per cent of a step); 0 switches it
  * off.  accordion_get_profile
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
- * of one stage since profiling was last switched on.  Stages are numbered 0 .. ACC_N_STAGES-1;
- * accordion_stage_name gives the kernel's name (NULL if out of range). */
-#define ACC_N_STAGES 32
+ * of one stage since profiling was last switched on.  Stages are numbered from 0, fewer than
+ * ACC_N_STAGES of them; accordion_stage_name gives the kernel's name, NULL beyond the last stage
+ * (accordion_get_profile returns ACC_EINVAL there). */
+#define ACC_N_STAGES 48
 int32_t accordion_set_profiling(acc_ctx* ctx, int32_t enable);
 int32_t accordion_get_profile(acc_ctx* ctx, int32_t stage, double* total_ms, int64_t* launches);
 const char* accordion_stage_name(int32_t stage);

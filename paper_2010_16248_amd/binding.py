@@ -21,9 +21,7 @@ ACC_MAX_RANK = 4
 
 _STATUS = {0: "ACC_OK", 1: "ACC_EINVAL", 2: "ACC_ESTATE", 3: "ACC_ENOSPACE", 4: "ACC_EHIP"}
 
-# ACCORDION_LIB selects another build of the same library (e.g. one with extra checks)
-LIB_PATH = os.environ.get("ACCORDION_LIB") or os.path.join(
-    os.path.dirname(os.path.abspath(__file__)), "libaccordion.so")
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaccordion.so")
 
 
 class acc_layer(C.Structure):
@@ -59,7 +57,7 @@ EXPORTS = [
     "accordion_set_profiling", "accordion_get_profile", "accordion_stage_name",
     "accordion_probe_copy", "accordion_topk_stats", "accordion_flush",
 ]
-ACC_N_STAGES = 32
+ACC_N_STAGES = 48     # upper bound of the stage numbers; accordion_stage_name is NULL beyond the last
 
 
 def load_library() -> C.CDLL:
@@ -352,6 +350,8 @@ class Accordion:
         """{kernel name: (total milliseconds, launches)} since profiling was switched on."""
         out = {}
         for s in range(ACC_N_STAGES):
+            if self._lib.accordion_stage_name(s) is None:
+                break
             ms, n = C.c_double(0.0), C.c_int64(0)
             _check(self._lib, self.ctx, self._lib.accordion_get_profile(self.ctx, s, C.byref(ms), C.byref(n)))
             if n.value:

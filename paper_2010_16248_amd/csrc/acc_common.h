@@ -13,6 +13,10 @@ constexpr int kT2Group = 16;             // TopK: consecutive tiles of a layer t
 constexpr int kQuadIters = (kTile / 4 + 1 + kFlatThreads - 1) / kFlatThreads;  // 9
 constexpr int kMatRows = 64;             // matrix tile: 64 rows x 256 columns
 constexpr int kMatCols = 256;
+#ifndef ACC_Q_ROWS
+#define ACC_Q_ROWS 128
+#endif
+constexpr int kQRows = ACC_Q_ROWS;       // rows of a tile of the right product Q = Delta^T P^ (a multiple of 4)
 constexpr int kHistBins = 2048;          // 11 key bits per radix level
 constexpr int kSubCap = 256;             // staged keys per guessed bin and wave quarter of a flat tile (TopK)
 // a wave quarter has at most ceil((kTile / 4 + 1) / 4) 16-byte groups: iterations of 64 lanes
@@ -29,7 +33,7 @@ struct LayerDev {
   int32_t rank[2];       // effective rank at level 0 (non-critical) / 1 (critical)
   int32_t k[2];          // TopK kept count at level 0 / 1
   int32_t n_colchunks;   // ceil(cols / kMatCols)
-  int32_t n_rowblocks;   // ceil(rows / kMatRows)
+  int32_t n_rowblocks;   // ceil(rows / kQRows)
   int32_t tile0;         // first flat tile of the layer
   int32_t ntiles;        // number of flat tiles
   int32_t t2slot0;       // TopK: the layer's first slot in a worker's level-2 count array (one slot per kT2Group tiles)
@@ -38,8 +42,8 @@ struct LayerDev {
                          // (4 * tile0 + layer index: one spare slot per layer for the totals)
   int64_t q_off;         // into Q      (cols rows of kMaxRank floats, zero beyond rmax)
   int64_t p_off;         // into Phat   (rows * rmax floats)
-  int64_t ppart_off;     // into one worker's P partials (n_colchunks * rows * rmax)
-  int64_t qpart_off;     // into one worker's Q partials (n_rowblocks * cols * rmax)
+  int64_t ppart_off;     // into one worker's P partials (n_colchunks * rows * rmax doubles)
+  int64_t qpart_off;     // into one worker's Q partials (n_rowblocks * cols * rmax doubles)
   int64_t pay_off;       // into one worker's payload arrays (entries)
   int64_t vec_off;       // into the 1-D mean buffer (PowerSGD, 1-D layers)
 };
@@ -49,6 +53,7 @@ struct LayerDev {
 struct FlatTile { int32_t layer, start, count, qslot0; };
 struct MatTile { int32_t layer, row0, col0, pad; };
 struct QTile { int32_t layer, col0; };
+struct PTile { int32_t layer, row0; };   // a block of rows of a matrix layer's P (PowerSGD, mean over workers)
 
 // Per (worker, layer) state of the TopK selection of the current step.
 struct SelState {
@@ -87,14 +92,17 @@ struct Ws {
   double* sq_part;             // per flat tile: sum over the window of ||g_0||^2 (MSDR detector)
   const FlatTile* ftiles;
   const MatTile* mtiles;
+  const MatTile* qmtiles;      // kQRows x 256 tiles of the matrix layers (right product)
   const QTile* qtiles;
   const int32_t* vectiles;     // flat-tile ids of 1-D layers (PowerSGD)
   const int32_t* matlayers;    // layer ids of matrix layers (PowerSGD)
   // PowerSGD
   float* Q;
   float* Phat;
-  float* Ppart;  int64_t ppart_stride;
-  float* Qpart;  int64_t qpart_stride;
+  double* Ppart; int64_t ppart_stride;   // per worker and 256-column chunk: that chunk's share of P_w, fp64
+  double* Pwork;               // p_total doubles: working columns of the orthogonalisation of tall layers
+  const PTile* ptiles;         // row blocks of the matrix layers (mean of P)
+  double* Qpart; int64_t qpart_stride;   // per worker and 64-row block: that block's share of Q_w, fp64
   float* vecmean;
   uint32_t* pending;           // one word: workers whose e still holds Delta (residual not formed yet)
   // TopK
@@ -123,7 +131,7 @@ struct Ws {
   int64_t n_model;             // elements that belong to a layer
   int64_t N;
   int32_t W, L, rmax;
-  int32_t n_ftiles, n_mtiles, n_qtiles, n_vectiles, n_mat;
+  int32_t n_ftiles, n_mtiles, n_qmtiles, n_qtiles, n_vectiles, n_mat, n_ptiles;
   int32_t n_t2slots;           // TopK: slots of t2 per worker
   float eta;
 };
@@ -155,6 +163,28 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
 #pragma unroll
   for (int d = 1; d < kWave; d <<= 1) v += __shfl_xor(v, d, kWave);
   return v;
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double readlane_d(double v, int l) {
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
+                          __builtin_amdgcn_readlane(__double2loint(v), l));
+}
+
+// fp64 sum over the 64 lanes in the order of wave_sum (lane exchanges through DPP moves, no LDS
+// traffic), same value returned to every lane.  All 64 lanes must be active.
+__device__ __forceinline__ double wave_sum_d(double v) {
+  v += dpp_d<0xB1>(v);
+  v += dpp_d<0x4E>(v);
+  v += dpp_d<0x141>(v);
+  v += dpp_d<0x140>(v);
+  return (readlane_d(v, 0) + readlane_d(v, 16)) + (readlane_d(v, 32) + readlane_d(v, 48));
 }
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {

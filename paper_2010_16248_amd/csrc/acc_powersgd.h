@@ -96,7 +96,7 @@ __device__ __forceinline__ float low_rank_entry(const float (&p)[kMaxRank], cons
 // the previous P^ (rows in ws.Phat) and Q~ (= the warm start, first rp columns).
 template <int R, bool V4>
 __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const float* __restrict__ g,
-                          float* __restrict__ e, float* __restrict__ A, float* __restrict__ ppart, int rp,
+                          float* __restrict__ e, float* __restrict__ A, double* __restrict__ ppart, int rp,
                           float (*ps)[kMaxRank]) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -149,17 +149,21 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
           for (int v = 0; v < 4; ++v) ad[b][v] += gd[b][v];
           store_row<V4, kPsgdStreamA>(A, rb, col, cm, ad[b]);
         }
-        float acc[R];
+        // the chunk's share of P_w's row in fp64: products of fp32 values are exact there, the
+        // sums carry an error far below the fp32 rounding of the stored P_w
+        double dd[4], acc[R];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dd[v] = (double)d[v];
 #pragma unroll
         for (int k = 0; k < R; ++k) {
-          float s = d[0] * q[0][k];
-          s = fmaf(d[1], q[1][k], s);
-          s = fmaf(d[2], q[2][k], s);
-          s = fmaf(d[3], q[3][k], s);
-          acc[k] = wave_sum(s);
+          double s = dd[0] * (double)q[0][k];
+          s = fma(dd[1], (double)q[1][k], s);
+          s = fma(dd[2], (double)q[2][k], s);
+          s = fma(dd[3], (double)q[3][k], s);
+          acc[k] = wave_sum_d(s);
         }
         if (lane == 0) {
-          float* dst = ppart + L.ppart_off + ((int64_t)chunk * L.rows + i) * ws.rmax;
+          double* dst = ppart + L.ppart_off + ((int64_t)chunk * L.rows + i) * ws.rmax;
 #pragma unroll
           for (int k = 0; k < R; ++k) dst[k] = acc[k];
         }
@@ -197,7 +201,7 @@ __global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradP
   const LayerDev& L = ws.layers[t.layer];
   const int r = L.rank[ws.level[t.layer]];
   const int rp = ((pending >> w) & 1u) ? ws.rank_used[t.layer] : 0;   // rank of the previous step's factors
-  float* ppart = ws.Ppart + (int64_t)w * ws.ppart_stride;
+  double* ppart = ws.Ppart + (int64_t)w * ws.ppart_stride;
   if (L.vec4) {
     switch (r) {
       case 1: ef_p_tile<1, true>(ws, L, t, g, e, A, ppart, rp, ps); break;
@@ -216,172 +220,152 @@ __global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradP
 }
 
 // ---- aggregate 0: P_bar = mean over workers (and column chunks), Gram-Schmidt -----------
+//
+// Precision.  Gram-Schmidt carries an error of its input into column k multiplied by the
+// condition number of P_bar, and P_bar = Delta_bar Q is as badly conditioned as the warm start Q
+// happens to be (a 2 x 2 Q with condition 2000 occurs among random starts).  So the whole chain
+// that leads to P^ runs in fp64 and rounds to fp32 exactly where the method stores an fp32
+// quantity: the products Delta Q are accumulated in fp64 per 256-column chunk (first pass), a
+// worker's chunks are summed in fp64 and rounded (P_w), the workers' P_w are summed in fp64,
+// divided by W and rounded (P_bar), the projections and norms of Gram-Schmidt are fp64 and the
+// finished column is rounded (P^).  The passes over Delta are bound by memory either way.
 
 constexpr int kOrthThreads = 1024;
 constexpr int kOrthWaves = kOrthThreads / kWave;
 
+// P_bar[i][k] = fl32( (sum_w fl32(sum_c partial[w][c][i][k])) / W ), chunks in index order.
+// One workgroup per 16 rows of a layer; thread = (share, row, column of P), four shares per entry:
+// share s sums the workers s, s + 4, ... (each worker's chunks in fp64, rounded to the fp32 value
+// P_w), then the four shares are added in order.  Many small workgroups: the partial sums of a
+// layer (1.2 MB for the largest ResNet-18 layer at four workers) are read by many compute units
+// at once, and a thread waits for few dependent batches of loads.
+constexpr int kPmeanRows = 16;
+constexpr int kPmeanLoads = 8;   // partial sums a thread has in flight
+
+__global__ __launch_bounds__(256) void psgd_pmean_kernel(const Ws ws) {
+  __shared__ double share_sum[4][kPmeanRows * 4];
+  const PTile t = ws.ptiles[blockIdx.x];
+  const LayerDev& L = ws.layers[t.layer];
+  const int r = L.rank[ws.level[t.layer]];
+  const int share = threadIdx.x >> 6, slot = threadIdx.x & 63;
+  const int i = t.row0 + (slot >> 2), k = slot & 3;
+  const bool live = i < L.rows && k < r;
+  double total = 0.0;
+  if (live) {
+    const int nc = L.n_colchunks;
+    const int64_t cstride = (int64_t)L.rows * ws.rmax;
+    const double* base = ws.Ppart + L.ppart_off + (int64_t)i * ws.rmax + k;
+    for (int w = share; w < ws.W; w += 4) {
+      const double* src = base + (int64_t)w * ws.ppart_stride;
+      double s = 0.0;
+      for (int c0 = 0; c0 < nc; c0 += kPmeanLoads) {
+        double v[kPmeanLoads];
+#pragma unroll
+        for (int u = 0; u < kPmeanLoads; ++u) v[u] = src[(int64_t)min(c0 + u, nc - 1) * cstride];
+#pragma unroll
+        for (int u = 0; u < kPmeanLoads; ++u) s += (c0 + u < nc) ? v[u] : 0.0;
+      }
+      total += (double)(float)s;                            // P_w is an fp32 quantity
+    }
+  }
+  share_sum[share][slot] = total;
+  __syncthreads();
+  if (share == 0 && live) {
+    const double sum = ((share_sum[0][slot] + share_sum[1][slot]) + share_sum[2][slot]) + share_sum[3][slot];
+    ws.Phat[L.p_off + (int64_t)i * ws.rmax + k] = (float)(sum / (double)ws.W);
+  }
+}
+
 // Sum over the threads of the orthogonalisation workgroup, same value for every thread.  `slot`
 // alternates between calls so that one barrier per call is enough.
 // Only the first nwaves waves of the workgroup are still running (the others have left).
-__device__ __forceinline__ float block_sum_orth(float v, float (*red)[kOrthWaves], int& slot, int nwaves) {
-  v = wave_sum(v);
+__device__ __forceinline__ double block_sum_orth(double v, double (*red)[kOrthWaves], int& slot, int nwaves) {
+  v = wave_sum_d(v);
   if (nwaves == 1) return v;
   const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) red[slot][wave] = v;
   __syncthreads();
-  float r = 0.f;
+  double r = 0.0;
   for (int i = 0; i < nwaves; ++i) r += red[slot][i];
   slot ^= 1;
   return r;
 }
 
-// Sum over workers and over the partial results of one worker (column chunks of P, row blocks
-// of Q) for one row of r values, divided by W.  The W * nparts addends are independent loads;
-// they are issued eight at a time (unconditionally, from clamped addresses, so that all eight are
-// in flight together) and added in a fixed order (worker-major).  The calling thread takes the
-// addends first, first + stride, ...
-template <int R, int U = 8>
-__device__ __forceinline__ void sum_of_partials(const float* __restrict__ base, int64_t wstride, int W,
-                                                int nparts, int64_t pstride, int first, int stride,
-                                                float (&acc)[R], bool vec4 = false) {
-#pragma unroll
-  for (int k = 0; k < R; ++k) acc[k] = 0.f;
-  const int np = W * nparts;
-  for (int p0 = first; p0 < np; p0 += U * stride) {
-    float v[U][R];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int p = min(p0 + u * stride, np - 1);
-      const int w = p / nparts, c = p - w * nparts;
-      const float* src = base + (int64_t)w * wstride + (int64_t)c * pstride;
-      if (vec4) {                                           // rows of four floats, 16-byte aligned: one load
-        const float4 x = *reinterpret_cast<const float4*>(src);
-        const float xs[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-        for (int k = 0; k < R; ++k) v[u][k] = xs[k];
-      } else {
-#pragma unroll
-        for (int k = 0; k < R; ++k) v[u][k] = src[k];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int k = 0; k < R; ++k) acc[k] += (p0 + u * stride < np) ? v[u][k] : 0.f;
-  }
-}
-
+// Modified Gram-Schmidt over the r columns of P_bar (in ws.Phat, fp32), in column order, in
+// fp64; a column of zero length stays zero; P^ (fp32) replaces P_bar.  Layers of up to
+// kOrthThreads rows live in registers, one row per thread; taller ones in an fp64 copy in
+// global memory (each thread only ever touches its own rows).
 template <int R>
-__device__ __forceinline__ void mean_of_partials(const float* __restrict__ base, int64_t wstride,
-                                                 int W, int nparts, int64_t pstride, float (&out)[R]) {
-  sum_of_partials<R>(base, wstride, W, nparts, pstride, 0, 1, out);
-#pragma unroll
-  for (int k = 0; k < R; ++k) out[k] = out[k] / (float)W;
-}
-
-// Modified Gram-Schmidt over the r columns of P_bar, in column order; a column of zero
-// length stays zero.  Layers of up to kOrthThreads rows live in registers, one row per thread
-// (short layers: several threads share the partial sums of a row and one of them keeps it);
-// taller ones in global memory (each thread only ever touches its own rows).
-constexpr int kOrthLoads = 12;   // partial rows a thread has in flight (8: 1.6 us slower; 16 spills)
-
-template <int R>
-__device__ void orth_layer(const Ws& ws, const LayerDev& L, float (*red)[kOrthWaves], float* psum) {
+__device__ void orth_layer(const Ws& ws, const LayerDev& L, double (*red)[kOrthWaves]) {
   const int n = L.rows;
   const int tid = threadIdx.x;
   float* ph = ws.Phat + L.p_off;
-  const float* pbase = ws.Ppart + L.ppart_off;
-  const int64_t pstride = (int64_t)L.rows * ws.rmax;
-  const float fw = (float)ws.W;
   int slot = 0;
   if (n <= kOrthThreads) {
-    int tpr = 1;                                            // threads per row, workgroup-uniform
-    while (tpr < 16 && 2 * tpr * n <= kOrthThreads) tpr *= 2;
-    const int rows_pad = kOrthThreads / tpr;                // >= n; thread t: row t % rows_pad, share t / rows_pad
-    const int row = tid & (rows_pad - 1), sub = tid / rows_pad;
-    float part[R];
+    const int nwaves = (n + kWave - 1) / kWave;
+    if (tid >= nwaves * kWave) return;                       // whole waves
+    const bool holder = tid < n;
+    double v[R];
 #pragma unroll
-    for (int k = 0; k < R; ++k) part[k] = 0.f;
-    if (row < n)
-      sum_of_partials<R, kOrthLoads>(pbase + (int64_t)row * ws.rmax, ws.ppart_stride, ws.W, L.n_colchunks, pstride,
-                                     sub, tpr, part, ws.rmax == 4);
-#pragma unroll
-    for (int k = 0; k < R; ++k) psum[tid * kMaxRank + k] = part[k];
-    __syncthreads();
-    if (tid >= rows_pad) return;                            // whole waves (rows_pad is a multiple of 64)
-    const int nwaves = rows_pad / kWave;
-    const bool holder = row < n;
-    float v[R];
-#pragma unroll
-    for (int k = 0; k < R; ++k) v[k] = 0.f;
-    if (holder) {
-      for (int j = 0; j < tpr; ++j)
-#pragma unroll
-        for (int k = 0; k < R; ++k) v[k] += psum[(j * rows_pad + tid) * kMaxRank + k];
-#pragma unroll
-      for (int k = 0; k < R; ++k) v[k] = v[k] / fw;
-    }
+    for (int k = 0; k < R; ++k) v[k] = holder ? (double)ph[(int64_t)tid * ws.rmax + k] : 0.0;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
 #pragma unroll
       for (int j = 0; j < R; ++j) {
         if (j < k) {
-          const float d = block_sum_orth(v[j] * v[k], red, slot, nwaves);
-          v[k] = fmaf(-d, v[j], v[k]);
+          const double d = block_sum_orth(v[j] * v[k], red, slot, nwaves);
+          v[k] = fma(-d, v[j], v[k]);
         }
       }
-      const float nn = block_sum_orth(v[k] * v[k], red, slot, nwaves);
-      const float nrm = sqrtf(nn);
-      v[k] = (nrm > 0.f) ? v[k] / nrm : 0.f;
+      const double nn = block_sum_orth(v[k] * v[k], red, slot, nwaves);
+      const double nrm = sqrt(nn);
+      v[k] = (nrm > 0.0) ? v[k] / nrm : 0.0;
     }
     if (holder) {
 #pragma unroll
-      for (int k = 0; k < R; ++k) ph[(int64_t)row * ws.rmax + k] = v[k];
+      for (int k = 0; k < R; ++k) ph[(int64_t)tid * ws.rmax + k] = (float)v[k];
     }
   } else {
-    for (int i = tid; i < n; i += kOrthThreads) {
-      float pb[R];
-      mean_of_partials<R>(pbase + (int64_t)i * ws.rmax, ws.ppart_stride, ws.W, L.n_colchunks, pstride, pb);
+    double* pw = ws.Pwork + L.p_off;
+    for (int i = tid; i < n; i += kOrthThreads)
 #pragma unroll
-      for (int k = 0; k < R; ++k) ph[(int64_t)i * ws.rmax + k] = pb[k];
-    }
+      for (int k = 0; k < R; ++k) pw[(int64_t)i * ws.rmax + k] = (double)ph[(int64_t)i * ws.rmax + k];
     for (int k = 0; k < R; ++k) {
       for (int j = 0; j < k; ++j) {
-        float d = 0.f;
+        double d = 0.0;
         for (int i = tid; i < n; i += kOrthThreads)
-          d = fmaf(ph[(int64_t)i * ws.rmax + j], ph[(int64_t)i * ws.rmax + k], d);
+          d = fma(pw[(int64_t)i * ws.rmax + j], pw[(int64_t)i * ws.rmax + k], d);
         d = block_sum_orth(d, red, slot, kOrthWaves);
         for (int i = tid; i < n; i += kOrthThreads)
-          ph[(int64_t)i * ws.rmax + k] =
-              fmaf(-d, ph[(int64_t)i * ws.rmax + j], ph[(int64_t)i * ws.rmax + k]);
+          pw[(int64_t)i * ws.rmax + k] = fma(-d, pw[(int64_t)i * ws.rmax + j], pw[(int64_t)i * ws.rmax + k]);
       }
-      float nn = 0.f;
+      double nn = 0.0;
       for (int i = tid; i < n; i += kOrthThreads) {
-        const float x = ph[(int64_t)i * ws.rmax + k];
-        nn = fmaf(x, x, nn);
+        const double x = pw[(int64_t)i * ws.rmax + k];
+        nn = fma(x, x, nn);
       }
       nn = block_sum_orth(nn, red, slot, kOrthWaves);
-      const float nrm = sqrtf(nn);
+      const double nrm = sqrt(nn);
       for (int i = tid; i < n; i += kOrthThreads) {
-        const float x = ph[(int64_t)i * ws.rmax + k];
-        ph[(int64_t)i * ws.rmax + k] = (nrm > 0.f) ? x / nrm : 0.f;
+        const double x = (nrm > 0.0) ? pw[(int64_t)i * ws.rmax + k] / nrm : 0.0;
+        pw[(int64_t)i * ws.rmax + k] = x;
+        ph[(int64_t)i * ws.rmax + k] = (float)x;
       }
     }
   }
 }
 
 __global__ __launch_bounds__(kOrthThreads) void psgd_orth_kernel(const Ws ws, const GradPtrs gp) {
-  __shared__ float red[2][kOrthWaves];
-  __shared__ float psum[kOrthThreads * kMaxRank];
+  __shared__ double red[2][kOrthWaves];
   if ((int)blockIdx.x >= ws.n_mat) {
     // 1-D layers are sent raw: mean over workers in worker order
     const FlatTile ft = ws.ftiles[ws.vectiles[blockIdx.x - ws.n_mat]];
     const LayerDev& L = ws.layers[ft.layer];
     for (int i = threadIdx.x; i < ft.count; i += kOrthThreads) {
       const int64_t a = L.offset + ft.start + i;
-      float s = gp.p[0][a];
-      for (int w = 1; w < ws.W; ++w) s += gp.p[w][a];
-      ws.vecmean[L.vec_off + ft.start + i] = s / (float)ws.W;
+      double s = (double)gp.p[0][a];
+      for (int w = 1; w < ws.W; ++w) s += (double)gp.p[w][a];
+      ws.vecmean[L.vec_off + ft.start + i] = (float)(s / (double)ws.W);
     }
     return;
   }
@@ -390,36 +374,45 @@ __global__ __launch_bounds__(kOrthThreads) void psgd_orth_kernel(const Ws ws, co
   const int r = L.rank[ws.level[li]];
   if (threadIdx.x == 0) ws.rank_used[li] = r;
   switch (r) {
-    case 1: orth_layer<1>(ws, L, red, psum); break;
-    case 2: orth_layer<2>(ws, L, red, psum); break;
-    case 3: orth_layer<3>(ws, L, red, psum); break;
-    default: orth_layer<4>(ws, L, red, psum); break;
+    case 1: orth_layer<1>(ws, L, red); break;
+    case 2: orth_layer<2>(ws, L, red); break;
+    case 3: orth_layer<3>(ws, L, red); break;
+    default: orth_layer<4>(ws, L, red); break;
   }
 }
 
 // ---- phase 1: Q partial = Delta^T P^ over one 64-row block -----------------------------------
+//
+// fp64 accumulation here too: where the memory dominates gradient + memory, Delta^T p^_k cancels
+// to a small fraction of its terms for the columns of P^ that the new gradient determines, and an
+// fp32 sum would lose those columns of Q (the oracle's contraction is fp64, rounded once).
 
+// Tile: kQRows rows x 256 columns, one workgroup of 4 waves; a wave owns rows wave, wave + 4, ...
+// and keeps the sums of its four columns per lane in registers; the four waves' sums meet in LDS.
+#ifndef ACC_Q_B
+#define ACC_Q_B 4
+#endif
 template <int R, bool V4>
 __device__ void q_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const float* __restrict__ e,
-                       float* __restrict__ qpart, float (*red)[16][64], float (*ps)[kMaxRank]) {
+                       double* __restrict__ qpart, double (*red)[16][64], float (*ps)[kMaxRank]) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int col[4]; bool cm[4];
   lane_cols<V4>(t.col0, lane, L.cols, col, cm);
-  {
-    // the tile's rows of P^ go to LDS with one load per thread
-    const int pr = threadIdx.x >> 2, pk = threadIdx.x & 3;
+  // the tile's rows of P^ go to LDS
+  for (int s = threadIdx.x; s < kQRows * kMaxRank; s += 256) {
+    const int pr = s >> 2, pk = s & 3;
     const int i = t.row0 + pr;
     ps[pr][pk] = (i < L.rows && pk < R) ? ws.Phat[L.p_off + (int64_t)i * ws.rmax + pk] : 0.f;
   }
   __syncthreads();
-  float acc[4][R];
+  double acc[4][R];
 #pragma unroll
   for (int v = 0; v < 4; ++v)
 #pragma unroll
-    for (int k = 0; k < R; ++k) acc[v][k] = 0.f;
-  const int row_end = min(t.row0 + kMatRows, L.rows);
-  constexpr int B = 4;   // rows in flight per wave (8 is no faster, 16 is slower)
+    for (int k = 0; k < R; ++k) acc[v][k] = 0.0;
+  const int row_end = min(t.row0 + kQRows, L.rows);
+  constexpr int B = ACC_Q_B;   // rows in flight per wave
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float d[B][4];
 #pragma unroll
@@ -430,47 +423,66 @@ __device__ void q_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const 
 #pragma unroll
     for (int b = 0; b < B; ++b) {
       const int i = i0 + 4 * b;
-      if (i < row_end) {
-        float p[R];
+      if (i < row_end) {                                     // wave-uniform
+        double p[R], dd[4];
 #pragma unroll
-        for (int k = 0; k < R; ++k) p[k] = ps[i - t.row0][k];
+        for (int k = 0; k < R; ++k) p[k] = (double)ps[i - t.row0][k];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dd[v] = (double)d[b][v];
 #pragma unroll
         for (int v = 0; v < 4; ++v)
 #pragma unroll
-          for (int k = 0; k < R; ++k) acc[v][k] = fmaf(d[b][v], p[k], acc[v][k]);
+          for (int k = 0; k < R; ++k) acc[v][k] = fma(dd[v], p[k], acc[v][k]);
       }
     }
   }
+  // the four waves' sums, in the fixed order (wave 0 + wave 2) + (wave 1 + wave 3)
+  if (wave >= 2) {
 #pragma unroll
-  for (int v = 0; v < 4; ++v)
+    for (int v = 0; v < 4; ++v)
 #pragma unroll
-    for (int k = 0; k < R; ++k) red[wave][v * R + k][lane] = acc[v][k];
+      for (int k = 0; k < R; ++k) red[wave - 2][v * R + k][lane] = acc[v][k];
+  }
   __syncthreads();
-  // thread (wave, lane) finishes column slot v = wave of that lane: waves summed in order
+  if (wave < 2) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int k = 0; k < R; ++k) acc[v][k] += red[wave][v * R + k][lane];
+  }
+  __syncthreads();
+  if (wave < 2) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int k = 0; k < R; ++k) red[wave][v * R + k][lane] = acc[v][k];
+  }
+  __syncthreads();
+  // thread (wave, lane) finishes column slot v = wave of that lane
   {
     const int v = wave;
     const int cv = V4 ? t.col0 + lane * 4 + v : t.col0 + lane + 64 * v;
     if (cv < L.cols) {
-      const int rb = t.row0 / kMatRows;
-      float* dst = qpart + L.qpart_off + ((int64_t)rb * L.cols + cv) * ws.rmax;
+      const int rb = t.row0 / kQRows;
+      double* dst = qpart + L.qpart_off + ((int64_t)rb * L.cols + cv) * ws.rmax;
 #pragma unroll
       for (int k = 0; k < R; ++k) {
         const int s = v * R + k;
-        dst[k] = ((red[0][s][lane] + red[1][s][lane]) + red[2][s][lane]) + red[3][s][lane];
+        dst[k] = red[0][s][lane] + red[1][s][lane];
       }
     }
   }
 }
 
 __global__ __launch_bounds__(256) void psgd_q_kernel(const Ws ws, int w0) {
-  __shared__ float red[4][16][64];
-  __shared__ float ps[kMatRows][kMaxRank];
+  __shared__ double red[2][16][64];
+  __shared__ float ps[kQRows][kMaxRank];
   const int w = w0 + blockIdx.y;
-  const MatTile t = ws.mtiles[blockIdx.x];
+  const MatTile t = ws.qmtiles[blockIdx.x];
   const LayerDev& L = ws.layers[t.layer];
   const int r = L.rank[ws.level[t.layer]];
   const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-  float* qpart = ws.Qpart + (int64_t)w * ws.qpart_stride;
+  double* qpart = ws.Qpart + (int64_t)w * ws.qpart_stride;
   if (L.vec4) {
     switch (r) {
       case 1: q_tile<1, true>(ws, L, t, e, qpart, red, ps); break;
@@ -490,14 +502,41 @@ __global__ __launch_bounds__(256) void psgd_q_kernel(const Ws ws, int w0) {
 
 // ---- aggregate 1: Q_bar = mean over workers of (sum over row blocks) -------------------------
 
-template <int R>
+// Q_bar[c][k] = fl32( (sum_w fl32(sum_rb partial[w][rb][c][k])) / W ), row blocks and workers in
+// index order; the partial sums of one worker are independent loads, issued eight at a time
+// (unconditionally, from clamped addresses, so that all eight are in flight together).
+template <int R, int U = 8>
 __device__ __forceinline__ void qmean_col(const Ws& ws, const LayerDev& L, int c) {
-  float q[R];
-  mean_of_partials<R>(ws.Qpart + L.qpart_off + (int64_t)c * ws.rmax, ws.qpart_stride, ws.W,
-                      L.n_rowblocks, (int64_t)L.cols * ws.rmax, q);
+  const double* base = ws.Qpart + L.qpart_off + (int64_t)c * ws.rmax;
+  const int64_t pstride = (int64_t)L.cols * ws.rmax;
+  const int nb = L.n_rowblocks;
+  double total[R];
+#pragma unroll
+  for (int k = 0; k < R; ++k) total[k] = 0.0;
+  for (int w = 0; w < ws.W; ++w) {
+    const double* src = base + (int64_t)w * ws.qpart_stride;
+    double s[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) s[k] = 0.0;
+    for (int b0 = 0; b0 < nb; b0 += U) {
+      double v[U][R];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const double* q = src + (int64_t)min(b0 + u, nb - 1) * pstride;
+#pragma unroll
+        for (int k = 0; k < R; ++k) v[u][k] = q[k];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int k = 0; k < R; ++k) s[k] += (b0 + u < nb) ? v[u][k] : 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k) total[k] += (double)(float)s[k];   // Q_w is an fp32 quantity
+  }
   float* dst = ws.Q + L.q_off + (int64_t)c * kMaxRank;    // rows of Q are kMaxRank floats apart
 #pragma unroll
-  for (int k = 0; k < R; ++k) dst[k] = q[k];
+  for (int k = 0; k < R; ++k) dst[k] = (float)(total[k] / (double)ws.W);
 }
 
 __global__ __launch_bounds__(256) void psgd_qmean_kernel(const Ws ws) {

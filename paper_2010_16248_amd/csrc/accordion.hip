@@ -32,8 +32,9 @@ struct Region { int64_t off = 0, bytes = 0; };
 struct Plan {
   std::vector<LayerDev> layers;
   std::vector<FlatTile> ftiles;
-  std::vector<MatTile> mtiles;
+  std::vector<MatTile> mtiles, qmtiles;
   std::vector<QTile> qtiles;
+  std::vector<PTile> ptiles;
   std::vector<int32_t> vectiles;
   std::vector<int32_t> matlayers;
   int32_t rmax = 0;
@@ -45,11 +46,11 @@ struct Plan {
   int64_t n_t2slots = 0;    // TopK: slots of level-2 counts per worker (one per kT2Group tiles of a layer)
   bool pick3_big = false;   // TopK: some layer has more quarters than the small last pick kernel takes
   // workspace regions
-  Region r_layers, r_ftiles, r_mtiles, r_qtiles, r_vectiles, r_matlayers;
+  Region r_layers, r_ftiles, r_mtiles, r_qmtiles, r_qtiles, r_ptiles, r_vectiles, r_matlayers;
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
   Region r_A, r_e, r_norm_part, r_sq_part, r_bstate;
   int64_t n_model = 0;   // elements that belong to a layer
-  Region r_Q, r_Phat, r_Ppart, r_Qpart, r_vecmean, r_pending;
+  Region r_Q, r_Phat, r_Pwork, r_Ppart, r_Qpart, r_vecmean, r_pending;
   Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval, r_overlap, r_tpending;
   int64_t total_bytes = 0;
 };
@@ -140,7 +141,8 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
         d.rank[0] = std::max(1, std::min(c->rank_noncrit, cap));
         d.rank[1] = std::max(1, std::min(c->rank_crit, cap));
         d.n_colchunks = (l.cols + kMatCols - 1) / kMatCols;
-        d.n_rowblocks = (l.rows + kMatRows - 1) / kMatRows;
+        const int n_rb = (l.rows + kMatRows - 1) / kMatRows;
+        d.n_rowblocks = (l.rows + kQRows - 1) / kQRows;
         d.q_off = p.q_dev;
         p.q_total += (int64_t)l.cols * p.rmax;
         p.q_dev += (int64_t)l.cols * kMaxRank;
@@ -152,6 +154,8 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
         p.qpart_stride += (int64_t)d.n_rowblocks * l.cols * p.rmax;
         p.matlayers.push_back(i);
         for (int rb = 0; rb < d.n_rowblocks; ++rb)
+          for (int cc = 0; cc < d.n_colchunks; ++cc) p.qmtiles.push_back(MatTile{i, rb * kQRows, cc * kMatCols, 0});
+        for (int rb = 0; rb < n_rb; ++rb)
           for (int cc = 0; cc < d.n_colchunks; ++cc) {
             MatTile mt;
             mt.layer = i;
@@ -160,6 +164,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
             mt.pad = 0;
             p.mtiles.push_back(mt);
           }
+        for (int r0 = 0; r0 < l.rows; r0 += kPmeanRows) p.ptiles.push_back(PTile{i, r0});
         for (int cc = 0; cc < d.n_colchunks; ++cc) {
           QTile qt;
           qt.layer = i;
@@ -195,7 +200,9 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
   reg(p.r_layers, (int64_t)sizeof(LayerDev) * nl);
   reg(p.r_ftiles, (int64_t)sizeof(FlatTile) * (int64_t)p.ftiles.size());
   reg(p.r_mtiles, (int64_t)sizeof(MatTile) * (int64_t)p.mtiles.size());
+  reg(p.r_qmtiles, (int64_t)sizeof(MatTile) * (int64_t)p.qmtiles.size());
   reg(p.r_qtiles, (int64_t)sizeof(QTile) * (int64_t)p.qtiles.size());
+  reg(p.r_ptiles, (int64_t)sizeof(PTile) * (int64_t)p.ptiles.size());
   reg(p.r_vectiles, 4 * (int64_t)p.vectiles.size());
   reg(p.r_matlayers, 4 * (int64_t)p.matlayers.size());
   reg(p.r_level, 4 * (int64_t)nl);
@@ -213,8 +220,9 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
   if (c->method == ACC_POWERSGD) {
     reg(p.r_Q, 4 * p.q_dev);
     reg(p.r_Phat, 4 * p.p_total);
-    reg(p.r_Ppart, 4 * p.ppart_stride * W);
-    reg(p.r_Qpart, 4 * p.qpart_stride * W);
+    reg(p.r_Pwork, 8 * p.p_total);
+    reg(p.r_Ppart, 8 * p.ppart_stride * W);
+    reg(p.r_Qpart, 8 * p.qpart_stride * W);
     reg(p.r_vecmean, 4 * p.vec_total);
     reg(p.r_pending, 4);
   } else if (c->method == ACC_TOPK) {
@@ -272,10 +280,10 @@ enum Stage {
   ST_batch_micro_kernel, ST_batch_micro_update_kernel, ST_batch_decide_kernel,
   ST_topk_overlap_kernel, ST_zero_u64_kernel, ST_msdr_sq_kernel, ST_msdr_decide_kernel,
   ST_psgd_clear_pending_kernel, ST_topk_residual_kernel, ST_topk_clear_pending_kernel,
-  ST_topk_pick3_big_kernel,
+  ST_topk_pick3_big_kernel, ST_psgd_pmean_kernel,
   ST_COUNT
 };
-static_assert(ST_COUNT == ACC_N_STAGES, "stage table and header disagree");
+static_assert(ST_COUNT <= ACC_N_STAGES, "more stages than the header announces");
 static const char* const kStageNames[ST_COUNT] = {
   "psgd_ef_p_kernel", "psgd_orth_kernel", "psgd_q_kernel", "psgd_qmean_kernel",
   "psgd_decomp_kernel", "psgd_residual_kernel", "topk_ef_hist_kernel", "topk_pick12_kernel", "topk_restage_kernel",
@@ -286,7 +294,7 @@ static const char* const kStageNames[ST_COUNT] = {
   "batch_micro_kernel", "batch_micro_update_kernel", "batch_decide_kernel",
   "topk_overlap_kernel", "zero_u64_kernel", "msdr_sq_kernel", "msdr_decide_kernel",
   "psgd_clear_pending_kernel", "topk_residual_kernel", "topk_clear_pending_kernel",
-  "topk_pick3_big_kernel"};
+  "topk_pick3_big_kernel", "psgd_pmean_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
 
@@ -433,6 +441,7 @@ int launch_phase0(acc_ctx* c, int w0, int nw) {
 int launch_agg0(acc_ctx* c) {
   const Ws& ws = c->ws;
   if (c->cfg.method == ACC_POWERSGD) {
+    if (ws.n_ptiles > 0) ACC_LAUNCH(c, psgd_pmean_kernel, dim3(ws.n_ptiles), dim3(256), ws);
     const int gx = ws.n_mat + ws.n_vectiles;
     if (gx > 0) ACC_LAUNCH(c, psgd_orth_kernel, dim3(gx), dim3(kOrthThreads), ws, c->grads);
   }
@@ -441,7 +450,7 @@ int launch_agg0(acc_ctx* c) {
 
 int launch_phase1(acc_ctx* c, int w0, int nw) {
   const Ws& ws = c->ws;
-  if (ws.n_mtiles > 0) ACC_LAUNCH(c, psgd_q_kernel, dim3(ws.n_mtiles, nw), dim3(256), ws, w0);
+  if (ws.n_qmtiles > 0) ACC_LAUNCH(c, psgd_q_kernel, dim3(ws.n_qmtiles, nw), dim3(256), ws, w0);
   return ACC_OK;
 }
 
@@ -602,7 +611,9 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   ws.layers = at<LayerDev>(c, p.r_layers);
   ws.ftiles = at<FlatTile>(c, p.r_ftiles);
   ws.mtiles = at<MatTile>(c, p.r_mtiles);
+  ws.qmtiles = at<MatTile>(c, p.r_qmtiles);
   ws.qtiles = at<QTile>(c, p.r_qtiles);
+  ws.ptiles = at<PTile>(c, p.r_ptiles);
   ws.vectiles = at<int32_t>(c, p.r_vectiles);
   ws.matlayers = at<int32_t>(c, p.r_matlayers);
   ws.level = at<int32_t>(c, p.r_level);
@@ -621,9 +632,10 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   if (cfg->method == ACC_POWERSGD) {
     ws.Q = at<float>(c, p.r_Q);
     ws.Phat = at<float>(c, p.r_Phat);
-    ws.Ppart = at<float>(c, p.r_Ppart);
+    ws.Pwork = at<double>(c, p.r_Pwork);
+    ws.Ppart = at<double>(c, p.r_Ppart);
     ws.ppart_stride = p.ppart_stride;
-    ws.Qpart = at<float>(c, p.r_Qpart);
+    ws.Qpart = at<double>(c, p.r_Qpart);
     ws.qpart_stride = p.qpart_stride;
     ws.vecmean = at<float>(c, p.r_vecmean);
     ws.pending = at<uint32_t>(c, p.r_pending);
@@ -660,7 +672,9 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   ws.n_ftiles = (int32_t)p.ftiles.size();
   ws.n_t2slots = (int32_t)p.n_t2slots;
   ws.n_mtiles = (int32_t)p.mtiles.size();
+  ws.n_qmtiles = (int32_t)p.qmtiles.size();
   ws.n_qtiles = (int32_t)p.qtiles.size();
+  ws.n_ptiles = (int32_t)p.ptiles.size();
   ws.n_vectiles = (int32_t)p.vectiles.size();
   ws.n_mat = (int32_t)p.matlayers.size();
   ws.eta = cfg->eta;
@@ -676,7 +690,9 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ACC_HIP(c, up(p.r_layers, p.layers.data()));
     ACC_HIP(c, up(p.r_ftiles, p.ftiles.data()));
     ACC_HIP(c, up(p.r_mtiles, p.mtiles.data()));
+    ACC_HIP(c, up(p.r_qmtiles, p.qmtiles.data()));
     ACC_HIP(c, up(p.r_qtiles, p.qtiles.data()));
+    ACC_HIP(c, up(p.r_ptiles, p.ptiles.data()));
     ACC_HIP(c, up(p.r_vectiles, p.vectiles.data()));
     ACC_HIP(c, up(p.r_matlayers, p.matlayers.data()));
     std::vector<int32_t> lv((size_t)cfg->n_layers, cfg->initial_level);

@@ -17,7 +17,9 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-5
 
 
-def _forced_step(gpu, ora, grads, tag, tol=TOL):
+def _forced_step(gpu, ora, grads, tag, tol=TOL, expect_strict_residual=False):
+    """One teacher-forced step of both sides, compared per layer.  expect_strict_residual: assert
+    that every residual was measured against its own norm (see below)."""
     gpu.set_state(H.oracle_state_blob(gpu, ora))
     ranks = {li: ora.layer_rank(li) for li, l in enumerate(ora.layers) if l[3]}
     out_ref = ora.step(grads)
@@ -36,14 +38,25 @@ def _forced_step(gpu, ora, grads, tag, tol=TOL):
             assert p_hat.shape == (rows, ranks[li]), tag
             errs = dict(P=H.rel_fro(p_hat, ora.P_hat[li]), Q=H.rel_fro(q_bar, ora.Q_bar[li]),
                         D=H.rel_fro(got[sl], out_ref[sl]))
-            # the residual is the difference Delta - D, so its error is D's: it is measured against
-            # the larger of |e| and |D| (a layer whose rank reaches its row count has D = Delta
-            # and a residual of rounding noise only)
-            d_norm = np.linalg.norm(out_ref[sl].astype(np.float64))
+            # beside the Frobenius ratio, no single entry of D may be off by more than the
+            # tolerance times the layer's largest entry
+            d_ref64 = out_ref[sl].astype(np.float64)
+            d_max = np.abs(d_ref64).max()
+            errs["Dmax"] = np.abs(got[sl].astype(np.float64) - d_ref64).max() / d_max if d_max > 0 else 0.0
+            # The residual e_w = Delta_w - D is compared against its own norm wherever it is at
+            # least as large as D (every layer of the benchmark workloads: a low-rank D takes a
+            # small part of an i.i.d. gradient).  Only where D is the larger of the two (a rank
+            # that reaches the layer's row count gives D = Delta and a residual of rounding
+            # noise) is D's norm the yardstick: the residual inherits D's absolute error.
+            d_norm = np.linalg.norm(d_ref64)
             for w in range(gpu.n_workers):
                 e_ref = ora.e[w, sl].astype(np.float64)
+                e_norm = np.linalg.norm(e_ref)
                 num = np.linalg.norm(st["e"][w, sl].astype(np.float64) - e_ref)
-                den = max(np.linalg.norm(e_ref), d_norm)
+                strict = e_norm >= d_norm
+                if expect_strict_residual:
+                    assert strict, f"{tag}: layer {li}: |e| {e_norm:.3e} < |D| {d_norm:.3e}"
+                den = e_norm if strict else d_norm
                 errs[f"e{w}"] = num / den if den > 0 else num
             # the whole Q block (unused columns included) is the next warm start
             qblk = st["Q"][qpos:qpos + cols * rmax].reshape(cols, rmax)
@@ -58,6 +71,73 @@ def _forced_step(gpu, ora, grads, tag, tol=TOL):
     H.assert_bits_equal(st["A"], ora.A, f"{tag}: accumulator")
     assert gpu.payload_words() == (ora.words_last, ora.words_cum)
     return worst
+
+
+def _p_bar_condition(ora, grads, li):
+    """Condition number of the P_bar the next oracle step will orthogonalise (layer li)."""
+    off, rows, cols, _ = ora.layers[li]
+    sl = slice(off, off + rows * cols)
+    r = ora.layer_rank(li)
+    q = ora.Q[li][:, :r]
+    deltas = [orc.ef_add(g[sl], ora.e[w, sl]).reshape(rows, cols) for w, g in enumerate(grads)]
+    p_w = [(d.astype(np.float64) @ q.astype(np.float64)).astype(np.float32) for d in deltas]
+    p_bar = (sum(p.astype(np.float64) for p in p_w) / len(p_w)).astype(np.float32)
+    return float(np.linalg.cond(p_bar.astype(np.float64)))
+
+
+def test_ill_conditioned_warm_start_of_a_two_column_layer():
+    """A random configuration on which fp32 accumulation fails the tolerance: the 614 x 2 layer's
+    random 2 x 2 warm start has condition number 2000, so P_bar = Delta_bar Q has it too, and
+    Gram-Schmidt multiplies any rounding difference in P_bar by it (4e-5 in P^ with fp32
+    products; the fp64 chain of the kernels is insensitive to it)."""
+    print("case ill-conditioned 614x2", flush=True)
+    rng = np.random.default_rng(5000 + 12042)
+    shapes = []
+    for _ in range(int(rng.integers(1, 7))):
+        if rng.random() < 0.3:
+            shapes.append((1, int(rng.integers(1, 20000)), 0))
+        else:
+            shapes.append((int(rng.integers(1, 700)), int(rng.integers(1, 1500)), 1))
+    assert shapes == [(614, 2, 1), (583, 570, 1), (408, 1141, 1)]
+    layers = wl.make_layers(shapes)
+    lt = H.layer_tuples(layers)
+    N = wl.total_params(layers)
+    W = int(rng.integers(1, 6))
+    crit, noncrit = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    assert (W, crit, noncrit) == (4, 2, 1)
+    q0 = rng.standard_normal(sum(c for (_, r, c, m) in lt if m) * max(crit, noncrit)).astype(np.float32)
+    gpu, ora = H.make_pair(B.ACC_POWERSGD, layers, W, crit, noncrit, 100, 0.5, 1, q0)
+    for s in range(3):
+        if s == 2:
+            ora.level[:] = 0
+        scale = 10.0 ** rng.uniform(-1, 0)
+        grads = [(rng.standard_normal(N) * scale).astype(np.float32) for _ in range(W)]
+        if s == 0:
+            assert _p_bar_condition(ora, grads, 0) > 1000
+        _forced_step(gpu, ora, grads, f"step {s}")
+    gpu.destroy()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_gradient_scale_drop_makes_p_bar_ill_conditioned(seed):
+    """Layers of 6 and 5 rows at rank 4 whose gradient shrinks a thousandfold after the first
+    step: gradient + memory is then dominated by the memory, which is orthogonal to the previous
+    P^, so that P_bar = Delta Q is almost rank-deficient (condition number 10^3 .. 10^5).  The
+    tolerance is the same 1e-5."""
+    print(f"case scale drop seed {seed}", flush=True)
+    layers = wl.make_layers([(6, 700, 1), (5, 33, 1)])
+    lt = H.layer_tuples(layers)
+    N = wl.total_params(layers)
+    W = 2
+    rng = np.random.default_rng(300 + seed)
+    q0 = rng.standard_normal(sum(c for (_, r, c, m) in lt if m) * 4).astype(np.float32)
+    gpu, ora = H.make_pair(B.ACC_POWERSGD, layers, W, 4, 4, 100, 0.5, 1, q0)
+    for s, scale in enumerate([1.0, 1e-3, 1e-3]):
+        grads = [(rng.standard_normal(N) * scale).astype(np.float32) for _ in range(W)]
+        if s > 0:
+            assert min(_p_bar_condition(ora, grads, li) for li in (0, 1)) > 500
+        _forced_step(gpu, ora, grads, f"seed {seed} step {s}")
+    gpu.destroy()
 
 
 def test_tiny_config_both_ranks_with_switch():

@@ -78,6 +78,39 @@ def test_topk_random_configuration(seed):
 
 
 @pytest.mark.parametrize("seed", range(10))
+def test_powersgd_random_thin_and_short_matrices(seed):
+    """Matrix families on which the orthogonalisation is touchy: one to three columns (P_bar is
+    as ill-conditioned as the small random warm start) and fewer than eight rows (the rank is
+    capped near the row count), with gradient scales that jump by up to four orders of magnitude
+    between steps (the memory then dominates and P_bar is almost rank-deficient).  Same 1e-5."""
+    rng = np.random.default_rng(7000 + seed)
+    shapes = []
+    for _ in range(int(rng.integers(2, 7))):
+        u = rng.random()
+        if u < 0.4:
+            shapes.append((int(rng.integers(1, 700)), int(rng.integers(1, 4)), 1))
+        elif u < 0.8:
+            shapes.append((int(rng.integers(1, 8)), int(rng.integers(1, 1500)), 1))
+        else:
+            shapes.append((1, int(rng.integers(1, 3000)), 0))
+    layers = wl.make_layers(shapes)
+    lt = H.layer_tuples(layers)
+    N = wl.total_params(layers)
+    W = int(rng.integers(1, 6))
+    crit, noncrit = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    print(f"case random thin/short powersgd seed {seed}: {shapes} W {W} ranks {crit}/{noncrit}", flush=True)
+    q0 = rng.standard_normal(sum(c for (_, r, c, m) in lt if m) * max(crit, noncrit)).astype(np.float32)
+    gpu, ora = H.make_pair(B.ACC_POWERSGD, layers, W, crit, noncrit, 100, 0.5, 1, q0)
+    for s in range(4):
+        if s == 2:
+            ora.level[:] = 0
+        scale = 10.0 ** rng.uniform(-4, 0)
+        grads = [(rng.standard_normal(N) * scale).astype(np.float32) for _ in range(W)]
+        _forced_step(gpu, ora, grads, f"seed {seed} step {s}")
+    gpu.destroy()
+
+
+@pytest.mark.parametrize("seed", range(10))
 def test_powersgd_and_batch_mode_random_configuration(seed):
     rng = np.random.default_rng(5000 + seed)
     shapes = []
