@@ -62,7 +62,7 @@ enum {
 enum { ACC_POWERSGD = 0, ACC_TOPK = 1, ACC_BATCH = 2 };
 
 /* Which statistic accordion_detect_regime decides on.  ACC_DETECT_NORM: the paper's own test
- * (Sec. 4.2, Algorithm 1).  ACC_DETECT_MSDR: the comparison method of Sec. 5.5 -- per layer, the
+ * (Sec. 4.2, Algorithm 1).  ACC_DETECT_MSDR: the comparison method of Sec. 5.6 -- per layer, the
  * mean to standard deviation ratio of worker 0's gradients over the window,
  *     m = || mean_t g_t || / sqrt( mean_t || g_t - mean ||^2 )
  * (from the accumulator, the sum of the squared gradient norms and the step count; fp64, result
@@ -246,7 +246,7 @@ int32_t accordion_get_norms(acc_ctx* ctx, float* old_host, float* curr_host);
 int32_t accordion_get_payload(acc_ctx* ctx, int32_t worker, int32_t layer, int32_t* idx_host,
                               float* val_host, int64_t capacity, int64_t* count_out);
 /* How a TopK layer's payload is laid out at a level (host-only arithmetic, no GPU needed).  The
- * paper's own runs keep K = 99 % inside critical regimes (Sec. 5.3, TopK tables), where a list of
+ * paper's own runs keep K = 99 % inside critical regimes (Sec. 5.4, TopK tables), where a list of
  * (index, value) pairs costs 1.98 n floats -- more than the dense tensor.  A layer that keeps more
  * than half of its n entries therefore sends its k values in index order plus the n - k indices
  * of the dropped entries: n floats, never more than dense.  format: ACC_PAYLOAD_INDEX_VALUE

@@ -29,7 +29,7 @@ What is computed, and where the paper defines it
   only allowed to grow).
 * Overlap of the Top-K supports of two stochastic gradients: Section 4.3
   ("Relationship between gradient compression and adaptive batch-size").
-* The comparison detector (Section 5.5 "Comparison with Prior Work"): the mean to
+* The comparison detector (Section 5.6 "Comparison with Prior Work"): the mean to
   standard deviation ratio (MSDR) of the gradients; when it has dropped by a given
   fraction the compression is reduced.
 * The optimizer that consumes the averaged decompressed gradient: SGD with
@@ -151,7 +151,7 @@ def topk_residual(delta: np.ndarray, kept: np.ndarray) -> np.ndarray:
 
 def payload_layout(n: int, kept: np.ndarray, values: np.ndarray):
     """What one worker sends for a layer of n entries of which `kept` (ascending indices) are
-    kept.  The paper's own levels keep K = 99 % inside critical regimes (Section 5.3, TopK
+    kept.  The paper's own levels keep K = 99 % inside critical regimes (Section 5.4, TopK
     tables); a list of (index, value) pairs then costs 1.98 n floats, more than the dense
     tensor.  So: at most half kept -> ("index_value", indices, values), 2k words; more than
     half kept -> ("values_holes", indices of the dropped entries ascending, values in index
@@ -204,7 +204,7 @@ def layer_norm(a: np.ndarray) -> np.float32:
 
 
 def msdr(grads: Sequence[np.ndarray]) -> np.float32:
-    """Mean to standard deviation ratio of T gradients of one layer (Section 5.5), written
+    """Mean to standard deviation ratio of T gradients of one layer (Section 5.6), written
     out as the definition: || mean_t g_t ||_2 over sqrt( mean_t || g_t - mean ||_2^2 ), in
     fp64 on the fp32 inputs; +inf when the gradients do not vary at all."""
     g = np.stack([np.asarray(x, dtype=F64).reshape(-1) for x in grads])
@@ -225,7 +225,7 @@ def msdr_streaming(sum_vec: np.ndarray, sum_sq: float, t: int) -> np.float32:
 
 
 def msdr_should_switch(ref, m, has_ref: bool, delta) -> bool:
-    """Reading of Section 5.5's description of the comparison method: once the ratio has
+    """Reading of Section 5.6's description of the comparison method: once the ratio has
     dropped by the fraction delta relative to its value at the last switch (or at the first
     window), the layer moves to the more accurate level, and it never moves back.  fp32."""
     if not has_ref:

@@ -18,7 +18,6 @@ constexpr int kMatCols = 256;
 #endif
 constexpr int kQRows = ACC_Q_ROWS;       // rows of a tile of the right product Q = Delta^T P^ (a multiple of 4)
 constexpr int kHistBins = 2048;          // 11 key bits per radix level
-constexpr int kSubCap = 256;             // staged keys per guessed bin and wave quarter of a flat tile (TopK)
 // a wave quarter has at most ceil((kTile / 4 + 1) / 4) 16-byte groups: iterations of 64 lanes
 constexpr int kSpanIters = ((kTile / 4 + 1 + 3) / 4 + kWave - 1) / kWave;   // 9
 constexpr int kMaxW = 32;
@@ -111,12 +110,14 @@ struct Ws {
   uint32_t* qlist;             // W x q_stride x kQListCap: per quarter, its keys in bin (b1, b2)
   SelState* sel;               // W x L
   uint32_t* hist2m;            // W x L x 64: level-2 counts of b1 of a layer whose guess missed
-  uint32_t* miss_any;          // W: some multi-tile layer of the worker missed its guessed bins this step
+  uint32_t* lflag;             // L: nonzero = this step's compaction of the layer reads Delta (a guess missed, a
+                               //   candidate list overflowed), not the candidate lists
   uint2* b1hist;               // W x L x 2 (level): {b1 | (last move + 64) << 16, step number} of the last step at this level
   uint32_t* guess;             // W x L x 2 (level): lowest of the adjacent level-1 bins staged by pass A
-  uint4* qinfo;                // W x q_stride: per wave quarter {entries above the staged bins, staged
-                               //   keys, of which in the second | third bin << 16, exact zeros}
-  uint32_t* seg;               // W x q_stride x 2 x kSubCap staged keys
+  uint4* qinfo;                // W x q_stride: per wave quarter {entries above the staged bin (one-bin lists),
+                               //   listed entries, 0, exact zeros (one-bin lists)}
+  uint32_t* cand_val;          // W x q_stride x kCandCap: per wave quarter, the values of its candidates (or keys of one bin)
+  uint16_t* cand_idx;          // W x q_stride x kCandCap: ... and their offsets inside the quarter
   uint32_t* gtq;               // W x q_stride entries above the threshold per quarter
   uint32_t* eqq;               // W x q_stride keys in bin (b1, b2) / entries equal to the threshold per quarter
   uint32_t* gtpre;             // W x q_stride exclusive prefix of gtq within the layer (+ total)

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(64) void regime_decide_kernel(const Ws ws, float lr
   }
 }
 
-// ---- comparison detector: mean to standard deviation ratio (Section 5.5) -----------------------
+// ---- comparison detector: mean to standard deviation ratio (Section 5.6) -----------------------
 
 // Per flat tile: sq_part[tile] += sum of squares of worker 0's gradient (fp64; one workgroup owns
 // a tile, the order inside is fixed: the running sums are reproducible).  Block 0 counts the step.

@@ -44,8 +44,20 @@ constexpr int kPickWaves = kPickThreads / kWave;
 static_assert(kHistBins == 2 * kPickThreads, "the pick kernels load two histogram bins per thread");
 constexpr int kQListCap = 16;            // keys of bin (b1, b2) listed per wave quarter
 constexpr int kL2Bins = 64;              // level 2: key bits 19..14
-constexpr int kGuessBins = 3;                // adjacent level-1 bins staged by the first pass (2 or 3)
-constexpr int kSub2 = kGuessBins * kL2Bins;  // a tile's level-2 counts of the guessed bins
+// A guess names nb adjacent level-1 bins, lo .. lo + nb - 1 (lo >= 1): the first pass lists every
+// entry of bin lo and above as a candidate and counts the level-2 bins of the nb guessed ones.
+// kGuessNarrow bins while the threshold rests (it has not moved for two steps), kGuessWide bins
+// while it moves: after a level switch the error memory adapts for ten steps or so, during which
+// the threshold moves by one to three bins per step (an eighth of an octave each), not quite
+// steadily.  A wide guess costs more candidates (18 % of the entries instead of 13 % at K = 10 %),
+// a missed one a second read of Delta and a slow decision for that layer.
+constexpr int kGuessNarrow = 3, kGuessWide = 7;
+constexpr int kSub2 = kGuessWide * kL2Bins;  // a tile's level-2 counts of the guessed bins
+__device__ __forceinline__ uint32_t make_guess(int lo, int nb) {
+  return (uint32_t)max(1, min(kHistBins - nb, lo)) | ((uint32_t)nb << 16);
+}
+__device__ __forceinline__ uint32_t guess_lo(uint32_t g) { return g & 0xffffu; }
+__device__ __forceinline__ uint32_t guess_nb(uint32_t g) { return g >> 16; }
 __device__ __forceinline__ uint32_t bin2_of(uint32_t key) { return (key >> 14) & 0x3fu; }
 __device__ __forceinline__ uint32_t bin3_of(uint32_t key) { return (key >> 6) & 0xffu; }
 __device__ __forceinline__ uint32_t bin4_of(uint32_t key) { return key & 0x3fu; }
@@ -144,37 +156,90 @@ __device__ __forceinline__ int64_t quarter_slot(const Ws& ws, const LayerDev& L,
   return (int64_t)w * ws.q_stride + L.qoff + 4 * (int64_t)tl + wave;
 }
 
-// Staging of one component's keys in the wave's LDS list (the keys of all guessed bins share
-// one list: a key carries its bin).  The count keeps running past the capacity (the counting
-// kernel sees the overflow).  n_in: wave-uniform; v_hi, v_nz: per lane, summed over the wave when
-// the quarter is flushed.
-struct StageCounts { uint32_t n_in, v_hi, v_nz; };
+// ---- candidate lists ---------------------------------------------------------------------------
+// Pass A leaves, per wave quarter, the list of its CANDIDATES: every entry whose level-1 bin is at
+// or above the lowest guessed bin, as (offset inside the quarter, value), in index order.  When the
+// guess holds, the kept entries are among them, and the passes after it -- the counting kernel, the
+// compaction and the mean -- read these 6 bytes per candidate (12 to 17 % of the entries at
+// K = 10 %, 2 % at K = 1 %) instead of Delta once more.  A wave collects its candidates in LDS
+// and writes them out, consecutive lanes to consecutive addresses, whenever another iteration
+// (up to 256 entries) might not fit.  A quarter with more than kCandCap candidates keeps the
+// first kCandCap and its full count: whoever reads the list sees the overflow and goes back to
+// Delta (and the layer is compacted from Delta).
+// The passes that stage ONE bin (bin 0 on a guess, or the bin of a missed guess) use the same
+// lists for that bin's keys (no offsets; zeros counted apart).
+constexpr int kCandCap = 1024;                   // candidates of a wave quarter kept in device memory
+constexpr int kCandLds = 512;                    // a wave's list in LDS
+constexpr int kCandLdsSlots = kCandLds + kWave;  // + one slot per lane that takes the writes of unselected elements
 
-constexpr int kSegCap = 2 * kSubCap;     // staged keys per wave quarter
+struct CandList { uint32_t* val; uint16_t* idx; };
 
-// Pass A: keys of the bins glo .. glo + kGuessBins - 1 (glo >= 1, so a staged key is never an exact zero;
-// zeros are not counted here: a threshold in bin 0 counts as a missed guess and the re-staging
-// pass counts them).  mv: lane mask of the valid elements; valid: the calling lane's bit of it.
-// Every ballot is taken from a single compare and combined with the other masks in scalar
-// registers.
-__device__ __forceinline__ void stage_guessed_bins(uint32_t* st, uint32_t* sub2, StageCounts& c, uint64_t mv,
-                                               bool valid, uint32_t key, uint32_t glo, int lane) {
-  const uint32_t bin = key >> 20;
-  const uint32_t rel = bin - glo;                          // 0 .. kGuessBins - 1 for the staged bins
-  c.v_hi += (valid && (int32_t)rel > kGuessBins - 1) ? 1u : 0u;
-  const uint64_t m = ballot64(rel <= (uint32_t)(kGuessBins - 1)) & mv;
-  if (m != 0) {
-    if (valid && rel <= (uint32_t)(kGuessBins - 1)) {
-      const uint32_t pos = c.n_in + lanes_below(m, lane);
-      if (pos < (uint32_t)kSegCap) st[pos] = key;
-      atomicAdd(&sub2[rel * kL2Bins + bin2_of(key)], 1u);
-    }
-    c.n_in += (uint32_t)__popcll(m);
+// n_lds: entries in the LDS list; n_out: entries already written out (both wave-uniform);
+// v_hi, v_nz: per lane, summed over the wave when the quarter is finished.
+struct StageCounts { uint32_t n_lds, n_out, v_hi, v_nz; };
+
+__device__ __forceinline__ void cand_write_out(const Ws& ws, int64_t qslot, const CandList& cl, StageCounts& c,
+                                               int lane) {
+  uint32_t* gv = ws.cand_val + qslot * kCandCap;
+  uint16_t* gi = ws.cand_idx + qslot * kCandCap;
+  __builtin_amdgcn_wave_barrier();                          // the list is complete (LDS is in order per wave)
+  for (uint32_t t = lane; t < c.n_lds; t += kWave) {
+    const uint32_t pos = c.n_out + t;
+    if (pos < (uint32_t)kCandCap) { gv[pos] = cl.val[t]; gi[pos] = cl.idx[t]; }
   }
+  __builtin_amdgcn_wave_barrier();
+  c.n_out += c.n_lds;
+  c.n_lds = 0u;
 }
 
-// The re-staging pass: the keys of bin b1 alone, exact zeros left out and counted.
-__device__ __forceinline__ void stage_one_bin(uint32_t* st, uint32_t* sub2, StageCounts& c, uint64_t mv,
+// Room for one more group of four elements per lane?  Called after every group (wave-uniform).
+__device__ __forceinline__ void cand_make_room(const Ws& ws, int64_t qslot, const CandList& cl, StageCounts& c,
+                                               int lane) {
+  if (c.n_lds > (uint32_t)(kCandLds - 4 * kWave)) cand_write_out(ws, qslot, cl, c, lane);
+}
+
+// Pass A, one group: the candidates among the four elements of every lane (bins glo and up;
+// glo >= 1, so a candidate is never an exact zero; zeros are not counted here: a threshold in bin 0
+// counts as a missed guess and the re-staging counts them).  mv: lane masks of the valid elements
+// per component.  i_rel: offset of the lane's first element inside the quarter.  The level-2 counts of
+// the kGuessBins guessed bins go to sub2.  Every ballot is taken from a single compare and
+// combined with the other masks in scalar registers; the list is in index order.
+template <bool MASKED>
+__device__ __forceinline__ void stage_candidates(const CandList& cl, uint32_t* sub2, StageCounts& c,
+                                                 uint64_t mv0, uint64_t mv1, uint64_t mv2, uint64_t mv3,
+                                                 const float4& d, uint32_t glo, uint32_t gnb, uint32_t i_rel,
+                                                 int lane) {
+  uint32_t key[4], rel[4];
+  uint64_t m[4];
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    key[x] = key_of(comp(d, x));
+    rel[x] = (key[x] >> 20) - glo;
+    m[x] = ballot64((int32_t)rel[x] >= 0);
+    if (MASKED) m[x] &= (x == 0 ? mv0 : x == 1 ? mv1 : x == 2 ? mv2 : mv3);
+  }
+  if ((m[0] | m[1] | m[2] | m[3]) == 0) return;              // wave-uniform
+  uint32_t place = c.n_lds, total = 0u;
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    place = __builtin_amdgcn_mbcnt_hi((uint32_t)(m[x] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m[x], place));
+    total += (uint32_t)__popcll(m[x]);
+  }
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    const bool sel = lane_bit(m[x]);
+    const uint32_t slot = sel ? place : (uint32_t)(kCandLds + lane);
+    cl.val[slot] = __float_as_uint(comp(d, x));
+    cl.idx[slot] = (uint16_t)(i_rel + x);
+    if (sel && rel[x] < gnb) atomicAdd(&sub2[rel[x] * kL2Bins + bin2_of(key[x])], 1u);
+    place += sel ? 1u : 0u;
+  }
+  c.n_lds += total;
+}
+
+// The passes that stage one bin: the keys of bin b1 alone, exact zeros left out and counted, the
+// entries of the bins above counted.  The caller makes room after every group.
+__device__ __forceinline__ void stage_one_bin(const CandList& cl, uint32_t* sub2, StageCounts& c, uint64_t mv,
                                               bool valid, uint32_t key, uint32_t b1, int lane) {
   const uint32_t bin = key >> 20;
   c.v_nz += (valid && key == 0u) ? 1u : 0u;
@@ -182,35 +247,21 @@ __device__ __forceinline__ void stage_one_bin(uint32_t* st, uint32_t* sub2, Stag
   const uint64_t m = ballot64(bin == b1) & ballot64(key != 0u) & mv;
   if (m != 0) {
     if (valid && bin == b1 && key != 0u) {
-      const uint32_t pos = c.n_in + lanes_below(m, lane);
-      if (pos < (uint32_t)kSegCap) st[pos] = key;
+      cl.val[c.n_lds + lanes_below(m, lane)] = key;
       atomicAdd(&sub2[bin2_of(key)], 1u);
     }
-    c.n_in += (uint32_t)__popcll(m);
+    c.n_lds += (uint32_t)__popcll(m);
   }
 }
 
-// qinfo of the quarter: {entries above the staged bins, staged keys, of which in the bins glo + 1
-// (low half) and glo + 2 (high half; a quarter has 2048 entries), exact zeros}.  The staged keys
-// are counted per bin here, from the list, and not as they come (fewer instructions; when the
-// list overflowed the counts are not used: the quarter is read again from Delta).  glo: lowest
-// staged bin of pass A; the one-bin passes give the bin itself.  Returns the number of exact
-// zeros (the same value in every lane).
-__device__ __forceinline__ uint32_t stage_flush(const Ws& ws, int64_t qslot, const uint32_t* st,
-                                                const StageCounts& c, uint32_t glo, int lane) {
-  uint32_t* seg = ws.seg + qslot * kSegCap;
-  const uint32_t m = min(c.n_in, (uint32_t)kSegCap);
-  uint32_t v1 = 0, v2 = 0;
-  for (uint32_t i = lane; i < m; i += kWave) {
-    const uint32_t key = st[i];
-    seg[i] = key;
-    const uint32_t rel = (key >> 20) - glo;
-    v1 += (rel == 1u) ? 1u : 0u;
-    v2 += (rel == 2u) ? 1u : 0u;
-  }
-  const uint32_t n12 = wave_sum_u32(v1 | (v2 << 16));      // both sums stay below 2^16
+// qinfo of the quarter: {entries above the staged bin (one-bin lists; 0 for candidate lists, which
+// hold those entries), staged entries (the full count, also beyond kCandCap), 0, exact zeros
+// (one-bin lists)}.  Returns the number of exact zeros (the same value in every lane).
+__device__ __forceinline__ uint32_t stage_finish(const Ws& ws, int64_t qslot, const CandList& cl, StageCounts& c,
+                                                 int lane) {
+  cand_write_out(ws, qslot, cl, c, lane);
   const uint32_t n_hi = wave_sum_u32(c.v_hi), nz = wave_sum_u32(c.v_nz);
-  if (lane == 0) ws.qinfo[qslot] = make_uint4(n_hi, c.n_in, n12, nz);
+  if (lane == 0) ws.qinfo[qslot] = make_uint4(n_hi, c.n_out, 0u, nz);
   return nz;
 }
 
@@ -305,7 +356,7 @@ __device__ __forceinline__ float4 drop_kept(const TileGeom& tg, int q, bool qa, 
 template <bool AL, bool SELECT, bool ZB>
 __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, int w, int tile_id,
                                              const FlatTile& ft, const LayerDev& L, const TileGeom& tg,
-                                             uint32_t* hist, uint32_t* st, uint32_t* sub2, uint32_t guess) {
+                                             uint32_t* hist, const CandList& cl, uint32_t* sub2, uint32_t guess) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -314,8 +365,8 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
   float* __restrict__ A = (w == 0) ? ws.A : nullptr;
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
-  uint32_t glo = 0x7ffffff0u;                              // no bin matches without a guess
-  if (SELECT && !ZB && guess != kNoGuess) glo = max(guess, 1u);
+  uint32_t glo = 0x7ffffff0u, gnb = 0u;                    // no bin matches without a guess
+  if (SELECT && !ZB && guess != kNoGuess) { glo = guess_lo(guess); gnb = guess_nb(guess); }
   // two groups per lane are requested before anything else
   constexpr int U = 2;   // (one group is as fast where the memory fits the caches, three or four are no faster anywhere)
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -334,10 +385,11 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   const bool pend = ((*ws.tpending >> w) & 1u) != 0u;      // uniform over the workgroup
   if (SELECT) {
     for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0;
-    if (tid < kSub2) sub2[tid] = 0;
+    for (int b = tid; b < kSub2; b += kFlatThreads) sub2[b] = 0;
     __syncthreads();
   }
-  StageCounts cnt = {0u, 0u, 0u};                          // n_in: wave-uniform
+  StageCounts cnt = {0u, 0u, 0u, 0u};
+  const int64_t qslot_mine = quarter_slot(ws, L, w, ft.start >> kTileShift, wave);
   for (int q0 = span.qbeg; q0 < span.qend; q0 += U * kWave) {
     float4 gn[U], en[U], an[U];
 #pragma unroll
@@ -362,34 +414,37 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
         }
       }
       if (SELECT) {
+        const uint32_t i_rel = 4u * (uint32_t)(q - span.qbeg);
         if (AL && full) {
           // every lane of both groups is inside the span: no masks
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const uint32_t key = key_of(comp(d, c));
             hist_add(hist, (key >> 20) != 0u, key >> 20);
-            if (ZB) stage_one_bin(st, sub2, cnt, ~0ull, true, key, 0u, lane);
-            else stage_guessed_bins(st, sub2, cnt, ~0ull, true, key, glo, lane);
+            if (ZB) stage_one_bin(cl, sub2, cnt, ~0ull, true, key, 0u, lane);
           }
+          if (!ZB) stage_candidates<false>(cl, sub2, cnt, 0ull, 0ull, 0ull, 0ull, d, glo, gnb, i_rel, lane);
         } else {
           const uint64_t m_span = ballot64(qa);
+          uint64_t mv[4];
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const bool valid = elem_valid<AL>(tg, q, c, qa);
-            const uint64_t mv = valid_mask<AL>(tg, q, c, qa, m_span);
+            mv[c] = valid_mask<AL>(tg, q, c, qa, m_span);
             const uint32_t key = key_of(comp(d, c));
             hist_add(hist, valid && (key >> 20) != 0u, key >> 20);
-            if (ZB) stage_one_bin(st, sub2, cnt, mv, valid, key, 0u, lane);
-            else stage_guessed_bins(st, sub2, cnt, mv, valid, key, glo, lane);
+            if (ZB) stage_one_bin(cl, sub2, cnt, mv[c], valid, key, 0u, lane);
           }
+          if (!ZB) stage_candidates<true>(cl, sub2, cnt, mv[0], mv[1], mv[2], mv[3], d, glo, gnb, i_rel, lane);
         }
+        cand_make_room(ws, qslot_mine, cl, cnt, lane);
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) { gc[u] = gn[u]; ec[u] = en[u]; ac[u] = an[u]; }
   }
   if (SELECT) {
-    stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, ZB ? 0u : glo, lane);
+    stage_finish(ws, qslot_mine, cl, cnt, lane);
     __syncthreads();
     uint32_t* gh = ws.hist1 + wl * kHistBins;                // bin 0 stays empty: the pick kernel derives it
     for (int b = tid; b < kHistBins; b += kFlatThreads) {
@@ -399,52 +454,58 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
     // the tile's level-2 counts are added to the slot its group of kT2Group tiles shares (integer
     // atomics; the pick kernel reads and clears the slots): one compute unit works on a whole
     // layer there, and a slot per tile is 2 MB to read for a layer of 22 M entries
-    if (tid < kSub2 && sub2[tid] != 0u) {
-      const int slot = L.t2slot0 + (ft.start >> kTileShift) / kT2Group;
-      atomicAdd(&ws.t2[((int64_t)w * ws.n_t2slots + slot) * kSub2 + tid], sub2[tid]);
-    }
+    const int slot = L.t2slot0 + (ft.start >> kTileShift) / kT2Group;
+    for (int b = tid; b < kSub2; b += kFlatThreads)
+      if (sub2[b] != 0u) atomicAdd(&ws.t2[((int64_t)w * ws.n_t2slots + slot) * kSub2 + b], sub2[b]);
   }
 }
 
 __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const GradPtrs gp, int w0) {
   __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t stage[4][2 * kSubCap];
+  __shared__ uint32_t cand_val[4][kCandLdsSlots];
+  __shared__ uint16_t cand_idx[4][kCandLdsSlots];
   __shared__ uint32_t sub2[kSub2];
   const int w = w0 + blockIdx.y;
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
-  uint32_t* st = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+  const int lw = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const CandList cl = {cand_val[lw], cand_idx[lw]};
+  // the layer's "compact from Delta" flag of the last step is cleared before this step's
+  // decision kernels (which set it) run
+  if (w == 0 && ft.start == 0 && threadIdx.x == 0) ws.lflag[ft.layer] = 0u;
   if (L.ntiles == 1) {
-    if (tg.aligned) ef_hist_tile<true, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, kNoGuess);
-    else ef_hist_tile<false, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, kNoGuess);
+    if (tg.aligned) ef_hist_tile<true, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, kNoGuess);
+    else ef_hist_tile<false, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, kNoGuess);
   } else {
     const uint32_t guess = ws.guess[((int64_t)w * ws.L + ft.layer) * 2 + ws.level[ft.layer]];
     if (guess == kGuessZero) {                               // uniform over the workgroup
-      if (tg.aligned) ef_hist_tile<true, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, guess);
-      else ef_hist_tile<false, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, guess);
+      if (tg.aligned) ef_hist_tile<true, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, guess);
+      else ef_hist_tile<false, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, guess);
     } else {
-      if (tg.aligned) ef_hist_tile<true, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, guess);
-      else ef_hist_tile<false, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, st, sub2, guess);
+      if (tg.aligned) ef_hist_tile<true, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, guess);
+      else ef_hist_tile<false, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, guess);
     }
   }
 }
 
-// ---- B: re-stage the keys of b1 for the layers whose guess missed --------------------------------
+// ---- B: re-stage the keys of b1 for a layer whose guess missed -----------------------------------
+// Run by the counting kernel's workgroup of the tile (the per-layer kernel after it then works from
+// these lists).
 
 template <bool AL>
 __device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile& ft,
-                                             const LayerDev& L, const TileGeom& tg, uint32_t b1, uint32_t* st,
+                                             const LayerDev& L, const TileGeom& tg, uint32_t b1, const CandList& cl,
                                              uint32_t* sub2) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const WaveSpan span = wave_span(tg, wave);
   const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
-  __syncthreads();                                         // the previous tile's counts have been written
-  if (tid < kSub2) sub2[tid] = 0;
+  if (tid < kL2Bins) sub2[tid] = 0;
   __syncthreads();
-  StageCounts cnt = {0u, 0u, 0u};
+  StageCounts cnt = {0u, 0u, 0u, 0u};
+  const int64_t qslot = quarter_slot(ws, L, w, ft.start >> kTileShift, wave);
   float4 cur = ld_span<AL>(e, tg, span, span.qbeg + lane);
   for (int q0 = span.qbeg; q0 < span.qend; q0 += kWave) {
     const int q = q0 + lane;
@@ -453,11 +514,12 @@ __device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile
     const uint64_t m_span = ballot64(qa);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
-      stage_one_bin(st, sub2, cnt, valid_mask<AL>(tg, q, c, qa, m_span), elem_valid<AL>(tg, q, c, qa),
+      stage_one_bin(cl, sub2, cnt, valid_mask<AL>(tg, q, c, qa, m_span), elem_valid<AL>(tg, q, c, qa),
                     key_of(comp(cur, c)), b1, lane);
+    cand_make_room(ws, qslot, cl, cnt, lane);
     cur = nxt;
   }
-  const uint32_t nz = stage_flush(ws, quarter_slot(ws, L, w, ft.start >> kTileShift, wave), st, cnt, b1, lane);
+  const uint32_t nz = stage_finish(ws, qslot, cl, cnt, lane);
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   if (lane == 0 && nz) atomicAdd(&ws.sel[wl].zeros, nz);
   __syncthreads();
@@ -465,72 +527,60 @@ __device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile
   if (tid < kL2Bins && sub2[tid]) atomicAdd(&ws.hist2m[wl * kL2Bins + tid], sub2[tid]);
 }
 
-// The grid is smaller than the tile table and strides over it; when no layer of the worker
-// missed (the usual case) every workgroup leaves after one load.
-__global__ __launch_bounds__(256) void topk_restage_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t stage[4][2 * kSubCap];
-  __shared__ uint32_t sub2[kSub2];
-  const int w = w0 + blockIdx.y;
-  if (ws.miss_any[w] == 0u) return;                        // uniform over the workgroup
-  uint32_t* st = stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
-  for (int t = blockIdx.x; t < ws.n_ftiles; t += gridDim.x) {
-    const FlatTile ft = ws.ftiles[t];
-    const LayerDev& L = ws.layers[ft.layer];
-    if (L.ntiles == 1) continue;
-    const SelState* sp = ws.sel + (int64_t)w * ws.L + ft.layer;
-    if (sp->mode != 1u) continue;
-    const TileGeom tg = tile_geom(L, ft);
-    if (tg.aligned) restage_tile<true>(ws, w, ft, L, tg, sp->b1, st, sub2);
-    else restage_tile<false>(ws, w, ft, L, tg, sp->b1, st, sub2);
-  }
-}
-
 // ---- the per-layer decisions ---------------------------------------------------------------------
 
-constexpr int kFirstChunks = kSegCap / kWave;   // 64-key chunks of a segment
-
-struct QuarterKeys {
-  uint4 info;                      // {entries above the staged bins, staged keys, of which 2nd | 3rd bin << 16, zeros}
-  uint32_t chunk[kFirstChunks];    // the calling lane's staged keys
+// The first kEagerChunks 64-entry chunks of a quarter's list are requested together with its
+// counts (the slot always exists; what lies past the count is ignored later), the rest once the
+// count is there and only if it reaches them: a quarter lists 40 to 350 candidates on Gaussian or
+// Laplacian gradients at K = 1 % to 10 %.
+constexpr int kEagerChunks = 4;
+struct QuarterHead {
+  uint4 info;                      // see stage_finish
+  uint32_t chunk[kEagerChunks];    // the calling lane's entries of the first chunks
 };
 
-// The first kEagerChunks chunks of a quarter's segment are requested together with its counts
-// (the slot always exists; what lies past the count is ignored later), the rest once the count is
-// there and only if it reaches them: a quarter stages 30 to 130 keys on Gaussian gradients at
-// K = 1 % to 10 %, and reading all 512 slots of every quarter is 90 MB per step on ResNet-18 shapes.
-constexpr int kEagerChunks = 3;
-__device__ __forceinline__ QuarterKeys load_quarter_keys(const Ws& ws, int64_t qslot, int lane) {
-  QuarterKeys k;
-  k.info = ws.qinfo[qslot];
-  const uint32_t* seg = ws.seg + qslot * kSegCap;
+__device__ __forceinline__ QuarterHead load_quarter_head(const Ws& ws, int64_t qslot, int lane) {
+  QuarterHead h;
+  h.info = ws.qinfo[qslot];
+  const uint32_t* cv = ws.cand_val + qslot * kCandCap;
 #pragma unroll
-  for (int ch = 0; ch < kEagerChunks; ++ch) k.chunk[ch] = seg[ch * kWave + lane];
-  const uint32_t n = rfl(k.info.y);
-#pragma unroll
-  for (int ch = kEagerChunks; ch < kFirstChunks; ++ch)
-    k.chunk[ch] = (n > (uint32_t)(ch * kWave)) ? seg[ch * kWave + lane] : 0u;   // uniform condition
-  return k;
+  for (int ch = 0; ch < kEagerChunks; ++ch) h.chunk[ch] = cv[ch * kWave + lane];
+  return h;
 }
 
 // Calls f(key, valid) with all 64 lanes for every key of bin b1 (zeros excluded) of one quarter
-// and returns the quarter's number of entries in bins above b1: from the staged segment and the
-// counts of pass A, or -- when the quarter has more staged keys than the segment holds, or when
-// nothing useful was staged (from_delta) -- from Delta itself.
-// side: b1 is the lower (0) or the upper (1) of the staged bins; tl: tile within the layer,
-// wave: quarter within the tile.
+// and returns the quarter's number of entries in bins above b1: from the quarter's list (the
+// candidates of pass A, or the keys of b1 alone with the entries above counted in info.x), or --
+// when the quarter has more entries than its list holds -- from Delta itself.
+// tl: tile within the layer, wave: quarter within the tile.
 template <class F>
 __device__ __forceinline__ uint32_t for_quarter_keys(const Ws& ws, const LayerDev& L, int w, int tl, int wave,
-                                                     const QuarterKeys& k, uint32_t side, uint32_t b1,
-                                                     bool from_delta, int lane, F f) {
-  const uint32_t n = k.info.y;
-  if (!from_delta && n <= (uint32_t)kSegCap) {
+                                                     int64_t qslot, const QuarterHead& h, uint32_t b1, int lane,
+                                                     F f) {
+  const uint32_t n = rfl(h.info.y);
+  if (n <= (uint32_t)kCandCap) {
+    uint32_t above = rfl(h.info.x);
+    auto visit = [&](uint32_t raw, uint32_t t) {
+      const uint32_t key = raw & 0x7fffffffu;
+      const uint32_t bin = key >> 20;
+      const uint64_t mvalid = ballot64(t < n);
+      above += (uint32_t)__popcll(ballot64(bin > b1) & mvalid);
+      f(key, t < n && bin == b1);
+    };
 #pragma unroll
-    for (int ch = 0; ch < kFirstChunks; ++ch)
-      if (n > (uint32_t)(ch * kWave))                                                       // uniform condition
-        f(k.chunk[ch], (uint32_t)(ch * kWave + lane) < n && (k.chunk[ch] >> 20) == b1);
-    // entries of the staged bins above b1: bins glo + 1 and glo + 2 are counted in the two halves of z
-    const uint32_t n1 = k.info.z & 0xffffu, n2 = k.info.z >> 16;
-    return k.info.x + (side == 0u ? n1 + n2 : (side == 1u ? n2 : 0u));
+    for (int ch = 0; ch < kEagerChunks; ++ch)
+      if (n > (uint32_t)(ch * kWave)) visit(h.chunk[ch], (uint32_t)(ch * kWave + lane));   // uniform condition
+    const uint32_t* cv = ws.cand_val + qslot * kCandCap;
+    constexpr int U = 4;
+    for (uint32_t t0 = kEagerChunks * kWave; t0 < n; t0 += U * kWave) {
+      uint32_t raw[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) raw[u] = cv[min(t0 + u * kWave + lane, (uint32_t)(kCandCap - 1))];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (n > t0 + u * kWave) visit(raw[u], t0 + u * kWave + lane);                         // uniform condition
+    }
+    return above;
   }
   FlatTile ft;
   ft.layer = 0;
@@ -697,19 +747,22 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
     pick_bin(hist, k_other, out, scratch);
     if (tid == 0) {
       const uint32_t bo = out[0];
-      ws.guess[wl * 2 + (1 - lv)] = (bo == 0u) ? kGuessZero : (uint32_t)max(0, min(kHistBins - kGuessBins, (int)bo - 1));
+      // (the memory will adapt to the new level for some steps: a wide guess)
+      ws.guess[wl * 2 + (1 - lv)] = (bo == 0u) ? kGuessZero : make_guess((int)bo - kGuessWide / 2, kGuessWide);
     }
     __syncthreads();
   }
-  const uint32_t glo = max(guess, 1u);                     // the bins pass A staged: glo .. glo + kGuessBins - 1
-  const bool hit = guess != kNoGuess && guess != kGuessZero && b1 != 0u && b1 >= glo && b1 - glo < (uint32_t)kGuessBins;
+  const bool guessed = guess != kNoGuess && guess != kGuessZero;
+  const uint32_t glo = guessed ? guess_lo(guess) : 0u;     // the bins pass A counted: glo .. glo + nb - 1
+  const bool hit = guessed && b1 >= glo && b1 - glo < guess_nb(guess);
   // bin 0 guessed and found: pass A left what the re-staging pass would (mode 2: staged already)
   const bool zhit = guess == kGuessZero && b1 == 0u;
   const uint32_t side = hit ? b1 - glo : 0u;
   if (tid == 0) {
     sp->b1 = b1; sp->need2 = need2; sp->k = k; sp->side = side; sp->zeros = 0u;
     sp->mode = hit ? 0u : (zhit ? 2u : 1u);
-    if (!hit && !zhit) ws.miss_any[w] = 1u;                // cleared by the compaction kernel
+    // the candidate lists of this layer cannot serve the compaction: it reads Delta instead
+    if (!hit) atomicOr(&ws.lflag[li], 1u);                 // cleared by the next step's first pass
     if (!hit && !zhit) atomicAdd(&ws.stats[0], 1ull);      // layers re-staged (diagnostic counter)
   }
   if (zhit) {
@@ -742,6 +795,9 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
 __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   __shared__ uint32_t hist[kHistBins];
   __shared__ uint32_t out[3], scratch[4];
+  __shared__ uint32_t cand_val[4][kCandLdsSlots];           // a missed layer: its tiles are staged again here
+  __shared__ uint16_t cand_idx[4][kCandLdsSlots];
+  __shared__ uint32_t sub2[kL2Bins];
   const int w = w0 + blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -750,14 +806,23 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   SelState* sp = ws.sel + wl;
   const int tl = ft.start >> kTileShift;
   const int64_t qslot = (int64_t)w * ws.q_stride + ft.qslot0 + wave;
-  // the segment is requested before the layer's entry and its state have arrived
-  const QuarterKeys qk = load_quarter_keys(ws, qslot, lane);
+  // the list is requested before the layer's entry and its state have arrived
+  const QuarterHead qh = load_quarter_head(ws, qslot, lane);
   const LayerDev& L = ws.layers[ft.layer];
   if (L.ntiles == 1) return;                               // decided by the last pick kernel
-  const uint32_t side = sp->side, b1 = sp->b1;
+  const uint32_t b1 = sp->b1, mode = sp->mode;
   uint32_t b2 = sp->b2;
-  if (sp->mode != 0u) {                                    // uniform over the workgroup
-    // a missed layer: its keys of b1 were re-staged and their level-2 counts summed
+  if (mode == 1u) {                                        // uniform over the workgroup
+    // The guess missed: nothing useful was staged.  This tile's keys of b1 are staged now (one
+    // more read of Delta) with their level-2 counts; the layer's pick kernel takes it from there.
+    const TileGeom tg = tile_geom(L, ft);
+    const CandList cl = {cand_val[wave], cand_idx[wave]};
+    if (tg.aligned) restage_tile<true>(ws, w, ft, L, tg, b1, cl, sub2);
+    else restage_tile<false>(ws, w, ft, L, tg, b1, cl, sub2);
+    return;
+  }
+  if (mode == 2u) {
+    // bin 0 guessed and found: its non-zero keys were staged and their level-2 counts summed
     const int tid = threadIdx.x;
     const uint32_t zeros = sp->zeros;
     for (int b = tid; b < kHistBins; b += kFlatThreads) {
@@ -771,9 +836,11 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
     b2 = out[0];
     if (tl == 0 && tid == 0) { sp->b2 = b2; sp->need3 = need2 - out[1]; }
   }
+  // more candidates than the list holds: the compaction of this layer reads Delta
+  if (lane == 0 && rfl(qh.info.y) > (uint32_t)kCandCap) atomicOr(&ws.lflag[ft.layer], 1u);
   uint32_t* list = ws.qlist + qslot * kQListCap;
   uint32_t n_gt = 0, n_in = 0;                             // wave-uniform
-  const uint32_t above = for_quarter_keys(ws, L, w, tl, wave, qk, side, b1, false, lane, [&](uint32_t key, bool valid) {
+  const uint32_t above = for_quarter_keys(ws, L, w, tl, wave, qslot, qh, b1, lane, [&](uint32_t key, bool valid) {
     const uint32_t bb = bin2_of(key);
     const uint64_t mv = ballot64(valid);
     n_gt += (uint32_t)__popcll(ballot64(bb > b2) & mv);
@@ -838,10 +905,29 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
   if (tid == 0) { flag = 0u; lcount = 0u; }
   // requested now, used by thread 0 at the very end (the guess for the next step)
   const uint2 prev_hist = ws.b1hist[wl * 2 + lv];
-  const uint32_t b1 = sp->b1, side = sp->side, b2 = sp->b2, zeros = sp->zeros;
+  const uint32_t b1 = sp->b1, zeros = sp->zeros, mode = sp->mode;
+  uint32_t b2 = sp->b2;
   uint32_t need = sp->need3;
-  const bool zero_bin = (b1 == 0u && b2 == 0u);            // bin (b1, b2) holds the exact zeros
   __syncthreads();
+  if (mode == 1u) {                                        // uniform over the workgroup
+    // The guess missed: the counting kernel's workgroups have staged the keys of b1 tile by tile
+    // and summed their level-2 counts.  b2 comes from those; what the quarter lists would have
+    // given is taken by sweeps over the staged keys (one workgroup for the whole layer: slower
+    // than the listed path, and rare).
+    for (int b = tid; b < kHistBins; b += kPickThreads) {
+      uint32_t h = (b < kL2Bins) ? ws.hist2m[wl * kL2Bins + b] : 0u;
+      if (b == 0 && b1 == 0u) h += zeros;                    // exact zeros: level-2 bin 0 of bin 0
+      hist[b] = h;
+    }
+    __syncthreads();
+    const uint32_t need2 = sp->need2;
+    pick_bin(hist, need2, out, scratch);
+    b2 = out[0];
+    need = need2 - out[1];
+    if (tid == 0) { flag = 1u; sp->b2 = b2; sp->need3 = need; }
+    __syncthreads();                                       // everybody has read out[]
+  }
+  const bool zero_bin = (b1 == 0u && b2 == 0u);            // bin (b1, b2) holds the exact zeros
   // Gather the listed keys of the whole layer in LDS, packed as (quarter << 14 | low 14 key
   // bits): the upper 17 key bits are those of (b1, b2).  A quarter's count and its list slot are
   // requested together.
@@ -884,7 +970,7 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
   // clamped indices, so that every lane runs every round.  Of a quarter's list the first four keys
   // come with its count; the rest only when the count reaches them.
   constexpr int G = 4;
-  for (int q0 = 0; q0 < nq; q0 += G * kPickThreads) {
+  for (int q0 = (mode == 1u ? nq : 0); q0 < nq; q0 += G * kPickThreads) {
     uint32_t n[G], g0[G], zq[G];
     uint4 k4[G][kQListCap / 4];
 #pragma unroll
@@ -981,13 +1067,14 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
       }
     }
   } else {
-    if (tid == 0) atomicAdd(&ws.stats[1], 1ull);            // layers decided by sweeps (diagnostic counter)
+    // layers whose tie class sent them to the sweeps (diagnostic counter; a missed guess is counted apart)
+    if (tid == 0 && mode != 1u) atomicAdd(&ws.stats[1], 1ull);
     // Slow path (some quarter holds more keys of bin (b1, b2) than its list, i.e. a large tie
-    // class): sweeps of the workgroup over the keys of bin b1 of the whole layer.
+    // class; or the guess missed): sweeps of the workgroup over the keys of bin b1 of the whole layer.
     auto sweep = [&](auto per_key, auto per_quarter) {
       for (int q = wave; q < nq; q += kPickWaves) {
-        const QuarterKeys qk = load_quarter_keys(ws, qbase + q, lane);
-        const uint32_t above = for_quarter_keys(ws, L, w, q >> 2, q & 3, qk, side, b1, false, lane, per_key);
+        const QuarterHead qh = load_quarter_head(ws, qbase + q, lane);
+        const uint32_t above = for_quarter_keys(ws, L, w, q >> 2, q & 3, qbase + q, qh, b1, lane, per_key);
         per_quarter(q, above);
       }
     };
@@ -1088,11 +1175,9 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
   }
   if (tid == 0) {
     sp->T = T; sp->ktie = ktie; sp->alleq = alleq; sp->mode = 0u;
-    // Next step's guess at this level: kGuessBins adjacent bins.  While the threshold is moving
-    // (the steps after a level switch, when the memory adapts) b1 is extrapolated from the last
-    // two steps.  Three bins: the extrapolated bin and both neighbours.  Two bins: the extrapolated
-    // bin paired with the bin it would reach if the move slowed down, or, when it rests, with the
-    // neighbour on the side of the threshold.
+    // Next step's guess at this level: adjacent bins centred on b1, or -- while the threshold is
+    // moving (the steps after a level switch, when the memory adapts) -- on the bin extrapolated
+    // from the last two steps; narrow when the last two steps did not move, wide otherwise.
     // b1hist: (b1 | (last move + 64) << 16, step)
     const uint2 prev = prev_hist;
     const bool consecutive = prev.y + 1u == step_id;
@@ -1100,19 +1185,12 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
     v = max(-64, min(64, v));
     const int pv = consecutive ? (int)(prev.x >> 16) - 64 : 0;   // the move before
     ws.b1hist[wl * 2 + lv] = make_uint2(b1 | ((uint32_t)(v + 64) << 16), step_id);
-    int g = (int)b1;
-    if (kGuessBins > 2) {
-      // a single step of one bin may well be taken back; larger moves and moves that go on in
-      // one direction are followed
-      const bool follow = v > 1 || v < -1 || (v != 0 && (v > 0) == (pv > 0) && pv != 0);
-      g = (int)b1 - 1 + (follow ? v : 0);
-    } else {
-      if (v > 0) g = (int)b1 + v - 1;
-      else if (v < 0) g = (int)b1 + v;
-      else if (b2 < (uint32_t)(kL2Bins / 2)) g = (int)b1 - 1;
-    }
-    uint32_t glo = (uint32_t)max(0, min(kHistBins - kGuessBins, g));
-    ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero : glo;
+    // a single step of one bin may well be taken back; larger moves and moves that go on in one
+    // direction are followed
+    const bool follow = v > 1 || v < -1 || (v != 0 && (v > 0) == (pv > 0) && pv != 0);
+    const int centre = (int)b1 + (follow ? v : 0);
+    const int nb = (consecutive && v == 0 && pv == 0) ? kGuessNarrow : kGuessWide;   // the first step at a level: wide
+    ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero : make_guess(centre - nb / 2, nb);
   }
 }
 
@@ -1320,7 +1398,6 @@ __global__ __launch_bounds__(256) void topk_compact_kernel(const Ws ws, int w0) 
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
   if (blockIdx.x == 0 && threadIdx.x == 0) {
-    ws.miss_any[w] = 0u;
     atomicAnd(ws.tpending, ~(1u << w));                    // this path writes the residual itself
   }
   __shared__ uint32_t stage[4][kStgWords];
@@ -1534,11 +1611,149 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
   }
 }
 
+// The same pass from the candidate lists of pass A instead of Delta: for a layer whose guess held
+// for every worker, whose lists are complete and which keeps at most half of its entries, a wave
+// reads the (offset, value) candidates of its quarter worker by worker (6 bytes per candidate),
+// picks the selected ones with the same rule (key >= t_all, or equal to T within the tie quota,
+// in index order), writes them to the payload at consecutive positions (the selected lanes of one
+// instruction write consecutive words) and adds the values into the quarter's dense sums in
+// LDS, workers in order from +0; the sums, divided by W, go out as the quarter's part of the
+// averaged gradient.  acc: the wave's kQuarterFloats floats of LDS.
+constexpr int kQuarterGroups = (kTile / 4 + 1 + 3) / 4;     // 513: 16-byte groups of a wave quarter at most
+constexpr int kQuarterFloats = 4 * kQuarterGroups + 12;     // rounded up to whole 64-byte rows
+
+template <bool AL, bool UPD>
+__device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& ft, const LayerDev& L,
+                                                 const TileGeom& tg, const Sink sink, float* acc, int wave) {
+  const int lane = threadIdx.x & 63;
+  const WaveSpan span = wave_span(tg, wave);
+  const int ng = span.qend - span.qbeg;                    // groups of the quarter, wave-uniform
+  if (ng <= 0) return;
+  const int64_t qslot_local = L.qoff + 4 * (int64_t)(ft.start >> kTileShift) + wave;
+  const int W = ws.W;
+  const int64_t pay_off = L.pay_off, pay_stride = ws.pay_stride, q_stride = ws.q_stride;
+  int32_t* const pay_idx = ws.pay_idx;
+  float* const pay_val = ws.pay_val;
+  const uint32_t* const cand_val = ws.cand_val;
+  const uint16_t* const cand_idx = ws.cand_idx;
+  // lane w holds worker w's selection state and candidate count for this quarter
+  QuarterSel mine = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+  uint32_t n_mine = 0u;
+  if (lane < W) {
+    mine = load_quarter_sel(ws, lane, ft.layer, qslot_local);
+    n_mine = min(ws.qinfo[(int64_t)lane * q_stride + qslot_local].y, (uint32_t)kCandCap);
+  }
+  // the first chunk of worker 0's list is requested before the sums are cleared
+  constexpr int U = 2;                                      // 64-entry chunks requested together
+  auto load_chunks = [&](int w, uint32_t t0, uint32_t (&v)[U], uint32_t (&ix)[U]) {
+    const int64_t base = ((int64_t)w * q_stride + qslot_local) * kCandCap;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t t = min(t0 + u * kWave + lane, (uint32_t)(kCandCap - 1));
+      v[u] = cand_val[base + t];
+      ix[u] = cand_idx[base + t];
+    }
+  };
+  uint32_t cv[U], ci[U];
+  load_chunks(0, 0u, cv, ci);
+  float4* acc4 = reinterpret_cast<float4*>(acc);
+  for (int g = lane; g < ng; g += kWave) acc4[g] = make_float4(0.f, 0.f, 0.f, 0.f);
+  __builtin_amdgcn_wave_barrier();
+  // index of the quarter's first element in the layer
+  const int32_t i_quarter = (int32_t)(tg.a0 + 4 * (int64_t)span.qbeg - L.offset);
+  for (int w = 0; w < W; ++w) {
+    const uint32_t n = (uint32_t)__builtin_amdgcn_readlane((int)n_mine, w);
+    const uint32_t t_all = (uint32_t)__builtin_amdgcn_readlane((int)mine.t_all, w);
+    const uint32_t k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
+    const bool ties = ((uint32_t)__builtin_amdgcn_readlane((int)mine.flags, w) & 1u) != 0u;
+    const uint32_t T = (uint32_t)__builtin_amdgcn_readlane((int)mine.T, w);
+    const uint32_t ktie = (uint32_t)__builtin_amdgcn_readlane((int)mine.ktie, w);
+    uint32_t eq_run = (uint32_t)__builtin_amdgcn_readlane((int)mine.eq_before, w);
+    uint32_t pos_run = (uint32_t)__builtin_amdgcn_readlane((int)mine.gt_before, w) + min(ktie, eq_run);
+    int32_t* __restrict__ pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
+    float* __restrict__ pval = pay_val + (int64_t)w * pay_stride + pay_off;
+    for (uint32_t t0 = 0u; t0 < n || t0 == 0u; t0 += U * kWave) {
+      // what the registers are loaded with next: the rest of this worker's list, else the head of
+      // the next worker's (requested whether or not anybody will look at it)
+      uint32_t nv[U], ni[U];
+      const bool more = t0 + U * kWave < n;
+      load_chunks(more ? w : min(w + 1, W - 1), more ? t0 + U * kWave : 0u, nv, ni);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t t = t0 + u * kWave + lane;
+        if (t0 + u * kWave < n) {                            // wave-uniform
+          const uint32_t key = cv[u] & 0x7fffffffu;
+          const uint64_t mvalid = ballot64(t < n);
+          uint64_t msel = ballot64(key >= t_all) & mvalid;
+          if (ties) {                                        // wave-uniform
+            const uint64_t meq = ballot64(key == T) & mvalid;
+            if (meq != 0) {
+              const uint32_t rank = eq_run + lanes_below(meq, lane);
+              msel |= ballot64(rank < ktie) & meq;
+              eq_run += (uint32_t)__popcll(meq);
+            }
+          }
+          msel = scalar_mask(msel);
+          if (lane_bit(msel)) {
+            const uint32_t pos = pos_run + lanes_below(msel, lane);
+            if (pos < k) {                                   // always true for consistent state
+              const uint32_t boff = pos << 2;
+              __builtin_nontemporal_store(i_quarter + (int32_t)ci[u], (int32_t*)((char*)pidx + boff));
+              __builtin_nontemporal_store(__uint_as_float(cv[u]), (float*)((char*)pval + boff));
+            }
+            // offsets are unique within a worker's list, and a wave's LDS operations keep their order
+            acc[ci[u]] += __uint_as_float(cv[u]);
+          }
+          pos_run += (uint32_t)__popcll(msel);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) { cv[u] = nv[u]; ci[u] = ni[u]; }
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  const float fw = (float)W;
+  const bool pow2 = (W & (W - 1)) == 0;                     // then x / W and x * (1 / W) round alike
+  const float rw = 1.0f / fw;
+  for (int g0 = 0; g0 < ng; g0 += kWave) {
+    const int g = g0 + lane;
+    const int q = span.qbeg + g;
+    float4 wq = make_float4(0.f, 0.f, 0.f, 0.f), vq = wq;
+    if (UPD) {
+      if (sink.stream_wv) {                                 // uniform: see stream_wv() on the host side
+        wq = ld_span<AL, true>(sink.wt, tg, span, q);
+        vq = ld_span<AL, true>(sink.vel, tg, span, q);
+      } else {
+        wq = ld_span<AL>(sink.wt, tg, span, q);
+        vq = ld_span<AL>(sink.vel, tg, span, q);
+      }
+    }
+    if (g < ng) {
+      const float4 a = acc4[g];
+      const float4 v = pow2 ? make_float4(a.x * rw, a.y * rw, a.z * rw, a.w * rw)
+                            : make_float4(a.x / fw, a.y / fw, a.z / fw, a.w / fw);
+      if (UPD) {
+        nesterov4(v, wq, vq, sink);
+        if (sink.stream_wv) {
+          stq<AL, true>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
+          stq<AL, true>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
+        } else {
+          stq<AL>(sink.wt, tg.a0, tg.lo, tg.hi, q, wq);
+          stq<AL>(sink.vel, tg.a0, tg.lo, tg.hi, q, vq);
+        }
+      } else {
+        stq<AL, kStreamOut>(sink.out, tg.a0, tg.lo, tg.hi, q, v);
+      }
+    }
+  }
+}
+
 // The waves of this pass are independent of each other (one quarter of a tile each), so the
 // workgroup can be smaller than a tile: kMeanWaves quarters per workgroup (two: 1 us faster than
 // four on ResNet-18 shapes, the same as one).
 constexpr int kMeanWaves = 2;
 constexpr int kMeanSplit = 4 / kMeanWaves;                  // workgroups per tile
+constexpr int kMeanLdsWords = kQuarterFloats > kChunkWords ? kQuarterFloats : kChunkWords;
 
 template <bool UPD>
 __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink) {
@@ -1549,10 +1764,10 @@ __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink
     ws.words[1] = ws.words[0];
     ws.words[2] += ws.words[0];
   }
-  if (blockIdx.x == 0 && threadIdx.x < ws.W) ws.miss_any[threadIdx.x] = 0u;
   // every e_w keeps Delta_w: the kept entries are dropped by the next pass over it
   if (blockIdx.x == 0 && threadIdx.x == 0) *ws.tpending = ws.W == 32 ? 0xffffffffu : ((1u << ws.W) - 1u);
-  __shared__ uint32_t stage[kMeanWaves][kChunkWords];
+  // a wave's LDS: the staging list of the pass over Delta, or the dense sums of the pass over the lists
+  __shared__ __attribute__((aligned(16))) uint32_t stage[kMeanWaves][kMeanLdsWords];
   const int lw = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t* stg = stage[lw];
   const int wave = (int)(blockIdx.x % kMeanSplit) * kMeanWaves + lw;   // the quarter of the tile
@@ -1562,6 +1777,10 @@ __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink
   if (holes) {
     if (tg.aligned) compact_mean_tile<true, UPD, true>(ws, ft, L, tg, sink, stg, wave);
     else compact_mean_tile<false, UPD, true>(ws, ft, L, tg, sink, stg, wave);
+  } else if (L.ntiles > 1 && rfl(ws.lflag[ft.layer]) == 0u) {
+    // every worker's guess held and every list is complete: the candidates serve
+    if (tg.aligned) gather_mean_tile<true, UPD>(ws, ft, L, tg, sink, reinterpret_cast<float*>(stg), wave);
+    else gather_mean_tile<false, UPD>(ws, ft, L, tg, sink, reinterpret_cast<float*>(stg), wave);
   } else {
     if (tg.aligned) compact_mean_tile<true, UPD, false>(ws, ft, L, tg, sink, stg, wave);
     else compact_mean_tile<false, UPD, false>(ws, ft, L, tg, sink, stg, wave);

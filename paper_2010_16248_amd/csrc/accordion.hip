@@ -51,7 +51,7 @@ struct Plan {
   Region r_A, r_e, r_norm_part, r_sq_part, r_bstate;
   int64_t n_model = 0;   // elements that belong to a layer
   Region r_Q, r_Phat, r_Pwork, r_Ppart, r_Qpart, r_vecmean, r_pending;
-  Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_miss, r_b1hist, r_guess, r_qinfo, r_seg, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval, r_overlap, r_tpending;
+  Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_lflag, r_b1hist, r_guess, r_qinfo, r_candval, r_candidx, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval, r_overlap, r_tpending;
   int64_t total_bytes = 0;
 };
 
@@ -231,11 +231,12 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
     reg(p.r_qlist, 4 * (int64_t)kQListCap * p.q_stride * W);
     reg(p.r_sel, (int64_t)sizeof(SelState) * nl * W);
     reg(p.r_hist2m, 4 * (int64_t)kL2Bins * nl * W);
-    reg(p.r_miss, 4 * W);
+    reg(p.r_lflag, 4 * (int64_t)nl);
     reg(p.r_b1hist, 8 * 2 * (int64_t)nl * W);
     reg(p.r_guess, 4 * 2 * (int64_t)nl * W);
     reg(p.r_qinfo, (int64_t)sizeof(uint4) * p.q_stride * W);
-    reg(p.r_seg, 4 * 2 * (int64_t)kSubCap * p.q_stride * W);
+    reg(p.r_candval, 4 * (int64_t)kCandCap * p.q_stride * W);
+    reg(p.r_candidx, 2 * (int64_t)kCandCap * p.q_stride * W);
     reg(p.r_gtq, 4 * p.q_stride * W);
     reg(p.r_eqq, 4 * p.q_stride * W);
     reg(p.r_gtpre, 4 * p.q_stride * W);
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(float4* __restrict__ ds
 
 enum Stage {
   ST_psgd_ef_p_kernel = 0, ST_psgd_orth_kernel, ST_psgd_q_kernel, ST_psgd_qmean_kernel,
-  ST_psgd_decomp_kernel, ST_psgd_residual_kernel, ST_topk_ef_hist_kernel, ST_topk_pick12_kernel, ST_topk_restage_kernel,
+  ST_psgd_decomp_kernel, ST_psgd_residual_kernel, ST_topk_ef_hist_kernel, ST_topk_pick12_kernel,
   ST_topk_count3_kernel, ST_topk_pick3_kernel,
   ST_topk_compact_kernel, ST_topk_compact_mean_kernel, ST_topk_sparse_mean_kernel,
   ST_norm_partial_kernel, ST_regime_decide_kernel, ST_recount_words_kernel, ST_zero_accum_kernel,
@@ -286,7 +287,7 @@ enum Stage {
 static_assert(ST_COUNT <= ACC_N_STAGES, "more stages than the header announces");
 static const char* const kStageNames[ST_COUNT] = {
   "psgd_ef_p_kernel", "psgd_orth_kernel", "psgd_q_kernel", "psgd_qmean_kernel",
-  "psgd_decomp_kernel", "psgd_residual_kernel", "topk_ef_hist_kernel", "topk_pick12_kernel", "topk_restage_kernel",
+  "psgd_decomp_kernel", "psgd_residual_kernel", "topk_ef_hist_kernel", "topk_pick12_kernel",
   "topk_count3_kernel", "topk_pick3_kernel",
   "topk_compact_kernel", "topk_compact_mean_kernel", "topk_sparse_mean_kernel",
   "norm_partial_kernel", "regime_decide_kernel", "recount_words_kernel", "zero_accum_kernel",
@@ -405,8 +406,6 @@ int launch_topk_select(acc_ctx* c, int w0, int nw) {
   const Ws& ws = c->ws;
   ACC_LAUNCH(c, topk_ef_hist_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, c->grads, w0);
   ACC_LAUNCH(c, topk_pick12_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0);
-  // mostly an empty launch (no guess missed): a grid that fills the chip when it is not, and no more
-  ACC_LAUNCH(c, topk_restage_kernel, dim3(std::min(ws.n_ftiles, std::max(512, 2048 / nw)), nw), dim3(256), ws, w0);
   ACC_LAUNCH(c, topk_count3_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
   ACC_LAUNCH(c, topk_pick3_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
   if (c->plan.pick3_big) ACC_LAUNCH(c, topk_pick3_big_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
@@ -645,11 +644,12 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
     ws.qlist = at<uint32_t>(c, p.r_qlist);
     ws.sel = at<SelState>(c, p.r_sel);
     ws.hist2m = at<uint32_t>(c, p.r_hist2m);
-    ws.miss_any = at<uint32_t>(c, p.r_miss);
+    ws.lflag = at<uint32_t>(c, p.r_lflag);
     ws.b1hist = at<uint2>(c, p.r_b1hist);
     ws.guess = at<uint32_t>(c, p.r_guess);
     ws.qinfo = at<uint4>(c, p.r_qinfo);
-    ws.seg = at<uint32_t>(c, p.r_seg);
+    ws.cand_val = at<uint32_t>(c, p.r_candval);
+    ws.cand_idx = at<uint16_t>(c, p.r_candidx);
     ws.gtq = at<uint32_t>(c, p.r_gtq);
     ws.eqq = at<uint32_t>(c, p.r_eqq);
     ws.gtpre = at<uint32_t>(c, p.r_gtpre);
@@ -1114,8 +1114,11 @@ int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
   if (c->cfg.method == ACC_POWERSGD)                         // the memory just written is explicit
     ACC_LAUNCH(c, psgd_clear_pending_kernel, dim3(1), dim3(64), c->ws);
   if (c->cfg.method == ACC_TOPK) ACC_LAUNCH(c, topk_clear_pending_kernel, dim3(1), dim3(64), c->ws);
-  if (c->plan.r_sq_part.bytes > 0)                           // the MSDR window restarts with the import
-    ACC_HIP(c, hipMemset(c->ws.sq_part, 0, (size_t)c->plan.r_sq_part.bytes));
+  if (c->plan.r_sq_part.bytes > 0) {                         // the MSDR window restarts with the import
+    const int n8 = (int)(c->plan.r_sq_part.bytes / 8);
+    ACC_LAUNCH(c, zero_u64_kernel, dim3((n8 + 255) / 256), dim3(256),
+               reinterpret_cast<unsigned long long*>(c->ws.sq_part), n8);
+  }
   ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)c->cfg.method);
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   return ACC_OK;

@@ -171,7 +171,7 @@ def workload(name: str) -> Workload:
                         window_scale_even=[1.00, 0.40, 0.38],
                         window_scale_odd=[1.00, 0.40, 0.38])
     if name == "resnet18_topk_k99":
-        # the levels the paper itself trains with (Section 5.3, TopK tables): K 99 % inside
+        # the levels the paper itself trains with (Section 5.4, TopK tables): K 99 % inside
         # critical regimes, K 25 % outside; ResNet-18 with 100 classes
         return Workload(name, METHOD_TOPK, resnet18_shapes(100), 4, 99, 25,
                         dist="laplace", window_steps=20, n_windows=3, seed=SEED_BASE + 7)

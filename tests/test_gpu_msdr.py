@@ -1,4 +1,4 @@
-"""GPU parity of the comparison detector (mean to standard deviation ratio, Section 5.5) against
+"""GPU parity of the comparison detector (mean to standard deviation ratio, Section 5.6) against
 the oracle: free-running TopK (bit-exact steps), ratios to 1e-6, identical level vectors."""
 import numpy as np
 import pytest

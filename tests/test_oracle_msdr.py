@@ -1,4 +1,4 @@
-"""Pins of the comparison detector's statistic (mean to standard deviation ratio, Section 5.5
+"""Pins of the comparison detector's statistic (mean to standard deviation ratio, Section 5.6
 "Comparison with Prior Work") and of the switching rule as this build reads it."""
 import numpy as np
 
