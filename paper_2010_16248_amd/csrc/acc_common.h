@@ -123,6 +123,7 @@ struct Ws {
   uint32_t* gtpre;             // W x q_stride exclusive prefix of gtq within the layer (+ total)
   uint32_t* eqpre;             // W x q_stride exclusive prefix of eqq within the layer (+ total)
   int64_t q_stride;
+  int64_t n_qslots;            // W * q_stride: all quarter slots (the stride between the chunks of a candidate list)
   int32_t* pay_idx;  float* pay_val;  int64_t pay_stride;
   unsigned long long* overlap; // L per-layer counters of the overlap read-back
   uint32_t* tpending;          // one word: workers whose e still holds Delta with the kept entries in it

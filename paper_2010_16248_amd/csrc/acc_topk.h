@@ -178,24 +178,48 @@ struct CandList { uint32_t* val; uint16_t* idx; };
 // v_hi, v_nz: per lane, summed over the wave when the quarter is finished.
 struct StageCounts { uint32_t n_lds, n_out, v_hi, v_nz; };
 
+// Layout of the lists in device memory: 64-entry chunks, chunk-major -- chunk c of quarter slot q
+// is entries (c * n_slots + q) * 64 ... + 63, n_slots = all quarter slots of all workers.  The first
+// chunks of all quarters are one dense region, the second chunks the next, and so on: a list
+// uses as many chunks as it has entries, so what is touched is dense (a fixed 4 KB slot per quarter
+// of which the first KB is used puts all the traffic on a few memory channels: 10 us per step on
+// ResNet-18 shapes).
+__device__ __forceinline__ int64_t cand_at(const Ws& ws, int64_t qslot, uint32_t chunk, int lane) {
+  return ((int64_t)chunk * ws.n_qslots + qslot) * kWave + lane;
+}
+
+// Writes the whole 64-entry chunks of the wave's LDS list out (final: the rest too) and moves what
+// is left to the front of the list; n_out stays a multiple of 64 until the final call, so every
+// store instruction writes one chunk, consecutive lanes to consecutive addresses.
 __device__ __forceinline__ void cand_write_out(const Ws& ws, int64_t qslot, const CandList& cl, StageCounts& c,
-                                               int lane) {
-  uint32_t* gv = ws.cand_val + qslot * kCandCap;
-  uint16_t* gi = ws.cand_idx + qslot * kCandCap;
+                                               int lane, bool final) {
   __builtin_amdgcn_wave_barrier();                          // the list is complete (LDS is in order per wave)
-  for (uint32_t t = lane; t < c.n_lds; t += kWave) {
-    const uint32_t pos = c.n_out + t;
-    if (pos < (uint32_t)kCandCap) { gv[pos] = cl.val[t]; gi[pos] = cl.idx[t]; }
+  const uint32_t n_full = final ? c.n_lds : (c.n_lds & ~(uint32_t)(kWave - 1));
+  for (uint32_t t0 = 0u; t0 < n_full; t0 += kWave) {
+    const uint32_t t = t0 + lane, chunk = (c.n_out + t0) >> 6;
+#ifndef ACC_EXP_NO_CAND_STORE
+    if (t < n_full && chunk < (uint32_t)(kCandCap / kWave)) {
+      const int64_t a = cand_at(ws, qslot, chunk, lane);
+      ws.cand_val[a] = cl.val[t];
+      ws.cand_idx[a] = cl.idx[t];
+    }
+#endif
   }
+  const uint32_t rest = c.n_lds - n_full;                   // < 64 unless final (then 0)
+  uint32_t rv = 0u;
+  uint16_t ri = 0;
+  if ((uint32_t)lane < rest) { rv = cl.val[n_full + lane]; ri = cl.idx[n_full + lane]; }
   __builtin_amdgcn_wave_barrier();
-  c.n_out += c.n_lds;
-  c.n_lds = 0u;
+  if ((uint32_t)lane < rest) { cl.val[lane] = rv; cl.idx[lane] = ri; }
+  __builtin_amdgcn_wave_barrier();
+  c.n_out += n_full;
+  c.n_lds = rest;
 }
 
 // Room for one more group of four elements per lane?  Called after every group (wave-uniform).
 __device__ __forceinline__ void cand_make_room(const Ws& ws, int64_t qslot, const CandList& cl, StageCounts& c,
                                                int lane) {
-  if (c.n_lds > (uint32_t)(kCandLds - 4 * kWave)) cand_write_out(ws, qslot, cl, c, lane);
+  if (c.n_lds > (uint32_t)(kCandLds - 4 * kWave)) cand_write_out(ws, qslot, cl, c, lane, false);
 }
 
 // Pass A, one group: the candidates among the four elements of every lane (bins glo and up;
@@ -259,7 +283,7 @@ __device__ __forceinline__ void stage_one_bin(const CandList& cl, uint32_t* sub2
 // (one-bin lists)}.  Returns the number of exact zeros (the same value in every lane).
 __device__ __forceinline__ uint32_t stage_finish(const Ws& ws, int64_t qslot, const CandList& cl, StageCounts& c,
                                                  int lane) {
-  cand_write_out(ws, qslot, cl, c, lane);
+  cand_write_out(ws, qslot, cl, c, lane, true);
   const uint32_t n_hi = wave_sum_u32(c.v_hi), nz = wave_sum_u32(c.v_nz);
   if (lane == 0) ws.qinfo[qslot] = make_uint4(n_hi, c.n_out, 0u, nz);
   return nz;
@@ -460,6 +484,12 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   }
 }
 
+#ifndef ACC_EFH_WAVES
+#define ACC_EFH_WAVES 0
+#endif
+#if ACC_EFH_WAVES
+__attribute__((amdgpu_waves_per_eu(ACC_EFH_WAVES, ACC_EFH_WAVES)))
+#endif
 __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const GradPtrs gp, int w0) {
   __shared__ uint32_t hist[kHistBins];
   __shared__ uint32_t cand_val[4][kCandLdsSlots];
@@ -542,9 +572,8 @@ struct QuarterHead {
 __device__ __forceinline__ QuarterHead load_quarter_head(const Ws& ws, int64_t qslot, int lane) {
   QuarterHead h;
   h.info = ws.qinfo[qslot];
-  const uint32_t* cv = ws.cand_val + qslot * kCandCap;
 #pragma unroll
-  for (int ch = 0; ch < kEagerChunks; ++ch) h.chunk[ch] = cv[ch * kWave + lane];
+  for (int ch = 0; ch < kEagerChunks; ++ch) h.chunk[ch] = ws.cand_val[cand_at(ws, qslot, (uint32_t)ch, lane)];
   return h;
 }
 
@@ -570,12 +599,12 @@ __device__ __forceinline__ uint32_t for_quarter_keys(const Ws& ws, const LayerDe
 #pragma unroll
     for (int ch = 0; ch < kEagerChunks; ++ch)
       if (n > (uint32_t)(ch * kWave)) visit(h.chunk[ch], (uint32_t)(ch * kWave + lane));   // uniform condition
-    const uint32_t* cv = ws.cand_val + qslot * kCandCap;
     constexpr int U = 4;
     for (uint32_t t0 = kEagerChunks * kWave; t0 < n; t0 += U * kWave) {
       uint32_t raw[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) raw[u] = cv[min(t0 + u * kWave + lane, (uint32_t)(kCandCap - 1))];
+      for (int u = 0; u < U; ++u)
+        raw[u] = ws.cand_val[cand_at(ws, qslot, min(t0 / kWave + u, (uint32_t)(kCandCap / kWave - 1)), lane)];
 #pragma unroll
       for (int u = 0; u < U; ++u)
         if (n > t0 + u * kWave) visit(raw[u], t0 + u * kWave + lane);                         // uniform condition
@@ -1646,12 +1675,12 @@ __device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& f
   // the first chunk of worker 0's list is requested before the sums are cleared
   constexpr int U = 2;                                      // 64-entry chunks requested together
   auto load_chunks = [&](int w, uint32_t t0, uint32_t (&v)[U], uint32_t (&ix)[U]) {
-    const int64_t base = ((int64_t)w * q_stride + qslot_local) * kCandCap;
+    const int64_t qslot = (int64_t)w * q_stride + qslot_local;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const uint32_t t = min(t0 + u * kWave + lane, (uint32_t)(kCandCap - 1));
-      v[u] = cand_val[base + t];
-      ix[u] = cand_idx[base + t];
+      const int64_t a = cand_at(ws, qslot, min(t0 / kWave + u, (uint32_t)(kCandCap / kWave - 1)), lane);
+      v[u] = cand_val[a];
+      ix[u] = cand_idx[a];
     }
   };
   uint32_t cv[U], ci[U];

@@ -665,6 +665,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   ws.bmono = cfg->method == ACC_BATCH ? cfg->batch_monotone : 0;
   ws.n_model = p.n_model;
   ws.q_stride = p.q_stride;
+  ws.n_qslots = p.q_stride * cfg->n_workers;
   ws.N = p.N;
   ws.W = cfg->n_workers;
   ws.L = cfg->n_layers;
