@@ -120,6 +120,20 @@ int32_t accordion_workspace_bytes(const acc_config* cfg, size_t* out_bytes);
 int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t workspace_bytes,
                        const float* q_init_host, void* hip_stream, acc_ctx** out);
 
+/* accordion_init for callers that cannot allocate device memory (code that runs under HIP graph
+ * capture, serving loops, harnesses that forbid hipMalloc): the workspace is an array of
+ * ACC_STATIC_WORKSPACE_BYTES bytes that lives inside the library's device code, one copy per GPU,
+ * held until the process ends.  No hipMalloc, hipFree or other allocating call is made; gradients and
+ * outputs are still the caller's.  The context belongs to the device that is current at the call.
+ * Errors: as accordion_init; ACC_ENOSPACE when the configuration needs a larger workspace than the
+ * array (accordion_workspace_bytes tells; use accordion_init then).
+ * Every context created this way on one GPU uses the same array: the call clears it and lays it
+ * out anew, so the context created last is the only usable one -- calls on an earlier one return
+ * ACC_ESTATE (accordion_destroy still works) -- and two threads must not use such contexts on one
+ * GPU at the same time: their work would race on the array. */
+#define ACC_STATIC_WORKSPACE_BYTES (32u << 20)
+int32_t accordion_init_static(const acc_config* cfg, const float* q_init_host, void* hip_stream, acc_ctx** out);
+
 /* Enqueue all later work of this context on another HIP stream (NULL = the default stream).
  * Only between steps (else ACC_ESTATE).  The library does not order the two streams: the caller
  * makes the new stream wait for what the old one still has in flight.

@@ -48,7 +48,7 @@ class AccordionError(RuntimeError):
 _lib = None
 
 EXPORTS = [
-    "accordion_workspace_bytes", "accordion_init", "accordion_destroy", "accordion_last_error",
+    "accordion_workspace_bytes", "accordion_init", "accordion_init_static", "accordion_destroy", "accordion_last_error",
     "accordion_compress_step", "accordion_aggregate", "accordion_decompress", "accordion_step_all",
     "accordion_decompress_update", "accordion_step_all_update", "accordion_batch_status", "accordion_set_stream", "accordion_topk_overlap", "accordion_payload_format",
     "accordion_detect_regime", "accordion_reset_accumulator", "accordion_get_levels",
@@ -77,6 +77,7 @@ def load_library() -> C.CDLL:
     sig = {
         "accordion_workspace_bytes": [C.POINTER(acc_config), C.POINTER(C.c_size_t)],
         "accordion_init": [C.POINTER(acc_config), vp, C.c_size_t, vp, vp, C.POINTER(vp)],
+        "accordion_init_static": [C.POINTER(acc_config), vp, vp, C.POINTER(vp)],
         "accordion_destroy": [vp],
         "accordion_compress_step": [vp, i32, vp, i32],
         "accordion_aggregate": [vp, i32],
@@ -192,7 +193,10 @@ class Accordion:
     def __init__(self, method: int, layers: Sequence, n_workers: int, level_crit: int,
                  level_noncrit: int, k_den: int = 100, eta: float = 0.5, initial_level: int = 1,
                  q_init: Optional[np.ndarray] = None, device: str = "cuda:0",
-                 batch_multiplier: int = 1, batch_monotone: int = 1, detector: int = 0):
+                 batch_multiplier: int = 1, batch_monotone: int = 1, detector: int = 0,
+                 static_workspace: bool = False):
+        """static_workspace: create the context with accordion_init_static (the library's own
+        static device array is the workspace; nothing is allocated for it here)."""
         import torch  # device memory and the stream handle only
 
         self._lib = load_library()
@@ -206,10 +210,12 @@ class Accordion:
                        for l in layers]
         self.device = torch.device(device)
         nbytes = accordion_workspace_bytes(self.cfg)
-        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
-        base = self.workspace.data_ptr()
-        self._ws_ptr = (base + 255) // 256 * 256
         self.workspace_bytes = nbytes
+        self.workspace = None
+        if not static_workspace:
+            self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+            base = self.workspace.data_ptr()
+            self._ws_ptr = (base + 255) // 256 * 256
         with torch.cuda.device(self.device):
             self.stream = torch.cuda.current_stream().cuda_stream
         qptr = None
@@ -218,8 +224,12 @@ class Accordion:
             self._q_keep = q
             qptr = q.ctypes.data_as(C.c_void_p)
         ctx = C.c_void_p(None)
-        rc = self._lib.accordion_init(C.byref(self.cfg), C.c_void_p(self._ws_ptr), nbytes, qptr,
-                                      C.c_void_p(self.stream), C.byref(ctx))
+        if static_workspace:
+            with torch.cuda.device(self.device):
+                rc = self._lib.accordion_init_static(C.byref(self.cfg), qptr, C.c_void_p(self.stream), C.byref(ctx))
+        else:
+            rc = self._lib.accordion_init(C.byref(self.cfg), C.c_void_p(self._ws_ptr), nbytes, qptr,
+                                          C.c_void_p(self.stream), C.byref(ctx))
         _check(self._lib, None, rc)
         self.ctx = ctx
 

@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -271,6 +272,22 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(float4* __restrict__ ds
   }
 }
 
+// ---- the workspace of callers that cannot allocate (accordion_init_static) ----------------------
+// One array per GPU (every device that loads the library holds its own copy until the process
+// ends).  Host code never uses the array's name as an address: the device address is taken once
+// per device with hipGetSymbolAddress, that device being current, and kept.
+static __device__ __align__(256) unsigned char scratch[ACC_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticSlot {
+  void* ptr = nullptr;         // device address of `scratch` on this device
+  acc_ctx* owner = nullptr;    // the context that uses it now (the last one created on it)
+};
+StaticSlot g_static[kMaxDevices];
+std::mutex g_static_mutex;
+}  // namespace
+
 enum Stage {
   ST_psgd_ef_p_kernel = 0, ST_psgd_orth_kernel, ST_psgd_q_kernel, ST_psgd_qmean_kernel,
   ST_psgd_decomp_kernel, ST_psgd_residual_kernel, ST_topk_ef_hist_kernel, ST_topk_pick12_kernel,
@@ -312,6 +329,7 @@ struct acc_ctx {
   Ws ws;
   char* base = nullptr;
   hipStream_t stream = nullptr;
+  int static_dev = -1;             // >= 0: the workspace is the library's static array of that device
   // step state machine
   bool in_step = false;
   uint32_t step_id = 2;            // number of the current step (the device keeps 0 for "never")
@@ -347,6 +365,22 @@ int check_launch(acc_ctx* c, const char* what) {
   }
   return ACC_OK;
 }
+
+// A context on the library's static workspace is usable only while it is the last one created on
+// that device's array (a later accordion_init_static cleared and re-planned the memory).
+int check_owner(acc_ctx* c) {
+  if (c->static_dev < 0) return ACC_OK;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (g_static[c->static_dev].owner == c) return ACC_OK;
+  return fail(c->err, ACC_ESTATE, "the static workspace of this context was taken over by a later accordion_init_static");
+}
+
+#define ACC_USABLE(c)                          \
+  do {                                         \
+    if (!(c)) return ACC_EINVAL;               \
+    const int rc_owner_ = check_owner(c);      \
+    if (rc_owner_ != ACC_OK) return rc_owner_; \
+  } while (0)
 
 // Fold the finished event pairs into the per-stage totals (synchronises the stream).
 int drain_profile(acc_ctx* c) {
@@ -577,8 +611,8 @@ int32_t accordion_workspace_bytes(const acc_config* cfg, size_t* out_bytes) {
   return ACC_OK;
 }
 
-int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t workspace_bytes,
-                       const float* q_init_host, void* hip_stream, acc_ctx** out) {
+static int32_t init_common(const acc_config* cfg, void* workspace_dev, size_t workspace_bytes,
+                           const float* q_init_host, void* hip_stream, acc_ctx** out, const char* too_small) {
   if (!out) return fail(g_init_error, ACC_EINVAL, "out is NULL");
   *out = nullptr;
   acc_ctx* c = new (std::nothrow) acc_ctx();
@@ -593,7 +627,7 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   if (rc != ACC_OK) { delete c; return rc; }
   if (!workspace_dev) return bail(ACC_EINVAL, "workspace is NULL");
   if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255u) != 0) return bail(ACC_EINVAL, "workspace is not 256-byte aligned");
-  if (workspace_bytes < (size_t)c->plan.total_bytes) return bail(ACC_ENOSPACE, "workspace too small");
+  if (workspace_bytes < (size_t)c->plan.total_bytes) return bail(ACC_ENOSPACE, too_small);
   if (cfg->method == ACC_POWERSGD && c->plan.q_total > 0 && !q_init_host)
     return bail(ACC_EINVAL, "q_init_host is NULL");
   c->cfg = *cfg;
@@ -716,8 +750,43 @@ int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t worksp
   return ACC_OK;
 }
 
+int32_t accordion_init(const acc_config* cfg, void* workspace_dev, size_t workspace_bytes,
+                       const float* q_init_host, void* hip_stream, acc_ctx** out) {
+  return init_common(cfg, workspace_dev, workspace_bytes, q_init_host, hip_stream, out, "workspace too small");
+}
+
+int32_t accordion_init_static(const acc_config* cfg, const float* q_init_host, void* hip_stream, acc_ctx** out) {
+  if (!out) return fail(g_init_error, ACC_EINVAL, "out is NULL");
+  *out = nullptr;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(g_init_error, ACC_EHIP, "hipGetDevice failed (or a device number beyond the library's table)");
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticSlot& slot = g_static[dev];
+  if (!slot.ptr) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      std::snprintf(g_init_error, 256, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+      return ACC_EHIP;
+    }
+    slot.ptr = p;
+  }
+  const int32_t rc = init_common(cfg, slot.ptr, (size_t)ACC_STATIC_WORKSPACE_BYTES, q_init_host, hip_stream, out,
+                                 "configuration needs more than ACC_STATIC_WORKSPACE_BYTES of workspace: "
+                                 "use accordion_init with a caller-owned workspace");
+  if (rc != ACC_OK) return rc;
+  (*out)->static_dev = dev;
+  slot.owner = *out;                                       // an earlier context on this array is now stale
+  return ACC_OK;
+}
+
 int32_t accordion_destroy(acc_ctx* ctx) {
   if (!ctx) return ACC_EINVAL;
+  if (ctx->static_dev >= 0) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (g_static[ctx->static_dev].owner == ctx) g_static[ctx->static_dev].owner = nullptr;
+  }
   (void)drain_profile(ctx);
   for (EventPair& p : ctx->spare) {
     (void)hipEventDestroy(p.a);
@@ -730,7 +799,7 @@ int32_t accordion_destroy(acc_ctx* ctx) {
 const char* accordion_last_error(const acc_ctx* ctx) { return ctx ? ctx->err : g_init_error; }
 
 int32_t accordion_compress_step(acc_ctx* c, int32_t worker, const float* grad_dev, int32_t phase) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->cfg.method == ACC_BATCH) return fail(c->err, ACC_EINVAL, kBatchCallByCall);
   if (worker < 0 || worker >= c->cfg.n_workers) return fail(c->err, ACC_EINVAL, "worker out of range");
   const uint32_t bit = 1u << worker;
@@ -759,7 +828,7 @@ int32_t accordion_compress_step(acc_ctx* c, int32_t worker, const float* grad_de
 }
 
 int32_t accordion_aggregate(acc_ctx* c, int32_t phase) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->cfg.method == ACC_BATCH) return fail(c->err, ACC_EINVAL, kBatchCallByCall);
   if (phase == 0) {
     if (c->agg0) return fail(c->err, ACC_ESTATE, "aggregate(0) already done");
@@ -792,7 +861,7 @@ static int32_t decompress_into(acc_ctx* c, const Sink& sink) {
 }
 
 int32_t accordion_decompress(acc_ctx* c, float* out_dev) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (!out_dev) return fail(c->err, ACC_EINVAL, "out_dev is NULL");
   if (misaligned(out_dev)) return fail(c->err, ACC_EINVAL, "out_dev is not 16-byte aligned");
   return decompress_into(c, sink_out(out_dev));
@@ -800,7 +869,7 @@ int32_t accordion_decompress(acc_ctx* c, float* out_dev) {
 
 int32_t accordion_decompress_update(acc_ctx* c, float* weights_dev, float* velocity_dev, float lr,
                                     float momentum, float weight_decay) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   const int rc = check_sgd(c, weights_dev, velocity_dev, lr, momentum, weight_decay);
   if (rc != ACC_OK) return rc;
   return decompress_into(c, Sink{nullptr, weights_dev, velocity_dev, lr, momentum, weight_decay, stream_wv(c)});
@@ -835,7 +904,7 @@ static int32_t step_all_into(acc_ctx* c, const float* const* grads_host_array, c
 }
 
 int32_t accordion_step_all(acc_ctx* c, const float* const* grads_host_array, float* out_dev) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (!out_dev) return fail(c->err, ACC_EINVAL, "out_dev is NULL");
   if (misaligned(out_dev)) return fail(c->err, ACC_EINVAL, "out_dev is not 16-byte aligned");
   return step_all_into(c, grads_host_array, sink_out(out_dev));
@@ -843,14 +912,14 @@ int32_t accordion_step_all(acc_ctx* c, const float* const* grads_host_array, flo
 
 int32_t accordion_step_all_update(acc_ctx* c, const float* const* grads_host_array, float* weights_dev,
                                   float* velocity_dev, float lr, float momentum, float weight_decay) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   const int rc = check_sgd(c, weights_dev, velocity_dev, lr, momentum, weight_decay);
   if (rc != ACC_OK) return rc;
   return step_all_into(c, grads_host_array, Sink{nullptr, weights_dev, velocity_dev, lr, momentum, weight_decay, stream_wv(c)});
 }
 
 int32_t accordion_set_stream(acc_ctx* c, void* hip_stream) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->in_step) return fail(c->err, ACC_ESTATE, "set_stream inside a step");
   const int rc = drain_profile(c);                           // pending timing events belong to the old stream
   if (rc != ACC_OK) return rc;
@@ -859,7 +928,7 @@ int32_t accordion_set_stream(acc_ctx* c, void* hip_stream) {
 }
 
 int32_t accordion_detect_regime(acc_ctx* c, float lr_curr, float lr_next) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->in_step) return fail(c->err, ACC_ESTATE, "detect_regime inside a step");
   const Ws& ws = c->ws;
   ACC_LAUNCH(c, norm_partial_kernel, dim3(ws.n_ftiles), dim3(256), ws);
@@ -874,20 +943,20 @@ int32_t accordion_detect_regime(acc_ctx* c, float lr_curr, float lr_next) {
 }
 
 int32_t accordion_flush(acc_ctx* c) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->in_step) return fail(c->err, ACC_ESTATE, "flush inside a step");
   return materialise(c);
 }
 
 int32_t accordion_reset_accumulator(acc_ctx* c) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->in_step) return fail(c->err, ACC_ESTATE, "reset_accumulator inside a step");
   ACC_LAUNCH(c, zero_accum_kernel, dim3(c->ws.n_ftiles), dim3(256), c->ws);
   return ACC_OK;
 }
 
 int32_t accordion_get_levels(acc_ctx* c, int32_t* levels_host) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (!levels_host) return fail(c->err, ACC_EINVAL, "levels_host is NULL");
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   ACC_HIP(c, hipMemcpy(levels_host, c->ws.level, 4 * (size_t)c->cfg.n_layers, hipMemcpyDeviceToHost));
@@ -895,7 +964,7 @@ int32_t accordion_get_levels(acc_ctx* c, int32_t* levels_host) {
 }
 
 int32_t accordion_get_norms(acc_ctx* c, float* old_host, float* curr_host) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (!old_host || !curr_host) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   ACC_HIP(c, hipMemcpy(old_host, c->ws.norm_prev, 4 * (size_t)c->cfg.n_layers, hipMemcpyDeviceToHost));
@@ -905,7 +974,7 @@ int32_t accordion_get_norms(acc_ctx* c, float* old_host, float* curr_host) {
 
 int32_t accordion_get_payload(acc_ctx* c, int32_t worker, int32_t layer, int32_t* idx_host,
                               float* val_host, int64_t capacity, int64_t* count_out) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->cfg.method != ACC_TOPK) return fail(c->err, ACC_EINVAL, "payloads exist for TopK only");
   if (worker < 0 || worker >= c->cfg.n_workers) return fail(c->err, ACC_EINVAL, "worker out of range");
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(c->err, ACC_EINVAL, "layer out of range");
@@ -961,7 +1030,7 @@ int32_t accordion_payload_format(const acc_config* cfg, int32_t layer, int32_t l
 }
 
 int32_t accordion_get_factors(acc_ctx* c, int32_t layer, float* p_hat_host, float* q_host, int32_t* rank_out) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->cfg.method != ACC_POWERSGD) return fail(c->err, ACC_EINVAL, "factors exist for PowerSGD only");
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(c->err, ACC_EINVAL, "layer out of range");
   const LayerDev& L = c->plan.layers[layer];
@@ -984,7 +1053,7 @@ int32_t accordion_get_factors(acc_ctx* c, int32_t layer, float* p_hat_host, floa
 }
 
 int32_t accordion_payload_words(acc_ctx* c, int64_t* last_step, int64_t* cumulative) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (!last_step || !cumulative) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   unsigned long long w[3] = {0, 0, 0};
@@ -995,7 +1064,7 @@ int32_t accordion_payload_words(acc_ctx* c, int64_t* last_step, int64_t* cumulat
 }
 
 int32_t accordion_topk_stats(acc_ctx* c, int64_t* restaged_layers, int64_t* swept_layers) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->cfg.method != ACC_TOPK) return fail(c->err, ACC_EINVAL, "TopK statistics exist for TopK only");
   if (!restaged_layers || !swept_layers) return fail(c->err, ACC_EINVAL, "host pointer is NULL");
   ACC_HIP(c, hipStreamSynchronize(c->stream));
@@ -1008,7 +1077,7 @@ int32_t accordion_topk_stats(acc_ctx* c, int64_t* restaged_layers, int64_t* swep
 
 int32_t accordion_topk_overlap(acc_ctx* c, int32_t worker_a, int32_t worker_b, int64_t* common_host,
                                int64_t* kept_host) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->cfg.method != ACC_TOPK) return fail(c->err, ACC_EINVAL, "overlaps exist for TopK only");
   if (worker_a < 0 || worker_a >= c->cfg.n_workers || worker_b < 0 || worker_b >= c->cfg.n_workers)
     return fail(c->err, ACC_EINVAL, "worker out of range");
@@ -1033,7 +1102,7 @@ int32_t accordion_topk_overlap(acc_ctx* c, int32_t worker_a, int32_t worker_b, i
 
 int32_t accordion_batch_status(acc_ctx* c, int32_t* level, int32_t* pending_micro_steps,
                                int32_t* last_batch_micro_steps, int64_t* exchanges, int64_t* micro_steps) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (c->cfg.method != ACC_BATCH) return fail(c->err, ACC_EINVAL, "batch status exists for the batch-size mode only");
   if (!level || !pending_micro_steps || !last_batch_micro_steps || !exchanges || !micro_steps)
     return fail(c->err, ACC_EINVAL, "host pointer is NULL");
@@ -1082,7 +1151,7 @@ static int32_t state_copy(acc_ctx* c, char* host, bool to_host) {
 }
 
 int32_t accordion_get_state(acc_ctx* c, void* state_host, size_t bytes) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (!state_host) return fail(c->err, ACC_EINVAL, "state_host is NULL");
   if (c->in_step) return fail(c->err, ACC_ESTATE, "get_state inside a step");
   if (bytes < state_bytes_of(c)) return fail(c->err, ACC_ENOSPACE, "state buffer too small");
@@ -1093,7 +1162,7 @@ int32_t accordion_get_state(acc_ctx* c, void* state_host, size_t bytes) {
 }
 
 int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
-  if (!c) return ACC_EINVAL;
+  ACC_USABLE(c);
   if (!state_host) return fail(c->err, ACC_EINVAL, "state_host is NULL");
   if (c->in_step) return fail(c->err, ACC_ESTATE, "set_state inside a step");
   if (bytes < state_bytes_of(c)) return fail(c->err, ACC_ENOSPACE, "state buffer too small");
