@@ -1,7 +1,8 @@
 """GPU parity at the full sizes of the benchmark configurations, through the same entry point
 (accordion_step_all) and launch configuration that bench.py times.  The oracle is fast enough
 to check every output element of the ResNet-18 and VGG-19 sets; for the LSTM set it checks two
-of the sixteen workers' worth of data (W = 2), every layer, every element."""
+of the sixteen workers' worth of data (W = 2), every layer, every element, and the full W = 16
+through properties that pin the result completely."""
 import numpy as np
 import pytest
 
@@ -22,7 +23,8 @@ def _set_levels(gpu, ora, value):
 def test_resnet18_topk_both_levels():
     print("case resnet18_topk full size", flush=True)
     w = wl.workload("resnet18_topk")
-    W = 2
+    W = w.n_workers                                         # 4: the configuration bench.py times
+    assert W == 4
     gpu, ora = H.make_pair(B.ACC_TOPK, w.layers, W, w.level_crit, w.level_noncrit, w.k_den)
     for step in range(2):                                   # K = 10 %; the second step takes the deferred route
         _check_step(gpu, ora, [wl.gradient(w, k, step) for k in range(W)], f"K10 step {step}",
@@ -118,14 +120,68 @@ def test_lstm_topk_two_workers_dense_tie_class():
     gpu.destroy()
 
 
+def _lstm_gradients(w, W, step, window=0):
+    """W seeded gradients of one step, generated several at a time (each takes seconds)."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        return list(ex.map(lambda k: wl.gradient(w, k, step, window), range(W)))
+
+
+def _check_topk_step_by_properties(gpu, lt, W, num, den, deltas, out, tag):
+    """One TopK step checked through properties that pin the result completely, for sizes where the
+    oracle would take minutes.  deltas: W device tensors, gradient + memory of every worker before
+    the step (fp32).  Per worker and layer: k = max(1, ceil(n num / den)) entries are kept, indices
+    ascending; kept values + residual give back delta bit for bit (compressed + residual =
+    gradient + old residual); no dropped entry is larger in magnitude than a kept one, and among
+    the entries equal to the smallest kept magnitude the kept ones have the lowest indices; the
+    averaged output is the fp32 sum of the kept values in worker order, from +0, divided by W.
+    Returns the memory after the step (host tensor W x N, from accordion_get_state)."""
+    import torch
+    N = gpu.n_params
+    acc = torch.zeros(N, dtype=torch.float32, device="cuda:0")
+    e_all = torch.from_numpy(gpu.unpack_state(gpu.get_state())["e"].copy())   # host, W x N
+    for k in range(W):
+        e_w = e_all[k].to("cuda:0")
+        recon = e_w.clone()
+        dense = torch.zeros(N, dtype=torch.float32, device="cuda:0")
+        for li, (off, rows, cols, _) in enumerate(lt):
+            n = rows * cols
+            kk = max(1, -((-n * num) // den))
+            idx, val = gpu.get_payload(k, li)
+            assert idx.size == kk and np.all(np.diff(idx) > 0) and idx[0] >= 0 and idx[-1] < n, (tag, k, li)
+            ti = torch.from_numpy(idx.astype(np.int64)).to("cuda:0") + off
+            tv = torch.from_numpy(val).to("cuda:0")
+            assert bool(torch.all(e_w[ti] == 0)), (tag, k, li)   # kept entries left the memory
+            recon[ti] = tv
+            dense[ti] = tv
+            layer_e = e_w[off:off + n].abs()
+            t_min = tv.abs().min()
+            assert bool(layer_e.max() <= t_min), (tag, k, li)
+            # ties at the smallest kept magnitude: lower index wins
+            kept_tie = ti[tv.abs() == t_min]
+            drop_tie = torch.nonzero(layer_e == t_min).flatten() + off
+            if t_min > 0 and drop_tie.numel():
+                assert int(kept_tie.max()) < int(drop_tie.min()), (tag, k, li)
+            if t_min == 0:                                       # zeros: every non-zero is kept, then index order
+                assert int(torch.count_nonzero(layer_e)) == 0
+                zero_kept = ti[tv == 0]
+                zero_all = torch.nonzero(deltas[k][off:off + n] == 0).flatten() + off
+                if zero_kept.numel() and zero_all.numel() > zero_kept.numel():
+                    assert int(zero_kept.max()) == int(zero_all[zero_kept.numel() - 1]), (tag, k, li)
+        assert torch.equal(recon.view(torch.int32), deltas[k].view(torch.int32)), f"{tag}: worker {k}: invariant"
+        acc = acc + dense                                        # worker order, from +0
+        del e_w, recon, dense
+    ref = acc / float(W)
+    assert torch.equal(out.view(torch.int32), ref.view(torch.int32)), f"{tag}: mean"
+    return e_all
+
+
 def test_lstm_topk_sixteen_workers_by_properties():
-    """The LSTM set in the configuration bench.py times (W = 16, K = 10 %), where the oracle
-    would take minutes: one step from an empty memory is checked through properties that pin
-    the result completely.  Per worker and layer: k entries are kept; kept values + residual
-    give back the gradient bit for bit (compressed + residual = gradient + old residual); no
-    dropped entry is larger in magnitude than a kept one, and among the entries equal to the
-    smallest kept magnitude the kept ones have the lowest indices; the averaged output is the
-    fp32 sum of the kept values in worker order divided by W."""
+    """The LSTM set in the configuration bench.py times (W = 16, K = 10 %).  Step 0 from an empty
+    memory and step 1 with the memory fed back are checked through complete properties (see
+    _check_topk_step_by_properties).  A twin context runs the same two steps without anybody
+    looking at its state in between, so that its second step forms the residual of the first on
+    the fly (the route the benchmark takes); it must give the same bits."""
     import torch
     print("case lstm_topk W=16 properties", flush=True)
     w = wl.workload("lstm_topk")
@@ -133,44 +189,67 @@ def test_lstm_topk_sixteen_workers_by_properties():
     assert W == 16
     lt = H.layer_tuples(w.layers)
     gpu = B.Accordion(B.ACC_TOPK, lt, W, w.level_crit, w.level_noncrit, w.k_den)
+    twin = B.Accordion(B.ACC_TOPK, lt, W, w.level_crit, w.level_noncrit, w.k_den)
     N = gpu.n_params
-    grads = [H.to_dev(wl.gradient(w, k, 0)) for k in range(W)]
+    out, out_twin = H.dev_out(N), H.dev_out(N)
+    e_prev = None
+    for step in range(2):
+        print(f"  step {step}", flush=True)
+        grads = [H.to_dev(g) for g in _lstm_gradients(w, W, step)]
+        deltas = grads if e_prev is None else [grads[k] + e_prev[k].to("cuda:0") for k in range(W)]
+        gpu.step_all(grads, out)
+        twin.step_all(grads, out_twin)
+        torch.cuda.synchronize()
+        e_prev = _check_topk_step_by_properties(gpu, lt, W, w.level_crit, w.k_den, deltas, out, f"step {step}")
+        assert torch.equal(out.view(torch.int32), out_twin.view(torch.int32)), f"step {step}: twin"
+        del grads, deltas
+    for k in (0, 7, 15):
+        for li in range(len(lt)):
+            ia, va = gpu.get_payload(k, li)
+            ib, vb = twin.get_payload(k, li)
+            assert np.array_equal(ia, ib) and np.array_equal(va.view(np.uint32), vb.view(np.uint32)), (k, li)
+    e_twin = twin.unpack_state(twin.get_state())["e"]
+    assert np.array_equal(e_twin.view(np.uint32), e_prev.numpy().view(np.uint32)), "twin memory"
+    twin.destroy()
+    gpu.destroy()
+
+
+def test_lstm_topk_levels_decided_on_the_device_end_at_k_one_percent():
+    """The LSTM configuration end to end at W = 16 with the level of every layer decided by
+    accordion_detect_regime: three windows (shortened to one step each) whose gradient scale goes
+    1.00, 0.40, 0.38, so that Algorithm 1 says critical (no history), critical (ratio 0.60),
+    not critical (ratio 0.05); K = 10 % runs in windows 1 to 3 and K = 1 % from the fourth, two
+    steps of which are checked through complete properties, with the memory of all the steps
+    before fed back."""
+    import torch
+    print("case lstm_topk W=16 device-decided levels", flush=True)
+    w = wl.workload("lstm_topk")
+    W = w.n_workers
+    lt = H.layer_tuples(w.layers)
+    gpu = B.Accordion(B.ACC_TOPK, lt, W, w.level_crit, w.level_noncrit, w.k_den)
+    N = gpu.n_params
     out = H.dev_out(N)
-    gpu.step_all(grads, out)
-    torch.cuda.synchronize()
-    acc = torch.zeros(N, dtype=torch.float32, device="cuda:0")
-    e_all = torch.from_numpy(gpu.unpack_state(gpu.get_state())["e"])   # host, W x N
-    for k in range(W):
-        e_w = e_all[k].to("cuda:0")
-        recon = e_w.clone()
-        dense = torch.zeros(N, dtype=torch.float32, device="cuda:0")
-        for li, (off, rows, cols, _) in enumerate(lt):
-            n = rows * cols
-            kk = max(1, -((-n * w.level_crit) // w.k_den))
-            idx, val = gpu.get_payload(k, li)
-            assert idx.size == kk and np.all(np.diff(idx) > 0) and idx[0] >= 0 and idx[-1] < n
-            ti = torch.from_numpy(idx.astype(np.int64)).to("cuda:0") + off
-            tv = torch.from_numpy(val).to("cuda:0")
-            assert bool(torch.all(e_w[ti] == 0))                 # kept entries left the memory
-            recon[ti] = tv
-            dense[ti] = tv
-            layer_e = e_w[off:off + n].abs()
-            t_min = tv.abs().min()
-            assert bool(layer_e.max() <= t_min), (k, li)
-            # ties at the smallest kept magnitude: lower index wins
-            kept_tie = ti[tv.abs() == t_min]
-            drop_tie = torch.nonzero(layer_e == t_min).flatten() + off
-            if t_min > 0 and drop_tie.numel():
-                assert int(kept_tie.max()) < int(drop_tie.min()), (k, li)
-            if t_min == 0:                                       # zeros: every non-zero is kept, then index order
-                assert int(torch.count_nonzero(layer_e)) == 0
-                zero_kept = ti[tv == 0]
-                zero_drop = torch.nonzero(grads[k][off:off + n] == 0).flatten() + off
-                if zero_kept.numel() and zero_drop.numel() > zero_kept.numel():
-                    assert int(zero_kept.max()) == int(zero_drop[zero_kept.numel() - 1])
-        assert torch.equal(recon.view(torch.int32), grads[k].view(torch.int32)), f"worker {k}: invariant"
-        acc = acc + dense                                        # worker order, from +0
-        del e_w, recon, dense
-    ref = acc / float(W)
-    assert torch.equal(out.view(torch.int32), ref.view(torch.int32)), "mean"
+    expected = [1, 1, 0]
+    norms = []
+    for window in range(3):
+        print(f"  window {window}", flush=True)
+        grads = [H.to_dev(g) for g in _lstm_gradients(w, W, window, window)]
+        assert np.all(gpu.get_levels() == 1)                    # K = 10 % in windows 1 to 3
+        gpu.step_all(grads, out)
+        gpu.detect_regime(0.1, 0.1)
+        assert np.all(gpu.get_levels() == expected[window]), f"window {window}"
+        norms.append(gpu.get_norms()[1].copy())
+        del grads
+    assert np.allclose(norms[1] / norms[0], 0.40, rtol=0.02) and np.allclose(norms[2] / norms[1], 0.95, rtol=0.02)
+    words_k10 = gpu.payload_words()[0]
+    e_prev = torch.from_numpy(gpu.unpack_state(gpu.get_state())["e"].copy())
+    for step in (3, 4):
+        print(f"  step {step} at K = 1 %", flush=True)
+        grads = [H.to_dev(g) for g in _lstm_gradients(w, W, step, 2)]
+        deltas = [grads[k] + e_prev[k].to("cuda:0") for k in range(W)]
+        gpu.step_all(grads, out)
+        torch.cuda.synchronize()
+        e_prev = _check_topk_step_by_properties(gpu, lt, W, w.level_noncrit, w.k_den, deltas, out, f"step {step}")
+        del grads, deltas
+    assert gpu.payload_words()[0] == 2 * 512658 and words_k10 == 2 * 5126556
     gpu.destroy()
