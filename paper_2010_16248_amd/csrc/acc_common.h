@@ -13,10 +13,8 @@ constexpr int kT2Group = 16;             // TopK: consecutive tiles of a layer t
 constexpr int kQuadIters = (kTile / 4 + 1 + kFlatThreads - 1) / kFlatThreads;  // 9
 constexpr int kMatRows = 64;             // matrix tile: 64 rows x 256 columns
 constexpr int kMatCols = 256;
-#ifndef ACC_Q_ROWS
-#define ACC_Q_ROWS 128
-#endif
-constexpr int kQRows = ACC_Q_ROWS;       // rows of a tile of the right product Q = Delta^T P^ (a multiple of 4)
+constexpr int kQRows = 128;              // rows of a tile of the right product Q = Delta^T P^ (64: 5 us slower on
+                                         // ResNet-18 shapes, twice the partial sums; 256: too few workgroups at W = 1)
 constexpr int kHistBins = 2048;          // 11 key bits per radix level
 // a wave quarter has at most ceil((kTile / 4 + 1) / 4) 16-byte groups: iterations of 64 lanes
 constexpr int kSpanIters = ((kTile / 4 + 1 + 3) / 4 + kWave - 1) / kWave;   // 9

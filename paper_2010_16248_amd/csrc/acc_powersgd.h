@@ -389,9 +389,6 @@ __global__ __launch_bounds__(kOrthThreads) void psgd_orth_kernel(const Ws ws, co
 
 // Tile: kQRows rows x 256 columns, one workgroup of 4 waves; a wave owns rows wave, wave + 4, ...
 // and keeps the sums of its four columns per lane in registers; the four waves' sums meet in LDS.
-#ifndef ACC_Q_B
-#define ACC_Q_B 4
-#endif
 template <int R, bool V4>
 __device__ void q_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const float* __restrict__ e,
                        double* __restrict__ qpart, double (*red)[16][64], float (*ps)[kMaxRank]) {
@@ -412,7 +409,7 @@ __device__ void q_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const 
 #pragma unroll
     for (int k = 0; k < R; ++k) acc[v][k] = 0.0;
   const int row_end = min(t.row0 + kQRows, L.rows);
-  constexpr int B = ACC_Q_B;   // rows in flight per wave
+  constexpr int B = 4;   // rows in flight per wave (2 and 8 are no faster)
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float d[B][4];
 #pragma unroll

@@ -197,13 +197,13 @@ __device__ __forceinline__ void cand_write_out(const Ws& ws, int64_t qslot, cons
   const uint32_t n_full = final ? c.n_lds : (c.n_lds & ~(uint32_t)(kWave - 1));
   for (uint32_t t0 = 0u; t0 < n_full; t0 += kWave) {
     const uint32_t t = t0 + lane, chunk = (c.n_out + t0) >> 6;
-#ifndef ACC_EXP_NO_CAND_STORE
     if (t < n_full && chunk < (uint32_t)(kCandCap / kWave)) {
+      // plain stores: the counting kernel and the compaction read the lists within microseconds
+      // (streaming stores here cost the compaction 6 us on ResNet-18 shapes)
       const int64_t a = cand_at(ws, qslot, chunk, lane);
       ws.cand_val[a] = cl.val[t];
       ws.cand_idx[a] = cl.idx[t];
     }
-#endif
   }
   const uint32_t rest = c.n_lds - n_full;                   // < 64 unless final (then 0)
   uint32_t rv = 0u;
@@ -484,12 +484,6 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   }
 }
 
-#ifndef ACC_EFH_WAVES
-#define ACC_EFH_WAVES 0
-#endif
-#if ACC_EFH_WAVES
-__attribute__((amdgpu_waves_per_eu(ACC_EFH_WAVES, ACC_EFH_WAVES)))
-#endif
 __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const GradPtrs gp, int w0) {
   __shared__ uint32_t hist[kHistBins];
   __shared__ uint32_t cand_val[4][kCandLdsSlots];
@@ -563,7 +557,7 @@ __device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile
 // counts (the slot always exists; what lies past the count is ignored later), the rest once the
 // count is there and only if it reaches them: a quarter lists 40 to 350 candidates on Gaussian or
 // Laplacian gradients at K = 1 % to 10 %.
-constexpr int kEagerChunks = 4;
+constexpr int kEagerChunks = 8;
 struct QuarterHead {
   uint4 info;                      // see stage_finish
   uint32_t chunk[kEagerChunks];    // the calling lane's entries of the first chunks
@@ -1648,6 +1642,7 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
 // instruction write consecutive words) and adds the values into the quarter's dense sums in
 // LDS, workers in order from +0; the sums, divided by W, go out as the quarter's part of the
 // averaged gradient.  acc: the wave's kQuarterFloats floats of LDS.
+constexpr int kGatherChunks = 4;                            // 64-entry chunks of a candidate list requested together (2 to 8: within 2 us)
 constexpr int kQuarterGroups = (kTile / 4 + 1 + 3) / 4;     // 513: 16-byte groups of a wave quarter at most
 constexpr int kQuarterFloats = 4 * kQuarterGroups + 12;     // rounded up to whole 64-byte rows
 
@@ -1672,9 +1667,12 @@ __device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& f
     mine = load_quarter_sel(ws, lane, ft.layer, qslot_local);
     n_mine = min(ws.qinfo[(int64_t)lane * q_stride + qslot_local].y, (uint32_t)kCandCap);
   }
-  // the first chunk of worker 0's list is requested before the sums are cleared
-  constexpr int U = 2;                                      // 64-entry chunks requested together
-  auto load_chunks = [&](int w, uint32_t t0, uint32_t (&v)[U], uint32_t (&ix)[U]) {
+  // A batch = up to kGatherChunks 64-entry chunks of one worker's list, requested together; the next
+  // batch (the rest of this worker's list, else the head of the next worker's) is requested before
+  // the current one is processed, whether or not anybody will look at it, so that a batch has the
+  // processing of the one before it to arrive.
+  constexpr int U = kGatherChunks;
+  auto load_batch = [&](int w, uint32_t t0, uint32_t (&v)[U], uint32_t (&ix)[U]) {
     const int64_t qslot = (int64_t)w * q_stride + qslot_local;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -1684,7 +1682,7 @@ __device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& f
     }
   };
   uint32_t cv[U], ci[U];
-  load_chunks(0, 0u, cv, ci);
+  load_batch(0, 0u, cv, ci);
   float4* acc4 = reinterpret_cast<float4*>(acc);
   for (int g = lane; g < ng; g += kWave) acc4[g] = make_float4(0.f, 0.f, 0.f, 0.f);
   __builtin_amdgcn_wave_barrier();
@@ -1702,11 +1700,9 @@ __device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& f
     int32_t* __restrict__ pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
     float* __restrict__ pval = pay_val + (int64_t)w * pay_stride + pay_off;
     for (uint32_t t0 = 0u; t0 < n || t0 == 0u; t0 += U * kWave) {
-      // what the registers are loaded with next: the rest of this worker's list, else the head of
-      // the next worker's (requested whether or not anybody will look at it)
       uint32_t nv[U], ni[U];
       const bool more = t0 + U * kWave < n;
-      load_chunks(more ? w : min(w + 1, W - 1), more ? t0 + U * kWave : 0u, nv, ni);
+      load_batch(more ? w : min(w + 1, W - 1), more ? t0 + U * kWave : 0u, nv, ni);
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t t = t0 + u * kWave + lane;
