@@ -238,6 +238,29 @@ __device__ __forceinline__ uint64_t scalar_mask(uint64_t mask) {
 
 __device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
+// Folding sums of two values over the wave (gfx950 lane swaps): the result holds, in the lower 32
+// lanes (fold32) / the even rows of 16 lanes (fold16), the sum of a over the two halves that are
+// folded together, and in the upper 32 lanes / the odd rows the same sum of b.  All lanes active.
+typedef unsigned int u2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ double fold32_d(double a, double b) {
+  const u2v lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(a), (unsigned)__double2loint(b), false, false);
+  const u2v hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(a), (unsigned)__double2hiint(b), false, false);
+  return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+}
+__device__ __forceinline__ double fold16_d(double a, double b) {
+  const u2v lo = __builtin_amdgcn_permlane16_swap((unsigned)__double2loint(a), (unsigned)__double2loint(b), false, false);
+  const u2v hi = __builtin_amdgcn_permlane16_swap((unsigned)__double2hiint(a), (unsigned)__double2hiint(b), false, false);
+  return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+}
+// Sum over each row of 16 lanes, returned to all its lanes.
+__device__ __forceinline__ double row_sum_d(double v) {
+  v += dpp_d<0xB1>(v);
+  v += dpp_d<0x4E>(v);
+  v += dpp_d<0x141>(v);
+  v += dpp_d<0x140>(v);
+  return v;
+}
+
 // ---- masked 16-byte access on a flat buffer ---------------------------------------
 // base is a multiple of 4 (elements) and the buffer is 16-byte aligned; elements outside
 // [lo, hi) are neither read nor written.
