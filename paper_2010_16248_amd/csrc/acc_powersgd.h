@@ -118,9 +118,9 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
   constexpr int B = 2;   // rows in flight per wave (one row is as fast; more rows cost registers and occupancy)
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float gd[B][4], ed[B][4], ad[B][4];
-    double part[B][R];                                       // a row that does not exist contributes zeros
+    double part[R >= 3 ? 1 : B][R];                          // a row that does not exist contributes zeros
 #pragma unroll
-    for (int b = 0; b < B; ++b)
+    for (int b = 0; b < (R >= 3 ? 1 : B); ++b)
 #pragma unroll
       for (int k = 0; k < R; ++k) part[b][k] = 0.0;
 #pragma unroll
@@ -165,36 +165,39 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
           s = fma(dd[1], (double)q[1][k], s);
           s = fma(dd[2], (double)q[2][k], s);
           s = fma(dd[3], (double)q[3][k], s);
-          part[b][k] = s;
+          part[R >= 3 ? 0 : b][k] = s;
+        }
+        if constexpr (R >= 3) {
+          // Three or four values per row: folded row by row (as many instructions as folding both
+          // rows together, half the registers).  The lower 32 lanes end with columns 0 and 1 of
+          // P (even / odd rows of 16 lanes), the upper 32 with columns 2 and 3.
+          const double y02 = fold32_d(part[0][0], part[0][2]);
+          const double y13 = fold32_d(part[0][1], R > 3 ? part[0][R - 1] : 0.0);
+          const double y = row_sum_d(fold16_d(y02, y13));
+          const int kcol = 2 * (lane >> 5) + ((lane >> 4) & 1);
+          if ((lane & 15) == 0 && kcol < R)
+            ppart[L.ppart_off + ((int64_t)chunk * L.rows + i) * ws.rmax + kcol] = y;
         }
       }
     }
-    // The sums over the 64 lanes of both rows' R values together: every folding step halves the
-    // number of values a lane carries (the upper 32 lanes keep the second row, the odd rows of 16
-    // lanes the second half of the columns of P), so the lane exchanges of a full butterfly per
-    // value (27 instructions each in fp64) shrink to 18 .. 42 for all of them.
-    const int hb = lane >> 5, rp16 = (lane >> 4) & 1;       // which row of the pair / which half of the columns
-    const int i_mine = i0 + 4 * hb;
-    double* dst = ppart + L.ppart_off + ((int64_t)chunk * L.rows + i_mine) * ws.rmax;
-    const bool writer = (lane & 15) == 0 && i_mine < row_end;
-    if (R == 1) {
-      double y = fold32_d(part[0][0], part[1][0]);
-      y = row_sum_d(y);
-      y = fold16_d(y, y);                                    // both rows of 16 lanes of a half
-      if (writer && rp16 == 0) dst[0] = y;
-    } else if (R == 2) {
-      const double y0 = fold32_d(part[0][0], part[1][0]), y1 = fold32_d(part[0][1], part[1][1]);
-      const double y = row_sum_d(fold16_d(y0, y1));         // even rows of 16 lanes: column 0, odd rows: column 1
-      if (writer) dst[rp16] = y;
-    } else {
-      double z[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) z[k] = fold32_d(k < R ? part[0][k] : 0.0, k < R ? part[1][k] : 0.0);
-      const double y0 = row_sum_d(fold16_d(z[0], z[2]));    // even rows of 16 lanes: columns 0 and 1, odd rows: 2 and 3
-      const double y1 = row_sum_d(fold16_d(z[1], z[3]));
-      if (writer) {
-        dst[2 * rp16] = y0;
-        if (2 * rp16 + 1 < R) dst[2 * rp16 + 1] = y1;
+    if constexpr (R <= 2) {
+      // One or two values per row: both rows' values are folded over the wave together (the upper
+      // 32 lanes keep the second row, the odd rows of 16 lanes the second column of P), so that
+      // the lane exchanges of a full butterfly per value (27 instructions each in fp64) shrink
+      // to about 20 for all of them.
+      const int hb = lane >> 5, rp16 = (lane >> 4) & 1;     // which row of the pair / which column
+      const int i_mine = i0 + 4 * hb;
+      double* dst = ppart + L.ppart_off + ((int64_t)chunk * L.rows + i_mine) * ws.rmax;
+      const bool writer = (lane & 15) == 0 && i_mine < row_end;
+      if constexpr (R == 1) {
+        double y = fold32_d(part[0][0], part[1][0]);
+        y = row_sum_d(y);
+        y = fold16_d(y, y);                                  // both rows of 16 lanes of a half
+        if (writer && rp16 == 0) dst[0] = y;
+      } else {
+        const double y0 = fold32_d(part[0][0], part[1][0]), y1 = fold32_d(part[0][1], part[1][1]);
+        const double y = row_sum_d(fold16_d(y0, y1));       // even rows of 16 lanes: column 0, odd rows: column 1
+        if (writer) dst[rp16] = y;
       }
     }
   }
