@@ -34,7 +34,7 @@ struct LayerDev {
   int32_t tile0;         // first flat tile of the layer
   int32_t ntiles;        // number of flat tiles
   int32_t t2slot0;       // TopK: the layer's first slot in a worker's level-2 count array (one slot per kT2Group tiles)
-  int32_t pad1;
+  int32_t mt0;           // PowerSGD matrix layer: its first 64 x 256 matrix tile (it has n_colchunks * ceil(rows / 64))
   int64_t qoff;          // slot of the layer's first wave quarter in the per-worker quarter arrays
                          // (4 * tile0 + layer index: one spare slot per layer for the totals)
   int64_t q_off;         // into Q      (cols rows of kMaxRank floats, zero beyond rmax)
@@ -85,7 +85,10 @@ struct Ws {
   float* A;                    // accumulated gradient, N
   float* e;                    // W x e_stride error memory (holds Delta during a step)
   int64_t e_stride;
-  double* norm_part;           // per flat tile
+  double* norm_part;           // per flat tile: sum of squares of A (kept up to date by the pass that adds the gradient)
+  double* norm_part_m;         // PowerSGD: the same per 64 x 256 matrix tile
+  uint32_t* a_fresh;           // one word: nonzero = the accumulation window has just restarted: A counts as zero
+                               //   (the next pass over it stores the gradient instead of adding it)
   double* sq_part;             // per flat tile: sum over the window of ||g_0||^2 (MSDR detector)
   const FlatTile* ftiles;
   const MatTile* mtiles;
@@ -237,6 +240,23 @@ __device__ __forceinline__ uint64_t scalar_mask(uint64_t mask) {
 }
 
 __device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+
+__device__ __forceinline__ double sq4(const float4& a) {
+  double s = (double)a.x * (double)a.x;
+  s += (double)a.y * (double)a.y;
+  s += (double)a.z * (double)a.z;
+  s += (double)a.w * (double)a.w;
+  return s;
+}
+
+// Sum over the workgroup's four waves of one fp64 value per lane; the result is valid in thread 0.
+// Every thread calls it (one barrier).
+__device__ __forceinline__ double block_sum4_d(double s, double* red4) {
+  s = wave_sum_d(s);
+  if ((threadIdx.x & 63) == 0) red4[threadIdx.x >> 6] = s;
+  __syncthreads();
+  return (red4[0] + red4[1]) + (red4[2] + red4[3]);
+}
 
 // Folding sums of two values over the wave (gfx950 lane swaps): the result holds, in the lower 32
 // lanes (fold32) / the even rows of 16 lanes (fold16), the sum of a over the two halves that are

@@ -97,7 +97,7 @@ __device__ __forceinline__ float low_rank_entry(const float (&p)[kMaxRank], cons
 template <int R, bool V4>
 __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, const float* __restrict__ g,
                           float* __restrict__ e, float* __restrict__ A, double* __restrict__ ppart, int rp,
-                          float (*ps)[kMaxRank]) {
+                          float (*ps)[kMaxRank], bool a_fresh, double* red4) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int col[4]; bool cm[4];
@@ -116,6 +116,7 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
   const int row_end = min(t.row0 + kMatRows, L.rows);
   const int chunk = t.col0 / kMatCols;
   constexpr int B = 2;   // rows in flight per wave (one row is as fast; more rows cost registers and occupancy)
+  double a_sq = 0.0;     // worker 0: the lane's share of the tile's sum of squares of A
   for (int i0 = t.row0 + wave; i0 < row_end; i0 += 4 * B) {
     float gd[B][4], ed[B][4], ad[B][4];
     double part[R >= 3 ? 1 : B][R];                          // a row that does not exist contributes zeros
@@ -130,7 +131,8 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
         const int64_t rb = L.offset + (int64_t)i * L.cols;
         load_row<V4, kPsgdStreamG>(g, rb, col, cm, gd[b]);
         load_row<V4>(e, rb, col, cm, ed[b]);
-        if (A) load_row<V4, kPsgdStreamA>(A, rb, col, cm, ad[b]);
+        if (A && !a_fresh) load_row<V4, kPsgdStreamA>(A, rb, col, cm, ad[b]);
+        else ad[b][0] = ad[b][1] = ad[b][2] = ad[b][3] = 0.f;
       }
     }
 #pragma unroll
@@ -153,6 +155,8 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
 #pragma unroll
           for (int v = 0; v < 4; ++v) ad[b][v] += gd[b][v];
           store_row<V4, kPsgdStreamA>(A, rb, col, cm, ad[b]);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) a_sq += (double)ad[b][v] * (double)ad[b][v];   // masked columns hold zeros
         }
         // the lane's share of the chunk's share of P_w's row, in fp64: products of fp32 values are
         // exact there, the sums carry an error far below the fp32 rounding of the stored P_w
@@ -201,6 +205,10 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
       }
     }
   }
+  if (A) {                                                 // uniform over the workgroup
+    const double tsum = block_sum4_d(a_sq, red4);
+    if (threadIdx.x == 0) ws.norm_part_m[blockIdx.x] = tsum;
+  }
 }
 
 // *ws.pending: bit w set = worker w's memory holds the previous Delta (see the top of this file).
@@ -208,24 +216,32 @@ __device__ void ef_p_tile(const Ws& ws, const LayerDev& L, const MatTile& t, con
 // out), so a captured graph of a step stays valid whatever happens between its replays.
 __global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradPtrs gp, int w0) {
   __shared__ float ps[kMatRows][kMaxRank];
+  __shared__ double red4[4];
   const uint32_t pending = *ws.pending;
   const int w = w0 + blockIdx.y;
   const float* __restrict__ g = gp.p[w];
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
   float* __restrict__ A = (w == 0) ? ws.A : nullptr;
+  // the accumulation window has just restarted: A counts as zero and is not read
+  const bool a_fresh = A && *ws.a_fresh != 0u;             // uniform over the workgroup
   if ((int)blockIdx.x >= ws.n_mtiles) {
-    // 1-D layers: only the accumulation A += g of worker 0 happens here
+    // 1-D layers: only the accumulation A += g of worker 0 happens here (and the tile's sum of squares)
     if (w != 0) return;
-    const FlatTile ft = ws.ftiles[ws.vectiles[blockIdx.x - ws.n_mtiles]];
+    const int tile_id = ws.vectiles[blockIdx.x - ws.n_mtiles];
+    const FlatTile ft = ws.ftiles[tile_id];
     const LayerDev& L = ws.layers[ft.layer];
     const TileGeom tg = tile_geom(L, ft);
+    double a_sq = 0.0;
     for (int q = threadIdx.x; q < tg.nquads; q += kFlatThreads) {
       const int64_t base = tg.a0 + 4 * (int64_t)q;
-      float4 a = ld_quad(ws.A, base, tg.lo, tg.hi);
+      float4 a = a_fresh ? make_float4(0.f, 0.f, 0.f, 0.f) : ld_quad(ws.A, base, tg.lo, tg.hi);
       const float4 gv = ld_quad(g, base, tg.lo, tg.hi);
       a.x += gv.x; a.y += gv.y; a.z += gv.z; a.w += gv.w;
       st_quad(ws.A, base, tg.lo, tg.hi, a);
+      a_sq += sq4(a);                                        // elements outside the tile were loaded as zeros
     }
+    a_sq = block_sum4_d(a_sq, red4);
+    if (threadIdx.x == 0) ws.norm_part[tile_id] = a_sq;
     return;
   }
   const MatTile t = ws.mtiles[blockIdx.x];
@@ -235,17 +251,17 @@ __global__ __launch_bounds__(256) void psgd_ef_p_kernel(const Ws ws, const GradP
   double* ppart = ws.Ppart + (int64_t)w * ws.ppart_stride;
   if (L.vec4) {
     switch (r) {
-      case 1: ef_p_tile<1, true>(ws, L, t, g, e, A, ppart, rp, ps); break;
-      case 2: ef_p_tile<2, true>(ws, L, t, g, e, A, ppart, rp, ps); break;
-      case 3: ef_p_tile<3, true>(ws, L, t, g, e, A, ppart, rp, ps); break;
-      default: ef_p_tile<4, true>(ws, L, t, g, e, A, ppart, rp, ps); break;
+      case 1: ef_p_tile<1, true>(ws, L, t, g, e, A, ppart, rp, ps, a_fresh, red4); break;
+      case 2: ef_p_tile<2, true>(ws, L, t, g, e, A, ppart, rp, ps, a_fresh, red4); break;
+      case 3: ef_p_tile<3, true>(ws, L, t, g, e, A, ppart, rp, ps, a_fresh, red4); break;
+      default: ef_p_tile<4, true>(ws, L, t, g, e, A, ppart, rp, ps, a_fresh, red4); break;
     }
   } else {
     switch (r) {
-      case 1: ef_p_tile<1, false>(ws, L, t, g, e, A, ppart, rp, ps); break;
-      case 2: ef_p_tile<2, false>(ws, L, t, g, e, A, ppart, rp, ps); break;
-      case 3: ef_p_tile<3, false>(ws, L, t, g, e, A, ppart, rp, ps); break;
-      default: ef_p_tile<4, false>(ws, L, t, g, e, A, ppart, rp, ps); break;
+      case 1: ef_p_tile<1, false>(ws, L, t, g, e, A, ppart, rp, ps, a_fresh, red4); break;
+      case 2: ef_p_tile<2, false>(ws, L, t, g, e, A, ppart, rp, ps, a_fresh, red4); break;
+      case 3: ef_p_tile<3, false>(ws, L, t, g, e, A, ppart, rp, ps, a_fresh, red4); break;
+      default: ef_p_tile<4, false>(ws, L, t, g, e, A, ppart, rp, ps, a_fresh, red4); break;
     }
   }
 }
@@ -388,6 +404,8 @@ __device__ void orth_layer(const Ws& ws, const LayerDev& L, double (*red)[kOrthW
 
 __global__ __launch_bounds__(kOrthThreads) void psgd_orth_kernel(const Ws ws, const GradPtrs gp) {
   __shared__ double red[2][kOrthWaves];
+  // worker 0's first pass has added its gradient to A: the window is no longer fresh
+  if (blockIdx.x == 0 && threadIdx.x == 0) *ws.a_fresh = 0u;
   if ((int)blockIdx.x >= ws.n_mat) {
     // 1-D layers are sent raw: mean over workers in worker order
     const FlatTile ft = ws.ftiles[ws.vectiles[blockIdx.x - ws.n_mat]];

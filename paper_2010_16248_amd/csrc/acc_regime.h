@@ -5,7 +5,40 @@
 
 namespace acc {
 
-// Per flat tile: sum of squares of A in fp64 (each fp32 square is exact in fp64), then A <- 0.
+// The norm of the accumulated gradient costs no pass of its own for TopK and PowerSGD: the pass
+// that adds worker 0's gradient to A has every element of A in registers and leaves the sum of
+// their squares per tile (fp64; each fp32 square is exact there) in norm_part / norm_part_m, and
+// "A <- 0" at the end of a window is a flag (a_fresh) that makes the next such pass store the
+// gradient instead of adding it.  A window end is then the decision kernel alone.  (The
+// batch-size mode keeps the separate pass below.)
+// After an import of A (accordion_set_state): the per-tile sums of squares of the imported A.
+// Workgroups 0 .. n_ftiles-1 take the flat tiles, the rest the matrix tiles (PowerSGD).
+__global__ __launch_bounds__(256) void norm_refresh_kernel(const Ws ws) {
+  __shared__ double red[4];
+  const int tid = threadIdx.x;
+  double s = 0.0;
+  if ((int)blockIdx.x < ws.n_ftiles) {
+    const FlatTile ft = ws.ftiles[blockIdx.x];
+    const LayerDev& L = ws.layers[ft.layer];
+    const TileGeom tg = tile_geom(L, ft);
+    for (int q = tid; q < tg.nquads; q += kFlatThreads) s += sq4(ld_quad(ws.A, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi));
+    s = block_sum4_d(s, red);
+    if (tid == 0) ws.norm_part[blockIdx.x] = s;
+  } else {
+    const int mt = (int)blockIdx.x - ws.n_ftiles;
+    const MatTile t = ws.mtiles[mt];
+    const LayerDev& L = ws.layers[t.layer];
+    const int rows = min(kMatRows, L.rows - t.row0), cols = min(kMatCols, L.cols - t.col0);
+    for (int x = tid; x < rows * cols; x += kFlatThreads) {
+      const float a = ws.A[L.offset + (int64_t)(t.row0 + x / cols) * L.cols + t.col0 + x % cols];
+      s += (double)a * (double)a;
+    }
+    s = block_sum4_d(s, red);
+    if (tid == 0) ws.norm_part_m[mt] = s;
+  }
+}
+
+// Batch-size mode.  Per flat tile: sum of squares of A in fp64, then A <- 0.
 __global__ __launch_bounds__(256) void norm_partial_kernel(const Ws ws) {
   __shared__ double red[4];
   const int tid = threadIdx.x;
@@ -29,17 +62,37 @@ __global__ __launch_bounds__(256) void norm_partial_kernel(const Ws ws) {
   if (tid == 0) ws.norm_part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-__global__ __launch_bounds__(256) void zero_accum_kernel(const Ws ws) {
+// The accumulation window restarts without a decision.  zero_a (batch-size mode): A is cleared
+// here; otherwise the restart is the a_fresh flag.
+__global__ __launch_bounds__(256) void zero_accum_kernel(const Ws ws, int zero_a) {
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int q = threadIdx.x; q < tg.nquads; q += kFlatThreads)
-    st_quad(ws.A, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi, zero);
+  if (zero_a) {
+    for (int q = threadIdx.x; q < tg.nquads; q += kFlatThreads)
+      st_quad(ws.A, tg.a0 + 4 * (int64_t)q, tg.lo, tg.hi, zero);
+  } else if (blockIdx.x == 0 && threadIdx.x == 0) {
+    *ws.a_fresh = 1u;
+  }
   if (threadIdx.x == 0) {                                   // the MSDR detector's window sums too
     if (ws.sq_part) ws.sq_part[blockIdx.x] = 0.0;
     if (blockIdx.x == 0) ws.words[3] = 0ull;
   }
+}
+
+// Sum of the layer's per-tile sums of squares of A (0 when the window has just restarted), the same
+// value in every lane of the wave.  batch: the partials are those of norm_partial_kernel.
+__device__ __forceinline__ double layer_sumsq(const Ws& ws, const LayerDev& L, int lane) {
+  if (*ws.a_fresh != 0u) return 0.0;
+  double s = 0.0;
+  if (L.is_matrix) {
+    const int nmt = L.n_colchunks * ((L.rows + kMatRows - 1) / kMatRows);
+    for (int t = lane; t < nmt; t += kWave) s += ws.norm_part_m[L.mt0 + t];
+  } else {
+    for (int t = lane; t < L.ntiles; t += kWave) s += ws.norm_part[L.tile0 + t];
+  }
+  return wave_sum_f64(s);
 }
 
 // One wave per layer: c = sqrt(sum of the layer's tile partials), then Algorithm 1 in fp32:
@@ -49,9 +102,7 @@ __global__ __launch_bounds__(64) void regime_decide_kernel(const Ws ws, float lr
   const int li = blockIdx.x;
   const int lane = threadIdx.x;
   const LayerDev& L = ws.layers[li];
-  double s = 0.0;
-  for (int t = lane; t < L.ntiles; t += kWave) s += ws.norm_part[L.tile0 + t];
-  s = wave_sum_f64(s);
+  const double s = layer_sumsq(ws, L, lane);
   if (lane == 0) {
     const float c = (float)sqrt(s);
     const float old = ws.norm_old[li];
@@ -105,13 +156,12 @@ __global__ __launch_bounds__(64) void msdr_decide_kernel(const Ws ws) {
   const int li = blockIdx.x;
   const int lane = threadIdx.x;
   const LayerDev& L = ws.layers[li];
-  double a = 0.0, q = 0.0;
+  const double a = layer_sumsq(ws, L, lane);
+  double q = 0.0;
   for (int t = lane; t < L.ntiles; t += kWave) {
-    a += ws.norm_part[L.tile0 + t];
     q += ws.sq_part[L.tile0 + t];
     ws.sq_part[L.tile0 + t] = 0.0;
   }
-  a = wave_sum_f64(a);
   q = wave_sum_f64(q);
   if (lane == 0) {
     const unsigned long long steps = ws.words[3];
@@ -133,9 +183,12 @@ __global__ __launch_bounds__(64) void msdr_decide_kernel(const Ws ws) {
 }
 
 // Floats one worker sends per step at the current levels (the paper's "Data Sent" unit).
-__global__ __launch_bounds__(256) void recount_words_kernel(const Ws ws, int method) {
+// fresh: 0 / 1 = what the a_fresh flag becomes (1 after a decision: the window restarts; 0 after an
+// import of A); -1 leaves it.
+__global__ __launch_bounds__(256) void recount_words_kernel(const Ws ws, int method, int fresh) {
   __shared__ unsigned long long red[256];
   if (threadIdx.x == 0) ws.words[3] = 0ull;                 // a new detection window starts
+  if (threadIdx.x == 0 && fresh >= 0) *ws.a_fresh = (uint32_t)fresh;
   if (method == 2) {                        // batch-size mode: an exchange is the dense model
     if (threadIdx.x == 0) ws.words[0] = (unsigned long long)ws.n_model;
     return;

@@ -380,7 +380,7 @@ __device__ __forceinline__ float4 drop_kept(const TileGeom& tg, int q, bool qa, 
 template <bool AL, bool SELECT, bool ZB>
 __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, int w, int tile_id,
                                              const FlatTile& ft, const LayerDev& L, const TileGeom& tg,
-                                             uint32_t* hist, const CandList& cl, uint32_t* sub2, uint32_t guess) {
+                                             uint32_t* hist, const CandList& cl, uint32_t* sub2, double* red4, uint32_t guess) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -388,6 +388,9 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   const float* __restrict__ g = gp.p[w];
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
   float* __restrict__ A = (w == 0) ? ws.A : nullptr;
+  // the accumulation window has just restarted: A counts as zero and is not read
+  const bool a_fresh = A && *ws.a_fresh != 0u;             // uniform over the workgroup
+  double a_sq = 0.0;                                       // worker 0: the lane's share of the tile's sum of squares of A
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   uint32_t glo = 0x7ffffff0u, gnb = 0u;                    // no bin matches without a guess
   if (SELECT && !ZB && guess != kNoGuess) { glo = guess_lo(guess); gnb = guess_nb(guess); }
@@ -400,7 +403,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
     const int q = span.qbeg + u * kWave + lane;
     gc[u] = ld_span<AL, kStreamG>(g, tg, span, q);
     ec[u] = ld_span<AL>(e, tg, span, q);
-    ac[u] = A ? ld_span<AL, kStreamA>(A, tg, span, q) : zero4;
+    ac[u] = (A && !a_fresh) ? ld_span<AL, kStreamA>(A, tg, span, q) : zero4;
   }
   // the batched path leaves Delta of the previous step in e: its kept entries are dropped here.
   // The previous selection is requested whether or not it is needed, so that its loads do not
@@ -421,7 +424,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
       const int q = q0 + (U + u) * kWave + lane;
       gn[u] = ld_span<AL, kStreamG>(g, tg, span, q);
       en[u] = ld_span<AL>(e, tg, span, q);
-      an[u] = A ? ld_span<AL, kStreamA>(A, tg, span, q) : zero4;
+      an[u] = (A && !a_fresh) ? ld_span<AL, kStreamA>(A, tg, span, q) : zero4;
     }
     const bool full = q0 + U * kWave <= span.qend;          // wave-uniform
 #pragma unroll
@@ -435,6 +438,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
         if (A) {
           const float4 a = make_float4(ac[u].x + gc[u].x, ac[u].y + gc[u].y, ac[u].z + gc[u].z, ac[u].w + gc[u].w);
           stq<AL, kStreamA>(A, tg.a0, tg.lo, tg.hi, q, a);
+          a_sq += sq4(a);                                    // elements outside the tile were loaded as zeros
         }
       }
       if (SELECT) {
@@ -467,6 +471,11 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
 #pragma unroll
     for (int u = 0; u < U; ++u) { gc[u] = gn[u]; ec[u] = en[u]; ac[u] = an[u]; }
   }
+  if (A) {                                                 // uniform over the workgroup
+    const double t = block_sum4_d(a_sq, red4);
+    if (tid == 0) ws.norm_part[tile_id] = t;
+    __syncthreads();
+  }
   if (SELECT) {
     stage_finish(ws, qslot_mine, cl, cnt, lane);
     __syncthreads();
@@ -489,6 +498,7 @@ __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const Gr
   __shared__ uint32_t cand_val[4][kCandLdsSlots];
   __shared__ uint16_t cand_idx[4][kCandLdsSlots];
   __shared__ uint32_t sub2[kSub2];
+  __shared__ double red4[4];
   const int w = w0 + blockIdx.y;
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
@@ -499,16 +509,16 @@ __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const Gr
   // decision kernels (which set it) run
   if (w == 0 && ft.start == 0 && threadIdx.x == 0) ws.lflag[ft.layer] = 0u;
   if (L.ntiles == 1) {
-    if (tg.aligned) ef_hist_tile<true, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, kNoGuess);
-    else ef_hist_tile<false, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, kNoGuess);
+    if (tg.aligned) ef_hist_tile<true, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, kNoGuess);
+    else ef_hist_tile<false, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, kNoGuess);
   } else {
     const uint32_t guess = ws.guess[((int64_t)w * ws.L + ft.layer) * 2 + ws.level[ft.layer]];
     if (guess == kGuessZero) {                               // uniform over the workgroup
-      if (tg.aligned) ef_hist_tile<true, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, guess);
-      else ef_hist_tile<false, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, guess);
+      if (tg.aligned) ef_hist_tile<true, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess);
+      else ef_hist_tile<false, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess);
     } else {
-      if (tg.aligned) ef_hist_tile<true, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, guess);
-      else ef_hist_tile<false, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, guess);
+      if (tg.aligned) ef_hist_tile<true, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess);
+      else ef_hist_tile<false, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess);
     }
   }
 }
@@ -715,6 +725,8 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   const int64_t wl = (int64_t)w * ws.L + li;
   const int lv = ws.level[li];
   const uint32_t k = (uint32_t)L.k[lv];
+  // worker 0's first pass has added its gradient to A: the window is no longer fresh
+  if (w == 0 && li == 0 && tid == 0) *ws.a_fresh = 0u;
   if (L.ntiles == 1) return;                               // decided by the last pick kernel, from Delta
   SelState* sp = ws.sel + wl;
   __shared__ uint32_t sub[kSub2];

@@ -49,7 +49,7 @@ struct Plan {
   // workspace regions
   Region r_layers, r_ftiles, r_mtiles, r_qmtiles, r_qtiles, r_ptiles, r_vectiles, r_matlayers;
   Region r_level, r_norm_old, r_norm_prev, r_norm_curr, r_has_old, r_rank_used, r_words;
-  Region r_A, r_e, r_norm_part, r_sq_part, r_bstate;
+  Region r_A, r_e, r_norm_part, r_norm_part_m, r_afresh, r_sq_part, r_bstate;
   int64_t n_model = 0;   // elements that belong to a layer
   Region r_Q, r_Phat, r_Pwork, r_Ppart, r_Qpart, r_vecmean, r_pending;
   Region r_hist1, r_t2, r_qlist, r_sel, r_hist2m, r_lflag, r_b1hist, r_guess, r_qinfo, r_candval, r_candidx, r_gtq, r_eqq, r_gtpre, r_eqpre, r_payidx, r_payval, r_overlap, r_tpending;
@@ -142,6 +142,7 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
         d.rank[0] = std::max(1, std::min(c->rank_noncrit, cap));
         d.rank[1] = std::max(1, std::min(c->rank_crit, cap));
         d.n_colchunks = (l.cols + kMatCols - 1) / kMatCols;
+        d.mt0 = (int32_t)p.mtiles.size();
         const int n_rb = (l.rows + kMatRows - 1) / kMatRows;
         d.n_rowblocks = (l.rows + kQRows - 1) / kQRows;
         d.q_off = p.q_dev;
@@ -216,6 +217,8 @@ int make_plan(const acc_config* c, Plan& p, char* err) {
   reg(p.r_A, 4 * p.e_stride);
   reg(p.r_e, 4 * p.e_stride * W);
   reg(p.r_norm_part, 8 * ntile);
+  reg(p.r_norm_part_m, 8 * (int64_t)p.mtiles.size());
+  reg(p.r_afresh, 4);
   reg(p.r_sq_part, c->detector == ACC_DETECT_MSDR ? 8 * ntile : 0);
   reg(p.r_bstate, 4 * 8);
   if (c->method == ACC_POWERSGD) {
@@ -298,7 +301,7 @@ enum Stage {
   ST_batch_micro_kernel, ST_batch_micro_update_kernel, ST_batch_decide_kernel,
   ST_topk_overlap_kernel, ST_zero_u64_kernel, ST_msdr_sq_kernel, ST_msdr_decide_kernel,
   ST_psgd_clear_pending_kernel, ST_topk_residual_kernel, ST_topk_clear_pending_kernel,
-  ST_topk_pick3_big_kernel, ST_psgd_pmean_kernel,
+  ST_topk_pick3_big_kernel, ST_psgd_pmean_kernel, ST_norm_refresh_kernel,
   ST_COUNT
 };
 static_assert(ST_COUNT <= ACC_N_STAGES, "more stages than the header announces");
@@ -312,7 +315,7 @@ static const char* const kStageNames[ST_COUNT] = {
   "batch_micro_kernel", "batch_micro_update_kernel", "batch_decide_kernel",
   "topk_overlap_kernel", "zero_u64_kernel", "msdr_sq_kernel", "msdr_decide_kernel",
   "psgd_clear_pending_kernel", "topk_residual_kernel", "topk_clear_pending_kernel",
-  "topk_pick3_big_kernel", "psgd_pmean_kernel"};
+  "topk_pick3_big_kernel", "psgd_pmean_kernel", "norm_refresh_kernel"};
 
 struct EventPair { hipEvent_t a, b; int stage; };
 
@@ -661,6 +664,8 @@ static int32_t init_common(const acc_config* cfg, void* workspace_dev, size_t wo
   ws.e = at<float>(c, p.r_e);
   ws.e_stride = p.e_stride;
   ws.norm_part = at<double>(c, p.r_norm_part);
+  ws.norm_part_m = at<double>(c, p.r_norm_part_m);
+  ws.a_fresh = at<uint32_t>(c, p.r_afresh);
   ws.sq_part = p.r_sq_part.bytes > 0 ? at<double>(c, p.r_sq_part) : nullptr;
   if (cfg->method == ACC_POWERSGD) {
     ws.Q = at<float>(c, p.r_Q);
@@ -740,7 +745,7 @@ static int32_t init_common(const acc_config* cfg, void* workspace_dev, size_t wo
       std::vector<uint32_t> none((size_t)2 * nl_ * cfg->n_workers, kNoGuess);
       ACC_HIP(c, up(p.r_guess, none.data()));
     }
-    ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)cfg->method);
+    ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)cfg->method, -1);
     ACC_HIP(c, hipStreamSynchronize(c->stream));
     return ACC_OK;
   };
@@ -931,14 +936,16 @@ int32_t accordion_detect_regime(acc_ctx* c, float lr_curr, float lr_next) {
   ACC_USABLE(c);
   if (c->in_step) return fail(c->err, ACC_ESTATE, "detect_regime inside a step");
   const Ws& ws = c->ws;
-  ACC_LAUNCH(c, norm_partial_kernel, dim3(ws.n_ftiles), dim3(256), ws);
   if (c->cfg.method == ACC_BATCH) {
+    ACC_LAUNCH(c, norm_partial_kernel, dim3(ws.n_ftiles), dim3(256), ws);
     ACC_LAUNCH(c, batch_decide_kernel, dim3(1), dim3(256), ws, lr_curr, lr_next);
     return ACC_OK;
   }
+  // the sums of squares of A are kept per tile by the pass that adds the gradient; "A <- 0" is a
+  // flag that the counting kernel sets once every layer has been decided
   if (c->cfg.detector == ACC_DETECT_MSDR) ACC_LAUNCH(c, msdr_decide_kernel, dim3(ws.L), dim3(64), ws);
   else ACC_LAUNCH(c, regime_decide_kernel, dim3(ws.L), dim3(64), ws, lr_curr, lr_next);
-  ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), ws, (int)c->cfg.method);
+  ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), ws, (int)c->cfg.method, 1);
   return ACC_OK;
 }
 
@@ -951,7 +958,7 @@ int32_t accordion_flush(acc_ctx* c) {
 int32_t accordion_reset_accumulator(acc_ctx* c) {
   ACC_USABLE(c);
   if (c->in_step) return fail(c->err, ACC_ESTATE, "reset_accumulator inside a step");
-  ACC_LAUNCH(c, zero_accum_kernel, dim3(c->ws.n_ftiles), dim3(256), c->ws);
+  ACC_LAUNCH(c, zero_accum_kernel, dim3(c->ws.n_ftiles), dim3(256), c->ws, c->cfg.method == ACC_BATCH ? 1 : 0);
   return ACC_OK;
 }
 
@@ -1136,7 +1143,14 @@ static int32_t state_copy(acc_ctx* c, char* host, bool to_host) {
     return e;
   };
   for (int w = 0; w < c->cfg.n_workers; ++w) ACC_HIP(c, cp(c->ws.e + (size_t)w * p.e_stride, N4));
-  ACC_HIP(c, cp(c->ws.A, N4));
+  uint32_t fresh = 0;                                        // the window has just restarted: A counts as zero
+  if (to_host) ACC_HIP(c, hipMemcpy(&fresh, c->ws.a_fresh, 4, hipMemcpyDeviceToHost));
+  if (fresh) {
+    std::memset(host, 0, N4);
+    host += N4;
+  } else {
+    ACC_HIP(c, cp(c->ws.A, N4));
+  }
   if (c->cfg.method == ACC_POWERSGD) {
     const int rq = copy_q(c, reinterpret_cast<float*>(host), to_host);
     if (rq != ACC_OK) return rq;
@@ -1189,7 +1203,10 @@ int32_t accordion_set_state(acc_ctx* c, const void* state_host, size_t bytes) {
     ACC_LAUNCH(c, zero_u64_kernel, dim3((n8 + 255) / 256), dim3(256),
                reinterpret_cast<unsigned long long*>(c->ws.sq_part), n8);
   }
-  ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)c->cfg.method);
+  // the imported A: its sums of squares per tile, and it is not "fresh"
+  if (c->cfg.method != ACC_BATCH)
+    ACC_LAUNCH(c, norm_refresh_kernel, dim3(c->ws.n_ftiles + c->ws.n_mtiles), dim3(256), c->ws);
+  ACC_LAUNCH(c, recount_words_kernel, dim3(1), dim3(256), c->ws, (int)c->cfg.method, c->cfg.method != ACC_BATCH ? 0 : -1);
   ACC_HIP(c, hipStreamSynchronize(c->stream));
   return ACC_OK;
 }

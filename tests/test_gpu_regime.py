@@ -85,3 +85,80 @@ def test_norms_accumulate_worker0_raw_gradient_over_multi_tile_layers():
         assert np.allclose(st["norm_old"], ora.norm_old, rtol=1e-6, atol=0)
         assert gpu.payload_words()[1] == ora.words_cum
     gpu.destroy()
+
+
+@pytest.mark.parametrize("method", ["topk", "powersgd"])
+def test_window_restart_without_a_pass_over_the_accumulator(method):
+    """The sums of squares of A are kept by the pass that adds the gradient, and a window end only
+    marks A as restarted.  Everything that looks at A or its norm in between must see what a
+    cleared A would give: a test right after a test (norm 0), a state export (zeros), a state import
+    followed directly by a test (the imported A's norm), a restart without a decision, steps issued
+    call by call with worker 0 last; levels, norms and A itself against the oracle throughout."""
+    shapes = [(1, 2 * 8192 + 7, 0), (70, 300, 1), (1, 5, 0), (3, 9000, 1)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 2
+    if method == "topk":
+        gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    else:
+        q0 = wl.q_init(layers, 2, 3)
+        gpu, ora = H.make_pair(B.ACC_POWERSGD, layers, W, 2, 1, 100, 0.5, 1, q0)
+    rng = np.random.default_rng(31)
+    out = H.dev_out(N)
+
+    def step(scale, by_call=False):
+        grads = [(rng.standard_normal(N) * scale).astype(np.float32) for _ in range(W)]
+        dg = [H.to_dev(g) for g in grads]
+        if not by_call:
+            gpu.step_all(dg, out)
+        else:
+            for w in (1, 0):                                         # worker 0 (the one that accumulates) last
+                gpu.compress_step(w, dg[w], 0)
+            gpu.aggregate(0)
+            if method == "powersgd":
+                for w in (1, 0):
+                    gpu.compress_step(w, None, 1)
+                gpu.aggregate(1)
+            gpu.decompress(out)
+        ora.step(grads)
+
+    def test_now(lr_next=0.1):
+        gpu.detect_regime(0.1, lr_next)
+        ref = ora.detect_regime(0.1, lr_next)
+        assert np.array_equal(gpu.get_levels(), ref)
+        old, cur = gpu.get_norms()
+        assert np.allclose(cur, ora.norm_curr, rtol=1e-6, atol=0) and np.allclose(old, ora.norm_prev, rtol=1e-6, atol=0)
+
+    def same_accumulator():
+        H.assert_bits_equal(gpu.unpack_state(gpu.get_state())["A"], ora.A, "accumulator")
+
+    step(1.0); step(1.0)
+    same_accumulator()
+    test_now()
+    same_accumulator()                                               # exported as zeros
+    test_now()                                                       # nothing accumulated: norm 0
+    assert np.all(gpu.get_norms()[1] == 0)
+    step(0.5, by_call=True)
+    same_accumulator()
+    step(0.5)
+    test_now()
+    step(0.4)
+    gpu.reset_accumulator(); ora.reset_accumulator()                 # restart without a decision
+    same_accumulator()
+    step(0.45, by_call=True)
+    same_accumulator()
+    test_now()
+    # import a state in the middle of a window and test at once: the imported A's norm
+    step(0.3); step(0.3)
+    blob = gpu.get_state().copy()
+    step(0.9)
+    gpu.set_state(blob)
+    st = gpu.unpack_state(blob)
+    ora.A[:] = st["A"]
+    if method == "powersgd":
+        gpu.set_state(H.oracle_state_blob(gpu, ora))                 # (the oracle's e and Q went one step further)
+    test_now()
+    same_accumulator()
+    step(0.3)
+    test_now(lr_next=0.01)
+    gpu.destroy()
