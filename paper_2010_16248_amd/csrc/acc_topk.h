@@ -44,15 +44,19 @@ constexpr int kPickWaves = kPickThreads / kWave;
 static_assert(kHistBins == 2 * kPickThreads, "the pick kernels load two histogram bins per thread");
 constexpr int kQListCap = 16;            // keys of bin (b1, b2) listed per wave quarter
 constexpr int kL2Bins = 64;              // level 2: key bits 19..14
-// A guess names nb adjacent level-1 bins, lo .. lo + nb - 1 (lo >= 1): the first pass lists every
-// entry of bin lo and above as a candidate and counts the level-2 bins of the nb guessed ones.
-// kGuessNarrow bins while the threshold rests (it has not moved for two steps), kGuessWide bins
-// while it moves: after a level switch the error memory adapts for ten steps or so, during which
-// the threshold moves by one to three bins per step (an eighth of an octave each), not quite
-// steadily.  A wide guess costs more candidates (18 % of the entries instead of 13 % at K = 10 %),
-// a missed one a second read of Delta and a slow decision for that layer.
-constexpr int kGuessNarrow = 3, kGuessWide = 7;
-constexpr int kSub2 = kGuessWide * kL2Bins;  // a tile's level-2 counts of the guessed bins
+// A guess names kGuessBins adjacent level-1 bins, lo .. lo + kGuessBins - 1 (lo >= 1): the first
+// pass lists every entry of bin lo and above as a candidate and counts the level-2 bins of the
+// guessed ones.  Bins above the threshold cost no candidates (their entries are kept anyway), so the
+// guess always reaches far up; what varies is how far below the expected bin it starts: one bin
+// while the threshold rests (no move for two steps in a row), three while it moves -- after a level
+// switch the error memory adapts for ten steps or so, during which the threshold moves by one to
+// three bins per step (an eighth of an octave each), not quite steadily, and a sparse layer's can
+// jump four bins up out of rest.  A deeper start costs more candidates (under error feedback the
+// entries pile up just below the threshold: 22 % of them lie within one and a half bins below it
+// at K = 10 %, 30 % within three and a half), a missed guess a second read of Delta and a slow
+// decision for that layer.
+constexpr int kGuessBins = 10, kGuessCalmBelow = 1, kGuessMovingBelow = 3, kGuessRestSteps = 2;
+constexpr int kSub2 = kGuessBins * kL2Bins;  // a tile's level-2 counts of the guessed bins
 __device__ __forceinline__ uint32_t make_guess(int lo, int nb) {
   return (uint32_t)max(1, min(kHistBins - nb, lo)) | ((uint32_t)nb << 16);
 }
@@ -783,7 +787,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
     if (tid == 0) {
       const uint32_t bo = out[0];
       // (the memory will adapt to the new level for some steps: a wide guess)
-      ws.guess[wl * 2 + (1 - lv)] = (bo == 0u) ? kGuessZero : make_guess((int)bo - kGuessWide / 2, kGuessWide);
+      ws.guess[wl * 2 + (1 - lv)] = (bo == 0u) ? kGuessZero : make_guess((int)bo - kGuessMovingBelow, kGuessBins);
     }
     __syncthreads();
   }
@@ -1213,19 +1217,20 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
     // Next step's guess at this level: adjacent bins centred on b1, or -- while the threshold is
     // moving (the steps after a level switch, when the memory adapts) -- on the bin extrapolated
     // from the last two steps; narrow when the last two steps did not move, wide otherwise.
-    // b1hist: (b1 | (last move + 64) << 16, step)
+    // b1hist: (b1 | (last move + 64) << 16 | steps at rest << 24, step)
     const uint2 prev = prev_hist;
     const bool consecutive = prev.y + 1u == step_id;
     int v = consecutive ? (int)b1 - (int)(prev.x & 0xffffu) : 0;
     v = max(-64, min(64, v));
-    const int pv = consecutive ? (int)(prev.x >> 16) - 64 : 0;   // the move before
-    ws.b1hist[wl * 2 + lv] = make_uint2(b1 | ((uint32_t)(v + 64) << 16), step_id);
-    // a single step of one bin may well be taken back; larger moves and moves that go on in one
-    // direction are followed
-    const bool follow = v > 1 || v < -1 || (v != 0 && (v > 0) == (pv > 0) && pv != 0);
-    const int centre = (int)b1 + (follow ? v : 0);
-    const int nb = (consecutive && v == 0 && pv == 0) ? kGuessNarrow : kGuessWide;   // the first step at a level: wide
-    ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero : make_guess(centre - nb / 2, nb);
+    // steps in a row without a move (two equal steps right after a level switch are no rest yet)
+    const int rest = (consecutive && v == 0) ? min(15, (int)(prev.x >> 24) + 1) : 0;
+    ws.b1hist[wl * 2 + lv] = make_uint2(b1 | ((uint32_t)(v + 64) << 16) | ((uint32_t)rest << 24), step_id);
+    // A move down is followed at once (the guess must start below the threshold); a move up only
+    // with a lag of two bins: the guess reaches four to six bins above its centre anyway, and a
+    // jump up is often followed by smaller steps.
+    const int centre = (int)b1 + (v < 0 ? v : max(0, v - 2));
+    const int below = rest >= kGuessRestSteps ? kGuessCalmBelow : kGuessMovingBelow;
+    ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero : make_guess(centre - below, kGuessBins);
   }
 }
 
