@@ -1214,9 +1214,7 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
   }
   if (tid == 0) {
     sp->T = T; sp->ktie = ktie; sp->alleq = alleq; sp->mode = 0u;
-    // Next step's guess at this level: adjacent bins centred on b1, or -- while the threshold is
-    // moving (the steps after a level switch, when the memory adapts) -- on the bin extrapolated
-    // from the last two steps; narrow when the last two steps did not move, wide otherwise.
+    // Next step's guess at this level, from the bin this step ended in and the last two moves.
     // b1hist: (b1 | (last move + 64) << 16 | steps at rest << 24, step)
     const uint2 prev = prev_hist;
     const bool consecutive = prev.y + 1u == step_id;
@@ -1229,7 +1227,11 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
     // with a lag of two bins: the guess reaches four to six bins above its centre anyway, and a
     // jump up is often followed by smaller steps.
     const int centre = (int)b1 + (v < 0 ? v : max(0, v - 2));
-    const int below = rest >= kGuessRestSteps ? kGuessCalmBelow : kGuessMovingBelow;
+    // how far below the centre the guess starts: one bin at rest, two while the move is steady (it
+    // changed by at most one bin from the step before), three otherwise (the first steps at a level)
+    const int pv = consecutive ? (int)((prev.x >> 16) & 0xffu) - 64 : 0;
+    const bool steady = consecutive && abs(v - pv) <= 1;
+    const int below = rest >= kGuessRestSteps ? kGuessCalmBelow : (steady ? kGuessMovingBelow - 1 : kGuessMovingBelow);
     ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero : make_guess(centre - below, kGuessBins);
   }
 }
