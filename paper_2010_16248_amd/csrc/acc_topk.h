@@ -176,7 +176,7 @@ constexpr int kCandCap = 1024;                   // candidates of a wave quarter
 constexpr int kCandLds = 512;                    // a wave's list in LDS
 constexpr int kCandLdsSlots = kCandLds + kWave;  // + one slot per lane that takes the writes of unselected elements
 
-struct CandList { uint32_t* val; uint16_t* idx; };
+struct CandList { uint32_t* val; uint16_t* idx; uint4* qi; };   // qi: the workgroup's four quarter records
 
 // n_lds: entries in the LDS list; n_out: entries already written out (both wave-uniform);
 // v_hi, v_nz: per lane, summed over the wave when the quarter is finished.
@@ -200,8 +200,10 @@ __device__ __forceinline__ void cand_write_out(const Ws& ws, int64_t qslot, cons
   __builtin_amdgcn_wave_barrier();                          // the list is complete (LDS is in order per wave)
   const uint32_t n_full = final ? c.n_lds : (c.n_lds & ~(uint32_t)(kWave - 1));
   for (uint32_t t0 = 0u; t0 < n_full; t0 += kWave) {
+    // the last chunk is written whole as well (its tail is whatever the LDS list holds there, and is
+    // never read): a store that fills only part of a 64-byte line is a read-modify-write in memory
     const uint32_t t = t0 + lane, chunk = (c.n_out + t0) >> 6;
-    if (t < n_full && chunk < (uint32_t)(kCandCap / kWave)) {
+    if (chunk < (uint32_t)(kCandCap / kWave)) {
       // plain stores: the counting kernel and the compaction read the lists within microseconds
       // (streaming stores here cost the compaction 6 us on ResNet-18 shapes)
       const int64_t a = cand_at(ws, qslot, chunk, lane);
@@ -284,13 +286,18 @@ __device__ __forceinline__ void stage_one_bin(const CandList& cl, uint32_t* sub2
 
 // qinfo of the quarter: {entries above the staged bin (one-bin lists; 0 for candidate lists, which
 // hold those entries), staged entries (the full count, also beyond kCandCap), 0, exact zeros
-// (one-bin lists)}.  Returns the number of exact zeros (the same value in every lane).
+// (one-bin lists)}.  Returns the number of exact zeros (the same value in every lane).  The record
+// goes to LDS; after a barrier qinfo_flush writes the tile's four records as one 64-byte line.
 __device__ __forceinline__ uint32_t stage_finish(const Ws& ws, int64_t qslot, const CandList& cl, StageCounts& c,
-                                                 int lane) {
+                                                 int wave, int lane) {
   cand_write_out(ws, qslot, cl, c, lane, true);
   const uint32_t n_hi = wave_sum_u32(c.v_hi), nz = wave_sum_u32(c.v_nz);
-  if (lane == 0) ws.qinfo[qslot] = make_uint4(n_hi, c.n_out, 0u, nz);
+  if (lane == 0) cl.qi[wave] = make_uint4(n_hi, c.n_out, 0u, nz);
   return nz;
+}
+
+__device__ __forceinline__ void qinfo_flush(const Ws& ws, int64_t qslot_tile, const CandList& cl) {
+  if (threadIdx.x < 4) ws.qinfo[qslot_tile + threadIdx.x] = cl.qi[threadIdx.x];
 }
 
 // What every group of a quarter needs from the selection of its (worker, layer): t_all = T when
@@ -481,8 +488,9 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
     __syncthreads();
   }
   if (SELECT) {
-    stage_finish(ws, qslot_mine, cl, cnt, lane);
+    stage_finish(ws, qslot_mine, cl, cnt, wave, lane);
     __syncthreads();
+    qinfo_flush(ws, qslot_mine - wave, cl);
     uint32_t* gh = ws.hist1 + wl * kHistBins;                // bin 0 stays empty: the pick kernel derives it
     for (int b = tid; b < kHistBins; b += kFlatThreads) {
       const uint32_t h = hist[b];
@@ -503,12 +511,13 @@ __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const Gr
   __shared__ uint16_t cand_idx[4][kCandLdsSlots];
   __shared__ uint32_t sub2[kSub2];
   __shared__ double red4[4];
+  __shared__ uint4 qi[4];
   const int w = w0 + blockIdx.y;
   const FlatTile ft = ws.ftiles[blockIdx.x];
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
   const int lw = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const CandList cl = {cand_val[lw], cand_idx[lw]};
+  const CandList cl = {cand_val[lw], cand_idx[lw], qi};
   // the layer's "compact from Delta" flag of the last step is cleared before this step's
   // decision kernels (which set it) run
   if (w == 0 && ft.start == 0 && threadIdx.x == 0) ws.lflag[ft.layer] = 0u;
@@ -557,10 +566,11 @@ __device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile
     cand_make_room(ws, qslot, cl, cnt, lane);
     cur = nxt;
   }
-  const uint32_t nz = stage_finish(ws, qslot, cl, cnt, lane);
+  const uint32_t nz = stage_finish(ws, qslot, cl, cnt, wave, lane);
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   if (lane == 0 && nz) atomicAdd(&ws.sel[wl].zeros, nz);
   __syncthreads();
+  qinfo_flush(ws, qslot - wave, cl);
   // the tile's level-2 counts of b1 go straight into the layer's (cleared by the pick kernel)
   if (tid < kL2Bins && sub2[tid]) atomicAdd(&ws.hist2m[wl * kL2Bins + tid], sub2[tid]);
 }
@@ -569,9 +579,10 @@ __device__ __forceinline__ void restage_tile(const Ws& ws, int w, const FlatTile
 
 // The first kEagerChunks 64-entry chunks of a quarter's list are requested together with its
 // counts (the slot always exists; what lies past the count is ignored later), the rest once the
-// count is there and only if it reaches them: a quarter lists 40 to 350 candidates on Gaussian or
-// Laplacian gradients at K = 1 % to 10 %.
-constexpr int kEagerChunks = 8;
+// count is there and only as far as it reaches: a quarter lists 60 to 500 candidates on Gaussian
+// or Laplacian gradients at K = 1 % to 10 %, and chunks requested for nothing are read from memory
+// all the same (eight early chunks were 0.8 GB per step on the LSTM set at K = 1 %).
+constexpr int kEagerChunks = 2;
 struct QuarterHead {
   uint4 info;                      // see stage_finish
   uint32_t chunk[kEagerChunks];    // the calling lane's entries of the first chunks
@@ -611,8 +622,10 @@ __device__ __forceinline__ uint32_t for_quarter_keys(const Ws& ws, const LayerDe
     for (uint32_t t0 = kEagerChunks * kWave; t0 < n; t0 += U * kWave) {
       uint32_t raw[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        raw[u] = ws.cand_val[cand_at(ws, qslot, min(t0 / kWave + u, (uint32_t)(kCandCap / kWave - 1)), lane)];
+      for (int u = 0; u < U; ++u) {
+        raw[u] = 0u;
+        if (n > t0 + u * kWave) raw[u] = ws.cand_val[cand_at(ws, qslot, t0 / kWave + u, lane)];   // uniform condition
+      }
 #pragma unroll
       for (int u = 0; u < U; ++u)
         if (n > t0 + u * kWave) visit(raw[u], t0 + u * kWave + lane);                         // uniform condition
@@ -831,38 +844,48 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   }
 }
 
-__global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
-  __shared__ uint32_t hist[kHistBins];
-  __shared__ uint32_t out[3], scratch[4];
-  __shared__ uint32_t cand_val[4][kCandLdsSlots];           // a missed layer: its tiles are staged again here
-  __shared__ uint16_t cand_idx[4][kCandLdsSlots];
-  __shared__ uint32_t sub2[kL2Bins];
-  const int w = w0 + blockIdx.y;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const FlatTile ft = ws.ftiles[blockIdx.x];
+// A workgroup takes kCountTiles consecutive tiles, a wave one quarter of each; everything the tiles
+// need is requested before the first of them is looked at.  (Two tiles per workgroup are no faster
+// than one, on 100 000 tiles as on 5 000.)
+constexpr int kCountTiles = 1;
+
+struct CountLds {
+  // One block for the two rare paths, which are never at work in a workgroup at the same time: the
+  // staging lists of a missed layer's tile (values, then offsets), or the histogram of the bin-0 pick.
+  static constexpr int kListWords = 4 * kCandLdsSlots;
+  static constexpr int kRareWords = kListWords + kListWords / 2 > kHistBins ? kListWords + kListWords / 2 : kHistBins;
+  uint32_t* rare;
+  uint32_t *out, *scratch, *sub2;
+  uint4* qi;
+};
+
+struct CountTile { FlatTile ft; int64_t qslot; QuarterHead qh; uint32_t b1, b2, mode; int ntiles; };
+
+__device__ __forceinline__ void count3_tile(const Ws& ws, int w, const CountTile& t, const CountLds& lds,
+                                            int wave, int lane) {
+  const FlatTile& ft = t.ft;
+  if (t.ntiles == 1) return;                               // decided by the last pick kernel
+  const LayerDev& L = ws.layers[ft.layer];
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   SelState* sp = ws.sel + wl;
   const int tl = ft.start >> kTileShift;
-  const int64_t qslot = (int64_t)w * ws.q_stride + ft.qslot0 + wave;
-  // the list is requested before the layer's entry and its state have arrived
-  const QuarterHead qh = load_quarter_head(ws, qslot, lane);
-  const LayerDev& L = ws.layers[ft.layer];
-  if (L.ntiles == 1) return;                               // decided by the last pick kernel
-  const uint32_t b1 = sp->b1, mode = sp->mode;
-  uint32_t b2 = sp->b2;
-  if (mode == 1u) {                                        // uniform over the workgroup
+  const uint32_t b1 = t.b1;
+  uint32_t b2 = t.b2;
+  if (t.mode == 1u) {                                      // uniform over the workgroup
     // The guess missed: nothing useful was staged.  This tile's keys of b1 are staged now (one
     // more read of Delta) with their level-2 counts; the layer's pick kernel takes it from there.
     const TileGeom tg = tile_geom(L, ft);
-    const CandList cl = {cand_val[wave], cand_idx[wave]};
-    if (tg.aligned) restage_tile<true>(ws, w, ft, L, tg, b1, cl, sub2);
-    else restage_tile<false>(ws, w, ft, L, tg, b1, cl, sub2);
+    const CandList cl = {lds.rare + wave * kCandLdsSlots,
+                         reinterpret_cast<uint16_t*>(lds.rare + CountLds::kListWords) + wave * kCandLdsSlots, lds.qi};
+    if (tg.aligned) restage_tile<true>(ws, w, ft, L, tg, b1, cl, lds.sub2);
+    else restage_tile<false>(ws, w, ft, L, tg, b1, cl, lds.sub2);
+    __syncthreads();                                       // the block of LDS may serve the next tile
     return;
   }
-  if (mode == 2u) {
+  if (t.mode == 2u) {
     // bin 0 guessed and found: its non-zero keys were staged and their level-2 counts summed
     const int tid = threadIdx.x;
+    uint32_t* hist = lds.rare;
     const uint32_t zeros = sp->zeros;
     for (int b = tid; b < kHistBins; b += kFlatThreads) {
       uint32_t h = (b < kL2Bins) ? ws.hist2m[wl * kL2Bins + b] : 0u;
@@ -871,15 +894,17 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
     }
     __syncthreads();
     const uint32_t need2 = sp->need2;
-    pick_bin(hist, need2, out, scratch);
-    b2 = out[0];
-    if (tl == 0 && tid == 0) { sp->b2 = b2; sp->need3 = need2 - out[1]; }
+    pick_bin(hist, need2, lds.out, lds.scratch);
+    b2 = lds.out[0];
+    const uint32_t above2 = lds.out[1];
+    __syncthreads();                                       // out[] and the block of LDS may serve the next tile
+    if (tl == 0 && tid == 0) { sp->b2 = b2; sp->need3 = need2 - above2; }
   }
   // more candidates than the list holds: the compaction of this layer reads Delta
-  if (lane == 0 && rfl(qh.info.y) > (uint32_t)kCandCap) atomicOr(&ws.lflag[ft.layer], 1u);
-  uint32_t* list = ws.qlist + qslot * kQListCap;
+  if (lane == 0 && rfl(t.qh.info.y) > (uint32_t)kCandCap) atomicOr(&ws.lflag[ft.layer], 1u);
+  uint32_t* list = ws.qlist + t.qslot * kQListCap;
   uint32_t n_gt = 0, n_in = 0;                             // wave-uniform
-  const uint32_t above = for_quarter_keys(ws, L, w, tl, wave, qslot, qh, b1, lane, [&](uint32_t key, bool valid) {
+  const uint32_t above = for_quarter_keys(ws, L, w, tl, wave, t.qslot, t.qh, b1, lane, [&](uint32_t key, bool valid) {
     const uint32_t bb = bin2_of(key);
     const uint64_t mv = ballot64(valid);
     n_gt += (uint32_t)__popcll(ballot64(bb > b2) & mv);
@@ -890,7 +915,37 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
       n_in += (uint32_t)__popcll(m2);
     }
   });
-  if (lane == 0) { ws.gtq[qslot] = above + n_gt; ws.eqq[qslot] = n_in; }
+  if (lane == 0) { ws.gtq[t.qslot] = above + n_gt; ws.eqq[t.qslot] = n_in; }
+}
+
+__global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
+  __shared__ __attribute__((aligned(16))) uint32_t rare[CountLds::kRareWords];
+  __shared__ uint32_t out[3], scratch[4];
+  __shared__ uint32_t sub2[kL2Bins];
+  __shared__ uint4 qi[4];
+  const CountLds lds = {rare, out, scratch, sub2, qi};
+  const int w = w0 + blockIdx.y;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int tile0 = (int)blockIdx.x * kCountTiles;
+  CountTile t[kCountTiles];
+#pragma unroll
+  for (int u = 0; u < kCountTiles; ++u) t[u].ft = ws.ftiles[min(tile0 + u, ws.n_ftiles - 1)];
+  // the lists are requested before the layers' entries and their states have arrived
+#pragma unroll
+  for (int u = 0; u < kCountTiles; ++u) {
+    t[u].qslot = (int64_t)w * ws.q_stride + t[u].ft.qslot0 + wave;
+    t[u].qh = load_quarter_head(ws, t[u].qslot, lane);
+  }
+#pragma unroll
+  for (int u = 0; u < kCountTiles; ++u) {
+    const SelState* sp = ws.sel + (int64_t)w * ws.L + t[u].ft.layer;
+    t[u].b1 = sp->b1; t[u].b2 = sp->b2; t[u].mode = sp->mode;
+    t[u].ntiles = ws.layers[t[u].ft.layer].ntiles;
+  }
+#pragma unroll
+  for (int u = 0; u < kCountTiles; ++u)
+    if (tile0 + u < ws.n_ftiles) count3_tile(ws, w, t[u], lds, wave, lane);   // uniform over the workgroup
 }
 
 // Two sizes of the last pick kernel: kLdsList keys of bin (b1, b2) of a layer gathered in LDS

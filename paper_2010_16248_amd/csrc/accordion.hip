@@ -443,7 +443,7 @@ int launch_topk_select(acc_ctx* c, int w0, int nw) {
   const Ws& ws = c->ws;
   ACC_LAUNCH(c, topk_ef_hist_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, c->grads, w0);
   ACC_LAUNCH(c, topk_pick12_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0);
-  ACC_LAUNCH(c, topk_count3_kernel, dim3(ws.n_ftiles, nw), dim3(256), ws, w0);
+  ACC_LAUNCH(c, topk_count3_kernel, dim3((ws.n_ftiles + kCountTiles - 1) / kCountTiles, nw), dim3(256), ws, w0);
   ACC_LAUNCH(c, topk_pick3_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
   if (c->plan.pick3_big) ACC_LAUNCH(c, topk_pick3_big_kernel, dim3(ws.L, nw), dim3(kPickThreads), ws, w0, c->step_id);
   return ACC_OK;
