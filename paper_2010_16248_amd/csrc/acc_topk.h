@@ -57,6 +57,14 @@ constexpr int kL2Bins = 64;              // level 2: key bits 19..14
 // decision for that layer.
 constexpr int kGuessBins = 10, kGuessCalmBelow = 1, kGuessMovingBelow = 3, kGuessRestSteps = 2;
 constexpr int kSub2 = kGuessBins * kL2Bins;  // a tile's level-2 counts of the guessed bins
+// Where a large part is kept (more than a sixth: the paper's own levels of 25 % and 99 %) the
+// entries above the threshold are too many to list: the guess is then a BAND of kBandBins bins, the
+// first pass lists the keys inside the band only and counts the entries above it, and the
+// compaction reads Delta.  A guess of fewer than kGuessBins bins means exactly that.
+constexpr int kBandBins = 8, kBandKeepDiv = 6;
+__device__ __forceinline__ int guess_bins_for(uint32_t k, uint32_t n) {
+  return (uint64_t)k * kBandKeepDiv > (uint64_t)n ? kBandBins : kGuessBins;
+}
 __device__ __forceinline__ uint32_t make_guess(int lo, int nb) {
   return (uint32_t)max(1, min(kHistBins - nb, lo)) | ((uint32_t)nb << 16);
 }
@@ -234,7 +242,7 @@ __device__ __forceinline__ void cand_make_room(const Ws& ws, int64_t qslot, cons
 // per component.  i_rel: offset of the lane's first element inside the quarter.  The level-2 counts of
 // the kGuessBins guessed bins go to sub2.  Every ballot is taken from a single compare and
 // combined with the other masks in scalar registers; the list is in index order.
-template <bool MASKED>
+template <bool MASKED, bool BAND>
 __device__ __forceinline__ void stage_candidates(const CandList& cl, uint32_t* sub2, StageCounts& c,
                                                  uint64_t mv0, uint64_t mv1, uint64_t mv2, uint64_t mv3,
                                                  const float4& d, uint32_t glo, uint32_t gnb, uint32_t i_rel,
@@ -245,8 +253,16 @@ __device__ __forceinline__ void stage_candidates(const CandList& cl, uint32_t* s
   for (int x = 0; x < 4; ++x) {
     key[x] = key_of(comp(d, x));
     rel[x] = (key[x] >> 20) - glo;
-    m[x] = ballot64((int32_t)rel[x] >= 0);
-    if (MASKED) m[x] &= (x == 0 ? mv0 : x == 1 ? mv1 : x == 2 ? mv2 : mv3);
+    const uint64_t mvx = (x == 0 ? mv0 : x == 1 ? mv1 : x == 2 ? mv2 : mv3);
+    if (BAND) {
+      // inside the band: listed; above it: counted (a bin below glo wraps to a huge rel)
+      m[x] = ballot64(rel[x] < gnb);
+      const bool above = (int32_t)rel[x] >= (int32_t)gnb;
+      c.v_hi += (above && (!MASKED || lane_bit(mvx))) ? 1u : 0u;
+    } else {
+      m[x] = ballot64((int32_t)rel[x] >= 0);
+    }
+    if (MASKED) m[x] &= mvx;
   }
   if ((m[0] | m[1] | m[2] | m[3]) == 0) return;              // wave-uniform
   uint32_t place = c.n_lds, total = 0u;
@@ -405,6 +421,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   uint32_t glo = 0x7ffffff0u, gnb = 0u;                    // no bin matches without a guess
   if (SELECT && !ZB && guess != kNoGuess) { glo = guess_lo(guess); gnb = guess_nb(guess); }
+  const bool band = gnb != 0u && gnb < (uint32_t)kGuessBins;   // uniform over the workgroup
   // two groups per lane are requested before anything else
   constexpr int U = 2;   // (one group is as fast where the memory fits the caches, three or four are no faster anywhere)
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -462,7 +479,10 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
             hist_add(hist, (key >> 20) != 0u, key >> 20);
             if (ZB) stage_one_bin(cl, sub2, cnt, ~0ull, true, key, 0u, lane);
           }
-          if (!ZB) stage_candidates<false>(cl, sub2, cnt, 0ull, 0ull, 0ull, 0ull, d, glo, gnb, i_rel, lane);
+          if (!ZB) {
+            if (band) stage_candidates<false, true>(cl, sub2, cnt, 0ull, 0ull, 0ull, 0ull, d, glo, gnb, i_rel, lane);
+            else stage_candidates<false, false>(cl, sub2, cnt, 0ull, 0ull, 0ull, 0ull, d, glo, gnb, i_rel, lane);
+          }
         } else {
           const uint64_t m_span = ballot64(qa);
           uint64_t mv[4];
@@ -474,7 +494,10 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
             hist_add(hist, valid && (key >> 20) != 0u, key >> 20);
             if (ZB) stage_one_bin(cl, sub2, cnt, mv[c], valid, key, 0u, lane);
           }
-          if (!ZB) stage_candidates<true>(cl, sub2, cnt, mv[0], mv[1], mv[2], mv[3], d, glo, gnb, i_rel, lane);
+          if (!ZB) {
+            if (band) stage_candidates<true, true>(cl, sub2, cnt, mv[0], mv[1], mv[2], mv[3], d, glo, gnb, i_rel, lane);
+            else stage_candidates<true, false>(cl, sub2, cnt, mv[0], mv[1], mv[2], mv[3], d, glo, gnb, i_rel, lane);
+          }
         }
         cand_make_room(ws, qslot_mine, cl, cnt, lane);
       }
@@ -800,7 +823,8 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
     if (tid == 0) {
       const uint32_t bo = out[0];
       // (the memory will adapt to the new level for some steps: a wide guess)
-      ws.guess[wl * 2 + (1 - lv)] = (bo == 0u) ? kGuessZero : make_guess((int)bo - kGuessMovingBelow, kGuessBins);
+      ws.guess[wl * 2 + (1 - lv)] = (bo == 0u) ? kGuessZero
+          : make_guess((int)bo - kGuessMovingBelow, guess_bins_for(k_other, (uint32_t)L.rows * (uint32_t)L.cols));
     }
     __syncthreads();
   }
@@ -813,8 +837,9 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   if (tid == 0) {
     sp->b1 = b1; sp->need2 = need2; sp->k = k; sp->side = side; sp->zeros = 0u;
     sp->mode = hit ? 0u : (zhit ? 2u : 1u);
-    // the candidate lists of this layer cannot serve the compaction: it reads Delta instead
-    if (!hit) atomicOr(&ws.lflag[li], 1u);                 // cleared by the next step's first pass
+    // the candidate lists of this layer cannot serve the compaction (a miss, or a band, which does
+    // not list what lies above it): it reads Delta instead
+    if (!hit || guess_nb(guess) < (uint32_t)kGuessBins) atomicOr(&ws.lflag[li], 1u);   // cleared by the next step's first pass
     if (!hit && !zhit) atomicAdd(&ws.stats[0], 1ull);      // layers re-staged (diagnostic counter)
   }
   if (zhit) {
@@ -1287,7 +1312,8 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
     const int pv = consecutive ? (int)((prev.x >> 16) & 0xffu) - 64 : 0;
     const bool steady = consecutive && abs(v - pv) <= 1;
     const int below = rest >= kGuessRestSteps ? kGuessCalmBelow : (steady ? kGuessMovingBelow - 1 : kGuessMovingBelow);
-    ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero : make_guess(centre - below, kGuessBins);
+    ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero
+        : make_guess(centre - below, guess_bins_for((uint32_t)L.k[lv], (uint32_t)L.rows * (uint32_t)L.cols));
   }
 }
 
