@@ -61,11 +61,14 @@ struct SelState {
   uint32_t b2;        // level-2 bin (key bits 19..14) within b1
   uint32_t need3;     // entries still to be taken from bin (b1, b2)
   uint32_t zeros;     // exact zeros of the layer (filled in when b1 == 0)
-  uint32_t pad;
+  uint32_t bin0;      // entries of level-1 bin 0 (exact zeros and the smallest denormals) in this step's Delta
   uint32_t k;         // kept count used by this step
   uint32_t T;         // exact threshold key (the k-th largest)
   uint32_t ktie;      // how many entries with key == T are selected (lowest indices first)
   uint32_t alleq;     // 1: every entry with key == T is selected
+  uint32_t fresh_nnz; // entries outside bin 0 in the last step whose threshold lay in bin 0 (everything
+                      //   non-zero was kept then, so these were the gradient's own); 0: no such step yet.
+                      //   Only steers the next guess.
 };
 
 struct GradPtrs { const float* p[kMaxW]; };

@@ -835,7 +835,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   const bool zhit = guess == kGuessZero && b1 == 0u;
   const uint32_t side = hit ? b1 - glo : 0u;
   if (tid == 0) {
-    sp->b1 = b1; sp->need2 = need2; sp->k = k; sp->side = side; sp->zeros = 0u;
+    sp->b1 = b1; sp->need2 = need2; sp->k = k; sp->side = side; sp->zeros = 0u; sp->bin0 = hist[0];
     sp->mode = hit ? 0u : (zhit ? 2u : 1u);
     // the candidate lists of this layer cannot serve the compaction (a miss, or a band, which does
     // not list what lies above it): it reads Delta instead
@@ -1312,8 +1312,17 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
     const int pv = consecutive ? (int)((prev.x >> 16) & 0xffu) - 64 : 0;
     const bool steady = consecutive && abs(v - pv) <= 1;
     const int below = rest >= kGuessRestSteps ? kGuessCalmBelow : (steady ? kGuessMovingBelow - 1 : kGuessMovingBelow);
-    ws.guess[wl * 2 + lv] = (b1 == 0u) ? kGuessZero
-        : make_guess(centre - below, guess_bins_for((uint32_t)L.k[lv], (uint32_t)L.rows * (uint32_t)L.cols));
+    // A sparse layer of which more is kept than the gradient brings in: once the memory has been
+    // emptied down to less than k non-zero entries the threshold drops to zero.  This step leaves
+    // nnz - k of its non-zero entries behind and the next gradient adds about as many as it did
+    // the last time everything non-zero was kept.
+    const uint32_t n_layer = (uint32_t)L.rows * (uint32_t)L.cols, k_now = (uint32_t)L.k[lv];
+    const uint32_t nnz = n_layer - min(sp->bin0, n_layer);
+    uint32_t fresh = sp->fresh_nnz;
+    if (b1 == 0u && nnz != 0u) { fresh = nnz; sp->fresh_nnz = nnz; }
+    const bool runs_dry = fresh != 0u && (uint64_t)(nnz - min(k_now, nnz)) + fresh <= (uint64_t)k_now;
+    ws.guess[wl * 2 + lv] = (b1 == 0u || runs_dry) ? kGuessZero
+        : make_guess(centre - below, guess_bins_for(k_now, n_layer));
   }
 }
 

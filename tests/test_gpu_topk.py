@@ -230,6 +230,41 @@ def test_threshold_among_exact_zeros_is_guessed_too():
     gpu.destroy()
 
 
+def test_a_sparse_layer_running_dry_is_seen_coming():
+    """A sparse gradient (3 % non-zero) whose memory has filled up while little was kept: the first
+    step that keeps 10 % again finds more than 10 % non-zero entries (threshold above zero) and
+    empties the memory to below that, so from the second step on the threshold is zero.  The step
+    that decides the first sees it coming (what it leaves behind plus what a gradient brought in
+    when everything non-zero was kept last time is less than k) and guesses bin 0 for the second:
+    nothing is staged twice there; every step is exact."""
+    print("case sparse layer runs dry", flush=True)
+    shapes = [(1, 6 * 8192 + 5, 0), (40, 1031, 1)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 2
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    rng = np.random.default_rng(23)
+    restaged = []
+    for step in range(12):
+        if step in (2, 4, 10):
+            # no history: critical (K 10 % stays); stationary norms: K 1 % from step 4; a
+            # learning-rate decay: K 10 % again from step 10
+            lr_next = 0.01 if step == 10 else 0.1
+            ref = ora.detect_regime(0.1, lr_next)
+            gpu.detect_regime(0.1, lr_next)
+            assert np.array_equal(gpu.get_levels(), ref)
+        grads = [(rng.standard_normal(N) * (rng.random(N) < 0.03)).astype(np.float32) for _ in range(W)]
+        _check_step(gpu, ora, grads, f"step {step}", check_state=(step in (5, 11)))
+        restaged.append(gpu.topk_stats()[0])
+    per_step = np.diff([0] + restaged)
+    assert list(ora.level) == [1, 1]
+    assert per_step[1:4].sum() == 0, per_step               # threshold zero, guessed
+    assert per_step[10] == 0, per_step                      # back at K 10 %: more than 10 % non-zero by now
+    assert per_step[11] == 0, per_step                      # and dry again, seen coming
+    gpu.destroy()
+
+
+
 def test_large_tie_classes_take_the_sweeps_and_stay_exact():
     """Quantised values in layers of several tiles: the tie class of the threshold is far larger
     than the per-quarter key lists, for several steps in a row.  While the threshold jumps from
