@@ -2,15 +2,21 @@
 """Benchmark of the Accordion gradient-compression hot path on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic gradients for all W
-simulated workers: error-feedback add, gradient accumulation, compression at the layer's current
-level (TopK select + payload + residual, or the PowerSGD products, orthogonalisation and
-residual), the mean over workers, and -- every `window` steps -- the per-layer norms and the
-critical-regime decision that picks the next window's levels.  Gradients are resident in HBM
-before the timed region starts (a pool of distinct seeded batches, rotated).
+simulated workers: error-feedback add, gradient accumulation (with the accumulated gradient's
+sums of squares), compression at the layer's current level (TopK select + payload + residual, or
+the PowerSGD products, orthogonalisation and residual) and the mean over workers.  Every
+`window` steps -- max(2, min(--window, steps // 4)), so at least four times at any --steps -- the
+per-layer norms are taken and the critical-regime decision picks the next window's levels; every
+second window ends with a learning-rate decay, so the levels alternate and both of them, and
+the steps right after a switch, are timed.  Gradients are resident in HBM before the timed region
+starts (a pool of distinct seeded batches, rotated).
 
-Prints ONE JSON line: gradient GB/s = 4 * N * W / t_step, plus the roofline of the dominant
-kernel (algorithmic bytes / its HIP-event duration against 8 TB/s) and the CPU oracle's rate on
-a bounded sample of the same workload.
+Prints ONE JSON line: gradient GB/s = 4 * N * W / t_step; how many regime tests and steps at each
+level the timed region held; the roofline of the dominant kernel (algorithmic bytes / its
+HIP-event duration against 8 TB/s; counted HBM traffic from profiles/ if it was taken on the
+kernel sources this run uses); the whole step's algorithmic bandwidth; the same figures for the
+other target workloads (`other_workloads`); and the CPU oracle's rate on a bounded sample of the
+headline workload.
 """
 from __future__ import annotations
 

@@ -281,10 +281,11 @@ int32_t accordion_get_factors(acc_ctx* ctx, int32_t layer, float* p_hat_host, fl
 int32_t accordion_payload_words(acc_ctx* ctx, int64_t* last_step, int64_t* cumulative);
 
 /* TopK diagnostics since init (they describe which path the selection took, never its result):
- * restaged_layers = (worker, layer) pairs whose threshold bin was not among the two bins the
- * error-feedback pass had staged on a guess, so that Delta was read once more for them;
- * swept_layers = pairs with a tie class too large for the per-quarter key lists, decided by
- * sweeps of one workgroup (slow). */
+ * restaged_layers = (worker, layer) pairs whose threshold bin lay outside the bins the
+ * error-feedback pass had worked on, on a guess: Delta was read once more for them and the
+ * layer was decided by sweeps of one workgroup (slow);
+ * swept_layers = pairs whose guess held but whose tie class was too large for the per-quarter
+ * key lists, decided by the same sweeps. */
 int32_t accordion_topk_stats(acc_ctx* ctx, int64_t* restaged_layers, int64_t* swept_layers);
 
 /* Overlap of the kept coordinates of two workers in the last step (Sec. 4.3: how much the

@@ -330,7 +330,7 @@ class Accordion:
         return int(a.value), int(b.value)
 
     def topk_stats(self) -> Tuple[int, int]:
-        """(layers re-staged after a missed guess, layers decided by sweeps) since init."""
+        """(layers whose guess missed, layers sent to the sweeps by a large tie class) since init."""
         a, b = C.c_int64(0), C.c_int64(0)
         _check(self._lib, self.ctx, self._lib.accordion_topk_stats(self.ctx, C.byref(a), C.byref(b)))
         return int(a.value), int(b.value)

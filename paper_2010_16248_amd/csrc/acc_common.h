@@ -116,7 +116,7 @@ struct Ws {
   uint32_t* hist2m;            // W x L x 64: level-2 counts of b1 of a layer whose guess missed
   uint32_t* lflag;             // L: nonzero = this step's compaction of the layer reads Delta (a guess missed, a
                                //   candidate list overflowed), not the candidate lists
-  uint2* b1hist;               // W x L x 2 (level): {b1 | (last move + 64) << 16, step number} of the last step at this level
+  uint2* b1hist;               // W x L x 2 (level): {b1 | (last move + 64) << 16 | steps at rest << 24, step number} of the last step at this level
   uint32_t* guess;             // W x L x 2 (level): lowest of the adjacent level-1 bins staged by pass A
   uint4* qinfo;                // W x q_stride: per wave quarter {entries above the staged bin (one-bin lists),
                                //   listed entries, 0, exact zeros (one-bin lists)}

@@ -1,30 +1,36 @@
 // TopK kernels: exact per-layer selection of the k entries with the largest |Delta|
 // (ties: lower flat index) by a radix select on the 31 magnitude bits, organised so that Delta
-// is streamed twice per step: once when it is formed and once when the selected entries are
-// written out.  Key bits: level 1 = 30..20 (2048 bins), level 2 = 19..14 (64), level 3 = 13..6
-// (256), level 4 = 5..0 (64).
+// is streamed once per step, when it is formed; the passes after that work on lists of CANDIDATES
+// that pass leaves.  Key bits: level 1 = 30..20 (2048 bins), level 2 = 19..14 (64), level 3 =
+// 13..6 (256), level 4 = 5..0 (64).
 //
-//   A   topk_ef_hist   Delta = g + e (in place), A += g (worker 0), level-1 histogram per
-//                      (worker, layer).  The level-1 bin b1 that will hold the k-th largest key is
-//                      not known yet, so the pass stages the keys of kGuessBins GUESSED adjacent
-//                      bins (around the bin the previous step at this level ended in) per wave
-//                      quarter of a tile, counts the entries above them and the exact zeros, and
-//                      writes the tile's level-2 counts of the guessed bins.
+//   A   topk_ef_hist   Delta = g + e (in place; the entries the previous step kept are dropped
+//                      from e first), A += g (worker 0) with its sum of squares, level-1 histogram
+//                      per (worker, layer).  The level-1 bin b1 that will hold the k-th largest key
+//                      is not known yet, so the pass works on a GUESS (from the previous steps at
+//                      this level): every entry at or above the lowest guessed bin goes into its
+//                      wave quarter's candidate list as (offset, value), and the tile's level-2
+//                      counts of the kGuessBins guessed bins are written.
 //   P12 topk_pick12    one workgroup per (worker, layer): b1 from the histogram; if it is one
 //                      of the guessed bins, b2 from the sum of the tiles' level-2 counts.
-//   C3  topk_count3    one workgroup per tile: per quarter the entries above bin (b1, b2); the
-//                      keys inside (b1, b2) go to a per-layer list with their quarter.
-//   P3  topk_pick3     per (worker, layer): levels 3 and 4 on the list, threshold key T and tie
+//   C3  topk_count3    one workgroup per tile: per quarter the candidates above cell (b1, b2); the
+//                      keys inside the cell go to a short list per quarter.  A layer whose guess
+//                      missed is staged again here, from Delta (the keys of b1 only).
+//   P3  topk_pick3     per (worker, layer): levels 3 and 4 on the lists, threshold key T and tie
 //                      quota; the listed keys are added to their quarters' counts; exclusive
-//                      prefix over the quarters = payload position of every quarter.
+//                      prefix over the quarters = payload position of every quarter; the next
+//                      step's guess.
 //                      Layers of a single tile, which skip the passes before, are decided here
 //                      completely, from Delta, by their own workgroups.
-//                      A layer whose guess missed (first step, level switch, shifted
-//                      distribution) or whose list overflowed (huge tie class) is decided here
-//                      by sweeps of one workgroup over Delta / the segments (correct, slow).
+//                      A layer whose guess missed (first step, shifted distribution) or whose
+//                      short lists overflowed (huge tie class) is decided here by sweeps of one
+//                      workgroup (correct, slow).
 //   E   topk_compact   ordered compaction of the selected entries into the payload (index
-//                      ascending), zeroing them in e.  The batched form loops over the workers
-//                      and also forms the dense mean of the kept values in registers.
+//                      ascending).  The batched form loops over the workers, forms the dense mean
+//                      of the kept values and leaves e as it is (Delta: the next pass A drops the
+//                      kept entries); it reads the candidate lists, or Delta where they cannot
+//                      serve (missed guess, overflow, holes layout, zero-bin and band guesses).
+//                      The call-by-call form reads Delta and zeroes the kept entries in e.
 //   K6  topk_sparse_mean  dense mean of the W payloads (call-by-call path).
 //
 // The guess only decides which path is taken, never the result.  Cross-workgroup combination
