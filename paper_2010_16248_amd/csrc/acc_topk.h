@@ -29,7 +29,8 @@
 //                      ascending).  The batched form loops over the workers, forms the dense mean
 //                      of the kept values and leaves e as it is (Delta: the next pass A drops the
 //                      kept entries); it reads the candidate lists, or Delta where they cannot
-//                      serve (missed guess, overflow, holes layout, zero-bin and band guesses).
+//                      serve (a layer with a missed guess, the holes layout or a band guess; a
+//                      worker's quarter whose list overflowed or that keeps exact zeros).
 //                      The call-by-call form reads Delta and zeroes the kept entries in e.
 //   K6  topk_sparse_mean  dense mean of the W payloads (call-by-call path).
 //
@@ -42,8 +43,8 @@ namespace acc {
 
 constexpr uint32_t kNoGuess = 0xffffffffu;
 // Guess "the threshold lies in bin 0" (exact zeros and the smallest denormals: sparse gradients of
-// which more is kept than is non-zero).  The first pass then stages bin 0 the way the re-staging
-// pass does: non-zero keys listed, exact zeros counted.
+// which more is kept than is non-zero).  The first pass then lists every non-zero entry as a
+// candidate and counts the exact zeros.
 constexpr uint32_t kGuessZero = 0xfffffffeu;
 constexpr int kPickThreads = 1024;
 constexpr int kPickWaves = kPickThreads / kWave;
@@ -248,7 +249,9 @@ __device__ __forceinline__ void cand_make_room(const Ws& ws, int64_t qslot, cons
 // per component.  i_rel: offset of the lane's first element inside the quarter.  The level-2 counts of
 // the kGuessBins guessed bins go to sub2.  Every ballot is taken from a single compare and
 // combined with the other masks in scalar registers; the list is in index order.
-template <bool MASKED, bool BAND>
+// ZERO (the guess is bin 0, glo = 0, gnb = 1): every non-zero entry is a candidate, the exact
+// zeros are counted, and the level-2 counts are those of the non-zero keys of bin 0.
+template <bool MASKED, bool BAND, bool ZERO = false>
 __device__ __forceinline__ void stage_candidates(const CandList& cl, uint32_t* sub2, StageCounts& c,
                                                  uint64_t mv0, uint64_t mv1, uint64_t mv2, uint64_t mv3,
                                                  const float4& d, uint32_t glo, uint32_t gnb, uint32_t i_rel,
@@ -260,7 +263,10 @@ __device__ __forceinline__ void stage_candidates(const CandList& cl, uint32_t* s
     key[x] = key_of(comp(d, x));
     rel[x] = (key[x] >> 20) - glo;
     const uint64_t mvx = (x == 0 ? mv0 : x == 1 ? mv1 : x == 2 ? mv2 : mv3);
-    if (BAND) {
+    if (ZERO) {
+      m[x] = ballot64(key[x] != 0u);
+      c.v_nz += (key[x] == 0u && (!MASKED || lane_bit(mvx))) ? 1u : 0u;
+    } else if (BAND) {
       // inside the band: listed; above it: counted (a bin below glo wraps to a huge rel)
       m[x] = ballot64(rel[x] < gnb);
       const bool above = (int32_t)rel[x] >= (int32_t)gnb;
@@ -483,9 +489,10 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
           for (int c = 0; c < 4; ++c) {
             const uint32_t key = key_of(comp(d, c));
             hist_add(hist, (key >> 20) != 0u, key >> 20);
-            if (ZB) stage_one_bin(cl, sub2, cnt, ~0ull, true, key, 0u, lane);
           }
-          if (!ZB) {
+          if (ZB) {
+            stage_candidates<false, false, true>(cl, sub2, cnt, 0ull, 0ull, 0ull, 0ull, d, 0u, 1u, i_rel, lane);
+          } else {
             if (band) stage_candidates<false, true>(cl, sub2, cnt, 0ull, 0ull, 0ull, 0ull, d, glo, gnb, i_rel, lane);
             else stage_candidates<false, false>(cl, sub2, cnt, 0ull, 0ull, 0ull, 0ull, d, glo, gnb, i_rel, lane);
           }
@@ -498,9 +505,10 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
             mv[c] = valid_mask<AL>(tg, q, c, qa, m_span);
             const uint32_t key = key_of(comp(d, c));
             hist_add(hist, valid && (key >> 20) != 0u, key >> 20);
-            if (ZB) stage_one_bin(cl, sub2, cnt, mv[c], valid, key, 0u, lane);
           }
-          if (!ZB) {
+          if (ZB) {
+            stage_candidates<true, false, true>(cl, sub2, cnt, mv[0], mv[1], mv[2], mv[3], d, 0u, 1u, i_rel, lane);
+          } else {
             if (band) stage_candidates<true, true>(cl, sub2, cnt, mv[0], mv[1], mv[2], mv[3], d, glo, gnb, i_rel, lane);
             else stage_candidates<true, false>(cl, sub2, cnt, mv[0], mv[1], mv[2], mv[3], d, glo, gnb, i_rel, lane);
           }
@@ -844,8 +852,10 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
     sp->b1 = b1; sp->need2 = need2; sp->k = k; sp->side = side; sp->zeros = 0u; sp->bin0 = hist[0];
     sp->mode = hit ? 0u : (zhit ? 2u : 1u);
     // the candidate lists of this layer cannot serve the compaction (a miss, or a band, which does
-    // not list what lies above it): it reads Delta instead
-    if (!hit || guess_nb(guess) < (uint32_t)kGuessBins) atomicOr(&ws.lflag[li], 1u);   // cleared by the next step's first pass
+    // not list what lies above it): it reads Delta instead.  (Bin 0 guessed and found: the lists
+    // hold every non-zero entry; the quarters that keep exact zeros go back to Delta one by one.)
+    if ((!hit && !zhit) || (guessed && guess_nb(guess) < (uint32_t)kGuessBins))
+      atomicOr(&ws.lflag[li], 1u);                         // cleared by the next step's first pass
     if (!hit && !zhit) atomicAdd(&ws.stats[0], 1ull);      // layers re-staged (diagnostic counter)
   }
   if (zhit) {
@@ -931,8 +941,6 @@ __device__ __forceinline__ void count3_tile(const Ws& ws, int w, const CountTile
     __syncthreads();                                       // out[] and the block of LDS may serve the next tile
     if (tl == 0 && tid == 0) { sp->b2 = b2; sp->need3 = need2 - above2; }
   }
-  // more candidates than the list holds: the compaction of this layer reads Delta
-  if (lane == 0 && rfl(t.qh.info.y) > (uint32_t)kCandCap) atomicOr(&ws.lflag[ft.layer], 1u);
   uint32_t* list = ws.qlist + t.qslot * kQListCap;
   uint32_t n_gt = 0, n_in = 0;                             // wave-uniform
   const uint32_t above = for_quarter_keys(ws, L, w, tl, wave, t.qslot, t.qh, b1, lane, [&](uint32_t key, bool valid) {
@@ -1760,14 +1768,18 @@ __device__ __forceinline__ void compact_mean_tile(const Ws& ws, const FlatTile& 
 constexpr int kGatherChunks = 4;                            // 64-entry chunks of a candidate list requested together (2 to 8: within 2 us)
 constexpr int kQuarterGroups = (kTile / 4 + 1 + 3) / 4;     // 513: 16-byte groups of a wave quarter at most
 constexpr int kQuarterFloats = 4 * kQuarterGroups + 12;     // rounded up to whole 64-byte rows
+constexpr int kPayRing = 128;                               // a wave's payload ring in LDS: entries (indices, then values)
 
 template <bool AL, bool UPD>
 __device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& ft, const LayerDev& L,
-                                                 const TileGeom& tg, const Sink sink, float* acc, int wave) {
+                                                 const TileGeom& tg, const Sink sink, float* acc, uint32_t* ring,
+                                                 int wave) {
   const int lane = threadIdx.x & 63;
   const WaveSpan span = wave_span(tg, wave);
   const int ng = span.qend - span.qbeg;                    // groups of the quarter, wave-uniform
   if (ng <= 0) return;
+  int32_t* const ring_idx = reinterpret_cast<int32_t*>(ring);
+  float* const ring_val = reinterpret_cast<float*>(ring + kPayRing);
   const int64_t qslot_local = L.qoff + 4 * (int64_t)(ft.start >> kTileShift) + wave;
   const int W = ws.W;
   const int64_t pay_off = L.pay_off, pay_stride = ws.pay_stride, q_stride = ws.q_stride;
@@ -1780,7 +1792,7 @@ __device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& f
   uint32_t n_mine = 0u;
   if (lane < W) {
     mine = load_quarter_sel(ws, lane, ft.layer, qslot_local);
-    n_mine = min(ws.qinfo[(int64_t)lane * q_stride + qslot_local].y, (uint32_t)kCandCap);
+    n_mine = ws.qinfo[(int64_t)lane * q_stride + qslot_local].y;   // beyond kCandCap: the list is incomplete
   }
   // A batch = up to kGatherChunks 64-entry chunks of one worker's list, requested together; the next
   // batch (the rest of this worker's list, else the head of the next worker's) is requested before
@@ -1804,7 +1816,7 @@ __device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& f
   // index of the quarter's first element in the layer
   const int32_t i_quarter = (int32_t)(tg.a0 + 4 * (int64_t)span.qbeg - L.offset);
   for (int w = 0; w < W; ++w) {
-    const uint32_t n = (uint32_t)__builtin_amdgcn_readlane((int)n_mine, w);
+    const uint32_t n_listed = (uint32_t)__builtin_amdgcn_readlane((int)n_mine, w);
     const uint32_t t_all = (uint32_t)__builtin_amdgcn_readlane((int)mine.t_all, w);
     const uint32_t k = (uint32_t)__builtin_amdgcn_readlane((int)mine.k, w);
     const bool ties = ((uint32_t)__builtin_amdgcn_readlane((int)mine.flags, w) & 1u) != 0u;
@@ -1814,6 +1826,67 @@ __device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& f
     uint32_t pos_run = (uint32_t)__builtin_amdgcn_readlane((int)mine.gt_before, w) + min(ktie, eq_run);
     int32_t* __restrict__ pidx = pay_idx + (int64_t)w * pay_stride + pay_off;
     float* __restrict__ pval = pay_val + (int64_t)w * pay_stride + pay_off;
+    // This worker's list cannot serve this quarter -- it overflowed, or the threshold is zero and
+    // some of the quarter's exact zeros, which no list holds, are kept (the tie quota is not used
+    // up before it): the quarter is taken from Delta, group by group, with the same selection rule.
+    const bool from_delta = n_listed > (uint32_t)kCandCap || (T == 0u && ties && eq_run < ktie);   // wave-uniform
+    const uint32_t n = from_delta ? 0u : n_listed;
+    if (from_delta) {
+      const float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
+      const SelCommon sc = {t_all, ties};
+      for (int g0 = 0; g0 < ng; g0 += kWave) {
+        const int q = span.qbeg + g0 + lane;
+        const bool qa = q < span.qend;
+        const float4 d = ld_span<AL>(e, tg, span, q);
+        const uint64_t m_span = ballot64(qa);
+        uint32_t key[4];
+        uint64_t mv[4], msel[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          mv[c] = valid_mask<AL>(tg, q, c, qa, m_span);
+          key[c] = key_of(comp(d, c));
+        }
+        group_select(sc, [&]() { SelTies t; t.T = T; t.ktie = ktie; return t; }, eq_run, key, mv, lane, msel);
+        // Payload positions in index order: lane by lane, component by component.  The entries
+        // pass through a ring in LDS (slot = position mod kPayRing), half a wave at a time -- 128
+        // entries at most --, and leave it through consecutive lanes at consecutive positions.
+        uint32_t pos = pos_run, total = 0u, total_lo = 0u;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          pos += lanes_below(msel[c], lane);
+          total += (uint32_t)__popcll(msel[c]);
+          total_lo += (uint32_t)__popcll(msel[c] & 0xffffffffull);
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const uint32_t h_lo = pos_run + (half ? total_lo : 0u), h_hi = pos_run + (half ? total : total_lo);
+          if (h_hi == h_lo) continue;                        // wave-uniform
+          if ((lane >> 5) == half) {
+            uint32_t p = pos;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              if (lane_bit(msel[c])) {
+                const int32_t off = 4 * (g0 + lane) + c;     // offset in the quarter
+                ring_idx[p & (kPayRing - 1)] = i_quarter + off;
+                ring_val[p & (kPayRing - 1)] = comp(d, c);
+                acc[off] += comp(d, c);
+                ++p;
+              }
+            }
+          }
+          __builtin_amdgcn_wave_barrier();
+          for (uint32_t j0 = h_lo; j0 < h_hi; j0 += kWave) {
+            const uint32_t j = j0 + lane;
+            if (j < h_hi && j < k) {                         // < k: always true for consistent state
+              __builtin_nontemporal_store(ring_idx[j & (kPayRing - 1)], pidx + j);
+              __builtin_nontemporal_store(ring_val[j & (kPayRing - 1)], pval + j);
+            }
+          }
+          __builtin_amdgcn_wave_barrier();
+        }
+        pos_run += total;
+      }
+    }
     for (uint32_t t0 = 0u; t0 < n || t0 == 0u; t0 += U * kWave) {
       uint32_t nv[U], ni[U];
       const bool more = t0 + U * kWave < n;
@@ -1893,7 +1966,7 @@ __device__ __forceinline__ void gather_mean_tile(const Ws& ws, const FlatTile& f
 // four on ResNet-18 shapes, the same as one).
 constexpr int kMeanWaves = 2;
 constexpr int kMeanSplit = 4 / kMeanWaves;                  // workgroups per tile
-constexpr int kMeanLdsWords = kQuarterFloats > kChunkWords ? kQuarterFloats : kChunkWords;
+constexpr int kMeanLdsWords = kQuarterFloats + 2 * kPayRing > kChunkWords ? kQuarterFloats + 2 * kPayRing : kChunkWords;
 
 template <bool UPD>
 __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink) {
@@ -1919,8 +1992,8 @@ __device__ __forceinline__ void compact_mean_body(const Ws& ws, const Sink& sink
     else compact_mean_tile<false, UPD, true>(ws, ft, L, tg, sink, stg, wave);
   } else if (L.ntiles > 1 && rfl(ws.lflag[ft.layer]) == 0u) {
     // every worker's guess held and every list is complete: the candidates serve
-    if (tg.aligned) gather_mean_tile<true, UPD>(ws, ft, L, tg, sink, reinterpret_cast<float*>(stg), wave);
-    else gather_mean_tile<false, UPD>(ws, ft, L, tg, sink, reinterpret_cast<float*>(stg), wave);
+    if (tg.aligned) gather_mean_tile<true, UPD>(ws, ft, L, tg, sink, reinterpret_cast<float*>(stg), stg + kQuarterFloats, wave);
+    else gather_mean_tile<false, UPD>(ws, ft, L, tg, sink, reinterpret_cast<float*>(stg), stg + kQuarterFloats, wave);
   } else {
     if (tg.aligned) compact_mean_tile<true, UPD, false>(ws, ft, L, tg, sink, stg, wave);
     else compact_mean_tile<false, UPD, false>(ws, ft, L, tg, sink, stg, wave);

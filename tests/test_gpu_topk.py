@@ -230,6 +230,39 @@ def test_threshold_among_exact_zeros_is_guessed_too():
     gpu.destroy()
 
 
+def test_zero_threshold_with_dense_rows_and_kept_zeros():
+    """An embedding-like layer: a few rows are dense, the rest exactly zero, and more is kept than is
+    non-zero.  Once bin 0 is guessed the first pass lists every non-zero entry; the quarters of
+    the dense rows overflow their lists, the first quarters of the layer keep exact zeros (which
+    no list holds), and both are taken from Delta quarter by quarter and worker by worker while
+    the others are served by the lists.  Every step is exact, payload order included."""
+    print("case zero threshold, dense rows", flush=True)
+    rows, cols = 96, 672                                    # 8 tiles
+    shapes = [(rows, cols, 1), (1, 3 * 8192 + 77, 0)]
+    layers = wl.make_layers(shapes)
+    N = wl.total_params(layers)
+    W = 3
+    gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    rng = np.random.default_rng(31)
+    restaged = []
+    for step in range(5):
+        grads = []
+        for w in range(W):
+            g = np.zeros(N, np.float32)
+            m = np.zeros((rows, cols), np.float32)
+            lo = 88 - 3 * w - (step % 2)                    # six dense rows, elsewhere per worker and step
+            m[lo:lo + 6] = rng.standard_normal((6, cols))
+            g[:rows * cols] = m.reshape(-1)
+            v = rng.standard_normal(N - rows * cols) * (rng.random(N - rows * cols) < 0.02)
+            g[rows * cols:] = v
+            grads.append(g)
+        _check_step(gpu, ora, grads, f"step {step}", check_state=(step in (2, 4)))
+        restaged.append(gpu.topk_stats()[0])
+    per_step = np.diff([0] + restaged)
+    assert per_step[2:].sum() == 0, per_step                # bin 0 guessed and found
+    gpu.destroy()
+
+
 def test_a_sparse_layer_running_dry_is_seen_coming():
     """A sparse gradient (3 % non-zero) whose memory has filled up while little was kept: the first
     step that keeps 10 % again finds more than 10 % non-zero entries (threshold above zero) and
