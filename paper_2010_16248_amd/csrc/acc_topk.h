@@ -789,22 +789,25 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   // the next step) and the tiles' level-2 counts of ALL guessed bins.
   uint32_t* gh = ws.hist1 + wl * kHistBins;
   uint32_t h0 = gh[tid], h1 = gh[tid + kPickThreads];
-  constexpr int kStripes = kPickThreads / kSub2;            // tiles summed side by side
-  const int col = tid % kSub2, stripe = tid / kSub2;
-  uint32_t* t2 = ws.t2 + ((int64_t)w * ws.n_t2slots + L.t2slot0) * kSub2 + col;
+  // a thread sums four adjacent counts (one 16-byte load) of every kStripes-th slot
+  constexpr int kCols4 = kSub2 / 4;
+  constexpr int kStripes = kPickThreads / kCols4;           // slots summed side by side
+  static_assert(kSub2 % 4 == 0 && kStripes >= 1, "four counts per load");
+  const int col4 = tid % kCols4, stripe = tid / kCols4;
+  uint4* t2 = reinterpret_cast<uint4*>(ws.t2 + ((int64_t)w * ws.n_t2slots + L.t2slot0) * kSub2) + col4;
   const int nslots = (L.ntiles + kT2Group - 1) / kT2Group;
-  uint32_t s2 = 0;
+  uint4 s2 = make_uint4(0u, 0u, 0u, 0u);
   constexpr int kT2Loads = 8;                               // independent loads in flight
   for (int sl0 = (stripe < kStripes ? stripe : nslots); sl0 < nslots; sl0 += kT2Loads * kStripes) {
-    uint32_t v[kT2Loads];
+    uint4 v[kT2Loads];
 #pragma unroll
-    for (int u = 0; u < kT2Loads; ++u) v[u] = t2[(int64_t)min(sl0 + u * kStripes, nslots - 1) * kSub2];
+    for (int u = 0; u < kT2Loads; ++u) v[u] = t2[(int64_t)min(sl0 + u * kStripes, nslots - 1) * kCols4];
 #pragma unroll
     for (int u = 0; u < kT2Loads; ++u) {
       const int sl = sl0 + u * kStripes;
       if (sl < nslots) {
-        s2 += v[u];
-        t2[(int64_t)sl * kSub2] = 0u;                        // cleared for the next step
+        s2.x += v[u].x; s2.y += v[u].y; s2.z += v[u].z; s2.w += v[u].w;
+        t2[(int64_t)sl * kCols4] = make_uint4(0u, 0u, 0u, 0u);   // cleared for the next step
       }
     }
   }
@@ -816,7 +819,10 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   if (tid < kSub2) sub[tid] = 0u;
   if (tid == 0) nb0 = 0u;
   __syncthreads();
-  if (s2) atomicAdd(&sub[col], s2);
+  if (s2.x) atomicAdd(&sub[4 * col4 + 0], s2.x);
+  if (s2.y) atomicAdd(&sub[4 * col4 + 1], s2.y);
+  if (s2.z) atomicAdd(&sub[4 * col4 + 2], s2.z);
+  if (s2.w) atomicAdd(&sub[4 * col4 + 3], s2.w);
   {
     // bin 0 (exact zeros and the smallest denormals) was not histogrammed: the rest of the layer
     const uint32_t part = wave_sum_u32(h0 + h1 - (tid == 0 ? h0 : 0u));
