@@ -866,12 +866,22 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   }
   if (zhit) {
     // level-2 counts of the non-zero keys of bin 0 (summed over the tiles above); the rest of
-    // bin 0 are exact zeros
-    if (tid < kL2Bins) ws.hist2m[wl * kL2Bins + tid] = sub[tid];
+    // bin 0 are exact zeros, which belong to level-2 bin 0
+    __shared__ uint32_t zeros_s;
     if (tid == 0) {
       uint32_t nnz0 = 0;
       for (int b = 0; b < kL2Bins; ++b) nnz0 += sub[b];
-      sp->zeros = hist[0] - min(nnz0, hist[0]);
+      zeros_s = hist[0] - min(nnz0, hist[0]);
+      sp->zeros = zeros_s;
+    }
+    __syncthreads();
+    for (int b = tid; b < kHistBins; b += kPickThreads)
+      hist[b] = (b < kL2Bins) ? sub[b] + (b == 0 ? zeros_s : 0u) : 0u;
+    __syncthreads();
+    pick_bin(hist, need2, out, scratch);
+    if (tid == 0) {
+      sp->b2 = out[0];
+      sp->need3 = need2 - out[1];
     }
     return;
   }
@@ -897,12 +907,11 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
 constexpr int kCountTiles = 1;
 
 struct CountLds {
-  // One block for the two rare paths, which are never at work in a workgroup at the same time: the
-  // staging lists of a missed layer's tile (values, then offsets), or the histogram of the bin-0 pick.
+  // The staging lists of a missed layer's tile (values, then offsets), used by that rare path only.
   static constexpr int kListWords = 4 * kCandLdsSlots;
-  static constexpr int kRareWords = kListWords + kListWords / 2 > kHistBins ? kListWords + kListWords / 2 : kHistBins;
+  static constexpr int kRareWords = kListWords + kListWords / 2;
   uint32_t* rare;
-  uint32_t *out, *scratch, *sub2;
+  uint32_t* sub2;
   uint4* qi;
 };
 
@@ -913,11 +922,8 @@ __device__ __forceinline__ void count3_tile(const Ws& ws, int w, const CountTile
   const FlatTile& ft = t.ft;
   if (t.ntiles == 1) return;                               // decided by the last pick kernel
   const LayerDev& L = ws.layers[ft.layer];
-  const int64_t wl = (int64_t)w * ws.L + ft.layer;
-  SelState* sp = ws.sel + wl;
   const int tl = ft.start >> kTileShift;
-  const uint32_t b1 = t.b1;
-  uint32_t b2 = t.b2;
+  const uint32_t b1 = t.b1, b2 = t.b2;
   if (t.mode == 1u) {                                      // uniform over the workgroup
     // The guess missed: nothing useful was staged.  This tile's keys of b1 are staged now (one
     // more read of Delta) with their level-2 counts; the layer's pick kernel takes it from there.
@@ -928,24 +934,6 @@ __device__ __forceinline__ void count3_tile(const Ws& ws, int w, const CountTile
     else restage_tile<false>(ws, w, ft, L, tg, b1, cl, lds.sub2);
     __syncthreads();                                       // the block of LDS may serve the next tile
     return;
-  }
-  if (t.mode == 2u) {
-    // bin 0 guessed and found: its non-zero keys were staged and their level-2 counts summed
-    const int tid = threadIdx.x;
-    uint32_t* hist = lds.rare;
-    const uint32_t zeros = sp->zeros;
-    for (int b = tid; b < kHistBins; b += kFlatThreads) {
-      uint32_t h = (b < kL2Bins) ? ws.hist2m[wl * kL2Bins + b] : 0u;
-      if (b == 0 && b1 == 0u) h += zeros;                    // exact zeros: level-2 bin 0 of bin 0
-      hist[b] = h;
-    }
-    __syncthreads();
-    const uint32_t need2 = sp->need2;
-    pick_bin(hist, need2, lds.out, lds.scratch);
-    b2 = lds.out[0];
-    const uint32_t above2 = lds.out[1];
-    __syncthreads();                                       // out[] and the block of LDS may serve the next tile
-    if (tl == 0 && tid == 0) { sp->b2 = b2; sp->need3 = need2 - above2; }
   }
   uint32_t* list = ws.qlist + t.qslot * kQListCap;
   uint32_t n_gt = 0, n_in = 0;                             // wave-uniform
@@ -965,10 +953,9 @@ __device__ __forceinline__ void count3_tile(const Ws& ws, int w, const CountTile
 
 __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
   __shared__ __attribute__((aligned(16))) uint32_t rare[CountLds::kRareWords];
-  __shared__ uint32_t out[3], scratch[4];
   __shared__ uint32_t sub2[kL2Bins];
   __shared__ uint4 qi[4];
-  const CountLds lds = {rare, out, scratch, sub2, qi};
+  const CountLds lds = {rare, sub2, qi};
   const int w = w0 + blockIdx.y;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
