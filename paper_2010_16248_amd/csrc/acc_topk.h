@@ -81,6 +81,16 @@ __device__ __forceinline__ uint32_t bin2_of(uint32_t key) { return (key >> 14) &
 __device__ __forceinline__ uint32_t bin3_of(uint32_t key) { return (key >> 6) & 0xffu; }
 __device__ __forceinline__ uint32_t bin4_of(uint32_t key) { return key & 0x3fu; }
 
+// A load the compiler leaves where it is written.  Plain loads are moved down to their first use,
+// behind every branch and every wait on the way: the loads of a quarter's record and list, written
+// at the top of the counting kernel, were issued after its chain of seven dependent scalar loads
+// instead of beside it, and the first pass read its flags, its level and its guess one after the
+// other before it requested any data.  A relaxed atomic load of wavefront scope is the same instruction as a
+// plain load and is not moved.
+__device__ __forceinline__ uint32_t ld_here(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+
 __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -387,9 +397,9 @@ __device__ __forceinline__ PrevSel load_prev_sel(const Ws& ws, int64_t wl, int64
   const SelState* sp = ws.sel + wl;
   PrevSel p;
   // wave-uniform values: into scalar registers, whatever kind of load fetched them
-  p.T = rfl(sp->T); p.ktie = rfl(sp->ktie);
-  p.eq_run = rfl(ws.eqpre[qslot]);
-  p.sc = sel_common(p.T, rfl(sp->alleq), rfl(ws.eqpre[qslot + 1]) - p.eq_run);   // the layer's last slot: the total
+  p.T = rfl(ld_here(&sp->T)); p.ktie = rfl(ld_here(&sp->ktie));
+  p.eq_run = rfl(ld_here(ws.eqpre + qslot));
+  p.sc = sel_common(p.T, rfl(ld_here(&sp->alleq)), rfl(ld_here(ws.eqpre + qslot + 1)) - p.eq_run);   // the layer's last slot: the total
   return p;
 }
 
@@ -419,7 +429,8 @@ __device__ __forceinline__ float4 drop_kept(const TileGeom& tg, int q, bool qa, 
 template <bool AL, bool SELECT, bool ZB>
 __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, int w, int tile_id,
                                              const FlatTile& ft, const LayerDev& L, const TileGeom& tg,
-                                             uint32_t* hist, const CandList& cl, uint32_t* sub2, double* red4, uint32_t guess) {
+                                             uint32_t* hist, const CandList& cl, uint32_t* sub2, double* red4, uint32_t guess,
+                                             bool window_fresh, uint32_t pending) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -428,7 +439,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   float* __restrict__ e = ws.e + (int64_t)w * ws.e_stride;
   float* __restrict__ A = (w == 0) ? ws.A : nullptr;
   // the accumulation window has just restarted: A counts as zero and is not read
-  const bool a_fresh = A && *ws.a_fresh != 0u;             // uniform over the workgroup
+  const bool a_fresh = A && window_fresh;                  // uniform over the workgroup
   double a_sq = 0.0;                                       // worker 0: the lane's share of the tile's sum of squares of A
   const int64_t wl = (int64_t)w * ws.L + ft.layer;
   uint32_t glo = 0x7ffffff0u, gnb = 0u;                    // no bin matches without a guess
@@ -449,7 +460,7 @@ __device__ __forceinline__ void ef_hist_tile(const Ws& ws, const GradPtrs& gp, i
   // The previous selection is requested whether or not it is needed, so that its loads do not
   // wait for the load of the mask.
   PrevSel ps = load_prev_sel(ws, wl, quarter_slot(ws, L, w, ft.start >> kTileShift, wave));
-  const bool pend = ((*ws.tpending >> w) & 1u) != 0u;      // uniform over the workgroup
+  const bool pend = ((pending >> w) & 1u) != 0u;           // uniform over the workgroup
   if (SELECT) {
     for (int b = tid; b < kHistBins; b += kFlatThreads) hist[b] = 0;
     for (int b = tid; b < kSub2; b += kFlatThreads) sub2[b] = 0;
@@ -551,6 +562,12 @@ __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const Gr
   __shared__ uint4 qi[4];
   const int w = w0 + blockIdx.y;
   const FlatTile ft = ws.ftiles[blockIdx.x];
+  // Everything else the tile depends on is requested together, as soon as its layer is known: the
+  // flags, the layer's level and the guesses of both levels (one of them is the one to use).
+  const uint32_t* gp2 = ws.guess + ((int64_t)w * ws.L + ft.layer) * 2;
+  const uint32_t guess0 = ld_here(gp2), guess1 = ld_here(gp2 + 1);
+  const uint32_t lvl = ld_here(reinterpret_cast<const uint32_t*>(ws.level + ft.layer));
+  const uint32_t fresh_w = ld_here(ws.a_fresh), pend_w = ld_here(ws.tpending);
   const LayerDev& L = ws.layers[ft.layer];
   const TileGeom tg = tile_geom(L, ft);
   const int lw = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -558,17 +575,19 @@ __global__ __launch_bounds__(256) void topk_ef_hist_kernel(const Ws ws, const Gr
   // the layer's "compact from Delta" flag of the last step is cleared before this step's
   // decision kernels (which set it) run
   if (w == 0 && ft.start == 0 && threadIdx.x == 0) ws.lflag[ft.layer] = 0u;
+  const bool fresh = rfl(fresh_w) != 0u;
+  const uint32_t pending = rfl(pend_w);
   if (L.ntiles == 1) {
-    if (tg.aligned) ef_hist_tile<true, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, kNoGuess);
-    else ef_hist_tile<false, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, kNoGuess);
+    if (tg.aligned) ef_hist_tile<true, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, kNoGuess, fresh, pending);
+    else ef_hist_tile<false, false, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, kNoGuess, fresh, pending);
   } else {
-    const uint32_t guess = ws.guess[((int64_t)w * ws.L + ft.layer) * 2 + ws.level[ft.layer]];
+    const uint32_t guess = rfl(rfl(lvl) != 0u ? guess1 : guess0);
     if (guess == kGuessZero) {                               // uniform over the workgroup
-      if (tg.aligned) ef_hist_tile<true, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess);
-      else ef_hist_tile<false, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess);
+      if (tg.aligned) ef_hist_tile<true, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess, fresh, pending);
+      else ef_hist_tile<false, true, true>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess, fresh, pending);
     } else {
-      if (tg.aligned) ef_hist_tile<true, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess);
-      else ef_hist_tile<false, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess);
+      if (tg.aligned) ef_hist_tile<true, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess, fresh, pending);
+      else ef_hist_tile<false, true, false>(ws, gp, w, blockIdx.x, ft, L, tg, hist, cl, sub2, red4, guess, fresh, pending);
     }
   }
 }
@@ -627,9 +646,10 @@ struct QuarterHead {
 
 __device__ __forceinline__ QuarterHead load_quarter_head(const Ws& ws, int64_t qslot, int lane) {
   QuarterHead h;
-  h.info = ws.qinfo[qslot];
+  const uint32_t* qi = reinterpret_cast<const uint32_t*>(ws.qinfo + qslot);
+  h.info = make_uint4(ld_here(qi), ld_here(qi + 1), ld_here(qi + 2), ld_here(qi + 3));
 #pragma unroll
-  for (int ch = 0; ch < kEagerChunks; ++ch) h.chunk[ch] = ws.cand_val[cand_at(ws, qslot, (uint32_t)ch, lane)];
+  for (int ch = 0; ch < kEagerChunks; ++ch) h.chunk[ch] = ld_here(ws.cand_val + cand_at(ws, qslot, (uint32_t)ch, lane));
   return h;
 }
 
@@ -972,8 +992,8 @@ __global__ __launch_bounds__(256) void topk_count3_kernel(const Ws ws, int w0) {
 #pragma unroll
   for (int u = 0; u < kCountTiles; ++u) {
     const SelState* sp = ws.sel + (int64_t)w * ws.L + t[u].ft.layer;
-    t[u].b1 = sp->b1; t[u].b2 = sp->b2; t[u].mode = sp->mode;
-    t[u].ntiles = ws.layers[t[u].ft.layer].ntiles;
+    t[u].b1 = rfl(ld_here(&sp->b1)); t[u].b2 = rfl(ld_here(&sp->b2)); t[u].mode = rfl(ld_here(&sp->mode));
+    t[u].ntiles = (int)rfl(ld_here(reinterpret_cast<const uint32_t*>(&ws.layers[t[u].ft.layer].ntiles)));
   }
 #pragma unroll
   for (int u = 0; u < kCountTiles; ++u)
