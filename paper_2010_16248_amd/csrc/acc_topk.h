@@ -795,27 +795,39 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   const int w = w0 + blockIdx.y;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const LayerDev& L = ws.layers[li];
   const int64_t wl = (int64_t)w * ws.L + li;
-  const int lv = ws.level[li];
-  const uint32_t k = (uint32_t)L.k[lv];
+  // Requested together, before anything is known (every address follows from the workgroup's
+  // index): the layer's entry, its level, the guesses of both levels and the layer's level-1
+  // histogram (cleared for the next step).  The tiles' level-2 counts of ALL guessed bins follow
+  // as soon as the entry says where they are.
+  const LayerDev* Lp = ws.layers + li;
+  const uint32_t l_ntiles = ld_here(reinterpret_cast<const uint32_t*>(&Lp->ntiles));
+  const uint32_t l_t2slot0 = ld_here(reinterpret_cast<const uint32_t*>(&Lp->t2slot0));
+  const uint32_t l_k0 = ld_here(reinterpret_cast<const uint32_t*>(&Lp->k[0]));
+  const uint32_t l_k1 = ld_here(reinterpret_cast<const uint32_t*>(&Lp->k[1]));
+  const uint32_t l_rows = ld_here(reinterpret_cast<const uint32_t*>(&Lp->rows));
+  const uint32_t l_cols = ld_here(reinterpret_cast<const uint32_t*>(&Lp->cols));
+  const uint32_t lvl_v = ld_here(reinterpret_cast<const uint32_t*>(ws.level + li));
+  const uint32_t guess0 = ld_here(ws.guess + wl * 2), guess1 = ld_here(ws.guess + wl * 2 + 1);
+  uint32_t* gh = ws.hist1 + wl * kHistBins;
+  uint32_t h0 = ld_here(gh + tid), h1 = ld_here(gh + tid + kPickThreads);
+  const int L_ntiles = (int)rfl(l_ntiles), L_t2slot0 = (int)rfl(l_t2slot0);
+  const uint32_t n_layer = rfl(l_rows) * rfl(l_cols);
+  const int lv = (int)rfl(lvl_v);
+  const uint32_t k = rfl(lv ? l_k1 : l_k0), k_other = rfl(lv ? l_k0 : l_k1);
   // worker 0's first pass has added its gradient to A: the window is no longer fresh
   if (w == 0 && li == 0 && tid == 0) *ws.a_fresh = 0u;
-  if (L.ntiles == 1) return;                               // decided by the last pick kernel, from Delta
+  if (L_ntiles == 1) return;                               // decided by the last pick kernel, from Delta
   SelState* sp = ws.sel + wl;
   __shared__ uint32_t sub[kSub2];
   __shared__ uint32_t nb0;
-  // Requested together, before anything is known: the layer's level-1 histogram (cleared for
-  // the next step) and the tiles' level-2 counts of ALL guessed bins.
-  uint32_t* gh = ws.hist1 + wl * kHistBins;
-  uint32_t h0 = gh[tid], h1 = gh[tid + kPickThreads];
   // a thread sums four adjacent counts (one 16-byte load) of every kStripes-th slot
   constexpr int kCols4 = kSub2 / 4;
   constexpr int kStripes = kPickThreads / kCols4;           // slots summed side by side
   static_assert(kSub2 % 4 == 0 && kStripes >= 1, "four counts per load");
   const int col4 = tid % kCols4, stripe = tid / kCols4;
-  uint4* t2 = reinterpret_cast<uint4*>(ws.t2 + ((int64_t)w * ws.n_t2slots + L.t2slot0) * kSub2) + col4;
-  const int nslots = (L.ntiles + kT2Group - 1) / kT2Group;
+  uint4* t2 = reinterpret_cast<uint4*>(ws.t2 + ((int64_t)w * ws.n_t2slots + L_t2slot0) * kSub2) + col4;
+  const int nslots = (L_ntiles + kT2Group - 1) / kT2Group;
   uint4 s2 = make_uint4(0u, 0u, 0u, 0u);
   constexpr int kT2Loads = 8;                               // independent loads in flight
   for (int sl0 = (stripe < kStripes ? stripe : nslots); sl0 < nslots; sl0 += kT2Loads * kStripes) {
@@ -831,7 +843,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
       }
     }
   }
-  const uint32_t guess = ws.guess[wl * 2 + lv];
+  const uint32_t guess = rfl(lv ? guess1 : guess0);
   gh[tid] = 0u;
   gh[tid + kPickThreads] = 0u;
   hist[tid] = h0;
@@ -849,14 +861,13 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
     if (lane == 0 && part) atomicAdd(&nb0, part);
   }
   __syncthreads();
-  if (tid == 0) hist[0] = (uint32_t)((int64_t)L.rows * L.cols) - nb0;
+  if (tid == 0) hist[0] = n_layer - nb0;
   __syncthreads();
   pick_bin(hist, k, out, scratch);
   const uint32_t b1 = out[0], need2 = k - out[1];
   // The other level's guess, from the same histogram: the bin its k-th largest key would lie in
   // in this step's Delta.  It serves the first step after a level switch, when the level's own
   // history is stale (or missing); after that the threshold is followed as usual.
-  const uint32_t k_other = (uint32_t)L.k[1 - lv];
   if (k_other != k) {                                      // uniform over the workgroup
     __syncthreads();                                       // everybody has read out[]
     pick_bin(hist, k_other, out, scratch);
@@ -864,7 +875,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
       const uint32_t bo = out[0];
       // (the memory will adapt to the new level for some steps: a wide guess)
       ws.guess[wl * 2 + (1 - lv)] = (bo == 0u) ? kGuessZero
-          : make_guess((int)bo - kGuessMovingBelow, guess_bins_for(k_other, (uint32_t)L.rows * (uint32_t)L.cols));
+          : make_guess((int)bo - kGuessMovingBelow, guess_bins_for(k_other, n_layer));
     }
     __syncthreads();
   }
