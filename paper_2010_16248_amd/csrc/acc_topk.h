@@ -1344,7 +1344,17 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
     // A move down is followed at once (the guess must start below the threshold); a move up only
     // with a lag of two bins: the guess reaches four to six bins above its centre anyway, and a
     // jump up is often followed by smaller steps.
-    const int centre = (int)b1 + (v < 0 ? v : max(0, v - 2));
+    int centre = (int)b1 + (v < 0 ? v : max(0, v - 2));
+    const uint32_t n_layer = (uint32_t)L.rows * (uint32_t)L.cols, k_now = (uint32_t)L.k[lv];
+    if (guess_bins_for(k_now, n_layer) < kGuessBins) {
+      // A level that keeps a large part empties the memory in one step: on the first step after
+      // a switch to it the threshold is that of gradient plus a full memory, from the second on that
+      // of the gradient alone, octaves below.  So the step after a switch is guessed where the
+      // threshold was the last time this level ran, and a jump of many bins is not taken for a drift.
+      const int remembered = (int)(prev.x & 0xffffu);
+      if (!consecutive && remembered != 0 && remembered < (int)b1) centre = remembered;
+      else if (consecutive && abs(v) > 6) centre = (int)b1;
+    }
     // how far below the centre the guess starts: one bin at rest, two while the move is steady (it
     // changed by at most one bin from the step before), three otherwise (the first steps at a level)
     const int pv = consecutive ? (int)((prev.x >> 16) & 0xffu) - 64 : 0;
@@ -1354,7 +1364,6 @@ __device__ __forceinline__ void pick3_body(const Ws& ws, int w0, uint32_t step_i
     // emptied down to less than k non-zero entries the threshold drops to zero.  This step leaves
     // nnz - k of its non-zero entries behind and the next gradient adds about as many as it did
     // the last time everything non-zero was kept.
-    const uint32_t n_layer = (uint32_t)L.rows * (uint32_t)L.cols, k_now = (uint32_t)L.k[lv];
     const uint32_t nnz = n_layer - min(sp->bin0, n_layer);
     uint32_t fresh = sp->fresh_nnz;
     if (b1 == 0u && nnz != 0u) { fresh = nnz; sp->fresh_nnz = nnz; }
