@@ -110,16 +110,16 @@ struct Ws {
   uint32_t* pending;           // one word: workers whose e still holds Delta (residual not formed yet)
   // TopK
   uint32_t* hist1;             // W x L x kHistBins, zero between steps
-  uint32_t* t2;                // W x n_t2slots x 192: level-2 counts of the guessed bins, summed over kT2Group tiles
+  uint32_t* t2;                // W x n_t2slots x 640: level-2 counts of the ten guessed bins, summed over kT2Group tiles
   uint32_t* qlist;             // W x q_stride x kQListCap: per quarter, its keys in bin (b1, b2)
   SelState* sel;               // W x L
   uint32_t* hist2m;            // W x L x 64: level-2 counts of b1 of a layer whose guess missed
-  uint32_t* lflag;             // L: nonzero = this step's compaction of the layer reads Delta (a guess missed, a
-                               //   candidate list overflowed), not the candidate lists
+  uint32_t* lflag;             // L: nonzero = this step's compaction of the layer reads Delta (some worker's guess
+                               //   missed, or the guess was a band), not the candidate lists
   uint2* b1hist;               // W x L x 2 (level): {b1 | (last move + 64) << 16 | steps at rest << 24, step number} of the last step at this level
-  uint32_t* guess;             // W x L x 2 (level): lowest of the adjacent level-1 bins staged by pass A
-  uint4* qinfo;                // W x q_stride: per wave quarter {entries above the staged bin (one-bin lists),
-                               //   listed entries, 0, exact zeros (one-bin lists)}
+  uint32_t* guess;             // W x L x 2 (level): lowest guessed level-1 bin | number of bins << 16, or a special value
+  uint4* qinfo;                // W x q_stride: per wave quarter {entries above what is listed (one-bin and band
+                               //   lists), listed entries, 0, exact zeros (one-bin and zero-guess lists)}
   uint32_t* cand_val;          // W x q_stride x kCandCap: per wave quarter, the values of its candidates (or keys of one bin)
   uint16_t* cand_idx;          // W x q_stride x kCandCap: ... and their offsets inside the quarter
   uint32_t* gtq;               // W x q_stride entries above the threshold per quarter

@@ -189,8 +189,9 @@ __device__ __forceinline__ int64_t quarter_slot(const Ws& ws, const LayerDev& L,
 // Pass A leaves, per wave quarter, the list of its CANDIDATES: every entry whose level-1 bin is at
 // or above the lowest guessed bin, as (offset inside the quarter, value), in index order.  When the
 // guess holds, the kept entries are among them, and the passes after it -- the counting kernel, the
-// compaction and the mean -- read these 6 bytes per candidate (12 to 17 % of the entries at
-// K = 10 %, 2 % at K = 1 %) instead of Delta once more.  A wave collects its candidates in LDS
+// compaction and the mean -- read these 6 bytes per candidate (under error feedback, which piles
+// the entries up just below the threshold, 17 to 27 % of the entries at K = 10 % and 8 to 18 % at
+// K = 1 %) instead of Delta once more.  A wave collects its candidates in LDS
 // and writes them out, consecutive lanes to consecutive addresses, whenever another iteration
 // (up to 256 entries) might not fit.  A quarter with more than kCandCap candidates keeps the
 // first kCandCap and its full count: whoever reads the list sees the overflow and goes back to
@@ -254,8 +255,10 @@ __device__ __forceinline__ void cand_make_room(const Ws& ws, int64_t qslot, cons
 }
 
 // Pass A, one group: the candidates among the four elements of every lane (bins glo and up;
-// glo >= 1, so a candidate is never an exact zero; zeros are not counted here: a threshold in bin 0
-// counts as a missed guess and the re-staging counts them).  mv: lane masks of the valid elements
+// glo >= 1, so a candidate is never an exact zero, and zeros are not counted: should the
+// threshold turn out to lie in bin 0 the guess has missed and the staging after a miss counts
+// them).  BAND: only the bins glo .. glo + gnb - 1 are listed, what lies above is counted.
+// mv: lane masks of the valid elements
 // per component.  i_rel: offset of the lane's first element inside the quarter.  The level-2 counts of
 // the kGuessBins guessed bins go to sub2.  Every ballot is taken from a single compare and
 // combined with the other masks in scalar registers; the list is in index order.
@@ -882,7 +885,7 @@ __global__ __launch_bounds__(kPickThreads) void topk_pick12_kernel(const Ws ws, 
   const bool guessed = guess != kNoGuess && guess != kGuessZero;
   const uint32_t glo = guessed ? guess_lo(guess) : 0u;     // the bins pass A counted: glo .. glo + nb - 1
   const bool hit = guessed && b1 >= glo && b1 - glo < guess_nb(guess);
-  // bin 0 guessed and found: pass A left what the re-staging pass would (mode 2: staged already)
+  // bin 0 guessed and found: pass A listed every non-zero entry and counted the zeros (mode 2)
   const bool zhit = guess == kGuessZero && b1 == 0u;
   const uint32_t side = hit ? b1 - glo : 0u;
   if (tid == 0) {
