@@ -4,6 +4,7 @@
 #include "../../include/accordion.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cmath>
@@ -416,21 +417,22 @@ bool prof_begin(acc_ctx* c, int stage, EventPair& p) {
     if (hipEventCreate(&p.b) != hipSuccess) { (void)hipEventDestroy(p.a); return false; }
   }
   p.stage = stage;
-  (void)hipEventRecord(p.a, c->stream);
   return true;
 }
 
-void prof_end(acc_ctx* c, EventPair& p) {
-  (void)hipEventRecord(p.b, c->stream);
-  c->pending.push_back(p);
-}
+void prof_end(acc_ctx* c, EventPair& p) { c->pending.push_back(p); }
 
 #define ACC_LAUNCH(ctx, name, grid, block, ...)                              \
   do {                                                                       \
     EventPair ep_;                                                           \
     const bool prof_ = prof_begin(ctx, ST_##name, ep_);                      \
-    hipLaunchKernelGGL(name, grid, block, 0, (ctx)->stream, __VA_ARGS__);    \
-    if (prof_) prof_end(ctx, ep_);                                           \
+    if (prof_) {                                                             \
+      /* the two events take the dispatch's own begin and end timestamps */  \
+      hipExtLaunchKernelGGL(name, grid, block, 0, (ctx)->stream, ep_.a, ep_.b, 0, __VA_ARGS__); \
+      prof_end(ctx, ep_);                                                    \
+    } else {                                                                 \
+      hipLaunchKernelGGL(name, grid, block, 0, (ctx)->stream, __VA_ARGS__);  \
+    }                                                                        \
     int rc_ = check_launch(ctx, #name);                                      \
     if (rc_ != ACC_OK) return rc_;                                           \
   } while (0)
