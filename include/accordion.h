@@ -307,12 +307,12 @@ int32_t accordion_get_state(acc_ctx* ctx, void* state_host, size_t bytes);
 int32_t accordion_set_state(acc_ctx* ctx, const void* state_host, size_t bytes);
 
 /* --- per-kernel timing (tracing aid; not part of the paper's method) -------------------------
- * With profiling on, kernel launches are bracketed by two HIP events on the context's stream and
- * the elapsed time is accumulated per stage: enable = 1 brackets every kernel, enable = 2 only the
- * fused error-feedback pass of the method (the kernel that moves the most bytes), which keeps
- * the event overhead out of the other launches, enable = 3 only every fourth launch of that pass
- * (a pair of events costs 5 to 7 us of stream time, a few per cent of a step); 0 switches it
- * off.  accordion_get_profile
+ * With profiling on, a kernel launch carries two HIP events that take the begin and the end
+ * timestamp of its dispatch on the context's stream, and the elapsed time is accumulated per
+ * stage: enable = 1 times every kernel, enable = 2 only the fused error-feedback pass of the
+ * method (the kernel that moves the most bytes), enable = 3 only every fourth launch of that
+ * pass (a timed launch costs a few us of stream time); 0 switches it off.  Not to be switched on
+ * while the stream is being captured into a graph.  accordion_get_profile
  * synchronises the stream and returns the accumulated milliseconds and the number of launches
  * of one stage since profiling was last switched on.  Stages are numbered from 0, fewer than
  * ACC_N_STAGES of them; accordion_stage_name gives the kernel's name, NULL beyond the last stage
