@@ -14,12 +14,13 @@ def _check_step(gpu, ora, grads, tag, check_state=True):
     """One batched step on both sides; mean and payloads always compared.  check_state=False
     leaves the library's memory alone (reading it writes the residual out, which the batched
     path otherwise defers to the next step's first pass): the deferred route is then the one
-    the next step takes."""
+    the next step takes.  Returns the mean."""
     out_ref = ora.step(grads)
     dg = [H.to_dev(g) for g in grads]
     out = H.dev_out(gpu.n_params)
     gpu.step_all(dg, out)
-    H.assert_bits_equal(out.cpu().numpy(), out_ref, f"{tag}: mean")
+    mean = out.cpu().numpy()
+    H.assert_bits_equal(mean, out_ref, f"{tag}: mean")
     for w in range(gpu.n_workers):
         for li in range(gpu.n_layers):
             idx, val = gpu.get_payload(w, li)
@@ -28,10 +29,11 @@ def _check_step(gpu, ora, grads, tag, check_state=True):
             H.assert_bits_equal(val, rv, f"{tag}: values worker {w} layer {li}")
     assert gpu.payload_words() == (ora.words_last, ora.words_cum)
     if not check_state:
-        return
+        return mean
     st = gpu.unpack_state(gpu.get_state())
     H.assert_bits_equal(st["e"], ora.e, f"{tag}: residual")
     H.assert_bits_equal(st["A"], ora.A, f"{tag}: accumulator")
+    return mean
 
 
 def _case_values(rng, case, n):
@@ -137,16 +139,21 @@ def test_mean_of_subnormal_values_rounds_like_a_division(W):
 
 
 def test_guessed_bins_hit_drift_and_miss():
-    """The error-feedback pass stages the keys of two level-1 bins on a guess.  Over many steps
-    with a stationary distribution the guess must hit (no more re-staging); a slow drift of the
-    gradient scale is followed by the extrapolated guess; a jump makes it miss.  Every step is
-    bit-exact whichever path is taken."""
+    """The error-feedback pass lists its candidates on a guess of where the threshold will lie.
+    Over many steps with a stationary distribution the guess must hit (nothing is staged again, the
+    compaction works from the lists); a slow drift of the gradient scale is followed by the
+    extrapolated guess; a jump makes it miss (the layer is staged again and compacted from Delta).
+    Every step is bit-exact whichever route is taken -- against the oracle, and word for word
+    against a second context that is driven call by call, where the compaction always reads
+    Delta and the mean is formed from the payloads."""
     print("case guessed bins", flush=True)
     shapes = [(1, 5 * 8192 + 13, 0), (64, 577, 1), (1, 100, 0), (6, 8192, 1)]
     layers = wl.make_layers(shapes)
     N = wl.total_params(layers)
     W = 2
     gpu, ora = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    twin, _ = H.make_pair(B.ACC_TOPK, layers, W, 10, 1)
+    out_twin = H.dev_out(N)
     rng = np.random.default_rng(5)
     scale = 1.0
     restaged = []
@@ -156,8 +163,20 @@ def test_guessed_bins_hit_drift_and_miss():
         if step == 12:
             scale *= 40.0                                   # far outside the guessed bins
         grads = [(rng.standard_normal(N) * scale).astype(np.float32) for _ in range(W)]
-        _check_step(gpu, ora, grads, f"step {step}", check_state=(step % 3 == 2 or step == 13))
+        mean = _check_step(gpu, ora, grads, f"step {step}", check_state=(step % 3 == 2 or step == 13))
         restaged.append(gpu.topk_stats()[0])
+        dg = [H.to_dev(g) for g in grads]
+        for w in range(W):
+            twin.compress_step(w, dg[w], 0)
+        twin.aggregate(0)
+        twin.decompress(out_twin)
+        H.assert_bits_equal(out_twin.cpu().numpy(), mean, f"step {step}: the two routes differ in the mean")
+        for w in range(W):
+            for li in range(gpu.n_layers):
+                ia, va = gpu.get_payload(w, li)
+                ib, vb = twin.get_payload(w, li)
+                assert np.array_equal(ia, ib), f"step {step}: the two routes differ in the indices"
+                H.assert_bits_equal(va, vb, f"step {step}: the two routes differ in the values")
     per_step = np.diff([0] + restaged)
     n_multi = 3 * W                                         # (worker, layer) pairs of more than one tile
     assert per_step[0] == n_multi                           # nothing to guess from at the first step
@@ -165,6 +184,7 @@ def test_guessed_bins_hit_drift_and_miss():
     assert per_step[12] == n_multi, per_step                # the jump is missed ...
     assert per_step[13] <= n_multi                          # ... and everything is still exact
     assert gpu.topk_stats()[1] == 0                         # no tie class needed the sweeps
+    twin.destroy()
     gpu.destroy()
 
 
